@@ -1,0 +1,232 @@
+"""CPU oracle of the mini-batch GCN hot path: ctypes front end to sgnn_oracle.c.
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg; the product package never imports it and it never imports the product.
+All arrays are numpy arrays on the host.  See the header of sgnn_oracle.c for the passages of
+the paper each routine follows and for how each is pinned.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sgnn_oracle.c")
+_LIB = os.path.join(_HERE, "libsgnn_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile sgnn_oracle.c with gcc (OpenMP over independent outer loops only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _p(a: Optional[np.ndarray], ct):
+    if a is None:
+        return None
+    return a.ctypes.data_as(C.POINTER(ct))
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        u32p, i32p, i64p, f32p, f64p, u64p = (C.POINTER(t) for t in
+                                              (C.c_uint32, C.c_int32, C.c_int64, C.c_float, C.c_double, C.c_uint64))
+        L.oracle_philox4x32_10.argtypes = [u32p, u32p, u32p]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_vertex_key.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
+        L.oracle_vertex_key.restype = C.c_uint64
+        L.oracle_vertex_keys.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, u64p]
+        L.oracle_vertex_keys.restype = None
+        L.oracle_sample_uniform.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64, i32p]
+        L.oracle_sample_uniform.restype = C.c_int
+        L.oracle_induced_csr.argtypes = [C.c_uint64, i64p, i32p, f32p, i32p, C.c_uint64, C.c_int, C.c_int,
+                                         i32p, i32p, f32p, C.c_int64]
+        L.oracle_induced_csr.restype = C.c_int64
+        L.oracle_gather_rows.argtypes = [f32p, C.c_int64, i32p, C.c_int64, f64p]
+        L.oracle_gather_rows.restype = None
+        L.oracle_gather_labels.argtypes = [i32p, i32p, C.c_int64, i32p]
+        L.oracle_gather_labels.restype = None
+        L.oracle_round_bf16.argtypes = [C.c_double]
+        L.oracle_round_bf16.restype = C.c_double
+        L.oracle_spmm.argtypes = [C.c_int64, i32p, i32p, f32p, f64p, C.c_int64, f64p]
+        L.oracle_spmm.restype = None
+        L.oracle_csr_transpose.argtypes = [C.c_int64, C.c_int64, i32p, i32p, f32p, i32p, i32p, f32p]
+        L.oracle_csr_transpose.restype = None
+        L.oracle_gemm.argtypes = [C.c_int64, C.c_int64, C.c_int64, f64p, f64p, f64p]
+        L.oracle_gemm.restype = None
+        L.oracle_gcn_fwd.argtypes = [C.c_int64, i32p, i32p, f32p, f64p, C.c_int64, f64p, C.c_int64, f64p,
+                                     C.c_int, C.c_int, f64p, f64p]
+        L.oracle_gcn_fwd.restype = None
+        L.oracle_gcn_bwd.argtypes = [C.c_int64, i32p, i32p, f32p, f64p, C.c_int64, f64p, C.c_int64, f64p, f64p,
+                                     C.c_int, C.c_int, f64p, f64p, f64p]
+        L.oracle_gcn_bwd.restype = None
+        L.oracle_softmax_xent.argtypes = [C.c_int64, C.c_int64, f64p, i32p, f64p]
+        L.oracle_softmax_xent.restype = C.c_double
+        L.oracle_num_threads.argtypes = []
+        L.oracle_num_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _arr(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=dtype)
+
+
+# ------------------------------------------------------------------------------------------------
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c = _arr(ctr, np.uint32); k = _arr(key, np.uint32); out = np.zeros(4, np.uint32)
+    lib().oracle_philox4x32_10(_p(c, C.c_uint32), _p(k, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def vertex_key(seed: int, step: int, v: int) -> int:
+    return int(lib().oracle_vertex_key(seed, step, v))
+
+
+def vertex_keys(seed: int, step: int, N: int) -> np.ndarray:
+    out = np.zeros(N, np.uint64)
+    lib().oracle_vertex_keys(seed, step, N, _p(out, C.c_uint64))
+    return out
+
+
+def sample_uniform(N: int, B: int, seed: int, step: int) -> np.ndarray:
+    """Eq. 20: ascending int32[B]."""
+    S = np.zeros(max(B, 1), np.int32)
+    rc = lib().oracle_sample_uniform(N, B, seed, step, _p(S, C.c_int32))
+    if rc != 0:
+        raise ValueError("oracle_sample_uniform: invalid arguments")
+    return S[:B]
+
+
+def induced_csr(N: int, rowptr, colidx, S, val=None, norm_mode: int = 0, rescale: int = 1
+                ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Eqs. 21-24: (rowptr_S int32[B+1], colidx_S int32[nnz], val_S float32[nnz])."""
+    rp = _arr(rowptr, np.int64); ci = _arr(colidx, np.int32); S = _arr(S, np.int32)
+    vv = None if val is None else _arr(val, np.float32)
+    B = int(S.shape[0])
+    cap = int(sum(int(rp[v + 1] - rp[v]) for v in S.tolist())) if B < 200000 else int((rp[S.astype(np.int64) + 1] - rp[S.astype(np.int64)]).sum())
+    cap = max(cap, 1)
+    rpS = np.zeros(B + 1, np.int32); ciS = np.zeros(cap, np.int32); vS = np.zeros(cap, np.float32)
+    nnz = lib().oracle_induced_csr(N, _p(rp, C.c_int64), _p(ci, C.c_int32), _p(vv, C.c_float), _p(S, C.c_int32), B,
+                                   norm_mode, rescale, _p(rpS, C.c_int32), _p(ciS, C.c_int32), _p(vS, C.c_float), cap)
+    if nnz < 0:
+        raise ValueError("oracle_induced_csr: invalid arguments")
+    return rpS, ciS[:nnz].copy(), vS[:nnz].copy()
+
+
+def gather_rows(X, S) -> np.ndarray:
+    X = _arr(X, np.float32); S = _arr(S, np.int32)
+    out = np.zeros((S.shape[0], X.shape[1]), np.float64)
+    lib().oracle_gather_rows(_p(X, C.c_float), X.shape[1], _p(S, C.c_int32), S.shape[0], _p(out, C.c_double))
+    return out
+
+
+def gather_labels(Y, S) -> np.ndarray:
+    Y = _arr(Y, np.int32); S = _arr(S, np.int32)
+    out = np.zeros(S.shape[0], np.int32)
+    lib().oracle_gather_labels(_p(Y, C.c_int32), _p(S, C.c_int32), S.shape[0], _p(out, C.c_int32))
+    return out
+
+
+def round_bf16(x):
+    f = lib().oracle_round_bf16
+    return np.vectorize(lambda t: f(float(t)), otypes=[np.float64])(np.asarray(x, np.float64))
+
+
+def spmm(rowptr, colidx, val, H) -> np.ndarray:
+    rp = _arr(rowptr, np.int32); ci = _arr(colidx, np.int32); v = _arr(val, np.float32); H = _arr(H, np.float64)
+    rows = rp.shape[0] - 1
+    out = np.zeros((rows, H.shape[1]), np.float64)
+    lib().oracle_spmm(rows, _p(rp, C.c_int32), _p(ci, C.c_int32), _p(v, C.c_float), _p(H, C.c_double), H.shape[1],
+                      _p(out, C.c_double))
+    return out
+
+
+def csr_transpose(rows: int, cols: int, rowptr, colidx, val):
+    rp = _arr(rowptr, np.int32); ci = _arr(colidx, np.int32); v = _arr(val, np.float32)
+    rpT = np.zeros(cols + 1, np.int32); ciT = np.zeros(max(ci.shape[0], 1), np.int32)
+    vT = np.zeros(max(ci.shape[0], 1), np.float32)
+    lib().oracle_csr_transpose(rows, cols, _p(rp, C.c_int32), _p(ci, C.c_int32), _p(v, C.c_float),
+                               _p(rpT, C.c_int32), _p(ciT, C.c_int32), _p(vT, C.c_float))
+    return rpT, ciT[:ci.shape[0]], vT[:ci.shape[0]]
+
+
+def gemm(A, Bm) -> np.ndarray:
+    A = _arr(A, np.float64); Bm = _arr(Bm, np.float64)
+    out = np.zeros((A.shape[0], Bm.shape[1]), np.float64)
+    lib().oracle_gemm(A.shape[0], A.shape[1], Bm.shape[1], _p(A, C.c_double), _p(Bm, C.c_double), _p(out, C.c_double))
+    return out
+
+
+def gcn_fwd(rowptr, colidx, val, H, W, bias=None, relu: bool = True, bf16: bool = False):
+    """Returns (T = A_S H, Y = act(T W + b)), both float64."""
+    rp = _arr(rowptr, np.int32); ci = _arr(colidx, np.int32); v = _arr(val, np.float32)
+    H = _arr(H, np.float64); W = _arr(W, np.float64)
+    b = None if bias is None else _arr(bias, np.float64)
+    B = rp.shape[0] - 1
+    T = np.zeros((B, W.shape[0]), np.float64); Y = np.zeros((B, W.shape[1]), np.float64)
+    lib().oracle_gcn_fwd(B, _p(rp, C.c_int32), _p(ci, C.c_int32), _p(v, C.c_float), _p(H, C.c_double), W.shape[0],
+                         _p(W, C.c_double), W.shape[1], _p(b, C.c_double), int(relu), int(bf16),
+                         _p(T, C.c_double), _p(Y, C.c_double))
+    return T, Y
+
+
+def gcn_bwd(rowptr_T, colidx_T, val_T, T, W, Y, dY, relu: bool = True, bf16: bool = False, need_dH: bool = True):
+    """Returns (dH or None, dW, db), float64."""
+    rp = _arr(rowptr_T, np.int32); ci = _arr(colidx_T, np.int32); v = _arr(val_T, np.float32)
+    T = _arr(T, np.float64); W = _arr(W, np.float64); Y = _arr(Y, np.float64); dY = _arr(dY, np.float64)
+    B = rp.shape[0] - 1
+    dH = np.zeros((B, W.shape[0]), np.float64) if need_dH else None
+    dW = np.zeros_like(W); db = np.zeros(W.shape[1], np.float64)
+    lib().oracle_gcn_bwd(B, _p(rp, C.c_int32), _p(ci, C.c_int32), _p(v, C.c_float), _p(T, C.c_double), W.shape[0],
+                         _p(W, C.c_double), W.shape[1], _p(Y, C.c_double), _p(dY, C.c_double), int(relu), int(bf16),
+                         _p(dH, C.c_double), _p(dW, C.c_double), _p(db, C.c_double))
+    return dH, dW, db
+
+
+def softmax_xent(O, labels):
+    """Returns (mean loss, dO)."""
+    O = _arr(O, np.float64); y = _arr(labels, np.int32)
+    dO = np.zeros_like(O)
+    loss = lib().oracle_softmax_xent(O.shape[0], O.shape[1], _p(O, C.c_double), _p(y, C.c_int32), _p(dO, C.c_double))
+    return float(loss), dO
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def gcn_step(N, rowptr, colidx, X, labels, weights, B, seed, step, bf16=False, norm_mode=0, rescale=1):
+    """One whole mini-batch step (Algorithm 1 without the parameter update): sample, induce,
+    slice, L layers forward (ReLU on all but the last), mean cross-entropy, L layers backward.
+    `weights` is a list of (W, b).  Returns a dict of every intermediate, float64."""
+    S = sample_uniform(N, B, seed, step)
+    rpS, ciS, vS = induced_csr(N, rowptr, colidx, S, None, norm_mode, rescale)
+    rpT, ciT, vT = csr_transpose(B, B, rpS, ciS, vS)
+    H = gather_rows(X, S)
+    yS = gather_labels(labels, S)
+    L = len(weights)
+    Ts, Hs = [], [H]
+    for l, (W, b) in enumerate(weights):
+        T, Y = gcn_fwd(rpS, ciS, vS, Hs[-1], W, b, relu=(l < L - 1), bf16=bf16)
+        Ts.append(T); Hs.append(Y)
+    loss, dY = softmax_xent(Hs[-1], yS)
+    dWs, dbs = [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        W, b = weights[l]
+        dH, dW, db = gcn_bwd(rpT, ciT, vT, Ts[l], W, Hs[l + 1], dY, relu=(l < L - 1), bf16=bf16, need_dH=(l > 0))
+        dWs[l], dbs[l] = dW, db
+        dY = dH
+    return dict(S=S, rowptr=rpS, colidx=ciS, val=vS, X_S=H, y_S=yS, T=Ts, H=Hs, loss=loss, dW=dWs, db=dbs)

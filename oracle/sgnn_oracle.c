@@ -1,0 +1,392 @@
+/*
+ * CPU oracle for the mini-batch GCN hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain statement of what the path computes.  It is used by the tests,
+ * by the smoke check and by the benchmark's cpu_baseline leg, and by nothing else; the product
+ * (the HIP library) never links, loads or calls it, and the two share no code.
+ *
+ * Every function follows one passage of the paper (ScaleGNN, arXiv 2604.02651):
+ *   oracle_sample_uniform   Sec. III-D "Vertex Sampling", Eq. 20  (uniform B-subset of V)
+ *   oracle_induced_csr      Sec. III-D Eq. 21 (induced edges), Eqs. 23-24 (p and the rescale),
+ *                           Sec. II-A Eq. 3 (symmetric normalisation of A + I)
+ *   oracle_gather_rows      Sec. III-D Eq. 26 (feature / label slicing)
+ *   oracle_spmm, oracle_gemm, oracle_gcn_fwd   Sec. III-B Eqs. 5-6 (+ ReLU, Eq. 8)
+ *   oracle_gcn_bwd          Sec. III-C, the three layer-backward equations (grad W, grad H_agg,
+ *                           transposed SpMM)
+ *   oracle_softmax_xent     Sec. III-B "Output Head and Loss" (cross-entropy, single label)
+ * The random generator is not the paper's (it uses a framework permutation whose stream is not
+ * reproducible).  The sample is pinned instead as: the B vertices with the smallest
+ * (key(v), v), where key(v) is 64 bits of Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11)
+ * keyed by the seed and counted by (v / 2, step).  Any exact selection of that set is uniform
+ * over B-subsets whenever keys are distinct, which is what Eq. 20 asks for.
+ *
+ * All floating-point work is done in double precision.  Values that the method stores in fp32
+ * (edge weights) are rounded to fp32 once, where the definition says they are stored.
+ *
+ * Parity pins (tests/, marker "not gpu"): Philox against the published known-answer vectors and a
+ * big-integer Python version; the sampler against an independent threshold selection and the
+ * inclusion-probability statistics of Eq. 20; the induced CSR against dense brute force, scipy
+ * slicing, a literal walk through Algorithm 2's phases and the exact enumeration of Eq. 25; the
+ * layer against dense numpy, torch autograd and central finite differences.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------------------------ */
+/* Philox4x32-10                                                                                */
+/* ------------------------------------------------------------------------------------------ */
+
+#define PHILOX_M0 0xD2511F53u
+#define PHILOX_M1 0xCD9E8D57u
+#define PHILOX_W0 0x9E3779B9u
+#define PHILOX_W1 0xBB67AE85u
+
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)PHILOX_M0 * c0;
+        uint64_t p1 = (uint64_t)PHILOX_M1 * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += PHILOX_W0;
+        k1 += PHILOX_W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* 64-bit selection key of vertex v at a given step: vertices 2j and 2j+1 share Philox block j;
+ * the even vertex takes words (1,0), the odd vertex words (3,2), high word first. */
+uint64_t oracle_vertex_key(uint64_t seed, uint64_t step, uint64_t v)
+{
+    uint64_t j = v >> 1;
+    uint32_t ctr[4] = { (uint32_t)j, (uint32_t)(j >> 32), (uint32_t)step, (uint32_t)(step >> 32) };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    if ((v & 1u) == 0)
+        return ((uint64_t)out[1] << 32) | out[0];
+    return ((uint64_t)out[3] << 32) | out[2];
+}
+
+void oracle_vertex_keys(uint64_t seed, uint64_t step, uint64_t N, uint64_t *keys)
+{
+    for (uint64_t v = 0; v < N; ++v)
+        keys[v] = oracle_vertex_key(seed, step, v);
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Eq. 20: uniform B-subset, returned ascending                                                 */
+/* ------------------------------------------------------------------------------------------ */
+
+typedef struct { uint64_t key; uint64_t v; } keyed_vertex;
+
+static int cmp_keyed(const void *a, const void *b)
+{
+    const keyed_vertex *x = (const keyed_vertex *)a, *y = (const keyed_vertex *)b;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    if (x->v != y->v) return x->v < y->v ? -1 : 1;
+    return 0;
+}
+
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* Returns 0, or -1 on invalid arguments / allocation failure. */
+int oracle_sample_uniform(uint64_t N, uint64_t B, uint64_t seed, uint64_t step, int32_t *S)
+{
+    if (B == 0 || B > N || N > 0x7fffffffull) return -1;
+    keyed_vertex *all = (keyed_vertex *)malloc(sizeof(keyed_vertex) * N);
+    if (!all) return -1;
+    for (uint64_t v = 0; v < N; ++v) {
+        all[v].key = oracle_vertex_key(seed, step, v);
+        all[v].v = v;
+    }
+    qsort(all, N, sizeof(keyed_vertex), cmp_keyed);
+    for (uint64_t i = 0; i < B; ++i) S[i] = (int32_t)all[i].v;
+    free(all);
+    qsort(S, B, sizeof(int32_t), cmp_i32);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Eqs. 21, 23, 24: induced, normalised, rescaled subgraph as CSR                               */
+/* ------------------------------------------------------------------------------------------ */
+
+/* index of u in ascending S, or -1 */
+static int64_t find_in_sample(const int32_t *S, int64_t B, int32_t u)
+{
+    int64_t lo = 0, hi = B - 1;
+    while (lo <= hi) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if (S[mid] == u) return mid;
+        if (S[mid] < u) lo = mid + 1; else hi = mid - 1;
+    }
+    return -1;
+}
+
+/*
+ * Input: canonical CSR of A + I on N vertices (ascending unique columns, one self-loop a row).
+ *   val == NULL: a_vu = 1 / sqrt(deg(v) deg(u)) with deg = row length (self-loop included), Eq. 3;
+ *   val != NULL: a_vu = val[e] verbatim (Algorithm 2 takes the weights as an input).
+ * norm_mode 0: weights inherited from the full graph (Sec. III-D, below Eq. 21).
+ * norm_mode 1: degrees recounted on the induced subgraph (val is ignored).
+ * rescale 1:  off-diagonal entries divided by p = (B-1)/(N-1), Eqs. 23-24; diagonal untouched.
+ * Output rows follow ascending S, columns are positions in S, ascending within a row.
+ * Returns nnz (entries beyond `capacity` are counted but not written), or -1 on bad arguments.
+ */
+int64_t oracle_induced_csr(uint64_t N, const int64_t *rowptr, const int32_t *colidx, const float *val,
+                           const int32_t *S, uint64_t B, int norm_mode, int rescale,
+                           int32_t *rowptr_S, int32_t *colidx_S, float *val_S, int64_t capacity)
+{
+    if (B == 0 || B > N) return -1;
+    /* p = Pr[u in S | v in S], Eq. 23.  With B == 1 no off-diagonal entry survives, p is unused. */
+    double p = 1.0;
+    if (rescale && B > 1) p = ((double)B - 1.0) / ((double)N - 1.0);
+    int64_t nnz = 0;
+    rowptr_S[0] = 0;
+    for (uint64_t i = 0; i < B; ++i) {
+        int64_t v = S[i];
+        double deg_v = (double)(rowptr[v + 1] - rowptr[v]);
+        for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            int32_t u = colidx[e];
+            int64_t j = find_in_sample(S, (int64_t)B, u);
+            if (j < 0) continue;
+            if (nnz < capacity) {
+                double a;
+                if (val) a = (double)val[e];
+                else {
+                    double deg_u = (double)(rowptr[(int64_t)u + 1] - rowptr[u]);
+                    a = 1.0 / sqrt(deg_v * deg_u);
+                }
+                if (u != v) a /= p;
+                colidx_S[nnz] = (int32_t)j;
+                val_S[nnz] = (float)a;
+            }
+            ++nnz;
+        }
+        rowptr_S[i + 1] = (int32_t)nnz;
+    }
+    if (norm_mode == 1) {
+        int64_t lim = nnz < capacity ? nnz : capacity;
+        for (uint64_t i = 0; i < B; ++i) {
+            double di = (double)(rowptr_S[i + 1] - rowptr_S[i]);
+            for (int64_t e = rowptr_S[i]; e < rowptr_S[i + 1] && e < lim; ++e) {
+                int32_t j = colidx_S[e];
+                double dj = (double)(rowptr_S[j + 1] - rowptr_S[j]);
+                double a = 1.0 / sqrt(di * dj);
+                if ((uint64_t)j != i) a /= p;
+                val_S[e] = (float)a;
+            }
+        }
+    }
+    return nnz;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Eq. 26: slicing                                                                              */
+/* ------------------------------------------------------------------------------------------ */
+
+void oracle_gather_rows(const float *X, int64_t d, const int32_t *S, int64_t B, double *out)
+{
+    for (int64_t i = 0; i < B; ++i)
+        for (int64_t j = 0; j < d; ++j)
+            out[i * d + j] = (double)X[(int64_t)S[i] * d + j];
+}
+
+void oracle_gather_labels(const int32_t *Y, const int32_t *S, int64_t B, int32_t *out)
+{
+    for (int64_t i = 0; i < B; ++i) out[i] = Y[S[i]];
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Eqs. 5-6 and the layer                                                                       */
+/* ------------------------------------------------------------------------------------------ */
+
+/* bfloat16 rounding (round to nearest, ties to even) of a double that already holds an fp32-
+ * representable or wider value: first to fp32, then the top 16 bits of that. */
+double oracle_round_bf16(double x)
+{
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (double)f; /* inf / nan unchanged */
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* out[i,:] = sum_e val[e] * H[col[e],:]  (Eq. 5) */
+void oracle_spmm(int64_t rows, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                 const double *H, int64_t d, double *out)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < rows; ++i) {
+        double *o = out + i * d;
+        for (int64_t j = 0; j < d; ++j) o[j] = 0.0;
+        for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+            double a = (double)val[e];
+            const double *h = H + (int64_t)colidx[e] * d;
+            for (int64_t j = 0; j < d; ++j) o[j] += a * h[j];
+        }
+    }
+}
+
+/* Explicit transpose of a CSR with `rows` rows and `cols` columns (counting sort on columns). */
+void oracle_csr_transpose(int64_t rows, int64_t cols, const int32_t *rowptr, const int32_t *colidx,
+                          const float *val, int32_t *rowptr_T, int32_t *colidx_T, float *val_T)
+{
+    for (int64_t j = 0; j <= cols; ++j) rowptr_T[j] = 0;
+    for (int64_t e = 0; e < rowptr[rows]; ++e) rowptr_T[colidx[e] + 1]++;
+    for (int64_t j = 0; j < cols; ++j) rowptr_T[j + 1] += rowptr_T[j];
+    int32_t *cursor = (int32_t *)malloc(sizeof(int32_t) * (size_t)(cols > 0 ? cols : 1));
+    for (int64_t j = 0; j < cols; ++j) cursor[j] = rowptr_T[j];
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+            int32_t q = cursor[colidx[e]]++;
+            colidx_T[q] = (int32_t)i;
+            val_T[q] = val[e];
+        }
+    free(cursor);
+}
+
+/* C[M x N] = A[M x K] * B[K x N], row-major, plain triple loop (Eq. 6) */
+void oracle_gemm(int64_t M, int64_t K, int64_t N, const double *A, const double *B, double *C)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        double *c = C + i * N;
+        for (int64_t j = 0; j < N; ++j) c[j] = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double a = A[i * K + k];
+            const double *b = B + k * N;
+            for (int64_t j = 0; j < N; ++j) c[j] += a * b[j];
+        }
+    }
+}
+
+static void round_copy(const double *src, double *dst, int64_t n, int bf16)
+{
+    for (int64_t i = 0; i < n; ++i) dst[i] = bf16 ? oracle_round_bf16(src[i]) : src[i];
+}
+
+/*
+ * One GCN layer forward: T = A_S H (Eq. 5), Z = T W + b (Eq. 6; the bias is an extension, NULL
+ * for none), Y = max(Z, 0) when relu (Eq. 8) else Z.  With bf16 != 0 the two GEMM operands T and W
+ * are rounded to bfloat16 before the product (accumulation stays in double); T is returned
+ * unrounded.
+ */
+void oracle_gcn_fwd(int64_t B, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                    const double *H, int64_t d_in, const double *W, int64_t d_out, const double *bias,
+                    int relu, int bf16, double *T, double *Y)
+{
+    oracle_spmm(B, rowptr, colidx, val, H, d_in, T);
+    double *Tr = T, *Wr = (double *)W;
+    if (bf16) {
+        Tr = (double *)malloc(sizeof(double) * (size_t)(B * d_in));
+        Wr = (double *)malloc(sizeof(double) * (size_t)(d_in * d_out));
+        round_copy(T, Tr, B * d_in, 1);
+        round_copy(W, Wr, d_in * d_out, 1);
+    }
+    oracle_gemm(B, d_in, d_out, Tr, Wr, Y);
+    if (bf16) { free(Tr); free(Wr); }
+    for (int64_t i = 0; i < B; ++i)
+        for (int64_t j = 0; j < d_out; ++j) {
+            double z = Y[i * d_out + j] + (bias ? bias[j] : 0.0);
+            if (relu && !(z > 0.0)) z = 0.0;
+            Y[i * d_out + j] = z;
+        }
+}
+
+/*
+ * Layer backward (Sec. III-C).  dZ = dY where Y > 0 (all of dY when relu == 0); db = column sums of
+ * dZ; dW = T^T dZ; dT = dZ W^T; dH = A_S^T dT, computed with the explicitly transposed CSR
+ * (rowptr_T, colidx_T, val_T).  dH may be NULL (first layer: features are not trained).  With
+ * bf16 != 0 the operands of both GEMMs (T, dZ, W) are rounded to bfloat16 first.
+ */
+void oracle_gcn_bwd(int64_t B, const int32_t *rowptr_T, const int32_t *colidx_T, const float *val_T,
+                    const double *T, int64_t d_in, const double *W, int64_t d_out, const double *Y,
+                    const double *dY, int relu, int bf16, double *dH, double *dW, double *db)
+{
+    double *dZ = (double *)malloc(sizeof(double) * (size_t)(B * d_out));
+    for (int64_t i = 0; i < B * d_out; ++i)
+        dZ[i] = (!relu || Y[i] > 0.0) ? dY[i] : 0.0;
+    if (db) {
+        for (int64_t j = 0; j < d_out; ++j) db[j] = 0.0;
+        for (int64_t i = 0; i < B; ++i)
+            for (int64_t j = 0; j < d_out; ++j) db[j] += dZ[i * d_out + j];
+    }
+    double *Tr = (double *)malloc(sizeof(double) * (size_t)(B * d_in));
+    double *Wr = (double *)malloc(sizeof(double) * (size_t)(d_in * d_out));
+    round_copy(T, Tr, B * d_in, bf16);
+    round_copy(W, Wr, d_in * d_out, bf16);
+    if (bf16) round_copy(dZ, dZ, B * d_out, 1);
+    /* dW[k, j] = sum_i T[i, k] dZ[i, j] */
+    for (int64_t k = 0; k < d_in * d_out; ++k) dW[k] = 0.0;
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < d_in; ++k)
+        for (int64_t i = 0; i < B; ++i) {
+            double t = Tr[i * d_in + k];
+            for (int64_t j = 0; j < d_out; ++j) dW[k * d_out + j] += t * dZ[i * d_out + j];
+        }
+    if (dH) {
+        double *dT = (double *)malloc(sizeof(double) * (size_t)(B * d_in));
+        /* dT[i, k] = sum_j dZ[i, j] W[k, j] */
+#pragma omp parallel for schedule(static)
+        for (int64_t i = 0; i < B; ++i)
+            for (int64_t k = 0; k < d_in; ++k) {
+                double s = 0.0;
+                for (int64_t j = 0; j < d_out; ++j) s += dZ[i * d_out + j] * Wr[k * d_out + j];
+                dT[i * d_in + k] = s;
+            }
+        oracle_spmm(B, rowptr_T, colidx_T, val_T, dT, d_in, dH);
+        free(dT);
+    }
+    free(Tr); free(Wr); free(dZ);
+}
+
+/* Mean softmax cross-entropy over B rows and its gradient dO = (softmax(O) - onehot(y)) / B. */
+double oracle_softmax_xent(int64_t B, int64_t C, const double *O, const int32_t *labels, double *dO)
+{
+    double loss = 0.0;
+    for (int64_t i = 0; i < B; ++i) {
+        const double *o = O + i * C;
+        double m = o[0];
+        for (int64_t j = 1; j < C; ++j) if (o[j] > m) m = o[j];
+        double s = 0.0;
+        for (int64_t j = 0; j < C; ++j) s += exp(o[j] - m);
+        double lse = m + log(s);
+        loss += lse - o[labels[i]];
+        if (dO)
+            for (int64_t j = 0; j < C; ++j)
+                dO[i * C + j] = (exp(o[j] - lse) - (j == labels[i] ? 1.0 : 0.0)) / (double)B;
+    }
+    return loss / (double)B;
+}
+
+int oracle_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}

@@ -1,0 +1,226 @@
+"""Pins for the oracle's layer forward / backward (Eqs. 5-6, layer-backward equations), the
+bf16 rounding, the transpose, the loss and the whole step."""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import torch
+
+import oracle
+import synth_inputs as si
+from helpers import csr_to_dense, dense_induced
+
+
+@pytest.fixture(scope="module")
+def sub():
+    g = si.rmat_graph(400, 2500, seed=21)
+    rp = g.rowptr.numpy(); ci = g.colidx.numpy()
+    S = oracle.sample_uniform(400, 96, 0, 0)
+    rpS, ciS, vS = oracle.induced_csr(400, rp, ci, S)
+    return 96, rpS, ciS, vS
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+def test_spmm_against_dense_and_scipy(sub):
+    B, rp, ci, v = sub
+    H = _rand((B, 19), 1)
+    ref = csr_to_dense(rp, ci, v, B) @ H
+    got = oracle.spmm(rp, ci, v, H)
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-13)
+    A = sp.csr_matrix((v.astype(np.float64), ci, rp), shape=(B, B))
+    assert np.allclose(got, A @ H, rtol=1e-12, atol=1e-13)
+
+
+def test_spmm_rectangular_and_empty_rows():
+    rp = np.array([0, 0, 2, 2, 3], np.int32); ci = np.array([4, 1, 0], np.int32)
+    v = np.array([2.0, -1.0, 0.5], np.float32)
+    H = _rand((5, 3), 2)
+    got = oracle.spmm(rp, ci, v, H)
+    assert np.allclose(got, csr_to_dense(rp, ci, v, 5) @ H)
+    assert np.all(got[0] == 0) and np.all(got[2] == 0)
+
+
+def test_transpose_against_scipy(sub):
+    B, rp, ci, v = sub
+    rpT, ciT, vT = oracle.csr_transpose(B, B, rp, ci, v)
+    A = sp.csr_matrix((v, ci, rp), shape=(B, B)).T.tocsr(); A.sort_indices()
+    assert np.array_equal(rpT, A.indptr) and np.array_equal(ciT, A.indices) and np.array_equal(vT, A.data)
+    # non-symmetric, rectangular
+    rp2 = np.array([0, 2, 3], np.int32); ci2 = np.array([0, 2, 1], np.int32); v2 = np.array([1, 2, 3], np.float32)
+    r, c, w = oracle.csr_transpose(2, 3, rp2, ci2, v2)
+    assert np.array_equal(csr_to_dense(r, c, w, 2), csr_to_dense(rp2, ci2, v2, 3).T)
+
+
+def test_gemm_against_numpy():
+    A = _rand((37, 23), 3); Bm = _rand((23, 11), 4)
+    assert np.allclose(oracle.gemm(A, Bm), A @ Bm, rtol=1e-13, atol=1e-13)
+    # a transposed-operand mistake would fail on non-square shapes
+    assert oracle.gemm(A, Bm).shape == (37, 11)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("use_bias", [False, True])
+def test_layer_forward_against_dense(sub, relu, use_bias):
+    B, rp, ci, v = sub
+    H = _rand((B, 13), 5); W = _rand((13, 7), 6); b = _rand(7, 7) if use_bias else None
+    T, Y = oracle.gcn_fwd(rp, ci, v, H, W, b, relu=relu)
+    A = csr_to_dense(rp, ci, v, B)
+    Z = A @ H @ W + (b if use_bias else 0.0)
+    assert np.allclose(T, A @ H, rtol=1e-12, atol=1e-13)
+    assert np.allclose(Y, np.maximum(Z, 0) if relu else Z, rtol=1e-12, atol=1e-12)
+    # both association orders agree
+    assert np.allclose(A @ (H @ W), (A @ H) @ W, rtol=1e-10, atol=1e-12)
+
+
+def test_layer_special_cases():
+    B = 17
+    rp = np.arange(B + 1, dtype=np.int32); ci = np.arange(B, dtype=np.int32); v = np.ones(B, np.float32)
+    H = _rand((B, 5), 8); W = _rand((5, 4), 9)
+    T, Y = oracle.gcn_fwd(rp, ci, v, H, W, None, relu=False)      # A = I: plain GEMM
+    assert np.array_equal(T, H) and np.allclose(Y, H @ W, rtol=1e-13)
+    g = si.rmat_graph(50, 150, seed=2)
+    S = np.arange(50, dtype=np.int32)
+    r, c, w = oracle.induced_csr(50, g.rowptr.numpy(), g.colidx.numpy(), S)
+    T, Y = oracle.gcn_fwd(r, c, w, _rand((50, 6), 1), np.eye(6), None, relu=False)   # W = I: plain SpMM
+    assert np.allclose(T, Y)
+
+
+def _torch_layer(A, H, W, b, relu):
+    Z = A @ H @ W + (b if b is not None else 0.0)
+    return torch.relu(Z) if relu else Z
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_layer_backward_against_autograd(sub, relu):
+    B, rp, ci, v = sub
+    H = _rand((B, 9), 10); W = _rand((9, 6), 11); b = _rand(6, 12); R = _rand((B, 6), 13)
+    T, Y = oracle.gcn_fwd(rp, ci, v, H, W, b, relu=relu)
+    rpT, ciT, vT = oracle.csr_transpose(B, B, rp, ci, v)
+    dH, dW, db = oracle.gcn_bwd(rpT, ciT, vT, T, W, Y, R, relu=relu)
+    A = torch.tensor(csr_to_dense(rp, ci, v, B))
+    Ht, Wt, bt = (torch.tensor(x, requires_grad=True) for x in (H, W, b))
+    (_torch_layer(A, Ht, Wt, bt, relu) * torch.tensor(R)).sum().backward()
+    assert np.allclose(dH, Ht.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(dW, Wt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(db, bt.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_layer_backward_with_asymmetric_matrix():
+    # a non-symmetric A catches a backward pass that forgets the transpose
+    rp = np.array([0, 2, 3, 6], np.int32); ci = np.array([0, 2, 0, 0, 1, 2], np.int32)
+    v = np.array([0.5, -1.0, 2.0, 0.25, 3.0, 1.5], np.float32)
+    H = _rand((3, 4), 1); W = _rand((4, 2), 2); R = _rand((3, 2), 3)
+    T, Y = oracle.gcn_fwd(rp, ci, v, H, W, None, relu=False)
+    rpT, ciT, vT = oracle.csr_transpose(3, 3, rp, ci, v)
+    dH, dW, _ = oracle.gcn_bwd(rpT, ciT, vT, T, W, Y, R, relu=False)
+    A = csr_to_dense(rp, ci, v, 3)
+    assert np.allclose(dH, A.T @ (R @ W.T)) and np.allclose(dW, (A @ H).T @ R)
+    assert not np.allclose(dH, A @ (R @ W.T))
+
+
+def test_layer_backward_finite_differences(sub):
+    B, rp, ci, v = sub
+    H = _rand((B, 5), 20); W = _rand((5, 4), 21); b = _rand(4, 22); R = _rand((B, 4), 23)
+    rpT, ciT, vT = oracle.csr_transpose(B, B, rp, ci, v)
+
+    def loss(H_, W_, b_):
+        return float((oracle.gcn_fwd(rp, ci, v, H_, W_, b_, relu=True)[1] * R).sum())
+
+    T, Y = oracle.gcn_fwd(rp, ci, v, H, W, b, relu=True)
+    dH, dW, db = oracle.gcn_bwd(rpT, ciT, vT, T, W, Y, R, relu=True)
+    h = 1e-6
+    rng = np.random.default_rng(0)
+    for _ in range(12):
+        i, j = rng.integers(B), rng.integers(5)
+        Hp, Hm = H.copy(), H.copy(); Hp[i, j] += h; Hm[i, j] -= h
+        assert abs((loss(Hp, W, b) - loss(Hm, W, b)) / (2 * h) - dH[i, j]) < 1e-6
+    for k in range(5):
+        for j in range(4):
+            Wp, Wm = W.copy(), W.copy(); Wp[k, j] += h; Wm[k, j] -= h
+            assert abs((loss(H, Wp, b) - loss(H, Wm, b)) / (2 * h) - dW[k, j]) < 1e-5
+    for j in range(4):
+        bp, bm = b.copy(), b.copy(); bp[j] += h; bm[j] -= h
+        assert abs((loss(H, W, bp) - loss(H, W, bm)) / (2 * h) - db[j]) < 1e-5
+
+
+def test_adjoint_identity_and_bias_as_ones_column(sub):
+    B, rp, ci, v = sub
+    rpT, ciT, vT = oracle.csr_transpose(B, B, rp, ci, v)
+    x = _rand((B, 3), 30); y = _rand((B, 3), 31)
+    assert abs((oracle.spmm(rp, ci, v, x) * y).sum() - (x * oracle.spmm(rpT, ciT, vT, y)).sum()) < 1e-10
+    # db equals the dW row of a constant-one input column
+    H = _rand((B, 4), 32); W = _rand((4, 3), 33); R = _rand((B, 3), 34)
+    T = np.concatenate([oracle.spmm(rp, ci, v, H), np.ones((B, 1))], 1)
+    W1 = np.concatenate([W, np.zeros((1, 3))], 0)
+    Y = T @ W1
+    _, dW, db = oracle.gcn_bwd(rpT, ciT, vT, T, W1, Y, R, relu=False, need_dH=False)
+    assert np.allclose(dW[-1], db)
+
+
+def test_relu_gradient_at_zero_is_zero():
+    rp = np.array([0, 1], np.int32); ci = np.array([0], np.int32); v = np.ones(1, np.float32)
+    H = np.zeros((1, 2)); W = np.ones((2, 2))
+    T, Y = oracle.gcn_fwd(rp, ci, v, H, W, None, relu=True)
+    dH, dW, db = oracle.gcn_bwd(rp, ci, v, T, W, Y, np.ones((1, 2)), relu=True)
+    assert np.all(dH == 0) and np.all(db == 0)
+
+
+def test_round_bf16_against_torch():
+    x = np.concatenate([_rand(2000, 40), _rand(2000, 41) * 1e-20, _rand(2000, 42) * 1e20,
+                        [0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 3.0e38]])
+    x32 = x.astype(np.float32)
+    ref = torch.tensor(x32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(oracle.round_bf16(x32), ref)
+
+
+def test_bf16_layer_rounds_gemm_operands(sub):
+    B, rp, ci, v = sub
+    H = _rand((B, 8), 50); W = _rand((8, 5), 51)
+    T, Y = oracle.gcn_fwd(rp, ci, v, H, W, None, relu=False, bf16=True)
+    Tr = torch.tensor(T).float().to(torch.bfloat16).double().numpy()
+    Wr = torch.tensor(W).float().to(torch.bfloat16).double().numpy()
+    assert np.allclose(Y, Tr @ Wr, rtol=1e-12, atol=1e-13)
+    _, Y32 = oracle.gcn_fwd(rp, ci, v, H, W, None, relu=False, bf16=False)
+    err = np.linalg.norm(Y - Y32) / np.linalg.norm(Y32)
+    assert 0 < err < 2e-2
+    rpT, ciT, vT = oracle.csr_transpose(B, B, rp, ci, v)
+    R = _rand((B, 5), 52)
+    dH, dW, db = oracle.gcn_bwd(rpT, ciT, vT, T, W, Y, R, relu=False, bf16=True)
+    Rr = torch.tensor(R).float().to(torch.bfloat16).double().numpy()
+    assert np.allclose(dW, Tr.T @ Rr, rtol=1e-12, atol=1e-13)
+    assert np.allclose(dH, csr_to_dense(rp, ci, v, B).T @ (Rr @ Wr.T), rtol=1e-12, atol=1e-13)
+    assert np.allclose(db, R.sum(0))
+
+
+def test_softmax_xent_against_torch():
+    O = _rand((33, 7), 60); y = np.random.default_rng(61).integers(0, 7, 33).astype(np.int32)
+    loss, dO = oracle.softmax_xent(O, y)
+    Ot = torch.tensor(O, requires_grad=True)
+    lt = torch.nn.functional.cross_entropy(Ot, torch.tensor(y, dtype=torch.long))
+    lt.backward()
+    assert abs(loss - lt.item()) < 1e-12 and np.allclose(dO, Ot.grad.numpy(), rtol=1e-10, atol=1e-14)
+
+
+def test_whole_step_against_autograd(tiny_graph):
+    cfg = si.CONFIGS["tiny"]
+    g = tiny_graph
+    rp = g.rowptr.numpy(); ci = g.colidx.numpy()
+    B = 128
+    X = si.normal_features(cfg.N, cfg.d_in).numpy(); labels = si.uniform_labels(cfg.N, cfg.classes).numpy()
+    weights = [(W.double().numpy(), b.double().numpy()) for W, b in si.layer_weights(cfg)]
+    out = oracle.gcn_step(cfg.N, rp, ci, X, labels, weights, B, 0, 0)
+    A = torch.tensor(dense_induced(cfg.N, rp, ci, out["S"]))
+    assert np.allclose(csr_to_dense(out["rowptr"], out["colidx"], out["val"], B), A.numpy(), rtol=1e-6)
+    A = torch.tensor(csr_to_dense(out["rowptr"], out["colidx"], out["val"], B))
+    H = torch.tensor(X[out["S"]].astype(np.float64))
+    params = [(torch.tensor(W, requires_grad=True), torch.tensor(b, requires_grad=True)) for W, b in weights]
+    for l, (W, b) in enumerate(params):
+        H = _torch_layer(A, H, W, b, l < len(params) - 1)
+    loss = torch.nn.functional.cross_entropy(H, torch.tensor(labels[out["S"]], dtype=torch.long))
+    loss.backward()
+    assert abs(out["loss"] - loss.item()) < 1e-10
+    for l, (W, b) in enumerate(params):
+        assert np.allclose(out["dW"][l], W.grad.numpy(), rtol=1e-9, atol=1e-13)
+        assert np.allclose(out["db"][l], b.grad.numpy(), rtol=1e-9, atol=1e-13)
