@@ -1,0 +1,211 @@
+/*
+ * sgnn - the single-GPU hot path of mini-batch GCN training with uniform vertex sampling
+ * (ScaleGNN, arXiv 2604.02651), as a C library of hand-written HIP kernels for gfx950.
+ *
+ * One training step (Algorithm 1 of the paper, without the parameter update) is
+ *     sgnn_sample_uniform   S ~ Uniform(B-subsets of V)                        (Eq. 20)
+ *     sgnn_induced_csr      A~[S,S]: induced edges, normalised, rescaled by 1/p (Eqs. 21-24)
+ *     sgnn_gather_rows      X_S = X[S], Y_S = Y[S]                              (Eq. 26)
+ *     sgnn_gcn_fwd  x L     T = A~ H (SpMM), Y = act(T W + b) (GEMM)            (Eqs. 5-6, 8)
+ *     sgnn_softmax_xent     mean cross-entropy and its gradient                 (Sec. III-B)
+ *     sgnn_gcn_bwd  x L     dW = T^T dZ, dT = dZ W^T, dH = A~^T dT              (Sec. III-C)
+ *
+ * Conventions
+ *  - Every array pointer is a DEVICE pointer owned by the caller unless a parameter says "host".
+ *    The library neither allocates nor frees caller-visible memory.  Its own scratch lives in
+ *    the context and grows only inside sgnn_ctx_reserve().
+ *  - Every call is asynchronous on the HIP stream passed last (a hipStream_t, passed as void*;
+ *    NULL is the default stream) and does not synchronise unless a host out-pointer is given.
+ *  - A context must be used from one stream at a time: calls that share a context and overlap
+ *    on different streams race on its scratch.  Use one context per concurrent stream.
+ *  - Matrices are dense row-major with a leading dimension in elements.
+ *  - Return value: SGNN_OK or a negative error code; sgnn_last_error() gives the message of the
+ *    last failing call on that context.  No call throws.
+ */
+#ifndef SGNN_H
+#define SGNN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SGNN_OK = 0,
+    SGNN_ERR_INVALID_ARG = -1, /* null pointer, B == 0, B > N, shape mismatch ...                  */
+    SGNN_ERR_CAPACITY = -2,    /* an output buffer or the reserved scratch is too small             */
+    SGNN_ERR_UNSUPPORTED = -3, /* a valid request this build does not implement                     */
+    SGNN_ERR_HIP = -4,         /* a HIP runtime call failed; the message names it                   */
+    SGNN_ERR_INTERNAL = -5     /* a device-side consistency check failed (see sgnn_ctx_status)      */
+};
+
+enum { SGNN_F32 = 0, SGNN_BF16 = 1 };
+
+/* layer flags */
+enum {
+    SGNN_RELU = 1,      /* Y = max(Z, 0) (Eq. 8); backward masks dY where Y <= 0                    */
+    SGNN_BF16_MFMA = 2  /* round both GEMM operands to bfloat16 (nearest even), accumulate in fp32  */
+};
+
+typedef struct sgnn_ctx sgnn_ctx;
+typedef void *sgnn_stream; /* hipStream_t */
+
+/* Context: binds a device, owns scratch.  `device` is a HIP device ordinal. */
+int sgnn_ctx_create(sgnn_ctx **out, int device);
+int sgnn_ctx_destroy(sgnn_ctx *ctx);
+
+/*
+ * Size the scratch for graphs of up to N vertices and E stored entries, samples of up to B
+ * vertices and layers of width up to d_max.  The only call that allocates device memory
+ * (hipMalloc); it synchronises the device when it has to grow.  Later calls that need more
+ * scratch than reserved fail with SGNN_ERR_CAPACITY.
+ */
+int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t d_max);
+
+/* Message of the last error on this context ("" if none).  Host string owned by the context. */
+const char *sgnn_last_error(const sgnn_ctx *ctx);
+
+/*
+ * Synchronises `stream` and reads the device-side status word that kernels set when a
+ * consistency check fails (sampler candidate buffer overflow).  Returns SGNN_OK or
+ * SGNN_ERR_INTERNAL, and clears the word.
+ */
+int sgnn_ctx_status(sgnn_ctx *ctx, sgnn_stream stream);
+
+/*
+ * Eq. 20: uniform sample of B of the N vertices without replacement.
+ * The sample is the B vertices with the smallest (key(v), v), key(v) = 64 bits of
+ * Philox4x32-10 with key words (seed lo, seed hi) and counter (v/2 lo, v/2 hi, step lo, step hi);
+ * vertex 2j takes output words (1,0), vertex 2j+1 words (3,2), high word first.  It depends on
+ * (N, B, seed, step) only, so every process that passes the same four values gets the same S.
+ *   S       out int32[B], ascending
+ *   bitmap  out uint64[ceil(N/64)], bit v%64 of word v/64 set iff v in S; the unused high bits of
+ *           the last word are zero
+ *   rank    out uint32[ceil(N/64)], rank[w] = number of sampled vertices below 64*w, so the
+ *           position of a sampled v in S is rank[v/64] + popcount(bitmap[v/64] & ((1<<v%64)-1))
+ * Errors: B == 0, B > N, N >= 2^31, null pointers -> SGNN_ERR_INVALID_ARG; scratch -> CAPACITY.
+ */
+int sgnn_sample_uniform(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, uint64_t step,
+                        int32_t *S, uint64_t *bitmap, uint32_t *rank, sgnn_stream stream);
+
+/*
+ * The full graph: canonical CSR of A + I (Eq. 3) - ascending unique columns in every row and
+ * exactly one self-loop per row.  rowptr has N+1 entries of int32 or int64.
+ * val == NULL: a_vu = 1/sqrt(deg(v) deg(u)), deg = row length (self-loop included);
+ * val != NULL: fp32[E] weights taken verbatim (Algorithm 2 lists them as an input).
+ */
+typedef struct {
+    uint64_t N;
+    uint64_t E; /* number of stored entries = rowptr[N] */
+    const void *rowptr;
+    int rowptr_is_i64;
+    const int32_t *colidx;
+    const float *val;
+} sgnn_graph;
+
+/*
+ * A mini-batch matrix in CSR: rows x cols, int32 rowptr[rows+1], colidx/val with room for
+ * `capacity` entries.  nnz_dev (device uint32[1], may be NULL) receives the number of entries.
+ */
+typedef struct {
+    uint32_t rows, cols;
+    int32_t *rowptr;
+    int32_t *colidx;
+    float *val;
+    uint64_t capacity;
+    uint32_t *nnz_dev;
+} sgnn_csr;
+
+/*
+ * Eqs. 21-24 / Algorithm 2 with the full row and column range: for i in [0,B), v = S[i], keep
+ * every u in row v of the graph with u in S; column = position of u in S (ascending within the
+ * row); value = a_vu / p for u != v and a_vv for u == v, p = (B-1)/(N-1).
+ *   S, bitmap, rank   as written by sgnn_sample_uniform for the same N and B
+ *   norm_mode 0       a_vu inherited from the full graph (the paper's definition)
+ *   norm_mode 1       a_vu recomputed from the degrees of the induced subgraph (val ignored)
+ *   rescale   1       divide off-diagonal entries by p;  0: leave them
+ *   out               rows/cols are set to B; rowptr[B+1] always complete; colidx/val are written
+ *                     up to out->capacity entries
+ *   nnz_host          NULL: fully asynchronous.  Otherwise the stream is synchronised, the entry
+ *                     count is stored there, and SGNN_ERR_CAPACITY is returned if it exceeds
+ *                     out->capacity (the required count is still reported).
+ * The entry count must stay below 2^31 (checked on the device, reported by sgnn_ctx_status).
+ */
+int sgnn_induced_csr(sgnn_ctx *ctx, const sgnn_graph *graph, const int32_t *S, uint32_t B,
+                     const uint64_t *bitmap, const uint32_t *rank, int norm_mode, int rescale,
+                     sgnn_csr *out, uint64_t *nnz_host, sgnn_stream stream);
+
+/*
+ * Dense row-major matrix.  row_index (may be NULL) makes logical row i the physical row
+ * row_index[i] of ptr; it is honoured only where a parameter says so.
+ */
+typedef struct {
+    void *ptr;
+    int dtype; /* SGNN_F32 (SGNN_BF16 storage is not implemented) */
+    int64_t rows, cols, ld;
+    const int32_t *row_index;
+} sgnn_mat;
+
+/*
+ * Eq. 26: out[i, :] = X[S[i], :] for i < B (fp32, d columns), and labels_out[i] = labels[S[i]]
+ * when labels != NULL.  X == NULL slices the labels only (the feature slice can instead be fused
+ * into the first layer through sgnn_mat.row_index).
+ */
+int sgnn_gather_rows(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, const int32_t *S,
+                     uint32_t B, float *out, int64_t ldo, const int32_t *labels,
+                     int32_t *labels_out, sgnn_stream stream);
+
+/*
+ * One GCN layer forward (Eqs. 5-6, 8): T = A H, Y = act(T W + bias).
+ *   A     B x B mini-batch CSR (entries beyond A->capacity are never read)
+ *   H     B x d_in fp32; H->row_index is honoured (fuses the slice of Eq. 26 into layer 1: pass
+ *         the full feature matrix with row_index = S)
+ *   W     d_in x d_out fp32;  bias fp32[d_out] or NULL
+ *   flags SGNN_RELU, SGNN_BF16_MFMA
+ *   Y     out B x d_out fp32
+ *   T     out B x d_in fp32, the aggregate, kept by the caller for the backward pass
+ */
+int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn_mat *W,
+                 const float *bias, int flags, sgnn_mat *Y, sgnn_mat *T, sgnn_stream stream);
+
+/*
+ * One GCN layer backward (Sec. III-C): dZ = dY where Y > 0 (all of dY without SGNN_RELU),
+ * dbias = column sums of dZ, dW = T^T dZ, dT = dZ W^T, dH = A_T dT.
+ *   A_T   the transpose of the forward matrix as CSR (the same object when it is symmetric)
+ *   T, W, Y   as in the forward call;  dY  B x d_out fp32
+ *   dH    out B x d_in fp32, or NULL to skip it (first layer)
+ *   dW    out fp32[d_in x d_out] row-major, overwritten;  dbias out fp32[d_out] or NULL
+ * The reduction over the B rows in dW and dbias uses a fixed split and a fixed summation order:
+ * results are bit-reproducible from run to run.
+ */
+int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sgnn_mat *W,
+                 const sgnn_mat *Y, const sgnn_mat *dY, int flags, sgnn_mat *dH, float *dW,
+                 float *dbias, sgnn_stream stream);
+
+/*
+ * Mean softmax cross-entropy over B rows of C logits (Sec. III-B, single-label loss) and its
+ * gradient dO = (softmax(O) - onehot(label)) / B.  loss_dev: device float[1] or NULL.
+ */
+int sgnn_softmax_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B,
+                      uint32_t C, float *loss_dev, float *dO, int64_t lddo, sgnn_stream stream);
+
+/* Plain operators, exported for tests and for callers that build their own layer. */
+
+/* out = A X: A rows x cols CSR, X cols x d fp32 (X->row_index honoured), out rows x d fp32. */
+int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, sgnn_mat *out, sgnn_stream stream);
+
+/*
+ * C = act(op(A) op(B) + bias): fp32 row-major, M x N result, reduction length K.
+ *   trans_a 0: A is M x K;  1: A is K x M (used as its transpose)
+ *   trans_b 0: B is K x N;  1: B is N x K (used as its transpose)
+ *   flags   SGNN_RELU, SGNN_BF16_MFMA;  bias fp32[N] or NULL
+ */
+int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
+              const float *A, int64_t lda, const float *B, int64_t ldb, const float *bias,
+              int flags, float *C, int64_t ldc, sgnn_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SGNN_H */

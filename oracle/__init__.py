@@ -208,25 +208,40 @@ def num_threads() -> int:
     return int(lib().oracle_num_threads())
 
 
-def gcn_step(N, rowptr, colidx, X, labels, weights, B, seed, step, bf16=False, norm_mode=0, rescale=1):
+def gcn_step(N, rowptr, colidx, X, labels, weights, B, seed, step, bf16=False, norm_mode=0, rescale=1,
+             relu_ties=None, tie_band=0.0):
     """One whole mini-batch step (Algorithm 1 without the parameter update): sample, induce,
     slice, L layers forward (ReLU on all but the last), mean cross-entropy, L layers backward.
-    `weights` is a list of (W, b).  Returns a dict of every intermediate, float64."""
+    `weights` is a list of (W, b).  Returns a dict of every intermediate, float64.
+
+    ReLU ties: a pre-activation within tie_band * max|Z| of zero has no decidable sign at the
+    working precision, and either mask value is a correct result there.  relu_ties[l], when
+    given, is a boolean B x d_out array; inside that band (and only there) the backward mask of
+    layer l takes its value instead of the oracle's own Z > 0.  The forward values never change."""
     S = sample_uniform(N, B, seed, step)
     rpS, ciS, vS = induced_csr(N, rowptr, colidx, S, None, norm_mode, rescale)
     rpT, ciT, vT = csr_transpose(B, B, rpS, ciS, vS)
     H = gather_rows(X, S)
     yS = gather_labels(labels, S)
     L = len(weights)
-    Ts, Hs = [], [H]
+    Ts, Hs, masks, bands = [], [H], [], []
     for l, (W, b) in enumerate(weights):
-        T, Y = gcn_fwd(rpS, ciS, vS, Hs[-1], W, b, relu=(l < L - 1), bf16=bf16)
-        Ts.append(T); Hs.append(Y)
+        relu = l < L - 1
+        T, Z = gcn_fwd(rpS, ciS, vS, Hs[-1], W, b, relu=False, bf16=bf16)
+        Y = np.maximum(Z, 0.0) if relu else Z
+        mask = Z > 0.0
+        band = np.abs(Z) <= tie_band * np.abs(Z).max() if relu else np.zeros_like(mask)
+        if relu and relu_ties is not None and relu_ties[l] is not None:
+            mask = np.where(band, np.asarray(relu_ties[l], bool), mask)
+        Ts.append(T); Hs.append(Y); masks.append(mask); bands.append(band)
     loss, dY = softmax_xent(Hs[-1], yS)
-    dWs, dbs = [None] * L, [None] * L
+    dWs, dbs, dHs = [None] * L, [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
         W, b = weights[l]
-        dH, dW, db = gcn_bwd(rpT, ciT, vT, Ts[l], W, Hs[l + 1], dY, relu=(l < L - 1), bf16=bf16, need_dH=(l > 0))
-        dWs[l], dbs[l] = dW, db
+        relu = l < L - 1
+        Ymask = masks[l].astype(np.float64) if relu else Hs[l + 1]     # gcn_bwd only tests Y > 0
+        dH, dW, db = gcn_bwd(rpT, ciT, vT, Ts[l], W, Ymask, dY, relu=relu, bf16=bf16, need_dH=(l > 0))
+        dWs[l], dbs[l], dHs[l] = dW, db, dH
         dY = dH
-    return dict(S=S, rowptr=rpS, colidx=ciS, val=vS, X_S=H, y_S=yS, T=Ts, H=Hs, loss=loss, dW=dWs, db=dbs)
+    return dict(S=S, rowptr=rpS, colidx=ciS, val=vS, X_S=H, y_S=yS, T=Ts, H=Hs, loss=loss, dW=dWs, db=dbs, dH=dHs,
+                relu_band=bands, relu_mask=masks)

@@ -1,0 +1,14 @@
+"""MI355X-native hot path of mini-batch GCN training with uniform vertex sampling
+(ScaleGNN, arXiv 2604.02651): Python binding of the C library libsgnn.
+
+Every step of the path runs in the hand-written HIP kernels of libsgnn.so; this package only
+marshals arguments (torch tensors -> raw device pointers).  There is no CPU fallback: importing
+the binding without a built library raises.
+"""
+from .binding import (  # noqa: F401
+    Context, Csr, SgnnError, lib, lib_path,
+    SGNN_RELU, SGNN_BF16_MFMA,
+    sgnn_sample_uniform, sgnn_induced_csr, sgnn_gather_rows, sgnn_gcn_fwd, sgnn_gcn_bwd,
+    sgnn_softmax_xent, sgnn_spmm, sgnn_gemm,
+)
+from .step import GcnStep  # noqa: F401

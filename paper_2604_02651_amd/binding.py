@@ -1,0 +1,268 @@
+"""ctypes binding of libsgnn.so: the same entry points as include/sgnn.h, taking torch tensors.
+
+Argument marshalling only.  Tensors must live on the context's GPU, be contiguous in their last
+dimension and have the dtype the C declaration states; the functions check that, pass raw device
+pointers, and raise SgnnError with the library's message on a negative return code.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsgnn.so")
+
+SGNN_RELU = 1
+SGNN_BF16_MFMA = 2
+SGNN_F32 = 0
+
+_ERR_NAMES = {-1: "SGNN_ERR_INVALID_ARG", -2: "SGNN_ERR_CAPACITY", -3: "SGNN_ERR_UNSUPPORTED", -4: "SGNN_ERR_HIP",
+              -5: "SGNN_ERR_INTERNAL"}
+
+
+class SgnnError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__("%s (%d): %s" % (_ERR_NAMES.get(code, "SGNN_ERR"), code, message))
+        self.code = code
+
+
+class _Graph(C.Structure):
+    _fields_ = [("N", C.c_uint64), ("E", C.c_uint64), ("rowptr", C.c_void_p), ("rowptr_is_i64", C.c_int),
+                ("colidx", C.c_void_p), ("val", C.c_void_p)]
+
+
+class _Csr(C.Structure):
+    _fields_ = [("rows", C.c_uint32), ("cols", C.c_uint32), ("rowptr", C.c_void_p), ("colidx", C.c_void_p),
+                ("val", C.c_void_p), ("capacity", C.c_uint64), ("nnz_dev", C.c_void_p)]
+
+
+class _Mat(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("dtype", C.c_int), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
+                ("row_index", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded C library.  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError("libsgnn.so is not built: run `python -m paper_2604_02651_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no CPU fallback")
+        L = C.CDLL(_LIB_PATH)
+        vp, u64, u32, i64, ci = C.c_void_p, C.c_uint64, C.c_uint32, C.c_int64, C.c_int
+        L.sgnn_ctx_create.argtypes = [C.POINTER(vp), ci]
+        L.sgnn_ctx_destroy.argtypes = [vp]
+        L.sgnn_ctx_reserve.argtypes = [vp, u64, u64, u32, u32]
+        L.sgnn_last_error.argtypes = [vp]
+        L.sgnn_last_error.restype = C.c_char_p
+        L.sgnn_ctx_status.argtypes = [vp, vp]
+        L.sgnn_sample_uniform.argtypes = [vp, u64, u32, u64, u64, vp, vp, vp, vp]
+        L.sgnn_induced_csr.argtypes = [vp, C.POINTER(_Graph), vp, u32, vp, vp, ci, ci, C.POINTER(_Csr),
+                                       C.POINTER(u64), vp]
+        L.sgnn_gather_rows.argtypes = [vp, vp, i64, i64, vp, u32, vp, i64, vp, vp, vp]
+        L.sgnn_gcn_fwd.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), vp, ci, C.POINTER(_Mat),
+                                   C.POINTER(_Mat), vp]
+        L.sgnn_gcn_bwd.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat),
+                                   C.POINTER(_Mat), ci, C.POINTER(_Mat), vp, vp, vp]
+        L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
+        L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), vp]
+        L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
+        for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
+                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd",
+                     "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm"):
+            getattr(L, name).restype = ci
+        _lib = L
+    return _lib
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    h = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    return C.c_void_p(h)
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError("%s must be a CUDA/HIP tensor" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if t.dim() >= 1 and t.numel() > 0 and t.stride(-1) != 1:
+        raise TypeError("%s must be contiguous in its last dimension" % name)
+    return C.c_void_p(t.data_ptr())
+
+
+def _mat(t: torch.Tensor, row_index: Optional[torch.Tensor] = None, name="matrix") -> _Mat:
+    if t.dim() != 2:
+        raise TypeError("%s must be 2-D" % name)
+    p = _ptr(t, torch.float32, name)
+    ri = _ptr(row_index, torch.int32, name + ".row_index")
+    rows = row_index.numel() if row_index is not None else t.shape[0]
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
+    return _Mat(p, SGNN_F32, rows, t.shape[1], ld, ri)
+
+
+class Context:
+    """Owns an sgnn_ctx.  One context per concurrently used stream."""
+
+    def __init__(self, device: int = 0):
+        self._h = C.c_void_p()
+        self.device = device
+        rc = lib().sgnn_ctx_create(C.byref(self._h), device)
+        if rc != 0:
+            raise SgnnError(rc, "sgnn_ctx_create failed (is a GPU visible?)")
+
+    def check(self, rc: int):
+        if rc != 0:
+            raise SgnnError(rc, lib().sgnn_last_error(self._h).decode())
+
+    def reserve(self, N: int, E: int, B: int, d_max: int):
+        self.check(lib().sgnn_ctx_reserve(self._h, N, E, B, d_max))
+
+    def status(self, stream=None):
+        self.check(lib().sgnn_ctx_status(self._h, _stream(stream)))
+
+    def close(self):
+        if self._h:
+            lib().sgnn_ctx_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Csr:
+    """Device buffers of a mini-batch CSR (rows x cols) with room for `capacity` entries."""
+
+    def __init__(self, rows: int, cols: int, capacity: int, device="cuda:0"):
+        self.rows, self.cols, self.capacity = rows, cols, capacity
+        self.rowptr = torch.zeros(rows + 1, dtype=torch.int32, device=device)
+        self.colidx = torch.zeros(max(capacity, 1), dtype=torch.int32, device=device)
+        self.val = torch.zeros(max(capacity, 1), dtype=torch.float32, device=device)
+        self.nnz_dev = torch.zeros(1, dtype=torch.int32, device=device)
+
+    @classmethod
+    def from_arrays(cls, rows, cols, rowptr, colidx, val, device="cuda:0"):
+        import numpy as np
+        c = cls(rows, cols, len(colidx), device)
+        c.rowptr.copy_(torch.as_tensor(np.asarray(rowptr, np.int32)))
+        if len(colidx):
+            c.colidx[:len(colidx)].copy_(torch.as_tensor(np.asarray(colidx, np.int32)))
+            c.val[:len(colidx)].copy_(torch.as_tensor(np.asarray(val, np.float32)))
+        c.nnz_dev.fill_(len(colidx))
+        return c
+
+    def struct(self) -> _Csr:
+        return _Csr(self.rows, self.cols, _ptr(self.rowptr, torch.int32), _ptr(self.colidx, torch.int32),
+                    _ptr(self.val, torch.float32), self.capacity, _ptr(self.nnz_dev, torch.int32))
+
+    def nnz(self) -> int:
+        return int(self.nnz_dev.item())
+
+
+# ------------------------------------------------------------------------------------------------
+# entry points, named as in include/sgnn.h
+# ------------------------------------------------------------------------------------------------
+
+def sgnn_sample_uniform(ctx: Context, N: int, B: int, seed: int, step: int, S: torch.Tensor, bitmap: torch.Tensor,
+                        rank: torch.Tensor, stream=None):
+    """S int32[B], bitmap int64[ceil(N/64)] (the bits of the C uint64 words), rank int32[ceil(N/64)]."""
+    W = (N + 63) // 64
+    if S is not None and S.numel() < B or bitmap is not None and bitmap.numel() < W or rank is not None and rank.numel() < W:
+        raise ValueError("output tensor too small")
+    ctx.check(lib().sgnn_sample_uniform(ctx._h, N, B, seed & (2**64 - 1), step & (2**64 - 1), _ptr(S, torch.int32, "S"),
+                                        _ptr(bitmap, torch.int64, "bitmap"), _ptr(rank, torch.int32, "rank"),
+                                        _stream(stream)))
+
+
+def sgnn_induced_csr(ctx: Context, N: int, rowptr: torch.Tensor, colidx: torch.Tensor, val: Optional[torch.Tensor],
+                     S: torch.Tensor, B: int, bitmap: torch.Tensor, rank: torch.Tensor, out: Csr,
+                     norm_mode: int = 0, rescale: int = 1, want_nnz: bool = False, stream=None) -> Optional[int]:
+    """Returns the entry count when want_nnz (synchronises), else None."""
+    if rowptr.dtype not in (torch.int32, torch.int64):
+        raise TypeError("rowptr must be int32 or int64")
+    if rowptr.numel() != N + 1:
+        raise ValueError("rowptr must have N+1 entries")
+    g = _Graph(N, colidx.numel(), _ptr(rowptr, None, "rowptr"), int(rowptr.dtype == torch.int64),
+               _ptr(colidx, torch.int32, "colidx"), _ptr(val, torch.float32, "val"))
+    if out.rowptr.numel() < B + 1:
+        raise ValueError("out.rowptr too small")
+    cs = out.struct()
+    nnz = C.c_uint64(0)
+    rc = lib().sgnn_induced_csr(ctx._h, C.byref(g), _ptr(S, torch.int32, "S"), B, _ptr(bitmap, torch.int64, "bitmap"),
+                                _ptr(rank, torch.int32, "rank"), norm_mode, rescale, C.byref(cs),
+                                C.byref(nnz) if want_nnz else None, _stream(stream))
+    out.rows = out.cols = B
+    ctx.check(rc)
+    return int(nnz.value) if want_nnz else None
+
+
+def sgnn_gather_rows(ctx: Context, X: Optional[torch.Tensor], S: torch.Tensor, B: int, out: Optional[torch.Tensor],
+                     labels: Optional[torch.Tensor] = None, labels_out: Optional[torch.Tensor] = None, stream=None):
+    if X is not None and (out.shape[0] < B or out.shape[1] != X.shape[1]):
+        raise ValueError("out has the wrong shape")
+    d, ldx, ldo = (X.shape[1], X.stride(0), out.stride(0)) if X is not None else (0, 0, 0)
+    ctx.check(lib().sgnn_gather_rows(ctx._h, _ptr(X, torch.float32, "X"), d, ldx,
+                                     _ptr(S, torch.int32, "S"), B, _ptr(out, torch.float32, "out"), ldo,
+                                     _ptr(labels, torch.int32, "labels"), _ptr(labels_out, torch.int32, "labels_out"),
+                                     _stream(stream)))
+
+
+def sgnn_gcn_fwd(ctx: Context, A: Csr, H: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], flags: int,
+                 Y: torch.Tensor, T: torch.Tensor, row_index: Optional[torch.Tensor] = None, stream=None):
+    a = A.struct()
+    h, w, y, t = _mat(H, row_index, "H"), _mat(W, None, "W"), _mat(Y, None, "Y"), _mat(T, None, "T")
+    ctx.check(lib().sgnn_gcn_fwd(ctx._h, C.byref(a), C.byref(h), C.byref(w), _ptr(bias, torch.float32, "bias"), flags,
+                                 C.byref(y), C.byref(t), _stream(stream)))
+
+
+def sgnn_gcn_bwd(ctx: Context, A_T: Csr, T: torch.Tensor, W: torch.Tensor, Y: Optional[torch.Tensor], dY: torch.Tensor,
+                 flags: int, dH: Optional[torch.Tensor], dW: torch.Tensor, dbias: Optional[torch.Tensor], stream=None):
+    a = A_T.struct()
+    t, w, dy = _mat(T, None, "T"), _mat(W, None, "W"), _mat(dY, None, "dY")
+    y = _mat(Y, None, "Y") if Y is not None else None
+    dh = _mat(dH, None, "dH") if dH is not None else None
+    if dW.shape != W.shape or not dW.is_contiguous():
+        raise ValueError("dW must be contiguous with the shape of W")
+    ctx.check(lib().sgnn_gcn_bwd(ctx._h, C.byref(a), C.byref(t), C.byref(w), C.byref(y) if y is not None else None,
+                                 C.byref(dy), flags, C.byref(dh) if dh is not None else None,
+                                 _ptr(dW, torch.float32, "dW"), _ptr(dbias, torch.float32, "dbias"), _stream(stream)))
+
+
+def sgnn_softmax_xent(ctx: Context, O: torch.Tensor, labels: torch.Tensor, loss: Optional[torch.Tensor],
+                      dO: Optional[torch.Tensor], stream=None):
+    ctx.check(lib().sgnn_softmax_xent(ctx._h, _ptr(O, torch.float32, "O"), O.stride(0), _ptr(labels, torch.int32, "labels"),
+                                      O.shape[0], O.shape[1], _ptr(loss, torch.float32, "loss"),
+                                      _ptr(dO, torch.float32, "dO"), dO.stride(0) if dO is not None else 0,
+                                      _stream(stream)))
+
+
+def sgnn_spmm(ctx: Context, A: Csr, X: torch.Tensor, out: torch.Tensor, row_index: Optional[torch.Tensor] = None,
+              stream=None):
+    a = A.struct()
+    x, o = _mat(X, row_index, "X"), _mat(out, None, "out")
+    ctx.check(lib().sgnn_spmm(ctx._h, C.byref(a), C.byref(x), C.byref(o), _stream(stream)))
+
+
+def sgnn_gemm(ctx: Context, trans_a: bool, trans_b: bool, A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor],
+              flags: int, Cm: torch.Tensor, stream=None):
+    M, N = Cm.shape
+    K = A.shape[0] if trans_a else A.shape[1]
+    ctx.check(lib().sgnn_gemm(ctx._h, int(trans_a), int(trans_b), M, N, K, _ptr(A, torch.float32, "A"), A.stride(0),
+                              _ptr(B, torch.float32, "B"), B.stride(0), _ptr(bias, torch.float32, "bias"), flags,
+                              _ptr(Cm, torch.float32, "C"), Cm.stride(0), _stream(stream)))

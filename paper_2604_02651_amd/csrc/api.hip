@@ -1,0 +1,299 @@
+// C ABI of libsgnn: argument validation, context and scratch management, and the composition of the
+// kernels into the calls declared in sgnn.h.
+#include <stdarg.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "common.h"
+
+size_t sgnn_sampler_persist_bytes();
+size_t sgnn_sampler_ws_bytes(uint64_t N);
+size_t sgnn_induced_ws_bytes(uint64_t E, uint32_t B);
+size_t sgnn_gemm_ws_bytes(uint32_t d_max);
+
+int sgnn_fail(sgnn_ctx *ctx, int code, const char *fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+namespace {
+
+constexpr size_t PERSIST_BYTES = 16384;
+
+int bind_device(sgnn_ctx *ctx)
+{
+    SGNN_HIP(ctx, hipSetDevice(ctx->device));
+    return SGNN_OK;
+}
+
+bool mat_ok(const sgnn_mat *m) { return m && m->ptr && m->dtype == SGNN_F32 && m->rows >= 0 && m->cols >= 0 && m->ld >= m->cols; }
+
+bool csr_ok(const sgnn_csr *c) { return c && c->rowptr && (c->capacity == 0 || (c->colidx && c->val)); }
+
+} // namespace
+
+extern "C" {
+
+int sgnn_ctx_create(sgnn_ctx **out, int device)
+{
+    if (!out) return SGNN_ERR_INVALID_ARG;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return SGNN_ERR_HIP;
+    sgnn_ctx *ctx = new (std::nothrow) sgnn_ctx();
+    if (!ctx) return SGNN_ERR_HIP;
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->device = device;
+    if (hipSetDevice(device) != hipSuccess || hipMalloc(&ctx->persist, PERSIST_BYTES) != hipSuccess) {
+        delete ctx;
+        return SGNN_ERR_HIP;
+    }
+    if (hipMemset(ctx->persist, 0, PERSIST_BYTES) != hipSuccess) {
+        hipFree(ctx->persist);
+        delete ctx;
+        return SGNN_ERR_HIP;
+    }
+    ctx->status = reinterpret_cast<uint32_t *>(ctx->persist + PERSIST_BYTES - 256);
+    *out = ctx;
+    return SGNN_OK;
+}
+
+int sgnn_ctx_destroy(sgnn_ctx *ctx)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    hipSetDevice(ctx->device);
+    hipDeviceSynchronize();
+    if (ctx->ws) hipFree(ctx->ws);
+    if (ctx->persist) hipFree(ctx->persist);
+    delete ctx;
+    return SGNN_OK;
+}
+
+const char *sgnn_last_error(const sgnn_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t d_max)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    size_t need = sgnn_sampler_ws_bytes(N);
+    need = std::max(need, sgnn_induced_ws_bytes(E, B));
+    // backward: dZ and dT (B x d_max each), split-K partials, column-sum partials
+    size_t layer = (size_t)2 * B * d_max * 4 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 + 16 * 256;
+    need = std::max(need, layer);
+    need = std::max(need, (size_t)B / 64 * 4 + 4096);
+    need += 4096;
+    if (need > ctx->ws_bytes) {
+        SGNN_HIP(ctx, hipDeviceSynchronize());
+        if (ctx->ws) SGNN_HIP(ctx, hipFree(ctx->ws));
+        ctx->ws = nullptr;
+        ctx->ws_bytes = 0;
+        SGNN_HIP(ctx, hipMalloc(&ctx->ws, need));
+        ctx->ws_bytes = need;
+    }
+    ctx->res_N = N; ctx->res_E = E; ctx->res_B = B; ctx->res_d = d_max;
+    return SGNN_OK;
+}
+
+int sgnn_ctx_status(sgnn_ctx *ctx, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t word = 0;
+    SGNN_HIP(ctx, hipMemcpyAsync(&word, ctx->status, sizeof(word), hipMemcpyDeviceToHost, st));
+    SGNN_HIP(ctx, hipStreamSynchronize(st));
+    if (word) {
+        SGNN_HIP(ctx, hipMemsetAsync(ctx->status, 0, sizeof(word), st));
+        SGNN_HIP(ctx, hipStreamSynchronize(st));
+        return sgnn_fail(ctx, SGNN_ERR_INTERNAL, "device status 0x%x:%s%s", word,
+                         (word & SGNN_ST_CAND_OVERFLOW) ? " sampler selection inconsistent" : "",
+                         (word & SGNN_ST_NNZ_OVERFLOW) ? " induced entry count exceeds int32" : "");
+    }
+    return SGNN_OK;
+}
+
+int sgnn_sample_uniform(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, uint64_t step, int32_t *S,
+                        uint64_t *bitmap, uint32_t *rank, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!S || !bitmap || !rank) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_sample_uniform: null output pointer");
+    if (B == 0 || B > N) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_sample_uniform: need 1 <= B <= N (B=%u, N=%llu)", B, (unsigned long long)N);
+    if (N >= (1ull << 31)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_sample_uniform: N must be below 2^31");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return sgnn_launch_sampler(ctx, N, B, seed, step, S, bitmap, rank, static_cast<hipStream_t>(stream));
+}
+
+int sgnn_induced_csr(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B, const uint64_t *bitmap,
+                     const uint32_t *rank, int norm_mode, int rescale, sgnn_csr *out, uint64_t *nnz_host,
+                     sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!g || !g->rowptr || !g->colidx || !S || !bitmap || !rank || !out || !out->rowptr)
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_induced_csr: null pointer");
+    if (out->capacity > 0 && (!out->colidx || !out->val))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_induced_csr: capacity > 0 but colidx/val is null");
+    if (B == 0 || B > g->N) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_induced_csr: need 1 <= B <= N");
+    if (g->N >= (1ull << 31)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_induced_csr: N must be below 2^31");
+    if (!g->rowptr_is_i64 && g->E >= (1ull << 31))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_induced_csr: E >= 2^31 needs an int64 rowptr");
+    if (norm_mode != 0 && norm_mode != 1) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_induced_csr: norm_mode must be 0 or 1");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t *nnz_dev = out->nnz_dev;
+    sgnn_csr o = *out;
+    o.rows = o.cols = B;
+    if (nnz_host && !nnz_dev) o.nnz_dev = ctx->status + 2;
+    rc = sgnn_launch_induced(ctx, g, S, B, bitmap, rank, norm_mode, rescale, &o, st);
+    if (rc) return rc;
+    out->rows = out->cols = B;
+    if (nnz_host) {
+        uint32_t n = 0;
+        SGNN_HIP(ctx, hipMemcpyAsync(&n, o.nnz_dev, sizeof(n), hipMemcpyDeviceToHost, st));
+        SGNN_HIP(ctx, hipStreamSynchronize(st));
+        *nnz_host = n;
+        if (n > out->capacity)
+            return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_induced_csr: %u entries do not fit capacity %llu", n,
+                             (unsigned long long)out->capacity);
+    }
+    return SGNN_OK;
+}
+
+int sgnn_gather_rows(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, const int32_t *S, uint32_t B, float *out,
+                     int64_t ldo, const int32_t *labels, int32_t *labels_out, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!S || (labels && !labels_out) || (!X && !labels))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gather_rows: bad argument");
+    if (X && (!out || d <= 0 || ldx < d || ldo < d))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gather_rows: bad matrix argument");
+    if (B == 0) return SGNN_OK;
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return sgnn_launch_gather(ctx, X, d, ldx, S, B, out, ldo, labels, labels_out, static_cast<hipStream_t>(stream));
+}
+
+int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, sgnn_mat *out, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!csr_ok(A) || !mat_ok(X) || !mat_ok(out)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: bad argument");
+    if (out->rows != A->rows || out->cols != X->cols || (!X->row_index && X->rows != A->cols))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: shape mismatch");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return sgnn_launch_spmm(ctx, A, static_cast<const float *>(X->ptr), X->ld, X->row_index, X->cols,
+                            static_cast<float *>(out->ptr), out->ld, static_cast<hipStream_t>(stream));
+}
+
+int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+              const float *B, int64_t ldb, const float *bias, int flags, float *C, int64_t ldc, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!A || !B || !C || M < 0 || N < 0 || K < 0) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: bad argument");
+    if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N)
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: leading dimension too small");
+    if (M == 0 || N == 0) return SGNN_OK;
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    ws_alloc ws(ctx);
+    return sgnn_launch_gemm(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, B, ldb, bias, flags, C, ldc, &ws,
+                            static_cast<hipStream_t>(stream));
+}
+
+int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn_mat *W, const float *bias, int flags,
+                 sgnn_mat *Y, sgnn_mat *T, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!csr_ok(A) || !mat_ok(H) || !mat_ok(W) || !mat_ok(Y) || !mat_ok(T))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_fwd: bad argument");
+    const int64_t Bn = A->rows, d_in = W->rows, d_out = W->cols;
+    if (H->cols != d_in || T->rows != Bn || T->cols != d_in || Y->rows != Bn || Y->cols != d_out ||
+        (!H->row_index && H->rows != A->cols) || W->row_index || Y->row_index || T->row_index)
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_fwd: shape mismatch");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = sgnn_launch_spmm(ctx, A, static_cast<const float *>(H->ptr), H->ld, H->row_index, d_in,
+                          static_cast<float *>(T->ptr), T->ld, st);
+    if (rc) return rc;
+    ws_alloc ws(ctx);
+    return sgnn_launch_gemm(ctx, 0, 0, Bn, d_out, d_in, static_cast<const float *>(T->ptr), T->ld,
+                            static_cast<const float *>(W->ptr), W->ld, bias, flags & (SGNN_RELU | SGNN_BF16_MFMA),
+                            static_cast<float *>(Y->ptr), Y->ld, &ws, st);
+}
+
+int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sgnn_mat *W, const sgnn_mat *Y,
+                 const sgnn_mat *dY, int flags, sgnn_mat *dH, float *dW, float *dbias, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!csr_ok(A_T) || !mat_ok(T) || !mat_ok(W) || !mat_ok(dY) || !dW || (dH && !mat_ok(dH)))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: bad argument");
+    const int relu = (flags & SGNN_RELU) ? 1 : 0;
+    if (relu && !mat_ok(Y)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: SGNN_RELU needs Y");
+    const int64_t Bn = T->rows, d_in = W->rows, d_out = W->cols;
+    if (T->cols != d_in || dY->rows != Bn || dY->cols != d_out || (relu && (Y->rows != Bn || Y->cols != d_out)) ||
+        (dH && (dH->rows != A_T->rows || dH->cols != d_in || A_T->cols != Bn)))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: shape mismatch");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ws_alloc ws(ctx);
+    const int mfma = flags & SGNN_BF16_MFMA;
+
+    // element-wise backward: ReLU mask and bias gradient
+    const float *dZ = static_cast<const float *>(dY->ptr);
+    int64_t lddz = dY->ld;
+    if (relu || dbias) {
+        float *dZbuf = nullptr;
+        if (relu) {
+            dZbuf = ws.get<float>((size_t)Bn * d_out);
+            if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
+        }
+        rc = sgnn_launch_relu_bwd_bias(ctx, relu ? static_cast<const float *>(Y->ptr) : nullptr, relu ? Y->ld : 0,
+                                       static_cast<const float *>(dY->ptr), dY->ld, relu, Bn, d_out, dZbuf, d_out, dbias,
+                                       &ws, st);
+        if (rc) return rc;
+        if (relu) { dZ = dZbuf; lddz = d_out; }
+    }
+    // dW = T^T dZ
+    rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, dZ, lddz, nullptr, mfma,
+                          dW, d_out, &ws, st);
+    if (rc) return rc;
+    if (dH) {
+        // dT = dZ W^T, dH = A^T dT
+        float *dT = ws.get<float>((size_t)Bn * d_in);
+        if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
+        rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, static_cast<const float *>(W->ptr), W->ld, nullptr,
+                              mfma, dT, d_in, &ws, st);
+        if (rc) return rc;
+        rc = sgnn_launch_spmm(ctx, A_T, dT, d_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, st);
+        if (rc) return rc;
+    }
+    return SGNN_OK;
+}
+
+int sgnn_softmax_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C,
+                      float *loss_dev, float *dO, int64_t lddo, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!O || !labels || B == 0 || C == 0 || ldo < C || (dO && lddo < C))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_softmax_xent: bad argument");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    ws_alloc ws(ctx);
+    return sgnn_launch_xent(ctx, O, ldo, labels, B, C, loss_dev, dO, lddo, &ws, static_cast<hipStream_t>(stream));
+}
+
+} // extern "C"

@@ -1,0 +1,63 @@
+// Wavefront (64 lanes) and workgroup primitives used by the integer kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+__device__ __forceinline__ unsigned lane_id() { return threadIdx.x & 63u; }
+
+// Inclusive prefix sum across the 64 lanes of a wavefront.
+template <class T> __device__ __forceinline__ T wave_incl_scan(T x)
+{
+    const unsigned lane = lane_id();
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        T y = __shfl_up(x, o, 64);
+        if (lane >= (unsigned)o) x += y;
+    }
+    return x;
+}
+
+template <class T> __device__ __forceinline__ T wave_sum(T x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+// Exclusive prefix sum over the NT threads of a workgroup (NT a multiple of 64, <= 1024).
+// Returns the exclusive prefix of x in thread order and stores the workgroup total in *total.
+// lds must hold NT/64 + 1 elements; the call contains two barriers and may be repeated
+// immediately (it ends with a barrier).
+template <class T, int NT> __device__ __forceinline__ T block_excl_scan(T x, T *total, T *lds)
+{
+    constexpr int NW = NT / 64;
+    const unsigned lane = lane_id(), w = threadIdx.x >> 6;
+    T inc = wave_incl_scan(x);
+    if (lane == 63) lds[w] = inc;
+    __syncthreads();
+    if (w == 0) {
+        T v = lane < NW ? lds[lane] : T(0);
+        T s = wave_incl_scan(v);
+        if (lane < NW) lds[lane] = s - v;
+        if (lane == NW - 1) lds[NW] = s;
+    }
+    __syncthreads();
+    T res = lds[w] + inc - x;
+    *total = lds[NW];
+    __syncthreads();
+    return res;
+}
+
+template <class T, int NT> __device__ __forceinline__ T block_sum(T x, T *lds)
+{
+    constexpr int NW = NT / 64;
+    const unsigned lane = lane_id(), w = threadIdx.x >> 6;
+    T s = wave_sum(x);
+    if (lane == 0) lds[w] = s;
+    __syncthreads();
+    T t = T(0);
+#pragma unroll
+    for (int i = 0; i < NW; ++i) t += lds[i];
+    __syncthreads();
+    return t;
+}

@@ -1,0 +1,87 @@
+// Internal declarations shared by the HIP translation units of libsgnn (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "sgnn.h"
+
+#define SGNN_WAVE 64
+
+struct sgnn_ctx {
+    int device;
+    char err[512];
+    uint8_t *ws;        // device scratch, carved afresh by every call
+    uint8_t *persist;   // small device area that keeps its contents between calls
+    size_t ws_bytes;
+    uint32_t *status;   // device uint32[4]: [0] sticky error bits set by kernels
+    uint64_t res_N, res_E;
+    uint32_t res_B, res_d;
+};
+
+// status bits
+#define SGNN_ST_CAND_OVERFLOW 1u
+#define SGNN_ST_NNZ_OVERFLOW 2u
+
+int sgnn_fail(sgnn_ctx *ctx, int code, const char *fmt, ...);
+
+#define SGNN_HIP(ctx, call)                                                                     \
+    do {                                                                                        \
+        hipError_t e_ = (call);                                                                 \
+        if (e_ != hipSuccess)                                                                   \
+            return sgnn_fail((ctx), SGNN_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+#define SGNN_LAUNCH_CHECK(ctx, name)                                                            \
+    do {                                                                                        \
+        hipError_t e_ = hipGetLastError();                                                      \
+        if (e_ != hipSuccess)                                                                   \
+            return sgnn_fail((ctx), SGNN_ERR_HIP, "launch of %s failed: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+// Bump allocator over the context scratch, reset at the start of every API call.
+struct ws_alloc {
+    uint8_t *base;
+    size_t cap, off;
+    bool ok;
+    explicit ws_alloc(sgnn_ctx *c) : base(c->ws), cap(c->ws_bytes), off(0), ok(true) {}
+    template <class T> T *get(size_t n) {
+        size_t bytes = (n * sizeof(T) + 255) & ~size_t(255);
+        if (!base || off + bytes > cap) { ok = false; off += bytes; return nullptr; }
+        T *p = reinterpret_cast<T *>(base + off);
+        off += bytes;
+        return p;
+    }
+};
+
+static inline unsigned cdiv(uint64_t a, uint64_t b) { return (unsigned)((a + b - 1) / b); }
+
+// ---- scan.hip ---------------------------------------------------------------------------------
+// Exclusive prefix sum of n uint32 (n known on the host), 64-bit result: out[i] = sum_{k<i} in[k]
+// for i <= n (out has n+1 entries).  tmp: ceil(n/2048)+1 uint64.
+size_t sgnn_scan_tmp_elems(uint64_t n);
+int sgnn_scan_u32_to_u64(sgnn_ctx *ctx, const uint32_t *in, uint64_t *out, uint64_t n, uint64_t *tmp,
+                         hipStream_t st);
+// Same with a 32-bit result and the element count read from device memory (*n_dev <= n_max).
+int sgnn_scan_u32_devn(sgnn_ctx *ctx, const uint32_t *in, uint32_t *out, const uint64_t *n_dev,
+                       uint64_t n_max, uint32_t *tmp, hipStream_t st);
+
+// ---- launchers ----------------------------------------------------------------------------------
+int sgnn_launch_sampler(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, uint64_t step, int32_t *S,
+                        uint64_t *bitmap, uint32_t *rank, hipStream_t st);
+int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B,
+                        const uint64_t *bitmap, const uint32_t *rank, int norm_mode, int rescale,
+                        sgnn_csr *out, hipStream_t st);
+int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index,
+                     int64_t d, float *out, int64_t ldo, hipStream_t st);
+int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A,
+                     int64_t lda, const float *B, int64_t ldb, const float *bias, int flags, float *C,
+                     int64_t ldc, ws_alloc *ws, hipStream_t st);
+int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const float *dY, int64_t lddy,
+                              int relu, int64_t rows, int64_t cols, float *dZ, int64_t lddz, float *dbias,
+                              ws_alloc *ws, hipStream_t st);
+int sgnn_launch_gather(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, const int32_t *S, uint32_t B,
+                       float *out, int64_t ldo, const int32_t *labels, int32_t *labels_out, hipStream_t st);
+int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C,
+                     float *loss, float *dO, int64_t lddo, ws_alloc *ws, hipStream_t st);

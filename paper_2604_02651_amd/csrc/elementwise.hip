@@ -1,0 +1,186 @@
+// Memory-bound helpers around the two big operators: the feature / label slice (Eq. 26), the
+// element-wise part of the layer backward (ReLU mask and bias gradient), and the harness loss.
+#include "block_prims.h"
+#include "common.h"
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// out[i, :] = X[S[i], :];  VEC = 4 when everything is 16-byte aligned, else 1.
+template <int VEC>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float *__restrict__ X, int64_t dv, int64_t ldx,
+                                                          const int32_t *__restrict__ S, uint32_t B,
+                                                          float *__restrict__ out, int64_t ldo,
+                                                          const int32_t *__restrict__ labels,
+                                                          int32_t *__restrict__ labels_out)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = idx / dv, c = idx % dv;
+    if (i >= B) return;
+    const int64_t v = S[i];
+    if (X) {
+        if (VEC == 4)
+            *reinterpret_cast<f32x4 *>(out + i * ldo + 4 * c) = *reinterpret_cast<const f32x4 *>(X + v * ldx + 4 * c);
+        else
+            out[i * ldo + c] = X[v * ldx + c];
+    }
+    if (c == 0 && labels) labels_out[i] = labels[v];
+}
+
+// dZ = dY where Y > 0 (or all of dY), and per-workgroup column sums of dZ.
+// Thread (tx, ty): tx < CW walks columns tx, tx+CW, ...; ty walks the rows of the workgroup's slab.
+template <int CW>
+__global__ __launch_bounds__(256) void relu_bwd_colsum_kernel(const float *__restrict__ Y, int64_t ldy,
+                                                              const float *__restrict__ dY, int64_t lddy, int relu,
+                                                              int64_t rows, int cols, int64_t rows_per_wg,
+                                                              float *__restrict__ dZ, int64_t lddz,
+                                                              float *__restrict__ partial)
+{
+    constexpr int RY = 256 / CW;
+    __shared__ float red[256];
+    const int tx = threadIdx.x % CW, ty = threadIdx.x / CW;
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_wg, r1 = min(rows, r0 + rows_per_wg);
+    for (int c0 = 0; c0 < cols; c0 += CW) {
+        const int col = c0 + tx;
+        float acc = 0.f;
+        if (col < cols) {
+            for (int64_t r = r0 + ty; r < r1; r += RY) {
+                float g = dY[r * lddy + col];
+                if (relu && !(Y[r * ldy + col] > 0.f)) g = 0.f;
+                if (dZ) dZ[r * lddz + col] = g;
+                acc += g;
+            }
+        }
+        if (partial) {
+            red[threadIdx.x] = acc;
+            __syncthreads();
+            if (ty == 0 && col < cols) {
+                float s = 0.f;
+#pragma unroll
+                for (int q = 0; q < RY; ++q) s += red[q * CW + tx];
+                partial[(int64_t)blockIdx.x * cols + col] = s;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restrict__ partial, int nwg, int cols,
+                                                           float *__restrict__ out)
+{
+    const int col = blockIdx.x * 256 + threadIdx.x;
+    if (col >= cols) return;
+    float s = 0.f;
+    for (int w = 0; w < nwg; ++w) s += partial[(int64_t)w * cols + col];
+    out[col] = s;
+}
+
+// One wavefront per row; a workgroup covers 64 rows and writes one partial loss.
+__global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, int64_t ldo,
+                                                   const int32_t *__restrict__ labels, uint32_t B, uint32_t C,
+                                                   float *__restrict__ dO, int64_t lddo, float *__restrict__ partial)
+{
+    __shared__ float lds[4];
+    const unsigned wave = threadIdx.x >> 6, lane = lane_id();
+    float loss = 0.f;
+    const float invB = 1.f / (float)B;
+    for (int q = 0; q < 16; ++q) {
+        const uint32_t row = blockIdx.x * 64 + q * 4 + wave;
+        if (row >= B) break;
+        const float *o = O + (int64_t)row * ldo;
+        float m = -INFINITY;
+        for (uint32_t j = lane; j < C; j += 64) m = fmaxf(m, o[j]);
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+        float sum = 0.f;
+        for (uint32_t j = lane; j < C; j += 64) sum += expf(o[j] - m);
+        sum = wave_sum(sum);
+        const float lse = m + logf(sum);
+        const int32_t y = labels[row];
+        loss += lse - ((uint32_t)y < C ? o[y] : 0.f);
+        if (dO)
+            for (uint32_t j = lane; j < C; j += 64)
+                dO[(int64_t)row * lddo + j] = (expf(o[j] - lse) - ((int32_t)j == y ? 1.f : 0.f)) * invB;
+    }
+    if (lane == 0) lds[wave] = loss;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = (lds[0] + lds[1]) + (lds[2] + lds[3]);
+}
+
+__global__ __launch_bounds__(1024) void xent_final_kernel(const float *__restrict__ partial, int n, float invB,
+                                                          float *__restrict__ loss)
+{
+    __shared__ float lds[1024 / 64];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < n; i += 1024) s += partial[i];
+    s = block_sum<float, 1024>(s, lds);
+    if (threadIdx.x == 0) *loss = s * invB;
+}
+
+} // namespace
+
+int sgnn_launch_gather(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, const int32_t *S, uint32_t B, float *out,
+                       int64_t ldo, const int32_t *labels, int32_t *labels_out, hipStream_t st)
+{
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(out);
+    if (!X) {   // labels only
+        hipLaunchKernelGGL(gather_rows_kernel<1>, dim3(cdiv(B, 256)), dim3(256), 0, st, X, 1, 0, S, B, out, 0, labels,
+                           labels_out);
+    } else if (d % 4 == 0 && ldx % 4 == 0 && ldo % 4 == 0 && (bits & 15) == 0) {
+        hipLaunchKernelGGL(gather_rows_kernel<4>, dim3(cdiv((uint64_t)B * (d / 4), 256)), dim3(256), 0, st, X, d / 4, ldx,
+                           S, B, out, ldo, labels, labels_out);
+    } else {
+        hipLaunchKernelGGL(gather_rows_kernel<1>, dim3(cdiv((uint64_t)B * d, 256)), dim3(256), 0, st, X, d, ldx, S, B, out,
+                           ldo, labels, labels_out);
+    }
+    SGNN_LAUNCH_CHECK(ctx, "gather_rows_kernel");
+    return SGNN_OK;
+}
+
+int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const float *dY, int64_t lddy, int relu,
+                              int64_t rows, int64_t cols, float *dZ, int64_t lddz, float *dbias, ws_alloc *ws,
+                              hipStream_t st)
+{
+    int64_t rows_per_wg = (rows + 1023) / 1024;
+    if (rows_per_wg < 64) rows_per_wg = 64;
+    const unsigned nwg = cdiv(rows, rows_per_wg);
+    float *partial = nullptr;
+    if (dbias) {
+        partial = ws->get<float>((size_t)nwg * cols);
+        if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
+    }
+    if (cols <= 32)
+        hipLaunchKernelGGL(relu_bwd_colsum_kernel<32>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
+                           rows_per_wg, dZ, lddz, partial);
+    else if (cols <= 64)
+        hipLaunchKernelGGL(relu_bwd_colsum_kernel<64>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
+                           rows_per_wg, dZ, lddz, partial);
+    else if (cols <= 128)
+        hipLaunchKernelGGL(relu_bwd_colsum_kernel<128>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
+                           rows_per_wg, dZ, lddz, partial);
+    else
+        hipLaunchKernelGGL(relu_bwd_colsum_kernel<256>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
+                           rows_per_wg, dZ, lddz, partial);
+    SGNN_LAUNCH_CHECK(ctx, "relu_bwd_colsum_kernel");
+    if (dbias) {
+        hipLaunchKernelGGL(colsum_final_kernel, dim3(cdiv(cols, 256)), dim3(256), 0, st, partial, (int)nwg, (int)cols, dbias);
+        SGNN_LAUNCH_CHECK(ctx, "colsum_final_kernel");
+    }
+    return SGNN_OK;
+}
+
+int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C, float *loss,
+                     float *dO, int64_t lddo, ws_alloc *ws, hipStream_t st)
+{
+    const unsigned nwg = cdiv(B, 64);
+    float *partial = ws->get<float>(nwg);
+    if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_softmax_xent: scratch too small: call sgnn_ctx_reserve");
+    hipLaunchKernelGGL(xent_kernel, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, dO, lddo, partial);
+    SGNN_LAUNCH_CHECK(ctx, "xent_kernel");
+    if (loss) {
+        hipLaunchKernelGGL(xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, 1.f / (float)B, loss);
+        SGNN_LAUNCH_CHECK(ctx, "xent_final_kernel");
+    }
+    return SGNN_OK;
+}

@@ -1,0 +1,328 @@
+// Uniform vertex sampling without replacement (Sec. III-D "Vertex Sampling", Eq. 20).
+//
+// The sample is the B vertices with the smallest (key(v), v), key(v) being 64 bits of
+// Philox4x32-10 (Salmon et al., SC'11) counted by (v/2, step) and keyed by the seed.  Keys are
+// never stored: every pass recomputes them (about 100 integer ALU operations per two vertices),
+// which is cheaper on this machine than writing and re-reading 8 bytes per vertex.
+//
+//   1. sampler_hist_kernel     histogram of the top 11 key bits (LDS histograms, one merge)
+//   2. sampler_pick_bin_kernel the bin b* that holds the B-th smallest key and the rank r inside
+//   3. sampler_collect_kernel  (key, v) of every vertex in bin b* -> candidate list (about N/2048)
+//   4. sampler_threshold_kernel exact r-th smallest (key, v) of the candidates, by radix select
+//   5. sampler_emit_kernel     bitmap word per 64 vertices from wave ballots + per-workgroup counts
+//   6. sampler_rank_kernel     rank prefix per bitmap word and the ascending list S
+#include "block_prims.h"
+#include <algorithm>
+
+#include "common.h"
+
+namespace {
+
+constexpr int HIST_BITS = 11;
+constexpr int HIST_BINS = 1 << HIST_BITS;
+constexpr int SAMP_NT = 256;
+constexpr unsigned EMIT_MAX_WG = 1024;
+
+struct sampler_state {
+    uint32_t bin;       // histogram bin of the threshold key
+    uint32_t r;         // 1-based rank of the threshold inside that bin
+    uint32_t ncand;     // candidates appended by the collect pass
+    uint32_t thr_v;     // threshold vertex
+    uint64_t thr_key;   // threshold key
+};
+
+struct philox_out { uint32_t w0, w1, w2, w3; };
+
+__device__ __forceinline__ philox_out philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                    uint32_t k1)
+{
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return {c0, c1, c2, c3};
+}
+
+// keys of vertices 2j (even) and 2j+1 (odd)
+__device__ __forceinline__ void vertex_pair_keys(uint64_t j, uint64_t seed, uint64_t step, uint64_t &ke, uint64_t &ko)
+{
+    philox_out o = philox4x32_10((uint32_t)j, (uint32_t)(j >> 32), (uint32_t)step, (uint32_t)(step >> 32),
+                                 (uint32_t)seed, (uint32_t)(seed >> 32));
+    ke = ((uint64_t)o.w1 << 32) | o.w0;
+    ko = ((uint64_t)o.w3 << 32) | o.w2;
+}
+
+__global__ __launch_bounds__(SAMP_NT) void sampler_hist_kernel(uint64_t N, uint64_t seed, uint64_t step,
+                                                               uint32_t *__restrict__ hist)
+{
+    __shared__ uint32_t lh[HIST_BINS];
+    for (int i = threadIdx.x; i < HIST_BINS; i += SAMP_NT) lh[i] = 0;
+    __syncthreads();
+    const uint64_t J = (N + 1) >> 1;
+    for (uint64_t j = (uint64_t)blockIdx.x * SAMP_NT + threadIdx.x; j < J; j += (uint64_t)gridDim.x * SAMP_NT) {
+        uint64_t ke, ko;
+        vertex_pair_keys(j, seed, step, ke, ko);
+        atomicAdd(&lh[ke >> (64 - HIST_BITS)], 1u);
+        if (2 * j + 1 < N) atomicAdd(&lh[ko >> (64 - HIST_BITS)], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < HIST_BINS; i += SAMP_NT) {
+        uint32_t c = lh[i];
+        if (c) atomicAdd(&hist[i], c);
+    }
+}
+
+// One workgroup of 1024 threads, two bins a thread.  Leaves the histogram zeroed for the next call.
+__global__ __launch_bounds__(1024) void sampler_pick_bin_kernel(uint32_t B, uint32_t *__restrict__ hist,
+                                                                sampler_state *__restrict__ state)
+{
+    __shared__ uint32_t lds[1024 / 64 + 1];
+    const uint32_t h0 = hist[2 * threadIdx.x], h1 = hist[2 * threadIdx.x + 1];
+    hist[2 * threadIdx.x] = 0;
+    hist[2 * threadIdx.x + 1] = 0;
+    uint32_t total;
+    const uint32_t ex = block_excl_scan<uint32_t, 1024>(h0 + h1, &total, lds);
+    if (ex < B && B <= ex + h0) {
+        state->bin = 2 * threadIdx.x;
+        state->r = B - ex;
+    } else if (ex + h0 < B && B <= ex + h0 + h1) {
+        state->bin = 2 * threadIdx.x + 1;
+        state->r = B - ex - h0;
+    }
+    if (threadIdx.x == 0) state->ncand = 0;
+}
+
+__global__ __launch_bounds__(SAMP_NT) void sampler_collect_kernel(uint64_t N, uint64_t seed, uint64_t step,
+                                                                  sampler_state *__restrict__ state,
+                                                                  uint64_t *__restrict__ cand_key,
+                                                                  uint32_t *__restrict__ cand_v, uint32_t cap,
+                                                                  uint32_t *__restrict__ status)
+{
+    const uint32_t bin = state->bin;
+    const uint64_t J = (N + 1) >> 1;
+    const uint64_t Jround = (J + 63) & ~uint64_t(63);   // whole wavefronts stay in the loop together
+    for (uint64_t j = (uint64_t)blockIdx.x * SAMP_NT + threadIdx.x; j < Jround; j += (uint64_t)gridDim.x * SAMP_NT) {
+        uint64_t ke = 0, ko = 0;
+        bool me = false, mo = false;
+        if (j < J) {
+            vertex_pair_keys(j, seed, step, ke, ko);
+            me = (uint32_t)(ke >> (64 - HIST_BITS)) == bin;
+            mo = (2 * j + 1 < N) && (uint32_t)(ko >> (64 - HIST_BITS)) == bin;
+        }
+        const uint64_t be = __ballot(me), bo = __ballot(mo);
+        const uint32_t ne = __popcll(be), no = __popcll(bo);
+        if (ne + no == 0) continue;
+        uint32_t base = 0;
+        if (lane_id() == 0) base = atomicAdd(&state->ncand, ne + no);
+        base = __shfl(base, 0, 64);
+        const uint64_t below = (1ull << lane_id()) - 1ull;
+        if (me) {
+            uint32_t p = base + __popcll(be & below);
+            if (p < cap) { cand_key[p] = ke; cand_v[p] = (uint32_t)(2 * j); }
+            else atomicOr(status, SGNN_ST_CAND_OVERFLOW);
+        }
+        if (mo) {
+            uint32_t p = base + ne + __popcll(bo & below);
+            if (p < cap) { cand_key[p] = ko; cand_v[p] = (uint32_t)(2 * j + 1); }
+            else atomicOr(status, SGNN_ST_CAND_OVERFLOW);
+        }
+    }
+}
+
+// Exact r-th smallest (key, v) among the candidates: most-significant-digit radix select over the
+// 96-bit composite, 8 bits a pass.  One workgroup.
+__global__ __launch_bounds__(1024) void sampler_threshold_kernel(sampler_state *__restrict__ state,
+                                                                 const uint64_t *__restrict__ cand_key,
+                                                                 const uint32_t *__restrict__ cand_v, uint32_t cap)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sel_digit, sel_r;
+    const uint32_t n = min(state->ncand, cap);
+    uint32_t r = state->r;
+    uint64_t pk = 0;   // decided high bits of the key
+    uint32_t pv = 0;   // decided high bits of the vertex
+    for (int pass = 0; pass < 12; ++pass) {
+        if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < n; i += 1024) {
+            const uint64_t k = cand_key[i];
+            const uint32_t v = cand_v[i];
+            bool match;
+            uint32_t digit;
+            if (pass < 8) {
+                const int decided = 8 * pass;
+                match = decided == 0 || (k >> (64 - decided)) == (pk >> (64 - decided));
+                digit = (uint32_t)(k >> (56 - decided)) & 255u;
+            } else {
+                const int decided = 8 * (pass - 8);
+                match = k == pk && (decided == 0 || (v >> (32 - decided)) == (pv >> (32 - decided)));
+                digit = (v >> (24 - decided)) & 255u;
+            }
+            if (match) atomicAdd(&hist[digit], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            // lane l owns digits 4l .. 4l+3
+            const uint32_t a0 = hist[4 * threadIdx.x], a1 = hist[4 * threadIdx.x + 1], a2 = hist[4 * threadIdx.x + 2],
+                           a3 = hist[4 * threadIdx.x + 3];
+            const uint32_t s = a0 + a1 + a2 + a3;
+            const uint32_t ex = wave_incl_scan(s) - s;
+            if (ex < r && r <= ex + s) {
+                uint32_t d = 4 * threadIdx.x, e = ex;
+                if (r > e + a0) { e += a0; ++d; if (r > e + a1) { e += a1; ++d; if (r > e + a2) { e += a2; ++d; } } }
+                sel_digit = d;
+                sel_r = r - e;
+            }
+        }
+        __syncthreads();
+        const uint32_t d = sel_digit;
+        r = sel_r;
+        if (pass < 8) pk |= (uint64_t)d << (56 - 8 * pass);
+        else pv |= d << (24 - 8 * (pass - 8));
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        state->thr_key = pk;
+        state->thr_v = pv;
+    }
+}
+
+__device__ __forceinline__ uint64_t spread_even(uint32_t x32)
+{
+    uint64_t x = x32;
+    x = (x | (x << 16)) & 0x0000FFFF0000FFFFull;
+    x = (x | (x << 8)) & 0x00FF00FF00FF00FFull;
+    x = (x | (x << 4)) & 0x0F0F0F0F0F0F0F0Full;
+    x = (x | (x << 2)) & 0x3333333333333333ull;
+    x = (x | (x << 1)) & 0x5555555555555555ull;
+    return x;
+}
+
+// Workgroup g owns bitmap words [g*wpw, (g+1)*wpw), wpw a multiple of 8.  A wavefront builds two
+// words per iteration: lane l evaluates vertices 2j and 2j+1 of Philox block j = 32*w0 + l.
+__global__ __launch_bounds__(SAMP_NT) void sampler_emit_kernel(uint64_t N, uint64_t seed, uint64_t step,
+                                                               const sampler_state *__restrict__ state,
+                                                               uint64_t *__restrict__ bitmap, uint64_t W, uint64_t wpw,
+                                                               uint32_t *__restrict__ wg_count)
+{
+    __shared__ uint32_t lds[SAMP_NT / 64];
+    const uint64_t tk = state->thr_key;
+    const uint32_t tv = state->thr_v;
+    const uint64_t wbeg = (uint64_t)blockIdx.x * wpw;
+    const uint64_t wend = min(W, wbeg + wpw);
+    const unsigned wave = threadIdx.x >> 6, lane = lane_id();
+    uint32_t cnt = 0;
+    for (uint64_t w0 = wbeg + 2 * wave; w0 < wend; w0 += 2 * (SAMP_NT / 64)) {
+        const uint64_t j = w0 * 32 + lane;
+        const uint64_t ve = 2 * j, vo = 2 * j + 1;
+        bool ie = false, io = false;
+        if (ve < N) {
+            uint64_t ke, ko;
+            vertex_pair_keys(j, seed, step, ke, ko);
+            ie = ke < tk || (ke == tk && (uint32_t)ve <= tv);
+            io = vo < N && (ko < tk || (ko == tk && (uint32_t)vo <= tv));
+        }
+        const uint64_t be = __ballot(ie), bo = __ballot(io);
+        const uint64_t word0 = spread_even((uint32_t)be) | (spread_even((uint32_t)bo) << 1);
+        const uint64_t word1 = spread_even((uint32_t)(be >> 32)) | (spread_even((uint32_t)(bo >> 32)) << 1);
+        if (lane == 0) bitmap[w0] = word0;
+        if (lane == 1 && w0 + 1 < wend) bitmap[w0 + 1] = word1;
+        cnt += __popcll(word0) + __popcll(word1);
+    }
+    if (lane == 0) lds[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int i = 0; i < SAMP_NT / 64; ++i) t += lds[i];
+        wg_count[blockIdx.x] = t;
+    }
+}
+
+__global__ __launch_bounds__(SAMP_NT) void sampler_rank_kernel(const uint64_t *__restrict__ bitmap, uint64_t W,
+                                                               uint64_t wpw, const uint32_t *__restrict__ wg_count,
+                                                               uint32_t B, uint32_t *__restrict__ rank,
+                                                               int32_t *__restrict__ S, uint32_t *__restrict__ status)
+{
+    __shared__ uint32_t lds[SAMP_NT / 64 + 1];
+    // sampled vertices in all earlier workgroups
+    uint32_t part = 0;
+    for (unsigned i = threadIdx.x; i < blockIdx.x; i += SAMP_NT) part += wg_count[i];
+    uint32_t running = block_sum<uint32_t, SAMP_NT>(part, lds);
+    const uint64_t wbeg = (uint64_t)blockIdx.x * wpw;
+    const uint64_t wend = min(W, wbeg + wpw);
+    for (uint64_t base = wbeg; base < wend; base += SAMP_NT) {
+        const uint64_t w = base + threadIdx.x;
+        uint64_t word = w < wend ? bitmap[w] : 0ull;
+        uint32_t total;
+        uint32_t ex = block_excl_scan<uint32_t, SAMP_NT>(__popcll(word), &total, lds) + running;
+        if (w < wend) rank[w] = ex;
+        while (word) {
+            const int b = __ffsll((unsigned long long)word) - 1;
+            if (ex < B) S[ex] = (int32_t)(w * 64 + b);
+            ++ex;
+            word &= word - 1;
+        }
+        running += total;
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0 && running != B) atomicOr(status, SGNN_ST_CAND_OVERFLOW);
+}
+
+} // namespace
+
+// scratch layout of the sampler inside the context's persistent area
+size_t sgnn_sampler_persist_bytes() { return HIST_BINS * sizeof(uint32_t) + 256; }
+
+static uint32_t cand_capacity(uint64_t N) { return (uint32_t)(2 * (N >> HIST_BITS) + 8192); }
+
+size_t sgnn_sampler_ws_bytes(uint64_t N)
+{
+    const size_t cap = cand_capacity(N);
+    return cap * 12 + EMIT_MAX_WG * 4 + 4 * 256;
+}
+
+int sgnn_launch_sampler(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, uint64_t step, int32_t *S,
+                        uint64_t *bitmap, uint32_t *rank, hipStream_t st)
+{
+    uint32_t *hist = reinterpret_cast<uint32_t *>(ctx->persist);
+    sampler_state *state = reinterpret_cast<sampler_state *>(ctx->persist + HIST_BINS * sizeof(uint32_t));
+    ws_alloc ws(ctx);
+    const uint32_t cap = cand_capacity(N);
+    uint64_t *cand_key = ws.get<uint64_t>(cap);
+    uint32_t *cand_v = ws.get<uint32_t>(cap);
+    uint32_t *wg_count = ws.get<uint32_t>(EMIT_MAX_WG);
+    if (!ws.ok)
+        return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_sample_uniform: scratch too small (%zu bytes needed): call sgnn_ctx_reserve",
+                         ws.off);
+
+    const uint64_t J = (N + 1) >> 1;
+    const unsigned grid = (unsigned)std::min<uint64_t>(cdiv(J, SAMP_NT), 2048);
+    hipLaunchKernelGGL(sampler_hist_kernel, dim3(grid), dim3(SAMP_NT), 0, st, N, seed, step, hist);
+    SGNN_LAUNCH_CHECK(ctx, "sampler_hist_kernel");
+    hipLaunchKernelGGL(sampler_pick_bin_kernel, dim3(1), dim3(1024), 0, st, B, hist, state);
+    SGNN_LAUNCH_CHECK(ctx, "sampler_pick_bin_kernel");
+    hipLaunchKernelGGL(sampler_collect_kernel, dim3(grid), dim3(SAMP_NT), 0, st, N, seed, step, state, cand_key, cand_v,
+                       cap, ctx->status);
+    SGNN_LAUNCH_CHECK(ctx, "sampler_collect_kernel");
+    hipLaunchKernelGGL(sampler_threshold_kernel, dim3(1), dim3(1024), 0, st, state, cand_key, cand_v, cap);
+    SGNN_LAUNCH_CHECK(ctx, "sampler_threshold_kernel");
+
+    const uint64_t W = (N + 63) / 64;
+    const unsigned egrid = (unsigned)std::min<uint64_t>(cdiv(W, 8), EMIT_MAX_WG);
+    const uint64_t wpw = (uint64_t)cdiv(cdiv(W, egrid), 8) * 8;
+    hipLaunchKernelGGL(sampler_emit_kernel, dim3(egrid), dim3(SAMP_NT), 0, st, N, seed, step, state, bitmap, W, wpw,
+                       wg_count);
+    SGNN_LAUNCH_CHECK(ctx, "sampler_emit_kernel");
+    hipLaunchKernelGGL(sampler_rank_kernel, dim3(egrid), dim3(SAMP_NT), 0, st, bitmap, W, wpw, wg_count, B, rank, S,
+                       ctx->status);
+    SGNN_LAUNCH_CHECK(ctx, "sampler_rank_kernel");
+    return SGNN_OK;
+}

@@ -1,0 +1,265 @@
+"""GPU parity: SpMM, MFMA GEMM, layer forward / backward and the whole step against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_02651_amd as sg
+import synth_inputs as si
+from gpu_util import DEV, TOL_BF16, TOL_F32, ctx, dev, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape).astype(np.float32)
+
+
+def _sub_csr(N=3000, edges=40000, B=1500, seed=5):
+    g = si.rmat_graph(N, edges, seed=seed)
+    S = oracle.sample_uniform(N, B, 0, 0)
+    rp, ci, v = oracle.induced_csr(N, g.rowptr.numpy(), g.colidx.numpy(), S)
+    return B, rp, ci, v
+
+
+@pytest.fixture(scope="module")
+def sub():
+    return _sub_csr()
+
+
+@pytest.mark.parametrize("d", [1, 3, 8, 32, 41, 47, 64, 100, 128, 172, 256, 602, 1024])
+def test_spmm_widths(sub, d):
+    B, rp, ci, v = sub
+    ctx().reserve(B, len(ci), B, d)
+    A = sg.Csr.from_arrays(B, B, rp, ci, v, DEV)
+    X = _rand((B, d), d)
+    out = torch.full((B, d), 7.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_spmm(ctx(), A, dev(X), out)
+    ref = oracle.spmm(rp, ci, v, X.astype(np.float64))
+    assert rel_err(out.cpu().numpy(), ref) < TOL_F32
+
+
+def test_spmm_row_index_and_padding(sub):
+    B, rp, ci, v = sub
+    A = sg.Csr.from_arrays(B, B, rp, ci, v, DEV)
+    big = _rand((5000, 130), 1)           # leading dimension 130, logical width 128
+    idx = np.random.default_rng(2).permutation(5000)[:B].astype(np.int32)
+    Xd = dev(big)[:, :128]
+    out_full = torch.zeros((B, 132), dtype=torch.float32, device=DEV)
+    out = out_full[:, :128]
+    sg.sgnn_spmm(ctx(), A, Xd, out, row_index=dev(idx))
+    ref = oracle.spmm(rp, ci, v, big[idx][:, :128].astype(np.float64))
+    assert rel_err(out.cpu().numpy(), ref) < TOL_F32
+    assert torch.all(out_full[:, 128:] == 0)
+
+
+def test_spmm_rectangular_empty_rows_and_long_row():
+    rows, cols, d = 70, 5000, 64
+    rng = np.random.default_rng(0)
+    lists = [np.zeros(0, np.int32) for _ in range(rows)]
+    lists[3] = np.sort(rng.permutation(cols)[:4500]).astype(np.int32)      # one very long row
+    for i in range(10, 70, 3):
+        lists[i] = np.sort(rng.permutation(cols)[:rng.integers(1, 9)]).astype(np.int32)
+    rp = np.concatenate([[0], np.cumsum([len(x) for x in lists])]).astype(np.int32)
+    ci = np.concatenate(lists); v = rng.standard_normal(len(ci)).astype(np.float32)
+    A = sg.Csr.from_arrays(rows, cols, rp, ci, v, DEV)
+    X = _rand((cols, d), 3)
+    out = torch.full((rows, d), 7.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_spmm(ctx(), A, dev(X), out)
+    assert rel_err(out.cpu().numpy(), oracle.spmm(rp, ci, v, X.astype(np.float64))) < TOL_F32
+
+
+GEMM_SHAPES = [(1, 1, 1), (5, 7, 3), (33, 65, 17), (128, 128, 16), (130, 129, 100), (257, 32, 256), (300, 8, 64),
+               (1000, 47, 256), (513, 256, 602), (2048, 172, 128), (64, 41, 33)]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_nn_with_epilogue(M, N, K, bf16):
+    A = _rand((M, K), 1); Bm = _rand((K, N), 2); bias = _rand(N, 3)
+    C = torch.full((M, N), 9.0, dtype=torch.float32, device=DEV)
+    flags = sg.SGNN_RELU | (sg.SGNN_BF16_MFMA if bf16 else 0)
+    sg.sgnn_gemm(ctx(), False, False, dev(A), dev(Bm), dev(bias), flags, C)
+    A64, B64 = A.astype(np.float64), Bm.astype(np.float64)
+    if bf16:
+        A64, B64 = oracle.round_bf16(A), oracle.round_bf16(Bm)
+    ref = np.maximum(oracle.gemm(A64, B64) + bias, 0)
+    # with identically rounded operands only the fp32 accumulation differs
+    assert rel_err(C.cpu().numpy(), ref) < (TOL_F32 if not bf16 else 1e-4)
+    if bf16:
+        full = np.maximum(A.astype(np.float64) @ Bm.astype(np.float64) + bias, 0)
+        assert rel_err(C.cpu().numpy(), full) < TOL_BF16
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_nt_and_tn(M, N, K, bf16):
+    flags = sg.SGNN_BF16_MFMA if bf16 else 0
+    rd = oracle.round_bf16 if bf16 else (lambda x: x.astype(np.float64))
+    tol = 1e-4 if bf16 else TOL_F32
+    A = _rand((M, K), 4); Bt = _rand((N, K), 5)
+    C = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), False, True, dev(A), dev(Bt), None, flags, C)
+    assert rel_err(C.cpu().numpy(), rd(A) @ rd(Bt).T) < tol
+    At = _rand((K, M), 6); Bm = _rand((K, N), 7)
+    C2 = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), True, False, dev(At), dev(Bm), None, flags, C2)
+    assert rel_err(C2.cpu().numpy(), rd(At).T @ rd(Bm)) < tol
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_gemm_long_reduction_is_split_and_reproducible(bf16):
+    # the weight-gradient shape: short result, reduction over tens of thousands of rows
+    K, M, N = 40000, 100, 256
+    ctx().reserve(1, 1, 40000, 256)
+    At = _rand((K, M), 8); Bm = _rand((K, N), 9)
+    flags = sg.SGNN_BF16_MFMA if bf16 else 0
+    rd = oracle.round_bf16 if bf16 else (lambda x: x.astype(np.float64))
+    C = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), True, False, dev(At), dev(Bm), None, flags, C)
+    assert rel_err(C.cpu().numpy(), rd(At).T @ rd(Bm)) < (1e-4 if bf16 else TOL_F32)
+    C2 = torch.zeros_like(C)
+    sg.sgnn_gemm(ctx(), True, False, dev(At), dev(Bm), None, flags, C2)
+    assert torch.equal(C, C2)
+
+
+def test_gemm_bf16_rounding_is_nearest_even():
+    # K = 1 against a one: the product is the rounded operand itself
+    x = np.concatenate([_rand(4000, 10), np.array([1.00390625, 1.01171875, -1.00390625, 0.0, 3.0e38], np.float32)])
+    A = x.reshape(-1, 1); one = np.ones((1, 1), np.float32)
+    C = torch.zeros((len(x), 1), dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), False, False, dev(A), dev(one), None, sg.SGNN_BF16_MFMA, C)
+    assert np.array_equal(C.cpu().numpy().astype(np.float64).ravel(), oracle.round_bf16(x))
+
+
+def test_gemm_strided_operands():
+    A = _rand((200, 70), 1); Bm = _rand((64, 50), 2)
+    Ad = dev(A)[:, :64]; Bd = dev(Bm)[:, :48]
+    Cfull = torch.zeros((200, 52), dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), False, False, Ad, Bd, None, 0, Cfull[:, :48])
+    assert rel_err(Cfull[:, :48].cpu().numpy(), A[:, :64].astype(np.float64) @ Bm[:, :48]) < TOL_F32
+    assert torch.all(Cfull[:, 48:] == 0)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("d_in,d_out,relu", [(32, 64, True), (64, 8, False), (100, 256, True), (256, 47, False)])
+def test_layer_forward_backward(sub, d_in, d_out, relu, bf16):
+    B, rp, ci, v = sub
+    ctx().reserve(B, len(ci), B, max(d_in, d_out))
+    A = sg.Csr.from_arrays(B, B, rp, ci, v, DEV)
+    H = _rand((B, d_in), 1); W = (_rand((d_in, d_out), 2) / np.sqrt(d_in)).astype(np.float32); b = _rand(d_out, 3) * 0.1
+    dY = _rand((B, d_out), 4)
+    flags = (sg.SGNN_RELU if relu else 0) | (sg.SGNN_BF16_MFMA if bf16 else 0)
+    tol = TOL_BF16 if bf16 else TOL_F32
+    Y = torch.zeros((B, d_out), dtype=torch.float32, device=DEV); T = torch.zeros((B, d_in), dtype=torch.float32, device=DEV)
+    sg.sgnn_gcn_fwd(ctx(), A, dev(H), dev(W), dev(b), flags, Y, T)
+    T_ref, Y_ref = oracle.gcn_fwd(rp, ci, v, H, W, b, relu=relu, bf16=bf16)
+    assert rel_err(T.cpu().numpy(), T_ref) < TOL_F32
+    assert rel_err(Y.cpu().numpy(), Y_ref) < tol
+    # backward from the oracle's own forward state
+    rpT, ciT, vT = oracle.csr_transpose(B, B, rp, ci, v)
+    dH_ref, dW_ref, db_ref = oracle.gcn_bwd(rpT, ciT, vT, T_ref, W, Y_ref, dY, relu=relu, bf16=bf16)
+    AT = sg.Csr.from_arrays(B, B, rpT, ciT, vT, DEV)
+    dH = torch.zeros((B, d_in), dtype=torch.float32, device=DEV)
+    dW = torch.zeros((d_in, d_out), dtype=torch.float32, device=DEV); db = torch.zeros(d_out, dtype=torch.float32, device=DEV)
+    sg.sgnn_gcn_bwd(ctx(), AT, dev(T_ref, torch.float32), dev(W), dev(Y_ref, torch.float32), dev(dY), flags, dH, dW, db)
+    assert rel_err(dH.cpu().numpy(), dH_ref) < tol
+    assert rel_err(dW.cpu().numpy(), dW_ref) < tol
+    assert rel_err(db.cpu().numpy(), db_ref) < TOL_F32
+    # first layer: dH skipped, nothing else changes
+    dW2 = torch.zeros_like(dW)
+    sg.sgnn_gcn_bwd(ctx(), AT, dev(T_ref, torch.float32), dev(W), dev(Y_ref, torch.float32), dev(dY), flags, None, dW2, None)
+    assert torch.equal(dW, dW2)
+
+
+def test_backward_uses_the_transpose():
+    rp = np.array([0, 2, 3, 6], np.int32); ci = np.array([0, 2, 0, 0, 1, 2], np.int32)
+    v = np.array([0.5, -1.0, 2.0, 0.25, 3.0, 1.5], np.float32)
+    H = _rand((3, 4), 1); W = _rand((4, 2), 2); R = _rand((3, 2), 3)
+    ctx().reserve(3, 6, 3, 4)
+    T_ref, Y_ref = oracle.gcn_fwd(rp, ci, v, H, W, None, relu=False)
+    rpT, ciT, vT = oracle.csr_transpose(3, 3, rp, ci, v)
+    dH_ref, dW_ref, _ = oracle.gcn_bwd(rpT, ciT, vT, T_ref, W, Y_ref, R, relu=False)
+    AT = sg.Csr.from_arrays(3, 3, rpT, ciT, vT, DEV)
+    dH = torch.zeros((3, 4), dtype=torch.float32, device=DEV); dW = torch.zeros((4, 2), dtype=torch.float32, device=DEV)
+    sg.sgnn_gcn_bwd(ctx(), AT, dev(T_ref, torch.float32), dev(W), None, dev(R), 0, dH, dW, None)
+    assert rel_err(dH.cpu().numpy(), dH_ref) < TOL_F32 and rel_err(dW.cpu().numpy(), dW_ref) < TOL_F32
+
+
+def test_softmax_xent_and_gather():
+    B, C = 1000, 47
+    O = _rand((B, C), 1) * 3; y = np.random.default_rng(2).integers(0, C, B).astype(np.int32)
+    ctx().reserve(B, 1, B, C)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV); dO = torch.zeros((B, C), dtype=torch.float32, device=DEV)
+    sg.sgnn_softmax_xent(ctx(), dev(O), dev(y), loss, dO)
+    l_ref, dO_ref = oracle.softmax_xent(O, y)
+    assert abs(loss.item() - l_ref) < TOL_F32 * abs(l_ref) and rel_err(dO.cpu().numpy(), dO_ref) < TOL_F32
+    X = _rand((5000, 100), 3); S = np.sort(np.random.default_rng(4).permutation(5000)[:B]).astype(np.int32)
+    labels = np.random.default_rng(5).integers(0, C, 5000).astype(np.int32)
+    out = torch.zeros((B, 100), dtype=torch.float32, device=DEV); lo = torch.zeros(B, dtype=torch.int32, device=DEV)
+    sg.sgnn_gather_rows(ctx(), dev(X), dev(S), B, out, dev(labels), lo)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.gather_rows(X, S))
+    assert np.array_equal(lo.cpu().numpy(), oracle.gather_labels(labels, S))
+    lo2 = torch.zeros(B, dtype=torch.int32, device=DEV)
+    sg.sgnn_gather_rows(ctx(), None, dev(S), B, None, dev(labels), lo2)
+    assert torch.equal(lo, lo2)
+
+
+def _run_config(name, steps, fuse_slice, bf16=None):
+    cfg = si.CONFIGS[name]
+    bf16 = cfg.bf16_mfma if bf16 is None else bf16
+    g = si.rmat_graph(cfg.N, cfg.undirected_edges, cfg.graph_seed)
+    X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed)
+    labels = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed)
+    weights = si.layer_weights(cfg)
+    st = sg.GcnStep(cfg.N, g.rowptr.to(DEV), g.colidx.to(DEV), X.to(DEV), labels.to(DEV),
+                    [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B, cfg.sampler_seed, bf16=bf16,
+                    fuse_slice=fuse_slice, device=DEV)
+    wnp = [(W.double().numpy(), b.double().numpy()) for W, b in weights]
+    tol = TOL_BF16 if bf16 else TOL_F32
+    band = 1e-3 if bf16 else 1e-5
+    for t in steps:
+        st.step(t)
+        torch.cuda.synchronize()
+        st.ctx.status()
+        args = (cfg.N, g.rowptr.numpy(), g.colidx.numpy(), X.numpy(), labels.numpy(), wnp, cfg.B, cfg.sampler_seed, t)
+        ref = oracle.gcn_step(*args, bf16=bf16, tie_band=band)
+        nnz = st.A.nnz()
+        assert np.array_equal(st.S.cpu().numpy(), ref["S"])
+        assert np.array_equal(st.A.rowptr.cpu().numpy(), ref["rowptr"]) and nnz == len(ref["colidx"])
+        assert np.array_equal(st.A.colidx.cpu().numpy()[:nnz], ref["colidx"])
+        assert np.array_equal(st.y_S.cpu().numpy(), ref["y_S"])
+        if not fuse_slice:
+            assert np.array_equal(st.X_S.cpu().numpy().astype(np.float64), ref["X_S"])
+        ties = []
+        for l in range(cfg.layers):
+            assert rel_err(st.T[l].cpu().numpy(), ref["T"][l]) < tol, ("T", l)
+            assert rel_err(st.H[l].cpu().numpy(), ref["H"][l + 1]) < tol, ("H", l)
+            # the ReLU decision must agree wherever the pre-activation is decidably non-zero
+            got_mask = st.H[l].cpu().numpy() > 0
+            if l < cfg.layers - 1:
+                assert np.array_equal(got_mask[~ref["relu_band"][l]], ref["relu_mask"][l][~ref["relu_band"][l]])
+            ties.append(got_mask)
+        assert abs(st.loss.item() - ref["loss"]) < tol * abs(ref["loss"])
+        # inside the undecidable band either mask is correct: the gradients are checked against the
+        # oracle evaluated with the decisions the kernels took there
+        if any((ties[l] != ref["relu_mask"][l]).any() for l in range(cfg.layers - 1)):
+            ref = oracle.gcn_step(*args, bf16=bf16, tie_band=band, relu_ties=ties)
+        for l in range(cfg.layers):
+            assert rel_err(st.dW[l].cpu().numpy(), ref["dW"][l]) < tol, ("dW", l)
+            assert rel_err(st.db[l].cpu().numpy(), ref["db"][l]) < tol, ("db", l)
+            if l > 0:
+                assert rel_err(st.dH[l].cpu().numpy(), ref["dH"][l]) < tol, ("dH", l)
+
+
+@pytest.mark.parametrize("fuse_slice", [False, True])
+def test_whole_step_tiny(fuse_slice):
+    _run_config("tiny", [0, 1], fuse_slice)
+
+
+def test_whole_step_tiny_bf16():
+    _run_config("tiny", [0], True, bf16=True)
+
+
+def test_whole_step_medium():
+    _run_config("medium", [0, 15], True)

@@ -1,0 +1,163 @@
+"""GPU parity: sampler and induced CSR against the CPU oracle, bit-exact on indices."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_02651_amd as sg
+import synth_inputs as si
+from gpu_util import DEV, TOL_VAL, bitmap_rank_from_sample, ctx, dev, gpu_sample
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("N,B,seed,step", [
+    (1, 1, 0, 0), (2, 1, 0, 0), (63, 17, 1, 2), (64, 64, 0, 0), (65, 64, 3, 1), (129, 1, 0, 5),
+    (4096, 1024, 0, 0), (4096, 1024, 0, 1), (5000, 4999, 9, 9), (100003, 777, 2**40 + 3, 2**35 + 1),
+    (262144, 32768, 0, 0), (262144, 32768, 0, 15), (1000003, 1000003, 4, 4), (1000003, 250000, 5, 6),
+])
+def test_sampler_matches_oracle(N, B, seed, step):
+    S, bitmap, rank = gpu_sample(N, B, seed, step)
+    S_ref = oracle.sample_uniform(N, B, seed, step)
+    assert np.array_equal(S.cpu().numpy(), S_ref)
+    words, rk = bitmap_rank_from_sample(N, S_ref)
+    assert np.array_equal(bitmap.cpu().numpy(), words)
+    assert np.array_equal(rank.cpu().numpy(), rk)
+
+
+def test_sampler_is_deterministic_and_stateless():
+    a = gpu_sample(300000, 30000, 7, 11)[0].cpu().numpy()
+    gpu_sample(4096, 10, 1, 1)
+    b = gpu_sample(300000, 30000, 7, 11)[0].cpu().numpy()
+    assert np.array_equal(a, b)
+
+
+def test_sampler_large_n():
+    # the vertex count of the largest configuration; B as in that configuration
+    N, B = 111059956, 1048576
+    S, bitmap, rank = gpu_sample(N, B, 0, 0)
+    S_ref = oracle.sample_uniform(N, B, 0, 0)
+    assert np.array_equal(S.cpu().numpy(), S_ref)
+    words, rk = bitmap_rank_from_sample(N, S_ref)
+    assert np.array_equal(bitmap.cpu().numpy(), words) and np.array_equal(rank.cpu().numpy(), rk)
+
+
+def test_sampler_rejects_bad_arguments():
+    S = torch.zeros(8, dtype=torch.int32, device=DEV)
+    bm = torch.zeros(1, dtype=torch.int64, device=DEV)
+    rk = torch.zeros(1, dtype=torch.int32, device=DEV)
+    for N, B in [(10, 0), (10, 11)]:
+        with pytest.raises(sg.SgnnError) as e:
+            sg.lib()  # make sure the library is the one in use
+            ctx().check(sg.lib().sgnn_sample_uniform(ctx()._h, N, B, 0, 0, S.data_ptr(), bm.data_ptr(), rk.data_ptr(), None))
+        assert e.value.code == -1
+    with pytest.raises(sg.SgnnError):
+        ctx().check(sg.lib().sgnn_sample_uniform(ctx()._h, 10, 5, 0, 0, None, bm.data_ptr(), rk.data_ptr(), None))
+    with pytest.raises(sg.SgnnError):
+        ctx().check(sg.lib().sgnn_sample_uniform(ctx()._h, 2**31, 5, 0, 0, S.data_ptr(), bm.data_ptr(), rk.data_ptr(), None))
+
+
+def _induce_gpu(g, B, seed, step, norm_mode=0, rescale=1, val=None, rowptr_dtype=torch.int64, capacity=None):
+    N = g.N
+    rowptr = g.rowptr.to(rowptr_dtype).to(DEV)
+    colidx = g.colidx.to(DEV)
+    ctx().reserve(N, g.E, B, 1)
+    S, bitmap, rank = gpu_sample(N, B, seed, step)
+    S_ref = oracle.sample_uniform(N, B, seed, step)
+    ref = oracle.induced_csr(N, g.rowptr.numpy(), g.colidx.numpy(), S_ref, val, norm_mode, rescale)
+    cap = len(ref[1]) if capacity is None else capacity
+    out = sg.Csr(B, B, cap, DEV)
+    out.rowptr.fill_(-7); out.colidx.fill_(-7)
+    vt = None if val is None else dev(val)
+    nnz = sg.sgnn_induced_csr(ctx(), N, rowptr, colidx, vt, S, B, bitmap, rank, out, norm_mode, rescale, want_nnz=True)
+    ctx().status()
+    return out, nnz, ref
+
+
+def _assert_csr_equal(out, nnz, ref):
+    rp, ci, v = ref
+    assert nnz == len(ci) == out.nnz()
+    assert np.array_equal(out.rowptr.cpu().numpy(), rp)
+    assert np.array_equal(out.colidx.cpu().numpy()[:nnz], ci)
+    got = out.val.cpu().numpy()[:nnz].astype(np.float64)
+    assert np.all(np.abs(got - v) <= TOL_VAL * np.abs(v))
+
+
+@pytest.mark.parametrize("norm_mode", [0, 1])
+@pytest.mark.parametrize("rescale", [0, 1])
+@pytest.mark.parametrize("B", [1, 2, 100, 1024, 4096])
+def test_induced_tiny(tiny_graph, B, rescale, norm_mode):
+    out, nnz, ref = _induce_gpu(tiny_graph, B, 0, B, norm_mode, rescale)
+    _assert_csr_equal(out, nnz, ref)
+
+
+def test_induced_all_vertices_is_identity(tiny_graph):
+    g = tiny_graph
+    out, nnz, ref = _induce_gpu(g, g.N, 0, 0)
+    assert np.array_equal(out.rowptr.cpu().numpy(), g.rowptr.numpy())
+    assert np.array_equal(out.colidx.cpu().numpy()[:nnz], g.colidx.numpy())
+    _assert_csr_equal(out, nnz, ref)
+
+
+def test_induced_int32_rowptr_and_given_weights(tiny_graph):
+    g = tiny_graph
+    rng = np.random.default_rng(3)
+    val = rng.random(g.E).astype(np.float32) + 0.5
+    out, nnz, ref = _induce_gpu(g, 700, 1, 2, 0, 1, val=val, rowptr_dtype=torch.int32)
+    _assert_csr_equal(out, nnz, ref)
+
+
+@pytest.fixture(scope="module")
+def medium_graph():
+    cfg = si.CONFIGS["medium"]
+    return si.rmat_graph(cfg.N, cfg.undirected_edges, cfg.graph_seed)
+
+
+@pytest.mark.parametrize("step", [0, 7, 15])
+def test_induced_medium(medium_graph, step):
+    cfg = si.CONFIGS["medium"]
+    out, nnz, ref = _induce_gpu(medium_graph, cfg.B, cfg.sampler_seed, step)
+    _assert_csr_equal(out, nnz, ref)
+
+
+def test_induced_medium_ragged_sizes(medium_graph):
+    # B not a multiple of anything, hub rows split across many tiles
+    out, nnz, ref = _induce_gpu(medium_graph, 100001, 3, 1)
+    _assert_csr_equal(out, nnz, ref)
+    out, nnz, ref = _induce_gpu(medium_graph, 2049, 3, 2, norm_mode=1)
+    _assert_csr_equal(out, nnz, ref)
+
+
+def test_induced_graph_with_empty_rows():
+    # rows without any stored entry (not canonical, but the extraction must still be exact)
+    N = 300
+    rng = np.random.default_rng(1)
+    rows = []
+    for v in range(N):
+        if v % 3 == 0 or v > 280:
+            rows.append(np.zeros(0, np.int32))
+        else:
+            rows.append(np.unique(rng.integers(0, N, rng.integers(1, 40))).astype(np.int32))
+    rowptr = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int64)
+    colidx = np.concatenate(rows).astype(np.int32)
+    g = si.Graph(N, torch.as_tensor(rowptr), torch.as_tensor(colidx))
+    val = np.ones(len(colidx), np.float32)
+    for B in (50, 299, 300):
+        out, nnz, ref = _induce_gpu(g, B, 5, B, 0, 1, val=val)
+        _assert_csr_equal(out, nnz, ref)
+
+
+def test_induced_capacity_overflow_is_reported(tiny_graph):
+    g = tiny_graph
+    with pytest.raises(sg.SgnnError) as e:
+        _induce_gpu(g, 1024, 0, 0, capacity=100)
+    assert e.value.code == -2
+    # the row pointer is still complete and the first `capacity` entries are right
+    N, B = g.N, 1024
+    S, bitmap, rank = gpu_sample(N, B, 0, 0)
+    out = sg.Csr(B, B, 100, DEV)
+    sg.sgnn_induced_csr(ctx(), N, g.rowptr.to(DEV), g.colidx.to(DEV), None, S, B, bitmap, rank, out)
+    ref = oracle.induced_csr(N, g.rowptr.numpy(), g.colidx.numpy(), oracle.sample_uniform(N, B, 0, 0))
+    assert np.array_equal(out.rowptr.cpu().numpy(), ref[0])
+    assert out.nnz() == len(ref[1])
+    assert np.array_equal(out.colidx.cpu().numpy()[:100], ref[1][:100])
