@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the mini-batch GCN hot path on one MI355X.
+
+One "step" is one pass of the whole path over one mini-batch: uniform vertex sample -> induced
+normalised CSR -> slice -> L GCN layers forward -> cross-entropy -> L layers backward, every
+stage in libsgnn's HIP kernels, inputs resident in HBM before the clock starts.
+
+Prints ONE JSON line: throughput in steps/s, the roofline figure of the kernel that takes the
+most time (measured with HIP events recorded on the launch stream, in a second pass over the
+same steps so that event overhead does not touch the throughput figure), and the CPU oracle
+timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "sampled GCN mini-batch steps/sec (fwd+bwd)"
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=160)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--config", default="medium", help="tiny | medium | large | dense (medium is the headline workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fuse-slice", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = pick by config)")
+    ap.add_argument("--breakdown", action="store_true", help="also print the per-kernel table to stderr")
+    return ap.parse_args()
+
+
+def gemm_flops(tag: str) -> float:
+    # tag: "NN 128x128 32768x256x256 f32"
+    dims = tag.split()[2].split("x")
+    return 2.0 * float(dims[0]) * float(dims[1]) * float(dims[2])
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is the single-GPU hot path; --gpus N with N > 1 is not supported "
+              "(no collectives are part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2604_02651_amd as sg
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    cfg = si.CONFIGS[args.config]
+    g = si.rmat_graph(cfg.N, cfg.undirected_edges, cfg.graph_seed, device=dev)
+    X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=dev)
+    labels = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=dev)
+    weights = si.layer_weights(cfg, device=dev)
+    st = sg.GcnStep(cfg.N, g.rowptr, g.colidx, X, labels, weights, cfg.B, cfg.sampler_seed, bf16=cfg.bf16_mfma,
+                    fuse_slice=not args.no_fuse_slice, device=dev)
+    period = max(cfg.steps, 1)   # the configuration's mini-batches: consecutive sampler counters
+
+    for i in range(args.warmup):
+        st.step(i % period)
+    torch.cuda.synchronize()
+    st.ctx.status()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        st.step(i % period)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    st.ctx.status()
+    steps_per_s = args.steps / elapsed
+
+    # ---- per-kernel pass: the same steps with every launch bracketed by events on its stream ----
+    nprof = min(args.steps, period)
+    st.ctx.profile(True)
+    nnz_total = 0
+    for i in range(nprof):
+        st.step(i % period)
+    recs = st.ctx.profile_read()
+    st.ctx.profile(False)
+    for i in range(nprof):     # entry counts of those steps, for the byte figures of the sparse kernels
+        st.sample(i % period); st.induce()
+        nnz_total += st.A.nnz()
+    nnz_avg = nnz_total / nprof
+    groups = {}
+    for name, tag, calls, ms in recs:
+        key = name
+        if name == "gemm_kernel":
+            p = tag.split()
+            key = "gemm_kernel<%s,%s,%s>" % (p[1], p[0], p[3])
+        gq = groups.setdefault(key, {"calls": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
+        gq["calls"] += calls
+        gq["ms"] += ms
+        if name == "gemm_kernel":
+            gq["flops"] += gemm_flops(tag) * calls
+        elif name == "spmm_rowsplit_kernel":
+            d = int(tag.split("d=")[1])
+            # compulsory traffic: CSR once, every input row once, the output once
+            gq["bytes"] += calls * (8.0 * nnz_avg + 4.0 * (cfg.B + 1) + 2.0 * cfg.B * d * 4)
+    total_ms = sum(v["ms"] for v in groups.values())
+    dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
+    if args.breakdown:
+        for k, v in sorted(groups.items(), key=lambda kv: -kv[1]["ms"]):
+            print("%-44s calls/step %5.1f  us/step %9.2f  avg us %8.2f" %
+                  (k, v["calls"] / nprof, 1e3 * v["ms"] / nprof, 1e3 * v["ms"] / v["calls"]), file=sys.stderr)
+        print("sum of kernel time per step: %.1f us; wall per step: %.1f us" % (1e3 * total_ms / nprof, 1e6 / steps_per_s),
+              file=sys.stderr)
+    if dom["flops"] > 0:
+        dt = "bf16" if dom_name.endswith("bf16>") else "f32"
+        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_TFLOPS[dt], "traffic": None}
+    else:
+        achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9 if dom["bytes"] > 0 else 0.0
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    roofline["kernel"] = dom_name
+    roofline["avg_launch_us"] = 1e3 * dom["ms"] / dom["calls"]
+    roofline["launches_per_step"] = dom["calls"] / nprof
+    roofline["share_of_kernel_time"] = dom["ms"] / total_ms if total_ms > 0 else None
+
+    out = {
+        "metric": METRIC, "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.bf16_mfma else "f32", "data": "synthetic",
+        "config": {"workload": "%s: R-MAT N=%d, E=%d stored entries, |S|=%d, GCN %s, %d mini-batches (sampler "
+                               "counters 0..%d)" % (cfg.name, cfg.N, g.E, cfg.B, "-".join(map(str, cfg.dims)), period,
+                                                     period - 1),
+                   "fuse_slice": not args.no_fuse_slice, "avg_induced_entries": nnz_avg,
+                   "kernel_time_us_per_step": 1e3 * total_ms / nprof},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        rp, ci = g.rowptr.cpu().numpy(), g.colidx.cpu().numpy()
+        Xh, lh = X.cpu().numpy(), labels.cpu().numpy()
+        wnp = [(W.double().cpu().numpy(), b.double().cpu().numpy()) for W, b in weights]
+        nsteps = args.cpu_steps or {"tiny": 50, "medium": 3}.get(cfg.name, 1)
+        oracle.gcn_step(cfg.N, rp, ci, Xh, lh, wnp, min(cfg.B, 1024), cfg.sampler_seed, 0, bf16=cfg.bf16_mfma)  # warm-up
+        c0 = time.perf_counter()
+        for t in range(nsteps):
+            oracle.gcn_step(cfg.N, rp, ci, Xh, lh, wnp, cfg.B, cfg.sampler_seed, t % period, bf16=cfg.bf16_mfma)
+        cpu_s = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": nsteps / cpu_s, "unit": "steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "%d whole steps (sampler counters 0..%d) of the same workload, %.1f s"
+                                         % (nsteps, nsteps - 1, cpu_s)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -74,6 +74,16 @@ const char *sgnn_last_error(const sgnn_ctx *ctx);
 int sgnn_ctx_status(sgnn_ctx *ctx, sgnn_stream stream);
 
 /*
+ * Per-kernel timing for benchmarks.  With enable != 0 every kernel launch made through this
+ * context is bracketed by two HIP events recorded on the launch's own stream (this costs a few
+ * microseconds per launch, so throughput is measured with profiling off); enabling also discards
+ * earlier records.  sgnn_ctx_profile_read synchronises the device and writes one line per
+ * (kernel, shape tag) into the host buffer: "name<TAB>tag<TAB>launches<TAB>total milliseconds".
+ */
+int sgnn_ctx_profile(sgnn_ctx *ctx, int enable);
+int sgnn_ctx_profile_read(sgnn_ctx *ctx, char *buf /* host */, uint64_t buf_len);
+
+/*
  * Eq. 20: uniform sample of B of the N vertices without replacement.
  * The sample is the B vertices with the smallest (key(v), v), key(v) = 64 bits of
  * Philox4x32-10 with key words (seed lo, seed hi) and counter (v/2 lo, v/2 hi, step lo, step hi);

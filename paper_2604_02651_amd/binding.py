@@ -66,6 +66,8 @@ def lib():
         L.sgnn_last_error.argtypes = [vp]
         L.sgnn_last_error.restype = C.c_char_p
         L.sgnn_ctx_status.argtypes = [vp, vp]
+        L.sgnn_ctx_profile.argtypes = [vp, ci]
+        L.sgnn_ctx_profile_read.argtypes = [vp, C.c_char_p, u64]
         L.sgnn_sample_uniform.argtypes = [vp, u64, u32, u64, u64, vp, vp, vp, vp]
         L.sgnn_induced_csr.argtypes = [vp, C.POINTER(_Graph), vp, u32, vp, vp, ci, ci, C.POINTER(_Csr),
                                        C.POINTER(u64), vp]
@@ -78,6 +80,7 @@ def lib():
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
+                     "sgnn_ctx_profile", "sgnn_ctx_profile_read",
                      "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd",
                      "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm"):
             getattr(L, name).restype = ci
@@ -133,6 +136,19 @@ class Context:
 
     def status(self, stream=None):
         self.check(lib().sgnn_ctx_status(self._h, _stream(stream)))
+
+    def profile(self, enable: bool):
+        self.check(lib().sgnn_ctx_profile(self._h, int(enable)))
+
+    def profile_read(self):
+        """[(kernel, tag, launches, total_ms)] recorded since profiling was enabled."""
+        buf = C.create_string_buffer(1 << 20)
+        self.check(lib().sgnn_ctx_profile_read(self._h, buf, len(buf)))
+        out = []
+        for line in buf.value.decode().splitlines():
+            name, tag, calls, ms = line.split("\t")
+            out.append((name, tag, int(calls), float(ms)))
+        return out
 
     def close(self):
         if self._h:

@@ -25,6 +25,34 @@ int sgnn_fail(sgnn_ctx *ctx, int code, const char *fmt, ...)
     return code;
 }
 
+void sgnn_prof_begin(sgnn_ctx *ctx, hipStream_t st, const char *name, const char *tag)
+{
+    if (ctx->prof_n == ctx->prof_cap) {
+        const size_t cap = ctx->prof_cap ? 2 * ctx->prof_cap : 1024;
+        sgnn_prof_rec *p = static_cast<sgnn_prof_rec *>(realloc(ctx->prof, cap * sizeof(sgnn_prof_rec)));
+        if (!p) { ctx->prof_on = 0; return; }
+        for (size_t i = ctx->prof_cap; i < cap; ++i) {
+            if (hipEventCreate(&p[i].e0) != hipSuccess || hipEventCreate(&p[i].e1) != hipSuccess) {
+                ctx->prof = p; ctx->prof_cap = i; ctx->prof_on = 0;
+                return;
+            }
+        }
+        ctx->prof = p;
+        ctx->prof_cap = cap;
+    }
+    sgnn_prof_rec &r = ctx->prof[ctx->prof_n];
+    r.name = name;
+    snprintf(r.tag, sizeof(r.tag), "%s", tag ? tag : "");
+    hipEventRecord(r.e0, st);
+}
+
+void sgnn_prof_end(sgnn_ctx *ctx, hipStream_t st)
+{
+    if (!ctx->prof_on || ctx->prof_n >= ctx->prof_cap) return;
+    hipEventRecord(ctx->prof[ctx->prof_n].e1, st);
+    ++ctx->prof_n;
+}
+
 namespace {
 
 constexpr size_t PERSIST_BYTES = 16384;
@@ -74,6 +102,11 @@ int sgnn_ctx_destroy(sgnn_ctx *ctx)
     hipDeviceSynchronize();
     if (ctx->ws) hipFree(ctx->ws);
     if (ctx->persist) hipFree(ctx->persist);
+    for (size_t i = 0; i < ctx->prof_cap; ++i) {
+        hipEventDestroy(ctx->prof[i].e0);
+        hipEventDestroy(ctx->prof[i].e1);
+    }
+    free(ctx->prof);
     delete ctx;
     return SGNN_OK;
 }
@@ -120,6 +153,47 @@ int sgnn_ctx_status(sgnn_ctx *ctx, sgnn_stream stream)
                          (word & SGNN_ST_CAND_OVERFLOW) ? " sampler selection inconsistent" : "",
                          (word & SGNN_ST_NNZ_OVERFLOW) ? " induced entry count exceeds int32" : "");
     }
+    return SGNN_OK;
+}
+
+int sgnn_ctx_profile(sgnn_ctx *ctx, int enable)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    ctx->prof_on = enable ? 1 : 0;
+    if (enable) ctx->prof_n = 0;
+    return SGNN_OK;
+}
+
+int sgnn_ctx_profile_read(sgnn_ctx *ctx, char *buf, uint64_t buf_len)
+{
+    if (!ctx || !buf || buf_len == 0) return SGNN_ERR_INVALID_ARG;
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    SGNN_HIP(ctx, hipDeviceSynchronize());
+    // aggregate by (name, tag) in order of first appearance
+    struct agg { const char *name; const char *tag; uint64_t calls; double ms; };
+    agg *a = static_cast<agg *>(calloc(ctx->prof_n ? ctx->prof_n : 1, sizeof(agg)));
+    if (!a) return sgnn_fail(ctx, SGNN_ERR_HIP, "sgnn_ctx_profile_read: out of host memory");
+    size_t na = 0;
+    for (size_t i = 0; i < ctx->prof_n; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ctx->prof[i].e0, ctx->prof[i].e1) != hipSuccess) ms = 0.f;
+        size_t j = 0;
+        for (; j < na; ++j)
+            if (a[j].name == ctx->prof[i].name && strcmp(a[j].tag, ctx->prof[i].tag) == 0) break;
+        if (j == na) { a[na].name = ctx->prof[i].name; a[na].tag = ctx->prof[i].tag; ++na; }
+        a[j].calls += 1;
+        a[j].ms += ms;
+    }
+    uint64_t off = 0;
+    buf[0] = 0;
+    for (size_t j = 0; j < na; ++j) {
+        int w = snprintf(buf + off, buf_len - off, "%s\t%s\t%llu\t%.6f\n", a[j].name, a[j].tag,
+                         (unsigned long long)a[j].calls, a[j].ms);
+        if (w < 0 || (uint64_t)w >= buf_len - off) { free(a); return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_ctx_profile_read: buffer too small"); }
+        off += (uint64_t)w;
+    }
+    free(a);
     return SGNN_OK;
 }
 

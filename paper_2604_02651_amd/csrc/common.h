@@ -9,8 +9,19 @@
 
 #define SGNN_WAVE 64
 
+// One timed kernel launch of the optional profiling mode (sgnn_ctx_profile).
+struct sgnn_prof_rec {
+    const char *name;   // kernel name (string literal)
+    char tag[56];       // shape of the launch, e.g. "NN 32768x256x256 f32"
+    hipEvent_t e0, e1;
+};
+
 struct sgnn_ctx {
     int device;
+    int prof_on;                 // bracket every launch with HIP events on its stream
+    sgnn_prof_rec *prof;         // event pool, grown on demand, reused
+    size_t prof_n, prof_cap;
+    const char *cur_tag;         // tag attached to the launches that follow
     char err[512];
     uint8_t *ws;        // device scratch, carved afresh by every call
     uint8_t *persist;   // small device area that keeps its contents between calls
@@ -38,6 +49,19 @@ int sgnn_fail(sgnn_ctx *ctx, int code, const char *fmt, ...);
         hipError_t e_ = hipGetLastError();                                                      \
         if (e_ != hipSuccess)                                                                   \
             return sgnn_fail((ctx), SGNN_ERR_HIP, "launch of %s failed: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+void sgnn_prof_begin(sgnn_ctx *ctx, hipStream_t st, const char *name, const char *tag);
+void sgnn_prof_end(sgnn_ctx *ctx, hipStream_t st);
+
+// Launch + error check; in profiling mode the launch is bracketed by two events on its stream.
+#define SGNN_TAG (ctx->cur_tag ? ctx->cur_tag : "")
+#define SGNN_LAUNCH(ctx, st, name, tag, ...)                                                    \
+    do {                                                                                        \
+        if ((ctx)->prof_on) sgnn_prof_begin((ctx), (st), name, tag);                            \
+        hipLaunchKernelGGL(__VA_ARGS__);                                                        \
+        if ((ctx)->prof_on) sgnn_prof_end((ctx), (st));                                         \
+        SGNN_LAUNCH_CHECK(ctx, name);                                                           \
     } while (0)
 
 // Bump allocator over the context scratch, reset at the start of every API call.

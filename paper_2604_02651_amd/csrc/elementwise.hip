@@ -125,16 +125,15 @@ int sgnn_launch_gather(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, co
 {
     const uintptr_t bits = reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(out);
     if (!X) {   // labels only
-        hipLaunchKernelGGL(gather_rows_kernel<1>, dim3(cdiv(B, 256)), dim3(256), 0, st, X, 1, 0, S, B, out, 0, labels,
+        SGNN_LAUNCH(ctx, st, "gather_rows_kernel", SGNN_TAG, gather_rows_kernel<1>, dim3(cdiv(B, 256)), dim3(256), 0, st, X, 1, 0, S, B, out, 0, labels,
                            labels_out);
     } else if (d % 4 == 0 && ldx % 4 == 0 && ldo % 4 == 0 && (bits & 15) == 0) {
-        hipLaunchKernelGGL(gather_rows_kernel<4>, dim3(cdiv((uint64_t)B * (d / 4), 256)), dim3(256), 0, st, X, d / 4, ldx,
+        SGNN_LAUNCH(ctx, st, "gather_rows_kernel", SGNN_TAG, gather_rows_kernel<4>, dim3(cdiv((uint64_t)B * (d / 4), 256)), dim3(256), 0, st, X, d / 4, ldx,
                            S, B, out, ldo, labels, labels_out);
     } else {
-        hipLaunchKernelGGL(gather_rows_kernel<1>, dim3(cdiv((uint64_t)B * d, 256)), dim3(256), 0, st, X, d, ldx, S, B, out,
+        SGNN_LAUNCH(ctx, st, "gather_rows_kernel", SGNN_TAG, gather_rows_kernel<1>, dim3(cdiv((uint64_t)B * d, 256)), dim3(256), 0, st, X, d, ldx, S, B, out,
                            ldo, labels, labels_out);
     }
-    SGNN_LAUNCH_CHECK(ctx, "gather_rows_kernel");
     return SGNN_OK;
 }
 
@@ -151,21 +150,19 @@ int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const 
         if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
     }
     if (cols <= 32)
-        hipLaunchKernelGGL(relu_bwd_colsum_kernel<32>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
+        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<32>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
                            rows_per_wg, dZ, lddz, partial);
     else if (cols <= 64)
-        hipLaunchKernelGGL(relu_bwd_colsum_kernel<64>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
+        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<64>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
                            rows_per_wg, dZ, lddz, partial);
     else if (cols <= 128)
-        hipLaunchKernelGGL(relu_bwd_colsum_kernel<128>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
+        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<128>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
                            rows_per_wg, dZ, lddz, partial);
     else
-        hipLaunchKernelGGL(relu_bwd_colsum_kernel<256>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
+        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<256>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
                            rows_per_wg, dZ, lddz, partial);
-    SGNN_LAUNCH_CHECK(ctx, "relu_bwd_colsum_kernel");
     if (dbias) {
-        hipLaunchKernelGGL(colsum_final_kernel, dim3(cdiv(cols, 256)), dim3(256), 0, st, partial, (int)nwg, (int)cols, dbias);
-        SGNN_LAUNCH_CHECK(ctx, "colsum_final_kernel");
+        SGNN_LAUNCH(ctx, st, "colsum_final_kernel", SGNN_TAG, colsum_final_kernel, dim3(cdiv(cols, 256)), dim3(256), 0, st, partial, (int)nwg, (int)cols, dbias);
     }
     return SGNN_OK;
 }
@@ -176,11 +173,9 @@ int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *
     const unsigned nwg = cdiv(B, 64);
     float *partial = ws->get<float>(nwg);
     if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_softmax_xent: scratch too small: call sgnn_ctx_reserve");
-    hipLaunchKernelGGL(xent_kernel, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, dO, lddo, partial);
-    SGNN_LAUNCH_CHECK(ctx, "xent_kernel");
+    SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, dO, lddo, partial);
     if (loss) {
-        hipLaunchKernelGGL(xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, 1.f / (float)B, loss);
-        SGNN_LAUNCH_CHECK(ctx, "xent_final_kernel");
+        SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, 1.f / (float)B, loss);
     }
     return SGNN_OK;
 }

@@ -267,10 +267,12 @@ template <int BM, int BN, int WM, int WN>
 int launch_cfg(sgnn_ctx *ctx, int ta, int tb, int bf16, const gemm_args &a, int splits, hipStream_t st)
 {
     dim3 grid(cdiv(a.M, BM), cdiv(a.N, BN), splits), block(256);
+    char tag[56];
+    snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld %s", ta ? 'T' : 'N', tb ? 'T' : 'N', BM, BN, (long long)a.M,
+             (long long)a.N, (long long)a.K, bf16 ? "bf16" : "f32");
 #define SGNN_GEMM_CASE(TA_, TB_, BF_)                                                                        \
     if (ta == TA_ && tb == TB_ && bf16 == BF_) {                                                             \
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, TA_, TB_, BF_>), grid, block, 0, st, a);             \
-        SGNN_LAUNCH_CHECK(ctx, "gemm_kernel");                                                               \
+        SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_kernel<BM, BN, WM, WN, TA_, TB_, BF_>), grid, block, 0, st, a); \
         return SGNN_OK;                                                                                      \
     }
     SGNN_GEMM_CASE(false, false, false)
@@ -327,9 +329,8 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     else rc = launch_cfg<256, 32, 64, 32>(ctx, ta, tb, bf16, a, splits, st);
     if (rc) return rc;
     if (splits > 1) {
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(cdiv(M * N, 256)), dim3(256), 0, st, a.partial, splits, M * N, N, C,
+        SGNN_LAUNCH(ctx, st, "splitk_reduce_kernel", SGNN_TAG, splitk_reduce_kernel, dim3(cdiv(M * N, 256)), dim3(256), 0, st, a.partial, splits, M * N, N, C,
                            ldc);
-        SGNN_LAUNCH_CHECK(ctx, "splitk_reduce_kernel");
     }
     return SGNN_OK;
 }

@@ -202,27 +202,23 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
         return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_induced_csr: scratch too small (%zu bytes needed): call sgnn_ctx_reserve",
                          ws.off);
 
-    hipLaunchKernelGGL(induced_deg_kernel<RP>, dim3(cdiv(B, 256)), dim3(256), 0, st, rowptr, S, B, deg);
-    SGNN_LAUNCH_CHECK(ctx, "induced_deg_kernel");
+    SGNN_LAUNCH(ctx, st, "induced_deg_kernel", SGNN_TAG, induced_deg_kernel<RP>, dim3(cdiv(B, 256)), dim3(256), 0, st, rowptr, S, B, deg);
     int rc = sgnn_scan_u32_to_u64(ctx, deg, P, B, scan_tmp64, st);
     if (rc) return rc;
     const unsigned grid = (unsigned)std::min<uint64_t>(max_tiles, IND_MAX_GRID);
-    hipLaunchKernelGGL(induced_count_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr, g->colidx, S, B, bitmap, P,
+    SGNN_LAUNCH(ctx, st, "induced_count_kernel", SGNN_TAG, induced_count_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr, g->colidx, S, B, bitmap, P,
                        tile_total, n_tiles);
-    SGNN_LAUNCH_CHECK(ctx, "induced_count_kernel");
     rc = sgnn_scan_u32_devn(ctx, tile_total, tile_off, n_tiles, max_tiles, scan_tmp32, st);
     if (rc) return rc;
     double p = 1.0;
     if (rescale && B > 1) p = ((double)B - 1.0) / ((double)g->N - 1.0);
-    hipLaunchKernelGGL(induced_fill_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr, g->colidx,
+    SGNN_LAUNCH(ctx, st, "induced_fill_kernel", SGNN_TAG, induced_fill_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr, g->colidx,
                        norm_mode == 0 ? g->val : nullptr, S, B, bitmap, rank, P, tile_off, n_tiles, p,
                        norm_mode == 0 ? 1 : 0, out->rowptr, out->colidx, out->val, out->capacity, out->nnz_dev,
                        ctx->status);
-    SGNN_LAUNCH_CHECK(ctx, "induced_fill_kernel");
     if (norm_mode == 1) {
-        hipLaunchKernelGGL(induced_renorm_kernel, dim3(cdiv((uint64_t)B * 64, 256)), dim3(256), 0, st, out->rowptr,
+        SGNN_LAUNCH(ctx, st, "induced_renorm_kernel", SGNN_TAG, induced_renorm_kernel, dim3(cdiv((uint64_t)B * 64, 256)), dim3(256), 0, st, out->rowptr,
                            out->colidx, out->val, B, out->capacity, p);
-        SGNN_LAUNCH_CHECK(ctx, "induced_renorm_kernel");
     }
     return SGNN_OK;
 }

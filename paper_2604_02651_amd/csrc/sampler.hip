@@ -305,24 +305,18 @@ int sgnn_launch_sampler(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, ui
 
     const uint64_t J = (N + 1) >> 1;
     const unsigned grid = (unsigned)std::min<uint64_t>(cdiv(J, SAMP_NT), 2048);
-    hipLaunchKernelGGL(sampler_hist_kernel, dim3(grid), dim3(SAMP_NT), 0, st, N, seed, step, hist);
-    SGNN_LAUNCH_CHECK(ctx, "sampler_hist_kernel");
-    hipLaunchKernelGGL(sampler_pick_bin_kernel, dim3(1), dim3(1024), 0, st, B, hist, state);
-    SGNN_LAUNCH_CHECK(ctx, "sampler_pick_bin_kernel");
-    hipLaunchKernelGGL(sampler_collect_kernel, dim3(grid), dim3(SAMP_NT), 0, st, N, seed, step, state, cand_key, cand_v,
+    SGNN_LAUNCH(ctx, st, "sampler_hist_kernel", SGNN_TAG, sampler_hist_kernel, dim3(grid), dim3(SAMP_NT), 0, st, N, seed, step, hist);
+    SGNN_LAUNCH(ctx, st, "sampler_pick_bin_kernel", SGNN_TAG, sampler_pick_bin_kernel, dim3(1), dim3(1024), 0, st, B, hist, state);
+    SGNN_LAUNCH(ctx, st, "sampler_collect_kernel", SGNN_TAG, sampler_collect_kernel, dim3(grid), dim3(SAMP_NT), 0, st, N, seed, step, state, cand_key, cand_v,
                        cap, ctx->status);
-    SGNN_LAUNCH_CHECK(ctx, "sampler_collect_kernel");
-    hipLaunchKernelGGL(sampler_threshold_kernel, dim3(1), dim3(1024), 0, st, state, cand_key, cand_v, cap);
-    SGNN_LAUNCH_CHECK(ctx, "sampler_threshold_kernel");
+    SGNN_LAUNCH(ctx, st, "sampler_threshold_kernel", SGNN_TAG, sampler_threshold_kernel, dim3(1), dim3(1024), 0, st, state, cand_key, cand_v, cap);
 
     const uint64_t W = (N + 63) / 64;
     const unsigned egrid = (unsigned)std::min<uint64_t>(cdiv(W, 8), EMIT_MAX_WG);
     const uint64_t wpw = (uint64_t)cdiv(cdiv(W, egrid), 8) * 8;
-    hipLaunchKernelGGL(sampler_emit_kernel, dim3(egrid), dim3(SAMP_NT), 0, st, N, seed, step, state, bitmap, W, wpw,
+    SGNN_LAUNCH(ctx, st, "sampler_emit_kernel", SGNN_TAG, sampler_emit_kernel, dim3(egrid), dim3(SAMP_NT), 0, st, N, seed, step, state, bitmap, W, wpw,
                        wg_count);
-    SGNN_LAUNCH_CHECK(ctx, "sampler_emit_kernel");
-    hipLaunchKernelGGL(sampler_rank_kernel, dim3(egrid), dim3(SAMP_NT), 0, st, bitmap, W, wpw, wg_count, B, rank, S,
+    SGNN_LAUNCH(ctx, st, "sampler_rank_kernel", SGNN_TAG, sampler_rank_kernel, dim3(egrid), dim3(SAMP_NT), 0, st, bitmap, W, wpw, wg_count, B, rank, S,
                        ctx->status);
-    SGNN_LAUNCH_CHECK(ctx, "sampler_rank_kernel");
     return SGNN_OK;
 }

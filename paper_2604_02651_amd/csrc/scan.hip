@@ -113,17 +113,13 @@ int scan_impl(sgnn_ctx *ctx, const uint32_t *in, OutT *out, const uint64_t *n_de
               hipStream_t st)
 {
     if (n_max <= SCAN_SINGLE_MAX) {
-        hipLaunchKernelGGL(scan_single_kernel<OutT>, dim3(1), dim3(1024), 0, st, in, out, n_dev, n_max);
-        SGNN_LAUNCH_CHECK(ctx, "scan_single_kernel");
+        SGNN_LAUNCH(ctx, st, "scan_single_kernel", SGNN_TAG, scan_single_kernel<OutT>, dim3(1), dim3(1024), 0, st, in, out, n_dev, n_max);
         return SGNN_OK;
     }
     const unsigned nb = cdiv(n_max, SCAN_TILE);
-    hipLaunchKernelGGL(scan_reduce_kernel<OutT>, dim3(nb), dim3(SCAN_NT), 0, st, in, tmp, n_dev, n_max);
-    SGNN_LAUNCH_CHECK(ctx, "scan_reduce_kernel");
-    hipLaunchKernelGGL(scan_partials_kernel<OutT>, dim3(1), dim3(1024), 0, st, tmp, n_dev, n_max);
-    SGNN_LAUNCH_CHECK(ctx, "scan_partials_kernel");
-    hipLaunchKernelGGL(scan_down_kernel<OutT>, dim3(nb), dim3(SCAN_NT), 0, st, in, out, tmp, n_dev, n_max);
-    SGNN_LAUNCH_CHECK(ctx, "scan_down_kernel");
+    SGNN_LAUNCH(ctx, st, "scan_reduce_kernel", SGNN_TAG, scan_reduce_kernel<OutT>, dim3(nb), dim3(SCAN_NT), 0, st, in, tmp, n_dev, n_max);
+    SGNN_LAUNCH(ctx, st, "scan_partials_kernel", SGNN_TAG, scan_partials_kernel<OutT>, dim3(1), dim3(1024), 0, st, tmp, n_dev, n_max);
+    SGNN_LAUNCH(ctx, st, "scan_down_kernel", SGNN_TAG, scan_down_kernel<OutT>, dim3(nb), dim3(SCAN_NT), 0, st, in, out, tmp, n_dev, n_max);
     return SGNN_OK;
 }
 

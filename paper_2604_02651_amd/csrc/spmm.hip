@@ -106,9 +106,10 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, con
               int64_t ldo, int lpr_log2, hipStream_t st)
 {
     const unsigned rows_per_block = 256u >> lpr_log2;
-    hipLaunchKernelGGL((spmm_rowsplit_kernel<VEC, CH>), dim3(cdiv(A->rows, rows_per_block)), dim3(256), 0, st, A->rows,
+    char tag[56];
+    snprintf(tag, sizeof(tag), "%ux%u d=%d", A->rows, A->cols, d);
+    SGNN_LAUNCH(ctx, st, "spmm_rowsplit_kernel", tag, (spmm_rowsplit_kernel<VEC, CH>), dim3(cdiv(A->rows, rows_per_block)), dim3(256), 0, st, A->rows,
                        A->rowptr, A->colidx, A->val, A->capacity, X, ldx, row_index, d, out, ldo, lpr_log2);
-    SGNN_LAUNCH_CHECK(ctx, "spmm_rowsplit_kernel");
     return SGNN_OK;
 }
 
