@@ -7,6 +7,22 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+template <int VEC> __device__ __forceinline__ void vload(float (&dst)[VEC], const float *p)
+{
+    if constexpr (VEC == 4) {
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(p);
+        dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
+    } else dst[0] = *p;
+}
+
+template <int VEC> __device__ __forceinline__ void vstore(float *p, const float (&src)[VEC])
+{
+    if constexpr (VEC == 4) {
+        f32x4 v = {src[0], src[1], src[2], src[3]};
+        *reinterpret_cast<f32x4 *>(p) = v;
+    } else *p = src[0];
+}
+
 // out[i, :] = X[S[i], :];  VEC = 4 when everything is 16-byte aligned, else 1.
 template <int VEC>
 __global__ __launch_bounds__(256) void gather_rows_kernel(const float *__restrict__ X, int64_t dv, int64_t ldx,
@@ -29,81 +45,115 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const float *__restric
 }
 
 // dZ = dY where Y > 0 (or all of dY), and per-workgroup column sums of dZ.
-// Thread (tx, ty): tx < CW walks columns tx, tx+CW, ...; ty walks the rows of the workgroup's slab.
-template <int CW>
+// A thread owns VEC consecutive columns; tx < cwp walks the column chunks, ty the rows of the
+// workgroup's slab, four rows in flight.
+template <int VEC>
 __global__ __launch_bounds__(256) void relu_bwd_colsum_kernel(const float *__restrict__ Y, int64_t ldy,
                                                               const float *__restrict__ dY, int64_t lddy, int relu,
-                                                              int64_t rows, int cols, int64_t rows_per_wg,
+                                                              int64_t rows, int cols, int64_t rows_per_wg, int cwp_log2,
                                                               float *__restrict__ dZ, int64_t lddz,
                                                               float *__restrict__ partial)
 {
-    constexpr int RY = 256 / CW;
-    __shared__ float red[256];
-    const int tx = threadIdx.x % CW, ty = threadIdx.x / CW;
+    __shared__ float red[256 * VEC];
+    const int cwp = 1 << cwp_log2, ry = 256 >> cwp_log2;
+    const int tx = threadIdx.x & (cwp - 1), ty = threadIdx.x >> cwp_log2;
+    const int cw = cols / VEC;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_wg, r1 = min(rows, r0 + rows_per_wg);
-    for (int c0 = 0; c0 < cols; c0 += CW) {
-        const int col = c0 + tx;
-        float acc = 0.f;
-        if (col < cols) {
-            for (int64_t r = r0 + ty; r < r1; r += RY) {
-                float g = dY[r * lddy + col];
-                if (relu && !(Y[r * ldy + col] > 0.f)) g = 0.f;
-                if (dZ) dZ[r * lddz + col] = g;
-                acc += g;
+    for (int c0 = 0; c0 < cw; c0 += cwp) {
+        const int ch = c0 + tx;
+        float acc[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+        if (ch < cw) {
+            const int col = ch * VEC;
+#pragma unroll 4
+            for (int64_t r = r0 + ty; r < r1; r += ry) {
+                float g[VEC], y[VEC];
+                vload<VEC>(g, dY + r * lddy + col);
+                if (relu) {
+                    vload<VEC>(y, Y + r * ldy + col);
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) if (!(y[i] > 0.f)) g[i] = 0.f;
+                }
+                if (dZ) vstore<VEC>(dZ + r * lddz + col, g);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] += g[i];
             }
         }
         if (partial) {
-            red[threadIdx.x] = acc;
-            __syncthreads();
-            if (ty == 0 && col < cols) {
-                float s = 0.f;
 #pragma unroll
-                for (int q = 0; q < RY; ++q) s += red[q * CW + tx];
-                partial[(int64_t)blockIdx.x * cols + col] = s;
+            for (int i = 0; i < VEC; ++i) red[threadIdx.x * VEC + i] = acc[i];
+            __syncthreads();
+            if (ty == 0 && ch < cw) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    float s = 0.f;
+                    for (int w = 0; w < ry; ++w) s += red[(w * cwp + tx) * VEC + i];
+                    partial[(int64_t)blockIdx.x * cols + ch * VEC + i] = s;
+                }
             }
             __syncthreads();
         }
     }
 }
 
-__global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restrict__ partial, int nwg, int cols,
-                                                           float *__restrict__ out)
+// out[col] = sum over workgroups of partial[w][col], in a fixed order: 16 interleaved chains a
+// column, then the 16 chain sums in order.
+__global__ __launch_bounds__(1024) void colsum_final_kernel(const float *__restrict__ partial, int nwg, int cols,
+                                                            float *__restrict__ out)
 {
-    const int col = blockIdx.x * 256 + threadIdx.x;
-    if (col >= cols) return;
+    __shared__ float red[1024];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int col = blockIdx.x * 64 + tx;
     float s = 0.f;
-    for (int w = 0; w < nwg; ++w) s += partial[(int64_t)w * cols + col];
-    out[col] = s;
+    if (col < cols) {
+#pragma unroll 8
+        for (int w = ty; w < nwg; w += 16) s += partial[(int64_t)w * cols + col];
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (ty == 0 && col < cols) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += red[w * 64 + tx];
+        out[col] = t;
+    }
 }
 
-// One wavefront per row; a workgroup covers 64 rows and writes one partial loss.
+// A group of lpr lanes (a power of two >= C, at most 64) owns a row; a workgroup covers
+// 4 * 256 / lpr rows and writes one partial loss.
 __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, int64_t ldo,
                                                    const int32_t *__restrict__ labels, uint32_t B, uint32_t C,
-                                                   float *__restrict__ dO, int64_t lddo, float *__restrict__ partial)
+                                                   int lpr_log2, float *__restrict__ dO, int64_t lddo,
+                                                   float *__restrict__ partial)
 {
     __shared__ float lds[4];
-    const unsigned wave = threadIdx.x >> 6, lane = lane_id();
+    const int lpr = 1 << lpr_log2;
+    const uint32_t rows_per_pass = 256u >> lpr_log2;
+    const uint32_t gq = threadIdx.x >> lpr_log2, g = threadIdx.x & (lpr - 1);
     float loss = 0.f;
     const float invB = 1.f / (float)B;
-    for (int q = 0; q < 16; ++q) {
-        const uint32_t row = blockIdx.x * 64 + q * 4 + wave;
-        if (row >= B) break;
-        const float *o = O + (int64_t)row * ldo;
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t row = (blockIdx.x * 4 + q) * rows_per_pass + gq;
+        const bool live = row < B;
+        const float *o = O + (int64_t)(live ? row : 0) * ldo;
         float m = -INFINITY;
-        for (uint32_t j = lane; j < C; j += 64) m = fmaxf(m, o[j]);
-#pragma unroll
-        for (int s = 32; s > 0; s >>= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+        if (live) for (uint32_t j = g; j < C; j += lpr) m = fmaxf(m, o[j]);
+        for (int s = lpr >> 1; s > 0; s >>= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
         float sum = 0.f;
-        for (uint32_t j = lane; j < C; j += 64) sum += expf(o[j] - m);
-        sum = wave_sum(sum);
-        const float lse = m + logf(sum);
-        const int32_t y = labels[row];
-        loss += lse - ((uint32_t)y < C ? o[y] : 0.f);
-        if (dO)
-            for (uint32_t j = lane; j < C; j += 64)
-                dO[(int64_t)row * lddo + j] = (expf(o[j] - lse) - ((int32_t)j == y ? 1.f : 0.f)) * invB;
+        if (live) for (uint32_t j = g; j < C; j += lpr) sum += expf(o[j] - m);
+        for (int s = lpr >> 1; s > 0; s >>= 1) sum += __shfl_xor(sum, s, 64);
+        if (live) {
+            const float lse = m + logf(sum);
+            const int32_t y = labels[row];
+            if (g == 0) loss += lse - ((uint32_t)y < C ? o[y] : 0.f);
+            if (dO)
+                for (uint32_t j = g; j < C; j += lpr)
+                    dO[(int64_t)row * lddo + j] = (expf(o[j] - lse) - ((int32_t)j == y ? 1.f : 0.f)) * invB;
+        }
     }
-    if (lane == 0) lds[wave] = loss;
+    loss = wave_sum(loss);
+    if (lane_id() == 0) lds[threadIdx.x >> 6] = loss;
     __syncthreads();
     if (threadIdx.x == 0) partial[blockIdx.x] = (lds[0] + lds[1]) + (lds[2] + lds[3]);
 }
@@ -149,31 +199,33 @@ int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const 
         partial = ws->get<float>((size_t)nwg * cols);
         if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
     }
-    if (cols <= 32)
-        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<32>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
-                           rows_per_wg, dZ, lddz, partial);
-    else if (cols <= 64)
-        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<64>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
-                           rows_per_wg, dZ, lddz, partial);
-    else if (cols <= 128)
-        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<128>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
-                           rows_per_wg, dZ, lddz, partial);
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(Y) | reinterpret_cast<uintptr_t>(dY) | reinterpret_cast<uintptr_t>(dZ);
+    const bool v4 = cols % 4 == 0 && lddy % 4 == 0 && (!relu || ldy % 4 == 0) && (!dZ || lddz % 4 == 0) && (bits & 15) == 0;
+    const int cw = (int)(v4 ? cols / 4 : cols);
+    int cwp_log2 = 0;
+    while ((1 << cwp_log2) < cw && cwp_log2 < 8) ++cwp_log2;
+    if (v4)
+        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<4>, dim3(nwg), dim3(256), 0, st, Y, ldy,
+                    dY, lddy, relu, rows, (int)cols, rows_per_wg, cwp_log2, dZ, lddz, partial);
     else
-        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<256>, dim3(nwg), dim3(256), 0, st, Y, ldy, dY, lddy, relu, rows, (int)cols,
-                           rows_per_wg, dZ, lddz, partial);
-    if (dbias) {
-        SGNN_LAUNCH(ctx, st, "colsum_final_kernel", SGNN_TAG, colsum_final_kernel, dim3(cdiv(cols, 256)), dim3(256), 0, st, partial, (int)nwg, (int)cols, dbias);
-    }
+        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<1>, dim3(nwg), dim3(256), 0, st, Y, ldy,
+                    dY, lddy, relu, rows, (int)cols, rows_per_wg, cwp_log2, dZ, lddz, partial);
+    if (dbias)
+        SGNN_LAUNCH(ctx, st, "colsum_final_kernel", SGNN_TAG, colsum_final_kernel, dim3(cdiv(cols, 64)), dim3(1024), 0, st,
+                    partial, (int)nwg, (int)cols, dbias);
     return SGNN_OK;
 }
 
 int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C, float *loss,
                      float *dO, int64_t lddo, ws_alloc *ws, hipStream_t st)
 {
-    const unsigned nwg = cdiv(B, 64);
+    int lpr_log2 = 0;
+    while ((1u << lpr_log2) < C && lpr_log2 < 6) ++lpr_log2;
+    const unsigned rows_per_wg = 4u * (256u >> lpr_log2);
+    const unsigned nwg = cdiv(B, rows_per_wg);
     float *partial = ws->get<float>(nwg);
     if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_softmax_xent: scratch too small: call sgnn_ctx_reserve");
-    SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, dO, lddo, partial);
+    SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial);
     if (loss) {
         SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, 1.f / (float)B, loss);
     }

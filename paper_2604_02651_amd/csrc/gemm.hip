@@ -258,9 +258,18 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= MN) return;
-    float s = 0.f;
-    for (int z = 0; z < splits; ++z) s += partial[(int64_t)z * MN + i];
-    C[(i / N) * ldc + (i % N)] = s;
+    // four interleaved chains, combined in a fixed order
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int z = 0;
+#pragma unroll 2
+    for (; z + 3 < splits; z += 4) {
+        s0 += partial[(int64_t)z * MN + i];
+        s1 += partial[(int64_t)(z + 1) * MN + i];
+        s2 += partial[(int64_t)(z + 2) * MN + i];
+        s3 += partial[(int64_t)(z + 3) * MN + i];
+    }
+    for (; z < splits; ++z) s0 += partial[(int64_t)z * MN + i];
+    C[(i / N) * ldc + (i % N)] = (s0 + s1) + (s2 + s3);
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -311,7 +320,7 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     const int64_t tiles = (int64_t)cdiv(M, bm) * cdiv(N, bn);
     if (tiles < 256 && K >= 4096 && !bias && !(flags & SGNN_RELU)) {
         // long reduction onto a small result (the weight gradient): split the reduction
-        int64_t want = (512 + tiles - 1) / tiles;
+        int64_t want = (256 + tiles - 1) / tiles;
         int64_t kps = ((K + want - 1) / want + BK - 1) / BK * BK;
         if (kps < 8 * BK) kps = 8 * BK;
         splits = (int)((K + kps - 1) / kps);
