@@ -114,6 +114,9 @@ def main():
     total_ms = sum(v["ms"] for v in groups.values())
     dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
     if args.breakdown:
+        for name, tag, calls, ms in recs:
+            if name.startswith("spmm"):
+                print("  %-24s %-28s calls %3d  avg us %8.2f" % (name, tag, calls, 1e3 * ms / calls), file=sys.stderr)
         for k, v in sorted(groups.items(), key=lambda kv: -kv[1]["ms"]):
             print("%-44s calls/step %5.1f  us/step %9.2f  avg us %8.2f" %
                   (k, v["calls"] / nprof, 1e3 * v["ms"] / nprof, 1e3 * v["ms"] / v["calls"]), file=sys.stderr)

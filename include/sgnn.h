@@ -57,11 +57,13 @@ int sgnn_ctx_destroy(sgnn_ctx *ctx);
 
 /*
  * Size the scratch for graphs of up to N vertices and E stored entries, samples of up to B
- * vertices and layers of width up to d_max.  The only call that allocates device memory
+ * vertices, layers of width up to d_max and mini-batch matrices with room for up to max_entries
+ * entries (their sgnn_csr.capacity).  The only call that allocates device memory
  * (hipMalloc); it synchronises the device when it has to grow.  Later calls that need more
  * scratch than reserved fail with SGNN_ERR_CAPACITY.
  */
-int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t d_max);
+int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t d_max,
+                     uint64_t max_entries);
 
 /* Message of the last error on this context ("" if none).  Host string owned by the context. */
 const char *sgnn_last_error(const sgnn_ctx *ctx);
@@ -117,6 +119,11 @@ typedef struct {
 /*
  * A mini-batch matrix in CSR: rows x cols, int32 rowptr[rows+1], colidx/val with room for
  * `capacity` entries.  nnz_dev (device uint32[1], may be NULL) receives the number of entries.
+ * plan (may be NULL) is a device buffer of sgnn_csr_plan_bytes(rows, capacity) bytes that holds
+ * the split of the long rows into chunks used by the sparse products.  sgnn_induced_csr fills it
+ * for the matrix it writes; sgnn_csr_plan fills it for any other matrix.  It stays valid while
+ * rows, capacity and the contents of rowptr do not change.  Without a plan every sparse product
+ * builds a temporary one in the context scratch (two more small kernel launches per product).
  */
 typedef struct {
     uint32_t rows, cols;
@@ -125,7 +132,11 @@ typedef struct {
     float *val;
     uint64_t capacity;
     uint32_t *nnz_dev;
+    void *plan;
 } sgnn_csr;
+
+uint64_t sgnn_csr_plan_bytes(uint32_t rows, uint64_t capacity);
+int sgnn_csr_plan(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_stream stream);
 
 /*
  * Eqs. 21-24 / Algorithm 2 with the full row and column range: for i in [0,B), v = S[i], keep

@@ -36,7 +36,7 @@ class _Graph(C.Structure):
 
 class _Csr(C.Structure):
     _fields_ = [("rows", C.c_uint32), ("cols", C.c_uint32), ("rowptr", C.c_void_p), ("colidx", C.c_void_p),
-                ("val", C.c_void_p), ("capacity", C.c_uint64), ("nnz_dev", C.c_void_p)]
+                ("val", C.c_void_p), ("capacity", C.c_uint64), ("nnz_dev", C.c_void_p), ("plan", C.c_void_p)]
 
 
 class _Mat(C.Structure):
@@ -62,7 +62,7 @@ def lib():
         vp, u64, u32, i64, ci = C.c_void_p, C.c_uint64, C.c_uint32, C.c_int64, C.c_int
         L.sgnn_ctx_create.argtypes = [C.POINTER(vp), ci]
         L.sgnn_ctx_destroy.argtypes = [vp]
-        L.sgnn_ctx_reserve.argtypes = [vp, u64, u64, u32, u32]
+        L.sgnn_ctx_reserve.argtypes = [vp, u64, u64, u32, u32, u64]
         L.sgnn_last_error.argtypes = [vp]
         L.sgnn_last_error.restype = C.c_char_p
         L.sgnn_ctx_status.argtypes = [vp, vp]
@@ -71,6 +71,9 @@ def lib():
         L.sgnn_sample_uniform.argtypes = [vp, u64, u32, u64, u64, vp, vp, vp, vp]
         L.sgnn_induced_csr.argtypes = [vp, C.POINTER(_Graph), vp, u32, vp, vp, ci, ci, C.POINTER(_Csr),
                                        C.POINTER(u64), vp]
+        L.sgnn_csr_plan_bytes.argtypes = [u32, u64]
+        L.sgnn_csr_plan_bytes.restype = u64
+        L.sgnn_csr_plan.argtypes = [vp, C.POINTER(_Csr), vp]
         L.sgnn_gather_rows.argtypes = [vp, vp, i64, i64, vp, u32, vp, i64, vp, vp, vp]
         L.sgnn_gcn_fwd.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), vp, ci, C.POINTER(_Mat),
                                    C.POINTER(_Mat), vp]
@@ -81,7 +84,7 @@ def lib():
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
-                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd",
+                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd",
                      "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm"):
             getattr(L, name).restype = ci
         _lib = L
@@ -131,8 +134,8 @@ class Context:
         if rc != 0:
             raise SgnnError(rc, lib().sgnn_last_error(self._h).decode())
 
-    def reserve(self, N: int, E: int, B: int, d_max: int):
-        self.check(lib().sgnn_ctx_reserve(self._h, N, E, B, d_max))
+    def reserve(self, N: int, E: int, B: int, d_max: int, max_entries: int = 0):
+        self.check(lib().sgnn_ctx_reserve(self._h, N, E, B, d_max, max_entries))
 
     def status(self, stream=None):
         self.check(lib().sgnn_ctx_status(self._h, _stream(stream)))
@@ -165,17 +168,23 @@ class Context:
 class Csr:
     """Device buffers of a mini-batch CSR (rows x cols) with room for `capacity` entries."""
 
-    def __init__(self, rows: int, cols: int, capacity: int, device="cuda:0"):
+    def __init__(self, rows: int, cols: int, capacity: int, device="cuda:0", with_plan: bool = True):
         self.rows, self.cols, self.capacity = rows, cols, capacity
+        self.plan = None
+        if with_plan:
+            nbytes = int(lib().sgnn_csr_plan_bytes(rows, capacity))
+            self.plan = torch.zeros((nbytes + 7) // 8, dtype=torch.int64, device=device)
         self.rowptr = torch.zeros(rows + 1, dtype=torch.int32, device=device)
         self.colidx = torch.zeros(max(capacity, 1), dtype=torch.int32, device=device)
         self.val = torch.zeros(max(capacity, 1), dtype=torch.float32, device=device)
         self.nnz_dev = torch.zeros(1, dtype=torch.int32, device=device)
 
     @classmethod
-    def from_arrays(cls, rows, cols, rowptr, colidx, val, device="cuda:0"):
+    def from_arrays(cls, rows, cols, rowptr, colidx, val, device="cuda:0", with_plan: bool = False):
+        """A matrix from host arrays.  Without with_plan the sparse products plan on the fly; with
+        it, call sgnn_csr_plan(ctx, csr) once after this."""
         import numpy as np
-        c = cls(rows, cols, len(colidx), device)
+        c = cls(rows, cols, len(colidx), device, with_plan)
         c.rowptr.copy_(torch.as_tensor(np.asarray(rowptr, np.int32)))
         if len(colidx):
             c.colidx[:len(colidx)].copy_(torch.as_tensor(np.asarray(colidx, np.int32)))
@@ -185,7 +194,8 @@ class Csr:
 
     def struct(self) -> _Csr:
         return _Csr(self.rows, self.cols, _ptr(self.rowptr, torch.int32), _ptr(self.colidx, torch.int32),
-                    _ptr(self.val, torch.float32), self.capacity, _ptr(self.nnz_dev, torch.int32))
+                    _ptr(self.val, torch.float32), self.capacity, _ptr(self.nnz_dev, torch.int32),
+                    _ptr(self.plan, torch.int64) if self.plan is not None else None)
 
     def nnz(self) -> int:
         return int(self.nnz_dev.item())
@@ -226,6 +236,11 @@ def sgnn_induced_csr(ctx: Context, N: int, rowptr: torch.Tensor, colidx: torch.T
     out.rows = out.cols = B
     ctx.check(rc)
     return int(nnz.value) if want_nnz else None
+
+
+def sgnn_csr_plan(ctx: Context, A: Csr, stream=None):
+    a = A.struct()
+    ctx.check(lib().sgnn_csr_plan(ctx._h, C.byref(a), _stream(stream)))
 
 
 def sgnn_gather_rows(ctx: Context, X: Optional[torch.Tensor], S: torch.Tensor, B: int, out: Optional[torch.Tensor],

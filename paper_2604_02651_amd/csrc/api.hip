@@ -13,6 +13,7 @@ size_t sgnn_sampler_persist_bytes();
 size_t sgnn_sampler_ws_bytes(uint64_t N);
 size_t sgnn_induced_ws_bytes(uint64_t E, uint32_t B);
 size_t sgnn_gemm_ws_bytes(uint32_t d_max);
+size_t sgnn_spmm_ws_bytes(uint64_t max_entries, uint32_t B, uint32_t d_max);
 
 int sgnn_fail(sgnn_ctx *ctx, int code, const char *fmt, ...)
 {
@@ -55,7 +56,7 @@ void sgnn_prof_end(sgnn_ctx *ctx, hipStream_t st)
 
 namespace {
 
-constexpr size_t PERSIST_BYTES = 16384;
+constexpr size_t PERSIST_BYTES = SGNN_PERSIST_BYTES;
 
 int bind_device(sgnn_ctx *ctx)
 {
@@ -113,7 +114,7 @@ int sgnn_ctx_destroy(sgnn_ctx *ctx)
 
 const char *sgnn_last_error(const sgnn_ctx *ctx) { return ctx ? ctx->err : "null context"; }
 
-int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t d_max)
+int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t d_max, uint64_t max_entries)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     int rc = bind_device(ctx);
@@ -121,7 +122,8 @@ int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t
     size_t need = sgnn_sampler_ws_bytes(N);
     need = std::max(need, sgnn_induced_ws_bytes(E, B));
     // backward: dZ and dT (B x d_max each), split-K partials, column-sum partials
-    size_t layer = (size_t)2 * B * d_max * 4 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 + 16 * 256;
+    size_t layer = (size_t)2 * B * d_max * 4 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 +
+                   sgnn_spmm_ws_bytes(max_entries, B, d_max) + 16 * 256;
     need = std::max(need, layer);
     need = std::max(need, (size_t)B / 64 * 4 + 4096);
     need += 4096;
@@ -232,6 +234,8 @@ int sgnn_induced_csr(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint3
     if (nnz_host && !nnz_dev) o.nnz_dev = ctx->status + 2;
     rc = sgnn_launch_induced(ctx, g, S, B, bitmap, rank, norm_mode, rescale, &o, st);
     if (rc) return rc;
+    rc = sgnn_launch_spmm_plan(ctx, &o, st);
+    if (rc) return rc;
     out->rows = out->cols = B;
     if (nnz_host) {
         uint32_t n = 0;
@@ -243,6 +247,15 @@ int sgnn_induced_csr(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint3
                              (unsigned long long)out->capacity);
     }
     return SGNN_OK;
+}
+
+int sgnn_csr_plan(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!A || !A->rowptr || !A->plan) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_csr_plan: null pointer");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return sgnn_launch_spmm_plan(ctx, A, static_cast<hipStream_t>(stream));
 }
 
 int sgnn_gather_rows(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, const int32_t *S, uint32_t B, float *out,
@@ -267,8 +280,9 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, sgnn_mat *out
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: shape mismatch");
     int rc = bind_device(ctx);
     if (rc) return rc;
+    ws_alloc ws(ctx);
     return sgnn_launch_spmm(ctx, A, static_cast<const float *>(X->ptr), X->ld, X->row_index, X->cols,
-                            static_cast<float *>(out->ptr), out->ld, static_cast<hipStream_t>(stream));
+                            static_cast<float *>(out->ptr), out->ld, &ws, static_cast<hipStream_t>(stream));
 }
 
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
@@ -299,10 +313,10 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
     int rc = bind_device(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    rc = sgnn_launch_spmm(ctx, A, static_cast<const float *>(H->ptr), H->ld, H->row_index, d_in,
-                          static_cast<float *>(T->ptr), T->ld, st);
-    if (rc) return rc;
     ws_alloc ws(ctx);
+    rc = sgnn_launch_spmm(ctx, A, static_cast<const float *>(H->ptr), H->ld, H->row_index, d_in,
+                          static_cast<float *>(T->ptr), T->ld, &ws, st);
+    if (rc) return rc;
     return sgnn_launch_gemm(ctx, 0, 0, Bn, d_out, d_in, static_cast<const float *>(T->ptr), T->ld,
                             static_cast<const float *>(W->ptr), W->ld, bias, flags & (SGNN_RELU | SGNN_BF16_MFMA),
                             static_cast<float *>(Y->ptr), Y->ld, &ws, st);
@@ -352,7 +366,7 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
         rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, static_cast<const float *>(W->ptr), W->ld, nullptr,
                               mfma, dT, d_in, &ws, st);
         if (rc) return rc;
-        rc = sgnn_launch_spmm(ctx, A_T, dT, d_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, st);
+        rc = sgnn_launch_spmm(ctx, A_T, dT, d_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, &ws, st);
         if (rc) return rc;
     }
     return SGNN_OK;

@@ -31,6 +31,10 @@ struct sgnn_ctx {
     uint32_t res_B, res_d;
 };
 
+// Offset in the persistent area of the SpMM chunk counter (uint32, zero between calls).
+#define SGNN_PERSIST_BYTES 32768
+#define SGNN_PERSIST_SPMM_OFF 12288
+
 // status bits
 #define SGNN_ST_CAND_OVERFLOW 1u
 #define SGNN_ST_NNZ_OVERFLOW 2u
@@ -98,7 +102,8 @@ int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, ui
                         const uint64_t *bitmap, const uint32_t *rank, int norm_mode, int rescale,
                         sgnn_csr *out, hipStream_t st);
 int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index,
-                     int64_t d, float *out, int64_t ldo, hipStream_t st);
+                     int64_t d, float *out, int64_t ldo, ws_alloc *ws, hipStream_t st);
+int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st);   // fills A->plan when it is attached
 int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A,
                      int64_t lda, const float *B, int64_t ldb, const float *bias, int flags, float *C,
                      int64_t ldc, ws_alloc *ws, hipStream_t st);

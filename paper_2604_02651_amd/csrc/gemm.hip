@@ -18,6 +18,10 @@
 // the slice of 16 is fed as k = 8*kh + s at step s: every lane then reads 8 consecutive values.
 #include "common.h"
 
+#ifndef SGNN_GEMM_BK_F32
+#define SGNN_GEMM_BK_F32 32   // reduction slice of the fp32 path (a multiple of 16)
+#endif
+
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -131,7 +135,7 @@ __device__ __forceinline__ void store_operand(void *lds, const f32x4 *reg)
 template <int BM, int BN, int WM, int WN, bool TA, bool TB, bool BF16>
 __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
 {
-    constexpr int BK = BF16 ? 32 : 16;
+    constexpr int BK = BF16 ? 32 : SGNN_GEMM_BK_F32;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int WAVES_N = BN / WN;
     static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts per workgroup");
@@ -173,42 +177,45 @@ __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
             fetch_operand<BN, BK, B_RC>(rb, a.B, a.ldb, n0, a.N, k0 + BK, kend, a.alignedB);
         }
         if constexpr (!BF16) {
-            float av[TM][8], bv[TN][8];
             const float *LA = reinterpret_cast<const float *>(ldsA);
             const float *LB = reinterpret_cast<const float *>(ldsB);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int row = wm0 + 32 * i + li;
-                if (A_RC) {
-                    const f32x4 x0 = *reinterpret_cast<const f32x4 *>(LA + row * (BK + 4) + 8 * kh);
-                    const f32x4 x1 = *reinterpret_cast<const f32x4 *>(LA + row * (BK + 4) + 8 * kh + 4);
+            for (int kk = 0; kk < BK; kk += 16) {
+                float av[TM][8], bv[TN][8];
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) { av[i][s] = x0[s]; av[i][4 + s] = x1[s]; }
-                } else {
+                for (int i = 0; i < TM; ++i) {
+                    const int row = wm0 + 32 * i + li;
+                    if (A_RC) {
+                        const f32x4 x0 = *reinterpret_cast<const f32x4 *>(LA + row * (BK + 4) + kk + 8 * kh);
+                        const f32x4 x1 = *reinterpret_cast<const f32x4 *>(LA + row * (BK + 4) + kk + 8 * kh + 4);
 #pragma unroll
-                    for (int s = 0; s < 8; ++s) av[i][s] = LA[(8 * kh + s) * (BM + 4) + row];
+                        for (int s = 0; s < 4; ++s) { av[i][s] = x0[s]; av[i][4 + s] = x1[s]; }
+                    } else {
+#pragma unroll
+                        for (int s = 0; s < 8; ++s) av[i][s] = LA[(kk + 8 * kh + s) * (BM + 4) + row];
+                    }
                 }
-            }
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = wn0 + 32 * j + li;
-                if (B_RC) {
-                    const f32x4 x0 = *reinterpret_cast<const f32x4 *>(LB + col * (BK + 4) + 8 * kh);
-                    const f32x4 x1 = *reinterpret_cast<const f32x4 *>(LB + col * (BK + 4) + 8 * kh + 4);
+                for (int j = 0; j < TN; ++j) {
+                    const int col = wn0 + 32 * j + li;
+                    if (B_RC) {
+                        const f32x4 x0 = *reinterpret_cast<const f32x4 *>(LB + col * (BK + 4) + kk + 8 * kh);
+                        const f32x4 x1 = *reinterpret_cast<const f32x4 *>(LB + col * (BK + 4) + kk + 8 * kh + 4);
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) { bv[j][s] = x0[s]; bv[j][4 + s] = x1[s]; }
-                } else {
+                        for (int s = 0; s < 4; ++s) { bv[j][s] = x0[s]; bv[j][4 + s] = x1[s]; }
+                    } else {
 #pragma unroll
-                    for (int s = 0; s < 8; ++s) bv[j][s] = LB[(8 * kh + s) * (BN + 4) + col];
+                        for (int s = 0; s < 8; ++s) bv[j][s] = LB[(kk + 8 * kh + s) * (BN + 4) + col];
+                    }
                 }
+#pragma unroll
+                for (int s = 0; s < 8; ++s)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][s], bv[j][s], acc[i][j], 0, 0, 0);
             }
-#pragma unroll
-            for (int s = 0; s < 8; ++s)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][s], bv[j][s], acc[i][j], 0, 0, 0);
         } else {
             const u16 *LA = reinterpret_cast<const u16 *>(ldsA);
             const u16 *LB = reinterpret_cast<const u16 *>(ldsB);
@@ -311,7 +318,7 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     a.k_per_split = K;
     a.partial = nullptr;
     const int bf16 = (flags & SGNN_BF16_MFMA) ? 1 : 0;
-    const int BK = bf16 ? 32 : 16;
+    const int BK = bf16 ? 32 : SGNN_GEMM_BK_F32;
 
     // tile shape by the width of C
     const int bn = N > 64 ? 128 : (N > 32 ? 64 : 32);

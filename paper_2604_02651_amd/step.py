@@ -31,7 +31,6 @@ class GcnStep:
         dims = [weights[0][0].shape[0]] + [w.shape[1] for w, _ in weights]
         self.dims = dims
         self.ctx = ctx or sg.Context(dev.index or 0)
-        self.ctx.reserve(N, E, B, max(dims))
         W = (N + 63) // 64
         self.S = torch.empty(B, dtype=torch.int32, device=dev)
         self.bitmap = torch.empty(W, dtype=torch.int64, device=dev)
@@ -40,6 +39,7 @@ class GcnStep:
             # expected entries B + (E-N) B(B-1)/(N(N-1)) with generous head-room
             exp = B + (E - N) * (B / N) * ((B - 1) / max(N - 1, 1))
             capacity = int(min(E, 2 * exp + 16 * B + 65536))
+        self.ctx.reserve(N, E, B, max(dims), capacity)
         self.A = sg.Csr(B, B, capacity, dev)
         self.y_S = torch.empty(B, dtype=torch.int32, device=dev)
         self.X_S = None if fuse_slice else torch.empty((B, dims[0]), dtype=torch.float32, device=dev)

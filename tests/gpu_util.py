@@ -18,6 +18,8 @@ def ctx():
     global _ctx
     if _ctx is None:
         _ctx = sg.Context(0)
+        # generous scratch for every test shape (vertices, stored entries, sample, width, mini-batch entries)
+        _ctx.reserve(1 << 21, 1 << 25, 1 << 18, 1024, 1 << 23)
     return _ctx
 
 

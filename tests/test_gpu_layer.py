@@ -30,7 +30,7 @@ def sub():
 @pytest.mark.parametrize("d", [1, 3, 8, 32, 41, 47, 64, 100, 128, 172, 256, 602, 1024])
 def test_spmm_widths(sub, d):
     B, rp, ci, v = sub
-    ctx().reserve(B, len(ci), B, d)
+    ctx().reserve(B, len(ci), B, d, len(ci))
     A = sg.Csr.from_arrays(B, B, rp, ci, v, DEV)
     X = _rand((B, d), d)
     out = torch.full((B, d), 7.0, dtype=torch.float32, device=DEV)
@@ -67,6 +67,48 @@ def test_spmm_rectangular_empty_rows_and_long_row():
     out = torch.full((rows, d), 7.0, dtype=torch.float32, device=DEV)
     sg.sgnn_spmm(ctx(), A, dev(X), out)
     assert rel_err(out.cpu().numpy(), oracle.spmm(rp, ci, v, X.astype(np.float64))) < TOL_F32
+
+
+@pytest.mark.parametrize("d", [32, 100, 256, 602])
+def test_spmm_rows_of_every_length_class(d):
+    # rows walked by one lane group, rows shared by a workgroup, rows cut into chunks (one of them
+    # starting exactly on a chunk boundary), empty rows in between
+    rng = np.random.default_rng(7)
+    rows, cols = 300, 9000
+    lens = rng.integers(0, 5, rows)
+    lens[[5, 17, 40]] = [65, 300, 512]
+    lens[[60, 61, 90, 299]] = [513, 2000, 5000, 1300]
+    lens[0] = 1024 - 0
+    lists = [np.sort(rng.permutation(cols)[:n]).astype(np.int32) for n in lens]
+    rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    ci = np.concatenate(lists); v = rng.standard_normal(len(ci)).astype(np.float32)
+    A = sg.Csr.from_arrays(rows, cols, rp, ci, v, DEV)
+    X = _rand((cols, d), 3)
+    out = torch.full((rows, d), 7.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_spmm(ctx(), A, dev(X), out)
+    assert rel_err(out.cpu().numpy(), oracle.spmm(rp, ci, v, X.astype(np.float64))) < TOL_F32
+    out2 = torch.zeros_like(out)
+    sg.sgnn_spmm(ctx(), A, dev(X), out2)
+    assert torch.equal(out, out2)          # bit-reproducible
+    # with a plan attached to the matrix (built once) the result is the same
+    Ap = sg.Csr.from_arrays(rows, cols, rp, ci, v, DEV, with_plan=True)
+    sg.sgnn_csr_plan(ctx(), Ap)
+    out3 = torch.zeros_like(out)
+    sg.sgnn_spmm(ctx(), Ap, dev(X), out3)
+    sg.sgnn_spmm(ctx(), Ap, dev(X), out3)
+    assert torch.equal(out, out3)
+
+
+def test_scratch_too_small_is_an_error():
+    small = sg.Context(0)
+    B, rp, ci, v = _sub_csr(500, 3000, 200, 1)
+    A = sg.Csr.from_arrays(B, B, rp, ci, v, DEV)
+    A.capacity = 100000        # pretend a large entry array: the chunk scratch no longer fits
+    A.colidx = torch.zeros(100000, dtype=torch.int32, device=DEV); A.val = torch.zeros(100000, dtype=torch.float32, device=DEV)
+    with pytest.raises(sg.SgnnError) as e:
+        sg.sgnn_spmm(small, A, dev(_rand((B, 8), 1)), torch.zeros((B, 8), dtype=torch.float32, device=DEV))
+    assert e.value.code == -2
+    small.close()
 
 
 GEMM_SHAPES = [(1, 1, 1), (5, 7, 3), (33, 65, 17), (128, 128, 16), (130, 129, 100), (257, 32, 256), (300, 8, 64),
@@ -145,7 +187,7 @@ def test_gemm_strided_operands():
 @pytest.mark.parametrize("d_in,d_out,relu", [(32, 64, True), (64, 8, False), (100, 256, True), (256, 47, False)])
 def test_layer_forward_backward(sub, d_in, d_out, relu, bf16):
     B, rp, ci, v = sub
-    ctx().reserve(B, len(ci), B, max(d_in, d_out))
+    ctx().reserve(B, len(ci), B, max(d_in, d_out), len(ci))
     A = sg.Csr.from_arrays(B, B, rp, ci, v, DEV)
     H = _rand((B, d_in), 1); W = (_rand((d_in, d_out), 2) / np.sqrt(d_in)).astype(np.float32); b = _rand(d_out, 3) * 0.1
     dY = _rand((B, d_out), 4)
@@ -176,7 +218,7 @@ def test_backward_uses_the_transpose():
     rp = np.array([0, 2, 3, 6], np.int32); ci = np.array([0, 2, 0, 0, 1, 2], np.int32)
     v = np.array([0.5, -1.0, 2.0, 0.25, 3.0, 1.5], np.float32)
     H = _rand((3, 4), 1); W = _rand((4, 2), 2); R = _rand((3, 2), 3)
-    ctx().reserve(3, 6, 3, 4)
+    ctx().reserve(3, 6, 3, 4, 6)
     T_ref, Y_ref = oracle.gcn_fwd(rp, ci, v, H, W, None, relu=False)
     rpT, ciT, vT = oracle.csr_transpose(3, 3, rp, ci, v)
     dH_ref, dW_ref, _ = oracle.gcn_bwd(rpT, ciT, vT, T_ref, W, Y_ref, R, relu=False)

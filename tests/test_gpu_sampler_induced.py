@@ -61,7 +61,7 @@ def _induce_gpu(g, B, seed, step, norm_mode=0, rescale=1, val=None, rowptr_dtype
     N = g.N
     rowptr = g.rowptr.to(rowptr_dtype).to(DEV)
     colidx = g.colidx.to(DEV)
-    ctx().reserve(N, g.E, B, 1)
+    ctx().reserve(N, g.E, B, 1, 0)
     S, bitmap, rank = gpu_sample(N, B, seed, step)
     S_ref = oracle.sample_uniform(N, B, seed, step)
     ref = oracle.induced_csr(N, g.rowptr.numpy(), g.colidx.numpy(), S_ref, val, norm_mode, rescale)
