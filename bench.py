@@ -107,7 +107,7 @@ def main():
         gq["ms"] += ms
         if name == "gemm_kernel":
             gq["flops"] += gemm_flops(tag) * calls
-        elif name == "spmm_rowsplit_kernel":
+        elif name == "spmm_main_kernel":
             d = int(tag.split("d=")[1])
             # compulsory traffic: CSR once, every input row once, the output once
             gq["bytes"] += calls * (8.0 * nnz_avg + 4.0 * (cfg.B + 1) + 2.0 * cfg.B * d * 4)

@@ -259,6 +259,210 @@ __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fast fp32 path: every 16-byte chunk of an operand is either wholly inside the matrix or wholly
+// outside (leading dimensions, pointers and the contiguous extents are multiples of four), so
+// the fetch is branch-free: rows past the edge are clamped to the last row (they only feed
+// results that are never stored) and the reduction tail is zeroed with selects.  LDS is double
+// buffered: one barrier per slice; the slice after next is fetched from memory while the
+// current one is multiplied.
+//
+// Operand staged reduction-contiguous ([R][BK+4]): tile i of the wavefront covers rows
+// w0 + 32 i + li, a lane reads eight consecutive reduction values with two 16-byte loads.
+// Operand staged [BK][R+4]: the T tiles of the wavefront are interleaved, tile i covers rows
+// w0 + T li + i, so one 4T-byte load gives a lane its value for all T tiles.
+// ---------------------------------------------------------------------------------------------
+template <int R, int BK, bool RC>
+__device__ __forceinline__ void fetch_fast(f32x4 *reg, const float *__restrict__ G, int64_t ld, int64_t row0,
+                                           int64_t rows_total, int64_t k0, int64_t k_end, int64_t k_total)
+{
+    using g = fetch_geom<R, BK, RC>;
+#pragma unroll
+    for (int v = 0; v < g::NV; ++v) {
+        const int idx = v * 256 + (int)threadIdx.x;
+        const int line = idx / g::CHUNKS_PER_LINE, ch = idx % g::CHUNKS_PER_LINE;
+        int64_t gr, gc;
+        bool valid;
+        if (RC) {
+            gr = min(row0 + line, rows_total - 1);
+            gc = k0 + 4 * ch;
+            valid = gc < k_end;
+            gc = min(gc, k_total - 4);
+        } else {
+            gr = k0 + line;
+            valid = gr < k_end;
+            gr = min(gr, k_total - 1);
+            gc = min(row0 + 4 * ch, rows_total - 4);
+        }
+        (void)valid;   // the reduction tail is zeroed by mask_fast when the slice is stored to LDS,
+                       // so that nothing here waits for the load
+        f32x4 x = {0.f, 0.f, 0.f, 0.f};
+        if (g::TOTAL % 256 == 0 || idx < g::TOTAL) x = *reinterpret_cast<const f32x4 *>(G + gr * ld + gc);
+        reg[v] = x;
+    }
+}
+
+// zero the chunks of a fetched slice that lie at or beyond the end of the reduction range
+template <int R, int BK, bool RC>
+__device__ __forceinline__ void mask_fast(f32x4 *reg, int64_t k0, int64_t k_end)
+{
+    using g = fetch_geom<R, BK, RC>;
+#pragma unroll
+    for (int v = 0; v < g::NV; ++v) {
+        const int idx = v * 256 + (int)threadIdx.x;
+        const int line = idx / g::CHUNKS_PER_LINE, ch = idx % g::CHUNKS_PER_LINE;
+        const bool valid = RC ? (k0 + 4 * ch < k_end) : (k0 + line < k_end);
+        if (!valid) reg[v] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+}
+
+template <int T> struct fvec;
+template <> struct fvec<1> { typedef float type; };
+template <> struct fvec<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct fvec<4> { typedef f32x4 type; };
+
+// One slice of BK reduction steps from LDS: 32x32x2 MFMAs over sixteen steps at a time.
+template <int BM, int BN, int WM, int WN, int BK, bool A_RC, bool B_RC>
+__device__ __forceinline__ void mma_slice(f32x16 (&acc)[WM / 32][WN / 32], const float *LA, const float *LB, int wm0, int wn0,
+                                          int li, int kh)
+{
+    constexpr int TM = WM / 32, TN = WN / 32;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+        float av[TM][8], bv[TN][8];
+        if constexpr (A_RC) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const float *p = LA + (wm0 + 32 * i + li) * (BK + 4) + kk + 8 * kh;
+                const f32x4 x0 = *reinterpret_cast<const f32x4 *>(p), x1 = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) { av[i][s] = x0[s]; av[i][4 + s] = x1[s]; }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const typename fvec<TM>::type x =
+                    *reinterpret_cast<const typename fvec<TM>::type *>(LA + (kk + 8 * kh + s) * (BM + 4) + wm0 + TM * li);
+                if constexpr (TM == 1) av[0][s] = x;
+                else {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) av[i][s] = x[i];
+                }
+            }
+        }
+        if constexpr (B_RC) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const float *p = LB + (wn0 + 32 * j + li) * (BK + 4) + kk + 8 * kh;
+                const f32x4 x0 = *reinterpret_cast<const f32x4 *>(p), x1 = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) { bv[j][s] = x0[s]; bv[j][4 + s] = x1[s]; }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const typename fvec<TN>::type x =
+                    *reinterpret_cast<const typename fvec<TN>::type *>(LB + (kk + 8 * kh + s) * (BN + 4) + wn0 + TN * li);
+                if constexpr (TN == 1) bv[0][s] = x;
+                else {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) bv[j][s] = x[j];
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][s], bv[j][s], acc[i][j], 0, 0, 0);
+    }
+}
+
+// Pipeline: slice s+2 is fetched from memory into registers while slice s is multiplied from LDS
+// buffer s & 1; the registers are stored to the other buffer after the multiply, so there is one
+// barrier per slice.
+template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+__global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
+{
+    constexpr int BK = 32;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int WAVES_N = BN / WN;
+    static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts per workgroup");
+    constexpr bool A_RC = !TA, B_RC = TB;
+    using gA = fetch_geom<BM, BK, A_RC>;
+    using gB = fetch_geom<BN, BK, B_RC>;
+    constexpr int LA_ELEMS = lds_geom<BM, BK, A_RC, false>::ELEMS;
+    constexpr int LB_ELEMS = lds_geom<BN, BK, B_RC, false>::ELEMS;
+    __shared__ __attribute__((aligned(16))) float ldsA[2][LA_ELEMS];
+    __shared__ __attribute__((aligned(16))) float ldsB[2][LB_ELEMS];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 31, kh = lane >> 5;
+    const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+    const int64_t m0 = (int64_t)blockIdx.x * BM, n0 = (int64_t)blockIdx.y * BN;
+    const int64_t kbeg = (int64_t)blockIdx.z * a.k_per_split;
+    const int64_t kend = min(a.K, kbeg + a.k_per_split);
+    const int nslices = (int)((kend - kbeg + BK - 1) / BK);
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    f32x4 ra[gA::NV], rb[gB::NV];
+    auto fetch = [&](int s) {
+        fetch_fast<BM, BK, A_RC>(ra, a.A, a.lda, m0, a.M, kbeg + (int64_t)s * BK, kend, a.K);
+        fetch_fast<BN, BK, B_RC>(rb, a.B, a.ldb, n0, a.N, kbeg + (int64_t)s * BK, kend, a.K);
+    };
+    auto stage = [&](int s) {
+        mask_fast<BM, BK, A_RC>(ra, kbeg + (int64_t)s * BK, kend);
+        mask_fast<BN, BK, B_RC>(rb, kbeg + (int64_t)s * BK, kend);
+        store_operand<BM, BK, A_RC, false>(ldsA[s & 1], ra);
+        store_operand<BN, BK, B_RC, false>(ldsB[s & 1], rb);
+    };
+    if (nslices > 0) {
+        fetch(0);
+        stage(0);
+        if (nslices > 1) fetch(1);
+    }
+    __syncthreads();
+    for (int it = 0; it < nslices; ++it) {
+        mma_slice<BM, BN, WM, WN, BK, A_RC, B_RC>(acc, ldsA[it & 1], ldsB[it & 1], wm0, wn0, li, kh);
+        if (it + 1 < nslices) {
+            // the other buffer was last read in iteration it-1, which every wave has left
+            stage(it + 1);
+            if (it + 2 < nslices) fetch(it + 2);
+        }
+        __syncthreads();
+    }
+
+    float *Cout = a.partial ? a.partial + (int64_t)blockIdx.z * a.M * a.N : a.C;
+    const int64_t ldc = a.partial ? a.N : a.ldc;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = n0 + wn0 + (B_RC ? 32 * j + li : TN * li + j);
+            if (col >= a.N) continue;
+            const float bj = (!a.partial && a.bias) ? a.bias[col] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rho = 8 * (r / 4) + 4 * kh + (r % 4);
+                const int64_t row = m0 + wm0 + (A_RC ? 32 * i + rho : TM * rho + i);
+                if (row < a.M) {
+                    float z = acc[i][j][r] + bj;
+                    if (!a.partial && a.relu) z = fmaxf(z, 0.f);
+                    Cout[row * ldc + col] = z;
+                }
+            }
+        }
+}
+
 // Sum of the split-K partial products in a fixed order (bit-reproducible).
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t MN,
                                                             int64_t N, float *__restrict__ C, int64_t ldc)
@@ -284,6 +488,17 @@ int launch_cfg(sgnn_ctx *ctx, int ta, int tb, int bf16, const gemm_args &a, int 
 {
     dim3 grid(cdiv(a.M, BM), cdiv(a.N, BN), splits), block(256);
     char tag[56];
+    // fast path: fp32, every 16-byte chunk wholly inside or outside the operands
+    const int64_t a_contig = ta ? a.M : a.K, b_contig = tb ? a.K : a.N;
+    const bool fast = !bf16 && a.alignedA && a.alignedB && a_contig % 4 == 0 && b_contig % 4 == 0 && a_contig >= 4 &&
+                      b_contig >= 4 && a.K >= 1 && a.M >= 1 && a.N >= 1;
+    if (fast) {
+        snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld f32", ta ? 'T' : 'N', tb ? 'T' : 'N', BM, BN, (long long)a.M,
+                 (long long)a.N, (long long)a.K);
+        if (!ta && !tb) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, false, false>), grid, block, 0, st, a); return SGNN_OK; }
+        if (!ta && tb) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, false, true>), grid, block, 0, st, a); return SGNN_OK; }
+        if (ta && !tb) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, true, false>), grid, block, 0, st, a); return SGNN_OK; }
+    }
     snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld %s", ta ? 'T' : 'N', tb ? 'T' : 'N', BM, BN, (long long)a.M,
              (long long)a.N, (long long)a.K, bf16 ? "bf16" : "f32");
 #define SGNN_GEMM_CASE(TA_, TB_, BF_)                                                                        \

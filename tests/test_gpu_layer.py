@@ -250,13 +250,17 @@ def test_softmax_xent_and_gather():
 def _run_config(name, steps, fuse_slice, bf16=None):
     cfg = si.CONFIGS[name]
     bf16 = cfg.bf16_mfma if bf16 is None else bf16
-    g = si.rmat_graph(cfg.N, cfg.undirected_edges, cfg.graph_seed)
-    X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed)
-    labels = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed)
+    # inputs are generated with torch on the GPU (integer parts are device independent) and copied
+    # to the host for the oracle
+    gd = si.rmat_graph(cfg.N, cfg.undirected_edges, cfg.graph_seed, device=DEV)
+    Xd = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=DEV)
+    ld = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=DEV)
     weights = si.layer_weights(cfg)
-    st = sg.GcnStep(cfg.N, g.rowptr.to(DEV), g.colidx.to(DEV), X.to(DEV), labels.to(DEV),
+    st = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld,
                     [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B, cfg.sampler_seed, bf16=bf16,
                     fuse_slice=fuse_slice, device=DEV)
+    g = si.Graph(cfg.N, gd.rowptr.cpu(), gd.colidx.cpu())
+    X, labels = Xd.cpu(), ld.cpu()
     wnp = [(W.double().numpy(), b.double().numpy()) for W, b in weights]
     tol = TOL_BF16 if bf16 else TOL_F32
     band = 1e-3 if bf16 else 1e-5
@@ -305,3 +309,13 @@ def test_whole_step_tiny_bf16():
 
 def test_whole_step_medium():
     _run_config("medium", [0, 15], True)
+
+
+def test_whole_step_large_bf16():
+    # co-purchase-shaped graph at full size: 2.4 M vertices, 124 M stored entries, |S| = 262144
+    _run_config("large", [0], True)
+
+
+def test_whole_step_dense():
+    # social-shaped graph at full size: mean degree about 490, |S| = 65536, 602 input features
+    _run_config("dense", [0], True)
