@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--no-fuse-slice", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = pick by config)")
     ap.add_argument("--breakdown", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 256 MiB copy kernel five times (reference point for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -131,6 +133,14 @@ def main():
         achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9 if dom["bytes"] > 0 else 0.0
         roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    # HBM bytes per launch of that kernel from the committed counter summary (rocprofv3 --pmc
+    # FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size), when it covers this workload
+    tpath = os.path.join(ROOT, "profiles", "step_%s_hbm_traffic.txt" % cfg.name)
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            w = line.split()
+            if len(w) == 3 and w[0] == "traffic" and w[1] == dom_name:
+                roofline["traffic"] = float(w[2])
     roofline["kernel"] = dom_name
     roofline["avg_launch_us"] = 1e3 * dom["ms"] / dom["calls"]
     roofline["launches_per_step"] = dom["calls"] / nprof
@@ -147,6 +157,13 @@ def main():
                    "kernel_time_us_per_step": 1e3 * total_ms / nprof},
         "roofline": roofline,
     }
+
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            sg.sgnn_copy_f32(st.ctx, src, dst)
+        torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
         import oracle

@@ -226,6 +226,13 @@ int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int
               const float *A, int64_t lda, const float *B, int64_t ldb, const float *bias,
               int flags, float *C, int64_t ldc, sgnn_stream stream);
 
+/*
+ * dst[0..n) = src[0..n) (fp32, 16-byte aligned, n a multiple of 4): a plain streaming copy of known
+ * size, the reference point against which hardware traffic counters of the other kernels are
+ * scaled in the benchmark.
+ */
+int sgnn_copy_f32(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, sgnn_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -81,11 +81,12 @@ def lib():
                                    C.POINTER(_Mat), ci, C.POINTER(_Mat), vp, vp, vp]
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), vp]
+        L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
                      "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd",
-                     "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm"):
+                     "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm", "sgnn_copy_f32"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -297,3 +298,8 @@ def sgnn_gemm(ctx: Context, trans_a: bool, trans_b: bool, A: torch.Tensor, B: to
     ctx.check(lib().sgnn_gemm(ctx._h, int(trans_a), int(trans_b), M, N, K, _ptr(A, torch.float32, "A"), A.stride(0),
                               _ptr(B, torch.float32, "B"), B.stride(0), _ptr(bias, torch.float32, "bias"), flags,
                               _ptr(Cm, torch.float32, "C"), Cm.stride(0), _stream(stream)))
+
+
+def sgnn_copy_f32(ctx: Context, src: torch.Tensor, dst: torch.Tensor, stream=None):
+    ctx.check(lib().sgnn_copy_f32(ctx._h, _ptr(src, torch.float32, "src"), _ptr(dst, torch.float32, "dst"), src.numel(),
+                                  _stream(stream)))

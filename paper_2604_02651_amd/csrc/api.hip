@@ -372,6 +372,17 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     return SGNN_OK;
 }
 
+int sgnn_copy_f32(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!src || !dst || n < 0 || n % 4 != 0 || ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_copy_f32: need 16-byte aligned pointers and n a multiple of 4");
+    if (n == 0) return SGNN_OK;
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return sgnn_launch_copy(ctx, src, dst, n, static_cast<hipStream_t>(stream));
+}
+
 int sgnn_softmax_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C,
                       float *loss_dev, float *dO, int64_t lddo, sgnn_stream stream)
 {

@@ -1,5 +1,7 @@
 // Memory-bound helpers around the two big operators: the feature / label slice (Eq. 26), the
 // element-wise part of the layer backward (ReLU mask and bias gradient), and the harness loss.
+#include <algorithm>
+
 #include "block_prims.h"
 #include "common.h"
 
@@ -168,7 +170,20 @@ __global__ __launch_bounds__(1024) void xent_final_kernel(const float *__restric
     if (threadIdx.x == 0) *loss = s * invB;
 }
 
+// plain copy, 16 bytes a lane: the reference point for bandwidth counters
+__global__ __launch_bounds__(256) void copy_f32_kernel(const f32x4 *__restrict__ src, f32x4 *__restrict__ dst, int64_t n4)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 } // namespace
+
+int sgnn_launch_copy(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, hipStream_t st)
+{
+    SGNN_LAUNCH(ctx, st, "copy_f32_kernel", SGNN_TAG, copy_f32_kernel, dim3((unsigned)std::min<int64_t>((n / 4 + 255) / 256, 16384)),
+                dim3(256), 0, st, reinterpret_cast<const f32x4 *>(src), reinterpret_cast<f32x4 *>(dst), n / 4);
+    return SGNN_OK;
+}
 
 int sgnn_launch_gather(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, const int32_t *S, uint32_t B, float *out,
                        int64_t ldo, const int32_t *labels, int32_t *labels_out, hipStream_t st)
