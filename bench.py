@@ -32,7 +32,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=160)
     ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--config", default="medium", help="tiny | medium | large | dense (medium is the headline workload)")
+    ap.add_argument("--config", default="medium", help="tiny | medium | large | dense | xlarge (medium is the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fuse-slice", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = pick by config)")
@@ -66,7 +66,7 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     cfg = si.CONFIGS[args.config]
-    g = si.rmat_graph(cfg.N, cfg.undirected_edges, cfg.graph_seed, device=dev)
+    g = si.config_graph(cfg, device=dev)
     X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=dev)
     labels = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=dev)
     weights = si.layer_weights(cfg, device=dev)
@@ -170,7 +170,7 @@ def main():
         rp, ci = g.rowptr.cpu().numpy(), g.colidx.cpu().numpy()
         Xh, lh = X.cpu().numpy(), labels.cpu().numpy()
         wnp = [(W.double().cpu().numpy(), b.double().cpu().numpy()) for W, b in weights]
-        nsteps = args.cpu_steps or {"tiny": 50, "medium": 3}.get(cfg.name, 1)
+        nsteps = args.cpu_steps or {"tiny": 50, "medium": 8}.get(cfg.name, 1)
         oracle.gcn_step(cfg.N, rp, ci, Xh, lh, wnp, min(cfg.B, 1024), cfg.sampler_seed, 0, bf16=cfg.bf16_mfma)  # warm-up
         c0 = time.perf_counter()
         for t in range(nsteps):

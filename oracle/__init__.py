@@ -220,9 +220,20 @@ def gcn_step(N, rowptr, colidx, X, labels, weights, B, seed, step, bf16=False, n
     layer l takes its value instead of the oracle's own Z > 0.  The forward values never change."""
     S = sample_uniform(N, B, seed, step)
     rpS, ciS, vS = induced_csr(N, rowptr, colidx, S, None, norm_mode, rescale)
-    rpT, ciT, vT = csr_transpose(B, B, rpS, ciS, vS)
     H = gather_rows(X, S)
     yS = gather_labels(labels, S)
+    out = layers_step(rpS, ciS, vS, H, yS, weights, bf16=bf16, relu_ties=relu_ties, tie_band=tie_band)
+    out["S"] = S
+    return out
+
+
+def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie_band=0.0):
+    """The layer part of a step on an already extracted mini-batch: L layers forward, mean
+    cross-entropy, L layers backward (see gcn_step for relu_ties / tie_band)."""
+    B = len(rpS) - 1
+    H = np.ascontiguousarray(X_S, np.float64)
+    yS = np.ascontiguousarray(y_S, np.int32)
+    rpT, ciT, vT = csr_transpose(B, B, rpS, ciS, vS)
     L = len(weights)
     Ts, Hs, masks, bands = [], [H], [], []
     for l, (W, b) in enumerate(weights):
@@ -243,5 +254,5 @@ def gcn_step(N, rowptr, colidx, X, labels, weights, B, seed, step, bf16=False, n
         dH, dW, db = gcn_bwd(rpT, ciT, vT, Ts[l], W, Ymask, dY, relu=relu, bf16=bf16, need_dH=(l > 0))
         dWs[l], dbs[l], dHs[l] = dW, db, dH
         dY = dH
-    return dict(S=S, rowptr=rpS, colidx=ciS, val=vS, X_S=H, y_S=yS, T=Ts, H=Hs, loss=loss, dW=dWs, db=dbs, dH=dHs,
+    return dict(rowptr=rpS, colidx=ciS, val=vS, X_S=H, y_S=yS, T=Ts, H=Hs, loss=loss, dW=dWs, db=dbs, dH=dHs,
                 relu_band=bands, relu_mask=masks)

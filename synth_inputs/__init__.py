@@ -148,6 +148,75 @@ def rmat_graph(N: int, undirected_edges: int, seed: int = 1234, device="cpu",
     return Graph(N=N, rowptr=rowptr, colidx=colidx)
 
 
+def rmat_graph_bucketed(N: int, undirected_edges: int, seed: int = 1234, device="cpu",
+                        abcd=(0.57, 0.19, 0.19, 0.05), permute: bool = True, chunk: int = 1 << 27,
+                        buckets: int = 64, oversample: float = 1.0) -> Graph:
+    """R-MAT graph for sizes at which one global sort of all directed edges is impractical
+    (billions of entries).  Same generator and rejection rules as rmat_graph, but the number of
+    DRAWS is fixed (undirected_edges * oversample accepted draws) instead of the number of distinct
+    edges, so the distinct count comes out slightly below the target (duplicates are merged); the
+    actual count is Graph.E.  Directed keys are sorted per chunk, split into `buckets` row ranges,
+    and every bucket is merged and deduplicated on its own.
+    """
+    device = torch.device(device)
+    scale = max(1, math.ceil(math.log2(max(N, 2))))
+    want = int(undirected_edges * oversample)
+    perm = None
+    if permute:
+        perm = torch.argsort(mix64(torch.arange(N, dtype=torch.int64, device=device), seed + 104729))
+    rows_per_bucket = (N + buckets - 1) // buckets
+    bounds = torch.arange(0, buckets + 1, dtype=torch.int64, device=device) * rows_per_bucket * N
+    parts = [[] for _ in range(buckets)]
+    accepted, drawn = 0, 0
+    while accepted < want:
+        u, v = _rmat_edges(drawn, chunk, scale, seed, abcd, device)
+        drawn += chunk
+        ok = (u < N) & (v < N) & (u != v)
+        u, v = u[ok], v[ok]
+        del ok
+        if accepted + int(u.numel()) > want:
+            keep = want - accepted
+            u, v = u[:keep], v[:keep]
+        accepted += int(u.numel())
+        if perm is not None:
+            u, v = perm[u], perm[v]
+        keys = torch.cat([u * N + v, v * N + u])
+        del u, v
+        keys, _ = torch.sort(keys)
+        cut = torch.searchsorted(keys, bounds).tolist()
+        for b in range(buckets):
+            if cut[b + 1] > cut[b]:
+                parts[b].append(keys[cut[b]:cut[b + 1]].clone())
+        del keys
+    del perm
+    counts = torch.zeros(N, dtype=torch.int64, device=device)
+    cols = []
+    for b in range(buckets):
+        r0, r1 = b * rows_per_bucket, min(N, (b + 1) * rows_per_bucket)
+        if r0 >= r1:
+            continue
+        loops = torch.arange(r0, r1, dtype=torch.int64, device=device)
+        k = torch.unique(torch.cat(parts[b] + [loops * N + loops]))
+        parts[b] = None
+        rows = k // N
+        cols.append((k - rows * N).to(torch.int32))
+        counts[r0:r1] = torch.bincount(rows - r0, minlength=r1 - r0)
+        del k, rows, loops
+    colidx = torch.cat(cols)
+    del cols
+    rowptr = torch.zeros(N + 1, dtype=torch.int64, device=device)
+    rowptr[1:] = torch.cumsum(counts, 0)
+    return Graph(N=N, rowptr=rowptr, colidx=colidx)
+
+
+def config_graph(cfg: "Config", device="cpu") -> Graph:
+    """The graph of a workload configuration (the largest one through the bucketed generator)."""
+    if cfg.undirected_edges > (1 << 28):
+        # 1.0149 accepted draws per target edge: about 1.5 % of the draws repeat an earlier edge
+        return rmat_graph_bucketed(cfg.N, cfg.undirected_edges, cfg.graph_seed, device=device, oversample=1.0149)
+    return rmat_graph(cfg.N, cfg.undirected_edges, cfg.graph_seed, device=device)
+
+
 def graph_from_edges(N: int, edges: List[Tuple[int, int]], device="cpu") -> Graph:
     """Canonical CSR of A + I from an explicit undirected edge list (for hand-made test graphs)."""
     pairs = set()
@@ -194,6 +263,11 @@ def normal_features(N: int, d: int, seed: int = 1, device="cpu", dtype=torch.flo
 def uniform_labels(N: int, classes: int, seed: int = 2, device="cpu") -> torch.Tensor:
     idx = torch.arange(N, dtype=torch.int64, device=device)
     return (uniform_bits(idx, seed, 31) % classes).to(torch.int32)
+
+
+def labels_for(rows: torch.Tensor, classes: int, seed: int = 2) -> torch.Tensor:
+    """Labels of the given vertex ids (the same values as uniform_labels(N, ...)[rows])."""
+    return (uniform_bits(rows.to(torch.int64), seed, 31) % classes).to(torch.int32)
 
 
 def glorot_uniform(fan_in: int, fan_out: int, seed: int = 3, device="cpu") -> torch.Tensor:

@@ -319,3 +319,50 @@ def test_whole_step_large_bf16():
 def test_whole_step_dense():
     # social-shaped graph at full size: mean degree about 490, |S| = 65536, 602 input features
     _run_config("dense", [0], True)
+
+
+def test_whole_step_xlarge_bf16():
+    """Citation-shaped graph at full size: 111 M vertices, 3.3 G stored entries, |S| = 2^20, bf16 GEMM
+    operands.  The oracle never sees the whole feature matrix: feature rows and labels are a function
+    of (seed, vertex), so it regenerates the sampled rows on the host."""
+    if torch.cuda.get_device_properties(0).total_memory < 200e9:
+        pytest.skip("needs the 288 GB of an MI355X")
+    cfg = si.CONFIGS["xlarge"]
+    gd = si.config_graph(cfg, device=DEV)
+    assert abs((gd.E - cfg.N) / 2 / cfg.undirected_edges - 1.0) < 0.01
+    Xd = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=DEV)
+    ld = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=DEV)
+    weights = si.layer_weights(cfg)
+    st = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B,
+                    cfg.sampler_seed, bf16=True, fuse_slice=True, device=DEV)
+    st.step(0)
+    torch.cuda.synchronize()
+    st.ctx.status()
+    # oracle side
+    S = oracle.sample_uniform(cfg.N, cfg.B, cfg.sampler_seed, 0)
+    assert np.array_equal(st.S.cpu().numpy(), S)
+    rp, ci = gd.rowptr.cpu().numpy(), gd.colidx.cpu().numpy()
+    rpS, ciS, vS = oracle.induced_csr(cfg.N, rp, ci, S)
+    del rp, ci
+    nnz = st.A.nnz()
+    assert nnz == len(ciS) and np.array_equal(st.A.rowptr.cpu().numpy(), rpS)
+    assert np.array_equal(st.A.colidx.cpu().numpy()[:nnz], ciS)
+    got_val = st.A.val.cpu().numpy()[:nnz].astype(np.float64)
+    assert np.all(np.abs(got_val - vS) <= 1e-6 * np.abs(vS))
+    St = torch.as_tensor(S.astype(np.int64))
+    X_S = si.normal_rows(St, cfg.d_in, cfg.feature_seed).numpy()
+    y_S = si.labels_for(St, cfg.classes, cfg.label_seed).numpy()
+    assert np.array_equal(st.y_S.cpu().numpy(), y_S)
+    wnp = [(W.double().numpy(), b.double().numpy()) for W, b in weights]
+    ref = oracle.layers_step(rpS, ciS, vS, X_S, y_S, wnp, bf16=True, tie_band=1e-3)
+    ties = [st.H[l].cpu().numpy() > 0 for l in range(cfg.layers)]
+    for l in range(cfg.layers - 1):
+        assert np.array_equal(ties[l][~ref["relu_band"][l]], ref["relu_mask"][l][~ref["relu_band"][l]])
+    if any((ties[l] != ref["relu_mask"][l]).any() for l in range(cfg.layers - 1)):
+        ref = oracle.layers_step(rpS, ciS, vS, X_S, y_S, wnp, bf16=True, tie_band=1e-3, relu_ties=ties)
+    for l in range(cfg.layers):
+        assert rel_err(st.T[l].cpu().numpy(), ref["T"][l]) < TOL_BF16, ("T", l)
+        assert rel_err(st.H[l].cpu().numpy(), ref["H"][l + 1]) < TOL_BF16, ("H", l)
+        assert rel_err(st.dW[l].cpu().numpy(), ref["dW"][l]) < TOL_BF16, ("dW", l)
+        assert rel_err(st.db[l].cpu().numpy(), ref["db"][l]) < TOL_BF16, ("db", l)
+    assert abs(st.loss.item() - ref["loss"]) < TOL_BF16 * abs(ref["loss"])
