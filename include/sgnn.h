@@ -45,7 +45,9 @@ enum { SGNN_F32 = 0, SGNN_BF16 = 1 };
 /* layer flags */
 enum {
     SGNN_RELU = 1,      /* Y = max(Z, 0) (Eq. 8); backward masks dY where Y <= 0                    */
-    SGNN_BF16_MFMA = 2  /* round both GEMM operands to bfloat16 (nearest even), accumulate in fp32  */
+    SGNN_BF16_MFMA = 2, /* round both GEMM operands to bfloat16 (nearest even), accumulate in fp32  */
+    SGNN_XFORM_FIRST = 4 /* evaluate A (H W) instead of (A H) W: the same result up to rounding, with
+                            the sparse product at width d_out; worth it when d_out < d_in           */
 };
 
 typedef struct sgnn_ctx sgnn_ctx;
@@ -185,7 +187,8 @@ int sgnn_gather_rows(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, cons
  *   W     d_in x d_out fp32;  bias fp32[d_out] or NULL
  *   flags SGNN_RELU, SGNN_BF16_MFMA
  *   Y     out B x d_out fp32
- *   T     out B x d_in fp32, the aggregate, kept by the caller for the backward pass
+ *   T     out B x d_in fp32, the aggregate, kept by the caller for the backward pass; unused (may be
+ *         NULL) with SGNN_XFORM_FIRST, where the backward pass needs the layer input H instead
  */
 int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn_mat *W,
                  const float *bias, int flags, sgnn_mat *Y, sgnn_mat *T, sgnn_stream stream);
@@ -195,6 +198,9 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
  * dbias = column sums of dZ, dW = T^T dZ, dT = dZ W^T, dH = A_T dT.
  *   A_T   the transpose of the forward matrix as CSR (the same object when it is symmetric)
  *   T, W, Y   as in the forward call;  dY  B x d_out fp32
+ *             with SGNN_XFORM_FIRST (same flag as in the forward call) T is the layer INPUT H
+ *             (B x d_in, row_index honoured) and the products are dP = A_T dZ, dW = H^T dP,
+ *             dH = dP W^T
  *   dH    out B x d_in fp32, or NULL to skip it (first layer)
  *   dW    out fp32[d_in x d_out] row-major, overwritten;  dbias out fp32[d_out] or NULL
  * The reduction over the B rows in dW and dbias uses a fixed split and a fixed summation order:

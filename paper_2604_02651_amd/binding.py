@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(_HERE, "libsgnn.so")
 
 SGNN_RELU = 1
 SGNN_BF16_MFMA = 2
+SGNN_XFORM_FIRST = 4
 SGNN_F32 = 0
 
 _ERR_NAMES = {-1: "SGNN_ERR_INVALID_ARG", -2: "SGNN_ERR_CAPACITY", -3: "SGNN_ERR_UNSUPPORTED", -4: "SGNN_ERR_HIP",
@@ -256,17 +257,20 @@ def sgnn_gather_rows(ctx: Context, X: Optional[torch.Tensor], S: torch.Tensor, B
 
 
 def sgnn_gcn_fwd(ctx: Context, A: Csr, H: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], flags: int,
-                 Y: torch.Tensor, T: torch.Tensor, row_index: Optional[torch.Tensor] = None, stream=None):
+                 Y: torch.Tensor, T: Optional[torch.Tensor], row_index: Optional[torch.Tensor] = None, stream=None):
     a = A.struct()
-    h, w, y, t = _mat(H, row_index, "H"), _mat(W, None, "W"), _mat(Y, None, "Y"), _mat(T, None, "T")
+    h, w, y = _mat(H, row_index, "H"), _mat(W, None, "W"), _mat(Y, None, "Y")
+    t = _mat(T, None, "T") if T is not None else None
     ctx.check(lib().sgnn_gcn_fwd(ctx._h, C.byref(a), C.byref(h), C.byref(w), _ptr(bias, torch.float32, "bias"), flags,
-                                 C.byref(y), C.byref(t), _stream(stream)))
+                                 C.byref(y), C.byref(t) if t is not None else None, _stream(stream)))
 
 
 def sgnn_gcn_bwd(ctx: Context, A_T: Csr, T: torch.Tensor, W: torch.Tensor, Y: Optional[torch.Tensor], dY: torch.Tensor,
-                 flags: int, dH: Optional[torch.Tensor], dW: torch.Tensor, dbias: Optional[torch.Tensor], stream=None):
+                 flags: int, dH: Optional[torch.Tensor], dW: torch.Tensor, dbias: Optional[torch.Tensor],
+                 row_index: Optional[torch.Tensor] = None, stream=None):
+    """T is the saved aggregate, or with SGNN_XFORM_FIRST the layer input (row_index honoured)."""
     a = A_T.struct()
-    t, w, dy = _mat(T, None, "T"), _mat(W, None, "W"), _mat(dY, None, "dY")
+    t, w, dy = _mat(T, row_index, "T"), _mat(W, None, "W"), _mat(dY, None, "dY")
     y = _mat(Y, None, "Y") if Y is not None else None
     dh = _mat(dH, None, "dH") if dH is not None else None
     if dW.shape != W.shape or not dW.is_contiguous():

@@ -282,7 +282,7 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, sgnn_mat *out
     if (rc) return rc;
     ws_alloc ws(ctx);
     return sgnn_launch_spmm(ctx, A, static_cast<const float *>(X->ptr), X->ld, X->row_index, X->cols,
-                            static_cast<float *>(out->ptr), out->ld, &ws, static_cast<hipStream_t>(stream));
+                            static_cast<float *>(out->ptr), out->ld, nullptr, 0, &ws, static_cast<hipStream_t>(stream));
 }
 
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
@@ -296,7 +296,7 @@ int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_gemm(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, B, ldb, bias, flags, C, ldc, &ws,
+    return sgnn_launch_gemm(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, nullptr, B, ldb, bias, flags, C, ldc, &ws,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -304,22 +304,37 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
                  sgnn_mat *Y, sgnn_mat *T, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
-    if (!csr_ok(A) || !mat_ok(H) || !mat_ok(W) || !mat_ok(Y) || !mat_ok(T))
+    const bool xform_first = (flags & SGNN_XFORM_FIRST) != 0;
+    if (!csr_ok(A) || !mat_ok(H) || !mat_ok(W) || !mat_ok(Y) || (!xform_first && !mat_ok(T)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_fwd: bad argument");
     const int64_t Bn = A->rows, d_in = W->rows, d_out = W->cols;
-    if (H->cols != d_in || T->rows != Bn || T->cols != d_in || Y->rows != Bn || Y->cols != d_out ||
-        (!H->row_index && H->rows != A->cols) || W->row_index || Y->row_index || T->row_index)
+    if (H->cols != d_in || Y->rows != Bn || Y->cols != d_out || (!H->row_index && H->rows != A->cols) ||
+        (H->row_index && H->rows != A->cols) || W->row_index || Y->row_index ||
+        (!xform_first && (T->rows != Bn || T->cols != d_in || T->row_index)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_fwd: shape mismatch");
     int rc = bind_device(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     ws_alloc ws(ctx);
-    rc = sgnn_launch_spmm(ctx, A, static_cast<const float *>(H->ptr), H->ld, H->row_index, d_in,
-                          static_cast<float *>(T->ptr), T->ld, &ws, st);
+    const int gflags = flags & (SGNN_RELU | SGNN_BF16_MFMA);
+    if (!xform_first) {
+        // Eqs. 5-6 in the paper's order: aggregate, then transform with bias and activation fused
+        rc = sgnn_launch_spmm(ctx, A, static_cast<const float *>(H->ptr), H->ld, H->row_index, d_in,
+                              static_cast<float *>(T->ptr), T->ld, nullptr, 0, &ws, st);
+        if (rc) return rc;
+        return sgnn_launch_gemm(ctx, 0, 0, Bn, d_out, d_in, static_cast<const float *>(T->ptr), T->ld, nullptr,
+                                static_cast<const float *>(W->ptr), W->ld, bias, gflags, static_cast<float *>(Y->ptr), Y->ld,
+                                &ws, st);
+    }
+    // A (H W): transform first (the aggregation then runs at width d_out), bias and activation
+    // fused into the sparse product
+    float *P = ws.get<float>((size_t)A->cols * d_out);
+    if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_fwd: scratch too small: call sgnn_ctx_reserve");
+    rc = sgnn_launch_gemm(ctx, 0, 0, A->cols, d_out, d_in, static_cast<const float *>(H->ptr), H->ld, H->row_index,
+                          static_cast<const float *>(W->ptr), W->ld, nullptr, flags & SGNN_BF16_MFMA, P, d_out, &ws, st);
     if (rc) return rc;
-    return sgnn_launch_gemm(ctx, 0, 0, Bn, d_out, d_in, static_cast<const float *>(T->ptr), T->ld,
-                            static_cast<const float *>(W->ptr), W->ld, bias, flags & (SGNN_RELU | SGNN_BF16_MFMA),
-                            static_cast<float *>(Y->ptr), Y->ld, &ws, st);
+    return sgnn_launch_spmm(ctx, A, P, d_out, nullptr, d_out, static_cast<float *>(Y->ptr), Y->ld, bias,
+                            (flags & SGNN_RELU) ? 1 : 0, &ws, st);
 }
 
 int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sgnn_mat *W, const sgnn_mat *Y,
@@ -329,10 +344,12 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     if (!csr_ok(A_T) || !mat_ok(T) || !mat_ok(W) || !mat_ok(dY) || !dW || (dH && !mat_ok(dH)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: bad argument");
     const int relu = (flags & SGNN_RELU) ? 1 : 0;
+    const bool xform_first = (flags & SGNN_XFORM_FIRST) != 0;
     if (relu && !mat_ok(Y)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: SGNN_RELU needs Y");
     const int64_t Bn = T->rows, d_in = W->rows, d_out = W->cols;
     if (T->cols != d_in || dY->rows != Bn || dY->cols != d_out || (relu && (Y->rows != Bn || Y->cols != d_out)) ||
-        (dH && (dH->rows != A_T->rows || dH->cols != d_in || A_T->cols != Bn)))
+        (dH && (dH->rows != A_T->rows || dH->cols != d_in || A_T->cols != Bn)) || (!xform_first && T->row_index) ||
+        (xform_first && (A_T->rows != Bn || A_T->cols != Bn)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: shape mismatch");
     int rc = bind_device(ctx);
     if (rc) return rc;
@@ -355,21 +372,36 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
         if (rc) return rc;
         if (relu) { dZ = dZbuf; lddz = d_out; }
     }
-    // dW = T^T dZ
-    rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, dZ, lddz, nullptr, mfma,
-                          dW, d_out, &ws, st);
-    if (rc) return rc;
-    if (dH) {
-        // dT = dZ W^T, dH = A^T dT
-        float *dT = ws.get<float>((size_t)Bn * d_in);
-        if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
-        rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, static_cast<const float *>(W->ptr), W->ld, nullptr,
-                              mfma, dT, d_in, &ws, st);
+    if (!xform_first) {
+        // dW = T^T dZ
+        rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, nullptr, dZ, lddz,
+                              nullptr, mfma, dW, d_out, &ws, st);
         if (rc) return rc;
-        rc = sgnn_launch_spmm(ctx, A_T, dT, d_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, &ws, st);
-        if (rc) return rc;
+        if (dH) {
+            // dT = dZ W^T, dH = A^T dT
+            float *dT = ws.get<float>((size_t)Bn * d_in);
+            if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
+            rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, nullptr, static_cast<const float *>(W->ptr), W->ld,
+                                  nullptr, mfma, dT, d_in, &ws, st);
+            if (rc) return rc;
+            rc = sgnn_launch_spmm(ctx, A_T, dT, d_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, &ws,
+                                  st);
+            if (rc) return rc;
+        }
+        return SGNN_OK;
     }
-    return SGNN_OK;
+    // transform-first layer: dP = A^T dZ (width d_out), dW = H^T dP, dH = dP W^T; T is the layer input H
+    float *dP = ws.get<float>((size_t)Bn * d_out);
+    if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
+    rc = sgnn_launch_spmm(ctx, A_T, dZ, lddz, nullptr, d_out, dP, d_out, nullptr, 0, &ws, st);
+    if (rc) return rc;
+    rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, T->row_index, dP, d_out,
+                          nullptr, mfma, dW, d_out, &ws, st);
+    if (rc) return rc;
+    if (dH)
+        rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dP, d_out, nullptr, static_cast<const float *>(W->ptr), W->ld,
+                              nullptr, mfma, static_cast<float *>(dH->ptr), dH->ld, &ws, st);
+    return rc;
 }
 
 int sgnn_copy_f32(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, sgnn_stream stream)

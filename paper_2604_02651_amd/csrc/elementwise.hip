@@ -122,8 +122,9 @@ __global__ __launch_bounds__(1024) void colsum_final_kernel(const float *__restr
     }
 }
 
-// A group of lpr lanes (a power of two >= C, at most 64) owns a row; a workgroup covers
-// 4 * 256 / lpr rows and writes one partial loss.
+// A group of lpr lanes (a power of two >= C, at most 64) owns a row and keeps it in registers
+// (NX values a lane: C <= 64 * NX); a workgroup covers 4 * 256 / lpr rows and writes one partial loss.
+template <int NX>
 __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, int64_t ldo,
                                                    const int32_t *__restrict__ labels, uint32_t B, uint32_t C,
                                                    int lpr_log2, float *__restrict__ dO, int64_t lddo,
@@ -139,19 +140,30 @@ __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, 
         const uint32_t row = (blockIdx.x * 4 + q) * rows_per_pass + gq;
         const bool live = row < B;
         const float *o = O + (int64_t)(live ? row : 0) * ldo;
+        float x[NX];
         float m = -INFINITY;
-        if (live) for (uint32_t j = g; j < C; j += lpr) m = fmaxf(m, o[j]);
+#pragma unroll
+        for (int t = 0; t < NX; ++t) {
+            const uint32_t j = g + t * lpr;
+            x[t] = (live && j < C) ? o[j] : -INFINITY;
+            m = fmaxf(m, x[t]);
+        }
         for (int s = lpr >> 1; s > 0; s >>= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
         float sum = 0.f;
-        if (live) for (uint32_t j = g; j < C; j += lpr) sum += expf(o[j] - m);
+#pragma unroll
+        for (int t = 0; t < NX; ++t) sum += (x[t] == -INFINITY) ? 0.f : expf(x[t] - m);
         for (int s = lpr >> 1; s > 0; s >>= 1) sum += __shfl_xor(sum, s, 64);
         if (live) {
             const float lse = m + logf(sum);
             const int32_t y = labels[row];
             if (g == 0) loss += lse - ((uint32_t)y < C ? o[y] : 0.f);
-            if (dO)
-                for (uint32_t j = g; j < C; j += lpr)
-                    dO[(int64_t)row * lddo + j] = (expf(o[j] - lse) - ((int32_t)j == y ? 1.f : 0.f)) * invB;
+            if (dO) {
+#pragma unroll
+                for (int t = 0; t < NX; ++t) {
+                    const uint32_t j = g + t * lpr;
+                    if (j < C) dO[(int64_t)row * lddo + j] = (expf(x[t] - lse) - ((int32_t)j == y ? 1.f : 0.f)) * invB;
+                }
+            }
         }
     }
     loss = wave_sum(loss);
@@ -240,7 +252,15 @@ int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *
     const unsigned nwg = cdiv(B, rows_per_wg);
     float *partial = ws->get<float>(nwg);
     if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_softmax_xent: scratch too small: call sgnn_ctx_reserve");
-    SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial);
+    const unsigned nx = (C + (1u << lpr_log2) - 1) >> lpr_log2;
+    if (nx <= 1)
+        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<1>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial);
+    else if (nx <= 4)
+        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<4>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial);
+    else if (nx <= 16)
+        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<16>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial);
+    else
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_softmax_xent: more than 1024 classes are not supported");
     if (loss) {
         SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, 1.f / (float)B, loss);
     }

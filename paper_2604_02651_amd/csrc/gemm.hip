@@ -32,6 +32,7 @@ typedef unsigned short u16;
 struct gemm_args {
     int64_t M, N, K;          // C is M x N, reduction length K
     const float *A; int64_t lda;
+    const int32_t *a_row_index;   // optional gather of the rows of A as stored in memory
     const float *B; int64_t ldb;
     const float *bias;
     float *C; int64_t ldc;
@@ -64,7 +65,7 @@ template <int R, int BK, bool RED_CONTIG> struct fetch_geom {
 template <int R, int BK, bool RED_CONTIG>
 __device__ __forceinline__ void fetch_operand(f32x4 *reg, const float *__restrict__ G,
                                               int64_t ld, int64_t row0, int64_t rows_total, int64_t k0, int64_t k_end,
-                                              int aligned)
+                                              int aligned, const int32_t *__restrict__ ridx = nullptr)
 {
     using g = fetch_geom<R, BK, RED_CONTIG>;
 #pragma unroll
@@ -78,6 +79,7 @@ __device__ __forceinline__ void fetch_operand(f32x4 *reg, const float *__restric
             if (RED_CONTIG) { gr = row0 + line; gc = k0 + 4 * ch; lim = k_end; line_ok = gr < rows_total; }
             else            { gr = k0 + line;  gc = row0 + 4 * ch; lim = rows_total; line_ok = gr < k_end; }
             if (line_ok) {
+                if (ridx) gr = ridx[gr];
                 const float *p = G + gr * ld + gc;
                 if (aligned && gc + 4 <= lim) x = *reinterpret_cast<const f32x4 *>(p);
                 else {
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
 
     f32x4 ra[gA::NV], rb[gB::NV];
     if (kbeg < kend) {
-        fetch_operand<BM, BK, A_RC>(ra, a.A, a.lda, m0, a.M, kbeg, kend, a.alignedA);
+        fetch_operand<BM, BK, A_RC>(ra, a.A, a.lda, m0, a.M, kbeg, kend, a.alignedA, a.a_row_index);
         fetch_operand<BN, BK, B_RC>(rb, a.B, a.ldb, n0, a.N, kbeg, kend, a.alignedB);
     }
     for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
         store_operand<BN, BK, B_RC, BF16>(ldsB, rb);
         __syncthreads();
         if (k0 + BK < kend) {
-            fetch_operand<BM, BK, A_RC>(ra, a.A, a.lda, m0, a.M, k0 + BK, kend, a.alignedA);
+            fetch_operand<BM, BK, A_RC>(ra, a.A, a.lda, m0, a.M, k0 + BK, kend, a.alignedA, a.a_row_index);
             fetch_operand<BN, BK, B_RC>(rb, a.B, a.ldb, n0, a.N, k0 + BK, kend, a.alignedB);
         }
         if constexpr (!BF16) {
@@ -274,7 +276,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
 // ---------------------------------------------------------------------------------------------
 template <int R, int BK, bool RC>
 __device__ __forceinline__ void fetch_fast(f32x4 *reg, const float *__restrict__ G, int64_t ld, int64_t row0,
-                                           int64_t rows_total, int64_t k0, int64_t k_end, int64_t k_total)
+                                           int64_t rows_total, int64_t k0, int64_t k_end, int64_t k_total,
+                                           const int32_t *__restrict__ ridx = nullptr)
 {
     using g = fetch_geom<R, BK, RC>;
 #pragma unroll
@@ -294,6 +297,7 @@ __device__ __forceinline__ void fetch_fast(f32x4 *reg, const float *__restrict__
             gr = min(gr, k_total - 1);
             gc = min(row0 + 4 * ch, rows_total - 4);
         }
+        if (ridx) gr = ridx[gr];
         (void)valid;   // the reduction tail is zeroed by mask_fast when the slice is stored to LDS,
                        // so that nothing here waits for the load
         f32x4 x = {0.f, 0.f, 0.f, 0.f};
@@ -416,7 +420,7 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
 
     f32x4 ra[gA::NV], rb[gB::NV];
     auto fetch = [&](int s) {
-        fetch_fast<BM, BK, A_RC>(ra, a.A, a.lda, m0, a.M, kbeg + (int64_t)s * BK, kend, a.K);
+        fetch_fast<BM, BK, A_RC>(ra, a.A, a.lda, m0, a.M, kbeg + (int64_t)s * BK, kend, a.K, a.a_row_index);
         fetch_fast<BN, BK, B_RC>(rb, a.B, a.ldb, n0, a.N, kbeg + (int64_t)s * BK, kend, a.K);
     };
     auto stage = [&](int s) {
@@ -521,10 +525,11 @@ int launch_cfg(sgnn_ctx *ctx, int ta, int tb, int bf16, const gemm_args &a, int 
 size_t sgnn_gemm_ws_bytes(uint32_t d_max) { return (size_t)256 * d_max * d_max * 4 + 256; }
 
 int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
-                     const float *B, int64_t ldb, const float *bias, int flags, float *C, int64_t ldc, ws_alloc *ws,
-                     hipStream_t st)
+                     const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias, int flags, float *C,
+                     int64_t ldc, ws_alloc *ws, hipStream_t st)
 {
     gemm_args a;
+    a.a_row_index = a_row_index;
     a.M = M; a.N = N; a.K = K;
     a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.bias = bias; a.C = C; a.ldc = ldc;
     a.relu = (flags & SGNN_RELU) ? 1 : 0;

@@ -107,34 +107,46 @@ __global__ __launch_bounds__(SAMP_NT) void sampler_collect_kernel(uint64_t N, ui
                                                                   uint32_t *__restrict__ cand_v, uint32_t cap,
                                                                   uint32_t *__restrict__ status)
 {
+    // Matches are rare (one vertex in 2048): a workgroup gathers its own in LDS and reserves room in
+    // the global list with ONE atomic add, instead of one add per match on a single hot address.
+    constexpr uint32_t LCAP = 1024;
+    __shared__ uint64_t l_key[LCAP];
+    __shared__ uint32_t l_v[LCAP];
+    __shared__ uint32_t l_n, l_base, l_fail;
     const uint32_t bin = state->bin;
     const uint64_t J = (N + 1) >> 1;
-    const uint64_t Jround = (J + 63) & ~uint64_t(63);   // whole wavefronts stay in the loop together
-    for (uint64_t j = (uint64_t)blockIdx.x * SAMP_NT + threadIdx.x; j < Jround; j += (uint64_t)gridDim.x * SAMP_NT) {
-        uint64_t ke = 0, ko = 0;
-        bool me = false, mo = false;
-        if (j < J) {
-            vertex_pair_keys(j, seed, step, ke, ko);
-            me = (uint32_t)(ke >> (64 - HIST_BITS)) == bin;
-            mo = (2 * j + 1 < N) && (uint32_t)(ko >> (64 - HIST_BITS)) == bin;
+    if (threadIdx.x == 0) { l_n = 0; l_fail = 0xffffffffu; }
+    __syncthreads();
+    for (uint64_t j = (uint64_t)blockIdx.x * SAMP_NT + threadIdx.x; j < J; j += (uint64_t)gridDim.x * SAMP_NT) {
+        uint64_t ke, ko;
+        vertex_pair_keys(j, seed, step, ke, ko);
+        const bool me = (uint32_t)(ke >> (64 - HIST_BITS)) == bin;
+        const bool mo = (2 * j + 1 < N) && (uint32_t)(ko >> (64 - HIST_BITS)) == bin;
+        if (me || mo) {
+            const uint32_t cnt = (me ? 1u : 0u) + (mo ? 1u : 0u);
+            uint32_t p = atomicAdd(&l_n, cnt);
+            if (p + cnt <= LCAP) {
+                if (me) { l_key[p] = ke; l_v[p] = (uint32_t)(2 * j); ++p; }
+                if (mo) { l_key[p] = ko; l_v[p] = (uint32_t)(2 * j + 1); }
+            } else {
+                // the local list is full (far beyond the expected load): straight to the global list.
+                // Reservations only grow, so every one before the first that failed fitted, and they
+                // fill [0, first failing offset) without holes.
+                atomicMin(&l_fail, p);
+                uint32_t q = atomicAdd(&state->ncand, cnt);
+                if (me) { if (q < cap) { cand_key[q] = ke; cand_v[q] = (uint32_t)(2 * j); } else atomicOr(status, SGNN_ST_CAND_OVERFLOW); ++q; }
+                if (mo) { if (q < cap) { cand_key[q] = ko; cand_v[q] = (uint32_t)(2 * j + 1); } else atomicOr(status, SGNN_ST_CAND_OVERFLOW); }
+            }
         }
-        const uint64_t be = __ballot(me), bo = __ballot(mo);
-        const uint32_t ne = __popcll(be), no = __popcll(bo);
-        if (ne + no == 0) continue;
-        uint32_t base = 0;
-        if (lane_id() == 0) base = atomicAdd(&state->ncand, ne + no);
-        base = __shfl(base, 0, 64);
-        const uint64_t below = (1ull << lane_id()) - 1ull;
-        if (me) {
-            uint32_t p = base + __popcll(be & below);
-            if (p < cap) { cand_key[p] = ke; cand_v[p] = (uint32_t)(2 * j); }
-            else atomicOr(status, SGNN_ST_CAND_OVERFLOW);
-        }
-        if (mo) {
-            uint32_t p = base + ne + __popcll(bo & below);
-            if (p < cap) { cand_key[p] = ko; cand_v[p] = (uint32_t)(2 * j + 1); }
-            else atomicOr(status, SGNN_ST_CAND_OVERFLOW);
-        }
+    }
+    __syncthreads();
+    const uint32_t n_local = min(l_n, l_fail);
+    if (threadIdx.x == 0) l_base = n_local ? atomicAdd(&state->ncand, n_local) : 0u;
+    __syncthreads();
+    const uint32_t base = l_base;
+    for (uint32_t i = threadIdx.x; i < n_local; i += SAMP_NT) {
+        if (base + i < cap) { cand_key[base + i] = l_key[i]; cand_v[base + i] = l_v[i]; }
+        else atomicOr(status, SGNN_ST_CAND_OVERFLOW);
     }
 }
 

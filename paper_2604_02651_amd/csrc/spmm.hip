@@ -223,6 +223,16 @@ __device__ __forceinline__ void spmm_reduce_store(const float (&acc)[CH][VEC], f
     }
 }
 
+// out = act(acc + bias) on the VEC columns starting at col
+template <int VEC> __device__ __forceinline__ void spmm_epilogue(float (&v)[VEC], const float *__restrict__ bias, int relu, int col)
+{
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        if (bias) v[i] += bias[col + i];
+        if (relu) v[i] = fmaxf(v[i], 0.f);
+    }
+}
+
 // Workgroups [0, n_chunk_wgs): chunks of long rows.  The chunk's entries are staged in LDS with
 // one coalesced load, every group of lanes takes a contiguous share, and the partial rows of the
 // groups are summed through LDS in a fixed order into part[chunk number].
@@ -237,7 +247,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
                                                             unsigned n_chunk_wgs, const uint32_t *__restrict__ n_chunks,
                                                             uint32_t max_chunks, const uint2 *__restrict__ desc,
                                                             float *__restrict__ part, float *__restrict__ out, int64_t ldo,
-                                                            int lpr_log2)
+                                                            const float *__restrict__ bias, int relu, int lpr_log2)
 {
     __shared__ float red[SPMM_NT * VEC];
     __shared__ int32_t s_src[SPMM_CHUNK];
@@ -284,7 +294,10 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
 #pragma unroll
     for (int m = 0; m < CH; ++m) {
         const int col = (m * lpr + g) * VEC;
-        if (col < d) vstore<VEC>(o + col, acc[m]);
+        if (col < d) {
+            spmm_epilogue<VEC>(acc[m], bias, relu, col);
+            vstore<VEC>(o + col, acc[m]);
+        }
     }
 }
 
@@ -293,7 +306,8 @@ template <int VEC, int CH>
 __global__ __launch_bounds__(256) void spmm_fixup_kernel(const int32_t *__restrict__ rowptr, uint64_t capacity, int d,
                                                          const uint32_t *__restrict__ n_chunks, uint32_t max_chunks,
                                                          const uint2 *__restrict__ desc, const float *__restrict__ part,
-                                                         float *__restrict__ out, int64_t ldo, int lpr_log2)
+                                                         float *__restrict__ out, int64_t ldo,
+                                                         const float *__restrict__ bias, int relu, int lpr_log2)
 {
     const int lpr = 1 << lpr_log2;
     const int G = 256 >> lpr_log2;
@@ -347,7 +361,10 @@ __global__ __launch_bounds__(256) void spmm_fixup_kernel(const int32_t *__restri
 #pragma unroll
         for (int m = 0; m < CH; ++m) {
             const int col = (m * lpr + g) * VEC;
-            if (col < d) vstore<VEC>(o + col, acc[m]);
+            if (col < d) {
+                spmm_epilogue<VEC>(acc[m], bias, relu, col);
+                vstore<VEC>(o + col, acc[m]);
+            }
         }
     }
 }
@@ -364,7 +381,7 @@ int build_plan(sgnn_ctx *ctx, const sgnn_csr *A, void *plan, hipStream_t st)
 
 template <int VEC, int CH>
 int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int d, float *out,
-              int64_t ldo, int lpr_log2, ws_alloc *ws, hipStream_t st)
+              int64_t ldo, const float *bias, int relu, int lpr_log2, ws_alloc *ws, hipStream_t st)
 {
     const unsigned rows_per_block = (unsigned)SPMM_NT >> lpr_log2;
     char tag[56];
@@ -394,33 +411,33 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, con
     }
     SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH>), dim3(n_chunk_wgs + cdiv(A->rows, rows_per_block)),
                 dim3(SPMM_NT), 0, st, A->rows, A->rowptr, A->colidx, A->val, A->capacity, X, ldx, row_index, d,
-                n_chunk_wgs, pv.n_chunks, max_chunks, pv.desc, part, out, ldo, lpr_log2);
+                n_chunk_wgs, pv.n_chunks, max_chunks, pv.desc, part, out, ldo, bias, relu, lpr_log2);
     if (may_have_long) {
         const unsigned groups = 256u >> lpr_log2;
         SGNN_LAUNCH(ctx, st, "spmm_fixup_kernel", tag, (spmm_fixup_kernel<VEC, CH>),
                     dim3(std::min<unsigned>(cdiv(max_chunks, groups), 1024)), dim3(256), 0, st, A->rowptr, A->capacity, d,
-                    pv.n_chunks, max_chunks, pv.desc, part, out, ldo, lpr_log2);
+                    pv.n_chunks, max_chunks, pv.desc, part, out, ldo, bias, relu, lpr_log2);
     }
     return SGNN_OK;
 }
 
 template <int VEC>
 int launch_v(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int d, float *out,
-             int64_t ldo, ws_alloc *ws, hipStream_t st)
+             int64_t ldo, const float *bias, int relu, ws_alloc *ws, hipStream_t st)
 {
     const int per = (d + VEC - 1) / VEC;   // lanes needed for one pass over the row
     int lpr_log2 = 0;
     while ((1 << lpr_log2) < per && lpr_log2 < 6) ++lpr_log2;
     const int ch = (per + (1 << lpr_log2) - 1) >> lpr_log2;
     switch (ch) {
-    case 1: return launch_vc<VEC, 1>(ctx, A, X, ldx, row_index, d, out, ldo, lpr_log2, ws, st);
-    case 2: return launch_vc<VEC, 2>(ctx, A, X, ldx, row_index, d, out, ldo, lpr_log2, ws, st);
-    case 3: return launch_vc<VEC, 3>(ctx, A, X, ldx, row_index, d, out, ldo, lpr_log2, ws, st);
-    case 4: return launch_vc<VEC, 4>(ctx, A, X, ldx, row_index, d, out, ldo, lpr_log2, ws, st);
-    case 5: return launch_vc<VEC, 5>(ctx, A, X, ldx, row_index, d, out, ldo, lpr_log2, ws, st);
-    case 6: return launch_vc<VEC, 6>(ctx, A, X, ldx, row_index, d, out, ldo, lpr_log2, ws, st);
-    case 7: return launch_vc<VEC, 7>(ctx, A, X, ldx, row_index, d, out, ldo, lpr_log2, ws, st);
-    case 8: return launch_vc<VEC, 8>(ctx, A, X, ldx, row_index, d, out, ldo, lpr_log2, ws, st);
+    case 1: return launch_vc<VEC, 1>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
+    case 2: return launch_vc<VEC, 2>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
+    case 3: return launch_vc<VEC, 3>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
+    case 4: return launch_vc<VEC, 4>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
+    case 5: return launch_vc<VEC, 5>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
+    case 6: return launch_vc<VEC, 6>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
+    case 7: return launch_vc<VEC, 7>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
+    case 8: return launch_vc<VEC, 8>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
     default: break;
     }
     return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_spmm: feature width %d is beyond %d columns", d, 64 * 8 * VEC);
@@ -447,13 +464,13 @@ int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st)
 }
 
 int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int64_t d,
-                     float *out, int64_t ldo, ws_alloc *ws, hipStream_t st)
+                     float *out, int64_t ldo, const float *bias, int relu, ws_alloc *ws, hipStream_t st)
 {
     if (A->rows == 0 || d == 0) return SGNN_OK;
     const uintptr_t bits = reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(out);
     if (d % 4 == 0 && ldx % 4 == 0 && ldo % 4 == 0 && (bits & 15) == 0)
-        return launch_v<4>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ws, st);
+        return launch_v<4>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
     if (d % 2 == 0 && ldx % 2 == 0 && ldo % 2 == 0 && (bits & 7) == 0)
-        return launch_v<2>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ws, st);
-    return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ws, st);
+        return launch_v<2>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
+    return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
 }

@@ -19,7 +19,8 @@ class GcnStep:
 
     def __init__(self, N: int, rowptr: torch.Tensor, colidx: torch.Tensor, X: torch.Tensor, labels: torch.Tensor,
                  weights: List[Tuple[torch.Tensor, torch.Tensor]], B: int, seed: int = 0, bf16: bool = False,
-                 fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None):
+                 fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None,
+                 auto_order: bool = True):
         self.N, self.B, self.seed = N, B, seed
         self.rowptr, self.colidx, self.X, self.labels = rowptr, colidx, X, labels
         self.weights = weights
@@ -43,7 +44,11 @@ class GcnStep:
         self.A = sg.Csr(B, B, capacity, dev)
         self.y_S = torch.empty(B, dtype=torch.int32, device=dev)
         self.X_S = None if fuse_slice else torch.empty((B, dims[0]), dtype=torch.float32, device=dev)
-        self.T = [torch.empty((B, dims[l]), dtype=torch.float32, device=dev) for l in range(self.L)]
+        # a layer that narrows (d_out < d_in) is evaluated transform-first: its sparse products run at
+        # width d_out, and its backward pass needs the layer input instead of the aggregate
+        self.xform_first = [auto_order and dims[l + 1] < dims[l] for l in range(self.L)]
+        self.T = [None if self.xform_first[l] else torch.empty((B, dims[l]), dtype=torch.float32, device=dev)
+                  for l in range(self.L)]
         self.H = [torch.empty((B, dims[l + 1]), dtype=torch.float32, device=dev) for l in range(self.L)]
         self.dH = [torch.empty((B, dims[l]), dtype=torch.float32, device=dev) if l > 0 else None for l in range(self.L)]
         self.dO = torch.empty((B, dims[-1]), dtype=torch.float32, device=dev)
@@ -64,7 +69,7 @@ class GcnStep:
 
     def forward(self):
         for l, (W, b) in enumerate(self.weights):
-            flags = self.flags | (sg.SGNN_RELU if l < self.L - 1 else 0)
+            flags = self.flags | (sg.SGNN_RELU if l < self.L - 1 else 0) | (sg.SGNN_XFORM_FIRST if self.xform_first[l] else 0)
             if l == 0 and self.fuse_slice:
                 sg.sgnn_gcn_fwd(self.ctx, self.A, self.X, W, b, flags, self.H[0], self.T[0], row_index=self.S)
             else:
@@ -78,9 +83,16 @@ class GcnStep:
         dY = self.dO
         for l in range(self.L - 1, -1, -1):
             W, _ = self.weights[l]
-            flags = self.flags | (sg.SGNN_RELU if l < self.L - 1 else 0)
+            flags = self.flags | (sg.SGNN_RELU if l < self.L - 1 else 0) | (sg.SGNN_XFORM_FIRST if self.xform_first[l] else 0)
+            saved, ridx = self.T[l], None
+            if self.xform_first[l]:
+                if l == 0:
+                    saved, ridx = (self.X, self.S) if self.fuse_slice else (self.X_S, None)
+                else:
+                    saved = self.H[l - 1]
             # the induced matrix of a symmetric graph is symmetric: it is its own transpose
-            sg.sgnn_gcn_bwd(self.ctx, self.A, self.T[l], W, self.H[l], dY, flags, self.dH[l], self.dW[l], self.db[l])
+            sg.sgnn_gcn_bwd(self.ctx, self.A, saved, W, self.H[l], dY, flags, self.dH[l], self.dW[l], self.db[l],
+                            row_index=ridx)
             dY = self.dH[l]
 
     def step(self, t: int):

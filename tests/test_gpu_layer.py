@@ -183,20 +183,22 @@ def test_gemm_strided_operands():
     assert torch.all(Cfull[:, 48:] == 0)
 
 
+@pytest.mark.parametrize("xform", [False, True])
 @pytest.mark.parametrize("bf16", [False, True])
-@pytest.mark.parametrize("d_in,d_out,relu", [(32, 64, True), (64, 8, False), (100, 256, True), (256, 47, False)])
-def test_layer_forward_backward(sub, d_in, d_out, relu, bf16):
+@pytest.mark.parametrize("d_in,d_out,relu", [(32, 64, True), (64, 8, False), (100, 256, True), (256, 47, False), (602, 256, True)])
+def test_layer_forward_backward(sub, d_in, d_out, relu, bf16, xform):
     B, rp, ci, v = sub
     ctx().reserve(B, len(ci), B, max(d_in, d_out), len(ci))
     A = sg.Csr.from_arrays(B, B, rp, ci, v, DEV)
     H = _rand((B, d_in), 1); W = (_rand((d_in, d_out), 2) / np.sqrt(d_in)).astype(np.float32); b = _rand(d_out, 3) * 0.1
     dY = _rand((B, d_out), 4)
-    flags = (sg.SGNN_RELU if relu else 0) | (sg.SGNN_BF16_MFMA if bf16 else 0)
+    flags = (sg.SGNN_RELU if relu else 0) | (sg.SGNN_BF16_MFMA if bf16 else 0) | (sg.SGNN_XFORM_FIRST if xform else 0)
     tol = TOL_BF16 if bf16 else TOL_F32
     Y = torch.zeros((B, d_out), dtype=torch.float32, device=DEV); T = torch.zeros((B, d_in), dtype=torch.float32, device=DEV)
-    sg.sgnn_gcn_fwd(ctx(), A, dev(H), dev(W), dev(b), flags, Y, T)
+    sg.sgnn_gcn_fwd(ctx(), A, dev(H), dev(W), dev(b), flags, Y, None if xform else T)
     T_ref, Y_ref = oracle.gcn_fwd(rp, ci, v, H, W, b, relu=relu, bf16=bf16)
-    assert rel_err(T.cpu().numpy(), T_ref) < TOL_F32
+    if not xform:
+        assert rel_err(T.cpu().numpy(), T_ref) < TOL_F32
     assert rel_err(Y.cpu().numpy(), Y_ref) < tol
     # backward from the oracle's own forward state
     rpT, ciT, vT = oracle.csr_transpose(B, B, rp, ci, v)
@@ -204,13 +206,14 @@ def test_layer_forward_backward(sub, d_in, d_out, relu, bf16):
     AT = sg.Csr.from_arrays(B, B, rpT, ciT, vT, DEV)
     dH = torch.zeros((B, d_in), dtype=torch.float32, device=DEV)
     dW = torch.zeros((d_in, d_out), dtype=torch.float32, device=DEV); db = torch.zeros(d_out, dtype=torch.float32, device=DEV)
-    sg.sgnn_gcn_bwd(ctx(), AT, dev(T_ref, torch.float32), dev(W), dev(Y_ref, torch.float32), dev(dY), flags, dH, dW, db)
+    saved = dev(H) if xform else dev(T_ref, torch.float32)     # transform-first layers keep their input
+    sg.sgnn_gcn_bwd(ctx(), AT, saved, dev(W), dev(Y_ref, torch.float32), dev(dY), flags, dH, dW, db)
     assert rel_err(dH.cpu().numpy(), dH_ref) < tol
     assert rel_err(dW.cpu().numpy(), dW_ref) < tol
     assert rel_err(db.cpu().numpy(), db_ref) < TOL_F32
     # first layer: dH skipped, nothing else changes
     dW2 = torch.zeros_like(dW)
-    sg.sgnn_gcn_bwd(ctx(), AT, dev(T_ref, torch.float32), dev(W), dev(Y_ref, torch.float32), dev(dY), flags, None, dW2, None)
+    sg.sgnn_gcn_bwd(ctx(), AT, saved, dev(W), dev(Y_ref, torch.float32), dev(dY), flags, None, dW2, None)
     assert torch.equal(dW, dW2)
 
 
@@ -247,7 +250,7 @@ def test_softmax_xent_and_gather():
     assert torch.equal(lo, lo2)
 
 
-def _run_config(name, steps, fuse_slice, bf16=None):
+def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True):
     cfg = si.CONFIGS[name]
     bf16 = cfg.bf16_mfma if bf16 is None else bf16
     # inputs are generated with torch on the GPU (integer parts are device independent) and copied
@@ -258,7 +261,7 @@ def _run_config(name, steps, fuse_slice, bf16=None):
     weights = si.layer_weights(cfg)
     st = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld,
                     [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B, cfg.sampler_seed, bf16=bf16,
-                    fuse_slice=fuse_slice, device=DEV)
+                    fuse_slice=fuse_slice, device=DEV, auto_order=auto_order)
     g = si.Graph(cfg.N, gd.rowptr.cpu(), gd.colidx.cpu())
     X, labels = Xd.cpu(), ld.cpu()
     wnp = [(W.double().numpy(), b.double().numpy()) for W, b in weights]
@@ -279,7 +282,8 @@ def _run_config(name, steps, fuse_slice, bf16=None):
             assert np.array_equal(st.X_S.cpu().numpy().astype(np.float64), ref["X_S"])
         ties = []
         for l in range(cfg.layers):
-            assert rel_err(st.T[l].cpu().numpy(), ref["T"][l]) < tol, ("T", l)
+            if st.T[l] is not None:      # transform-first layers never form the aggregate
+                assert rel_err(st.T[l].cpu().numpy(), ref["T"][l]) < tol, ("T", l)
             assert rel_err(st.H[l].cpu().numpy(), ref["H"][l + 1]) < tol, ("H", l)
             # the ReLU decision must agree wherever the pre-activation is decidably non-zero
             got_mask = st.H[l].cpu().numpy() > 0
@@ -298,9 +302,23 @@ def _run_config(name, steps, fuse_slice, bf16=None):
                 assert rel_err(st.dH[l].cpu().numpy(), ref["dH"][l]) < tol, ("dH", l)
 
 
+@pytest.mark.parametrize("auto_order", [False, True])
 @pytest.mark.parametrize("fuse_slice", [False, True])
-def test_whole_step_tiny(fuse_slice):
-    _run_config("tiny", [0, 1], fuse_slice)
+def test_whole_step_tiny(fuse_slice, auto_order):
+    _run_config("tiny", [0, 1], fuse_slice, auto_order=auto_order)
+
+
+def test_whole_step_with_a_narrowing_first_layer():
+    # first layer 32 -> 16 evaluated transform-first straight from the full feature matrix
+    # (row_index = S in the forward GEMM and in the weight-gradient GEMM)
+    import copy
+    cfg = copy.deepcopy(si.CONFIGS["tiny"]); cfg.hidden = 16; cfg.name = "tiny_narrow"
+    si.CONFIGS["tiny_narrow"] = cfg
+    try:
+        _run_config("tiny_narrow", [0], True)
+        _run_config("tiny_narrow", [1], False)
+    finally:
+        del si.CONFIGS["tiny_narrow"]
 
 
 def test_whole_step_tiny_bf16():
@@ -361,7 +379,8 @@ def test_whole_step_xlarge_bf16():
     if any((ties[l] != ref["relu_mask"][l]).any() for l in range(cfg.layers - 1)):
         ref = oracle.layers_step(rpS, ciS, vS, X_S, y_S, wnp, bf16=True, tie_band=1e-3, relu_ties=ties)
     for l in range(cfg.layers):
-        assert rel_err(st.T[l].cpu().numpy(), ref["T"][l]) < TOL_BF16, ("T", l)
+        if st.T[l] is not None:
+            assert rel_err(st.T[l].cpu().numpy(), ref["T"][l]) < TOL_BF16, ("T", l)
         assert rel_err(st.H[l].cpu().numpy(), ref["H"][l + 1]) < TOL_BF16, ("H", l)
         assert rel_err(st.dW[l].cpu().numpy(), ref["dW"][l]) < TOL_BF16, ("dW", l)
         assert rel_err(st.db[l].cpu().numpy(), ref["db"][l]) < TOL_BF16, ("db", l)
