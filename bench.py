@@ -35,6 +35,9 @@ def parse_args():
     ap.add_argument("--config", default="medium", help="tiny | medium | large | dense | xlarge (medium is the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fuse-slice", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="everything on one stream (default: the next mini-batch is sampled on a second stream while this one trains)")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = pick by config)")
     ap.add_argument("--breakdown", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -74,17 +77,34 @@ def main():
                     fuse_slice=not args.no_fuse_slice, device=dev)
     period = max(cfg.steps, 1)   # the configuration's mini-batches: consecutive sampler counters
 
-    for i in range(args.warmup):
-        st.step(i % period)
+    use_graph = not args.no_graph and not args.no_overlap and period % 2 == 0
+    if use_graph:
+        st.build_graphs(range(period))
+
+    def run(n):
+        if args.no_overlap:
+            for i in range(n):
+                st.step(i % period)
+        elif use_graph:
+            st.run_graphs(n)
+        else:
+            st.run([i % period for i in range(n)])
+
+    run(args.warmup)
     torch.cuda.synchronize()
     st.ctx.status()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        st.step(i % period)
+    run(args.steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     st.ctx.status()
     steps_per_s = args.steps / elapsed
+    # the same K steps on a single stream, for reference
+    t1 = time.perf_counter()
+    for i in range(args.steps):
+        st.step(i % period)
+    torch.cuda.synchronize()
+    single_stream_steps_per_s = args.steps / (time.perf_counter() - t1)
 
     # ---- per-kernel pass: the same steps with every launch bracketed by events on its stream ----
     nprof = min(args.steps, period)
@@ -153,7 +173,8 @@ def main():
         "config": {"workload": "%s: R-MAT N=%d, E=%d stored entries, |S|=%d, GCN %s, %d mini-batches (sampler "
                                "counters 0..%d)" % (cfg.name, cfg.N, g.E, cfg.B, "-".join(map(str, cfg.dims)), period,
                                                      period - 1),
-                   "fuse_slice": not args.no_fuse_slice, "avg_induced_entries": nnz_avg,
+                   "fuse_slice": not args.no_fuse_slice, "overlap_sampling": not args.no_overlap, "hip_graph": use_graph,
+                   "single_stream_steps_per_s": single_stream_steps_per_s, "avg_induced_entries": nnz_avg,
                    "kernel_time_us_per_step": 1e3 * total_ms / nprof},
         "roofline": roofline,
     }

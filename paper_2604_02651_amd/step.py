@@ -32,18 +32,15 @@ class GcnStep:
         dims = [weights[0][0].shape[0]] + [w.shape[1] for w, _ in weights]
         self.dims = dims
         self.ctx = ctx or sg.Context(dev.index or 0)
-        W = (N + 63) // 64
-        self.S = torch.empty(B, dtype=torch.int32, device=dev)
-        self.bitmap = torch.empty(W, dtype=torch.int64, device=dev)
-        self.rank = torch.empty(W, dtype=torch.int32, device=dev)
         if capacity is None:
             # expected entries B + (E-N) B(B-1)/(N(N-1)) with generous head-room
             exp = B + (E - N) * (B / N) * ((B - 1) / max(N - 1, 1))
             capacity = int(min(E, 2 * exp + 16 * B + 65536))
+        self.capacity = capacity
         self.ctx.reserve(N, E, B, max(dims), capacity)
-        self.A = sg.Csr(B, B, capacity, dev)
-        self.y_S = torch.empty(B, dtype=torch.int32, device=dev)
-        self.X_S = None if fuse_slice else torch.empty((B, dims[0]), dtype=torch.float32, device=dev)
+        self.dev = dev
+        self.batches = [self._new_batch()]
+        self._use(self.batches[0])
         # a layer that narrows (d_out < d_in) is evaluated transform-first: its sparse products run at
         # width d_out, and its backward pass needs the layer input instead of the aggregate
         self.xform_first = [auto_order and dims[l + 1] < dims[l] for l in range(self.L)]
@@ -55,6 +52,25 @@ class GcnStep:
         self.dW = [torch.empty_like(w) for w, _ in weights]
         self.db = [torch.empty_like(b) for _, b in weights]
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+
+    def _new_batch(self):
+        """Device buffers of one mini-batch: the sample, its bitmap and rank prefix, the induced CSR
+        (with its long-row plan), the sliced labels and (unfused) features."""
+        W = (self.N + 63) // 64
+        dev = self.dev
+        b = type("Batch", (), {})()
+        b.S = torch.empty(self.B, dtype=torch.int32, device=dev)
+        b.bitmap = torch.empty(W, dtype=torch.int64, device=dev)
+        b.rank = torch.empty(W, dtype=torch.int32, device=dev)
+        b.A = sg.Csr(self.B, self.B, self.capacity, dev)
+        b.y_S = torch.empty(self.B, dtype=torch.int32, device=dev)
+        b.X_S = None if self.fuse_slice else torch.empty((self.B, self.dims[0]), dtype=torch.float32, device=dev)
+        b.ready = torch.cuda.Event()
+        b.free = torch.cuda.Event()
+        return b
+
+    def _use(self, b):
+        self.S, self.bitmap, self.rank, self.A, self.y_S, self.X_S = b.S, b.bitmap, b.rank, b.A, b.y_S, b.X_S
 
     def sample(self, t: int):
         sg.sgnn_sample_uniform(self.ctx, self.N, self.B, self.seed, t, self.S, self.bitmap, self.rank)
@@ -96,9 +112,96 @@ class GcnStep:
             dY = self.dH[l]
 
     def step(self, t: int):
+        """One whole step on the current stream."""
         self.sample(t)
         self.induce()
         self.slice()
         self.forward()
         self.loss_and_grad()
         self.backward()
+
+    # ---- sampling of step t+1 overlapped with the training of step t (Sec. V-A of the paper) ----
+
+    def _prefetch(self, t: int, b, wait_free: bool = True):
+        """sample -> induced CSR -> slice for step t into batch b, on the side stream with its own
+        context (scratch), after the training that last used b has finished."""
+        st = self.side_stream
+        if wait_free:
+            st.wait_event(b.free)
+        sg.sgnn_sample_uniform(self.side_ctx, self.N, self.B, self.seed, t, b.S, b.bitmap, b.rank, stream=st)
+        sg.sgnn_induced_csr(self.side_ctx, self.N, self.rowptr, self.colidx, None, b.S, self.B, b.bitmap, b.rank, b.A,
+                            stream=st)
+        sg.sgnn_gather_rows(self.side_ctx, None if self.fuse_slice else self.X, b.S, self.B, b.X_S, self.labels, b.y_S,
+                            stream=st)
+        b.ready.record(st)
+
+    def _init_side(self):
+        if not hasattr(self, "side_stream"):
+            self.side_stream = torch.cuda.Stream(device=self.dev)       # default priority
+            self.side_ctx = sg.Context(self.dev.index or 0)
+            self.side_ctx.reserve(self.N, int(self.colidx.numel()), self.B, 1, self.capacity)
+            self.batches.append(self._new_batch())
+            main = torch.cuda.current_stream()
+            for b in self.batches:
+                b.free.record(main)
+
+    def run(self, steps):
+        """Run the given steps with the mini-batch of the next step built on a second stream while
+        the current one trains.  The prefetch crosses whatever boundary (epoch) the list contains.
+        Results of the last step are left in the usual buffers; returns nothing."""
+        steps = list(steps)
+        if not steps:
+            return
+        self._init_side()
+        main = torch.cuda.current_stream()
+        self.side_stream.wait_stream(main)       # earlier work on the main stream that wrote the buffers
+        self._prefetch(steps[0], self.batches[0])
+        for i, t in enumerate(steps):
+            b = self.batches[i % 2]
+            if i + 1 < len(steps):
+                self._prefetch(steps[i + 1], self.batches[(i + 1) % 2])
+            main.wait_event(b.ready)
+            self._use(b)
+            self.forward()
+            self.loss_and_grad()
+            self.backward()
+            b.free.record(main)
+        main.wait_stream(self.side_stream)
+
+    # ---- the same pipeline captured in HIP graphs (one per mini-batch of a cycle) ----
+
+    def build_graphs(self, cycle):
+        """Capture, for every position i of the cycle of steps (even length), one HIP graph that
+        trains the mini-batch of cycle[i] (already in buffer set i % 2) while it builds the one of
+        cycle[i+1] in the other set on a forked stream.  Replaying the graphs in order, round and
+        round, is the overlapped pipeline without any per-kernel launch work on the host."""
+        cycle = list(cycle)
+        if len(cycle) % 2:
+            raise ValueError("the cycle must have an even number of steps (two buffer sets)")
+        self._init_side()
+        torch.cuda.synchronize()
+        self.cycle, self.graphs = cycle, []
+        cap = torch.cuda.Stream(device=self.dev)
+        for i, t in enumerate(cycle):
+            b, nb = self.batches[i % 2], self.batches[(i + 1) % 2]
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=cap):
+                main = torch.cuda.current_stream()
+                self.side_stream.wait_stream(main)                     # fork
+                self._prefetch(cycle[(i + 1) % len(cycle)], nb, wait_free=False)
+                self._use(b)
+                self.forward()
+                self.loss_and_grad()
+                self.backward()
+                main.wait_stream(self.side_stream)                     # join
+            self.graphs.append(g)
+        torch.cuda.synchronize()
+
+    def run_graphs(self, n: int):
+        """n steps of the captured cycle, starting at its first step."""
+        self.side_stream.wait_stream(torch.cuda.current_stream())
+        self._prefetch(self.cycle[0], self.batches[0], wait_free=False)
+        torch.cuda.current_stream().wait_stream(self.side_stream)
+        for i in range(n):
+            self.graphs[i % len(self.graphs)].replay()
+        self._use(self.batches[(n - 1) % 2])
