@@ -1,11 +1,13 @@
 // Sparse aggregation of the GCN layer (Sec. III-B Eq. 5 and the transposed SpMM of Sec. III-C):
 // out = A X with A in CSR.
 //
-// Row-split with a side path for long rows.  A group of LPR lanes (a power of two up to a whole
-// wavefront) owns one output row and walks its entries; each lane keeps VEC*CH columns of the row
-// in registers, so every gathered feature row is read with full-width coalesced vector loads and
-// the output row is written once.  Rows much longer than the mean (power-law graphs have them)
-// would leave one wavefront walking alone long after the others are done, so a plan built once
+// Row-split with a side path for long rows.  A wavefront owns a block of consecutive output rows
+// and walks their entries as one stream: the CSR entries of the block are contiguous, so they are
+// fetched 64 at a time with one coalesced load, and several gathered feature rows are in flight
+// however short the rows are.  The 64 lanes cover the columns (VEC*CH of them per lane), so every
+// feature row is read with coalesced vector loads and every output row is written once.  Rows
+// much longer than the mean (power-law graphs have them) would leave one wavefront walking
+// alone long after the others are done, so a plan built once
 // per matrix cuts them into chunks of 256 entries:
 //   spmm_plan_kernel    (once per matrix) chunk descriptors of the long rows
 //   spmm_main_kernel    workgroups [0, n_chunk_wgs) take chunks (entries staged in LDS, partial row
@@ -49,10 +51,10 @@ template <int VEC> __device__ __forceinline__ void vstore(float *p, const float 
     }
 }
 
-constexpr int SPMM_NT = 1024;      // threads of a workgroup
+constexpr int SPMM_NT = 256;       // threads of a workgroup
 constexpr int SPMM_SHORT = 32;     // smallest length from which a row counts as long
-constexpr int SPMM_CHUNK = 256;    // entries per chunk of a long row
-constexpr unsigned SPMM_CHUNK_WGS = 256;
+constexpr int SPMM_CHUNK = 64;     // entries per piece of a long row: what one wavefront fetches at once
+constexpr unsigned SPMM_PIECE_WAVES = 2048;
 
 // Plan of a matrix (device memory): header, first chunk number per row, chunk descriptors.
 struct spmm_plan_view {
@@ -70,6 +72,18 @@ __host__ __device__ inline int spmm_long_len(uint32_t rows, uint64_t entries)
     if (t < SPMM_SHORT) t = SPMM_SHORT;
     if (t > (1u << 20)) t = 1u << 20;
     return (int)t;
+}
+
+// Rows that one wavefront walks as a block: about 16 entries, at most 8 rows, and no fewer than
+// 4096 wavefronts while the rows last.  The plan holds the figure for the true entry count (header
+// word 2); the host sizes the grid with the capacity in its place, which can only give fewer rows.
+__host__ __device__ inline int spmm_rows_per_wave(uint32_t rows, uint64_t entries)
+{
+    const uint64_t mean = rows && entries >= rows ? entries / rows : 1;
+    uint64_t r = 16 / (mean < 16 ? mean : 16);
+    if (r > 8) r = 8;
+    if (r > rows / 4096) r = rows / 4096;
+    return r < 1 ? 1 : (int)r;
 }
 
 inline uint32_t spmm_max_chunks(uint32_t rows, uint64_t capacity)
@@ -102,8 +116,12 @@ __global__ __launch_bounds__(256) void spmm_plan_kernel(uint32_t rows, const int
                                                         uint2 *__restrict__ desc)
 {
     const uint32_t row = blockIdx.x * 256 + threadIdx.x;
-    const int long_len = spmm_long_len(rows, min((uint64_t)rowptr[rows], capacity));
-    if (row == 0) n_chunks[1] = (uint32_t)long_len;
+    const uint64_t entries = min((uint64_t)rowptr[rows], capacity);
+    const int long_len = spmm_long_len(rows, entries);
+    if (row == 0) {
+        n_chunks[1] = (uint32_t)long_len;
+        n_chunks[2] = (uint32_t)spmm_rows_per_wave(rows, entries);
+    }
     if (row >= rows) return;
     const int64_t len = min((int64_t)rowptr[row + 1], (int64_t)capacity) - min((int64_t)rowptr[row], (int64_t)capacity);
     if (len <= long_len) return;
@@ -111,116 +129,6 @@ __global__ __launch_bounds__(256) void spmm_plan_kernel(uint32_t rows, const int
     const uint32_t base = atomicAdd(n_chunks, nch);
     part_base[row] = base;
     for (uint32_t c = 0; c < nch && base + c < max_chunks; ++c) desc[base + c] = make_uint2(row, c);
-}
-
-// U entries e, e+1, ... fetched together: acc[m][:] += a_e * X[src_e, cols of chunk m].
-// Entries at or past `re` are redirected to entry e and masked out.
-template <int VEC, int CH, int U>
-__device__ __forceinline__ void spmm_batch(float (&acc)[CH][VEC], const int32_t *__restrict__ colidx,
-                                           const float *__restrict__ val, int64_t e, int64_t re,
-                                           const float *__restrict__ X, int64_t ldx, const int32_t *__restrict__ row_index,
-                                           int d, int lpr, int g)
-{
-    float a[U];
-    bool ok[U];
-    const float *x[U];
-#pragma unroll
-    for (int t = 0; t < U; ++t) {
-        ok[t] = e + t < re;
-        const int64_t ec = ok[t] ? e + t : e;
-        const int32_t c = colidx[ec];
-        a[t] = val[ec];
-        x[t] = X + (int64_t)(row_index ? row_index[c] : c) * ldx;
-    }
-    float v[U][CH][VEC];
-#pragma unroll
-    for (int t = 0; t < U; ++t)
-#pragma unroll
-        for (int m = 0; m < CH; ++m) {
-            const int col = (m * lpr + g) * VEC;
-            if (col < d) vload<VEC>(v[t][m], x[t] + col);
-        }
-#pragma unroll
-    for (int t = 0; t < U; ++t)
-#pragma unroll
-        for (int m = 0; m < CH; ++m) {
-            const int col = (m * lpr + g) * VEC;
-            if (col < d && ok[t]) {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[m][i] = fmaf(a[t], v[t][m][i], acc[m][i]);
-            }
-        }
-}
-
-// acc += sum over the entries [e, re) of a row.  Entries are fetched four at a time while three or
-// more are left, so a short row costs one round trip to memory without redundant loads.
-template <int VEC, int CH>
-__device__ __forceinline__ void spmm_accumulate(float (&acc)[CH][VEC], const int32_t *__restrict__ colidx,
-                                                const float *__restrict__ val, int64_t e, int64_t re,
-                                                const float *__restrict__ X, int64_t ldx,
-                                                const int32_t *__restrict__ row_index, int d, int lpr, int g)
-{
-    for (; e + 2 < re; e += 4) spmm_batch<VEC, CH, 4>(acc, colidx, val, e, re, X, ldx, row_index, d, lpr, g);
-    if (e + 1 < re) spmm_batch<VEC, CH, 2>(acc, colidx, val, e, re, X, ldx, row_index, d, lpr, g);
-    else if (e < re) spmm_batch<VEC, CH, 1>(acc, colidx, val, e, re, X, ldx, row_index, d, lpr, g);
-}
-
-// The same over entries already staged in LDS (source row and weight), eight in flight.
-template <int VEC, int CH>
-__device__ __forceinline__ void spmm_accumulate_staged(float (&acc)[CH][VEC], const int32_t *s_src, const float *s_val, int i0,
-                                                       int i1, const float *__restrict__ X, int64_t ldx, int d, int lpr, int g)
-{
-    constexpr int U = 8;
-    for (int i = i0; i < i1; i += U) {
-        float v[U][CH][VEC];
-#pragma unroll
-        for (int t = 0; t < U; ++t) {
-            const float *x = X + (int64_t)s_src[min(i + t, i1 - 1)] * ldx;
-#pragma unroll
-            for (int m = 0; m < CH; ++m) {
-                const int col = (m * lpr + g) * VEC;
-                if (col < d) vload<VEC>(v[t][m], x + col);
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < U; ++t) {
-            const float a = s_val[min(i + t, i1 - 1)];
-#pragma unroll
-            for (int m = 0; m < CH; ++m) {
-                const int col = (m * lpr + g) * VEC;
-                if (col < d && i + t < i1) {
-#pragma unroll
-                    for (int k = 0; k < VEC; ++k) acc[m][k] = fmaf(a, v[t][m][k], acc[m][k]);
-                }
-            }
-        }
-    }
-}
-
-// Sum of the per-group partial rows of a workgroup through LDS, in group order; group 0 stores.
-template <int VEC, int CH>
-__device__ __forceinline__ void spmm_reduce_store(const float (&acc)[CH][VEC], float *red, float *__restrict__ o, int d,
-                                                  int lpr, int G, int q, int g)
-{
-#pragma unroll
-    for (int m = 0; m < CH; ++m) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) red[(q * lpr + g) * VEC + i] = acc[m][i];
-        __syncthreads();
-        if (q == 0) {
-            const int col = (m * lpr + g) * VEC;
-            if (col < d) {
-                float sum[VEC];
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) sum[i] = 0.f;
-                for (int w = 0; w < G; ++w)
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) sum[i] += red[(w * lpr + g) * VEC + i];
-                vstore<VEC>(o + col, sum);
-            }
-        }
-        __syncthreads();
-    }
 }
 
 // out = act(acc + bias) on the VEC columns starting at col
@@ -233,72 +141,205 @@ template <int VEC> __device__ __forceinline__ void spmm_epilogue(float (&v)[VEC]
     }
 }
 
-// Workgroups [0, n_chunk_wgs): chunks of long rows.  The chunk's entries are staged in LDS with
-// one coalesced load, every group of lanes takes a contiguous share, and the partial rows of the
-// groups are summed through LDS in a fixed order into part[chunk number].
-// The other workgroups own G = 1024 / lpr consecutive rows each, a group of lpr lanes per row; a
-// row of up to long_len entries is walked by its group alone, a longer one is left to the fix-up.
+// One wavefront walks `rows_per_wave` consecutive rows as one stream of entries.  The entries of
+// consecutive rows are contiguous in the CSR arrays, so 64 of them are fetched with one coalesced
+// load (lane l keeps entry e + l) and handed out by lane index; U gathered feature rows are in
+// flight at a time whatever the lengths of the rows, the 64 lanes covering the columns.  Every
+// value that steers the walk (row number, row bounds, entry number) is the same in all lanes.
+// A row longer than long_len is left out: its chunks and the fix-up write it.
+template <int VEC, int CH>
+__device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const int32_t *__restrict__ rowptr,
+                                               const int32_t *__restrict__ colidx, const float *__restrict__ val,
+                                               uint64_t capacity, const float *__restrict__ X, int64_t ldx,
+                                               const int32_t *__restrict__ row_index, int d, uint32_t wave, int rows_per_wave,
+                                               int long_len, float *__restrict__ out, int64_t ldo,
+                                               const float *__restrict__ bias, int relu)
+{
+    constexpr int U = CH * VEC <= 4 ? 8 : (CH * VEC <= 8 ? 4 : 2);
+    const int lane = threadIdx.x & 63;
+    const uint64_t r0 = (uint64_t)wave * (uint64_t)rows_per_wave;
+    if (r0 >= rows) return;
+    const int nr = (int)min((uint64_t)rows_per_wave, rows - r0);
+    const int32_t cap = (int32_t)min(capacity, (uint64_t)0x7fffffff);
+    const int32_t rp = lane <= nr ? min(rowptr[r0 + lane], cap) : 0;   // lane k: start of row r0 + k
+    const int e_end = __builtin_amdgcn_readlane(rp, nr);
+    int e = __builtin_amdgcn_readlane(rp, 0);
+    int row = 0, row_end = __builtin_amdgcn_readlane(rp, 1);
+    bool row_long = row_end - e > long_len;
+    float acc[CH][VEC];
+#pragma unroll
+    for (int m = 0; m < CH; ++m)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[m][i] = 0.f;
+
+    // the current row is complete: write it (unless it is a long one) and move to the next
+    auto next_row = [&]() {
+        if (!row_long) {
+            float *o = out + (int64_t)(r0 + row) * ldo;
+#pragma unroll
+            for (int m = 0; m < CH; ++m) {
+                const int col = (m * 64 + lane) * VEC;
+                if (col < d) {
+                    spmm_epilogue<VEC>(acc[m], bias, relu, col);
+                    vstore<VEC>(o + col, acc[m]);
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < CH; ++m)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[m][i] = 0.f;
+        ++row;
+        if (row < nr) {
+            const int rs = row_end;
+            row_end = __builtin_amdgcn_readlane(rp, __builtin_amdgcn_readfirstlane(row + 1));
+            row_long = row_end - rs > long_len;
+        }
+    };
+
+    for (;;) {
+        while (row < nr && (e >= row_end || row_long)) {
+            if (row_long) e = max(e, row_end);
+            next_row();
+        }
+        if (row >= nr) break;
+        // e is an entry of a row this wavefront sums: fetch up to 64 entries from there
+        const int n = min(64, e_end - e);
+        int32_t src = 0;
+        float a = 0.f;
+        if (lane < n) {
+            const int32_t c = colidx[e + lane];
+            a = val[e + lane];
+            src = row_index ? row_index[c] : c;
+        }
+        int used = n;
+        for (int j0 = 0; j0 < n && used == n; j0 += U) {
+            float v[U][CH][VEC], av[U];
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                const int jj = __builtin_amdgcn_readfirstlane(min(j0 + t, n - 1));
+                const float *x = X + (int64_t)__builtin_amdgcn_readlane(src, jj) * ldx;
+                av[t] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), jj));
+#pragma unroll
+                for (int m = 0; m < CH; ++m) {
+                    const int col = (m * 64 + lane) * VEC;
+                    if (col < d) vload<VEC>(v[t][m], x + col);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                if (j0 + t < n && used == n) {
+                    const int ee = e + j0 + t;
+                    while (ee >= row_end) next_row();     // ee < e_end: a later row of this block holds it
+                    if (row_long) used = j0 + t;          // stop in front of the long row
+                    else {
+#pragma unroll
+                        for (int m = 0; m < CH; ++m) {
+                            const int col = (m * 64 + lane) * VEC;
+                            if (col < d) {
+#pragma unroll
+                                for (int i = 0; i < VEC; ++i) acc[m][i] = fmaf(av[t], v[t][m][i], acc[m][i]);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        e += used;
+    }
+}
+
+// acc += sum over the n <= 64 entries starting at e, which lane l < n holds as (src, a): U feature
+// rows in flight at a time, handed out by lane index.  keep(j) tells whether entry j still counts
+// and may move the caller's row state; it is called in entry order.
+template <int VEC, int CH, int U, typename Keep>
+__device__ __forceinline__ void spmm_wave_entries(float (&acc)[CH][VEC], int32_t src, float a, int n, const float *__restrict__ X,
+                                                  int64_t ldx, int d, int lane, Keep keep)
+{
+    bool go = true;
+    for (int j0 = 0; j0 < n && go; j0 += U) {
+        float v[U][CH][VEC], av[U];
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+            const int jj = __builtin_amdgcn_readfirstlane(min(j0 + t, n - 1));
+            const float *x = X + (int64_t)__builtin_amdgcn_readlane(src, jj) * ldx;
+            av[t] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), jj));
+#pragma unroll
+            for (int m = 0; m < CH; ++m) {
+                const int col = (m * 64 + lane) * VEC;
+                if (col < d) vload<VEC>(v[t][m], x + col);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+            if (j0 + t < n && go) {
+                go = keep(j0 + t);
+                if (go) {
+#pragma unroll
+                    for (int m = 0; m < CH; ++m) {
+                        const int col = (m * 64 + lane) * VEC;
+                        if (col < d) {
+#pragma unroll
+                            for (int i = 0; i < VEC; ++i) acc[m][i] = fmaf(av[t], v[t][m][i], acc[m][i]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int VEC, int CH> struct spmm_unroll { static constexpr int U = CH * VEC <= 4 ? 8 : (CH * VEC <= 8 ? 4 : 2); };
+
+// Wavefronts [0, n_piece_waves) take pieces of long rows (grid-stride over the pieces the plan
+// lists) and write one partial row per piece; the others take blocks of rows_per_wave rows.
 template <int VEC, int CH>
 __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const int32_t *__restrict__ rowptr,
                                                             const int32_t *__restrict__ colidx,
                                                             const float *__restrict__ val, uint64_t capacity,
                                                             const float *__restrict__ X, int64_t ldx,
                                                             const int32_t *__restrict__ row_index, int d,
-                                                            unsigned n_chunk_wgs, const uint32_t *__restrict__ n_chunks,
+                                                            unsigned n_piece_waves, const uint32_t *__restrict__ n_chunks,
                                                             uint32_t max_chunks, const uint2 *__restrict__ desc,
                                                             float *__restrict__ part, float *__restrict__ out, int64_t ldo,
-                                                            const float *__restrict__ bias, int relu, int lpr_log2)
+                                                            const float *__restrict__ bias, int relu, int rows_per_wave)
 {
-    __shared__ float red[SPMM_NT * VEC];
-    __shared__ int32_t s_src[SPMM_CHUNK];
-    __shared__ float s_val[SPMM_CHUNK];
-    const int lpr = 1 << lpr_log2;
-    const int G = SPMM_NT >> lpr_log2;
-    const int q = threadIdx.x >> lpr_log2;
-    const int g = threadIdx.x & (lpr - 1);
-    if (blockIdx.x < n_chunk_wgs) {
+    constexpr int U = spmm_unroll<VEC, CH>::U;
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave = blockIdx.x * (uint32_t)(SPMM_NT / 64) + (threadIdx.x >> 6);
+    const int32_t cap = (int32_t)min(capacity, (uint64_t)0x7fffffff);
+    if (wave < n_piece_waves) {
         const uint32_t total = min(*n_chunks, max_chunks);
-        for (uint32_t pc = blockIdx.x; pc < total; pc += n_chunk_wgs) {
+        for (uint32_t pc = wave; pc < total; pc += n_piece_waves) {
             const uint2 rc = desc[pc];
-            const int64_t rs = rowptr[rc.x], re = min((int64_t)rowptr[rc.x + 1], (int64_t)capacity);
-            const int64_t c0 = rs + (int64_t)rc.y * SPMM_CHUNK, c1 = min(re, c0 + SPMM_CHUNK);
-            if (c0 + threadIdx.x < c1) {
-                const int32_t cc = colidx[c0 + threadIdx.x];
-                s_src[threadIdx.x] = row_index ? row_index[cc] : cc;
-                s_val[threadIdx.x] = val[c0 + threadIdx.x];
+            const int re = min(rowptr[rc.x + 1], cap);
+            const int c0 = min(rowptr[rc.x], re) + (int)rc.y * SPMM_CHUNK;
+            const int n = max(0, min(re - c0, SPMM_CHUNK));
+            int32_t src = 0;
+            float a = 0.f;
+            if (lane < n) {
+                const int32_t c = colidx[c0 + lane];
+                a = val[c0 + lane];
+                src = row_index ? row_index[c] : c;
             }
-            __syncthreads();
             float acc[CH][VEC];
 #pragma unroll
             for (int m = 0; m < CH; ++m)
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[m][i] = 0.f;
-            const int nent = (int)(c1 - c0), per = (SPMM_CHUNK + G - 1) / G;
-            spmm_accumulate_staged<VEC, CH>(acc, s_src, s_val, min(nent, q * per), min(nent, (q + 1) * per), X, ldx, d, lpr, g);
-            spmm_reduce_store<VEC, CH>(acc, red, part + (int64_t)pc * d, d, lpr, G, q, g);   // ends with a barrier
+            spmm_wave_entries<VEC, CH, U>(acc, src, a, n, X, ldx, d, lane, [](int) { return true; });
+            float *o = part + (int64_t)pc * d;
+#pragma unroll
+            for (int m = 0; m < CH; ++m) {
+                const int col = (m * 64 + lane) * VEC;
+                if (col < d) vstore<VEC>(o + col, acc[m]);
+            }
         }
         return;
     }
-    const uint32_t row = (blockIdx.x - n_chunk_wgs) * (uint32_t)G + q;
-    if (row >= rows) return;
-    const int64_t re = min((int64_t)rowptr[row + 1], (int64_t)capacity);
-    const int64_t rs = min((int64_t)rowptr[row], re);
-    if (n_chunks && re - rs > (int64_t)n_chunks[1]) return;   // a long row: its chunks and the fix-up write it
-    float acc[CH][VEC];
-#pragma unroll
-    for (int m = 0; m < CH; ++m)
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[m][i] = 0.f;
-    spmm_accumulate<VEC, CH>(acc, colidx, val, rs, re, X, ldx, row_index, d, lpr, g);
-    float *o = out + (int64_t)row * ldo;
-#pragma unroll
-    for (int m = 0; m < CH; ++m) {
-        const int col = (m * lpr + g) * VEC;
-        if (col < d) {
-            spmm_epilogue<VEC>(acc[m], bias, relu, col);
-            vstore<VEC>(o + col, acc[m]);
-        }
-    }
+    spmm_wave_rows<VEC, CH>(rows, rowptr, colidx, val, cap, X, ldx, row_index, d, wave - n_piece_waves,
+                            n_chunks ? (int)n_chunks[2] : rows_per_wave, n_chunks ? (int)n_chunks[1] : 0x7fffffff, out, ldo, bias,
+                            relu);
 }
 
 // Long rows: a group of lpr lanes per row adds its partial rows up in chunk order.
@@ -383,14 +424,15 @@ template <int VEC, int CH>
 int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int d, float *out,
               int64_t ldo, const float *bias, int relu, int lpr_log2, ws_alloc *ws, hipStream_t st)
 {
-    const unsigned rows_per_block = (unsigned)SPMM_NT >> lpr_log2;
+    const int rows_per_wave = spmm_rows_per_wave(A->rows, A->capacity);   // lower bound of the plan's figure
+    const unsigned rows_per_block = (unsigned)(SPMM_NT / 64) * (unsigned)rows_per_wave;
     char tag[56];
     snprintf(tag, sizeof(tag), "%ux%u d=%d", A->rows, A->cols, d);
     const bool may_have_long = A->capacity > (uint64_t)SPMM_SHORT;
     spmm_plan_view pv = {nullptr, nullptr, nullptr};
     float *part = nullptr;
     uint32_t max_chunks = 0;
-    unsigned n_chunk_wgs = 0;
+    unsigned n_piece_waves = 0;
     if (may_have_long) {
         max_chunks = spmm_max_chunks(A->rows, A->capacity);
         void *plan = A->plan;
@@ -407,11 +449,11 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, con
         if (!ws->ok)
             return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_spmm: scratch too small (%zu bytes needed): call sgnn_ctx_reserve",
                              ws->off);
-        n_chunk_wgs = std::min<unsigned>(max_chunks, SPMM_CHUNK_WGS);
+        n_piece_waves = cdiv(std::min<unsigned>(max_chunks, SPMM_PIECE_WAVES), SPMM_NT / 64) * (SPMM_NT / 64);
     }
-    SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH>), dim3(n_chunk_wgs + cdiv(A->rows, rows_per_block)),
+    SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH>), dim3(n_piece_waves / (SPMM_NT / 64) + cdiv(A->rows, rows_per_block)),
                 dim3(SPMM_NT), 0, st, A->rows, A->rowptr, A->colidx, A->val, A->capacity, X, ldx, row_index, d,
-                n_chunk_wgs, pv.n_chunks, max_chunks, pv.desc, part, out, ldo, bias, relu, lpr_log2);
+                n_piece_waves, pv.n_chunks, max_chunks, pv.desc, part, out, ldo, bias, relu, rows_per_wave);
     if (may_have_long) {
         const unsigned groups = 256u >> lpr_log2;
         SGNN_LAUNCH(ctx, st, "spmm_fixup_kernel", tag, (spmm_fixup_kernel<VEC, CH>),
@@ -468,9 +510,14 @@ int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t l
 {
     if (A->rows == 0 || d == 0) return SGNN_OK;
     const uintptr_t bits = reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(out);
-    if (d % 4 == 0 && ldx % 4 == 0 && ldo % 4 == 0 && (bits & 15) == 0)
+    // the narrowest vector with which one wavefront still covers the row
+    const bool ok4 = d % 4 == 0 && ldx % 4 == 0 && ldo % 4 == 0 && (bits & 15) == 0;
+    const bool ok2 = d % 2 == 0 && ldx % 2 == 0 && ldo % 2 == 0 && (bits & 7) == 0;
+    if (d <= 64) return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
+    if (d <= 128 && ok2) return launch_v<2>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
+    if (ok4)
         return launch_v<4>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
-    if (d % 2 == 0 && ldx % 2 == 0 && ldo % 2 == 0 && (bits & 7) == 0)
+    if (ok2)
         return launch_v<2>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
     return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
 }
