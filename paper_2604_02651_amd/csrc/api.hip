@@ -70,6 +70,8 @@ bool csr_ok(const sgnn_csr *c) { return c && c->rowptr && (c->capacity == 0 || (
 
 } // namespace
 
+static inline int64_t pad4(int64_t d) { return (d + 3) & ~int64_t(3); }
+
 extern "C" {
 
 int sgnn_ctx_create(sgnn_ctx **out, int device)
@@ -122,7 +124,7 @@ int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t
     size_t need = sgnn_sampler_ws_bytes(N);
     need = std::max(need, sgnn_induced_ws_bytes(E, B));
     // backward: dZ and dT (B x d_max each), split-K partials, column-sum partials
-    size_t layer = (size_t)2 * B * d_max * 4 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 +
+    size_t layer = (size_t)2 * B * pad4(d_max) * 4 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 +
                    sgnn_spmm_ws_bytes(max_entries, B, d_max) + 16 * 256;
     need = std::max(need, layer);
     need = std::max(need, (size_t)B / 64 * 4 + 4096);
@@ -328,12 +330,13 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
     }
     // A (H W): transform first (the aggregation then runs at width d_out), bias and activation
     // fused into the sparse product
-    float *P = ws.get<float>((size_t)A->cols * d_out);
+    const int64_t ldp = pad4(d_out);   // rows of the scratch matrices start 16-byte aligned
+    float *P = ws.get<float>((size_t)A->cols * ldp);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_fwd: scratch too small: call sgnn_ctx_reserve");
     rc = sgnn_launch_gemm(ctx, 0, 0, A->cols, d_out, d_in, static_cast<const float *>(H->ptr), H->ld, H->row_index,
-                          static_cast<const float *>(W->ptr), W->ld, nullptr, flags & SGNN_BF16_MFMA, P, d_out, &ws, st);
+                          static_cast<const float *>(W->ptr), W->ld, nullptr, flags & SGNN_BF16_MFMA, P, ldp, &ws, st);
     if (rc) return rc;
-    return sgnn_launch_spmm(ctx, A, P, d_out, nullptr, d_out, static_cast<float *>(Y->ptr), Y->ld, bias,
+    return sgnn_launch_spmm(ctx, A, P, ldp, nullptr, d_out, static_cast<float *>(Y->ptr), Y->ld, bias,
                             (flags & SGNN_RELU) ? 1 : 0, &ws, st);
 }
 
@@ -356,6 +359,7 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     hipStream_t st = static_cast<hipStream_t>(stream);
     ws_alloc ws(ctx);
     const int mfma = flags & SGNN_BF16_MFMA;
+    const int64_t ld_out = pad4(d_out), ld_in = pad4(d_in);   // rows of the scratch matrices start 16-byte aligned
 
     // element-wise backward: ReLU mask and bias gradient
     const float *dZ = static_cast<const float *>(dY->ptr);
@@ -363,14 +367,14 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     if (relu || dbias) {
         float *dZbuf = nullptr;
         if (relu) {
-            dZbuf = ws.get<float>((size_t)Bn * d_out);
+            dZbuf = ws.get<float>((size_t)Bn * ld_out);
             if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
         }
         rc = sgnn_launch_relu_bwd_bias(ctx, relu ? static_cast<const float *>(Y->ptr) : nullptr, relu ? Y->ld : 0,
-                                       static_cast<const float *>(dY->ptr), dY->ld, relu, Bn, d_out, dZbuf, d_out, dbias,
+                                       static_cast<const float *>(dY->ptr), dY->ld, relu, Bn, d_out, dZbuf, ld_out, dbias,
                                        &ws, st);
         if (rc) return rc;
-        if (relu) { dZ = dZbuf; lddz = d_out; }
+        if (relu) { dZ = dZbuf; lddz = ld_out; }
     }
     if (!xform_first) {
         // dW = T^T dZ
@@ -379,27 +383,27 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
         if (rc) return rc;
         if (dH) {
             // dT = dZ W^T, dH = A^T dT
-            float *dT = ws.get<float>((size_t)Bn * d_in);
+            float *dT = ws.get<float>((size_t)Bn * ld_in);
             if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
             rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, nullptr, static_cast<const float *>(W->ptr), W->ld,
-                                  nullptr, mfma, dT, d_in, &ws, st);
+                                  nullptr, mfma, dT, ld_in, &ws, st);
             if (rc) return rc;
-            rc = sgnn_launch_spmm(ctx, A_T, dT, d_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, &ws,
+            rc = sgnn_launch_spmm(ctx, A_T, dT, ld_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, &ws,
                                   st);
             if (rc) return rc;
         }
         return SGNN_OK;
     }
     // transform-first layer: dP = A^T dZ (width d_out), dW = H^T dP, dH = dP W^T; T is the layer input H
-    float *dP = ws.get<float>((size_t)Bn * d_out);
+    float *dP = ws.get<float>((size_t)Bn * ld_out);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
-    rc = sgnn_launch_spmm(ctx, A_T, dZ, lddz, nullptr, d_out, dP, d_out, nullptr, 0, &ws, st);
+    rc = sgnn_launch_spmm(ctx, A_T, dZ, lddz, nullptr, d_out, dP, ld_out, nullptr, 0, &ws, st);
     if (rc) return rc;
-    rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, T->row_index, dP, d_out,
+    rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, T->row_index, dP, ld_out,
                           nullptr, mfma, dW, d_out, &ws, st);
     if (rc) return rc;
     if (dH)
-        rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dP, d_out, nullptr, static_cast<const float *>(W->ptr), W->ld,
+        rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dP, ld_out, nullptr, static_cast<const float *>(W->ptr), W->ld,
                               nullptr, mfma, static_cast<float *>(dH->ptr), dH->ld, &ws, st);
     return rc;
 }

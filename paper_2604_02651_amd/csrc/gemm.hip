@@ -16,6 +16,8 @@
 //   result register r of lane (kh, j) is C[8*(r/4) + 4*kh + r%4][j].
 // The order in which the reduction index is fed is free as long as both operands agree, so for fp32
 // the slice of 16 is fed as k = 8*kh + s at step s: every lane then reads 8 consecutive values.
+#include <algorithm>
+
 #include "common.h"
 
 #ifndef SGNN_GEMM_BK_F32
@@ -40,7 +42,27 @@ struct gemm_args {
     int alignedA, alignedB;   // 16-byte aligned base and leading dimension a multiple of 4
     int64_t k_per_split;      // reduction range of one blockIdx.z (a multiple of BK); K when unsplit
     float *partial;           // split-K: [splits][M][N] partial products, else NULL
+    uint32_t mtiles, ntiles, splits;   // the tile grid, walked by tile_of_block()
 };
+
+// Tile of a workgroup.  The grid is one-dimensional and the hardware hands consecutive workgroup
+// numbers to the eight XCDs in turn, each with an L2 of its own.  Tiles that read the same
+// operand data form a group (the column tiles of one row block; with a split reduction all tiles
+// of one reduction range) and are numbered so that a group's members run on one XCD next to each
+// other: the shared rows then come from HBM once and from that L2 afterwards.
+struct gemm_tile { uint32_t bx, by, bz; bool valid; };
+__device__ __forceinline__ gemm_tile tile_of_block(const gemm_args &a)
+{
+    const uint32_t members = a.splits > 1 ? a.mtiles * a.ntiles : a.ntiles;
+    const uint32_t groups = a.splits > 1 ? a.splits : a.mtiles;
+    const uint32_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const uint32_t group = (slot / members) * 8 + xcd, mem = slot % members;
+    gemm_tile t;
+    t.valid = group < groups;
+    if (a.splits > 1) { t.bz = group; t.bx = mem % a.mtiles; t.by = mem / a.mtiles; }
+    else              { t.bz = 0; t.bx = group; t.by = mem; }
+    return t;
+}
 
 __device__ __forceinline__ u16 to_bf16_bits(float x)
 {
@@ -152,8 +174,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 31, kh = lane >> 5;
     const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
-    const int64_t m0 = (int64_t)blockIdx.x * BM, n0 = (int64_t)blockIdx.y * BN;
-    const int64_t kbeg = (int64_t)blockIdx.z * a.k_per_split;
+    const gemm_tile tb_ = tile_of_block(a);
+    if (!tb_.valid) return;
+    const int64_t m0 = (int64_t)tb_.bx * BM, n0 = (int64_t)tb_.by * BN;
+    const int64_t kbeg = (int64_t)tb_.bz * a.k_per_split;
     const int64_t kend = min(a.K, kbeg + a.k_per_split);
 
     f32x16 acc[TM][TN];
@@ -240,7 +264,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
     }
 
     // epilogue
-    float *Cout = a.partial ? a.partial + (int64_t)blockIdx.z * a.M * a.N : a.C;
+    float *Cout = a.partial ? a.partial + (int64_t)tb_.bz * a.M * a.N : a.C;
     const int64_t ldc = a.partial ? a.N : a.ldc;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -262,7 +286,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast fp32 path: every 16-byte chunk of an operand is either wholly inside the matrix or wholly
+// Fast path: every 16-byte chunk of an operand is either wholly inside the matrix or wholly
 // outside (leading dimensions, pointers and the contiguous extents are multiples of four), so
 // the fetch is branch-free: rows past the edge are clamped to the last row (they only feed
 // results that are never stored) and the reduction tail is zeroed with selects.  LDS is double
@@ -384,10 +408,64 @@ __device__ __forceinline__ void mma_slice(f32x16 (&acc)[WM / 32][WN / 32], const
     }
 }
 
+// The same for the bf16 path, 32x32x16 MFMAs.  An operand staged reduction-contiguous lies in LDS
+// as bfloat16 ([R][BK+8], one 16-byte load per lane and tile); an operand staged [BK][R+4] stays
+// fp32 in LDS, tiles interleaved as above, and is rounded to bfloat16 when it is read.
+template <int BM, int BN, int WM, int WN, int BK, bool A_RC, bool B_RC>
+__device__ __forceinline__ void mma_slice_bf16(f32x16 (&acc)[WM / 32][WN / 32], const void *LAv, const void *LBv, int wm0,
+                                               int wn0, int li, int kh)
+{
+    constexpr int TM = WM / 32, TN = WN / 32;
+#pragma unroll
+    for (int s = 0; s < BK / 16; ++s) {
+        bf16x8 av[TM], bv[TN];
+        if constexpr (A_RC) {
+            const u16 *LA = static_cast<const u16 *>(LAv);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                av[i] = *reinterpret_cast<const bf16x8 *>(LA + (wm0 + 32 * i + li) * (BK + 8) + 16 * s + 8 * kh);
+        } else {
+            const float *LA = static_cast<const float *>(LAv);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const typename fvec<TM>::type x =
+                    *reinterpret_cast<const typename fvec<TM>::type *>(LA + (16 * s + 8 * kh + t) * (BM + 4) + wm0 + TM * li);
+                if constexpr (TM == 1) av[0][t] = (__bf16)x;
+                else {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) av[i][t] = (__bf16)x[i];
+                }
+            }
+        }
+        if constexpr (B_RC) {
+            const u16 *LB = static_cast<const u16 *>(LBv);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                bv[j] = *reinterpret_cast<const bf16x8 *>(LB + (wn0 + 32 * j + li) * (BK + 8) + 16 * s + 8 * kh);
+        } else {
+            const float *LB = static_cast<const float *>(LBv);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const typename fvec<TN>::type x =
+                    *reinterpret_cast<const typename fvec<TN>::type *>(LB + (16 * s + 8 * kh + t) * (BN + 4) + wn0 + TN * li);
+                if constexpr (TN == 1) bv[0][t] = (__bf16)x;
+                else {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) bv[j][t] = (__bf16)x[j];
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+    }
+}
+
 // Pipeline: slice s+2 is fetched from memory into registers while slice s is multiplied from LDS
 // buffer s & 1; the registers are stored to the other buffer after the multiply, so there is one
 // barrier per slice.
-template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, bool BF16>
 __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
 {
     constexpr int BK = 32;
@@ -397,16 +475,19 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
     constexpr bool A_RC = !TA, B_RC = TB;
     using gA = fetch_geom<BM, BK, A_RC>;
     using gB = fetch_geom<BN, BK, B_RC>;
-    constexpr int LA_ELEMS = lds_geom<BM, BK, A_RC, false>::ELEMS;
-    constexpr int LB_ELEMS = lds_geom<BN, BK, B_RC, false>::ELEMS;
-    __shared__ __attribute__((aligned(16))) float ldsA[2][LA_ELEMS];
-    __shared__ __attribute__((aligned(16))) float ldsB[2][LB_ELEMS];
+    constexpr bool A16 = BF16 && A_RC, B16 = BF16 && B_RC;   // staged as bfloat16 (else fp32)
+    constexpr int LA_BYTES = lds_geom<BM, BK, A_RC, A16>::BYTES;
+    constexpr int LB_BYTES = lds_geom<BN, BK, B_RC, B16>::BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char ldsA[2][LA_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char ldsB[2][LB_BYTES];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 31, kh = lane >> 5;
     const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
-    const int64_t m0 = (int64_t)blockIdx.x * BM, n0 = (int64_t)blockIdx.y * BN;
-    const int64_t kbeg = (int64_t)blockIdx.z * a.k_per_split;
+    const gemm_tile tb_ = tile_of_block(a);
+    if (!tb_.valid) return;
+    const int64_t m0 = (int64_t)tb_.bx * BM, n0 = (int64_t)tb_.by * BN;
+    const int64_t kbeg = (int64_t)tb_.bz * a.k_per_split;
     const int64_t kend = min(a.K, kbeg + a.k_per_split);
     const int nslices = (int)((kend - kbeg + BK - 1) / BK);
 
@@ -426,8 +507,8 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
     auto stage = [&](int s) {
         mask_fast<BM, BK, A_RC>(ra, kbeg + (int64_t)s * BK, kend);
         mask_fast<BN, BK, B_RC>(rb, kbeg + (int64_t)s * BK, kend);
-        store_operand<BM, BK, A_RC, false>(ldsA[s & 1], ra);
-        store_operand<BN, BK, B_RC, false>(ldsB[s & 1], rb);
+        store_operand<BM, BK, A_RC, A16>(ldsA[s & 1], ra);
+        store_operand<BN, BK, B_RC, B16>(ldsB[s & 1], rb);
     };
     if (nslices > 0) {
         fetch(0);
@@ -436,7 +517,10 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
     }
     __syncthreads();
     for (int it = 0; it < nslices; ++it) {
-        mma_slice<BM, BN, WM, WN, BK, A_RC, B_RC>(acc, ldsA[it & 1], ldsB[it & 1], wm0, wn0, li, kh);
+        if constexpr (BF16) mma_slice_bf16<BM, BN, WM, WN, BK, A_RC, B_RC>(acc, ldsA[it & 1], ldsB[it & 1], wm0, wn0, li, kh);
+        else
+            mma_slice<BM, BN, WM, WN, BK, A_RC, B_RC>(acc, reinterpret_cast<const float *>(ldsA[it & 1]),
+                                                      reinterpret_cast<const float *>(ldsB[it & 1]), wm0, wn0, li, kh);
         if (it + 1 < nslices) {
             // the other buffer was last read in iteration it-1, which every wave has left
             stage(it + 1);
@@ -445,7 +529,7 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
         __syncthreads();
     }
 
-    float *Cout = a.partial ? a.partial + (int64_t)blockIdx.z * a.M * a.N : a.C;
+    float *Cout = a.partial ? a.partial + (int64_t)tb_.bz * a.M * a.N : a.C;
     const int64_t ldc = a.partial ? a.N : a.ldc;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -465,6 +549,239 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
                 }
             }
         }
+}
+
+// ---------------------------------------------------------------------------------------------
+// bf16 path, tall A and a small B (K <= 256, N <= 256: the layer transform and the feature
+// gradient of a mini-batch with hundreds of thousands of rows).  The product is bound by reading
+// A and writing C once, so the kernel is built around that stream:
+//  - B is rounded to bfloat16 once per workgroup and stays in LDS ([n][K rounded up + 8]) for the
+//    whole launch; workgroups are persistent and walk blocks of 256 rows;
+//  - a wavefront owns 32 rows of the block and all N columns.  It reads its rows in slices of 32
+//    along K with full 128-byte row segments, up to four slices ahead in registers, turns a
+//    slice into MFMA operand order through an LDS patch of its own (no workgroup barrier), and
+//    keeps the 32 x N accumulators in registers until the row block is complete.
+// ---------------------------------------------------------------------------------------------
+constexpr int SKINNY_WAVES = 8;
+constexpr int SKINNY_PATCH = 32 * 40;   // 16-bit elements of a wavefront's patch: [32][32 + 8]
+
+inline size_t skinny_lds_bytes(int nt8, int kp)
+{
+    return ((size_t)32 * nt8 * kp + (size_t)SKINNY_WAVES * SKINNY_PATCH) * 2 + (size_t)32 * nt8 * sizeof(float);
+}
+
+// NT8 = column tiles of 32 (N <= 32 NT8), S = slices of 32 along the reduction (K <= 32 S).  Both are
+// compile-time so that the order of every load and store of a row block is fixed: the waits on the
+// slices in flight then count exactly the operations issued after them.
+template <int NT8, int S>
+__global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gemm_args a, int tb, uint32_t n_rowblocks)
+{
+    constexpr int D = S == 8 ? 4 : (S == 6 ? 3 : S);   // slices in flight; divides S
+    constexpr int KP = 32 * S + 8;                      // row length of B in LDS
+    constexpr int NP = 32 * NT8;
+    extern __shared__ __attribute__((aligned(16))) unsigned char skinny_smem[];
+    u16 *LB = reinterpret_cast<u16 *>(skinny_smem);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 31, kh = lane >> 5;
+    u16 *LA = LB + NP * KP + wave * SKINNY_PATCH;
+    const int K = (int)a.K, N = (int)a.N;
+
+    // B -> LDS as bfloat16, zero beyond N and K; eight loads in flight per thread
+    constexpr int NTHR = 64 * SKINNY_WAVES;
+    if (a.alignedB && (tb ? K : N) % 4 == 0) {
+        constexpr int CHUNKS = NP * 8 * S;   // 16-byte chunks of the padded B
+        for (int base = threadIdx.x; base < CHUNKS; base += 8 * NTHR) {
+            f32x4 x[8];
+            int n[8], k[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * NTHR;
+                if (tb) {   // B given N x K: a chunk is four k of one n
+                    n[u] = idx / (8 * S);
+                    k[u] = 4 * (idx % (8 * S));
+                } else {    // B given K x N: a chunk is four n of one k; 8 chunks x 8 k per wavefront load
+                    const int rest = idx >> 6;
+                    n[u] = 32 * (rest % NT8) + 4 * (idx & 7);
+                    k[u] = 8 * (rest / NT8) + ((idx >> 3) & 7);
+                }
+                x[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (idx < CHUNKS && n[u] < N && k[u] < K)
+                    x[u] = *reinterpret_cast<const f32x4 *>(tb ? a.B + (int64_t)n[u] * a.ldb + k[u] : a.B + (int64_t)k[u] * a.ldb + n[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (base + u * NTHR >= CHUNKS) continue;
+                if (tb) {
+                    uint2 w;
+                    w.x = (uint32_t)to_bf16_bits(x[u][0]) | ((uint32_t)to_bf16_bits(x[u][1]) << 16);
+                    w.y = (uint32_t)to_bf16_bits(x[u][2]) | ((uint32_t)to_bf16_bits(x[u][3]) << 16);
+                    *reinterpret_cast<uint2 *>(LB + n[u] * KP + k[u]) = w;
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) LB[(n[u] + c) * KP + k[u]] = to_bf16_bits(x[u][c]);
+                }
+            }
+        }
+    } else {
+        for (int base = threadIdx.x; base < NP * 32 * S; base += 8 * NTHR) {
+            float x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * NTHR;
+                const int n = tb ? idx / (32 * S) : idx % NP, k = tb ? idx % (32 * S) : idx / NP;
+                x[u] = 0.f;
+                if (idx < NP * 32 * S && n < N && k < K) x[u] = tb ? a.B[(int64_t)n * a.ldb + k] : a.B[(int64_t)k * a.ldb + n];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * NTHR;
+                const int n = tb ? idx / (32 * S) : idx % NP, k = tb ? idx % (32 * S) : idx / NP;
+                if (idx < NP * 32 * S) LB[n * KP + k] = to_bf16_bits(x[u]);
+            }
+        }
+    }
+    float *Lbias = reinterpret_cast<float *>(LB + NP * KP + SKINNY_WAVES * SKINNY_PATCH);   // kept in LDS: no load in the stream
+    for (int n = threadIdx.x; n < NP; n += 64 * SKINNY_WAVES) Lbias[n] = (a.bias && n < N) ? a.bias[n] : 0.f;
+    __syncthreads();
+
+    f32x16 acc[NT8];
+#pragma unroll
+    for (int j = 0; j < NT8; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    const bool relu = a.relu != 0;
+
+    // loads: lane -> rows lr + 8 v (v = 0..3) of the wavefront's 32, 16-byte chunk kc of the slice
+    const int lr = lane >> 3, kc = lane & 7;
+    const int last_chunk = (K - 1) & ~3;
+    const float *rowp[4];
+    auto row_pointers = [&](uint32_t rb) {   // a row block past the end repeats the last one (loaded, never used)
+        rb = min(rb, n_rowblocks - 1);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            int64_t row = min((int64_t)rb * (32 * SKINNY_WAVES) + wave * 32 + lr + 8 * v, a.M - 1);
+            if (a.a_row_index) row = a.a_row_index[row];
+            rowp[v] = a.A + row * a.lda;
+        }
+    };
+    auto issue = [&](f32x4 (&r)[4], int slice) {
+        const int k = min(32 * slice + 4 * kc, last_chunk);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) r[v] = *reinterpret_cast<const f32x4 *>(rowp[v] + k);
+    };
+    auto stage = [&](f32x4 (&r)[4], int slice) {
+        const int k = 32 * slice + 4 * kc;
+        if (k + 4 > K) {     // the ragged end of the reduction
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (k + e >= K) r[v][e] = 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            uint2 w;
+            w.x = (uint32_t)to_bf16_bits(r[v][0]) | ((uint32_t)to_bf16_bits(r[v][1]) << 16);
+            w.y = (uint32_t)to_bf16_bits(r[v][2]) | ((uint32_t)to_bf16_bits(r[v][3]) << 16);
+            *reinterpret_cast<uint2 *>(LA + (lr + 8 * v) * 40 + 4 * kc) = w;
+        }
+    };
+    auto multiply = [&](int slice) {
+        bf16x8 av[2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) av[ks] = *reinterpret_cast<const bf16x8 *>(LA + li * 40 + 16 * ks + 8 * kh);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int j = 0; j < NT8; ++j) {
+                const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(LB + (32 * j + li) * KP + 32 * slice + 16 * ks + 8 * kh);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ks], bv, acc[j], 0, 0, 0);
+            }
+    };
+
+    f32x4 ring[D][4];
+    row_pointers(blockIdx.x);
+#pragma unroll
+    for (int u = 0; u < D; ++u) issue(ring[u], u);
+    for (uint32_t rb = blockIdx.x; rb < n_rowblocks; rb += gridDim.x) {
+#pragma unroll
+        for (int sl = 0; sl < S; ++sl) {
+            stage(ring[sl % D], sl);
+            if (sl + D == S) row_pointers(rb + gridDim.x);       // the loads from here on belong to the next row block
+            issue(ring[sl % D], (sl + D) % S);
+            multiply(sl);
+        }
+        // the row block is complete: write it
+        const int64_t wrow = (int64_t)rb * (32 * SKINNY_WAVES) + wave * 32;
+        const int64_t row0 = wrow + 4 * kh;   // the lane's first row
+        float *cl = a.C + row0 * a.ldc + li;
+        if (wrow + 32 <= a.M) {
+#pragma unroll
+            for (int j = 0; j < NT8; ++j) {
+                if (32 * j + li < N) {
+                    const float bj = Lbias[32 * j + li];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float z = acc[j][r] + bj;
+                        cl[(int64_t)(8 * (r / 4) + (r % 4)) * a.ldc + 32 * j] = relu ? fmaxf(z, 0.f) : z;
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NT8; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int rr = 8 * (r / 4) + (r % 4);
+                    const float z = acc[j][r] + Lbias[32 * j + li];
+                    if (32 * j + li < N && row0 + rr < a.M) cl[(int64_t)rr * a.ldc + 32 * j] = relu ? fmaxf(z, 0.f) : z;
+                }
+        }
+#pragma unroll
+        for (int j = 0; j < NT8; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    }
+}
+
+template <int NT8, int S>
+int launch_skinny_ns(sgnn_ctx *ctx, const gemm_args &a, int tb, hipStream_t st)
+{
+    const size_t lds = skinny_lds_bytes(NT8, 32 * S + 8);
+    static bool attr_set = false;
+    if (!attr_set) {
+        SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny_bf16_kernel<NT8, S>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        attr_set = true;
+    }
+    const uint32_t n_rowblocks = (uint32_t)cdiv(a.M, 32 * SKINNY_WAVES);
+    char tag[56];
+    snprintf(tag, sizeof(tag), "N%c skinny %lldx%lldx%lld bf16", tb ? 'T' : 'N', (long long)a.M, (long long)a.N, (long long)a.K);
+    SGNN_LAUNCH(ctx, st, "gemm_skinny_bf16_kernel", tag, (gemm_skinny_bf16_kernel<NT8, S>),
+                dim3(std::min<uint32_t>(n_rowblocks, 256)), dim3(64 * SKINNY_WAVES), lds, st, a, tb, n_rowblocks);
+    return SGNN_OK;
+}
+
+template <int NT8>
+int launch_skinny_n(sgnn_ctx *ctx, const gemm_args &a, int tb, hipStream_t st)
+{
+    const int s2 = (int)((a.K + 63) / 64);   // slices, rounded up to an even count
+    switch (s2) {
+    case 1: return launch_skinny_ns<NT8, 2>(ctx, a, tb, st);
+    case 2: return launch_skinny_ns<NT8, 4>(ctx, a, tb, st);
+    case 3: return launch_skinny_ns<NT8, 6>(ctx, a, tb, st);
+    default: return launch_skinny_ns<NT8, 8>(ctx, a, tb, st);
+    }
+}
+
+int launch_skinny(sgnn_ctx *ctx, const gemm_args &a, int tb, hipStream_t st)
+{
+    switch ((int)((a.N + 63) / 64)) {   // column tiles, rounded up to an even count
+    case 1: return launch_skinny_n<2>(ctx, a, tb, st);
+    case 2: return launch_skinny_n<4>(ctx, a, tb, st);
+    case 3: return launch_skinny_n<6>(ctx, a, tb, st);
+    default: return launch_skinny_n<8>(ctx, a, tb, st);
+    }
 }
 
 // Sum of the split-K partial products in a fixed order (bit-reproducible).
@@ -488,20 +805,36 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 }
 
 template <int BM, int BN, int WM, int WN>
-int launch_cfg(sgnn_ctx *ctx, int ta, int tb, int bf16, const gemm_args &a, int splits, hipStream_t st)
+int launch_cfg(sgnn_ctx *ctx, int ta, int tb, int bf16, gemm_args a, int splits, hipStream_t st)
 {
-    dim3 grid(cdiv(a.M, BM), cdiv(a.N, BN), splits), block(256);
+    a.mtiles = (uint32_t)cdiv(a.M, BM);
+    a.ntiles = (uint32_t)cdiv(a.N, BN);
+    a.splits = (uint32_t)splits;
+    const uint64_t members = splits > 1 ? (uint64_t)a.mtiles * a.ntiles : a.ntiles;
+    const uint64_t groups = splits > 1 ? (uint64_t)splits : a.mtiles;
+    const uint64_t nblocks = cdiv(groups, 8) * 8 * members;
+    if (nblocks > 0x7fffffffull) return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gemm: more than 2^31 tiles");
+    dim3 grid((unsigned)nblocks), block(256);
     char tag[56];
-    // fast path: fp32, every 16-byte chunk wholly inside or outside the operands
+    // fast path: every 16-byte chunk wholly inside or outside the operands
     const int64_t a_contig = ta ? a.M : a.K, b_contig = tb ? a.K : a.N;
-    const bool fast = !bf16 && a.alignedA && a.alignedB && a_contig % 4 == 0 && b_contig % 4 == 0 && a_contig >= 4 &&
-                      b_contig >= 4 && a.K >= 1 && a.M >= 1 && a.N >= 1;
-    if (fast) {
-        snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld f32", ta ? 'T' : 'N', tb ? 'T' : 'N', BM, BN, (long long)a.M,
-                 (long long)a.N, (long long)a.K);
-        if (!ta && !tb) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, false, false>), grid, block, 0, st, a); return SGNN_OK; }
-        if (!ta && tb) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, false, true>), grid, block, 0, st, a); return SGNN_OK; }
-        if (ta && !tb) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, true, false>), grid, block, 0, st, a); return SGNN_OK; }
+    const bool fast = a.alignedA && a.alignedB && a_contig % 4 == 0 && b_contig % 4 == 0 && a_contig >= 4 && b_contig >= 4 &&
+                      a.K >= 1 && a.M >= 1 && a.N >= 1;
+    if (fast && !(ta && tb)) {
+        snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld %s", ta ? 'T' : 'N', tb ? 'T' : 'N', BM, BN, (long long)a.M,
+                 (long long)a.N, (long long)a.K, bf16 ? "bf16" : "f32");
+#define SGNN_GEMM_FAST(TA_, TB_, BF_)                                                                              \
+    if (ta == TA_ && tb == TB_ && bf16 == BF_) {                                                                   \
+        SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, TA_, TB_, BF_>), grid, block, 0, st, a); \
+        return SGNN_OK;                                                                                            \
+    }
+        SGNN_GEMM_FAST(false, false, false)
+        SGNN_GEMM_FAST(false, true, false)
+        SGNN_GEMM_FAST(true, false, false)
+        SGNN_GEMM_FAST(false, false, true)
+        SGNN_GEMM_FAST(false, true, true)
+        SGNN_GEMM_FAST(true, false, true)
+#undef SGNN_GEMM_FAST
     }
     snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld %s", ta ? 'T' : 'N', tb ? 'T' : 'N', BM, BN, (long long)a.M,
              (long long)a.N, (long long)a.K, bf16 ? "bf16" : "f32");
@@ -539,6 +872,10 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     a.partial = nullptr;
     const int bf16 = (flags & SGNN_BF16_MFMA) ? 1 : 0;
     const int BK = bf16 ? 32 : SGNN_GEMM_BK_F32;
+
+    // tall A times a small B on the bf16 path: stream A once with B resident in LDS
+    if (bf16 && !ta && K >= 1 && K <= 256 && N >= 1 && N <= 256 && M >= 4096 && a.alignedA)
+        return launch_skinny(ctx, a, tb, st);
 
     // tile shape by the width of C
     const int bn = N > 64 ? 128 : (N > 32 ? 64 : 32);

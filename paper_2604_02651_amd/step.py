@@ -44,11 +44,12 @@ class GcnStep:
         # a layer that narrows (d_out < d_in) is evaluated transform-first: its sparse products run at
         # width d_out, and its backward pass needs the layer input instead of the aggregate
         self.xform_first = [auto_order and dims[l + 1] < dims[l] for l in range(self.L)]
-        self.T = [None if self.xform_first[l] else torch.empty((B, dims[l]), dtype=torch.float32, device=dev)
-                  for l in range(self.L)]
-        self.H = [torch.empty((B, dims[l + 1]), dtype=torch.float32, device=dev) for l in range(self.L)]
-        self.dH = [torch.empty((B, dims[l]), dtype=torch.float32, device=dev) if l > 0 else None for l in range(self.L)]
-        self.dO = torch.empty((B, dims[-1]), dtype=torch.float32, device=dev)
+        def mat(d):   # B x d with rows starting 16-byte aligned (leading dimension a multiple of 4)
+            return torch.empty((B, (d + 3) // 4 * 4), dtype=torch.float32, device=dev)[:, :d]
+        self.T = [None if self.xform_first[l] else mat(dims[l]) for l in range(self.L)]
+        self.H = [mat(dims[l + 1]) for l in range(self.L)]
+        self.dH = [mat(dims[l]) if l > 0 else None for l in range(self.L)]
+        self.dO = mat(dims[-1])
         self.dW = [torch.empty_like(w) for w, _ in weights]
         self.db = [torch.empty_like(b) for _, b in weights]
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)

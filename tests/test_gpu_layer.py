@@ -165,6 +165,24 @@ def test_gemm_long_reduction_is_split_and_reproducible(bf16):
     assert torch.equal(C, C2)
 
 
+@pytest.mark.parametrize("M,N,K,ldpad", [(5000, 256, 256, 0), (4100, 47, 256, 0), (9000, 172, 128, 4), (4097, 256, 100, 0),
+                                         (6000, 256, 47, 1), (4608, 64, 32, 0), (4096, 200, 172, 0), (70000, 256, 256, 0)])
+def test_gemm_bf16_tall_operand(M, N, K, ldpad):
+    # tall A, small B: the shape of the layer transform and of the feature gradient of a large mini-batch
+    # (ldpad: extra columns behind A's rows, holding values that must not enter the product)
+    A = _rand((M, K + ldpad), 11); Bm = _rand((K, N), 12); Bt = _rand((N, K), 13); bias = _rand(N, 14)
+    Ad = dev(A)[:, :K]
+    Ar = oracle.round_bf16(A[:, :K])
+    Cfull = torch.full((M, N + 3), 9.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), False, False, Ad, dev(Bm), dev(bias), sg.SGNN_RELU | sg.SGNN_BF16_MFMA, Cfull[:, :N])
+    ref = np.maximum(oracle.gemm(Ar, oracle.round_bf16(Bm)) + bias, 0)
+    assert rel_err(Cfull[:, :N].cpu().numpy(), ref) < 1e-4
+    assert torch.all(Cfull[:, N:] == 9.0)
+    C = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), False, True, Ad, dev(Bt), None, sg.SGNN_BF16_MFMA, C)
+    assert rel_err(C.cpu().numpy(), oracle.gemm(Ar, oracle.round_bf16(Bt).T.copy())) < 1e-4
+
+
 def test_gemm_bf16_rounding_is_nearest_even():
     # K = 1 against a one: the product is the rounded operand itself
     x = np.concatenate([_rand(4000, 10), np.array([1.00390625, 1.01171875, -1.00390625, 0.0, 3.0e38], np.float32)])
