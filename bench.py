@@ -120,21 +120,25 @@ def main():
     nnz_avg = nnz_total / nprof
     groups = {}
     for name, tag, calls, ms in recs:
-        key = name
+        key = name   # one group per kernel symbol, as rocprofv3 lists them
         if name == "gemm_kernel":
             p = tag.split()
             key = "gemm_kernel<%s,%s,%s>" % (p[1], p[0], p[3])
+        elif name in ("spmm_main_kernel", "spmm_fixup_kernel"):
+            key = name + tag.split()[2]
         gq = groups.setdefault(key, {"calls": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
         gq["calls"] += calls
         gq["ms"] += ms
         if name == "gemm_kernel":
             gq["flops"] += gemm_flops(tag) * calls
         elif name == "spmm_main_kernel":
-            d = int(tag.split("d=")[1])
+            d = int(tag.split("d=")[1].split()[0])
             # compulsory traffic: CSR once, every input row once, the output once
             gq["bytes"] += calls * (8.0 * nnz_avg + 4.0 * (cfg.B + 1) + 2.0 * cfg.B * d * 4)
     total_ms = sum(v["ms"] for v in groups.values())
     dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
+    sp = [v for k, v in groups.items() if k.startswith("spmm_main_kernel")]
+    sparse_ms, sparse_bytes = sum(v["ms"] for v in sp), sum(v["bytes"] for v in sp)
     if args.breakdown:
         for name, tag, calls, ms in recs:
             if name.startswith("spmm"):
@@ -165,6 +169,9 @@ def main():
     roofline["avg_launch_us"] = 1e3 * dom["ms"] / dom["calls"]
     roofline["launches_per_step"] = dom["calls"] / nprof
     roofline["share_of_kernel_time"] = dom["ms"] / total_ms if total_ms > 0 else None
+    # the sparse products as a whole (all widths), the other large group
+    roofline["spmm_all_widths"] = {"bound": "hbm", "achieved": sparse_bytes / (sparse_ms * 1e-3) / 1e9 if sparse_ms > 0 else 0.0,
+                                   "peak": PEAK_HBM_GBS, "unit": "GB/s", "us_per_step": 1e3 * sparse_ms / nprof}
 
     out = {
         "metric": METRIC, "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": args.steps,

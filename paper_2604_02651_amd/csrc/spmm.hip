@@ -427,7 +427,7 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, con
     const int rows_per_wave = spmm_rows_per_wave(A->rows, A->capacity);   // lower bound of the plan's figure
     const unsigned rows_per_block = (unsigned)(SPMM_NT / 64) * (unsigned)rows_per_wave;
     char tag[56];
-    snprintf(tag, sizeof(tag), "%ux%u d=%d", A->rows, A->cols, d);
+    snprintf(tag, sizeof(tag), "%ux%u d=%d <%d,%d>", A->rows, A->cols, d, VEC, CH);
     const bool may_have_long = A->capacity > (uint64_t)SPMM_SHORT;
     spmm_plan_view pv = {nullptr, nullptr, nullptr};
     float *part = nullptr;
