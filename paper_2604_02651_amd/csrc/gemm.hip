@@ -552,6 +552,224 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
 }
 
 // ---------------------------------------------------------------------------------------------
+// fp32 path with direct global -> LDS loads (global_load_lds_dwordx4: lane l's 16 bytes land at
+// a wave-uniform LDS base + 16 l, no register staging).  256 x 128 tile, eight wavefronts with
+// 64 x 64 sub-tiles (two per SIMD), slices of 32 along the reduction in a ring of three LDS
+// stages: slice s + 2 is in flight while slice s is multiplied, one barrier per slice placed in the
+// middle of the slice's multiplies, waits on the loads stated explicitly (vmcnt).  Needs whole 16-byte chunks (as the fast path) and a
+// reduction range that is a multiple of 32.
+//
+// LDS layouts (no padding, a wavefront load covers 1 KB of contiguous LDS):
+//   reduction-contiguous operand: [row][8 chunks of 16 bytes]; position p of row r holds chunk
+//     p ^ ((r >> 1) & 7) of the slice, so that the 32 rows a half-wavefront reads at one reduction
+//     offset fall into different banks;
+//   operand given [reduction][rows]: [k][R] as in memory; a lane reads its tiles' values at
+//     consecutive addresses (tiles interleaved as in the fast path).
+// ---------------------------------------------------------------------------------------------
+#define SGNN_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define SGNN_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
+constexpr int DIRECT_BM = 256, DIRECT_BN = 128, DIRECT_BK = 32, DIRECT_STAGES = 3, DIRECT_WAVES = 8;
+constexpr int DIRECT_STAGE_FLOATS = (DIRECT_BM + DIRECT_BN) * DIRECT_BK;
+constexpr size_t DIRECT_LDS_BYTES = (size_t)DIRECT_STAGES * DIRECT_STAGE_FLOATS * sizeof(float);
+
+// s_waitcnt vmcnt(n) only (expcnt and lgkmcnt left at their maxima), gfx9 encoding
+#define SGNN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+
+// Issues the loads of one operand slice: R rows, wave-loads dealt round-robin to the 8 wavefronts.
+template <int R, bool RC>
+__device__ __forceinline__ void direct_issue(float *lds, const float *__restrict__ G, int64_t ld, int64_t row0, int64_t rows_total,
+                                             int64_t k0, const int32_t *__restrict__ ridx, int lane, int wave)
+{
+    constexpr int LOADS = R * DIRECT_BK / 4 / 64 / DIRECT_WAVES;   // wave-loads per wavefront
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+        const int q = wave + DIRECT_WAVES * j;   // wave-load number: LDS floats [256 q, 256 q + 256)
+        const float *g;
+        if (RC) {
+            const int r = 8 * q + (lane >> 3), pos = lane & 7;
+            int64_t gr = min(row0 + r, rows_total - 1);
+            if (ridx) gr = ridx[gr];
+            g = G + gr * ld + k0 + 4 * (pos ^ ((r >> 1) & 7));
+        } else {
+            const int f = 64 * q + lane;                   // chunk number in the [k][R / 4] array
+            const int k = f / (R / 4), ch = f % (R / 4);
+            g = G + (k0 + k) * ld + min(row0 + 4 * ch, rows_total - 4);
+        }
+        __builtin_amdgcn_global_load_lds(SGNN_GPTR(g), SGNN_LPTR(lds + 256 * q), 16, 0, 0);
+    }
+}
+
+// Operand values of one quad of a slice: reduction steps kk + 8 kh + 4 half + {0..3} for the T tiles of the wavefront.
+template <int R, bool RC, int T>
+__device__ __forceinline__ void direct_frag(float (&v)[T][4], const float *L, int w0, int kk, int half, int li, int kh)
+{
+    if constexpr (RC) {
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int r = w0 + 32 * t + li, c = kk / 4 + 2 * kh + half;
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(L + r * 32 + 4 * (c ^ ((r >> 1) & 7)));
+#pragma unroll
+            for (int s = 0; s < 4; ++s) v[t][s] = x[s];
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const typename fvec<T>::type x =
+                *reinterpret_cast<const typename fvec<T>::type *>(L + (kk + 8 * kh + 4 * half + s) * R + w0 + T * li);
+            if constexpr (T == 1) v[0][s] = x;
+            else {
+#pragma unroll
+                for (int t = 0; t < T; ++t) v[t][s] = x[t];
+            }
+        }
+    }
+}
+
+template <bool TA, bool TB, bool GATHER>
+__global__ __launch_bounds__(64 * DIRECT_WAVES) void gemm_direct_kernel(gemm_args a)
+{
+    constexpr int BM = DIRECT_BM, BN = DIRECT_BN, BK = DIRECT_BK, TM = 2, TN = 2;
+    constexpr bool A_RC = !TA, B_RC = TB;
+    constexpr int LOADS = (BM + BN) * BK / 4 / 64 / DIRECT_WAVES;   // loads per thread and slice
+    extern __shared__ __attribute__((aligned(16))) float direct_smem[];
+    const gemm_tile tb_ = tile_of_block(a);
+    if (!tb_.valid) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 31, kh = lane >> 5;
+    const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+    const int64_t m0 = (int64_t)tb_.bx * BM, n0 = (int64_t)tb_.by * BN;
+    const int64_t kbeg = (int64_t)tb_.bz * a.k_per_split;
+    const int64_t kend = min(a.K, kbeg + a.k_per_split);
+    const int nslices = (int)((kend - kbeg) / BK);
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // a slice number past the end loads the last slice again, into a stage nobody reads any more:
+    // the loop body then has no branch, and every wait in it counts a fixed number of operations
+    auto issue = [&](int s) {
+        float *st = direct_smem + (s % DIRECT_STAGES) * DIRECT_STAGE_FLOATS;
+        const int64_t k0 = kbeg + (int64_t)min(s, nslices - 1) * BK;
+        direct_issue<BM, A_RC>(st, a.A, a.lda, m0, a.M, k0, GATHER ? a.a_row_index : nullptr, lane, wave);
+        direct_issue<BN, B_RC>(st + BM * BK, a.B, a.ldb, n0, a.N, k0, nullptr, lane, wave);
+    };
+    // Schedule of a slice (four quads of four reduction steps each, operand values double buffered in
+    // registers):   read q1 | multiply q0 | read q2 | multiply q1 | wait + barrier + issue slice it+2 |
+    //               read q3 | multiply q2 | read q0 of slice it+1 | multiply q3
+    // The barrier sits in the middle of the multiplies: it publishes slice it + 1 (loaded one slice
+    // ago) and proves that everyone has left slice it - 1, whose stage the new loads overwrite, so
+    // no wavefront ever waits on memory or LDS latency with an empty MFMA queue behind it.
+    float av[2][TM][4], bv[2][TN][4];
+    auto frags = [&](int buf, int slice, int q) {
+        const float *LA = direct_smem + (slice % DIRECT_STAGES) * DIRECT_STAGE_FLOATS, *LB = LA + BM * BK;
+        direct_frag<BM, A_RC, TM>(av[buf], LA, wm0, 16 * (q / 2), q & 1, li, kh);
+        direct_frag<BN, B_RC, TN>(bv[buf], LB, wn0, 16 * (q / 2), q & 1, li, kh);
+    };
+    auto multiply = [&](int buf) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[buf][i][s], bv[buf][j][s], acc[i][j], 0, 0, 0);
+    };
+    if (nslices > 0) {
+        issue(0);
+        issue(1);
+        SGNN_WAIT_VMCNT(LOADS);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        frags(0, 0, 0);
+    }
+    for (int it = 0; it < nslices; ++it) {
+        frags(1, it, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(0);
+        __builtin_amdgcn_sched_barrier(0);
+        frags(0, it, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(1);
+        __builtin_amdgcn_sched_barrier(0);
+        SGNN_WAIT_VMCNT(0);   // this thread's part of slice it + 1 (the only loads in flight) has landed
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        issue(it + 2);   // into the stage slice it - 1 was read from
+        frags(1, it, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(0);
+        __builtin_amdgcn_sched_barrier(0);
+        frags(0, it + 1, 0);   // (after the last slice: values nobody uses)
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    float *Cout = a.partial ? a.partial + (int64_t)tb_.bz * a.M * a.N : a.C;
+    const int64_t ldc = a.partial ? a.N : a.ldc;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = n0 + wn0 + (B_RC ? 32 * j + li : TN * li + j);
+            if (col >= a.N) continue;
+            const float bj = (!a.partial && a.bias) ? a.bias[col] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rho = 8 * (r / 4) + 4 * kh + (r % 4);
+                const int64_t row = m0 + wm0 + (A_RC ? 32 * i + rho : TM * rho + i);
+                if (row < a.M) {
+                    float z = acc[i][j][r] + bj;
+                    if (!a.partial && a.relu) z = fmaxf(z, 0.f);
+                    Cout[row * ldc + col] = z;
+                }
+            }
+        }
+}
+
+int launch_direct(sgnn_ctx *ctx, int ta, int tb, gemm_args a, int splits, hipStream_t st)
+{
+    a.mtiles = (uint32_t)cdiv(a.M, DIRECT_BM);
+    a.ntiles = (uint32_t)cdiv(a.N, DIRECT_BN);
+    a.splits = (uint32_t)splits;
+    const uint64_t members = splits > 1 ? (uint64_t)a.mtiles * a.ntiles : a.ntiles;
+    const uint64_t groups = splits > 1 ? (uint64_t)splits : a.mtiles;
+    const uint64_t nblocks = cdiv(groups, 8) * 8 * members;
+    if (nblocks > 0x7fffffffull) return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gemm: more than 2^31 tiles");
+    char tag[56];
+    snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld f32", ta ? 'T' : 'N', tb ? 'T' : 'N', DIRECT_BM, DIRECT_BN, (long long)a.M,
+             (long long)a.N, (long long)a.K);
+    dim3 grid((unsigned)nblocks), block(64 * DIRECT_WAVES);
+    const bool gather = a.a_row_index != nullptr;
+#define SGNN_DIRECT_CASE(TA_, TB_, G_)                                                                                  \
+    if (ta == TA_ && tb == TB_ && gather == G_) {                                                                       \
+        static bool attr_set = false;                                                                                   \
+        if (!attr_set) {                                                                                                \
+            SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_direct_kernel<TA_, TB_, G_>),        \
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));                 \
+            attr_set = true;                                                                                            \
+        }                                                                                                               \
+        SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_direct_kernel<TA_, TB_, G_>), grid, block, DIRECT_LDS_BYTES, st, a); \
+        return SGNN_OK;                                                                                                 \
+    }
+    SGNN_DIRECT_CASE(false, false, false)
+    SGNN_DIRECT_CASE(false, true, false)
+    SGNN_DIRECT_CASE(true, false, false)
+    SGNN_DIRECT_CASE(false, false, true)
+    SGNN_DIRECT_CASE(false, true, true)
+    SGNN_DIRECT_CASE(true, false, true)
+#undef SGNN_DIRECT_CASE
+    return SGNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // bf16 path, tall A and a small B (K <= 256, N <= 256: the layer transform and the feature
 // gradient of a mini-batch with hundreds of thousands of rows).  The product is bound by reading
 // A and writing C once, so the kernel is built around that stream:
@@ -877,9 +1095,14 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     if (bf16 && !ta && K >= 1 && K <= 256 && N >= 1 && N <= 256 && M >= 4096 && a.alignedA)
         return launch_skinny(ctx, a, tb, st);
 
+    // wide fp32 results with whole chunks and whole slices: the direct-to-LDS kernel, 256 x 128 tiles
+    const int64_t a_contig = ta ? M : K, b_contig = tb ? K : N;
+    const bool direct = !bf16 && !(ta && tb) && a.alignedA && a.alignedB && a_contig % 4 == 0 && b_contig % 4 == 0 &&
+                        a_contig >= 4 && b_contig >= 4 && K % 32 == 0 && K >= 32 && N > 64 && M > 128;
+
     // tile shape by the width of C
     const int bn = N > 64 ? 128 : (N > 32 ? 64 : 32);
-    const int bm = bn == 32 ? 256 : 128;
+    const int bm = direct ? DIRECT_BM : (bn == 32 ? 256 : 128);
     int splits = 1;
     const int64_t tiles = (int64_t)cdiv(M, bm) * cdiv(N, bn);
     if (tiles < 256 && K >= 4096 && !bias && !(flags & SGNN_RELU)) {
@@ -897,7 +1120,8 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
         } else splits = 1;
     }
     int rc;
-    if (bn == 128) rc = launch_cfg<128, 128, 64, 64>(ctx, ta, tb, bf16, a, splits, st);
+    if (direct) rc = launch_direct(ctx, ta, tb, a, splits, st);
+    else if (bn == 128) rc = launch_cfg<128, 128, 64, 64>(ctx, ta, tb, bf16, a, splits, st);
     else if (bn == 64) rc = launch_cfg<128, 64, 64, 32>(ctx, ta, tb, bf16, a, splits, st);
     else rc = launch_cfg<256, 32, 64, 32>(ctx, ta, tb, bf16, a, splits, st);
     if (rc) return rc;

@@ -165,6 +165,37 @@ def test_gemm_long_reduction_is_split_and_reproducible(bf16):
     assert torch.equal(C, C2)
 
 
+@pytest.mark.parametrize("M,N,K", [(1000, 256, 256), (4096, 128, 64), (300, 172, 128), (129, 68, 32), (2500, 256, 96),
+                                   (777, 100, 160)])
+def test_gemm_fp32_wide_results(M, N, K):
+    # wide fp32 results with a reduction length that is a multiple of 32 (the direct global -> LDS tile kernel),
+    # ragged in M and N, all three operand orders
+    ctx().reserve(1, 1, 40000, 256)
+    A = _rand((M, K), 21); Bm = _rand((K, N), 22); bias = _rand(N, 23)
+    C = torch.full((M, N), 9.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), False, False, dev(A), dev(Bm), dev(bias), sg.SGNN_RELU, C)
+    assert rel_err(C.cpu().numpy(), np.maximum(oracle.gemm(A, Bm) + bias, 0)) < TOL_F32
+    Bt = _rand((N, K), 24)
+    sg.sgnn_gemm(ctx(), False, True, dev(A), dev(Bt), None, 0, C)
+    assert rel_err(C.cpu().numpy(), oracle.gemm(A, Bt.T.copy())) < TOL_F32
+    At = _rand((K, M), 25)
+    sg.sgnn_gemm(ctx(), True, False, dev(At), dev(Bm), None, 0, C)
+    assert rel_err(C.cpu().numpy(), oracle.gemm(At.T.copy(), Bm)) < TOL_F32
+
+
+def test_gemm_fp32_weight_gradient_shape():
+    # dW = T^T dZ of the headline workload: 256 x 256 result, reduction over 32768 rows, split and summed in a fixed order
+    K, M, N = 32768, 256, 256
+    ctx().reserve(1, 1, 40000, 256)
+    At = _rand((K, M), 26); Bm = _rand((K, N), 27)
+    C = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), True, False, dev(At), dev(Bm), None, 0, C)
+    assert rel_err(C.cpu().numpy(), oracle.gemm(At.T.copy(), Bm)) < TOL_F32
+    C2 = torch.zeros_like(C)
+    sg.sgnn_gemm(ctx(), True, False, dev(At), dev(Bm), None, 0, C2)
+    assert torch.equal(C, C2)
+
+
 @pytest.mark.parametrize("M,N,K,ldpad", [(5000, 256, 256, 0), (4100, 47, 256, 0), (9000, 172, 128, 4), (4097, 256, 100, 0),
                                          (6000, 256, 47, 1), (4608, 64, 32, 0), (4096, 200, 172, 0), (70000, 256, 256, 0)])
 def test_gemm_bf16_tall_operand(M, N, K, ldpad):
