@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--config", default="medium", help="tiny | medium | large | dense | xlarge (medium is the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fuse-slice", action="store_true")
+    ap.add_argument("--no-fuse-relu-bwd", action="store_true",
+                    help="separate ReLU-backward pass instead of masking inside the product that writes the input gradient")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     ap.add_argument("--no-overlap", action="store_true",
                     help="everything on one stream (default: the next mini-batch is sampled on a second stream while this one trains)")
@@ -74,7 +76,7 @@ def main():
     labels = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=dev)
     weights = si.layer_weights(cfg, device=dev)
     st = sg.GcnStep(cfg.N, g.rowptr, g.colidx, X, labels, weights, cfg.B, cfg.sampler_seed, bf16=cfg.bf16_mfma,
-                    fuse_slice=not args.no_fuse_slice, device=dev)
+                    fuse_slice=not args.no_fuse_slice, device=dev, fuse_relu_bwd=not args.no_fuse_relu_bwd)
     period = max(cfg.steps, 1)   # the configuration's mini-batches: consecutive sampler counters
 
     use_graph = not args.no_graph and not args.no_overlap and period % 2 == 0
@@ -180,7 +182,7 @@ def main():
         "config": {"workload": "%s: R-MAT N=%d, E=%d stored entries, |S|=%d, GCN %s, %d mini-batches (sampler "
                                "counters 0..%d)" % (cfg.name, cfg.N, g.E, cfg.B, "-".join(map(str, cfg.dims)), period,
                                                      period - 1),
-                   "fuse_slice": not args.no_fuse_slice, "overlap_sampling": not args.no_overlap, "hip_graph": use_graph,
+                   "fuse_slice": not args.no_fuse_slice, "fuse_relu_bwd": not args.no_fuse_relu_bwd, "overlap_sampling": not args.no_overlap, "hip_graph": use_graph,
                    "single_stream_steps_per_s": single_stream_steps_per_s, "avg_induced_entries": nnz_avg,
                    "kernel_time_us_per_step": 1e3 * total_ms / nprof},
         "roofline": roofline,

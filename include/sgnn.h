@@ -46,6 +46,8 @@ enum { SGNN_F32 = 0, SGNN_BF16 = 1 };
 enum {
     SGNN_RELU = 1,      /* Y = max(Z, 0) (Eq. 8); backward masks dY where Y <= 0                    */
     SGNN_BF16_MFMA = 2, /* round both GEMM operands to bfloat16 (nearest even), accumulate in fp32  */
+    SGNN_DY_MASKED = 8, /* backward only: dY already carries the ReLU mask of this layer's output (the
+                           layer above was given H_in), so it is not applied again                   */
     SGNN_XFORM_FIRST = 4 /* evaluate A (H W) instead of (A H) W: the same result up to rounding, with
                             the sparse product at width d_out; worth it when d_out < d_in           */
 };
@@ -194,7 +196,7 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
                  const float *bias, int flags, sgnn_mat *Y, sgnn_mat *T, sgnn_stream stream);
 
 /*
- * One GCN layer backward (Sec. III-C): dZ = dY where Y > 0 (all of dY without SGNN_RELU),
+ * One GCN layer backward (Sec. III-C): dZ = dY where Y > 0 (all of dY without SGNN_RELU or with SGNN_DY_MASKED),
  * dbias = column sums of dZ, dW = T^T dZ, dT = dZ W^T, dH = A_T dT.
  *   A_T   the transpose of the forward matrix as CSR (the same object when it is symmetric)
  *   T, W, Y   as in the forward call;  dY  B x d_out fp32
@@ -202,13 +204,17 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
  *             (B x d_in, row_index honoured) and the products are dP = A_T dZ, dW = H^T dP,
  *             dH = dP W^T
  *   dH    out B x d_in fp32, or NULL to skip it (first layer)
+ *   H_in  optional (NULL = none; needs dH): the layer's input activations, B x d_in fp32, the output
+ *         of the ReLU of the layer below.  dH is then returned already multiplied by [H_in > 0],
+ *         i.e. with that layer's ReLU backward fused into the product that writes dH; call that
+ *         layer's backward with SGNN_DY_MASKED so that it skips its own masking pass.
  *   dW    out fp32[d_in x d_out] row-major, overwritten;  dbias out fp32[d_out] or NULL
  * The reduction over the B rows in dW and dbias uses a fixed split and a fixed summation order:
  * results are bit-reproducible from run to run.
  */
 int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sgnn_mat *W,
-                 const sgnn_mat *Y, const sgnn_mat *dY, int flags, sgnn_mat *dH, float *dW,
-                 float *dbias, sgnn_stream stream);
+                 const sgnn_mat *Y, const sgnn_mat *dY, int flags, sgnn_mat *dH, const sgnn_mat *H_in,
+                 float *dW, float *dbias, sgnn_stream stream);
 
 /*
  * Mean softmax cross-entropy over B rows of C logits (Sec. III-B, single-label loss) and its

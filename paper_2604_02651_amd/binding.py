@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libsgnn.so")
 SGNN_RELU = 1
 SGNN_BF16_MFMA = 2
 SGNN_XFORM_FIRST = 4
+SGNN_DY_MASKED = 8
 SGNN_F32 = 0
 
 _ERR_NAMES = {-1: "SGNN_ERR_INVALID_ARG", -2: "SGNN_ERR_CAPACITY", -3: "SGNN_ERR_UNSUPPORTED", -4: "SGNN_ERR_HIP",
@@ -79,7 +80,7 @@ def lib():
         L.sgnn_gcn_fwd.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), vp, ci, C.POINTER(_Mat),
                                    C.POINTER(_Mat), vp]
         L.sgnn_gcn_bwd.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat),
-                                   C.POINTER(_Mat), ci, C.POINTER(_Mat), vp, vp, vp]
+                                   C.POINTER(_Mat), ci, C.POINTER(_Mat), C.POINTER(_Mat), vp, vp, vp]
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
@@ -267,17 +268,19 @@ def sgnn_gcn_fwd(ctx: Context, A: Csr, H: torch.Tensor, W: torch.Tensor, bias: O
 
 def sgnn_gcn_bwd(ctx: Context, A_T: Csr, T: torch.Tensor, W: torch.Tensor, Y: Optional[torch.Tensor], dY: torch.Tensor,
                  flags: int, dH: Optional[torch.Tensor], dW: torch.Tensor, dbias: Optional[torch.Tensor],
-                 row_index: Optional[torch.Tensor] = None, stream=None):
-    """T is the saved aggregate, or with SGNN_XFORM_FIRST the layer input (row_index honoured)."""
+                 row_index: Optional[torch.Tensor] = None, stream=None, H_in: Optional[torch.Tensor] = None):
+    """T is the saved aggregate, or with SGNN_XFORM_FIRST the layer input (row_index honoured).
+    H_in (the layer input, output of the ReLU below): dH comes back multiplied by [H_in > 0]."""
     a = A_T.struct()
     t, w, dy = _mat(T, row_index, "T"), _mat(W, None, "W"), _mat(dY, None, "dY")
     y = _mat(Y, None, "Y") if Y is not None else None
     dh = _mat(dH, None, "dH") if dH is not None else None
+    hin = _mat(H_in, None, "H_in") if H_in is not None else None
     if dW.shape != W.shape or not dW.is_contiguous():
         raise ValueError("dW must be contiguous with the shape of W")
     ctx.check(lib().sgnn_gcn_bwd(ctx._h, C.byref(a), C.byref(t), C.byref(w), C.byref(y) if y is not None else None,
                                  C.byref(dy), flags, C.byref(dh) if dh is not None else None,
-                                 _ptr(dW, torch.float32, "dW"), _ptr(dbias, torch.float32, "dbias"), _stream(stream)))
+                                 C.byref(hin) if hin is not None else None, _ptr(dW, torch.float32, "dW"), _ptr(dbias, torch.float32, "dbias"), _stream(stream)))
 
 
 def sgnn_softmax_xent(ctx: Context, O: torch.Tensor, labels: torch.Tensor, loss: Optional[torch.Tensor],

@@ -284,7 +284,7 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, sgnn_mat *out
     if (rc) return rc;
     ws_alloc ws(ctx);
     return sgnn_launch_spmm(ctx, A, static_cast<const float *>(X->ptr), X->ld, X->row_index, X->cols,
-                            static_cast<float *>(out->ptr), out->ld, nullptr, 0, &ws, static_cast<hipStream_t>(stream));
+                            static_cast<float *>(out->ptr), out->ld, nullptr, 0, nullptr, 0, &ws, static_cast<hipStream_t>(stream));
 }
 
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
@@ -298,7 +298,7 @@ int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_gemm(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, nullptr, B, ldb, bias, flags, C, ldc, &ws,
+    return sgnn_launch_gemm(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, nullptr, B, ldb, bias, flags, C, ldc, nullptr, 0, &ws,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -322,11 +322,11 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
     if (!xform_first) {
         // Eqs. 5-6 in the paper's order: aggregate, then transform with bias and activation fused
         rc = sgnn_launch_spmm(ctx, A, static_cast<const float *>(H->ptr), H->ld, H->row_index, d_in,
-                              static_cast<float *>(T->ptr), T->ld, nullptr, 0, &ws, st);
+                              static_cast<float *>(T->ptr), T->ld, nullptr, 0, nullptr, 0, &ws, st);
         if (rc) return rc;
         return sgnn_launch_gemm(ctx, 0, 0, Bn, d_out, d_in, static_cast<const float *>(T->ptr), T->ld, nullptr,
                                 static_cast<const float *>(W->ptr), W->ld, bias, gflags, static_cast<float *>(Y->ptr), Y->ld,
-                                &ws, st);
+                                nullptr, 0, &ws, st);
     }
     // A (H W): transform first (the aggregation then runs at width d_out), bias and activation
     // fused into the sparse product
@@ -334,23 +334,29 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
     float *P = ws.get<float>((size_t)A->cols * ldp);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_fwd: scratch too small: call sgnn_ctx_reserve");
     rc = sgnn_launch_gemm(ctx, 0, 0, A->cols, d_out, d_in, static_cast<const float *>(H->ptr), H->ld, H->row_index,
-                          static_cast<const float *>(W->ptr), W->ld, nullptr, flags & SGNN_BF16_MFMA, P, ldp, &ws, st);
+                          static_cast<const float *>(W->ptr), W->ld, nullptr, flags & SGNN_BF16_MFMA, P, ldp, nullptr, 0, &ws, st);
     if (rc) return rc;
     return sgnn_launch_spmm(ctx, A, P, ldp, nullptr, d_out, static_cast<float *>(Y->ptr), Y->ld, bias,
-                            (flags & SGNN_RELU) ? 1 : 0, &ws, st);
+                            (flags & SGNN_RELU) ? 1 : 0, nullptr, 0, &ws, st);
 }
 
 int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sgnn_mat *W, const sgnn_mat *Y,
-                 const sgnn_mat *dY, int flags, sgnn_mat *dH, float *dW, float *dbias, sgnn_stream stream)
+                 const sgnn_mat *dY, int flags, sgnn_mat *dH, const sgnn_mat *H_in, float *dW, float *dbias,
+                 sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     if (!csr_ok(A_T) || !mat_ok(T) || !mat_ok(W) || !mat_ok(dY) || !dW || (dH && !mat_ok(dH)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: bad argument");
     const int relu = (flags & SGNN_RELU) ? 1 : 0;
     const bool xform_first = (flags & SGNN_XFORM_FIRST) != 0;
-    if (relu && !mat_ok(Y)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: SGNN_RELU needs Y");
+    const bool dy_masked = (flags & SGNN_DY_MASKED) != 0;   // the caller's dY already carries this layer's ReLU mask
+    if (relu && !dy_masked && !mat_ok(Y)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: SGNN_RELU needs Y");
+    if (H_in && (!dH || !mat_ok(H_in) || H_in->row_index))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: H_in needs dH and must be a plain matrix");
     const int64_t Bn = T->rows, d_in = W->rows, d_out = W->cols;
-    if (T->cols != d_in || dY->rows != Bn || dY->cols != d_out || (relu && (Y->rows != Bn || Y->cols != d_out)) ||
+    if (T->cols != d_in || dY->rows != Bn || dY->cols != d_out ||
+        (relu && !dy_masked && (Y->rows != Bn || Y->cols != d_out)) ||
+        (H_in && (H_in->rows != dH->rows || H_in->cols != d_in)) ||
         (dH && (dH->rows != A_T->rows || dH->cols != d_in || A_T->cols != Bn)) || (!xform_first && T->row_index) ||
         (xform_first && (A_T->rows != Bn || A_T->cols != Bn)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: shape mismatch");
@@ -364,31 +370,34 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     // element-wise backward: ReLU mask and bias gradient
     const float *dZ = static_cast<const float *>(dY->ptr);
     int64_t lddz = dY->ld;
-    if (relu || dbias) {
+    const int mask_here = relu && !dy_masked;
+    const float *hmask = H_in ? static_cast<const float *>(H_in->ptr) : nullptr;
+    const int64_t ldhm = H_in ? H_in->ld : 0;
+    if (mask_here || dbias) {
         float *dZbuf = nullptr;
-        if (relu) {
+        if (mask_here) {
             dZbuf = ws.get<float>((size_t)Bn * ld_out);
             if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
         }
-        rc = sgnn_launch_relu_bwd_bias(ctx, relu ? static_cast<const float *>(Y->ptr) : nullptr, relu ? Y->ld : 0,
-                                       static_cast<const float *>(dY->ptr), dY->ld, relu, Bn, d_out, dZbuf, ld_out, dbias,
-                                       &ws, st);
+        rc = sgnn_launch_relu_bwd_bias(ctx, mask_here ? static_cast<const float *>(Y->ptr) : nullptr, mask_here ? Y->ld : 0,
+                                       static_cast<const float *>(dY->ptr), dY->ld, mask_here, Bn, d_out, dZbuf, ld_out,
+                                       dbias, &ws, st);
         if (rc) return rc;
-        if (relu) { dZ = dZbuf; lddz = ld_out; }
+        if (mask_here) { dZ = dZbuf; lddz = ld_out; }
     }
     if (!xform_first) {
         // dW = T^T dZ
         rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, nullptr, dZ, lddz,
-                              nullptr, mfma, dW, d_out, &ws, st);
+                              nullptr, mfma, dW, d_out, nullptr, 0, &ws, st);
         if (rc) return rc;
         if (dH) {
             // dT = dZ W^T, dH = A^T dT
             float *dT = ws.get<float>((size_t)Bn * ld_in);
             if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
             rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, nullptr, static_cast<const float *>(W->ptr), W->ld,
-                                  nullptr, mfma, dT, ld_in, &ws, st);
+                                  nullptr, mfma, dT, ld_in, nullptr, 0, &ws, st);
             if (rc) return rc;
-            rc = sgnn_launch_spmm(ctx, A_T, dT, ld_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, &ws,
+            rc = sgnn_launch_spmm(ctx, A_T, dT, ld_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, hmask, ldhm, &ws,
                                   st);
             if (rc) return rc;
         }
@@ -397,14 +406,14 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     // transform-first layer: dP = A^T dZ (width d_out), dW = H^T dP, dH = dP W^T; T is the layer input H
     float *dP = ws.get<float>((size_t)Bn * ld_out);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
-    rc = sgnn_launch_spmm(ctx, A_T, dZ, lddz, nullptr, d_out, dP, ld_out, nullptr, 0, &ws, st);
+    rc = sgnn_launch_spmm(ctx, A_T, dZ, lddz, nullptr, d_out, dP, ld_out, nullptr, 0, nullptr, 0, &ws, st);
     if (rc) return rc;
     rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, T->row_index, dP, ld_out,
-                          nullptr, mfma, dW, d_out, &ws, st);
+                          nullptr, mfma, dW, d_out, nullptr, 0, &ws, st);
     if (rc) return rc;
     if (dH)
         rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dP, ld_out, nullptr, static_cast<const float *>(W->ptr), W->ld,
-                              nullptr, mfma, static_cast<float *>(dH->ptr), dH->ld, &ws, st);
+                              nullptr, mfma, static_cast<float *>(dH->ptr), dH->ld, hmask, ldhm, &ws, st);
     return rc;
 }
 

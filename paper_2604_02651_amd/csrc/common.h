@@ -102,13 +102,14 @@ int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, ui
                         const uint64_t *bitmap, const uint32_t *rank, int norm_mode, int rescale,
                         sgnn_csr *out, hipStream_t st);
 int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index,
-                     int64_t d, float *out, int64_t ldo, const float *bias, int relu, ws_alloc *ws, hipStream_t st);
+                     int64_t d, float *out, int64_t ldo, const float *bias, int relu, const float *mask, int64_t ldm,
+                     ws_alloc *ws, hipStream_t st);
 int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st);   // fills A->plan when it is attached
 // a_row_index (may be NULL): physical row of A for every logical row (M x K operand: rows of the
 // result; K x M operand used transposed: reduction index)
 int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A,
                      int64_t lda, const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias,
-                     int flags, float *C, int64_t ldc, ws_alloc *ws, hipStream_t st);
+                     int flags, float *C, int64_t ldc, const float *mask, int64_t ldm, ws_alloc *ws, hipStream_t st);
 int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const float *dY, int64_t lddy,
                               int relu, int64_t rows, int64_t cols, float *dZ, int64_t lddz, float *dbias,
                               ws_alloc *ws, hipStream_t st);

@@ -39,6 +39,7 @@ struct gemm_args {
     const float *bias;
     float *C; int64_t ldc;
     int relu;
+    const float *mask; int64_t ldm;   // optional: C is zeroed where this M x N matrix is not positive
     int alignedA, alignedB;   // 16-byte aligned base and leading dimension a multiple of 4
     int64_t k_per_split;      // reduction range of one blockIdx.z (a multiple of BK); K when unsplit
     float *partial;           // split-K: [splits][M][N] partial products, else NULL
@@ -279,6 +280,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
                 if (row < a.M) {
                     float z = acc[i][j][r] + bj;
                     if (!a.partial && a.relu) z = fmaxf(z, 0.f);
+                    if (!a.partial && a.mask && !(a.mask[row * a.ldm + col] > 0.f)) z = 0.f;
                     Cout[row * ldc + col] = z;
                 }
             }
@@ -545,6 +547,7 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
                 if (row < a.M) {
                     float z = acc[i][j][r] + bj;
                     if (!a.partial && a.relu) z = fmaxf(z, 0.f);
+                    if (!a.partial && a.mask && !(a.mask[row * a.ldm + col] > 0.f)) z = 0.f;
                     Cout[row * ldc + col] = z;
                 }
             }
@@ -728,6 +731,7 @@ __global__ __launch_bounds__(64 * DIRECT_WAVES) void gemm_direct_kernel(gemm_arg
                 if (row < a.M) {
                     float z = acc[i][j][r] + bj;
                     if (!a.partial && a.relu) z = fmaxf(z, 0.f);
+                    if (!a.partial && a.mask && !(a.mask[row * a.ldm + col] > 0.f)) z = 0.f;
                     Cout[row * ldc + col] = z;
                 }
             }
@@ -933,6 +937,7 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
         const int64_t wrow = (int64_t)rb * (32 * SKINNY_WAVES) + wave * 32;
         const int64_t row0 = wrow + 4 * kh;   // the lane's first row
         float *cl = a.C + row0 * a.ldc + li;
+        const float *mk = a.mask ? a.mask + row0 * a.ldm + li : nullptr;
         if (wrow + 32 <= a.M) {
 #pragma unroll
             for (int j = 0; j < NT8; ++j) {
@@ -940,8 +945,11 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
                     const float bj = Lbias[32 * j + li];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const float z = acc[j][r] + bj;
-                        cl[(int64_t)(8 * (r / 4) + (r % 4)) * a.ldc + 32 * j] = relu ? fmaxf(z, 0.f) : z;
+                        const int rr = 8 * (r / 4) + (r % 4);
+                        float z = acc[j][r] + bj;
+                        z = relu ? fmaxf(z, 0.f) : z;
+                        if (mk) z = mk[(int64_t)rr * a.ldm + 32 * j] > 0.f ? z : 0.f;
+                        cl[(int64_t)rr * a.ldc + 32 * j] = z;
                     }
                 }
             }
@@ -951,8 +959,12 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int rr = 8 * (r / 4) + (r % 4);
-                    const float z = acc[j][r] + Lbias[32 * j + li];
-                    if (32 * j + li < N && row0 + rr < a.M) cl[(int64_t)rr * a.ldc + 32 * j] = relu ? fmaxf(z, 0.f) : z;
+                    float z = acc[j][r] + Lbias[32 * j + li];
+                    z = relu ? fmaxf(z, 0.f) : z;
+                    if (32 * j + li < N && row0 + rr < a.M) {
+                        if (mk) z = mk[(int64_t)rr * a.ldm + 32 * j] > 0.f ? z : 0.f;
+                        cl[(int64_t)rr * a.ldc + 32 * j] = z;
+                    }
                 }
         }
 #pragma unroll
@@ -1077,9 +1089,10 @@ size_t sgnn_gemm_ws_bytes(uint32_t d_max) { return (size_t)256 * d_max * d_max *
 
 int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
                      const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias, int flags, float *C,
-                     int64_t ldc, ws_alloc *ws, hipStream_t st)
+                     int64_t ldc, const float *mask, int64_t ldm, ws_alloc *ws, hipStream_t st)
 {
     gemm_args a;
+    a.mask = mask; a.ldm = ldm;
     a.a_row_index = a_row_index;
     a.M = M; a.N = N; a.K = K;
     a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.bias = bias; a.C = C; a.ldc = ldc;
@@ -1105,7 +1118,7 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     const int bm = direct ? DIRECT_BM : (bn == 32 ? 256 : 128);
     int splits = 1;
     const int64_t tiles = (int64_t)cdiv(M, bm) * cdiv(N, bn);
-    if (tiles < 256 && K >= 4096 && !bias && !(flags & SGNN_RELU)) {
+    if (tiles < 256 && K >= 4096 && !bias && !(flags & SGNN_RELU) && !mask) {
         // long reduction onto a small result (the weight gradient): split the reduction
         int64_t want = (256 + tiles - 1) / tiles;
         int64_t kps = ((K + want - 1) / want + BK - 1) / BK * BK;

@@ -131,13 +131,28 @@ __global__ __launch_bounds__(256) void spmm_plan_kernel(uint32_t rows, const int
     for (uint32_t c = 0; c < nch && base + c < max_chunks; ++c) desc[base + c] = make_uint2(row, c);
 }
 
-// out = act(acc + bias) on the VEC columns starting at col
-template <int VEC> __device__ __forceinline__ void spmm_epilogue(float (&v)[VEC], const float *__restrict__ bias, int relu, int col)
+// What happens to a finished output row: out = act(acc + bias), then (optionally) zero where the
+// mask matrix is not positive - the ReLU backward of the layer below, fused into this product.
+struct spmm_epi {
+    const float *bias;
+    int relu;
+    const float *mask;
+    int64_t ldm;
+};
+
+template <int VEC>
+__device__ __forceinline__ void spmm_epilogue(float (&v)[VEC], const spmm_epi &ep, int64_t row, int col)
 {
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
-        if (bias) v[i] += bias[col + i];
-        if (relu) v[i] = fmaxf(v[i], 0.f);
+        if (ep.bias) v[i] += ep.bias[col + i];
+        if (ep.relu) v[i] = fmaxf(v[i], 0.f);
+    }
+    if (ep.mask) {
+        float m[VEC];
+        vload<VEC>(m, ep.mask + row * ep.ldm + col);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] = m[i] > 0.f ? v[i] : 0.f;
     }
 }
 
@@ -153,7 +168,7 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const int32_t *__r
                                                uint64_t capacity, const float *__restrict__ X, int64_t ldx,
                                                const int32_t *__restrict__ row_index, int d, uint32_t wave, int rows_per_wave,
                                                int long_len, float *__restrict__ out, int64_t ldo,
-                                               const float *__restrict__ bias, int relu)
+                                               const spmm_epi &ep)
 {
     constexpr int U = CH * VEC <= 4 ? 8 : (CH * VEC <= 8 ? 4 : 2);
     const int lane = threadIdx.x & 63;
@@ -180,7 +195,7 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const int32_t *__r
             for (int m = 0; m < CH; ++m) {
                 const int col = (m * 64 + lane) * VEC;
                 if (col < d) {
-                    spmm_epilogue<VEC>(acc[m], bias, relu, col);
+                    spmm_epilogue<VEC>(acc[m], ep, (int64_t)(r0 + row), col);
                     vstore<VEC>(o + col, acc[m]);
                 }
             }
@@ -302,7 +317,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
                                                             unsigned n_piece_waves, const uint32_t *__restrict__ n_chunks,
                                                             uint32_t max_chunks, const uint2 *__restrict__ desc,
                                                             float *__restrict__ part, float *__restrict__ out, int64_t ldo,
-                                                            const float *__restrict__ bias, int relu, int rows_per_wave)
+                                                            spmm_epi ep, int rows_per_wave)
 {
     constexpr int U = spmm_unroll<VEC, CH>::U;
     const int lane = threadIdx.x & 63;
@@ -338,8 +353,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
         return;
     }
     spmm_wave_rows<VEC, CH>(rows, rowptr, colidx, val, cap, X, ldx, row_index, d, wave - n_piece_waves,
-                            n_chunks ? (int)n_chunks[2] : rows_per_wave, n_chunks ? (int)n_chunks[1] : 0x7fffffff, out, ldo, bias,
-                            relu);
+                            n_chunks ? (int)n_chunks[2] : rows_per_wave, n_chunks ? (int)n_chunks[1] : 0x7fffffff, out, ldo, ep);
 }
 
 // Long rows: a group of lpr lanes per row adds its partial rows up in chunk order.
@@ -348,7 +362,7 @@ __global__ __launch_bounds__(256) void spmm_fixup_kernel(const int32_t *__restri
                                                          const uint32_t *__restrict__ n_chunks, uint32_t max_chunks,
                                                          const uint2 *__restrict__ desc, const float *__restrict__ part,
                                                          float *__restrict__ out, int64_t ldo,
-                                                         const float *__restrict__ bias, int relu, int lpr_log2)
+                                                         spmm_epi ep, int lpr_log2)
 {
     const int lpr = 1 << lpr_log2;
     const int G = 256 >> lpr_log2;
@@ -403,7 +417,7 @@ __global__ __launch_bounds__(256) void spmm_fixup_kernel(const int32_t *__restri
         for (int m = 0; m < CH; ++m) {
             const int col = (m * lpr + g) * VEC;
             if (col < d) {
-                spmm_epilogue<VEC>(acc[m], bias, relu, col);
+                spmm_epilogue<VEC>(acc[m], ep, (int64_t)rc.x, col);
                 vstore<VEC>(o + col, acc[m]);
             }
         }
@@ -422,7 +436,7 @@ int build_plan(sgnn_ctx *ctx, const sgnn_csr *A, void *plan, hipStream_t st)
 
 template <int VEC, int CH>
 int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int d, float *out,
-              int64_t ldo, const float *bias, int relu, int lpr_log2, ws_alloc *ws, hipStream_t st)
+              int64_t ldo, const spmm_epi &ep, int lpr_log2, ws_alloc *ws, hipStream_t st)
 {
     const int rows_per_wave = spmm_rows_per_wave(A->rows, A->capacity);   // lower bound of the plan's figure
     const unsigned rows_per_block = (unsigned)(SPMM_NT / 64) * (unsigned)rows_per_wave;
@@ -453,33 +467,33 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, con
     }
     SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH>), dim3(n_piece_waves / (SPMM_NT / 64) + cdiv(A->rows, rows_per_block)),
                 dim3(SPMM_NT), 0, st, A->rows, A->rowptr, A->colidx, A->val, A->capacity, X, ldx, row_index, d,
-                n_piece_waves, pv.n_chunks, max_chunks, pv.desc, part, out, ldo, bias, relu, rows_per_wave);
+                n_piece_waves, pv.n_chunks, max_chunks, pv.desc, part, out, ldo, ep, rows_per_wave);
     if (may_have_long) {
         const unsigned groups = 256u >> lpr_log2;
         SGNN_LAUNCH(ctx, st, "spmm_fixup_kernel", tag, (spmm_fixup_kernel<VEC, CH>),
                     dim3(std::min<unsigned>(cdiv(max_chunks, groups), 1024)), dim3(256), 0, st, A->rowptr, A->capacity, d,
-                    pv.n_chunks, max_chunks, pv.desc, part, out, ldo, bias, relu, lpr_log2);
+                    pv.n_chunks, max_chunks, pv.desc, part, out, ldo, ep, lpr_log2);
     }
     return SGNN_OK;
 }
 
 template <int VEC>
 int launch_v(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int d, float *out,
-             int64_t ldo, const float *bias, int relu, ws_alloc *ws, hipStream_t st)
+             int64_t ldo, const spmm_epi &ep, ws_alloc *ws, hipStream_t st)
 {
     const int per = (d + VEC - 1) / VEC;   // lanes needed for one pass over the row
     int lpr_log2 = 0;
     while ((1 << lpr_log2) < per && lpr_log2 < 6) ++lpr_log2;
     const int ch = (per + (1 << lpr_log2) - 1) >> lpr_log2;
     switch (ch) {
-    case 1: return launch_vc<VEC, 1>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
-    case 2: return launch_vc<VEC, 2>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
-    case 3: return launch_vc<VEC, 3>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
-    case 4: return launch_vc<VEC, 4>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
-    case 5: return launch_vc<VEC, 5>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
-    case 6: return launch_vc<VEC, 6>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
-    case 7: return launch_vc<VEC, 7>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
-    case 8: return launch_vc<VEC, 8>(ctx, A, X, ldx, row_index, d, out, ldo, bias, relu, lpr_log2, ws, st);
+    case 1: return launch_vc<VEC, 1>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
+    case 2: return launch_vc<VEC, 2>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
+    case 3: return launch_vc<VEC, 3>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
+    case 4: return launch_vc<VEC, 4>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
+    case 5: return launch_vc<VEC, 5>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
+    case 6: return launch_vc<VEC, 6>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
+    case 7: return launch_vc<VEC, 7>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
+    case 8: return launch_vc<VEC, 8>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
     default: break;
     }
     return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_spmm: feature width %d is beyond %d columns", d, 64 * 8 * VEC);
@@ -506,18 +520,21 @@ int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st)
 }
 
 int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int64_t d,
-                     float *out, int64_t ldo, const float *bias, int relu, ws_alloc *ws, hipStream_t st)
+                     float *out, int64_t ldo, const float *bias, int relu, const float *mask, int64_t ldm, ws_alloc *ws,
+                     hipStream_t st)
 {
+    const spmm_epi ep = {bias, relu, mask, ldm};
     if (A->rows == 0 || d == 0) return SGNN_OK;
-    const uintptr_t bits = reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(out);
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(mask);
     // the narrowest vector with which one wavefront still covers the row
-    const bool ok4 = d % 4 == 0 && ldx % 4 == 0 && ldo % 4 == 0 && (bits & 15) == 0;
-    const bool ok2 = d % 2 == 0 && ldx % 2 == 0 && ldo % 2 == 0 && (bits & 7) == 0;
-    if (d <= 64) return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
-    if (d <= 128 && ok2) return launch_v<2>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
+    const int64_t lds_ = ldx | ldo | (mask ? ldm : 0);
+    const bool ok4 = d % 4 == 0 && lds_ % 4 == 0 && (bits & 15) == 0;
+    const bool ok2 = d % 2 == 0 && lds_ % 2 == 0 && (bits & 7) == 0;
+    if (d <= 64) return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
+    if (d <= 128 && ok2) return launch_v<2>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
     if (ok4)
-        return launch_v<4>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
+        return launch_v<4>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
     if (ok2)
-        return launch_v<2>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
-    return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, bias, relu, ws, st);
+        return launch_v<2>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
+    return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
 }

@@ -20,7 +20,7 @@ class GcnStep:
     def __init__(self, N: int, rowptr: torch.Tensor, colidx: torch.Tensor, X: torch.Tensor, labels: torch.Tensor,
                  weights: List[Tuple[torch.Tensor, torch.Tensor]], B: int, seed: int = 0, bf16: bool = False,
                  fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None,
-                 auto_order: bool = True):
+                 auto_order: bool = True, fuse_relu_bwd: bool = True):
         self.N, self.B, self.seed = N, B, seed
         self.rowptr, self.colidx, self.X, self.labels = rowptr, colidx, X, labels
         self.weights = weights
@@ -44,6 +44,7 @@ class GcnStep:
         # a layer that narrows (d_out < d_in) is evaluated transform-first: its sparse products run at
         # width d_out, and its backward pass needs the layer input instead of the aggregate
         self.xform_first = [auto_order and dims[l + 1] < dims[l] for l in range(self.L)]
+        self.fuse_relu_bwd = fuse_relu_bwd
         def mat(d):   # B x d with rows starting 16-byte aligned (leading dimension a multiple of 4)
             return torch.empty((B, (d + 3) // 4 * 4), dtype=torch.float32, device=dev)[:, :d]
         self.T = [None if self.xform_first[l] else mat(dims[l]) for l in range(self.L)]
@@ -98,19 +99,25 @@ class GcnStep:
 
     def backward(self):
         dY = self.dO
+        masked = False    # dY already carries the ReLU mask of the layer it enters
         for l in range(self.L - 1, -1, -1):
             W, _ = self.weights[l]
             flags = self.flags | (sg.SGNN_RELU if l < self.L - 1 else 0) | (sg.SGNN_XFORM_FIRST if self.xform_first[l] else 0)
+            if masked:
+                flags |= sg.SGNN_DY_MASKED
             saved, ridx = self.T[l], None
             if self.xform_first[l]:
                 if l == 0:
                     saved, ridx = (self.X, self.S) if self.fuse_slice else (self.X_S, None)
                 else:
                     saved = self.H[l - 1]
+            # the ReLU backward of the layer below is fused into the product that writes dH
+            fuse = self.fuse_relu_bwd and l > 0
             # the induced matrix of a symmetric graph is symmetric: it is its own transpose
             sg.sgnn_gcn_bwd(self.ctx, self.A, saved, W, self.H[l], dY, flags, self.dH[l], self.dW[l], self.db[l],
-                            row_index=ridx)
+                            row_index=ridx, H_in=self.H[l - 1] if fuse else None)
             dY = self.dH[l]
+            masked = fuse
 
     def step(self, t: int):
         """One whole step on the current stream."""

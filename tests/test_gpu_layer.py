@@ -264,6 +264,17 @@ def test_layer_forward_backward(sub, d_in, d_out, relu, bf16, xform):
     dW2 = torch.zeros_like(dW)
     sg.sgnn_gcn_bwd(ctx(), AT, saved, dev(W), dev(Y_ref, torch.float32), dev(dY), flags, None, dW2, None)
     assert torch.equal(dW, dW2)
+    # the ReLU backward of the layer below fused into the product that writes dH: zero where H_in <= 0
+    Hm = np.maximum(_rand((B, d_in), 5), 0)
+    dH3 = torch.full((B, d_in), 7.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_gcn_bwd(ctx(), AT, saved, dev(W), dev(Y_ref, torch.float32), dev(dY), flags, dH3, dW2, None, H_in=dev(Hm))
+    assert torch.equal(dH3, dH * (dev(Hm) > 0))
+    # ... and the other side of that contract: a dY that already carries this layer's mask needs no Y
+    if relu:
+        dYm = dY * (Y_ref > 0)
+        dH4 = torch.zeros_like(dH); dW4 = torch.zeros_like(dW); db4 = torch.zeros_like(db)
+        sg.sgnn_gcn_bwd(ctx(), AT, saved, dev(W), None, dev(dYm.astype(np.float32)), flags | sg.SGNN_DY_MASKED, dH4, dW4, db4)
+        assert torch.equal(dH4, dH) and torch.equal(dW4, dW) and torch.equal(db4, db)
 
 
 def test_backward_uses_the_transpose():
@@ -299,7 +310,7 @@ def test_softmax_xent_and_gather():
     assert torch.equal(lo, lo2)
 
 
-def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True):
+def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_bwd=True):
     cfg = si.CONFIGS[name]
     bf16 = cfg.bf16_mfma if bf16 is None else bf16
     # inputs are generated with torch on the GPU (integer parts are device independent) and copied
@@ -310,7 +321,7 @@ def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True):
     weights = si.layer_weights(cfg)
     st = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld,
                     [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B, cfg.sampler_seed, bf16=bf16,
-                    fuse_slice=fuse_slice, device=DEV, auto_order=auto_order)
+                    fuse_slice=fuse_slice, device=DEV, auto_order=auto_order, fuse_relu_bwd=fuse_relu_bwd)
     g = si.Graph(cfg.N, gd.rowptr.cpu(), gd.colidx.cpu())
     X, labels = Xd.cpu(), ld.cpu()
     wnp = [(W.double().numpy(), b.double().numpy()) for W, b in weights]
@@ -348,13 +359,17 @@ def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True):
             assert rel_err(st.dW[l].cpu().numpy(), ref["dW"][l]) < tol, ("dW", l)
             assert rel_err(st.db[l].cpu().numpy(), ref["db"][l]) < tol, ("db", l)
             if l > 0:
-                assert rel_err(st.dH[l].cpu().numpy(), ref["dH"][l]) < tol, ("dH", l)
+                # with the ReLU backward of layer l-1 fused into the product that writes dH, the buffer holds
+                # dH where H_{l-1} > 0 and zero elsewhere (the mask was checked against the oracle's above)
+                want = ref["dH"][l] * ties[l - 1] if fuse_relu_bwd else ref["dH"][l]
+                assert rel_err(st.dH[l].cpu().numpy(), want) < tol, ("dH", l)
 
 
+@pytest.mark.parametrize("fuse_relu_bwd", [False, True])
 @pytest.mark.parametrize("auto_order", [False, True])
 @pytest.mark.parametrize("fuse_slice", [False, True])
-def test_whole_step_tiny(fuse_slice, auto_order):
-    _run_config("tiny", [0, 1], fuse_slice, auto_order=auto_order)
+def test_whole_step_tiny(fuse_slice, auto_order, fuse_relu_bwd):
+    _run_config("tiny", [0, 1], fuse_slice, auto_order=auto_order, fuse_relu_bwd=fuse_relu_bwd)
 
 
 def test_whole_step_with_a_narrowing_first_layer():
