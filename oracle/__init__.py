@@ -204,6 +204,48 @@ def softmax_xent(O, labels):
     return float(loss), dO
 
 
+def dropout_keep(seed: int, layer: int, step: int, n_elems: int, q: float) -> np.ndarray:
+    """Boolean keep mask of the first n_elems elements of a layer (row-major element numbering)."""
+    L = lib()
+    L.oracle_dropout_mask.restype = None
+    L.oracle_dropout_mask.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint64, C.c_double, C.c_void_p]
+    out = np.zeros(n_elems, np.uint8)
+    L.oracle_dropout_mask(seed, layer, step, n_elems, q, out.ctypes.data)
+    return out.astype(bool)
+
+
+def tail_fwd(Z, gamma=None, eps: float = 1e-6, R=None, q: float = 0.0, seed: int = 0, layer: int = 0, step: int = 0):
+    """Y = dropout(relu(rmsnorm(Z; gamma, eps)), q) + R  (Eqs. 7-10).  Returns (Y, inv_rms, Xn), float64."""
+    Z = _arr(Z, np.float64)
+    g = None if gamma is None else _arr(gamma, np.float64)
+    r = None if R is None else _arr(R, np.float64)
+    Bn, d = Z.shape
+    Y = np.zeros_like(Z); ir = np.zeros(Bn, np.float64); Xn = np.zeros_like(Z)
+    L = lib()
+    L.oracle_tail_fwd.restype = None
+    L.oracle_tail_fwd.argtypes = [C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p, C.c_double,
+                                  C.c_uint64, C.c_uint32, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.oracle_tail_fwd(Bn, d, Z.ctypes.data, g.ctypes.data if g is not None else None, eps,
+                      r.ctypes.data if r is not None else None, q, seed, layer, step, Y.ctypes.data, ir.ctypes.data,
+                      Xn.ctypes.data)
+    return Y, ir, Xn
+
+
+def tail_bwd(Z, dY, gamma=None, eps: float = 1e-6, q: float = 0.0, seed: int = 0, layer: int = 0, step: int = 0):
+    """Backward of the main branch of the layer tail.  Returns (dZ, dgamma), float64."""
+    Z = _arr(Z, np.float64); dY = _arr(dY, np.float64)
+    g = None if gamma is None else _arr(gamma, np.float64)
+    Bn, d = Z.shape
+    dZ = np.zeros_like(Z); dg = np.zeros(d, np.float64)
+    L = lib()
+    L.oracle_tail_bwd.restype = None
+    L.oracle_tail_bwd.argtypes = [C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_double, C.c_double, C.c_uint64,
+                                  C.c_uint32, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.oracle_tail_bwd(Bn, d, Z.ctypes.data, g.ctypes.data if g is not None else None, eps, q, seed, layer, step,
+                      dY.ctypes.data, dZ.ctypes.data, dg.ctypes.data)
+    return dZ, dg
+
+
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
 

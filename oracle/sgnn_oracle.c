@@ -14,11 +14,21 @@
  *   oracle_gcn_bwd          Sec. III-C, the three layer-backward equations (grad W, grad H_agg,
  *                           transposed SpMM)
  *   oracle_softmax_xent     Sec. III-B "Output Head and Loss" (cross-entropy, single label)
+ *   oracle_tail_fwd/_bwd    Sec. III-B Eqs. 7-10 (RMSNorm with a learnable scale, ReLU, dropout,
+ *                           residual add) and the element-wise part of Sec. III-C
+ *   oracle_dropout_keep     the dropout mask M_drop of Eq. 9 (see below)
  * The random generator is not the paper's (it uses a framework permutation whose stream is not
  * reproducible).  The sample is pinned instead as: the B vertices with the smallest
  * (key(v), v), where key(v) is 64 bits of Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11)
  * keyed by the seed and counted by (v / 2, step).  Any exact selection of that set is uniform
  * over B-subsets whenever keys are distinct, which is what Eq. 20 asks for.
+ *
+ * Dropout (Eq. 9) needs random numbers too.  The mask is pinned as: element e = i * d + j of
+ * layer l at step t is kept iff word (e mod 4) of Philox4x32-10 with key = (seed lo, seed hi) and
+ * counter = (e / 4 lo, e / 4 hi, t mod 2^32, 2^31 + l) is >= floor(q * 2^32); kept elements are
+ * scaled by 1 / (1 - q) (the paper only says a fraction is zeroed; the scaling that keeps the
+ * expectation is the reading taken).  RMSNorm: n = gamma * z / sqrt(mean(z^2) + eps); the paper's
+ * RMS has no eps (eps = 0 gives its formula exactly).
  *
  * All floating-point work is done in double precision.  Values that the method stores in fp32
  * (edge weights) are rounded to fp32 once, where the definition says they are stored.
@@ -376,6 +386,86 @@ double oracle_softmax_xent(int64_t B, int64_t C, const double *O, const int32_t 
                 dO[i * C + j] = (exp(o[j] - lse) - (j == labels[i] ? 1.0 : 0.0)) / (double)B;
     }
     return loss / (double)B;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Layer tail (Eqs. 7-10): Y = dropout(relu(rmsnorm(Z))) + R                                    */
+
+/* 1 if element e of layer `layer` at step `step` survives dropout with drop probability q. */
+int oracle_dropout_keep(uint64_t seed, uint32_t layer, uint64_t step, uint64_t e, double q)
+{
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    const uint64_t blk = e / 4;
+    const uint32_t ctr[4] = {(uint32_t)blk, (uint32_t)(blk >> 32), (uint32_t)step, 0x80000000u + layer};
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    const uint32_t thr = (uint32_t)floor(q * 4294967296.0);
+    return out[e % 4] >= thr;
+}
+
+void oracle_dropout_mask(uint64_t seed, uint32_t layer, uint64_t step, uint64_t n, double q, uint8_t *keep)
+{
+    for (uint64_t e = 0; e < n; ++e) keep[e] = (uint8_t)oracle_dropout_keep(seed, layer, step, e, q);
+}
+
+/*
+ * Forward.  Z: B x d (the convolution output X_conv), gamma: d (NULL = ones), R: B x d residual
+ * input X_{h,l-1} or NULL.  Y: B x d out.  Optional outputs (NULL to skip): inv_rms[B] =
+ * 1 / sqrt(mean(z^2) + eps), Xn: B x d the normalised values of Eq. 7.
+ */
+void oracle_tail_fwd(int64_t B, int64_t d, const double *Z, const double *gamma, double eps, const double *R,
+                     double q, uint64_t seed, uint32_t layer, uint64_t step, double *Y, double *inv_rms, double *Xn)
+{
+    const double scale = q > 0.0 ? 1.0 / (1.0 - q) : 1.0;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < B; ++i) {
+        double ss = 0.0;
+        for (int64_t j = 0; j < d; ++j) ss += Z[i * d + j] * Z[i * d + j];
+        const double ir = 1.0 / sqrt(ss / (double)d + eps);                           /* Eq. 7 */
+        if (inv_rms) inv_rms[i] = ir;
+        for (int64_t j = 0; j < d; ++j) {
+            const double n = (gamma ? gamma[j] : 1.0) * Z[i * d + j] * ir;
+            if (Xn) Xn[i * d + j] = n;
+            double r = n > 0.0 ? n : 0.0;                                             /* Eq. 8 */
+            if (q > 0.0) r = oracle_dropout_keep(seed, layer, step, (uint64_t)(i * d + j), q) ? r * scale : 0.0; /* Eq. 9 */
+            Y[i * d + j] = r + (R ? R[i * d + j] : 0.0);                              /* Eq. 10 */
+        }
+    }
+}
+
+/*
+ * Backward of the main branch (Sec. III-C: dropout mask, ReLU mask, RMSNorm backward): given
+ * dY = grad of Y, returns dZ (B x d) and dgamma (d, NULL to skip).  The gradient of the skip path
+ * is dY itself (Eq. 10) and is not formed here.
+ * With zhat = z * inv_rms and n = gamma * zhat:  dn = dY * M_drop * [n > 0],
+ * dgamma = sum_i dn * zhat,  dzhat = dn * gamma,  dz = (dzhat - zhat * mean_j(dzhat * zhat)) * inv_rms.
+ */
+void oracle_tail_bwd(int64_t B, int64_t d, const double *Z, const double *gamma, double eps, double q, uint64_t seed,
+                     uint32_t layer, uint64_t step, const double *dY, double *dZ, double *dgamma)
+{
+    const double scale = q > 0.0 ? 1.0 / (1.0 - q) : 1.0;
+    if (dgamma) for (int64_t j = 0; j < d; ++j) dgamma[j] = 0.0;
+    double *dn = (double *)malloc(sizeof(double) * (size_t)(d > 0 ? d : 1));
+    for (int64_t i = 0; i < B; ++i) {
+        double ss = 0.0;
+        for (int64_t j = 0; j < d; ++j) ss += Z[i * d + j] * Z[i * d + j];
+        const double ir = 1.0 / sqrt(ss / (double)d + eps);
+        double dot = 0.0;
+        for (int64_t j = 0; j < d; ++j) {
+            const double g = gamma ? gamma[j] : 1.0, zh = Z[i * d + j] * ir, n = g * zh;
+            double m = n > 0.0 ? 1.0 : 0.0;
+            if (q > 0.0) m *= oracle_dropout_keep(seed, layer, step, (uint64_t)(i * d + j), q) ? scale : 0.0;
+            dn[j] = dY[i * d + j] * m;
+            if (dgamma) dgamma[j] += dn[j] * zh;
+            dot += dn[j] * g * zh;
+        }
+        dot /= (double)d;
+        for (int64_t j = 0; j < d; ++j) {
+            const double g = gamma ? gamma[j] : 1.0, zh = Z[i * d + j] * ir;
+            dZ[i * d + j] = (dn[j] * g - zh * dot) * ir;
+        }
+    }
+    free(dn);
 }
 
 int oracle_num_threads(void)
