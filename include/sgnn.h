@@ -217,6 +217,38 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
                  float *dW, float *dbias, sgnn_stream stream);
 
 /*
+ * The element-wise tail of the paper's GNN layer as one kernel (Sec. III-B Eqs. 7-10; the fusion of
+ * Sec. V "Kernel Fusion"):   Y = dropout(relu(rmsnorm(Z))) + R
+ *   rmsnorm(z)_j = gamma_j z_j / sqrt(mean_j z_j^2 + eps)        (Eq. 7; the paper's RMS has no eps: eps = 0)
+ *   dropout: element e = i * d + j of layer `layer` at step `step` is kept iff word e % 4 of
+ *            Philox4x32-10 with key = (drop_seed lo, hi), counter = (e / 4 lo, e / 4 hi, step mod 2^32,
+ *            2^31 + layer) is >= floor(drop_q * 2^32); kept values are multiplied by 1 / (1 - drop_q)
+ *   Z       B x d fp32, the convolution output X_conv;  gamma fp32[d] or NULL (ones)
+ *   R       optional B x d fp32 residual input X_{h,l-1} (Eq. 10), NULL = none
+ *   drop_q  drop probability, 0 <= q < 1 (0 = no dropout)
+ *   Y       out B x d fp32 (must not alias Z);  inv_rms out fp32[B] = 1 / sqrt(mean z^2 + eps), kept
+ *           by the caller for sgnn_tail_bwd (NULL to skip)
+ * Rows of up to 2048 values (512 when d, the leading dimensions or the pointers are not multiples of 4 /
+ * 16 bytes); wider rows are SGNN_ERR_UNSUPPORTED.
+ */
+int sgnn_tail_fwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *gamma, float eps, const sgnn_mat *R,
+                  float drop_q, uint64_t drop_seed, uint32_t layer, uint64_t step, sgnn_mat *Y,
+                  float *inv_rms, sgnn_stream stream);
+
+/*
+ * Backward of the main branch of that tail (Sec. III-C: dropout mask, ReLU mask, RMSNorm backward).
+ * The dropout mask is recomputed from (drop_seed, layer, step), never stored.
+ *   Z, inv_rms, gamma   as in / from the forward call;  dY  B x d fp32, the gradient of Y
+ *   dZ      out B x d fp32, the gradient of X_conv (must not alias dY)
+ *   dgamma  out fp32[d] or NULL;  dbias out fp32[d] or NULL: column sums of dZ (the gradient of a
+ *           bias added in front of the tail).  Fixed summation order: bit-reproducible.
+ * The gradient of the skip path of Eq. 10 is dY itself and is not formed here.
+ */
+int sgnn_tail_bwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *inv_rms, const float *gamma, float drop_q,
+                  uint64_t drop_seed, uint32_t layer, uint64_t step, const sgnn_mat *dY, sgnn_mat *dZ,
+                  float *dgamma, float *dbias, sgnn_stream stream);
+
+/*
  * Mean softmax cross-entropy over B rows of C logits (Sec. III-B, single-label loss) and its
  * gradient dO = (softmax(O) - onehot(label)) / B.  loss_dev: device float[1] or NULL.
  */

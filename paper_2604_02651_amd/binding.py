@@ -81,13 +81,17 @@ def lib():
                                    C.POINTER(_Mat), vp]
         L.sgnn_gcn_bwd.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat),
                                    C.POINTER(_Mat), ci, C.POINTER(_Mat), C.POINTER(_Mat), vp, vp, vp]
+        u64, cf = C.c_uint64, C.c_float
+        L.sgnn_tail_fwd.argtypes = [vp, C.POINTER(_Mat), vp, cf, C.POINTER(_Mat), cf, u64, u32, u64, C.POINTER(_Mat), vp, vp]
+        L.sgnn_tail_bwd.argtypes = [vp, C.POINTER(_Mat), vp, vp, cf, u64, u32, u64, C.POINTER(_Mat), C.POINTER(_Mat), vp, vp,
+                                    vp]
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
-                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd",
+                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd",
                      "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm", "sgnn_copy_f32"):
             getattr(L, name).restype = ci
         _lib = L
@@ -281,6 +285,26 @@ def sgnn_gcn_bwd(ctx: Context, A_T: Csr, T: torch.Tensor, W: torch.Tensor, Y: Op
     ctx.check(lib().sgnn_gcn_bwd(ctx._h, C.byref(a), C.byref(t), C.byref(w), C.byref(y) if y is not None else None,
                                  C.byref(dy), flags, C.byref(dh) if dh is not None else None,
                                  C.byref(hin) if hin is not None else None, _ptr(dW, torch.float32, "dW"), _ptr(dbias, torch.float32, "dbias"), _stream(stream)))
+
+
+def sgnn_tail_fwd(ctx: Context, Z: torch.Tensor, gamma: Optional[torch.Tensor], eps: float, R: Optional[torch.Tensor],
+                  drop_q: float, drop_seed: int, layer: int, step: int, Y: torch.Tensor, inv_rms: Optional[torch.Tensor],
+                  stream=None):
+    """Y = dropout(relu(rmsnorm(Z; gamma, eps)), drop_q) + R; inv_rms (fp32[B]) is kept for sgnn_tail_bwd."""
+    z, y = _mat(Z, None, "Z"), _mat(Y, None, "Y")
+    r = _mat(R, None, "R") if R is not None else None
+    ctx.check(lib().sgnn_tail_fwd(ctx._h, C.byref(z), _ptr(gamma, torch.float32, "gamma"), eps,
+                                  C.byref(r) if r is not None else None, drop_q, drop_seed, layer, step, C.byref(y),
+                                  _ptr(inv_rms, torch.float32, "inv_rms"), _stream(stream)))
+
+
+def sgnn_tail_bwd(ctx: Context, Z: torch.Tensor, inv_rms: torch.Tensor, gamma: Optional[torch.Tensor], drop_q: float,
+                  drop_seed: int, layer: int, step: int, dY: torch.Tensor, dZ: torch.Tensor,
+                  dgamma: Optional[torch.Tensor], dbias: Optional[torch.Tensor], stream=None):
+    z, dy, dz = _mat(Z, None, "Z"), _mat(dY, None, "dY"), _mat(dZ, None, "dZ")
+    ctx.check(lib().sgnn_tail_bwd(ctx._h, C.byref(z), _ptr(inv_rms, torch.float32, "inv_rms"),
+                                  _ptr(gamma, torch.float32, "gamma"), drop_q, drop_seed, layer, step, C.byref(dy), C.byref(dz),
+                                  _ptr(dgamma, torch.float32, "dgamma"), _ptr(dbias, torch.float32, "dbias"), _stream(stream)))
 
 
 def sgnn_softmax_xent(ctx: Context, O: torch.Tensor, labels: torch.Tensor, loss: Optional[torch.Tensor],

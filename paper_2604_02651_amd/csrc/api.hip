@@ -417,6 +417,38 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     return rc;
 }
 
+int sgnn_tail_fwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *gamma, float eps, const sgnn_mat *R, float drop_q,
+                  uint64_t drop_seed, uint32_t layer, uint64_t step, sgnn_mat *Y, float *inv_rms, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!mat_ok(Z) || !mat_ok(Y) || (R && !mat_ok(R)) || Z->row_index || Y->row_index || (R && R->row_index) || !(eps >= 0.f))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_tail_fwd: bad argument");
+    if (Y->rows != Z->rows || Y->cols != Z->cols || (R && (R->rows != Z->rows || R->cols != Z->cols)))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_tail_fwd: shape mismatch");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return sgnn_launch_tail_fwd(ctx, Z->rows, Z->cols, static_cast<const float *>(Z->ptr), Z->ld, gamma, eps,
+                                R ? static_cast<const float *>(R->ptr) : nullptr, R ? R->ld : 0, drop_q, drop_seed, layer, step,
+                                static_cast<float *>(Y->ptr), Y->ld, inv_rms, static_cast<hipStream_t>(stream));
+}
+
+int sgnn_tail_bwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *inv_rms, const float *gamma, float drop_q,
+                  uint64_t drop_seed, uint32_t layer, uint64_t step, const sgnn_mat *dY, sgnn_mat *dZ, float *dgamma,
+                  float *dbias, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!mat_ok(Z) || !mat_ok(dY) || !mat_ok(dZ) || !inv_rms || Z->row_index || dY->row_index || dZ->row_index)
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_tail_bwd: bad argument");
+    if (dY->rows != Z->rows || dY->cols != Z->cols || dZ->rows != Z->rows || dZ->cols != Z->cols)
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_tail_bwd: shape mismatch");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    ws_alloc ws(ctx);
+    return sgnn_launch_tail_bwd(ctx, Z->rows, Z->cols, static_cast<const float *>(Z->ptr), Z->ld, inv_rms, gamma, drop_q,
+                                drop_seed, layer, step, static_cast<const float *>(dY->ptr), dY->ld,
+                                static_cast<float *>(dZ->ptr), dZ->ld, dgamma, dbias, &ws, static_cast<hipStream_t>(stream));
+}
+
 int sgnn_copy_f32(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;

@@ -115,6 +115,12 @@ int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const 
                               ws_alloc *ws, hipStream_t st);
 int sgnn_launch_gather(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, const int32_t *S, uint32_t B,
                        float *out, int64_t ldo, const int32_t *labels, int32_t *labels_out, hipStream_t st);
+int sgnn_launch_tail_fwd(sgnn_ctx *ctx, int64_t rows, int64_t d, const float *Z, int64_t ldz, const float *gamma, float eps,
+                         const float *R, int64_t ldr, float q, uint64_t seed, uint32_t layer, uint64_t step, float *Y,
+                         int64_t ldy, float *inv_rms, hipStream_t st);
+int sgnn_launch_tail_bwd(sgnn_ctx *ctx, int64_t rows, int64_t d, const float *Z, int64_t ldz, const float *inv_rms,
+                         const float *gamma, float q, uint64_t seed, uint32_t layer, uint64_t step, const float *dY,
+                         int64_t lddy, float *dZ, int64_t lddz, float *dgamma, float *dbias, ws_alloc *ws, hipStream_t st);
 int sgnn_launch_copy(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, hipStream_t st);
 int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C,
                      float *loss, float *dO, int64_t lddo, ws_alloc *ws, hipStream_t st);

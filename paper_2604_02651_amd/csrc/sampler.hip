@@ -15,6 +15,7 @@
 #include <algorithm>
 
 #include "common.h"
+#include "philox.h"
 
 namespace {
 
@@ -30,27 +31,6 @@ struct sampler_state {
     uint32_t thr_v;     // threshold vertex
     uint64_t thr_key;   // threshold key
 };
-
-struct philox_out { uint32_t w0, w1, w2, w3; };
-
-__device__ __forceinline__ philox_out philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
-                                                    uint32_t k1)
-{
-#pragma unroll
-    for (int i = 0; i < 10; ++i) {
-        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
-        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
-        c1 = (uint32_t)p1;
-        c3 = (uint32_t)p0;
-        c0 = n0;
-        c2 = n2;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    return {c0, c1, c2, c3};
-}
 
 // keys of vertices 2j (even) and 2j+1 (odd)
 __device__ __forceinline__ void vertex_pair_keys(uint64_t j, uint64_t seed, uint64_t step, uint64_t &ke, uint64_t &ko)
