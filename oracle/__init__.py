@@ -246,6 +246,61 @@ def tail_bwd(Z, dY, gamma=None, eps: float = 1e-6, q: float = 0.0, seed: int = 0
     return dZ, dg
 
 
+def sgd_step(w, g, lr: float, weight_decay: float = 0.0) -> np.ndarray:
+    """w - lr (g + weight_decay w): the plain gradient step (Alg. 1 line 7 names no optimizer)."""
+    w = _arr(w, np.float64); g = _arr(g, np.float64)
+    return w - lr * (g + weight_decay * w)
+
+
+def adam_step(w, g, m, v, lr: float, t: int, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8):
+    """One step of Adam (Kingma & Ba, ICLR 2015, Algorithm 1), t = 1, 2, ...  Returns (w, m, v)."""
+    w = _arr(w, np.float64); g = _arr(g, np.float64); m = _arr(m, np.float64); v = _arr(v, np.float64)
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** t)
+    vhat = v / (1.0 - beta2 ** t)
+    return w - lr * mhat / (np.sqrt(vhat) + eps), m, v
+
+
+def model_step(rowptr, colidx, val, X_S, y_S, params, drop_q: float = 0.0, drop_seed: int = 0, step: int = 0,
+               eps: float = 1e-6, bf16: bool = False):
+    """The paper's complete model on one mini-batch (Fig. 2; Sec. III-B, III-C), forward and backward:
+        X_h0 = X_S W_in;  for l = 1..L:  T_l = A X_h,l-1,  Z_l = T_l W_l,
+        X_h,l = dropout(relu(rmsnorm(Z_l; gamma_l))) + X_h,l-1;   O = X_h,L W_out;  mean cross-entropy.
+    params = {"W_in": d_in x d_h, "layers": [(W_l d_h x d_h, gamma_l d_h), ...], "W_out": d_h x c}.
+    Returns a dict with the loss, every activation and the gradient of every parameter (float64).
+    bf16: GEMM operands rounded to bfloat16 as in gcn_fwd / gcn_bwd."""
+    rp = _arr(rowptr, np.int32); ci = _arr(colidx, np.int32); v = _arr(val, np.float32)
+    Bn = rp.shape[0] - 1
+    rd = (lambda a: round_bf16(a)) if bf16 else (lambda a: _arr(a, np.float64))
+    X_S = _arr(X_S, np.float64)
+    W_in = _arr(params["W_in"], np.float64); W_out = _arr(params["W_out"], np.float64)
+    Xh = [gemm(rd(X_S), rd(W_in))]
+    T, Z, IR = [], [], []
+    for l, (W, gam) in enumerate(params["layers"]):
+        T.append(spmm(rp, ci, v, Xh[-1]))                                    # Eq. 5
+        Z.append(gemm(rd(T[-1]), rd(W)))                                     # Eq. 6
+        Y, ir, _ = tail_fwd(Z[-1], gamma=gam, eps=eps, R=Xh[-1], q=drop_q, seed=drop_seed, layer=l, step=step)   # Eqs. 7-10
+        Xh.append(Y); IR.append(ir)
+    O = gemm(rd(Xh[-1]), rd(W_out))
+    loss, dO = softmax_xent(O, y_S)
+    out = {"Xh": Xh, "T": T, "Z": Z, "inv_rms": IR, "O": O, "loss": loss, "dO": dO}
+    # backward (Sec. III-C)
+    out["dW_out"] = gemm(rd(Xh[-1]).T.copy(), rd(dO))
+    dX = gemm(rd(dO), rd(W_out).T.copy())
+    rpT, ciT, vT = csr_transpose(Bn, Bn, rp, ci, v)
+    dWs, dgs = [None] * len(Z), [None] * len(Z)
+    for l in range(len(Z) - 1, -1, -1):
+        W, gam = params["layers"][l]
+        dZ, dg = tail_bwd(Z[l], dX, gamma=gam, eps=eps, q=drop_q, seed=drop_seed, layer=l, step=step)
+        dWs[l] = gemm(rd(T[l]).T.copy(), rd(dZ)); dgs[l] = dg
+        dT = gemm(rd(dZ), rd(_arr(W, np.float64)).T.copy())
+        dX = spmm(rpT, ciT, vT, dT) + dX                                     # conv path + skip path
+    out["dW"] = dWs; out["dgamma"] = dgs
+    out["dW_in"] = gemm(rd(X_S).T.copy(), rd(dX)); out["dXh0"] = dX
+    return out
+
+
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
 
