@@ -255,10 +255,28 @@ int sgnn_tail_bwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *inv_rms, const 
 int sgnn_softmax_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B,
                       uint32_t C, float *loss_dev, float *dO, int64_t lddo, sgnn_stream stream);
 
+/*
+ * Parameter update ("update parameters", Alg. 1 line 7; the paper names no optimizer).
+ * sgnn_sgd_step:  w <- w - lr * (g + weight_decay * w)
+ * sgnn_adam_step: Adam (Kingma & Ba, ICLR 2015, Algorithm 1) with bias correction:
+ *     m <- b1 m + (1 - b1) g;  v <- b2 v + (1 - b2) g^2;
+ *     w <- w - lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps),   t = 1, 2, ... the step number
+ * w, g, m, v: device fp32[n], updated in place (g is read only).  The scalars are host doubles; the factors
+ * derived from them (1 - b1, 1 / (1 - b1^t), ...) are evaluated in double precision and rounded to fp32 once.
+ */
+int sgnn_sgd_step(sgnn_ctx *ctx, float *w, const float *g, int64_t n, double lr, double weight_decay,
+                  sgnn_stream stream);
+int sgnn_adam_step(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v, int64_t n, double lr,
+                   double beta1, double beta2, double eps, int64_t t, sgnn_stream stream);
+
 /* Plain operators, exported for tests and for callers that build their own layer. */
 
-/* out = A X: A rows x cols CSR, X cols x d fp32 (X->row_index honoured), out rows x d fp32. */
-int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, sgnn_mat *out, sgnn_stream stream);
+/*
+ * out = A X (+ add): A rows x cols CSR, X cols x d fp32 (X->row_index honoured), out rows x d fp32;
+ * add: optional rows x d fp32 matrix added to the product (NULL = none; must not be `out`) - the skip path of a residual layer merged into the transposed product of Sec. III-C.
+ */
+int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_mat *add, sgnn_mat *out,
+              sgnn_stream stream);
 
 /*
  * C = act(op(A) op(B) + bias): fp32 row-major, M x N result, reduction length K.

@@ -85,13 +85,16 @@ def lib():
         L.sgnn_tail_fwd.argtypes = [vp, C.POINTER(_Mat), vp, cf, C.POINTER(_Mat), cf, u64, u32, u64, C.POINTER(_Mat), vp, vp]
         L.sgnn_tail_bwd.argtypes = [vp, C.POINTER(_Mat), vp, vp, cf, u64, u32, u64, C.POINTER(_Mat), C.POINTER(_Mat), vp, vp,
                                     vp]
+        cd = C.c_double
+        L.sgnn_sgd_step.argtypes = [vp, vp, vp, i64, cd, cd, vp]
+        L.sgnn_adam_step.argtypes = [vp, vp, vp, vp, vp, i64, cd, cd, cd, cd, i64, vp]
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
-        L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), vp]
+        L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
-                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd",
+                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_sgd_step", "sgnn_adam_step",
                      "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm", "sgnn_copy_f32"):
             getattr(L, name).restype = ci
         _lib = L
@@ -316,10 +319,38 @@ def sgnn_softmax_xent(ctx: Context, O: torch.Tensor, labels: torch.Tensor, loss:
 
 
 def sgnn_spmm(ctx: Context, A: Csr, X: torch.Tensor, out: torch.Tensor, row_index: Optional[torch.Tensor] = None,
-              stream=None):
+              stream=None, add: Optional[torch.Tensor] = None):
+    """out = A X (+ add)."""
     a = A.struct()
     x, o = _mat(X, row_index, "X"), _mat(out, None, "out")
-    ctx.check(lib().sgnn_spmm(ctx._h, C.byref(a), C.byref(x), C.byref(o), _stream(stream)))
+    ad = _mat(add, None, "add") if add is not None else None
+    ctx.check(lib().sgnn_spmm(ctx._h, C.byref(a), C.byref(x), C.byref(ad) if ad is not None else None, C.byref(o),
+                              _stream(stream)))
+
+
+def _flat(t: torch.Tensor, name: str) -> torch.Tensor:
+    if t.dtype != torch.float32 or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous float32 tensor" % name)
+    return t
+
+
+def sgnn_sgd_step(ctx: Context, w: torch.Tensor, g: torch.Tensor, lr: float, weight_decay: float = 0.0, stream=None):
+    """w <- w - lr (g + weight_decay w), in place."""
+    _flat(w, "w"); _flat(g, "g")
+    if g.numel() != w.numel():
+        raise ValueError("g must have as many elements as w")
+    ctx.check(lib().sgnn_sgd_step(ctx._h, w.data_ptr(), g.data_ptr(), w.numel(), lr, weight_decay, _stream(stream)))
+
+
+def sgnn_adam_step(ctx: Context, w: torch.Tensor, g: torch.Tensor, m: torch.Tensor, v: torch.Tensor, lr: float, t: int,
+                   beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, stream=None):
+    """One Adam update of w in place; m, v are the moment buffers, t = 1, 2, ... the step number."""
+    for x, nm in ((w, "w"), (g, "g"), (m, "m"), (v, "v")):
+        _flat(x, nm)
+        if x.numel() != w.numel():
+            raise ValueError("%s must have as many elements as w" % nm)
+    ctx.check(lib().sgnn_adam_step(ctx._h, w.data_ptr(), g.data_ptr(), m.data_ptr(), v.data_ptr(), w.numel(), lr, beta1,
+                                   beta2, eps, t, _stream(stream)))
 
 
 def sgnn_gemm(ctx: Context, trans_a: bool, trans_b: bool, A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor],

@@ -274,17 +274,20 @@ int sgnn_gather_rows(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, cons
     return sgnn_launch_gather(ctx, X, d, ldx, S, B, out, ldo, labels, labels_out, static_cast<hipStream_t>(stream));
 }
 
-int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, sgnn_mat *out, sgnn_stream stream)
+int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_mat *add, sgnn_mat *out, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     if (!csr_ok(A) || !mat_ok(X) || !mat_ok(out)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: bad argument");
-    if (out->rows != A->rows || out->cols != X->cols || (!X->row_index && X->rows != A->cols))
+    if (out->rows != A->rows || out->cols != X->cols || (!X->row_index && X->rows != A->cols) ||
+        (add && (!mat_ok(add) || add->row_index || add->rows != out->rows || add->cols != out->cols)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: shape mismatch");
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
     return sgnn_launch_spmm(ctx, A, static_cast<const float *>(X->ptr), X->ld, X->row_index, X->cols,
-                            static_cast<float *>(out->ptr), out->ld, nullptr, 0, nullptr, 0, &ws, static_cast<hipStream_t>(stream));
+                            static_cast<float *>(out->ptr), out->ld, nullptr, 0, nullptr, 0,
+                            add ? static_cast<const float *>(add->ptr) : nullptr, add ? add->ld : 0, &ws,
+                            static_cast<hipStream_t>(stream));
 }
 
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
@@ -322,7 +325,7 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
     if (!xform_first) {
         // Eqs. 5-6 in the paper's order: aggregate, then transform with bias and activation fused
         rc = sgnn_launch_spmm(ctx, A, static_cast<const float *>(H->ptr), H->ld, H->row_index, d_in,
-                              static_cast<float *>(T->ptr), T->ld, nullptr, 0, nullptr, 0, &ws, st);
+                              static_cast<float *>(T->ptr), T->ld, nullptr, 0, nullptr, 0, nullptr, 0, &ws, st);
         if (rc) return rc;
         return sgnn_launch_gemm(ctx, 0, 0, Bn, d_out, d_in, static_cast<const float *>(T->ptr), T->ld, nullptr,
                                 static_cast<const float *>(W->ptr), W->ld, bias, gflags, static_cast<float *>(Y->ptr), Y->ld,
@@ -337,7 +340,7 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
                           static_cast<const float *>(W->ptr), W->ld, nullptr, flags & SGNN_BF16_MFMA, P, ldp, nullptr, 0, &ws, st);
     if (rc) return rc;
     return sgnn_launch_spmm(ctx, A, P, ldp, nullptr, d_out, static_cast<float *>(Y->ptr), Y->ld, bias,
-                            (flags & SGNN_RELU) ? 1 : 0, nullptr, 0, &ws, st);
+                            (flags & SGNN_RELU) ? 1 : 0, nullptr, 0, nullptr, 0, &ws, st);
 }
 
 int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sgnn_mat *W, const sgnn_mat *Y,
@@ -397,7 +400,7 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
             rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, nullptr, static_cast<const float *>(W->ptr), W->ld,
                                   nullptr, mfma, dT, ld_in, nullptr, 0, &ws, st);
             if (rc) return rc;
-            rc = sgnn_launch_spmm(ctx, A_T, dT, ld_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, hmask, ldhm, &ws,
+            rc = sgnn_launch_spmm(ctx, A_T, dT, ld_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, hmask, ldhm, nullptr, 0, &ws,
                                   st);
             if (rc) return rc;
         }
@@ -406,7 +409,7 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     // transform-first layer: dP = A^T dZ (width d_out), dW = H^T dP, dH = dP W^T; T is the layer input H
     float *dP = ws.get<float>((size_t)Bn * ld_out);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
-    rc = sgnn_launch_spmm(ctx, A_T, dZ, lddz, nullptr, d_out, dP, ld_out, nullptr, 0, nullptr, 0, &ws, st);
+    rc = sgnn_launch_spmm(ctx, A_T, dZ, lddz, nullptr, d_out, dP, ld_out, nullptr, 0, nullptr, 0, nullptr, 0, &ws, st);
     if (rc) return rc;
     rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, T->row_index, dP, ld_out,
                           nullptr, mfma, dW, d_out, nullptr, 0, &ws, st);
@@ -447,6 +450,26 @@ int sgnn_tail_bwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *inv_rms, const 
     return sgnn_launch_tail_bwd(ctx, Z->rows, Z->cols, static_cast<const float *>(Z->ptr), Z->ld, inv_rms, gamma, drop_q,
                                 drop_seed, layer, step, static_cast<const float *>(dY->ptr), dY->ld,
                                 static_cast<float *>(dZ->ptr), dZ->ld, dgamma, dbias, &ws, static_cast<hipStream_t>(stream));
+}
+
+int sgnn_sgd_step(sgnn_ctx *ctx, float *w, const float *g, int64_t n, double lr, double weight_decay, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (n < 0 || (n > 0 && (!w || !g))) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_sgd_step: bad argument");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return sgnn_launch_sgd(ctx, w, g, n, lr, weight_decay, static_cast<hipStream_t>(stream));
+}
+
+int sgnn_adam_step(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v, int64_t n, double lr, double beta1,
+                   double beta2, double eps, int64_t t, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (n < 0 || t < 1 || !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0) || (n > 0 && (!w || !g || !m || !v)))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_adam_step: bad argument");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return sgnn_launch_adam(ctx, w, g, m, v, n, lr, beta1, beta2, eps, t, static_cast<hipStream_t>(stream));
 }
 
 int sgnn_copy_f32(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, sgnn_stream stream)

@@ -103,7 +103,7 @@ int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, ui
                         sgnn_csr *out, hipStream_t st);
 int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index,
                      int64_t d, float *out, int64_t ldo, const float *bias, int relu, const float *mask, int64_t ldm,
-                     ws_alloc *ws, hipStream_t st);
+                     const float *add, int64_t ldadd, ws_alloc *ws, hipStream_t st);
 int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st);   // fills A->plan when it is attached
 // a_row_index (may be NULL): physical row of A for every logical row (M x K operand: rows of the
 // result; K x M operand used transposed: reduction index)
@@ -121,6 +121,9 @@ int sgnn_launch_tail_fwd(sgnn_ctx *ctx, int64_t rows, int64_t d, const float *Z,
 int sgnn_launch_tail_bwd(sgnn_ctx *ctx, int64_t rows, int64_t d, const float *Z, int64_t ldz, const float *inv_rms,
                          const float *gamma, float q, uint64_t seed, uint32_t layer, uint64_t step, const float *dY,
                          int64_t lddy, float *dZ, int64_t lddz, float *dgamma, float *dbias, ws_alloc *ws, hipStream_t st);
+int sgnn_launch_sgd(sgnn_ctx *ctx, float *w, const float *g, int64_t n, double lr, double wd, hipStream_t st);
+int sgnn_launch_adam(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v, int64_t n, double lr, double b1, double b2,
+                     double eps, int64_t t, hipStream_t st);
 int sgnn_launch_copy(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, hipStream_t st);
 int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C,
                      float *loss, float *dO, int64_t lddo, ws_alloc *ws, hipStream_t st);

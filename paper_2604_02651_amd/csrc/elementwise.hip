@@ -3,6 +3,8 @@
 #include <algorithm>
 
 #include "block_prims.h"
+#include <math.h>
+
 #include "common.h"
 
 namespace {
@@ -188,6 +190,29 @@ __global__ __launch_bounds__(256) void copy_f32_kernel(const f32x4 *__restrict__
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// w <- w - lr * (g + wd * w)
+__global__ __launch_bounds__(256) void sgd_kernel(float *__restrict__ w, const float *__restrict__ g, int64_t n, float lr,
+                                                  float wd)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) w[i] = w[i] - lr * (g[i] + wd * w[i]);
+}
+
+// Adam with bias correction; omb = 1 - b, c1 = 1 / (1 - b1^t), c2 = 1 / (1 - b2^t) evaluated on the host in double precision
+__global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, const float *__restrict__ g, float *__restrict__ m,
+                                                   float *__restrict__ v, int64_t n, float lr, float b1, float b2, float omb1,
+                                                   float omb2, float eps, float c1, float c2)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const float gi = g[i];
+    const float mi = b1 * m[i] + omb1 * gi;
+    const float vi = b2 * v[i] + omb2 * gi * gi;
+    m[i] = mi;
+    v[i] = vi;
+    w[i] = w[i] - lr * (mi * c1) / (sqrtf(vi * c2) + eps);
+}
+
 } // namespace
 
 int sgnn_launch_copy(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, hipStream_t st)
@@ -264,5 +289,22 @@ int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *
     if (loss) {
         SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, 1.f / (float)B, loss);
     }
+    return SGNN_OK;
+}
+
+int sgnn_launch_sgd(sgnn_ctx *ctx, float *w, const float *g, int64_t n, double lr, double wd, hipStream_t st)
+{
+    if (n == 0) return SGNN_OK;
+    SGNN_LAUNCH(ctx, st, "sgd_kernel", SGNN_TAG, sgd_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, w, g, n, (float)lr, (float)wd);
+    return SGNN_OK;
+}
+
+int sgnn_launch_adam(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v, int64_t n, double lr, double b1, double b2,
+                     double eps, int64_t t, hipStream_t st)
+{
+    if (n == 0) return SGNN_OK;
+    const float c1 = (float)(1.0 / (1.0 - pow(b1, (double)t))), c2 = (float)(1.0 / (1.0 - pow(b2, (double)t)));
+    SGNN_LAUNCH(ctx, st, "adam_kernel", SGNN_TAG, adam_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, w, g, m, v, n, (float)lr,
+                (float)b1, (float)b2, (float)(1.0 - b1), (float)(1.0 - b2), (float)eps, c1, c2);
     return SGNN_OK;
 }

@@ -138,6 +138,8 @@ struct spmm_epi {
     int relu;
     const float *mask;
     int64_t ldm;
+    const float *add;   // optional matrix added to the result last (the skip path of a residual layer)
+    int64_t ldadd;
 };
 
 template <int VEC>
@@ -153,6 +155,12 @@ __device__ __forceinline__ void spmm_epilogue(float (&v)[VEC], const spmm_epi &e
         vload<VEC>(m, ep.mask + row * ep.ldm + col);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) v[i] = m[i] > 0.f ? v[i] : 0.f;
+    }
+    if (ep.add) {
+        float a[VEC];
+        vload<VEC>(a, ep.add + row * ep.ldadd + col);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] += a[i];
     }
 }
 
@@ -520,14 +528,15 @@ int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st)
 }
 
 int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int64_t d,
-                     float *out, int64_t ldo, const float *bias, int relu, const float *mask, int64_t ldm, ws_alloc *ws,
-                     hipStream_t st)
+                     float *out, int64_t ldo, const float *bias, int relu, const float *mask, int64_t ldm, const float *add,
+                     int64_t ldadd, ws_alloc *ws, hipStream_t st)
 {
-    const spmm_epi ep = {bias, relu, mask, ldm};
+    const spmm_epi ep = {bias, relu, mask, ldm, add, ldadd};
     if (A->rows == 0 || d == 0) return SGNN_OK;
-    const uintptr_t bits = reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(mask);
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(mask) |
+                           reinterpret_cast<uintptr_t>(add);
     // the narrowest vector with which one wavefront still covers the row
-    const int64_t lds_ = ldx | ldo | (mask ? ldm : 0);
+    const int64_t lds_ = ldx | ldo | (mask ? ldm : 0) | (add ? ldadd : 0);
     const bool ok4 = d % 4 == 0 && lds_ % 4 == 0 && (bits & 15) == 0;
     const bool ok2 = d % 2 == 0 && lds_ % 2 == 0 && (bits & 7) == 0;
     if (d <= 64) return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
