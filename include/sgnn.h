@@ -217,6 +217,17 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
                  float *dW, float *dbias, sgnn_stream stream);
 
 /*
+ * The full graph as a sparse matrix for the full-graph evaluation forward (the paper's evaluation
+ * rounds run the model on all N vertices): int32 row offsets and the weights of Eq. 3,
+ * a_vu = 1 / sqrt(deg(v) deg(u)) (g->val verbatim when given), no 1/p rescale.
+ *   rowptr32  out device int32[N + 1];  val out device fp32[E]
+ * Together with g->colidx they form an sgnn_csr {rows = cols = N, capacity = E} for sgnn_gcn_fwd /
+ * sgnn_spmm.  Graphs with 2^31 - 1 or more stored entries are SGNN_ERR_UNSUPPORTED (32-bit offsets).
+ */
+int sgnn_graph_normalized_csr(sgnn_ctx *ctx, const sgnn_graph *g, int32_t *rowptr32, float *val,
+                              sgnn_stream stream);
+
+/*
  * The element-wise tail of the paper's GNN layer as one kernel (Sec. III-B Eqs. 7-10; the fusion of
  * Sec. V "Kernel Fusion"):   Y = dropout(relu(rmsnorm(Z))) + R
  *   rmsnorm(z)_j = gamma_j z_j / sqrt(mean_j z_j^2 + eps)        (Eq. 7; the paper's RMS has no eps: eps = 0)

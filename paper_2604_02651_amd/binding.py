@@ -88,13 +88,14 @@ def lib():
         cd = C.c_double
         L.sgnn_sgd_step.argtypes = [vp, vp, vp, i64, cd, cd, vp]
         L.sgnn_adam_step.argtypes = [vp, vp, vp, vp, vp, i64, cd, cd, cd, cd, i64, vp]
+        L.sgnn_graph_normalized_csr.argtypes = [vp, C.POINTER(_Graph), vp, vp, vp]
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
-                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_sgd_step", "sgnn_adam_step",
+                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr",
                      "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm", "sgnn_copy_f32"):
             getattr(L, name).restype = ci
         _lib = L
@@ -246,6 +247,32 @@ def sgnn_induced_csr(ctx: Context, N: int, rowptr: torch.Tensor, colidx: torch.T
     out.rows = out.cols = B
     ctx.check(rc)
     return int(nnz.value) if want_nnz else None
+
+
+def sgnn_graph_normalized_csr(ctx: Context, N: int, rowptr: torch.Tensor, colidx: torch.Tensor,
+                              val: Optional[torch.Tensor] = None, with_plan: bool = True, stream=None) -> Csr:
+    """The full graph as an N x N Csr for the full-graph evaluation forward: int32 row offsets and the weights of
+    Eq. 3 are written by the library; the column indices are the graph's own tensor (shared, not copied)."""
+    if rowptr.numel() != N + 1:
+        raise ValueError("rowptr must have N+1 entries")
+    E = int(colidx.numel())
+    g = _Graph(N, E, _ptr(rowptr, None, "rowptr"), int(rowptr.dtype == torch.int64), _ptr(colidx, torch.int32, "colidx"),
+               _ptr(val, torch.float32, "val"))
+    out = Csr.__new__(Csr)
+    out.rows, out.cols, out.capacity = N, N, E
+    dev = colidx.device
+    out.rowptr = torch.empty(N + 1, dtype=torch.int32, device=dev)
+    out.colidx = colidx
+    out.val = torch.empty(max(E, 1), dtype=torch.float32, device=dev)
+    out.nnz_dev = torch.full((1,), E, dtype=torch.int32, device=dev)
+    out.plan = None
+    ctx.check(lib().sgnn_graph_normalized_csr(ctx._h, C.byref(g), _ptr(out.rowptr, torch.int32), _ptr(out.val, torch.float32),
+                                              _stream(stream)))
+    if with_plan:
+        nbytes = int(lib().sgnn_csr_plan_bytes(N, E))
+        out.plan = torch.zeros((nbytes + 7) // 8, dtype=torch.int64, device=dev)
+        sgnn_csr_plan(ctx, out, stream=stream)
+    return out
 
 
 def sgnn_csr_plan(ctx: Context, A: Csr, stream=None):

@@ -472,6 +472,19 @@ int sgnn_adam_step(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v, 
     return sgnn_launch_adam(ctx, w, g, m, v, n, lr, beta1, beta2, eps, t, static_cast<hipStream_t>(stream));
 }
 
+int sgnn_graph_normalized_csr(sgnn_ctx *ctx, const sgnn_graph *g, int32_t *rowptr32, float *val, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!g || !g->rowptr || !g->colidx || !rowptr32 || !val)
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_graph_normalized_csr: bad argument");
+    if (g->E >= 0x7fffffffull || g->N >= 0x7fffffffull)
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_graph_normalized_csr: %llu entries do not fit 32-bit row offsets",
+                         (unsigned long long)g->E);
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return sgnn_launch_graph_normalize(ctx, g, rowptr32, val, static_cast<hipStream_t>(stream));
+}
+
 int sgnn_copy_f32(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;

@@ -368,6 +368,35 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
     return SGNN_OK;
 }
 
+// Full graph as a matrix for the evaluation forward (Sec. VI: full-graph inference): int32 row offsets and
+// the weights of Eq. 3, a_vu = 1 / sqrt(deg(v) deg(u)), evaluated in double precision and rounded once
+// (the same arithmetic as the mini-batch weights).  One wavefront per row, grid-stride; a set-up kernel.
+template <typename RP>
+__global__ __launch_bounds__(256) void graph_normalize_kernel(uint64_t N, const RP *__restrict__ rowptr,
+                                                              const int32_t *__restrict__ colidx,
+                                                              const float *__restrict__ val_in, int32_t *__restrict__ rowptr32,
+                                                              float *__restrict__ val)
+{
+    const int lane = threadIdx.x & 63;
+    const uint64_t wave = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6), nwaves = (uint64_t)gridDim.x * 4;
+    for (uint64_t v = wave; v < N; v += nwaves) {
+        const int64_t rs = (int64_t)rowptr[v], re = (int64_t)rowptr[v + 1];
+        if (lane == 0) {
+            rowptr32[v] = (int32_t)rs;
+            if (v + 1 == N) rowptr32[N] = (int32_t)re;
+        }
+        const double dv = (double)(re - rs);
+        for (int64_t e = rs + lane; e < re; e += 64) {
+            if (val_in) val[e] = val_in[e];
+            else {
+                const int64_t u = colidx[e];
+                const double du = (double)((int64_t)rowptr[u + 1] - (int64_t)rowptr[u]);
+                val[e] = (float)(1.0 / sqrt(dv * du));
+            }
+        }
+    }
+}
+
 } // namespace
 
 size_t sgnn_induced_ws_bytes(uint64_t E, uint32_t B)
@@ -382,4 +411,17 @@ int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, ui
 {
     if (g->rowptr_is_i64) return launch_typed<int64_t>(ctx, g, S, B, bitmap, rank, norm_mode, rescale, out, st);
     return launch_typed<int32_t>(ctx, g, S, B, bitmap, rank, norm_mode, rescale, out, st);
+}
+
+int sgnn_launch_graph_normalize(sgnn_ctx *ctx, const sgnn_graph *g, int32_t *rowptr32, float *val, hipStream_t st)
+{
+    if (g->N == 0) return SGNN_OK;
+    const unsigned nwg = (unsigned)std::min<uint64_t>((g->N + 3) / 4, 1u << 16);
+    if (g->rowptr_is_i64)
+        SGNN_LAUNCH(ctx, st, "graph_normalize_kernel", SGNN_TAG, graph_normalize_kernel<int64_t>, dim3(nwg), dim3(256), 0, st, g->N,
+                    static_cast<const int64_t *>(g->rowptr), g->colidx, g->val, rowptr32, val);
+    else
+        SGNN_LAUNCH(ctx, st, "graph_normalize_kernel", SGNN_TAG, graph_normalize_kernel<int32_t>, dim3(nwg), dim3(256), 0, st, g->N,
+                    static_cast<const int32_t *>(g->rowptr), g->colidx, g->val, rowptr32, val);
+    return SGNN_OK;
 }
