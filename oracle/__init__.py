@@ -126,6 +126,26 @@ def induced_csr(N: int, rowptr, colidx, S, val=None, norm_mode: int = 0, rescale
     return rpS, ciS[:nnz].copy(), vS[:nnz].copy()
 
 
+def induced_csr_range(N: int, rowptr, colidx, S, R0: int, R1: int, C0: int, C1: int, val=None, rescale: int = 1):
+    """Algorithm 2 for one shard: rows of S in [R0, R1), columns of S in [C0, C1); B x B namespace."""
+    rp = _arr(rowptr, np.int64); ci = _arr(colidx, np.int32); S = _arr(S, np.int32)
+    vv = None if val is None else _arr(val, np.float32)
+    B = int(S.shape[0])
+    cap = max(int((rp[S.astype(np.int64) + 1] - rp[S.astype(np.int64)]).sum()), 1)
+    rpS = np.zeros(B + 1, np.int32); ciS = np.zeros(cap, np.int32); vS = np.zeros(cap, np.float32)
+    L = lib()
+    L.oracle_induced_csr_range.restype = C.c_int64
+    L.oracle_induced_csr_range.argtypes = [C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_int,
+                                           C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_int64]
+    nnz = L.oracle_induced_csr_range(N, rp.ctypes.data, ci.ctypes.data, vv.ctypes.data if vv is not None else None,
+                                     S.ctypes.data, B, rescale, R0, R1, C0, C1, rpS.ctypes.data, ciS.ctypes.data,
+                                     vS.ctypes.data, cap)
+    if nnz < 0:
+        raise ValueError("oracle_induced_csr_range: invalid arguments")
+    return rpS, ciS[:nnz].copy(), vS[:nnz].copy()
+
+
 def gather_rows(X, S) -> np.ndarray:
     X = _arr(X, np.float32); S = _arr(S, np.int32)
     out = np.zeros((S.shape[0], X.shape[1]), np.float64)

@@ -9,6 +9,7 @@
  *   oracle_sample_uniform   Sec. III-D "Vertex Sampling", Eq. 20  (uniform B-subset of V)
  *   oracle_induced_csr      Sec. III-D Eq. 21 (induced edges), Eqs. 23-24 (p and the rescale),
  *                           Sec. II-A Eq. 3 (symmetric normalisation of A + I)
+ *   oracle_induced_csr_range   Algorithm 2 with its row and column ranges (one shard of that matrix)
  *   oracle_gather_rows      Sec. III-D Eq. 26 (feature / label slicing)
  *   oracle_spmm, oracle_gemm, oracle_gcn_fwd   Sec. III-B Eqs. 5-6 (+ ReLU, Eq. 8)
  *   oracle_gcn_bwd          Sec. III-C, the three layer-backward equations (grad W, grad H_agg,
@@ -201,6 +202,50 @@ int64_t oracle_induced_csr(uint64_t N, const int64_t *rowptr, const int32_t *col
                 val_S[e] = (float)a;
             }
         }
+    }
+    return nnz;
+}
+
+/*
+ * One shard of the same matrix (Algorithm 2 with a row range [R0, R1) and a column range [C0, C1) of
+ * global vertex ids): the B x B matrix restricted to the rows of S inside the row range (S_r, Alg. 2
+ * line 4) and the columns of S inside the column range (S_c, line 5), in the same [0, B) namespace;
+ * rows outside the row range are empty.  Weights as in norm_mode 0 (full-graph degrees, or val).
+ */
+int64_t oracle_induced_csr_range(uint64_t N, const int64_t *rowptr, const int32_t *colidx, const float *val,
+                                 const int32_t *S, uint64_t B, int rescale, int64_t R0, int64_t R1, int64_t C0,
+                                 int64_t C1, int32_t *rowptr_S, int32_t *colidx_S, float *val_S, int64_t capacity)
+{
+    if (B == 0 || B > N) return -1;
+    if (R0 < 0 || R1 < R0 || (uint64_t)R1 > N || C0 < 0 || C1 < C0 || (uint64_t)C1 > N) return -1;
+    double p = 1.0;
+    if (rescale && B > 1) p = ((double)B - 1.0) / ((double)N - 1.0);
+    int64_t nnz = 0;
+    rowptr_S[0] = 0;
+    for (uint64_t i = 0; i < B; ++i) {
+        int64_t v = S[i];
+        if (v >= R0 && v < R1) {
+            double deg_v = (double)(rowptr[v + 1] - rowptr[v]);
+            for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+                int32_t u = colidx[e];
+                if (u < C0 || u >= C1) continue;
+                int64_t j = find_in_sample(S, (int64_t)B, u);
+                if (j < 0) continue;
+                if (nnz < capacity) {
+                    double a;
+                    if (val) a = (double)val[e];
+                    else {
+                        double deg_u = (double)(rowptr[(int64_t)u + 1] - rowptr[u]);
+                        a = 1.0 / sqrt(deg_v * deg_u);
+                    }
+                    if (u != v) a /= p;
+                    colidx_S[nnz] = (int32_t)j;
+                    val_S[nnz] = (float)a;
+                }
+                ++nnz;
+            }
+        }
+        rowptr_S[i + 1] = (int32_t)nnz;
     }
     return nnz;
 }

@@ -177,3 +177,45 @@ def test_invalid_arguments(small):
     N, rp, ci = small
     with pytest.raises(ValueError):
         oracle.induced_csr(N, rp, ci, np.zeros(0, np.int32))
+
+
+# ---- Algorithm 2's row / column ranges: one shard of the mini-batch matrix ----
+
+def test_shards_tile_the_full_matrix(tiny_graph):
+    g = tiny_graph
+    N = g.N; B = 700
+    rpg, cig = g.rowptr.numpy(), g.colidx.numpy()
+    S = oracle.sample_uniform(N, B, 5, 2)
+    rp, ci, v = oracle.induced_csr(N, rpg, cig, S)
+    full = csr_to_dense(rp, ci, v, B)
+    cuts_r = [0, 1000, 1001, 2500, N]          # ragged, one range of a single vertex
+    cuts_c = [0, 17, 3000, N]
+    total = np.zeros_like(full); count = 0
+    for a, b in zip(cuts_r[:-1], cuts_r[1:]):
+        for c, d in zip(cuts_c[:-1], cuts_c[1:]):
+            rpt, cit, vt = oracle.induced_csr_range(N, rpg, cig, S, a, b, c, d)
+            tile = csr_to_dense(rpt, cit, vt, B)
+            # the tile is the full matrix restricted to the rows / columns of S inside the ranges
+            rows_in = (S >= a) & (S < b); cols_in = (S >= c) & (S < d)
+            want = np.where(rows_in[:, None] & cols_in[None, :], full, 0.0)
+            assert np.array_equal(tile, want)
+            assert all(np.all(np.diff(cit[rpt[i]:rpt[i + 1]]) > 0) for i in range(B))      # ascending columns
+            total += tile; count += len(cit)
+    assert np.array_equal(total, full) and count == len(ci)
+
+
+def test_shard_edge_cases(tiny_graph):
+    g = tiny_graph
+    rpg, cig = g.rowptr.numpy(), g.colidx.numpy()
+    S = oracle.sample_uniform(g.N, 300, 1, 0)
+    full = oracle.induced_csr(g.N, rpg, cig, S)
+    whole = oracle.induced_csr_range(g.N, rpg, cig, S, 0, g.N, 0, g.N)
+    assert all(np.array_equal(a, b) for a, b in zip(full, whole))
+    rpt, cit, vt = oracle.induced_csr_range(g.N, rpg, cig, S, 10, 10, 0, g.N)          # empty row range
+    assert len(cit) == 0 and np.all(rpt == 0)
+    with pytest.raises(ValueError):
+        oracle.induced_csr_range(g.N, rpg, cig, S, 0, g.N + 1, 0, g.N)
+    # the symmetric matrix of an undirected graph: the transpose of tile (R, C) is tile (C, R)
+    a = csr_to_dense(*oracle.induced_csr_range(g.N, rpg, cig, S, 0, 2000, 1500, g.N), 300)
+    b = csr_to_dense(*oracle.induced_csr_range(g.N, rpg, cig, S, 1500, g.N, 0, 2000), 300)
+    assert np.array_equal(a.T, b)
