@@ -162,6 +162,28 @@ int sgnn_induced_csr(sgnn_ctx *ctx, const sgnn_graph *graph, const int32_t *S, u
                      sgnn_csr *out, uint64_t *nnz_host, sgnn_stream stream);
 
 /*
+ * One shard of the mini-batch matrix (Algorithm 2 as stated there, "per GPU"): the same B x B matrix
+ * restricted to the rows of S inside the row range [R0, R1) and the columns of S inside the column
+ * range [C0, C1), both in global vertex ids.  Row and column numbers stay in the [0, B) namespace of the
+ * whole sample (the shards of a grid tile the full matrix); rows outside the row range are empty.
+ * Weights from the full-graph degrees (or g->val), as with norm_mode 0.  Everything else as
+ * sgnn_induced_csr.  S depends on (seed, step, N) only, so every owner of a shard derives it alone.
+ */
+int sgnn_induced_csr_range(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B,
+                           const uint64_t *bitmap, const uint32_t *rank, int rescale, int64_t R0, int64_t R1,
+                           int64_t C0, int64_t C1, sgnn_csr *out, uint64_t *nnz_host, sgnn_stream stream);
+
+/*
+ * out = A^T as CSR with ascending columns (Algorithm 2's last phase assembles the matrix and its
+ * transpose; Sec. III-C multiplies by the transpose).  Needed for shards with different row and column
+ * ranges and for directed graphs; the full matrix of an undirected graph is its own transpose.
+ *   out   cols x rows (set out->rows / out->cols accordingly), capacity >= A's, plan optional (filled)
+ * The result does not depend on timing (bit-reproducible).
+ */
+int sgnn_csr_transpose(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_csr *out, sgnn_stream stream);
+
+
+/*
  * Dense row-major matrix.  row_index (may be NULL) makes logical row i the physical row
  * row_index[i] of ptr; it is honoured only where a parameter says so.
  */

@@ -89,13 +89,15 @@ def lib():
         L.sgnn_sgd_step.argtypes = [vp, vp, vp, i64, cd, cd, vp]
         L.sgnn_adam_step.argtypes = [vp, vp, vp, vp, vp, i64, cd, cd, cd, cd, i64, vp]
         L.sgnn_graph_normalized_csr.argtypes = [vp, C.POINTER(_Graph), vp, vp, vp]
+        L.sgnn_induced_csr_range.argtypes = [vp, C.POINTER(_Graph), vp, u32, vp, vp, ci, i64, i64, i64, i64, C.POINTER(_Csr), vp, vp]
+        L.sgnn_csr_transpose.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Csr), vp]
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
-                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr",
+                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose",
                      "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm", "sgnn_copy_f32"):
             getattr(L, name).restype = ci
         _lib = L
@@ -273,6 +275,30 @@ def sgnn_graph_normalized_csr(ctx: Context, N: int, rowptr: torch.Tensor, colidx
         out.plan = torch.zeros((nbytes + 7) // 8, dtype=torch.int64, device=dev)
         sgnn_csr_plan(ctx, out, stream=stream)
     return out
+
+
+def sgnn_induced_csr_range(ctx: Context, N: int, rowptr: torch.Tensor, colidx: torch.Tensor, val: Optional[torch.Tensor],
+                           S: torch.Tensor, B: int, bitmap: torch.Tensor, rank: torch.Tensor, R0: int, R1: int, C0: int,
+                           C1: int, out: Csr, rescale: int = 1, want_nnz: bool = False, stream=None) -> Optional[int]:
+    """One shard (rows of S in [R0, R1), columns of S in [C0, C1)) of the mini-batch matrix; B x B namespace."""
+    if rowptr.numel() != N + 1:
+        raise ValueError("rowptr must have N+1 entries")
+    g = _Graph(N, colidx.numel(), _ptr(rowptr, None, "rowptr"), int(rowptr.dtype == torch.int64),
+               _ptr(colidx, torch.int32, "colidx"), _ptr(val, torch.float32, "val"))
+    cs = out.struct()
+    nnz = C.c_uint64(0)
+    rc = lib().sgnn_induced_csr_range(ctx._h, C.byref(g), _ptr(S, torch.int32, "S"), B, _ptr(bitmap, torch.int64, "bitmap"),
+                                      _ptr(rank, torch.int32, "rank"), rescale, R0, R1, C0, C1, C.byref(cs),
+                                      C.byref(nnz) if want_nnz else None, _stream(stream))
+    out.rows = out.cols = B
+    ctx.check(rc)
+    return int(nnz.value) if want_nnz else None
+
+
+def sgnn_csr_transpose(ctx: Context, A: Csr, out: Csr, stream=None):
+    """out = A^T (out: cols x rows of A, capacity >= A's)."""
+    a, o = A.struct(), out.struct()
+    ctx.check(lib().sgnn_csr_transpose(ctx._h, C.byref(a), C.byref(o), _stream(stream)))
 
 
 def sgnn_csr_plan(ctx: Context, A: Csr, stream=None):

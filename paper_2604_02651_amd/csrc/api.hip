@@ -127,6 +127,7 @@ int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t
     size_t layer = (size_t)2 * B * pad4(d_max) * 4 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 +
                    sgnn_spmm_ws_bytes(max_entries, B, d_max) + 16 * 256;
     need = std::max(need, layer);
+    need = std::max(need, sgnn_transpose_ws_bytes(max_entries, B));
     need = std::max(need, (size_t)B / 64 * 4 + 4096);
     need += 4096;
     if (need > ctx->ws_bytes) {
@@ -213,9 +214,9 @@ int sgnn_sample_uniform(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, ui
     return sgnn_launch_sampler(ctx, N, B, seed, step, S, bitmap, rank, static_cast<hipStream_t>(stream));
 }
 
-int sgnn_induced_csr(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B, const uint64_t *bitmap,
-                     const uint32_t *rank, int norm_mode, int rescale, sgnn_csr *out, uint64_t *nnz_host,
-                     sgnn_stream stream)
+static int induced_impl(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B, const uint64_t *bitmap,
+                        const uint32_t *rank, int norm_mode, int rescale, int64_t R0, int64_t R1, int64_t C0, int64_t C1,
+                        sgnn_csr *out, uint64_t *nnz_host, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     if (!g || !g->rowptr || !g->colidx || !S || !bitmap || !rank || !out || !out->rowptr)
@@ -234,7 +235,7 @@ int sgnn_induced_csr(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint3
     sgnn_csr o = *out;
     o.rows = o.cols = B;
     if (nnz_host && !nnz_dev) o.nnz_dev = ctx->status + 2;
-    rc = sgnn_launch_induced(ctx, g, S, B, bitmap, rank, norm_mode, rescale, &o, st);
+    rc = sgnn_launch_induced(ctx, g, S, B, bitmap, rank, norm_mode, rescale, R0, R1, C0, C1, &o, st);
     if (rc) return rc;
     rc = sgnn_launch_spmm_plan(ctx, &o, st);
     if (rc) return rc;
@@ -249,6 +250,41 @@ int sgnn_induced_csr(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint3
                              (unsigned long long)out->capacity);
     }
     return SGNN_OK;
+}
+
+int sgnn_induced_csr(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B, const uint64_t *bitmap,
+                     const uint32_t *rank, int norm_mode, int rescale, sgnn_csr *out, uint64_t *nnz_host,
+                     sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!g) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_induced_csr: null pointer");
+    return induced_impl(ctx, g, S, B, bitmap, rank, norm_mode, rescale, 0, (int64_t)g->N, 0, (int64_t)g->N, out, nnz_host, stream);
+}
+
+int sgnn_induced_csr_range(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B, const uint64_t *bitmap,
+                           const uint32_t *rank, int rescale, int64_t R0, int64_t R1, int64_t C0, int64_t C1, sgnn_csr *out,
+                           uint64_t *nnz_host, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!g) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_induced_csr_range: null pointer");
+    if (R0 < 0 || R1 < R0 || (uint64_t)R1 > g->N || C0 < 0 || C1 < C0 || (uint64_t)C1 > g->N)
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_induced_csr_range: need 0 <= R0 <= R1 <= N and 0 <= C0 <= C1 <= N");
+    return induced_impl(ctx, g, S, B, bitmap, rank, 0, rescale, R0, R1, C0, C1, out, nnz_host, stream);
+}
+
+int sgnn_csr_transpose(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_csr *out, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!csr_ok(A) || !out || !out->rowptr || (out->capacity > 0 && (!out->colidx || !out->val)))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_csr_transpose: bad argument");
+    if (out->rows != A->cols || out->cols != A->rows || out->capacity < A->capacity)
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_csr_transpose: out must be cols x rows with at least A's capacity");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    ws_alloc ws(ctx);
+    rc = sgnn_launch_csr_transpose(ctx, A, out, &ws, static_cast<hipStream_t>(stream));
+    if (rc) return rc;
+    return sgnn_launch_spmm_plan(ctx, out, static_cast<hipStream_t>(stream));
 }
 
 int sgnn_csr_plan(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_stream stream)

@@ -99,8 +99,10 @@ int sgnn_scan_u32_devn(sgnn_ctx *ctx, const uint32_t *in, uint32_t *out, const u
 int sgnn_launch_sampler(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, uint64_t step, int32_t *S,
                         uint64_t *bitmap, uint32_t *rank, hipStream_t st);
 int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B,
-                        const uint64_t *bitmap, const uint32_t *rank, int norm_mode, int rescale,
-                        sgnn_csr *out, hipStream_t st);
+                        const uint64_t *bitmap, const uint32_t *rank, int norm_mode, int rescale, int64_t R0,
+                        int64_t R1, int64_t C0, int64_t C1, sgnn_csr *out, hipStream_t st);
+int sgnn_launch_csr_transpose(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_csr *out, ws_alloc *ws, hipStream_t st);
+size_t sgnn_transpose_ws_bytes(uint64_t max_entries, uint32_t B);
 int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index,
                      int64_t d, float *out, int64_t ldo, const float *bias, int relu, const float *mask, int64_t ldm,
                      const float *add, int64_t ldadd, ws_alloc *ws, hipStream_t st);

@@ -31,9 +31,12 @@ constexpr int IND_GROUP = 2048;                   // tiles per group of the two-
 constexpr unsigned IND_MAX_GRID = 8192;
 constexpr int DEG_TILE = 2048;                    // sampled rows per workgroup in the offset kernels
 
+// Row and column range of a shard (Algorithm 2: [R0, R1) x [C0, C1) in global vertex ids); the whole graph by default.
+struct shard_range { int64_t r0, r1, c0, c1; };
+
 template <class RP>
 __global__ __launch_bounds__(256) void induced_deg_kernel(const RP *__restrict__ rowptr, const int32_t *__restrict__ S,
-                                                          uint32_t B, uint32_t *__restrict__ deg,
+                                                          uint32_t B, shard_range rg, uint32_t *__restrict__ deg,
                                                           uint64_t *__restrict__ wg_sum)
 {
     __shared__ uint64_t lds[256 / 64];
@@ -43,7 +46,8 @@ __global__ __launch_bounds__(256) void induced_deg_kernel(const RP *__restrict__
         const uint32_t i = blockIdx.x * DEG_TILE + k * 256 + threadIdx.x;
         if (i < B) {
             const int64_t v = S[i];
-            const uint32_t dgr = (uint32_t)(rowptr[v + 1] - rowptr[v]);
+            // a sampled row outside the shard's row range contributes no edge: it comes out as an empty row
+            const uint32_t dgr = (v >= rg.r0 && v < rg.r1) ? (uint32_t)(rowptr[v + 1] - rowptr[v]) : 0u;
             deg[i] = dgr;
             s += dgr;
         }
@@ -138,7 +142,7 @@ template <class RP>
 __global__ __launch_bounds__(IND_NT) void induced_count_kernel(const RP *__restrict__ rowptr,
                                                                const int32_t *__restrict__ colidx,
                                                                const int32_t *__restrict__ S, uint32_t B,
-                                                               const uint64_t *__restrict__ bitmap,
+                                                               const uint64_t *__restrict__ bitmap, shard_range rg,
                                                                const uint64_t *__restrict__ P,
                                                                uint32_t *__restrict__ tile_total,
                                                                uint64_t *__restrict__ n_tiles_out)
@@ -165,6 +169,7 @@ __global__ __launch_bounds__(IND_NT) void induced_count_kernel(const RP *__restr
                     e = (int64_t)rowptr[S[r]] + (int64_t)(f - P[r]);
                 }
                 u[k] = colidx[e];
+                if (u[k] < rg.c0 || u[k] >= rg.c1) u[k] = -1;   // a column outside the shard
             }
         }
         uint32_t cnt = 0;
@@ -205,7 +210,7 @@ template <class RP>
 __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
     const RP *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *__restrict__ gval,
     const int32_t *__restrict__ S, uint32_t B, const uint64_t *__restrict__ bitmap, const uint32_t *__restrict__ rank,
-    const uint64_t *__restrict__ P, const uint32_t *__restrict__ tile_total, const uint32_t *__restrict__ group_total,
+    shard_range rg, const uint64_t *__restrict__ P, const uint32_t *__restrict__ tile_total, const uint32_t *__restrict__ group_total,
     const uint64_t *__restrict__ n_tiles_p, double p, int write_val, int32_t *__restrict__ rowptr_S,
     int32_t *__restrict__ colidx_S, float *__restrict__ val_S, uint64_t capacity, uint32_t *__restrict__ nnz_dev,
     uint32_t *__restrict__ status)
@@ -260,7 +265,7 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
         for (int k = 0; k < IND_ITEMS; ++k) word[k] = u[k] >= 0 ? bitmap[(uint32_t)u[k] >> 6] : 0ull;
 #pragma unroll
         for (int k = 0; k < IND_ITEMS; ++k) {
-            const bool keep = u[k] >= 0 && ((word[k] >> (u[k] & 63)) & 1ull);
+            const bool keep = u[k] >= 0 && u[k] >= rg.c0 && u[k] < rg.c1 && ((word[k] >> (u[k] & 63)) & 1ull);
             bal[k] = __ballot(keep);
             if (lane == 0) wcnt[k][wave] = __popcll(bal[k]);
         }
@@ -328,7 +333,7 @@ __global__ __launch_bounds__(256) void induced_renorm_kernel(const int32_t *__re
 
 template <class RP>
 int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B, const uint64_t *bitmap,
-                 const uint32_t *rank, int norm_mode, int rescale, sgnn_csr *out, hipStream_t st)
+                 const uint32_t *rank, int norm_mode, int rescale, shard_range rg, sgnn_csr *out, hipStream_t st)
 {
     const RP *rowptr = static_cast<const RP *>(g->rowptr);
     ws_alloc ws(ctx);
@@ -346,12 +351,12 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
                          ws.off);
 
     SGNN_LAUNCH(ctx, st, "induced_deg_kernel", SGNN_TAG, induced_deg_kernel<RP>, dim3(n_deg_wg), dim3(256), 0, st, rowptr, S, B,
-                deg, deg_sum);
+                rg, deg, deg_sum);
     SGNN_LAUNCH(ctx, st, "induced_offsets_kernel", SGNN_TAG, induced_offsets_kernel, dim3(n_deg_wg), dim3(256), 0, st, deg, B,
                 deg_sum, P);
     const unsigned grid = (unsigned)std::min<uint64_t>(max_tiles, IND_MAX_GRID);
     SGNN_LAUNCH(ctx, st, "induced_count_kernel", SGNN_TAG, induced_count_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr,
-                g->colidx, S, B, bitmap, P, tile_total, n_tiles);
+                g->colidx, S, B, bitmap, rg, P, tile_total, n_tiles);
     const bool grouped = max_tiles > IND_GROUP;
     if (grouped)
         SGNN_LAUNCH(ctx, st, "induced_group_kernel", SGNN_TAG, induced_group_kernel, dim3(n_groups), dim3(256), 0, st,
@@ -359,7 +364,7 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
     double p = 1.0;
     if (rescale && B > 1) p = ((double)B - 1.0) / ((double)g->N - 1.0);
     SGNN_LAUNCH(ctx, st, "induced_fill_kernel", SGNN_TAG, induced_fill_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr,
-                g->colidx, norm_mode == 0 ? g->val : nullptr, S, B, bitmap, rank, P, tile_total,
+                g->colidx, norm_mode == 0 ? g->val : nullptr, S, B, bitmap, rank, rg, P, tile_total,
                 grouped ? group_total : nullptr, n_tiles, p, norm_mode == 0 ? 1 : 0, out->rowptr, out->colidx, out->val,
                 out->capacity, out->nnz_dev, ctx->status);
     if (norm_mode == 1)
@@ -407,10 +412,12 @@ size_t sgnn_induced_ws_bytes(uint64_t E, uint32_t B)
 }
 
 int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B, const uint64_t *bitmap,
-                        const uint32_t *rank, int norm_mode, int rescale, sgnn_csr *out, hipStream_t st)
+                        const uint32_t *rank, int norm_mode, int rescale, int64_t R0, int64_t R1, int64_t C0, int64_t C1,
+                        sgnn_csr *out, hipStream_t st)
 {
-    if (g->rowptr_is_i64) return launch_typed<int64_t>(ctx, g, S, B, bitmap, rank, norm_mode, rescale, out, st);
-    return launch_typed<int32_t>(ctx, g, S, B, bitmap, rank, norm_mode, rescale, out, st);
+    const shard_range rg = {R0, R1, C0, C1};
+    if (g->rowptr_is_i64) return launch_typed<int64_t>(ctx, g, S, B, bitmap, rank, norm_mode, rescale, rg, out, st);
+    return launch_typed<int32_t>(ctx, g, S, B, bitmap, rank, norm_mode, rescale, rg, out, st);
 }
 
 int sgnn_launch_graph_normalize(sgnn_ctx *ctx, const sgnn_graph *g, int32_t *rowptr32, float *val, hipStream_t st)
