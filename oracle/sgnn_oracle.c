@@ -38,7 +38,9 @@
  * big-integer Python version; the sampler against an independent threshold selection and the
  * inclusion-probability statistics of Eq. 20; the induced CSR against dense brute force, scipy
  * slicing, a literal walk through Algorithm 2's phases and the exact enumeration of Eq. 25; the
- * layer against dense numpy, torch autograd and central finite differences.
+ * layer against dense numpy, torch autograd and central finite differences; the shards of Algorithm 2
+ * by tiling against the full matrix; the layer tail against closed forms, its invariances, an independent
+ * evaluation of the dropout counter mapping, torch autograd and finite differences.
  */
 #include <math.h>
 #include <stdint.h>
