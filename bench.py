@@ -33,6 +33,10 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=160)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--config", default="medium", help="tiny | medium | large | dense | xlarge (medium is the headline workload)")
+    ap.add_argument("--workload", default="gcn", choices=["gcn", "model"],
+                    help="gcn: the plain GCN stack of the configuration (the headline); model: the paper's complete model "
+                         "(input projection, residual layers with RMSNorm / ReLU / dropout, output head, Adam) at the "
+                         "configuration's sizes - an extra measurement, not the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fuse-slice", action="store_true")
     ap.add_argument("--no-fuse-relu-bwd", action="store_true",
@@ -75,8 +79,20 @@ def main():
     X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=dev)
     labels = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=dev)
     weights = si.layer_weights(cfg, device=dev)
-    st = sg.GcnStep(cfg.N, g.rowptr, g.colidx, X, labels, weights, cfg.B, cfg.sampler_seed, bf16=cfg.bf16_mfma,
-                    fuse_slice=not args.no_fuse_slice, device=dev, fuse_relu_bwd=not args.no_fuse_relu_bwd)
+    model = args.workload == "model"
+    if model:
+        d_h = cfg.hidden
+        n_layers = max(cfg.layers - 1, 1)
+        params = {"W_in": si.glorot_uniform(cfg.d_in, d_h, 100, device=dev).contiguous(),
+                  "layers": [(si.glorot_uniform(d_h, d_h, 110 + l, device=dev).contiguous(), torch.ones(d_h, device=dev))
+                             for l in range(n_layers)],
+                  "W_out": si.glorot_uniform(d_h, cfg.classes, 130, device=dev).contiguous()}
+        st = sg.ScaleGnnModel(cfg.N, g.rowptr, g.colidx, X, labels, params, cfg.B, sampler_seed=cfg.sampler_seed, drop_q=0.1,
+                              drop_seed=1, bf16=cfg.bf16_mfma, optimizer="adam", lr=1e-3, device=dev)
+        args.no_overlap = True      # the model runs on one stream
+    else:
+        st = sg.GcnStep(cfg.N, g.rowptr, g.colidx, X, labels, weights, cfg.B, cfg.sampler_seed, bf16=cfg.bf16_mfma,
+                        fuse_slice=not args.no_fuse_slice, device=dev, fuse_relu_bwd=not args.no_fuse_relu_bwd)
     period = max(cfg.steps, 1)   # the configuration's mini-batches: consecutive sampler counters
 
     use_graph = not args.no_graph and not args.no_overlap and period % 2 == 0
@@ -117,7 +133,10 @@ def main():
     recs = st.ctx.profile_read()
     st.ctx.profile(False)
     for i in range(nprof):     # entry counts of those steps, for the byte figures of the sparse kernels
-        st.sample(i % period); st.induce()
+        if model:
+            st.minibatch(i % period)
+        else:
+            st.sample(i % period); st.induce()
         nnz_total += st.A.nnz()
     nnz_avg = nnz_total / nprof
     groups = {}
@@ -179,9 +198,11 @@ def main():
         "metric": METRIC, "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.bf16_mfma else "f32", "data": "synthetic",
-        "config": {"workload": "%s: R-MAT N=%d, E=%d stored entries, |S|=%d, GCN %s, %d mini-batches (sampler "
-                               "counters 0..%d)" % (cfg.name, cfg.N, g.E, cfg.B, "-".join(map(str, cfg.dims)), period,
-                                                     period - 1),
+        "config": {"workload": "%s: R-MAT N=%d, E=%d stored entries, |S|=%d, %s, %d mini-batches (sampler "
+                               "counters 0..%d)" % (cfg.name, cfg.N, g.E, cfg.B,
+                                                     ("complete model %d-[%d x %d]-%d with dropout 0.1 and Adam"
+                                                      % (cfg.d_in, cfg.hidden, max(cfg.layers - 1, 1), cfg.classes)) if model
+                                                     else "GCN " + "-".join(map(str, cfg.dims)), period, period - 1),
                    "fuse_slice": not args.no_fuse_slice, "fuse_relu_bwd": not args.no_fuse_relu_bwd, "overlap_sampling": not args.no_overlap, "hip_graph": use_graph,
                    "single_stream_steps_per_s": single_stream_steps_per_s, "avg_induced_entries": nnz_avg,
                    "kernel_time_us_per_step": 1e3 * total_ms / nprof},
@@ -195,7 +216,7 @@ def main():
             sg.sgnn_copy_f32(st.ctx, src, dst)
         torch.cuda.synchronize()
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not model:
         import oracle
         rp, ci = g.rowptr.cpu().numpy(), g.colidx.cpu().numpy()
         Xh, lh = X.cpu().numpy(), labels.cpu().numpy()

@@ -1108,9 +1108,11 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     if (bf16 && !ta && K >= 1 && K <= 256 && N >= 1 && N <= 256 && M >= 4096 && a.alignedA)
         return launch_skinny(ctx, a, tb, st);
 
-    // wide fp32 results with whole chunks and whole slices: the direct-to-LDS kernel, 256 x 128 tiles
+    // wide fp32 results with whole chunks and whole slices: the direct-to-LDS kernel, 256 x 128 tiles.  Not for
+    // the long reductions onto a small result (T^T dZ): with two 256 x 128 tiles the split would have to be
+    // twice as fine, and the partial products it writes cost more than the kernel gains.
     const int64_t a_contig = ta ? M : K, b_contig = tb ? K : N;
-    const bool direct = !bf16 && !(ta && tb) && a.alignedA && a.alignedB && a_contig % 4 == 0 && b_contig % 4 == 0 &&
+    const bool direct = !bf16 && !ta && a.alignedA && a.alignedB && a_contig % 4 == 0 && b_contig % 4 == 0 &&
                         a_contig >= 4 && b_contig >= 4 && K % 32 == 0 && K >= 32 && N > 64 && M > 128;
 
     // tile shape by the width of C
