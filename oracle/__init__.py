@@ -321,6 +321,16 @@ def model_step(rowptr, colidx, val, X_S, y_S, params, drop_q: float = 0.0, drop_
     return out
 
 
+def sigmoid_bce(O, Y):
+    """Mean binary cross-entropy on logits and its gradient.  Returns (loss, dO)."""
+    O = _arr(O, np.float64); Y = _arr(Y, np.float64)
+    dO = np.zeros_like(O)
+    L = lib()
+    L.oracle_sigmoid_bce.restype = C.c_double
+    L.oracle_sigmoid_bce.argtypes = [C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+    return float(L.oracle_sigmoid_bce(O.shape[0], O.shape[1], O.ctypes.data, Y.ctypes.data, dO.ctypes.data)), dO
+
+
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
 

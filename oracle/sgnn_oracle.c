@@ -515,6 +515,25 @@ void oracle_tail_bwd(int64_t B, int64_t d, const double *Z, const double *gamma,
     free(dn);
 }
 
+/*
+ * Binary cross-entropy on logits, the paper's loss for multi-label tasks (Sec. III-B "Output Head and
+ * Loss"): mean over the B x C entries of  -[y log s(o) + (1 - y) log(1 - s(o))],  s = logistic function,
+ * written as max(o, 0) - o y + log(1 + exp(-|o|)); dO = (s(o) - y) / (B C).  Y holds the targets (0 / 1,
+ * any value in [0, 1] is accepted).  The paper does not say mean or sum: the mean is the reading taken.
+ */
+double oracle_sigmoid_bce(int64_t B, int64_t C, const double *O, const double *Y, double *dO)
+{
+    double loss = 0.0;
+    const double inv = 1.0 / ((double)B * (double)C);
+    for (int64_t i = 0; i < B * C; ++i) {
+        const double o = O[i], y = Y[i];
+        loss += (o > 0.0 ? o : 0.0) - o * y + log1p(exp(-fabs(o)));
+        const double sg = o >= 0.0 ? 1.0 / (1.0 + exp(-o)) : exp(o) / (1.0 + exp(o));
+        if (dO) dO[i] = (sg - y) * inv;
+    }
+    return loss * inv;
+}
+
 int oracle_num_threads(void)
 {
     int n = 1;

@@ -82,3 +82,20 @@ def test_model_step_against_torch_autograd(q):
     for l in range(L):
         assert np.allclose(out["dW"][l], tp["layers"][l][0].grad.numpy(), rtol=1e-10, atol=1e-13), l
         assert np.allclose(out["dgamma"][l], tp["layers"][l][1].grad.numpy(), rtol=1e-10, atol=1e-13), l
+
+
+def test_binary_cross_entropy_against_torch_and_closed_forms():
+    O = _rand((17, 9), 40) * 4; Y = (np.random.default_rng(41).random((17, 9)) < 0.3).astype(np.float64)
+    loss, dO = oracle.sigmoid_bce(O, Y)
+    ot = torch.tensor(O, requires_grad=True)
+    lt = torch.nn.functional.binary_cross_entropy_with_logits(ot, torch.tensor(Y))
+    lt.backward()
+    assert abs(loss - lt.item()) < 1e-13 and np.allclose(dO, ot.grad.numpy(), rtol=1e-12, atol=1e-16)
+    # zero logits: every entry costs log 2; saturated logits of the right sign cost nothing and stay finite
+    l0, d0 = oracle.sigmoid_bce(np.zeros((3, 4)), Y[:3, :4])
+    assert abs(l0 - np.log(2.0)) < 1e-15 and np.allclose(d0, (0.5 - Y[:3, :4]) / 12)
+    big = np.where(Y > 0, 800.0, -800.0)
+    lb, db = oracle.sigmoid_bce(big, Y)
+    assert lb == 0.0 and np.all(db == 0.0)
+    lw, _ = oracle.sigmoid_bce(-big, Y)
+    assert abs(lw - 800.0) < 1e-9
