@@ -289,6 +289,14 @@ int sgnn_softmax_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t 
                       uint32_t C, float *loss_dev, float *dO, int64_t lddo, sgnn_stream stream);
 
 /*
+ * Mean binary cross-entropy on logits over the B x C entries, the paper's loss for multi-label tasks
+ * (Sec. III-B), and its gradient dO = (logistic(O) - Y) / (B C).  Y: fp32 targets in [0, 1], B x C.
+ * loss_dev: device float[1] or NULL; dO may be NULL.  Fixed summation order.
+ */
+int sgnn_sigmoid_bce(sgnn_ctx *ctx, const float *O, int64_t ldo, const float *Y, int64_t ldy, uint32_t B,
+                     uint32_t C, float *loss_dev, float *dO, int64_t lddo, sgnn_stream stream);
+
+/*
  * Parameter update ("update parameters", Alg. 1 line 7; the paper names no optimizer).
  * sgnn_sgd_step:  w <- w - lr * (g + weight_decay * w)
  * sgnn_adam_step: Adam (Kingma & Ba, ICLR 2015, Algorithm 1) with bias correction:

@@ -91,13 +91,14 @@ def lib():
         L.sgnn_graph_normalized_csr.argtypes = [vp, C.POINTER(_Graph), vp, vp, vp]
         L.sgnn_induced_csr_range.argtypes = [vp, C.POINTER(_Graph), vp, u32, vp, vp, ci, i64, i64, i64, i64, C.POINTER(_Csr), vp, vp]
         L.sgnn_csr_transpose.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Csr), vp]
+        L.sgnn_sigmoid_bce.argtypes = [vp, vp, i64, vp, i64, u32, u32, vp, vp, i64, vp]
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
-                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose",
+                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose", "sgnn_sigmoid_bce",
                      "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm", "sgnn_copy_f32"):
             getattr(L, name).restype = ci
         _lib = L
@@ -341,6 +342,14 @@ def sgnn_gcn_bwd(ctx: Context, A_T: Csr, T: torch.Tensor, W: torch.Tensor, Y: Op
     ctx.check(lib().sgnn_gcn_bwd(ctx._h, C.byref(a), C.byref(t), C.byref(w), C.byref(y) if y is not None else None,
                                  C.byref(dy), flags, C.byref(dh) if dh is not None else None,
                                  C.byref(hin) if hin is not None else None, _ptr(dW, torch.float32, "dW"), _ptr(dbias, torch.float32, "dbias"), _stream(stream)))
+
+
+def sgnn_sigmoid_bce(ctx: Context, O: torch.Tensor, Y: torch.Tensor, loss: Optional[torch.Tensor],
+                     dO: Optional[torch.Tensor], stream=None):
+    """Mean binary cross-entropy on logits (multi-label loss) and its gradient."""
+    ctx.check(lib().sgnn_sigmoid_bce(ctx._h, _ptr(O, torch.float32, "O"), O.stride(0), _ptr(Y, torch.float32, "Y"), Y.stride(0),
+                                     O.shape[0], O.shape[1], _ptr(loss, torch.float32, "loss"), _ptr(dO, torch.float32, "dO"),
+                                     dO.stride(0) if dO is not None else 0, _stream(stream)))
 
 
 def sgnn_tail_fwd(ctx: Context, Z: torch.Tensor, gamma: Optional[torch.Tensor], eps: float, R: Optional[torch.Tensor],

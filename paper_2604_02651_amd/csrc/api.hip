@@ -488,6 +488,18 @@ int sgnn_tail_bwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *inv_rms, const 
                                 static_cast<float *>(dZ->ptr), dZ->ld, dgamma, dbias, &ws, static_cast<hipStream_t>(stream));
 }
 
+int sgnn_sigmoid_bce(sgnn_ctx *ctx, const float *O, int64_t ldo, const float *Y, int64_t ldy, uint32_t B, uint32_t C,
+                     float *loss_dev, float *dO, int64_t lddo, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!O || !Y || B == 0 || C == 0 || ldo < C || ldy < C || (dO && lddo < C))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_sigmoid_bce: bad argument");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    ws_alloc ws(ctx);
+    return sgnn_launch_bce(ctx, O, ldo, Y, ldy, B, C, loss_dev, dO, lddo, &ws, static_cast<hipStream_t>(stream));
+}
+
 int sgnn_sgd_step(sgnn_ctx *ctx, float *w, const float *g, int64_t n, double lr, double weight_decay, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;

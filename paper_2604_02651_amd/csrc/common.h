@@ -123,6 +123,8 @@ int sgnn_launch_tail_fwd(sgnn_ctx *ctx, int64_t rows, int64_t d, const float *Z,
 int sgnn_launch_tail_bwd(sgnn_ctx *ctx, int64_t rows, int64_t d, const float *Z, int64_t ldz, const float *inv_rms,
                          const float *gamma, float q, uint64_t seed, uint32_t layer, uint64_t step, const float *dY,
                          int64_t lddy, float *dZ, int64_t lddz, float *dgamma, float *dbias, ws_alloc *ws, hipStream_t st);
+int sgnn_launch_bce(sgnn_ctx *ctx, const float *O, int64_t ldo, const float *Y, int64_t ldy, int64_t B, int64_t C, float *loss,
+                    float *dO, int64_t lddo, ws_alloc *ws, hipStream_t st);
 int sgnn_launch_sgd(sgnn_ctx *ctx, float *w, const float *g, int64_t n, double lr, double wd, hipStream_t st);
 int sgnn_launch_adam(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v, int64_t n, double lr, double b1, double b2,
                      double eps, int64_t t, hipStream_t st);

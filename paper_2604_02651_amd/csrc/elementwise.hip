@@ -190,6 +190,29 @@ __global__ __launch_bounds__(256) void copy_f32_kernel(const f32x4 *__restrict__
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// Binary cross-entropy on logits: a thread per entry (grid-stride), per-workgroup partial sums of
+// max(o, 0) - o y + log(1 + exp(-|o|)); dO = (s(o) - y) * inv, inv = 1 / (B C).
+__global__ __launch_bounds__(256) void bce_kernel(const float *__restrict__ O, int64_t ldo, const float *__restrict__ Y, int64_t ldy,
+                                                  int64_t B, int64_t C, float inv, float *__restrict__ dO, int64_t lddo,
+                                                  float *__restrict__ partial)
+{
+    __shared__ float lds[256 / 64];
+    float s = 0.f;
+    const int64_t n = B * C;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / C, c = i % C;
+        const float o = O[r * ldo + c], y = Y[r * ldy + c];
+        const float e = expf(-fabsf(o));
+        s += fmaxf(o, 0.f) - o * y + log1pf(e);
+        if (dO) {
+            const float sg = o >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
+            dO[r * lddo + c] = (sg - y) * inv;
+        }
+    }
+    s = block_sum<float, 256>(s, lds);
+    if (threadIdx.x == 0) partial[blockIdx.x] = s;
+}
+
 // w <- w - lr * (g + wd * w)
 __global__ __launch_bounds__(256) void sgd_kernel(float *__restrict__ w, const float *__restrict__ g, int64_t n, float lr,
                                                   float wd)
@@ -306,5 +329,18 @@ int sgnn_launch_adam(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v
     const float c1 = (float)(1.0 / (1.0 - pow(b1, (double)t))), c2 = (float)(1.0 / (1.0 - pow(b2, (double)t)));
     SGNN_LAUNCH(ctx, st, "adam_kernel", SGNN_TAG, adam_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, w, g, m, v, n, (float)lr,
                 (float)b1, (float)b2, (float)(1.0 - b1), (float)(1.0 - b2), (float)eps, c1, c2);
+    return SGNN_OK;
+}
+
+int sgnn_launch_bce(sgnn_ctx *ctx, const float *O, int64_t ldo, const float *Y, int64_t ldy, int64_t B, int64_t C, float *loss,
+                    float *dO, int64_t lddo, ws_alloc *ws, hipStream_t st)
+{
+    const unsigned nwg = (unsigned)std::max<int64_t>(1, std::min<int64_t>((B * C + 255) / 256, 1024));
+    float *partial = ws->get<float>(nwg);
+    if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_sigmoid_bce: scratch too small: call sgnn_ctx_reserve");
+    const float inv = (float)(1.0 / ((double)B * (double)C));
+    SGNN_LAUNCH(ctx, st, "bce_kernel", SGNN_TAG, bce_kernel, dim3(nwg), dim3(256), 0, st, O, ldo, Y, ldy, B, C, inv, dO, lddo, partial);
+    if (loss)
+        SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, inv, loss);
     return SGNN_OK;
 }

@@ -148,3 +148,14 @@ def test_training_reduces_the_loss():
     first, last = np.mean(losses[:10]), np.mean(losses[-10:])
     assert np.isfinite(losses).all()
     assert last < 0.5 * first, (first, last)
+
+
+@pytest.mark.parametrize("Bn,Cn", [(1000, 47), (33, 1), (4096, 128)])
+def test_binary_cross_entropy(Bn, Cn):
+    O = _rand((Bn, Cn + 3), 1) * 5; Y = (np.random.default_rng(2).random((Bn, Cn)) < 0.25).astype(np.float32)
+    O[0, 0] = 90.0; O[1 % Bn, 0] = -90.0          # saturated logits stay finite
+    loss = torch.zeros(1, device=DEV); dO = torch.zeros((Bn, Cn), dtype=torch.float32, device=DEV)
+    sg.sgnn_sigmoid_bce(ctx(), dev(O)[:, :Cn], dev(Y), loss, dO)
+    lref, dref = oracle.sigmoid_bce(O[:, :Cn], Y)
+    assert abs(loss.item() - lref) < TOL_F32 * abs(lref)
+    assert rel_err(dO.cpu().numpy(), dref) < TOL_F32
