@@ -230,7 +230,9 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
  *         of the ReLU of the layer below.  dH is then returned already multiplied by [H_in > 0],
  *         i.e. with that layer's ReLU backward fused into the product that writes dH; call that
  *         layer's backward with SGNN_DY_MASKED so that it skips its own masking pass.
- *   dW    out fp32[d_in x d_out] row-major, overwritten;  dbias out fp32[d_out] or NULL
+ *   dW    out fp32[d_in x d_out] row-major, overwritten, or NULL to skip it (a caller that computes
+ *         T^T dZ itself, e.g. on another stream: with SGNN_DY_MASKED or without SGNN_RELU dZ is dY);
+ *         dbias out fp32[d_out] or NULL
  * The reduction over the B rows in dW and dbias uses a fixed split and a fixed summation order:
  * results are bit-reproducible from run to run.
  */

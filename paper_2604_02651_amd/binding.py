@@ -328,7 +328,7 @@ def sgnn_gcn_fwd(ctx: Context, A: Csr, H: torch.Tensor, W: torch.Tensor, bias: O
 
 
 def sgnn_gcn_bwd(ctx: Context, A_T: Csr, T: torch.Tensor, W: torch.Tensor, Y: Optional[torch.Tensor], dY: torch.Tensor,
-                 flags: int, dH: Optional[torch.Tensor], dW: torch.Tensor, dbias: Optional[torch.Tensor],
+                 flags: int, dH: Optional[torch.Tensor], dW: Optional[torch.Tensor], dbias: Optional[torch.Tensor],
                  row_index: Optional[torch.Tensor] = None, stream=None, H_in: Optional[torch.Tensor] = None):
     """T is the saved aggregate, or with SGNN_XFORM_FIRST the layer input (row_index honoured).
     H_in (the layer input, output of the ReLU below): dH comes back multiplied by [H_in > 0]."""
@@ -337,7 +337,7 @@ def sgnn_gcn_bwd(ctx: Context, A_T: Csr, T: torch.Tensor, W: torch.Tensor, Y: Op
     y = _mat(Y, None, "Y") if Y is not None else None
     dh = _mat(dH, None, "dH") if dH is not None else None
     hin = _mat(H_in, None, "H_in") if H_in is not None else None
-    if dW.shape != W.shape or not dW.is_contiguous():
+    if dW is not None and (dW.shape != W.shape or not dW.is_contiguous()):
         raise ValueError("dW must be contiguous with the shape of W")
     ctx.check(lib().sgnn_gcn_bwd(ctx._h, C.byref(a), C.byref(t), C.byref(w), C.byref(y) if y is not None else None,
                                  C.byref(dy), flags, C.byref(dh) if dh is not None else None,

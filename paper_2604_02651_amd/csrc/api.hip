@@ -384,7 +384,7 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
                  sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
-    if (!csr_ok(A_T) || !mat_ok(T) || !mat_ok(W) || !mat_ok(dY) || !dW || (dH && !mat_ok(dH)))
+    if (!csr_ok(A_T) || !mat_ok(T) || !mat_ok(W) || !mat_ok(dY) || (dH && !mat_ok(dH)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: bad argument");
     const int relu = (flags & SGNN_RELU) ? 1 : 0;
     const bool xform_first = (flags & SGNN_XFORM_FIRST) != 0;
@@ -426,9 +426,11 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     }
     if (!xform_first) {
         // dW = T^T dZ
-        rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, nullptr, dZ, lddz,
-                              nullptr, mfma, dW, d_out, nullptr, 0, &ws, st);
-        if (rc) return rc;
+        if (dW) {
+            rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, nullptr, dZ, lddz,
+                                  nullptr, mfma, dW, d_out, nullptr, 0, &ws, st);
+            if (rc) return rc;
+        }
         if (dH) {
             // dT = dZ W^T, dH = A^T dT
             float *dT = ws.get<float>((size_t)Bn * ld_in);
@@ -447,9 +449,11 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
     rc = sgnn_launch_spmm(ctx, A_T, dZ, lddz, nullptr, d_out, dP, ld_out, nullptr, 0, nullptr, 0, nullptr, 0, &ws, st);
     if (rc) return rc;
-    rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, T->row_index, dP, ld_out,
-                          nullptr, mfma, dW, d_out, nullptr, 0, &ws, st);
-    if (rc) return rc;
+    if (dW) {
+        rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, T->row_index, dP, ld_out,
+                              nullptr, mfma, dW, d_out, nullptr, 0, &ws, st);
+        if (rc) return rc;
+    }
     if (dH)
         rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dP, ld_out, nullptr, static_cast<const float *>(W->ptr), W->ld,
                               nullptr, mfma, static_cast<float *>(dH->ptr), dH->ld, hmask, ldhm, &ws, st);

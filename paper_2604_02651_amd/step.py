@@ -20,7 +20,7 @@ class GcnStep:
     def __init__(self, N: int, rowptr: torch.Tensor, colidx: torch.Tensor, X: torch.Tensor, labels: torch.Tensor,
                  weights: List[Tuple[torch.Tensor, torch.Tensor]], B: int, seed: int = 0, bf16: bool = False,
                  fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None,
-                 auto_order: bool = True, fuse_relu_bwd: bool = True):
+                 auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = True):
         self.N, self.B, self.seed = N, B, seed
         self.rowptr, self.colidx, self.X, self.labels = rowptr, colidx, X, labels
         self.weights = weights
@@ -45,6 +45,7 @@ class GcnStep:
         # width d_out, and its backward pass needs the layer input instead of the aggregate
         self.xform_first = [auto_order and dims[l + 1] < dims[l] for l in range(self.L)]
         self.fuse_relu_bwd = fuse_relu_bwd
+        self.side_dw = side_dw      # run() / graphs: weight-gradient GEMMs on the second stream
         def mat(d):   # B x d with rows starting 16-byte aligned (leading dimension a multiple of 4)
             return torch.empty((B, (d + 3) // 4 * 4), dtype=torch.float32, device=dev)[:, :d]
         self.T = [None if self.xform_first[l] else mat(dims[l]) for l in range(self.L)]
@@ -97,12 +98,16 @@ class GcnStep:
     def loss_and_grad(self):
         sg.sgnn_softmax_xent(self.ctx, self.H[-1], self.y_S, self.loss, self.dO)
 
-    def backward(self):
+    def backward(self, side=None):
+        """side = (stream, context): the weight gradients dW = T^T dZ of the layers whose dZ is the incoming
+        dY itself (no masking pass in between) are computed there, concurrently with the rest of the backward
+        pass on the current stream; the caller joins the two streams."""
         dY = self.dO
         masked = False    # dY already carries the ReLU mask of the layer it enters
         for l in range(self.L - 1, -1, -1):
             W, _ = self.weights[l]
-            flags = self.flags | (sg.SGNN_RELU if l < self.L - 1 else 0) | (sg.SGNN_XFORM_FIRST if self.xform_first[l] else 0)
+            relu = l < self.L - 1
+            flags = self.flags | (sg.SGNN_RELU if relu else 0) | (sg.SGNN_XFORM_FIRST if self.xform_first[l] else 0)
             if masked:
                 flags |= sg.SGNN_DY_MASKED
             saved, ridx = self.T[l], None
@@ -111,10 +116,18 @@ class GcnStep:
                     saved, ridx = (self.X, self.S) if self.fuse_slice else (self.X_S, None)
                 else:
                     saved = self.H[l - 1]
+            dW = self.dW[l]
+            if side is not None and not self.xform_first[l] and (masked or not relu):
+                main = torch.cuda.current_stream()
+                ev = torch.cuda.Event()
+                ev.record(main)                      # dY is complete
+                side[0].wait_event(ev)
+                sg.sgnn_gemm(side[1], True, False, saved, dY, None, self.flags, dW, stream=side[0])
+                dW = None
             # the ReLU backward of the layer below is fused into the product that writes dH
             fuse = self.fuse_relu_bwd and l > 0
             # the induced matrix of a symmetric graph is symmetric: it is its own transpose
-            sg.sgnn_gcn_bwd(self.ctx, self.A, saved, W, self.H[l], dY, flags, self.dH[l], self.dW[l], self.db[l],
+            sg.sgnn_gcn_bwd(self.ctx, self.A, saved, W, self.H[l], dY, flags, self.dH[l], dW, self.db[l],
                             row_index=ridx, H_in=self.H[l - 1] if fuse else None)
             dY = self.dH[l]
             masked = fuse
@@ -147,7 +160,7 @@ class GcnStep:
         if not hasattr(self, "side_stream"):
             self.side_stream = torch.cuda.Stream(device=self.dev)       # default priority
             self.side_ctx = sg.Context(self.dev.index or 0)
-            self.side_ctx.reserve(self.N, int(self.colidx.numel()), self.B, 1, self.capacity)
+            self.side_ctx.reserve(self.N, int(self.colidx.numel()), self.B, max(self.dims), self.capacity)
             self.batches.append(self._new_batch())
             main = torch.cuda.current_stream()
             for b in self.batches:
@@ -172,44 +185,51 @@ class GcnStep:
             self._use(b)
             self.forward()
             self.loss_and_grad()
-            self.backward()
+            self.backward(side=(self.side_stream, self.side_ctx) if self.side_dw else None)
+            if self.side_dw:
+                main.wait_stream(self.side_stream)     # the weight gradients computed over there
             b.free.record(main)
         main.wait_stream(self.side_stream)
 
     # ---- the same pipeline captured in HIP graphs (one per mini-batch of a cycle) ----
 
-    def build_graphs(self, cycle):
-        """Capture, for every position i of the cycle of steps (even length), one HIP graph that
-        trains the mini-batch of cycle[i] (already in buffer set i % 2) while it builds the one of
-        cycle[i+1] in the other set on a forked stream.  Replaying the graphs in order, round and
+    def build_graphs(self, cycle, steps_per_graph: int = 0):
+        """Capture the overlapped pipeline over a cycle of steps (even length) in HIP graphs of
+        steps_per_graph steps each (0 = the whole cycle in one graph; must be even and divide the cycle).
+        Every step trains the mini-batch of cycle[i] (already in buffer set i % 2) while it builds the
+        one of cycle[i+1] in the other set on a forked stream.  Replaying the graphs in order, round and
         round, is the overlapped pipeline without any per-kernel launch work on the host."""
         cycle = list(cycle)
-        if len(cycle) % 2:
-            raise ValueError("the cycle must have an even number of steps (two buffer sets)")
+        spg = steps_per_graph or len(cycle)
+        if len(cycle) % 2 or spg % 2 or len(cycle) % spg:
+            raise ValueError("the cycle and the steps per graph must be even, and the latter must divide the former")
         self._init_side()
         torch.cuda.synchronize()
-        self.cycle, self.graphs = cycle, []
+        self.cycle, self.graphs, self.steps_per_graph = cycle, [], spg
         cap = torch.cuda.Stream(device=self.dev)
-        for i, t in enumerate(cycle):
-            b, nb = self.batches[i % 2], self.batches[(i + 1) % 2]
+        for g0 in range(0, len(cycle), spg):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=cap):
                 main = torch.cuda.current_stream()
-                self.side_stream.wait_stream(main)                     # fork
-                self._prefetch(cycle[(i + 1) % len(cycle)], nb, wait_free=False)
-                self._use(b)
-                self.forward()
-                self.loss_and_grad()
-                self.backward()
-                main.wait_stream(self.side_stream)                     # join
+                for i in range(g0, g0 + spg):
+                    b, nb = self.batches[i % 2], self.batches[(i + 1) % 2]
+                    self.side_stream.wait_stream(main)                     # fork
+                    self._prefetch(cycle[(i + 1) % len(cycle)], nb, wait_free=False)
+                    self._use(b)
+                    self.forward()
+                    self.loss_and_grad()
+                    self.backward(side=(self.side_stream, self.side_ctx) if self.side_dw else None)
+                    main.wait_stream(self.side_stream)                     # join
             self.graphs.append(g)
         torch.cuda.synchronize()
 
     def run_graphs(self, n: int):
-        """n steps of the captured cycle, starting at its first step."""
+        """n steps of the captured cycle, starting at its first step (n a multiple of the steps per graph)."""
+        if n % self.steps_per_graph:
+            raise ValueError("n must be a multiple of the %d steps of a graph" % self.steps_per_graph)
         self.side_stream.wait_stream(torch.cuda.current_stream())
         self._prefetch(self.cycle[0], self.batches[0], wait_free=False)
         torch.cuda.current_stream().wait_stream(self.side_stream)
-        for i in range(n):
+        for i in range(n // self.steps_per_graph):
             self.graphs[i % len(self.graphs)].replay()
         self._use(self.batches[(n - 1) % 2])

@@ -473,12 +473,13 @@ def test_overlapped_pipeline_matches_single_stream():
     b.ctx.status(); b.side_ctx.status()
     # the same pipeline replayed from HIP graphs, several rounds, checked after every replay count
     c = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, weights, cfg.B, cfg.sampler_seed, device=DEV)
-    c.build_graphs(range(4))
-    for n in (1, 2, 3, 4, 7, 9):
-        c.run_graphs(n)
-        a.step((n - 1) % 4)
-        torch.cuda.synchronize()
-        assert torch.equal(a.S, c.S) and torch.equal(a.A.rowptr, c.A.rowptr) and torch.equal(a.loss, c.loss)
-        for l in range(cfg.layers):
-            assert torch.equal(a.dW[l], c.dW[l]) and torch.equal(a.db[l], c.db[l]) and torch.equal(a.H[l], c.H[l])
+    for spg, counts in ((2, (2, 4, 6, 10)), (0, (4, 8, 12))):      # two steps a graph; the whole cycle in one graph
+        c.build_graphs(range(4), steps_per_graph=spg)
+        for n in counts:
+            c.run_graphs(n)
+            a.step((n - 1) % 4)
+            torch.cuda.synchronize()
+            assert torch.equal(a.S, c.S) and torch.equal(a.A.rowptr, c.A.rowptr) and torch.equal(a.loss, c.loss)
+            for l in range(cfg.layers):
+                assert torch.equal(a.dW[l], c.dW[l]) and torch.equal(a.db[l], c.db[l]) and torch.equal(a.H[l], c.H[l])
     c.ctx.status(); c.side_ctx.status()
