@@ -299,6 +299,12 @@ int sgnn_sigmoid_bce(sgnn_ctx *ctx, const float *O, int64_t ldo, const float *Y,
                      uint32_t C, float *loss_dev, float *dO, int64_t lddo, sgnn_stream stream);
 
 /*
+ * out[j] = sum over the rows of X[:, j] (fixed summation order): the bias gradient of Sec. III-C as an
+ * operator of its own, for callers that take it off the main stream.  X rows x cols fp32, out fp32[cols].
+ */
+int sgnn_colsum(sgnn_ctx *ctx, const sgnn_mat *X, float *out, sgnn_stream stream);
+
+/*
  * Parameter update ("update parameters", Alg. 1 line 7; the paper names no optimizer).
  * sgnn_sgd_step:  w <- w - lr * (g + weight_decay * w)
  * sgnn_adam_step: Adam (Kingma & Ba, ICLR 2015, Algorithm 1) with bias correction:

@@ -92,13 +92,14 @@ def lib():
         L.sgnn_induced_csr_range.argtypes = [vp, C.POINTER(_Graph), vp, u32, vp, vp, ci, i64, i64, i64, i64, C.POINTER(_Csr), vp, vp]
         L.sgnn_csr_transpose.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Csr), vp]
         L.sgnn_sigmoid_bce.argtypes = [vp, vp, i64, vp, i64, u32, u32, vp, vp, i64, vp]
+        L.sgnn_colsum.argtypes = [vp, C.POINTER(_Mat), vp, vp]
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
-                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose", "sgnn_sigmoid_bce",
+                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose", "sgnn_sigmoid_bce", "sgnn_colsum",
                      "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm", "sgnn_copy_f32"):
             getattr(L, name).restype = ci
         _lib = L
@@ -350,6 +351,12 @@ def sgnn_sigmoid_bce(ctx: Context, O: torch.Tensor, Y: torch.Tensor, loss: Optio
     ctx.check(lib().sgnn_sigmoid_bce(ctx._h, _ptr(O, torch.float32, "O"), O.stride(0), _ptr(Y, torch.float32, "Y"), Y.stride(0),
                                      O.shape[0], O.shape[1], _ptr(loss, torch.float32, "loss"), _ptr(dO, torch.float32, "dO"),
                                      dO.stride(0) if dO is not None else 0, _stream(stream)))
+
+
+def sgnn_colsum(ctx: Context, X: torch.Tensor, out: torch.Tensor, stream=None):
+    """out[j] = sum_i X[i, j] (fixed order)."""
+    x = _mat(X, None, "X")
+    ctx.check(lib().sgnn_colsum(ctx._h, C.byref(x), _ptr(out, torch.float32, "out"), _stream(stream)))
 
 
 def sgnn_tail_fwd(ctx: Context, Z: torch.Tensor, gamma: Optional[torch.Tensor], eps: float, R: Optional[torch.Tensor],

@@ -504,6 +504,17 @@ int sgnn_sigmoid_bce(sgnn_ctx *ctx, const float *O, int64_t ldo, const float *Y,
     return sgnn_launch_bce(ctx, O, ldo, Y, ldy, B, C, loss_dev, dO, lddo, &ws, static_cast<hipStream_t>(stream));
 }
 
+int sgnn_colsum(sgnn_ctx *ctx, const sgnn_mat *X, float *out, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!mat_ok(X) || X->row_index || !out) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_colsum: bad argument");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    ws_alloc ws(ctx);
+    return sgnn_launch_relu_bwd_bias(ctx, nullptr, 0, static_cast<const float *>(X->ptr), X->ld, 0, X->rows, X->cols, nullptr, 0,
+                                     out, &ws, static_cast<hipStream_t>(stream));
+}
+
 int sgnn_sgd_step(sgnn_ctx *ctx, float *w, const float *g, int64_t n, double lr, double weight_decay, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;

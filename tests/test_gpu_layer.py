@@ -483,3 +483,14 @@ def test_overlapped_pipeline_matches_single_stream():
             for l in range(cfg.layers):
                 assert torch.equal(a.dW[l], c.dW[l]) and torch.equal(a.db[l], c.db[l]) and torch.equal(a.H[l], c.H[l])
     c.ctx.status(); c.side_ctx.status()
+
+
+@pytest.mark.parametrize("rows,cols", [(1000, 256), (77, 47), (4100, 32), (5, 1)])
+def test_column_sums(rows, cols):
+    X = _rand((rows, cols + 2), 31)
+    out = torch.full((cols,), 9.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_colsum(ctx(), dev(X)[:, :cols], out)
+    assert rel_err(out.cpu().numpy(), X[:, :cols].astype(np.float64).sum(axis=0)) < TOL_F32
+    out2 = torch.zeros_like(out)
+    sg.sgnn_colsum(ctx(), dev(X)[:, :cols], out2)
+    assert torch.equal(out, out2)
