@@ -48,6 +48,7 @@ enum {
     SGNN_BF16_MFMA = 2, /* round both GEMM operands to bfloat16 (nearest even), accumulate in fp32  */
     SGNN_DY_MASKED = 8, /* backward only: dY already carries the ReLU mask of this layer's output (the
                            layer above was given H_in), so it is not applied again                   */
+    SGNN_FUSE_TAIL = 16, /* sgnn_gemm_tail_fwd only: run the tail in the epilogue of the product (see there)  */
     SGNN_XFORM_FIRST = 4 /* evaluate A (H W) instead of (A H) W: the same result up to rounding, with
                             the sparse product at width d_out; worth it when d_out < d_in           */
 };
@@ -269,6 +270,21 @@ int sgnn_graph_normalized_csr(sgnn_ctx *ctx, const sgnn_graph *g, int32_t *rowpt
 int sgnn_tail_fwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *gamma, float eps, const sgnn_mat *R,
                   float drop_q, uint64_t drop_seed, uint32_t layer, uint64_t step, sgnn_mat *Y,
                   float *inv_rms, sgnn_stream stream);
+
+/*
+ * The dense transform and the tail in one call: Z = T W (Eq. 6), Y = dropout(relu(rmsnorm(Z))) + R
+ * (Eqs. 7-10).  By default the product and sgnn_tail_fwd run one after the other.  With SGNN_FUSE_TAIL,
+ * SGNN_BF16_MFMA and a tall T (at least 4096 rows, at most 256 columns in T and W, W's width a multiple
+ * of 4, T's rows 16-byte aligned) both run in ONE kernel - the tail in the epilogue of the product, whose
+ * wavefronts own whole rows - so Z is written for the backward pass but never read back.  Same result up
+ * to the summation order of the mean square.  On MI355X the fused form is the slower one (its epilogue
+ * has no registers left to hide the loads of R): it is kept as an option, not as the default.
+ *   T  B x d_in fp32;  W  d_in x d fp32;  flags  SGNN_BF16_MFMA, SGNN_FUSE_TAIL;  the rest as in sgnn_tail_fwd
+ *   Z  out B x d fp32 (kept for sgnn_tail_bwd);  Y  out B x d fp32
+ */
+int sgnn_gemm_tail_fwd(sgnn_ctx *ctx, const sgnn_mat *T, const sgnn_mat *W, const float *gamma, float eps,
+                       const sgnn_mat *R, float drop_q, uint64_t drop_seed, uint32_t layer, uint64_t step,
+                       int flags, sgnn_mat *Z, sgnn_mat *Y, float *inv_rms, sgnn_stream stream);
 
 /*
  * Backward of the main branch of that tail (Sec. III-C: dropout mask, ReLU mask, RMSNorm backward).

@@ -19,6 +19,7 @@ SGNN_RELU = 1
 SGNN_BF16_MFMA = 2
 SGNN_XFORM_FIRST = 4
 SGNN_DY_MASKED = 8
+SGNN_FUSE_TAIL = 16
 SGNN_F32 = 0
 
 _ERR_NAMES = {-1: "SGNN_ERR_INVALID_ARG", -2: "SGNN_ERR_CAPACITY", -3: "SGNN_ERR_UNSUPPORTED", -4: "SGNN_ERR_HIP",
@@ -83,6 +84,8 @@ def lib():
                                    C.POINTER(_Mat), ci, C.POINTER(_Mat), C.POINTER(_Mat), vp, vp, vp]
         u64, cf = C.c_uint64, C.c_float
         L.sgnn_tail_fwd.argtypes = [vp, C.POINTER(_Mat), vp, cf, C.POINTER(_Mat), cf, u64, u32, u64, C.POINTER(_Mat), vp, vp]
+        L.sgnn_gemm_tail_fwd.argtypes = [vp, C.POINTER(_Mat), C.POINTER(_Mat), vp, cf, C.POINTER(_Mat), cf, u64, u32, u64, ci,
+                                         C.POINTER(_Mat), C.POINTER(_Mat), vp, vp]
         L.sgnn_tail_bwd.argtypes = [vp, C.POINTER(_Mat), vp, vp, cf, u64, u32, u64, C.POINTER(_Mat), C.POINTER(_Mat), vp, vp,
                                     vp]
         cd = C.c_double
@@ -99,7 +102,7 @@ def lib():
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
-                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose", "sgnn_sigmoid_bce", "sgnn_colsum",
+                     "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_gemm_tail_fwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose", "sgnn_sigmoid_bce", "sgnn_colsum",
                      "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm", "sgnn_copy_f32"):
             getattr(L, name).restype = ci
         _lib = L
@@ -368,6 +371,17 @@ def sgnn_tail_fwd(ctx: Context, Z: torch.Tensor, gamma: Optional[torch.Tensor], 
     ctx.check(lib().sgnn_tail_fwd(ctx._h, C.byref(z), _ptr(gamma, torch.float32, "gamma"), eps,
                                   C.byref(r) if r is not None else None, drop_q, drop_seed, layer, step, C.byref(y),
                                   _ptr(inv_rms, torch.float32, "inv_rms"), _stream(stream)))
+
+
+def sgnn_gemm_tail_fwd(ctx: Context, T: torch.Tensor, W: torch.Tensor, gamma: Optional[torch.Tensor], eps: float,
+                       R: Optional[torch.Tensor], drop_q: float, drop_seed: int, layer: int, step: int, flags: int,
+                       Z: torch.Tensor, Y: torch.Tensor, inv_rms: Optional[torch.Tensor], stream=None):
+    """Z = T W and Y = dropout(relu(rmsnorm(Z))) + R in one call (one kernel for tall bf16 products)."""
+    t, w, z, y = _mat(T, None, "T"), _mat(W, None, "W"), _mat(Z, None, "Z"), _mat(Y, None, "Y")
+    r = _mat(R, None, "R") if R is not None else None
+    ctx.check(lib().sgnn_gemm_tail_fwd(ctx._h, C.byref(t), C.byref(w), _ptr(gamma, torch.float32, "gamma"), eps,
+                                       C.byref(r) if r is not None else None, drop_q, drop_seed, layer, step, flags,
+                                       C.byref(z), C.byref(y), _ptr(inv_rms, torch.float32, "inv_rms"), _stream(stream)))
 
 
 def sgnn_tail_bwd(ctx: Context, Z: torch.Tensor, inv_rms: torch.Tensor, gamma: Optional[torch.Tensor], drop_q: float,

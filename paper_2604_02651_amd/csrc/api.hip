@@ -475,6 +475,37 @@ int sgnn_tail_fwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *gamma, float ep
                                 static_cast<float *>(Y->ptr), Y->ld, inv_rms, static_cast<hipStream_t>(stream));
 }
 
+int sgnn_gemm_tail_fwd(sgnn_ctx *ctx, const sgnn_mat *T, const sgnn_mat *W, const float *gamma, float eps, const sgnn_mat *R,
+                       float drop_q, uint64_t drop_seed, uint32_t layer, uint64_t step, int flags, sgnn_mat *Z, sgnn_mat *Y,
+                       float *inv_rms, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!mat_ok(T) || !mat_ok(W) || !mat_ok(Z) || !mat_ok(Y) || (R && !mat_ok(R)) || T->row_index || W->row_index ||
+        Z->row_index || Y->row_index || (R && R->row_index) || !(eps >= 0.f))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm_tail_fwd: bad argument");
+    const int64_t M = T->rows, K = T->cols, N = W->cols;
+    if (W->rows != K || Z->rows != M || Z->cols != N || Y->rows != M || Y->cols != N || (R && (R->rows != M || R->cols != N)))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm_tail_fwd: shape mismatch");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const float *Rp = R ? static_cast<const float *>(R->ptr) : nullptr;
+    const int64_t ldr = R ? R->ld : 0;
+    if ((flags & SGNN_BF16_MFMA) && (flags & SGNN_FUSE_TAIL)) {
+        rc = sgnn_launch_gemm_tail(ctx, M, N, K, static_cast<const float *>(T->ptr), T->ld, static_cast<const float *>(W->ptr),
+                                   W->ld, gamma, eps, Rp, ldr, drop_q, drop_seed, layer, step, static_cast<float *>(Z->ptr),
+                                   Z->ld, static_cast<float *>(Y->ptr), Y->ld, inv_rms, st);
+        if (rc != SGNN_ERR_UNSUPPORTED) return rc;     // done, or a real error
+    }
+    // shapes outside the fused kernel: the product, then the tail
+    ws_alloc ws(ctx);
+    rc = sgnn_launch_gemm(ctx, 0, 0, M, N, K, static_cast<const float *>(T->ptr), T->ld, nullptr, static_cast<const float *>(W->ptr),
+                          W->ld, nullptr, flags & SGNN_BF16_MFMA, static_cast<float *>(Z->ptr), Z->ld, nullptr, 0, &ws, st);
+    if (rc) return rc;
+    return sgnn_launch_tail_fwd(ctx, M, N, static_cast<const float *>(Z->ptr), Z->ld, gamma, eps, Rp, ldr, drop_q, drop_seed, layer,
+                                step, static_cast<float *>(Y->ptr), Y->ld, inv_rms, st);
+}
+
 int sgnn_tail_bwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *inv_rms, const float *gamma, float drop_q,
                   uint64_t drop_seed, uint32_t layer, uint64_t step, const sgnn_mat *dY, sgnn_mat *dZ, float *dgamma,
                   float *dbias, sgnn_stream stream)

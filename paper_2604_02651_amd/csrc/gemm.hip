@@ -16,9 +16,12 @@
 //   result register r of lane (kh, j) is C[8*(r/4) + 4*kh + r%4][j].
 // The order in which the reduction index is fed is free as long as both operands agree, so for fp32
 // the slice of 16 is fed as k = 8*kh + s at step s: every lane then reads 8 consecutive values.
+#include <math.h>
+
 #include <algorithm>
 
 #include "common.h"
+#include "philox.h"
 
 #ifndef SGNN_GEMM_BK_F32
 #define SGNN_GEMM_BK_F32 32   // reduction slice of the fp32 path (a multiple of 16)
@@ -789,14 +792,38 @@ constexpr int SKINNY_PATCH = 32 * 40;   // 16-bit elements of a wavefront's patc
 
 inline size_t skinny_lds_bytes(int nt8, int kp)
 {
-    return ((size_t)32 * nt8 * kp + (size_t)SKINNY_WAVES * SKINNY_PATCH) * 2 + (size_t)32 * nt8 * sizeof(float);
+    return ((size_t)32 * nt8 * kp + (size_t)SKINNY_WAVES * SKINNY_PATCH) * 2 + (size_t)2 * 32 * nt8 * sizeof(float);
 }
+
+// value of lane k (0..3) of the caller's quad of lanes, in every lane of the quad (DPP quad_perm, no LDS)
+__device__ __forceinline__ uint32_t quad_broadcast(uint32_t v, int k)
+{
+    switch (k) {
+    case 0: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x00, 0xF, 0xF, false);
+    case 1: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x55, 0xF, 0xF, false);
+    case 2: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xAA, 0xF, 0xF, false);
+    default: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xFF, 0xF, 0xF, false);
+    }
+}
+
+// Optional layer tail fused into the epilogue (Sec. III-B Eqs. 7-10; Sec. V "Kernel Fusion"): a wavefront
+// owns whole rows of the result, so the RMS of a row is a reduction inside the wavefront and
+// Y = dropout(relu(rmsnorm(Z))) + R is written next to Z without reading Z back.
+struct skinny_tail {
+    const float *gamma;   // [N] or NULL
+    float eps;
+    const float *R; int64_t ldr;   // residual input or NULL
+    float *Y; int64_t ldy;
+    float *inv_rms;       // [M] or NULL
+    uint32_t thr; float scale; uint32_t k0, k1, c2, c3;   // dropout: keep iff word >= thr (thr = 0: none)
+};
 
 // NT8 = column tiles of 32 (N <= 32 NT8), S = slices of 32 along the reduction (K <= 32 S).  Both are
 // compile-time so that the order of every load and store of a row block is fixed: the waits on the
 // slices in flight then count exactly the operations issued after them.
-template <int NT8, int S>
-__global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gemm_args a, int tb, uint32_t n_rowblocks)
+template <int NT8, int S, bool TAIL>
+__global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gemm_args a, int tb, uint32_t n_rowblocks,
+                                                                             skinny_tail tl)
 {
     constexpr int D = S == 8 ? 4 : (S == 6 ? 3 : S);   // slices in flight; divides S
     constexpr int KP = 32 * S + 8;                      // row length of B in LDS
@@ -863,7 +890,11 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
         }
     }
     float *Lbias = reinterpret_cast<float *>(LB + NP * KP + SKINNY_WAVES * SKINNY_PATCH);   // kept in LDS: no load in the stream
-    for (int n = threadIdx.x; n < NP; n += 64 * SKINNY_WAVES) Lbias[n] = (a.bias && n < N) ? a.bias[n] : 0.f;
+    float *Lgamma = Lbias + NP;
+    for (int n = threadIdx.x; n < NP; n += 64 * SKINNY_WAVES) {
+        Lbias[n] = (a.bias && n < N) ? a.bias[n] : 0.f;
+        if (TAIL) Lgamma[n] = (tl.gamma && n < N) ? tl.gamma[n] : 1.f;
+    }
     __syncthreads();
 
     f32x16 acc[NT8];
@@ -967,6 +998,66 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
                     }
                 }
         }
+        if constexpr (TAIL) {
+            // 1 / rms of the lane's sixteen rows: squares summed over its columns, then over the 32 lanes that
+            // share those rows (xor distances below 32 stay inside the half wavefront)
+            float ir[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ir[r] = 0.f;
+#pragma unroll
+            for (int j = 0; j < NT8; ++j) {
+                if (32 * j + li < N) {
+                    const float bj = Lbias[32 * j + li];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float z = acc[j][r] + bj;
+                        ir[r] = fmaf(z, z, ir[r]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) ir[r] += __shfl_xor(ir[r], o);
+                ir[r] = 1.f / sqrtf(ir[r] / (float)N + tl.eps);                     // Eq. 7
+                const int64_t row = row0 + 8 * (r / 4) + (r % 4);
+                if (tl.inv_rms && li == 0 && row < a.M) tl.inv_rms[row] = ir[r];
+            }
+#pragma unroll
+            for (int j = 0; j < NT8; ++j) {
+                const int col = 32 * j + li;
+                const float bj = Lbias[col], gj = Lgamma[col];
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    // dropout words: the four lanes of a quad hold four consecutive columns = one Philox block per
+                    // row; lane k of the quad evaluates the block of row 8 rg + k, the quad then shares the four
+                    philox_out o = {0u, 0u, 0u, 0u};
+                    if (tl.thr) {
+                        const uint64_t e = (uint64_t)(row0 + 8 * rg + (li & 3)) * (uint64_t)N + (uint64_t)(32 * j + (li & ~3));
+                        o = philox4x32_10((uint32_t)(e >> 2), (uint32_t)(e >> 34), tl.c2, tl.c3, tl.k0, tl.k1);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int r = 4 * rg + k;
+                        const int64_t row = row0 + 8 * rg + k;
+                        float keep = 1.f;
+                        if (tl.thr) {
+                            const uint32_t w0 = quad_broadcast(o.w0, k);
+                            const uint32_t w1 = quad_broadcast(o.w1, k);
+                            const uint32_t w2 = quad_broadcast(o.w2, k);
+                            const uint32_t w3 = quad_broadcast(o.w3, k);
+                            const uint32_t w = (li & 2) ? ((li & 1) ? w3 : w2) : ((li & 1) ? w1 : w0);
+                            keep = w >= tl.thr ? tl.scale : 0.f;
+                        }
+                        if (col < N && row < a.M) {
+                            const float n = gj * (acc[j][r] + bj) * ir[r];
+                            const float res = tl.R ? tl.R[row * tl.ldr + col] : 0.f;
+                            tl.Y[row * tl.ldy + col] = fmaxf(n, 0.f) * keep + res;   // Eqs. 8-10
+                        }
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int j = 0; j < NT8; ++j)
 #pragma unroll
@@ -974,44 +1065,52 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
     }
 }
 
-template <int NT8, int S>
-int launch_skinny_ns(sgnn_ctx *ctx, const gemm_args &a, int tb, hipStream_t st)
+template <int NT8, int S, bool TAIL>
+int launch_skinny_ns(sgnn_ctx *ctx, const gemm_args &a, int tb, const skinny_tail &tl, hipStream_t st)
 {
     const size_t lds = skinny_lds_bytes(NT8, 32 * S + 8);
     static bool attr_set = false;
     if (!attr_set) {
-        SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny_bf16_kernel<NT8, S>),
+        SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny_bf16_kernel<NT8, S, TAIL>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_set = true;
     }
     const uint32_t n_rowblocks = (uint32_t)cdiv(a.M, 32 * SKINNY_WAVES);
     char tag[56];
-    snprintf(tag, sizeof(tag), "N%c skinny %lldx%lldx%lld bf16", tb ? 'T' : 'N', (long long)a.M, (long long)a.N, (long long)a.K);
-    SGNN_LAUNCH(ctx, st, "gemm_skinny_bf16_kernel", tag, (gemm_skinny_bf16_kernel<NT8, S>),
-                dim3(std::min<uint32_t>(n_rowblocks, 256)), dim3(64 * SKINNY_WAVES), lds, st, a, tb, n_rowblocks);
+    snprintf(tag, sizeof(tag), "N%c skinny%s %lldx%lldx%lld bf16", tb ? 'T' : 'N', TAIL ? "+tail" : "", (long long)a.M, (long long)a.N,
+             (long long)a.K);
+    SGNN_LAUNCH(ctx, st, "gemm_skinny_bf16_kernel", tag, (gemm_skinny_bf16_kernel<NT8, S, TAIL>),
+                dim3(std::min<uint32_t>(n_rowblocks, 256)), dim3(64 * SKINNY_WAVES), lds, st, a, tb, n_rowblocks, tl);
     return SGNN_OK;
 }
 
-template <int NT8>
-int launch_skinny_n(sgnn_ctx *ctx, const gemm_args &a, int tb, hipStream_t st)
+template <int NT8, bool TAIL>
+int launch_skinny_n(sgnn_ctx *ctx, const gemm_args &a, int tb, const skinny_tail &tl, hipStream_t st)
 {
     const int s2 = (int)((a.K + 63) / 64);   // slices, rounded up to an even count
     switch (s2) {
-    case 1: return launch_skinny_ns<NT8, 2>(ctx, a, tb, st);
-    case 2: return launch_skinny_ns<NT8, 4>(ctx, a, tb, st);
-    case 3: return launch_skinny_ns<NT8, 6>(ctx, a, tb, st);
-    default: return launch_skinny_ns<NT8, 8>(ctx, a, tb, st);
+    case 1: return launch_skinny_ns<NT8, 2, TAIL>(ctx, a, tb, tl, st);
+    case 2: return launch_skinny_ns<NT8, 4, TAIL>(ctx, a, tb, tl, st);
+    case 3: return launch_skinny_ns<NT8, 6, TAIL>(ctx, a, tb, tl, st);
+    default: return launch_skinny_ns<NT8, 8, TAIL>(ctx, a, tb, tl, st);
+    }
+}
+
+template <bool TAIL>
+int launch_skinny_t(sgnn_ctx *ctx, const gemm_args &a, int tb, const skinny_tail &tl, hipStream_t st)
+{
+    switch ((int)((a.N + 63) / 64)) {   // column tiles, rounded up to an even count
+    case 1: return launch_skinny_n<2, TAIL>(ctx, a, tb, tl, st);
+    case 2: return launch_skinny_n<4, TAIL>(ctx, a, tb, tl, st);
+    case 3: return launch_skinny_n<6, TAIL>(ctx, a, tb, tl, st);
+    default: return launch_skinny_n<8, TAIL>(ctx, a, tb, tl, st);
     }
 }
 
 int launch_skinny(sgnn_ctx *ctx, const gemm_args &a, int tb, hipStream_t st)
 {
-    switch ((int)((a.N + 63) / 64)) {   // column tiles, rounded up to an even count
-    case 1: return launch_skinny_n<2>(ctx, a, tb, st);
-    case 2: return launch_skinny_n<4>(ctx, a, tb, st);
-    case 3: return launch_skinny_n<6>(ctx, a, tb, st);
-    default: return launch_skinny_n<8>(ctx, a, tb, st);
-    }
+    const skinny_tail none = {};
+    return launch_skinny_t<false>(ctx, a, tb, none, st);
 }
 
 // Sum of the split-K partial products in a fixed order (bit-reproducible).
@@ -1145,4 +1244,31 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
                            ldc);
     }
     return SGNN_OK;
+}
+
+// Z = A W with the layer tail fused into the epilogue (bf16 operands, the tall-operand kernel).  Returns
+// SGNN_ERR_UNSUPPORTED without launching when the shape is outside that kernel's range: the caller then runs
+// the product and the tail as two launches.
+int sgnn_launch_gemm_tail(sgnn_ctx *ctx, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *W,
+                          int64_t ldw, const float *gamma, float eps, const float *R, int64_t ldr, float q, uint64_t seed,
+                          uint32_t layer, uint64_t step, float *Z, int64_t ldz, float *Y, int64_t ldy, float *inv_rms,
+                          hipStream_t st)
+{
+    if (!(q >= 0.f) || !(q < 1.f)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm_tail_fwd: need 0 <= drop_q < 1");
+    const bool alignedA = (reinterpret_cast<uintptr_t>(A) & 15) == 0 && lda % 4 == 0;
+    if (!(K >= 1 && K <= 256 && N >= 1 && N <= 256 && N % 4 == 0 && M >= 4096 && alignedA)) return SGNN_ERR_UNSUPPORTED;
+    gemm_args a;
+    a.a_row_index = nullptr;
+    a.M = M; a.N = N; a.K = K;
+    a.A = A; a.lda = lda; a.B = W; a.ldb = ldw; a.bias = nullptr; a.C = Z; a.ldc = ldz;
+    a.relu = 0; a.mask = nullptr; a.ldm = 0;
+    a.alignedA = 1;
+    a.alignedB = ((reinterpret_cast<uintptr_t>(W) & 15) == 0 && ldw % 4 == 0) ? 1 : 0;
+    a.k_per_split = K; a.partial = nullptr; a.mtiles = a.ntiles = a.splits = 0;
+    skinny_tail tl;
+    tl.gamma = gamma; tl.eps = eps; tl.R = R; tl.ldr = ldr; tl.Y = Y; tl.ldy = ldy; tl.inv_rms = inv_rms;
+    tl.thr = (uint32_t)floor((double)q * 4294967296.0);
+    tl.scale = q > 0.f ? (float)(1.0 / (1.0 - (double)q)) : 1.f;
+    tl.k0 = (uint32_t)seed; tl.k1 = (uint32_t)(seed >> 32); tl.c2 = (uint32_t)step; tl.c3 = 0x80000000u + layer;
+    return launch_skinny_t<true>(ctx, a, 0, tl, st);
 }

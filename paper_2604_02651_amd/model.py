@@ -85,9 +85,8 @@ class ScaleGnnModel:
         sg.sgnn_gemm(c, False, False, self.X_S, self.p["W_in"], None, f, self.Xh[0])
         for l, (W, gam) in enumerate(self.p["layers"]):
             sg.sgnn_spmm(c, self.A, self.Xh[l], self.T[l])                                    # Eq. 5
-            sg.sgnn_gemm(c, False, False, self.T[l], W, None, f, self.Z[l])                   # Eq. 6
-            sg.sgnn_tail_fwd(c, self.Z[l], gam, self.eps, self.Xh[l], self.drop_q, self.drop_seed, l, t,
-                             self.Xh[l + 1], self.inv_rms[l])                                 # Eqs. 7-10
+            sg.sgnn_gemm_tail_fwd(c, self.T[l], W, gam, self.eps, self.Xh[l], self.drop_q, self.drop_seed, l, t, f,
+                                  self.Z[l], self.Xh[l + 1], self.inv_rms[l])                 # Eqs. 6-10
         sg.sgnn_gemm(c, False, False, self.Xh[self.L], self.p["W_out"], None, f, self.O)
 
     # lines 6-7 (Sec. III-C); the induced matrix of a symmetric graph is its own transpose

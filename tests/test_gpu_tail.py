@@ -77,3 +77,29 @@ def test_tail_rejects_bad_arguments():
     wide = dev(_rand((2, 2052), 2))
     with pytest.raises(sg.SgnnError):
         sg.sgnn_tail_fwd(ctx(), wide, None, 1e-6, None, 0.0, 0, 0, 0, torch.zeros_like(wide), None)
+
+
+@pytest.mark.parametrize("fuse", [True, False])
+@pytest.mark.parametrize("bf16", [True, False])
+@pytest.mark.parametrize("q", [0.0, 0.3])
+@pytest.mark.parametrize("M,K,N", [(5000, 256, 256), (4100, 100, 128), (4096, 64, 64), (9001, 172, 200), (700, 64, 64),
+                                   (4500, 256, 47)])
+def test_transform_and_tail_in_one_call(M, K, N, q, bf16, fuse):
+    # with SGNN_FUSE_TAIL tall bf16 products run the tail in the epilogue of the product (one kernel); the other
+    # shapes, fp32 and the default run the two kernels one after the other.  Either way: Z = T W, Y = tail(Z).
+    ctx().reserve(1, 1, 16384, 256)
+    T = _rand((M, K), 1); W = (_rand((K, N), 2) / np.sqrt(K)).astype(np.float32)
+    g = (1.0 + 0.5 * _rand(N, 3)).astype(np.float32); R = _rand((M, N), 4)
+    seed, layer, step, eps = 12345, 1, 7, 1e-6
+    Z = torch.zeros((M, N), dtype=torch.float32, device=DEV); Y = torch.zeros_like(Z)
+    ir = torch.zeros(M, dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm_tail_fwd(ctx(), dev(T), dev(W), dev(g), eps, dev(R), q, seed, layer, step,
+                          (sg.SGNN_BF16_MFMA if bf16 else 0) | (sg.SGNN_FUSE_TAIL if fuse else 0), Z, Y, ir)
+    rd = oracle.round_bf16 if bf16 else (lambda x: x.astype(np.float64))
+    Z_ref = oracle.gemm(rd(T), rd(W))
+    assert rel_err(Z.cpu().numpy(), Z_ref) < (1e-4 if bf16 else TOL_F32)
+    # the tail of the Z the kernels produced (so that the ReLU and dropout decisions are those of the same values)
+    Zk = Z.cpu().numpy()
+    Y_ref, ir_ref, _ = oracle.tail_fwd(Zk, gamma=g, eps=eps, R=R, q=q, seed=seed, layer=layer, step=step)
+    assert rel_err(Y.cpu().numpy(), Y_ref) < TOL_F32
+    assert rel_err(ir.cpu().numpy(), ir_ref) < TOL_F32
