@@ -224,3 +224,33 @@ def test_whole_step_against_autograd(tiny_graph):
     for l, (W, b) in enumerate(params):
         assert np.allclose(out["dW"][l], W.grad.numpy(), rtol=1e-9, atol=1e-13)
         assert np.allclose(out["db"][l], b.grad.numpy(), rtol=1e-9, atol=1e-13)
+
+
+def test_relu_tie_band_only_acts_inside_the_band():
+    # layers_step(relu_ties=..., tie_band=...) replaces the oracle's own ReLU decision only where the
+    # pre-activation lies within the band; outside it the supplied mask is ignored, and with a zero band
+    # nothing changes at all.
+    rng = np.random.default_rng(0)
+    Bn = 12
+    dense = (rng.random((Bn, Bn)) < 0.4) * rng.random((Bn, Bn)) + np.eye(Bn)
+    rp = [0]; ci = []; v = []
+    for i in range(Bn):
+        nz = np.nonzero(dense[i])[0]
+        ci += list(nz); v += list(dense[i, nz].astype(np.float32)); rp.append(len(ci))
+    rp, ci, v = np.array(rp, np.int32), np.array(ci, np.int32), np.array(v, np.float32)
+    X = rng.standard_normal((Bn, 5)); y = rng.integers(0, 3, Bn).astype(np.int32)
+    Ws = [(rng.standard_normal((5, 6)), rng.standard_normal(6) * 0.1), (rng.standard_normal((6, 3)), np.zeros(3))]
+    base = oracle.layers_step(rp, ci, v, X, y, Ws)
+    flipped = [~base["relu_mask"][0], None]
+    same = oracle.layers_step(rp, ci, v, X, y, Ws, relu_ties=flipped, tie_band=0.0)
+    assert all(np.array_equal(a, b) for a, b in zip(same["dW"], base["dW"]))
+    # a band that covers the smallest |Z| only: exactly that decision flips, and the gradients move
+    T0, Z0 = oracle.gcn_fwd(rp, ci, v, X, Ws[0][0], Ws[0][1], relu=False)
+    az = np.abs(Z0); k = np.unravel_index(np.argmin(az), az.shape)
+    band = (az[k] * 1.0000001) / az.max()
+    out = oracle.layers_step(rp, ci, v, X, y, Ws, relu_ties=flipped, tie_band=band)
+    assert out["relu_band"][0].sum() == 1 and out["relu_band"][0][k]
+    diff = out["relu_mask"][0] != base["relu_mask"][0]
+    assert diff.sum() == 1 and diff[k]
+    assert np.array_equal(out["loss"], base["loss"]) and all(np.array_equal(a, b) for a, b in zip(out["H"], base["H"]))
+    assert not np.array_equal(out["dW"][0], base["dW"][0])
