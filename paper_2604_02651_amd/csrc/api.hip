@@ -327,7 +327,8 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_ma
 }
 
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
-              const float *B, int64_t ldb, const float *bias, int flags, float *C, int64_t ldc, sgnn_stream stream)
+              const float *B, int64_t ldb, const float *bias, int flags, float *C, int64_t ldc, float *b_colsum,
+              sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     if (!A || !B || !C || M < 0 || N < 0 || K < 0) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: bad argument");
@@ -337,7 +338,7 @@ int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_gemm(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, nullptr, B, ldb, bias, flags, C, ldc, nullptr, 0, &ws,
+    return sgnn_launch_gemm(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, nullptr, B, ldb, bias, flags, C, ldc, nullptr, 0, b_colsum, &ws,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -365,7 +366,7 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
         if (rc) return rc;
         return sgnn_launch_gemm(ctx, 0, 0, Bn, d_out, d_in, static_cast<const float *>(T->ptr), T->ld, nullptr,
                                 static_cast<const float *>(W->ptr), W->ld, bias, gflags, static_cast<float *>(Y->ptr), Y->ld,
-                                nullptr, 0, &ws, st);
+                                nullptr, 0, nullptr, &ws, st);
     }
     // A (H W): transform first (the aggregation then runs at width d_out), bias and activation
     // fused into the sparse product
@@ -373,7 +374,7 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
     float *P = ws.get<float>((size_t)A->cols * ldp);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_fwd: scratch too small: call sgnn_ctx_reserve");
     rc = sgnn_launch_gemm(ctx, 0, 0, A->cols, d_out, d_in, static_cast<const float *>(H->ptr), H->ld, H->row_index,
-                          static_cast<const float *>(W->ptr), W->ld, nullptr, flags & SGNN_BF16_MFMA, P, ldp, nullptr, 0, &ws, st);
+                          static_cast<const float *>(W->ptr), W->ld, nullptr, flags & SGNN_BF16_MFMA, P, ldp, nullptr, 0, nullptr, &ws, st);
     if (rc) return rc;
     return sgnn_launch_spmm(ctx, A, P, ldp, nullptr, d_out, static_cast<float *>(Y->ptr), Y->ld, bias,
                             (flags & SGNN_RELU) ? 1 : 0, nullptr, 0, nullptr, 0, &ws, st);
@@ -412,7 +413,9 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     const int mask_here = relu && !dy_masked;
     const float *hmask = H_in ? static_cast<const float *>(H_in->ptr) : nullptr;
     const int64_t ldhm = H_in ? H_in->ld : 0;
-    if (mask_here || dbias) {
+    // the bias gradient rides on the weight-gradient product when both read the same dZ = dY
+    const bool db_in_gemm = dbias && dW && !mask_here && !xform_first;
+    if (mask_here || (dbias && !db_in_gemm)) {
         float *dZbuf = nullptr;
         if (mask_here) {
             dZbuf = ws.get<float>((size_t)Bn * ld_out);
@@ -428,7 +431,7 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
         // dW = T^T dZ
         if (dW) {
             rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, nullptr, dZ, lddz,
-                                  nullptr, mfma, dW, d_out, nullptr, 0, &ws, st);
+                                  nullptr, mfma, dW, d_out, nullptr, 0, db_in_gemm ? dbias : nullptr, &ws, st);
             if (rc) return rc;
         }
         if (dH) {
@@ -436,7 +439,7 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
             float *dT = ws.get<float>((size_t)Bn * ld_in);
             if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
             rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, nullptr, static_cast<const float *>(W->ptr), W->ld,
-                                  nullptr, mfma, dT, ld_in, nullptr, 0, &ws, st);
+                                  nullptr, mfma, dT, ld_in, nullptr, 0, nullptr, &ws, st);
             if (rc) return rc;
             rc = sgnn_launch_spmm(ctx, A_T, dT, ld_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, hmask, ldhm, nullptr, 0, &ws,
                                   st);
@@ -451,12 +454,12 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     if (rc) return rc;
     if (dW) {
         rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, T->row_index, dP, ld_out,
-                              nullptr, mfma, dW, d_out, nullptr, 0, &ws, st);
+                              nullptr, mfma, dW, d_out, nullptr, 0, nullptr, &ws, st);
         if (rc) return rc;
     }
     if (dH)
         rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dP, ld_out, nullptr, static_cast<const float *>(W->ptr), W->ld,
-                              nullptr, mfma, static_cast<float *>(dH->ptr), dH->ld, hmask, ldhm, &ws, st);
+                              nullptr, mfma, static_cast<float *>(dH->ptr), dH->ld, hmask, ldhm, nullptr, &ws, st);
     return rc;
 }
 
@@ -500,7 +503,7 @@ int sgnn_gemm_tail_fwd(sgnn_ctx *ctx, const sgnn_mat *T, const sgnn_mat *W, cons
     // shapes outside the fused kernel: the product, then the tail
     ws_alloc ws(ctx);
     rc = sgnn_launch_gemm(ctx, 0, 0, M, N, K, static_cast<const float *>(T->ptr), T->ld, nullptr, static_cast<const float *>(W->ptr),
-                          W->ld, nullptr, flags & SGNN_BF16_MFMA, static_cast<float *>(Z->ptr), Z->ld, nullptr, 0, &ws, st);
+                          W->ld, nullptr, flags & SGNN_BF16_MFMA, static_cast<float *>(Z->ptr), Z->ld, nullptr, 0, nullptr, &ws, st);
     if (rc) return rc;
     return sgnn_launch_tail_fwd(ctx, M, N, static_cast<const float *>(Z->ptr), Z->ld, gamma, eps, Rp, ldr, drop_q, drop_seed, layer,
                                 step, static_cast<float *>(Y->ptr), Y->ld, inv_rms, st);

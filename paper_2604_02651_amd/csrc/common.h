@@ -111,7 +111,8 @@ int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st);   /
 // result; K x M operand used transposed: reduction index)
 int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A,
                      int64_t lda, const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias,
-                     int flags, float *C, int64_t ldc, const float *mask, int64_t ldm, ws_alloc *ws, hipStream_t st);
+                     int flags, float *C, int64_t ldc, const float *mask, int64_t ldm, float *b_colsum, ws_alloc *ws,
+                     hipStream_t st);
 int sgnn_launch_gemm_tail(sgnn_ctx *ctx, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *W,
                           int64_t ldw, const float *gamma, float eps, const float *R, int64_t ldr, float q, uint64_t seed,
                           uint32_t layer, uint64_t step, float *Z, int64_t ldz, float *Y, int64_t ldy, float *inv_rms,

@@ -47,6 +47,7 @@ struct gemm_args {
     int64_t k_per_split;      // reduction range of one blockIdx.z (a multiple of BK); K when unsplit
     float *partial;           // split-K: [splits][M][N] partial products, else NULL
     uint32_t mtiles, ntiles, splits;   // the tile grid, walked by tile_of_block()
+    float *colsum;            // optional (A^T B products): column sums of B; [splits][N] partial sums when split
 };
 
 // Tile of a workgroup.  The grid is one-dimensional and the hardware hands consecutive workgroup
@@ -509,9 +510,19 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
         fetch_fast<BM, BK, A_RC>(ra, a.A, a.lda, m0, a.M, kbeg + (int64_t)s * BK, kend, a.K, a.a_row_index);
         fetch_fast<BN, BK, B_RC>(rb, a.B, a.ldb, n0, a.N, kbeg + (int64_t)s * BK, kend, a.K);
     };
+    // column sums of B (the bias gradient next to dW = T^T dZ): every thread fetches the same four columns
+    // of B in every slice, so it adds its chunks up as they pass; only the first row block of tiles does it
+    f32x4 cs = {0.f, 0.f, 0.f, 0.f};
+    const bool do_cs = TA && !TB && a.colsum && tb_.bx == 0;
     auto stage = [&](int s) {
         mask_fast<BM, BK, A_RC>(ra, kbeg + (int64_t)s * BK, kend);
         mask_fast<BN, BK, B_RC>(rb, kbeg + (int64_t)s * BK, kend);
+        if constexpr (TA && !TB) {
+            if (do_cs) {
+#pragma unroll
+                for (int v = 0; v < gB::NV; ++v) cs += rb[v];
+            }
+        }
         store_operand<BM, BK, A_RC, A16>(ldsA[s & 1], ra);
         store_operand<BN, BK, B_RC, B16>(ldsB[s & 1], rb);
     };
@@ -532,6 +543,24 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
             if (it + 2 < nslices) fetch(it + 2);
         }
         __syncthreads();
+    }
+
+    if constexpr (TA && !TB) {
+        if (do_cs) {   // the loop ended with a barrier: the staging buffers are free
+            static_assert(gB::TOTAL % 256 == 0 && 256 % gB::CHUNKS_PER_LINE == 0, "a thread keeps its columns in every slice");
+            constexpr int CPL = gB::CHUNKS_PER_LINE, G = 256 / CPL;
+            float *red = reinterpret_cast<float *>(ldsA[0]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) red[threadIdx.x * 4 + e] = cs[e];
+            __syncthreads();
+            if (threadIdx.x < BN) {
+                const int ch = threadIdx.x >> 2, e = threadIdx.x & 3;
+                float t = 0.f;
+                for (int q = 0; q < G; ++q) t += red[(ch + CPL * q) * 4 + e];
+                const int64_t col = n0 + threadIdx.x;
+                if (col < a.N) a.colsum[(a.partial ? (int64_t)tb_.bz * a.N : 0) + col] = t;
+            }
+        }
     }
 
     float *Cout = a.partial ? a.partial + (int64_t)tb_.bz * a.M * a.N : a.C;
@@ -1115,10 +1144,29 @@ int launch_skinny(sgnn_ctx *ctx, const gemm_args &a, int tb, hipStream_t st)
 
 // Sum of the split-K partial products in a fixed order (bit-reproducible).
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t MN,
-                                                            int64_t N, float *__restrict__ C, int64_t ldc)
+                                                            int64_t N, float *__restrict__ C, int64_t ldc,
+                                                            const float *__restrict__ cs_partial, float *__restrict__ cs_out)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= MN) return;
+    if (i >= MN) {
+        // the threads behind the matrix add up the column sums of B, split by split
+        const int64_t col = i - MN;
+        if (cs_partial && col < N) {
+            // eight loads in flight, the same fixed order of additions every time
+            float t = 0.f;
+            int z = 0;
+            for (; z + 8 <= splits; z += 8) {
+                float x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = cs_partial[(int64_t)(z + u) * N + col];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t += x[u];
+            }
+            for (; z < splits; ++z) t += cs_partial[(int64_t)z * N + col];
+            cs_out[col] = t;
+        }
+        return;
+    }
     // four interleaved chains, combined in a fixed order
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
     int z = 0;
@@ -1184,14 +1232,15 @@ int launch_cfg(sgnn_ctx *ctx, int ta, int tb, int bf16, gemm_args a, int splits,
 
 } // namespace
 
-size_t sgnn_gemm_ws_bytes(uint32_t d_max) { return (size_t)256 * d_max * d_max * 4 + 256; }
+size_t sgnn_gemm_ws_bytes(uint32_t d_max) { return (size_t)256 * d_max * d_max * 4 + (size_t)256 * d_max * 4 + 512; }
 
 int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
                      const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias, int flags, float *C,
-                     int64_t ldc, const float *mask, int64_t ldm, ws_alloc *ws, hipStream_t st)
+                     int64_t ldc, const float *mask, int64_t ldm, float *b_colsum, ws_alloc *ws, hipStream_t st)
 {
     gemm_args a;
     a.mask = mask; a.ldm = ldm;
+    a.colsum = nullptr;
     a.a_row_index = a_row_index;
     a.M = M; a.N = N; a.K = K;
     a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.bias = bias; a.C = C; a.ldc = ldc;
@@ -1233,6 +1282,21 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
                 return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gemm: scratch too small for the split reduction: call sgnn_ctx_reserve");
         } else splits = 1;
     }
+    // column sums of B next to A^T B: inside the tile kernel when it is the chunked (fast) one, else a pass of its own
+    float *cs_partial = nullptr;
+    bool cs_fused = false;
+    if (b_colsum) {
+        if (!ta || tb) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: column sums of B go with A^T B only");
+        cs_fused = !direct && a.alignedA && a.alignedB && M % 4 == 0 && N % 4 == 0 && M >= 4 && N >= 4 && K >= 1;
+        if (cs_fused) {
+            if (splits > 1) {
+                cs_partial = ws->get<float>((size_t)splits * N);
+                if (!ws->ok)
+                    return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gemm: scratch too small for the split reduction: call sgnn_ctx_reserve");
+                a.colsum = cs_partial;
+            } else a.colsum = b_colsum;
+        }
+    }
     int rc;
     if (direct) rc = launch_direct(ctx, ta, tb, a, splits, st);
     else if (bn == 128) rc = launch_cfg<128, 128, 64, 64>(ctx, ta, tb, bf16, a, splits, st);
@@ -1240,9 +1304,11 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     else rc = launch_cfg<256, 32, 64, 32>(ctx, ta, tb, bf16, a, splits, st);
     if (rc) return rc;
     if (splits > 1) {
-        SGNN_LAUNCH(ctx, st, "splitk_reduce_kernel", SGNN_TAG, splitk_reduce_kernel, dim3(cdiv(M * N, 256)), dim3(256), 0, st, a.partial, splits, M * N, N, C,
-                           ldc);
+        SGNN_LAUNCH(ctx, st, "splitk_reduce_kernel", SGNN_TAG, splitk_reduce_kernel, dim3(cdiv(M * N + (cs_partial ? N : 0), 256)),
+                    dim3(256), 0, st, a.partial, splits, M * N, N, C, ldc, cs_partial, b_colsum);
     }
+    if (b_colsum && !cs_fused)
+        return sgnn_launch_relu_bwd_bias(ctx, nullptr, 0, B, ldb, 0, K, N, nullptr, 0, b_colsum, ws, st);
     return SGNN_OK;
 }
 
@@ -1264,7 +1330,7 @@ int sgnn_launch_gemm_tail(sgnn_ctx *ctx, int64_t M, int64_t N, int64_t K, const 
     a.relu = 0; a.mask = nullptr; a.ldm = 0;
     a.alignedA = 1;
     a.alignedB = ((reinterpret_cast<uintptr_t>(W) & 15) == 0 && ldw % 4 == 0) ? 1 : 0;
-    a.k_per_split = K; a.partial = nullptr; a.mtiles = a.ntiles = a.splits = 0;
+    a.k_per_split = K; a.partial = nullptr; a.mtiles = a.ntiles = a.splits = 0; a.colsum = nullptr;
     skinny_tail tl;
     tl.gamma = gamma; tl.eps = eps; tl.R = R; tl.ldr = ldr; tl.Y = Y; tl.ldy = ldy; tl.inv_rms = inv_rms;
     tl.thr = (uint32_t)floor((double)q * 4294967296.0);

@@ -116,18 +116,18 @@ class GcnStep:
                     saved, ridx = (self.X, self.S) if self.fuse_slice else (self.X_S, None)
                 else:
                     saved = self.H[l - 1]
-            dW = self.dW[l]
+            dW, db = self.dW[l], self.db[l]
             if side is not None and not self.xform_first[l] and (masked or not relu):
                 main = torch.cuda.current_stream()
                 ev = torch.cuda.Event()
                 ev.record(main)                      # dY is complete
                 side[0].wait_event(ev)
-                sg.sgnn_gemm(side[1], True, False, saved, dY, None, self.flags, dW, stream=side[0])
-                dW = None
+                sg.sgnn_gemm(side[1], True, False, saved, dY, None, self.flags, dW, stream=side[0], b_colsum=db)
+                dW = db = None
             # the ReLU backward of the layer below is fused into the product that writes dH
             fuse = self.fuse_relu_bwd and l > 0
             # the induced matrix of a symmetric graph is symmetric: it is its own transpose
-            sg.sgnn_gcn_bwd(self.ctx, self.A, saved, W, self.H[l], dY, flags, self.dH[l], dW, self.db[l],
+            sg.sgnn_gcn_bwd(self.ctx, self.A, saved, W, self.H[l], dY, flags, self.dH[l], dW, db,
                             row_index=ridx, H_in=self.H[l - 1] if fuse else None)
             dY = self.dH[l]
             masked = fuse

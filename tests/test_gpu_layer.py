@@ -183,6 +183,25 @@ def test_gemm_fp32_wide_results(M, N, K):
     assert rel_err(C.cpu().numpy(), oracle.gemm(At.T.copy(), Bm)) < TOL_F32
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 32768), (128, 256, 5000), (100, 64, 300), (64, 32, 40000), (33, 47, 129)])
+def test_gemm_weight_gradient_with_column_sums(M, N, K, bf16):
+    # dW = T^T dZ with db = column sums of dZ from the same pass (split and unsplit, chunked and masked kernels)
+    ctx().reserve(1, 1, 40000, 256)
+    At = _rand((K, M), 28); Bm = _rand((K, N), 29)
+    flags = sg.SGNN_BF16_MFMA if bf16 else 0
+    rd = oracle.round_bf16 if bf16 else (lambda x: x.astype(np.float64))
+    C = torch.zeros((M, N), dtype=torch.float32, device=DEV); cs = torch.full((N,), 9.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), True, False, dev(At), dev(Bm), None, flags, C, b_colsum=cs)
+    assert rel_err(C.cpu().numpy(), oracle.gemm(rd(At).T.copy(), rd(Bm))) < (1e-4 if bf16 else TOL_F32)
+    assert rel_err(cs.cpu().numpy(), Bm.astype(np.float64).sum(axis=0)) < TOL_F32      # the sums are of the fp32 values
+    C2 = torch.zeros_like(C); cs2 = torch.zeros_like(cs)
+    sg.sgnn_gemm(ctx(), True, False, dev(At), dev(Bm), None, flags, C2, b_colsum=cs2)
+    assert torch.equal(C, C2) and torch.equal(cs, cs2)
+    with pytest.raises(sg.SgnnError):
+        sg.sgnn_gemm(ctx(), False, False, dev(At.T.copy()), dev(Bm), None, flags, C2, b_colsum=cs2)
+
+
 def test_gemm_fp32_weight_gradient_shape():
     # dW = T^T dZ of the headline workload: 256 x 256 result, reduction over 32768 rows, split and summed in a fixed order
     K, M, N = 32768, 256, 256
@@ -274,7 +293,9 @@ def test_layer_forward_backward(sub, d_in, d_out, relu, bf16, xform):
         dYm = dY * (Y_ref > 0)
         dH4 = torch.zeros_like(dH); dW4 = torch.zeros_like(dW); db4 = torch.zeros_like(db)
         sg.sgnn_gcn_bwd(ctx(), AT, saved, dev(W), None, dev(dYm.astype(np.float32)), flags | sg.SGNN_DY_MASKED, dH4, dW4, db4)
-        assert torch.equal(dH4, dH) and torch.equal(dW4, dW) and torch.equal(db4, db)
+        assert torch.equal(dH4, dH) and torch.equal(dW4, dW)
+        # the bias gradient now rides on the weight-gradient product: another (fixed) summation order
+        assert rel_err(db4.cpu().numpy(), db_ref) < TOL_F32
 
 
 def test_backward_uses_the_transpose():
