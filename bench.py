@@ -153,7 +153,7 @@ def main():
         if name == "gemm_kernel":
             p = tag.split()
             key = "gemm_kernel<%s,%s,%s>" % (p[1], p[0], p[3])
-        elif name in ("spmm_main_kernel", "spmm_fixup_kernel"):
+        elif name == "spmm_main_kernel":
             key = name + tag.split()[2]
         gq = groups.setdefault(key, {"calls": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
         gq["calls"] += calls

@@ -7,13 +7,16 @@
 // however short the rows are.  The 64 lanes cover the columns (VEC*CH of them per lane), so every
 // feature row is read with coalesced vector loads and every output row is written once.  Rows
 // much longer than the mean (power-law graphs have them) would leave one wavefront walking
-// alone long after the others are done, so a plan built once
-// per matrix cuts them into chunks of 256 entries:
-//   spmm_plan_kernel    (once per matrix) chunk descriptors of the long rows
-//   spmm_main_kernel    workgroups [0, n_chunk_wgs) take chunks (entries staged in LDS, partial row
-//                       per chunk), the others take rows; both kinds run side by side
-//   spmm_fixup_kernel   adds the partial rows of every long row up, in chunk order
-// No atomics touch floating-point data: results are bit-reproducible.
+// alone long after the others are done, so a plan built once per matrix cuts them into pieces of
+// 64 entries:
+//   spmm_plan_kernel    (once per matrix) piece descriptors of the long rows, one ticket per long row
+//   spmm_main_kernel    the first wavefronts take pieces (one partial row per piece), the others take
+//                       blocks of rows; both kinds run side by side.  A piece wavefront that has
+//                       stored its partial row draws a ticket of its row; the one that draws the last
+//                       ticket adds the partial rows of the row up, in piece order, and writes the row.
+// No atomics touch floating-point data and the order of every sum is fixed: results are
+// bit-reproducible.  Nothing waits on another wavefront.  Two products that use the same plan must
+// not run at the same time (they would share the tickets).
 #include <stdlib.h>
 
 #include <algorithm>
@@ -51,6 +54,22 @@ template <int VEC> __device__ __forceinline__ void vstore(float *p, const float 
     }
 }
 
+// Device-scope stores and loads (relaxed atomics, one word each): the store goes through to the
+// level of the memory system that all compute dies share and the load reads from there, so data
+// handed from one wavefront to another inside a kernel needs no write-back or invalidation of a
+// whole cache.
+template <int VEC> __device__ __forceinline__ void vstore_device(float *p, const float (&src)[VEC])
+{
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) __hip_atomic_store(p + i, src[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int VEC> __device__ __forceinline__ void vload_device(float (&dst)[VEC], const float *p)
+{
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) dst[i] = __hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 constexpr int SPMM_NT = 256;       // threads of a workgroup
 constexpr int SPMM_SHORT = 32;     // smallest length from which a row counts as long
 constexpr int SPMM_CHUNK = 64;     // entries per piece of a long row: what one wavefront fetches at once
@@ -61,6 +80,7 @@ struct spmm_plan_view {
     uint32_t *n_chunks;     // header word 0
     uint32_t *part_base;    // [rows], defined for long rows only
     uint2 *desc;            // [max_chunks] (row, chunk index inside the row)
+    uint32_t *ticket;       // [max_chunks], used at the first chunk number of a long row; zero between products
 };
 
 // Rows longer than this count as long: four times the mean row length of the matrix.  Evaluated
@@ -95,13 +115,14 @@ inline uint32_t spmm_max_chunks(uint32_t rows, uint64_t capacity)
     return (uint32_t)std::min<uint64_t>(n, 0x7fffffffu);
 }
 
-inline spmm_plan_view plan_view(void *plan, uint32_t rows)
+inline spmm_plan_view plan_view(void *plan, uint32_t rows, uint32_t max_chunks)
 {
     uint8_t *p = static_cast<uint8_t *>(plan);
     spmm_plan_view v;
     v.n_chunks = reinterpret_cast<uint32_t *>(p);
     v.part_base = reinterpret_cast<uint32_t *>(p + 256);
     v.desc = reinterpret_cast<uint2 *>(p + 256 + (((size_t)rows * 4 + 255) & ~size_t(255)));
+    v.ticket = reinterpret_cast<uint32_t *>(v.desc + max_chunks);
     return v;
 }
 
@@ -113,7 +134,7 @@ __global__ void spmm_plan_clear_kernel(uint32_t *n_chunks) { *n_chunks = 0; }
 __global__ __launch_bounds__(256) void spmm_plan_kernel(uint32_t rows, const int32_t *__restrict__ rowptr, uint64_t capacity,
                                                         uint32_t *__restrict__ n_chunks,
                                                         uint32_t max_chunks, uint32_t *__restrict__ part_base,
-                                                        uint2 *__restrict__ desc)
+                                                        uint2 *__restrict__ desc, uint32_t *__restrict__ ticket)
 {
     const uint32_t row = blockIdx.x * 256 + threadIdx.x;
     const uint64_t entries = min((uint64_t)rowptr[rows], capacity);
@@ -128,6 +149,7 @@ __global__ __launch_bounds__(256) void spmm_plan_kernel(uint32_t rows, const int
     const uint32_t nch = (uint32_t)((len + SPMM_CHUNK - 1) / SPMM_CHUNK);
     const uint32_t base = atomicAdd(n_chunks, nch);
     part_base[row] = base;
+    if (base < max_chunks) ticket[base] = 0;
     for (uint32_t c = 0; c < nch && base + c < max_chunks; ++c) desc[base + c] = make_uint2(row, c);
 }
 
@@ -316,6 +338,11 @@ template <int VEC, int CH> struct spmm_unroll { static constexpr int U = CH * VE
 
 // Wavefronts [0, n_piece_waves) take pieces of long rows (grid-stride over the pieces the plan
 // lists) and write one partial row per piece; the others take blocks of rows_per_wave rows.
+// A long row is finished by whichever of its piece wavefronts stores its partial row last: the
+// partial row is written with device-scope stores, the wavefront waits for them to complete and
+// draws a ticket of the row, and the holder of the last ticket reads all partial rows back with
+// device-scope loads and adds them up in piece order - the same sum whoever does it.  That wavefront also puts the ticket counter
+// back to zero for the next product with this plan.
 template <int VEC, int CH>
 __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const int32_t *__restrict__ rowptr,
                                                             const int32_t *__restrict__ colidx,
@@ -324,8 +351,8 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
                                                             const int32_t *__restrict__ row_index, int d,
                                                             unsigned n_piece_waves, const uint32_t *__restrict__ n_chunks,
                                                             uint32_t max_chunks, const uint2 *__restrict__ desc,
-                                                            float *__restrict__ part, float *__restrict__ out, int64_t ldo,
-                                                            spmm_epi ep, int rows_per_wave)
+                                                            uint32_t *__restrict__ ticket, float *part, float *__restrict__ out,
+                                                            int64_t ldo, spmm_epi ep, int rows_per_wave)
 {
     constexpr int U = spmm_unroll<VEC, CH>::U;
     const int lane = threadIdx.x & 63;
@@ -336,7 +363,8 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
         for (uint32_t pc = wave; pc < total; pc += n_piece_waves) {
             const uint2 rc = desc[pc];
             const int re = min(rowptr[rc.x + 1], cap);
-            const int c0 = min(rowptr[rc.x], re) + (int)rc.y * SPMM_CHUNK;
+            const int rs = min(rowptr[rc.x], re);
+            const int c0 = rs + (int)rc.y * SPMM_CHUNK;
             const int n = max(0, min(re - c0, SPMM_CHUNK));
             int32_t src = 0;
             float a = 0.f;
@@ -355,8 +383,67 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
 #pragma unroll
             for (int m = 0; m < CH; ++m) {
                 const int col = (m * 64 + lane) * VEC;
-                if (col < d) vstore<VEC>(o + col, acc[m]);
+                if (col < d) vstore_device<VEC>(o + col, acc[m]);
             }
+            // pieces of this row that exist (the list may have been cut short at max_chunks)
+            const uint32_t first = pc - rc.y;
+            const uint32_t nch = min((uint32_t)((re - rs + SPMM_CHUNK - 1) / SPMM_CHUNK), total - first);
+            // the partial row went out with device-scope stores: once they have completed it is visible
+            // to every wavefront of the device, and only then is the ticket drawn
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            uint32_t t = 0;
+            if (lane == 0) t = atomicAdd(&ticket[first], 1u);
+            t = (uint32_t)__builtin_amdgcn_readfirstlane((int)t);
+            if (t + 1 != nch) continue;
+            // last ticket: all partial rows of the row are complete; they are read with device-scope loads
+#pragma unroll
+            for (int m = 0; m < CH; ++m)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[m][i] = 0.f;
+            const float *pr = part + (int64_t)first * d;
+            uint32_t c = 0;
+            for (; c + 4 <= nch; c += 4) {
+                float v[4][CH][VEC];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int m = 0; m < CH; ++m) {
+                        const int col = (m * 64 + lane) * VEC;
+                        if (col < d) vload_device<VEC>(v[u][m], pr + (int64_t)(c + u) * d + col);
+                    }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int m = 0; m < CH; ++m) {
+                        const int col = (m * 64 + lane) * VEC;
+                        if (col < d) {
+#pragma unroll
+                            for (int i = 0; i < VEC; ++i) acc[m][i] += v[u][m][i];
+                        }
+                    }
+            }
+            for (; c < nch; ++c) {
+#pragma unroll
+                for (int m = 0; m < CH; ++m) {
+                    const int col = (m * 64 + lane) * VEC;
+                    if (col < d) {
+                        float v[VEC];
+                        vload_device<VEC>(v, pr + (int64_t)c * d + col);
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) acc[m][i] += v[i];
+                    }
+                }
+            }
+            float *orow = out + (int64_t)rc.x * ldo;
+#pragma unroll
+            for (int m = 0; m < CH; ++m) {
+                const int col = (m * 64 + lane) * VEC;
+                if (col < d) {
+                    spmm_epilogue<VEC>(acc[m], ep, (int64_t)rc.x, col);
+                    vstore<VEC>(orow + col, acc[m]);
+                }
+            }
+            if (lane == 0) ticket[first] = 0;
         }
         return;
     }
@@ -364,94 +451,26 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
                             n_chunks ? (int)n_chunks[2] : rows_per_wave, n_chunks ? (int)n_chunks[1] : 0x7fffffff, out, ldo, ep);
 }
 
-// Long rows: a group of lpr lanes per row adds its partial rows up in chunk order.
-template <int VEC, int CH>
-__global__ __launch_bounds__(256) void spmm_fixup_kernel(const int32_t *__restrict__ rowptr, uint64_t capacity, int d,
-                                                         const uint32_t *__restrict__ n_chunks, uint32_t max_chunks,
-                                                         const uint2 *__restrict__ desc, const float *__restrict__ part,
-                                                         float *__restrict__ out, int64_t ldo,
-                                                         spmm_epi ep, int lpr_log2)
-{
-    const int lpr = 1 << lpr_log2;
-    const int G = 256 >> lpr_log2;
-    const int q = threadIdx.x >> lpr_log2;
-    const int g = threadIdx.x & (lpr - 1);
-    const uint32_t total = min(*n_chunks, max_chunks);
-    for (uint32_t pc = blockIdx.x * (uint32_t)G + q; pc < total; pc += gridDim.x * (uint32_t)G) {
-        const uint2 rc = desc[pc];
-        if (rc.y != 0) continue;      // only the first chunk of a row starts a sum
-        const int64_t len = min((int64_t)rowptr[rc.x + 1], (int64_t)capacity) - (int64_t)rowptr[rc.x];
-        const uint32_t nch = min((uint32_t)((len + SPMM_CHUNK - 1) / SPMM_CHUNK), total - pc);
-        float acc[CH][VEC];
-#pragma unroll
-        for (int m = 0; m < CH; ++m)
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[m][i] = 0.f;
-        uint32_t c = 0;
-        for (; c + 4 <= nch; c += 4) {
-            float v[4][CH][VEC];
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int m = 0; m < CH; ++m) {
-                    const int col = (m * lpr + g) * VEC;
-                    if (col < d) vload<VEC>(v[t][m], part + (int64_t)(pc + c + t) * d + col);
-                }
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int m = 0; m < CH; ++m) {
-                    const int col = (m * lpr + g) * VEC;
-                    if (col < d) {
-#pragma unroll
-                        for (int i = 0; i < VEC; ++i) acc[m][i] += v[t][m][i];
-                    }
-                }
-        }
-        for (; c < nch; ++c) {
-#pragma unroll
-            for (int m = 0; m < CH; ++m) {
-                const int col = (m * lpr + g) * VEC;
-                if (col < d) {
-                    float v[VEC];
-                    vload<VEC>(v, part + (int64_t)(pc + c) * d + col);
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[m][i] += v[i];
-                }
-            }
-        }
-        float *o = out + (int64_t)rc.x * ldo;
-#pragma unroll
-        for (int m = 0; m < CH; ++m) {
-            const int col = (m * lpr + g) * VEC;
-            if (col < d) {
-                spmm_epilogue<VEC>(acc[m], ep, (int64_t)rc.x, col);
-                vstore<VEC>(o + col, acc[m]);
-            }
-        }
-    }
-}
-
 int build_plan(sgnn_ctx *ctx, const sgnn_csr *A, void *plan, hipStream_t st)
 {
-    const spmm_plan_view pv = plan_view(plan, A->rows);
     const uint32_t max_chunks = spmm_max_chunks(A->rows, A->capacity);
+    const spmm_plan_view pv = plan_view(plan, A->rows, max_chunks);
     SGNN_LAUNCH(ctx, st, "spmm_plan_clear_kernel", SGNN_TAG, spmm_plan_clear_kernel, dim3(1), dim3(1), 0, st, pv.n_chunks);
     SGNN_LAUNCH(ctx, st, "spmm_plan_kernel", SGNN_TAG, spmm_plan_kernel, dim3(cdiv(A->rows, 256)), dim3(256), 0, st, A->rows,
-                A->rowptr, A->capacity, pv.n_chunks, max_chunks, pv.part_base, pv.desc);
+                A->rowptr, A->capacity, pv.n_chunks, max_chunks, pv.part_base, pv.desc, pv.ticket);
     return SGNN_OK;
 }
 
 template <int VEC, int CH>
 int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int d, float *out,
-              int64_t ldo, const spmm_epi &ep, int lpr_log2, ws_alloc *ws, hipStream_t st)
+              int64_t ldo, const spmm_epi &ep, ws_alloc *ws, hipStream_t st)
 {
     const int rows_per_wave = spmm_rows_per_wave(A->rows, A->capacity);   // lower bound of the plan's figure
     const unsigned rows_per_block = (unsigned)(SPMM_NT / 64) * (unsigned)rows_per_wave;
     char tag[56];
     snprintf(tag, sizeof(tag), "%ux%u d=%d <%d,%d>", A->rows, A->cols, d, VEC, CH);
     const bool may_have_long = A->capacity > (uint64_t)SPMM_SHORT;
-    spmm_plan_view pv = {nullptr, nullptr, nullptr};
+    spmm_plan_view pv = {nullptr, nullptr, nullptr, nullptr};
     float *part = nullptr;
     uint32_t max_chunks = 0;
     unsigned n_piece_waves = 0;
@@ -466,7 +485,7 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, con
             int rc = build_plan(ctx, A, plan, st);
             if (rc) return rc;
         }
-        pv = plan_view(plan, A->rows);
+        pv = plan_view(plan, A->rows, max_chunks);
         part = ws->get<float>((size_t)max_chunks * d);
         if (!ws->ok)
             return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_spmm: scratch too small (%zu bytes needed): call sgnn_ctx_reserve",
@@ -475,13 +494,7 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, con
     }
     SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH>), dim3(n_piece_waves / (SPMM_NT / 64) + cdiv(A->rows, rows_per_block)),
                 dim3(SPMM_NT), 0, st, A->rows, A->rowptr, A->colidx, A->val, A->capacity, X, ldx, row_index, d,
-                n_piece_waves, pv.n_chunks, max_chunks, pv.desc, part, out, ldo, ep, rows_per_wave);
-    if (may_have_long) {
-        const unsigned groups = 256u >> lpr_log2;
-        SGNN_LAUNCH(ctx, st, "spmm_fixup_kernel", tag, (spmm_fixup_kernel<VEC, CH>),
-                    dim3(std::min<unsigned>(cdiv(max_chunks, groups), 1024)), dim3(256), 0, st, A->rowptr, A->capacity, d,
-                    pv.n_chunks, max_chunks, pv.desc, part, out, ldo, ep, lpr_log2);
-    }
+                n_piece_waves, pv.n_chunks, max_chunks, pv.desc, pv.ticket, part, out, ldo, ep, rows_per_wave);
     return SGNN_OK;
 }
 
@@ -490,18 +503,16 @@ int launch_v(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, cons
              int64_t ldo, const spmm_epi &ep, ws_alloc *ws, hipStream_t st)
 {
     const int per = (d + VEC - 1) / VEC;   // lanes needed for one pass over the row
-    int lpr_log2 = 0;
-    while ((1 << lpr_log2) < per && lpr_log2 < 6) ++lpr_log2;
-    const int ch = (per + (1 << lpr_log2) - 1) >> lpr_log2;
+    const int ch = (per + 63) / 64;
     switch (ch) {
-    case 1: return launch_vc<VEC, 1>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
-    case 2: return launch_vc<VEC, 2>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
-    case 3: return launch_vc<VEC, 3>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
-    case 4: return launch_vc<VEC, 4>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
-    case 5: return launch_vc<VEC, 5>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
-    case 6: return launch_vc<VEC, 6>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
-    case 7: return launch_vc<VEC, 7>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
-    case 8: return launch_vc<VEC, 8>(ctx, A, X, ldx, row_index, d, out, ldo, ep, lpr_log2, ws, st);
+    case 1: return launch_vc<VEC, 1>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 2: return launch_vc<VEC, 2>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 3: return launch_vc<VEC, 3>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 4: return launch_vc<VEC, 4>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 5: return launch_vc<VEC, 5>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 6: return launch_vc<VEC, 6>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 7: return launch_vc<VEC, 7>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 8: return launch_vc<VEC, 8>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
     default: break;
     }
     return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_spmm: feature width %d is beyond %d columns", d, 64 * 8 * VEC);
@@ -513,12 +524,12 @@ size_t sgnn_spmm_ws_bytes(uint64_t max_entries, uint32_t B, uint32_t d_max)
 {
     // a plan built on the fly plus the partial rows, for the smallest long-row threshold
     const size_t max_chunks = (size_t)(max_entries / SPMM_SHORT + max_entries / SPMM_CHUNK + 2);
-    return max_chunks * ((size_t)d_max * sizeof(float) + 8) + (size_t)B * 4 + 4 * 256;
+    return max_chunks * ((size_t)d_max * sizeof(float) + 12) + (size_t)B * 4 + 5 * 256;
 }
 
 extern "C" uint64_t sgnn_csr_plan_bytes(uint32_t rows, uint64_t capacity)
 {
-    return 256 + (((uint64_t)rows * 4 + 255) & ~uint64_t(255)) + (uint64_t)spmm_max_chunks(rows, capacity) * 8 + 256;
+    return 256 + (((uint64_t)rows * 4 + 255) & ~uint64_t(255)) + (uint64_t)spmm_max_chunks(rows, capacity) * 12 + 512;
 }
 
 int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st)

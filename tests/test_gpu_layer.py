@@ -99,6 +99,32 @@ def test_spmm_rows_of_every_length_class(d):
     assert torch.equal(out, out3)
 
 
+@pytest.mark.parametrize("d", [32, 256])
+def test_spmm_many_long_rows_repeated(d):
+    # thousands of pieces of long rows in flight on all compute dies, their partial rows handed from
+    # wavefront to wavefront inside the kernel; the tickets of the plan are used again by every product
+    rng = np.random.default_rng(11)
+    rows, cols = 3000, 20000
+    lens = rng.integers(0, 6, rows)
+    long_rows = rng.permutation(rows)[:700]
+    lens[long_rows] = rng.integers(65, 1500, len(long_rows))
+    lists = [np.sort(rng.choice(cols, n, replace=False)).astype(np.int32) for n in lens]
+    rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    ci = np.concatenate(lists); v = rng.standard_normal(len(ci)).astype(np.float32)
+    ctx().reserve(cols, len(ci), rows, d, len(ci))
+    A = sg.Csr.from_arrays(rows, cols, rp, ci, v, DEV, with_plan=True)
+    sg.sgnn_csr_plan(ctx(), A)
+    X = dev(_rand((cols, d), 3))
+    first = torch.zeros((rows, d), dtype=torch.float32, device=DEV)
+    sg.sgnn_spmm(ctx(), A, X, first)
+    assert rel_err(first.cpu().numpy(), oracle.spmm(rp, ci, v, X.cpu().numpy().astype(np.float64))) < TOL_F32
+    out = torch.empty_like(first)
+    for _ in range(40):
+        out.fill_(-1.0)
+        sg.sgnn_spmm(ctx(), A, X, out)
+        assert torch.equal(out, first)
+
+
 def test_scratch_too_small_is_an_error():
     small = sg.Context(0)
     B, rp, ci, v = _sub_csr(500, 3000, 200, 1)
