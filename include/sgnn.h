@@ -348,13 +348,17 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_ma
  *   trans_a 0: A is M x K;  1: A is K x M (used as its transpose)
  *   trans_b 0: B is K x N;  1: B is N x K (used as its transpose)
  *   flags   SGNN_RELU, SGNN_BF16_MFMA;  bias fp32[N] or NULL
+ *   mask    optional M x N fp32 matrix (leading dimension ldm), read only: C is set to zero wherever
+ *           mask <= 0 - the ReLU backward of the layer below (Sec. III-C) applied to an input
+ *           gradient as it is written, with that layer's output as the mask.  NULL = none.
  *   b_colsum  optional, with trans_a = 1 and trans_b = 0 only: out fp32[N], the column sums of B over its
  *             K rows - the bias gradient next to the weight gradient T^T dZ (Sec. III-C), taken from
  *             the operand the product reads anyway.  NULL = not wanted.
  */
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
               const float *A, int64_t lda, const float *B, int64_t ldb, const float *bias,
-              int flags, float *C, int64_t ldc, float *b_colsum, sgnn_stream stream);
+              int flags, float *C, int64_t ldc, const float *mask, int64_t ldm, float *b_colsum,
+              sgnn_stream stream);
 
 /*
  * dst[0..n) = src[0..n) (fp32, 16-byte aligned, n a multiple of 4): a plain streaming copy of known

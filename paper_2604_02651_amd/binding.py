@@ -99,7 +99,7 @@ def lib():
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
-        L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp, vp]
+        L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp, i64, vp, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
                      "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_gemm_tail_fwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose", "sgnn_sigmoid_bce", "sgnn_colsum",
@@ -437,12 +437,17 @@ def sgnn_adam_step(ctx: Context, w: torch.Tensor, g: torch.Tensor, m: torch.Tens
 
 
 def sgnn_gemm(ctx: Context, trans_a: bool, trans_b: bool, A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor],
-              flags: int, Cm: torch.Tensor, stream=None, b_colsum: Optional[torch.Tensor] = None):
+              flags: int, Cm: torch.Tensor, stream=None, b_colsum: Optional[torch.Tensor] = None,
+              mask: Optional[torch.Tensor] = None):
+    """C = act(op(A) op(B) + bias), zero where mask <= 0 (mask: a matrix shaped like C); b_colsum: column sums of B."""
     M, N = Cm.shape
+    if mask is not None and tuple(mask.shape) != (M, N):
+        raise ValueError("mask must have the shape of C")
     K = A.shape[0] if trans_a else A.shape[1]
     ctx.check(lib().sgnn_gemm(ctx._h, int(trans_a), int(trans_b), M, N, K, _ptr(A, torch.float32, "A"), A.stride(0),
                               _ptr(B, torch.float32, "B"), B.stride(0), _ptr(bias, torch.float32, "bias"), flags,
-                              _ptr(Cm, torch.float32, "C"), Cm.stride(0), _ptr(b_colsum, torch.float32, "b_colsum"),
+                              _ptr(Cm, torch.float32, "C"), Cm.stride(0), _ptr(mask, torch.float32, "mask"),
+                              mask.stride(0) if mask is not None else 0, _ptr(b_colsum, torch.float32, "b_colsum"),
                               _stream(stream)))
 
 

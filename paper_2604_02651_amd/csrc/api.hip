@@ -327,18 +327,18 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_ma
 }
 
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
-              const float *B, int64_t ldb, const float *bias, int flags, float *C, int64_t ldc, float *b_colsum,
-              sgnn_stream stream)
+              const float *B, int64_t ldb, const float *bias, int flags, float *C, int64_t ldc, const float *mask,
+              int64_t ldm, float *b_colsum, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     if (!A || !B || !C || M < 0 || N < 0 || K < 0) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: bad argument");
-    if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N)
+    if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N || (mask && ldm < N))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: leading dimension too small");
     if (M == 0 || N == 0) return SGNN_OK;
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_gemm(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, nullptr, B, ldb, bias, flags, C, ldc, nullptr, 0, b_colsum, &ws,
+    return sgnn_launch_gemm(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, nullptr, B, ldb, bias, flags, C, ldc, mask, mask ? ldm : 0, b_colsum, &ws,
                             static_cast<hipStream_t>(stream));
 }
 

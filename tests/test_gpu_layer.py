@@ -176,6 +176,21 @@ def test_gemm_nt_and_tn(M, N, K, bf16):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("M,N,K", [(1000, 256, 32), (300, 172, 128), (5000, 256, 256), (77, 40, 8), (4100, 100, 47)])
+def test_gemm_masked_result(M, N, K, bf16):
+    # the ReLU backward of the layer below applied while the input gradient dP W^T is written
+    flags = sg.SGNN_BF16_MFMA if bf16 else 0
+    rd = oracle.round_bf16 if bf16 else (lambda x: x.astype(np.float64))
+    A = _rand((M, K), 14); Bt = _rand((N, K), 15)
+    mask = np.maximum(_rand((M, N + 3), 16), 0.0)          # about half the entries are zero, as after a ReLU
+    C = torch.full((M, N), 5.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), False, True, dev(A), dev(Bt), None, flags, C, mask=dev(mask)[:, :N])
+    ref = np.where(mask[:, :N] > 0, rd(A) @ rd(Bt).T, 0.0)
+    assert rel_err(C.cpu().numpy(), ref) < (1e-4 if bf16 else TOL_F32)
+    assert torch.all(C[dev(mask)[:, :N] <= 0] == 0)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
 def test_gemm_long_reduction_is_split_and_reproducible(bf16):
     # the weight-gradient shape: short result, reduction over tens of thousands of rows
     K, M, N = 40000, 100, 256
