@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Measurements of the parts of the method around the headline step, one JSON line each:
+
+  python -m paper_2604_02651_amd.bench_extras --what tail  [--config medium]
+      the fused layer tail (RMSNorm + ReLU + dropout + residual, Eqs. 7-10) forward and backward
+  python -m paper_2604_02651_amd.bench_extras --what eval  [--config large]
+      the full-graph evaluation forward: normalised adjacency of all N vertices (Eq. 3), every layer
+  python -m paper_2604_02651_amd.bench_extras --what shard [--config medium] [--grid 2]
+      one GPU's share of the distributed extraction (Algorithm 2): the shard of the mini-batch matrix
+      for one row range and one column range of a grid x grid partition, and its transpose
+
+Every figure is measured with HIP events recorded on the launch stream around each kernel; byte
+counts are the compulsory ones (each operand once).  The headline benchmark is bench.py.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+
+
+def _timed(ctx, fn, reps, warm=2):
+    """Per-kernel [(kernel, tag, launches, total_ms)] of `reps` calls of fn, after `warm` untimed ones."""
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    ctx.profile(True)
+    for _ in range(reps):
+        fn()
+    recs = ctx.profile_read()
+    ctx.profile(False)
+    return recs
+
+
+def _kernels(recs, reps):
+    return {"%s %s" % (n, t) if t else n: {"launches_per_call": c / reps, "avg_us": 1e3 * ms / c} for n, t, c, ms in recs}
+
+
+def bench_tail(cfg, args):
+    import torch
+    import paper_2604_02651_amd as sg
+    dev = "cuda:0"
+    Bn, d = cfg.B, cfg.hidden
+    ctx = sg.Context(0)
+    ctx.reserve(1, 1, 1024, 2048)
+    gen = torch.Generator(device=dev).manual_seed(1)
+    Z = torch.randn((Bn, d), device=dev, generator=gen)
+    R = torch.randn((Bn, d), device=dev, generator=gen)
+    gam = torch.rand(d, device=dev, generator=gen) + 0.5
+    dY = torch.randn((Bn, d), device=dev, generator=gen)
+    Y, dZ = torch.empty_like(Z), torch.empty_like(Z)
+    ir = torch.empty(Bn, device=dev)
+    dg, db = torch.empty(d, device=dev), torch.empty(d, device=dev)
+    q = 0.5
+
+    def fn():
+        sg.sgnn_tail_fwd(ctx, Z, gam, 1e-6, R, q, 1, 0, 0, Y, ir)
+        sg.sgnn_tail_bwd(ctx, Z, ir, gam, q, 1, 0, 0, dY, dZ, dg, db)
+    reps = 20
+    recs = _timed(ctx, fn, reps)
+    byt = 3.0 * Bn * d * 4          # forward: Z, R in, Y out; backward: Z, dY in, dZ out
+    ks = _kernels(recs, reps)
+    fwd = next(v for k, v in ks.items() if k.startswith("tail_fwd_kernel"))
+    bwd = next(v for k, v in ks.items() if k.startswith("tail_bwd_kernel"))
+    ctx.status()
+    return {"metric": "fused layer tail (RMSNorm+ReLU+dropout+residual), forward + backward", "unit": "GB/s",
+            "value": 2 * byt / ((fwd["avg_us"] + bwd["avg_us"]) * 1e-6) / 1e9, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "%s: %d x %d activations, dropout q = %.1f" % (cfg.name, Bn, d, q)},
+            "roofline": {"bound": "hbm", "kernel": "tail_fwd_kernel", "achieved": byt / (fwd["avg_us"] * 1e-6) / 1e9,
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": byt / (fwd["avg_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                         "avg_launch_us": fwd["avg_us"], "traffic": None,
+                         "tail_bwd_kernel": {"achieved": byt / (bwd["avg_us"] * 1e-6) / 1e9, "avg_launch_us": bwd["avg_us"]}},
+            "kernels": ks}
+
+
+def bench_eval(cfg, args):
+    import time
+    import torch
+    import paper_2604_02651_amd as sg
+    import synth_inputs as si
+    dev = "cuda:0"
+    g = si.config_graph(cfg, device=dev)
+    E = int(g.colidx.numel())
+    X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=dev)
+    weights = si.layer_weights(cfg, device=dev)
+    ctx = sg.Context(0)
+    dmax = max([cfg.d_in] + [W.shape[1] for W, _ in weights])
+    ctx.reserve(cfg.N, E, cfg.N, dmax, E)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    A = sg.sgnn_graph_normalized_csr(ctx, cfg.N, g.rowptr, g.colidx)
+    torch.cuda.synchronize()
+    build_ms = 1e3 * (time.perf_counter() - t0)
+    flags0 = sg.SGNN_BF16_MFMA if cfg.bf16_mfma else 0
+    bufs = [(torch.empty((cfg.N, W.shape[1]), dtype=torch.float32, device=dev),
+             torch.empty((cfg.N, W.shape[0]), dtype=torch.float32, device=dev)) for W, _ in weights]
+
+    def fn():
+        H = X
+        for l, (W, b) in enumerate(weights):
+            # a layer that narrows runs transform-first, as in the training step
+            fl = flags0 | (sg.SGNN_RELU if l < len(weights) - 1 else 0) | (sg.SGNN_XFORM_FIRST if W.shape[1] < W.shape[0] else 0)
+            sg.sgnn_gcn_fwd(ctx, A, H, W, b, fl, bufs[l][0], bufs[l][1])
+            H = bufs[l][0]
+    reps = 3
+    recs = _timed(ctx, fn, reps, warm=1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    wall_ms = 1e3 * (time.perf_counter() - t0) / reps
+    ks = _kernels(recs, reps)
+    sp_ms = sum(ms for n, t, c, ms in recs if n == "spmm_main_kernel") / reps
+    sp_bytes = sp_gather = 0.0
+    for n, t, c, ms in recs:
+        if n == "spmm_main_kernel":
+            d = int(t.split("d=")[1].split()[0])
+            sp_bytes += (c / reps) * (8.0 * E + 4.0 * (cfg.N + 1) + 2.0 * cfg.N * d * 4)
+            sp_gather += (c / reps) * (E * d * 4.0)
+    ctx.status()
+    return {"metric": "full-graph evaluation forward passes/s", "unit": "passes/s", "value": 1e3 / wall_ms, "ms_per_pass": wall_ms,
+            "dtype": "bf16" if cfg.bf16_mfma else "f32", "data": "synthetic",
+            "config": {"workload": "%s: R-MAT N=%d, E=%d stored entries, GCN %s over all vertices" %
+                                   (cfg.name, cfg.N, E, "-".join(map(str, cfg.dims))),
+                       "normalised_matrix_and_plan_ms": build_ms},
+            "roofline": {"bound": "hbm", "kernel": "spmm_main_kernel (all widths)", "achieved": sp_bytes / (sp_ms * 1e-3) / 1e9,
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": sp_bytes / (sp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                         "ms_per_pass": sp_ms, "traffic": None,
+                         "gather_GBps": sp_gather / (sp_ms * 1e-3) / 1e9},
+            "kernels": ks}
+
+
+def bench_shard(cfg, args):
+    import torch
+    import paper_2604_02651_amd as sg
+    import synth_inputs as si
+    dev = "cuda:0"
+    g = si.config_graph(cfg, device=dev)
+    E = int(g.colidx.numel())
+    G = args.grid
+    ctx = sg.Context(0)
+    cap = int(min(E, 4 * (E * (cfg.B / cfg.N) ** 2 + cfg.B) + 65536))
+    ctx.reserve(cfg.N, E, cfg.B, 8, cap)
+    W = (cfg.N + 63) // 64
+    S = torch.empty(cfg.B, dtype=torch.int32, device=dev)
+    bm = torch.empty(W, dtype=torch.int64, device=dev)
+    rk = torch.empty(W, dtype=torch.int32, device=dev)
+    sg.sgnn_sample_uniform(ctx, cfg.N, cfg.B, cfg.sampler_seed, 0, S, bm, rk)
+    full = sg.Csr(cfg.B, cfg.B, cap, dev)
+    nnz_full = sg.sgnn_induced_csr(ctx, cfg.N, g.rowptr, g.colidx, None, S, cfg.B, bm, rk, full, want_nnz=True)
+    # the shard in the middle of the grid: rows of block G//2, columns of block G//2 - 1 (off the diagonal, so
+    # the transpose is a different matrix)
+    cut = [cfg.N * i // G for i in range(G + 1)]
+    r0, r1 = cut[G // 2], cut[G // 2 + 1]
+    c0, c1 = cut[max(G // 2 - 1, 0)], cut[max(G // 2 - 1, 0) + 1]
+    A = sg.Csr(cfg.B, cfg.B, cap, dev)
+    AT = sg.Csr(cfg.B, cfg.B, cap, dev)
+    nnz = sg.sgnn_induced_csr_range(ctx, cfg.N, g.rowptr, g.colidx, None, S, cfg.B, bm, rk, r0, r1, c0, c1, A, want_nnz=True)
+    reps = 10
+    rec_full = _timed(ctx, lambda: sg.sgnn_induced_csr(ctx, cfg.N, g.rowptr, g.colidx, None, S, cfg.B, bm, rk, full), reps)
+    rec_sh = _timed(ctx, lambda: sg.sgnn_induced_csr_range(ctx, cfg.N, g.rowptr, g.colidx, None, S, cfg.B, bm, rk, r0, r1, c0, c1, A), reps)
+    rec_tr = _timed(ctx, lambda: sg.sgnn_csr_transpose(ctx, A, AT), reps)
+    us = lambda recs: 1e3 * sum(ms for _, _, _, ms in recs) / reps
+    ctx.status()
+    return {"metric": "shard of the mini-batch matrix + its transpose (one GPU's share of Algorithm 2)", "unit": "us",
+            "value": us(rec_sh) + us(rec_tr), "higher_is_better": False, "dtype": "int32 indices, f32 values", "data": "synthetic",
+            "config": {"workload": "%s: R-MAT N=%d, E=%d stored entries, |S|=%d, grid %d x %d, rows [%d,%d) x columns [%d,%d)" %
+                                   (cfg.name, cfg.N, E, cfg.B, G, G, r0, r1, c0, c1),
+                       "shard_entries": nnz, "whole_matrix_entries": nnz_full},
+            "shard_extraction_us": us(rec_sh), "transpose_us": us(rec_tr), "whole_matrix_extraction_us": us(rec_full),
+            "kernels": {"shard": _kernels(rec_sh, reps), "transpose": _kernels(rec_tr, reps), "whole": _kernels(rec_full, reps)}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--what", required=True, choices=["tail", "eval", "shard"])
+    ap.add_argument("--config", default=None, help="tiny | medium | large | dense (default: medium; eval: large)")
+    ap.add_argument("--grid", type=int, default=2, help="shard: the matrix is cut into grid x grid shards")
+    args = ap.parse_args()
+    import torch
+    import synth_inputs as si
+    if not torch.cuda.is_available():
+        print("bench_extras: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cfg = si.CONFIGS[args.config or ("large" if args.what == "eval" else "medium")]
+    out = {"tail": bench_tail, "eval": bench_eval, "shard": bench_shard}[args.what](cfg, args)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -213,8 +213,11 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
     shard_range rg, const uint64_t *__restrict__ P, const uint32_t *__restrict__ tile_total, const uint32_t *__restrict__ group_total,
     const uint64_t *__restrict__ n_tiles_p, double p, int write_val, int32_t *__restrict__ rowptr_S,
     int32_t *__restrict__ colidx_S, float *__restrict__ val_S, uint64_t capacity, uint32_t *__restrict__ nnz_dev,
-    uint32_t *__restrict__ status)
+    uint32_t *__restrict__ status, int empty_rows_here)
 {
+    // empty_rows_here: rows without any stored entry get their offset from the thread that holds the first
+    // entry of the next row, one after the other (fine for the odd isolated vertex); 0: a kernel of its own
+    // does it afterwards (a shard leaves every sampled row outside its row range empty)
     __shared__ tile_table tt;
     __shared__ uint32_t lds[IND_NT / 64];
     __shared__ uint32_t wcnt[IND_ITEMS][IND_NT / 64];
@@ -227,7 +230,8 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
             if (total > 0x7fffffffu) atomicOr(status, SGNN_ST_NNZ_OVERFLOW);
             rowptr_S[B] = (int32_t)total;
             // rows at the end that have no stored entry at all
-            for (int64_t r = (int64_t)B - 1; r >= 0 && P[r] == F; --r) rowptr_S[r] = (int32_t)total;
+            if (empty_rows_here)
+                for (int64_t r = (int64_t)B - 1; r >= 0 && P[r] == F; --r) rowptr_S[r] = (int32_t)total;
             if (nnz_dev) *nnz_dev = total;
         }
     }
@@ -288,8 +292,10 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
             if (first[k]) {
                 // everything before the first entry of row r belongs to earlier rows
                 rowptr_S[r] = (int32_t)pos;
-                const uint64_t Pr = P[r];
-                for (int64_t q = (int64_t)r - 1; q >= 0 && P[q] == Pr; --q) rowptr_S[q] = (int32_t)pos;
+                if (empty_rows_here) {
+                    const uint64_t Pr = P[r];
+                    for (int64_t q = (int64_t)r - 1; q >= 0 && P[q] == Pr; --q) rowptr_S[q] = (int32_t)pos;
+                }
             }
             if (((bal[k] >> lane) & 1ull) && pos < capacity) {
                 colidx_S[pos] = (int32_t)(rank[(uint32_t)u[k] >> 6] + __popcll(word[k] & ((1ull << (u[k] & 63)) - 1ull)));
@@ -309,6 +315,20 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
         }
         __syncthreads();   // wcnt and the row table are reused by the next tile
     }
+}
+
+// Offsets of the rows without any stored entry, one thread per row: such a row starts where the next
+// row that has stored entries starts (found by binary search in the flat offsets), or at the end.
+__global__ __launch_bounds__(256) void induced_empty_rows_kernel(const uint64_t *__restrict__ P, uint32_t B,
+                                                                 int32_t *rowptr_S)
+{
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= B) return;
+    const uint64_t Pi = P[i];
+    if (P[i + 1] != Pi) return;
+    // the last row whose flat offset is still Pi is the one that holds the entries (none does when Pi is the
+    // end of the flat range); its offset was written by the fill kernel and no thread of this kernel touches it
+    rowptr_S[i] = Pi == P[B] ? rowptr_S[B] : rowptr_S[find_row(P, i, B - 1, Pi)];
 }
 
 // norm_mode 1: a_ij = 1/sqrt(c_i c_j) with c = entry counts of the induced rows, off-diagonal / p.
@@ -363,10 +383,14 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
                     tile_total, n_tiles, group_total);
     double p = 1.0;
     if (rescale && B > 1) p = ((double)B - 1.0) / ((double)g->N - 1.0);
+    const bool whole_rows = rg.r0 <= 0 && rg.r1 >= (int64_t)g->N;
     SGNN_LAUNCH(ctx, st, "induced_fill_kernel", SGNN_TAG, induced_fill_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr,
                 g->colidx, norm_mode == 0 ? g->val : nullptr, S, B, bitmap, rank, rg, P, tile_total,
                 grouped ? group_total : nullptr, n_tiles, p, norm_mode == 0 ? 1 : 0, out->rowptr, out->colidx, out->val,
-                out->capacity, out->nnz_dev, ctx->status);
+                out->capacity, out->nnz_dev, ctx->status, whole_rows ? 1 : 0);
+    if (!whole_rows)
+        SGNN_LAUNCH(ctx, st, "induced_empty_rows_kernel", SGNN_TAG, induced_empty_rows_kernel, dim3(cdiv(B, 256)), dim3(256), 0,
+                    st, P, B, out->rowptr);
     if (norm_mode == 1)
         SGNN_LAUNCH(ctx, st, "induced_renorm_kernel", SGNN_TAG, induced_renorm_kernel, dim3(cdiv((uint64_t)B * 64, 256)),
                     dim3(256), 0, st, out->rowptr, out->colidx, out->val, B, out->capacity, p);

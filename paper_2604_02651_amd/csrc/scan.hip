@@ -10,31 +10,48 @@ constexpr int SCAN_ITEMS = 8;
 constexpr int SCAN_TILE = SCAN_NT * SCAN_ITEMS;   // 2048
 constexpr uint64_t SCAN_SINGLE_MAX = 65536;
 
-// One workgroup scans everything: 1024 threads, chunks of 1024*8 with a running carry.
+// One workgroup scans everything: 1024 threads, chunks of 1024*16 with a running carry; the loads of the
+// next chunk are issued before the current one is scanned.
 template <class OutT>
 __global__ __launch_bounds__(1024) void scan_single_kernel(const uint32_t *__restrict__ in, OutT *__restrict__ out,
                                                            const uint64_t *n_dev, uint64_t n_host)
 {
+    constexpr int PER = 16;
     __shared__ OutT lds[1024 / 64 + 1];
     const uint64_t n = n_dev ? *n_dev : n_host;
+    const bool vec = (reinterpret_cast<uintptr_t>(in) & 15) == 0;
+    auto fetch = [&](uint64_t base, uint32_t (&v)[PER]) {
+        const uint64_t i0 = base + (uint64_t)threadIdx.x * PER;
+        if (vec && i0 + PER <= n) {
+#pragma unroll
+            for (int k = 0; k < PER / 4; ++k) {
+                const uint4 q = *reinterpret_cast<const uint4 *>(in + i0 + 4 * k);
+                v[4 * k] = q.x; v[4 * k + 1] = q.y; v[4 * k + 2] = q.z; v[4 * k + 3] = q.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < PER; ++k) v[k] = (i0 + k < n) ? in[i0 + k] : 0u;
+        }
+    };
     OutT carry = 0;
-    for (uint64_t base = 0; base < n; base += 1024 * 8) {
-        const uint64_t i0 = base + (uint64_t)threadIdx.x * 8;
-        uint32_t v[8];
+    uint32_t v[PER], nxt[PER] = {};
+    fetch(0, v);
+    for (uint64_t base = 0; base < n; base += 1024 * PER) {
+        const uint64_t i0 = base + (uint64_t)threadIdx.x * PER;
+        if (base + 1024 * PER < n) fetch(base + 1024 * PER, nxt);
         OutT s = 0;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            v[k] = (i0 + k < n) ? in[i0 + k] : 0u;
-            s += v[k];
-        }
+        for (int k = 0; k < PER; ++k) s += v[k];
         OutT total;
         OutT ex = block_excl_scan<OutT, 1024>(s, &total, lds) + carry;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < PER; ++k) {
             if (i0 + k < n) out[i0 + k] = ex;
             ex += v[k];
         }
         carry += total;
+#pragma unroll
+        for (int k = 0; k < PER; ++k) v[k] = nxt[k];
     }
     if (threadIdx.x == 0) out[n] = carry;
 }

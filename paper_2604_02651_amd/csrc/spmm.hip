@@ -8,7 +8,7 @@
 // feature row is read with coalesced vector loads and every output row is written once.  Rows
 // much longer than the mean (power-law graphs have them) would leave one wavefront walking
 // alone long after the others are done, so a plan built once per matrix cuts them into pieces of
-// 64 entries:
+// 64 entries (longer pieces for hub rows, so that no row has more than 256 of them):
 //   spmm_plan_kernel    (once per matrix) piece descriptors of the long rows, one ticket per long row
 //   spmm_main_kernel    the first wavefronts take pieces (one partial row per piece), the others take
 //                       blocks of rows; both kinds run side by side.  A piece wavefront that has
@@ -57,22 +57,34 @@ template <int VEC> __device__ __forceinline__ void vstore(float *p, const float 
 // Device-scope stores and loads (relaxed atomics, one word each): the store goes through to the
 // level of the memory system that all compute dies share and the load reads from there, so data
 // handed from one wavefront to another inside a kernel needs no write-back or invalidation of a
-// whole cache.
+// whole cache.  p points at the lane's first word; the VEC words of a lane are 64 words apart, so
+// that every store or load instruction of the wavefront covers 256 contiguous bytes.
 template <int VEC> __device__ __forceinline__ void vstore_device(float *p, const float (&src)[VEC])
 {
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) __hip_atomic_store(p + i, src[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int i = 0; i < VEC; ++i) __hip_atomic_store(p + i * 64, src[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int VEC> __device__ __forceinline__ void vload_device(float (&dst)[VEC], const float *p)
 {
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) dst[i] = __hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int i = 0; i < VEC; ++i) dst[i] = __hip_atomic_load(p + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 constexpr int SPMM_NT = 256;       // threads of a workgroup
 constexpr int SPMM_SHORT = 32;     // smallest length from which a row counts as long
 constexpr int SPMM_CHUNK = 64;     // entries per piece of a long row: what one wavefront fetches at once
+constexpr int SPMM_MAX_PIECES = 256;   // pieces per row: longer rows get longer pieces
+
+// Entries per piece of a row with `len` entries: 64, doubled until the row has at most
+// SPMM_MAX_PIECES pieces, so that the wavefront that adds the partial rows of a hub row up has a
+// bounded number of them to read.
+__host__ __device__ inline int64_t spmm_piece_len(int64_t len)
+{
+    int64_t c = SPMM_CHUNK;
+    while (len > c * SPMM_MAX_PIECES) c *= 2;
+    return c;
+}
 constexpr unsigned SPMM_PIECE_WAVES = 2048;
 
 // Plan of a matrix (device memory): header, first chunk number per row, chunk descriptors.
@@ -146,7 +158,8 @@ __global__ __launch_bounds__(256) void spmm_plan_kernel(uint32_t rows, const int
     if (row >= rows) return;
     const int64_t len = min((int64_t)rowptr[row + 1], (int64_t)capacity) - min((int64_t)rowptr[row], (int64_t)capacity);
     if (len <= long_len) return;
-    const uint32_t nch = (uint32_t)((len + SPMM_CHUNK - 1) / SPMM_CHUNK);
+    const int64_t plen = spmm_piece_len(len);
+    const uint32_t nch = (uint32_t)((len + plen - 1) / plen);
     const uint32_t base = atomicAdd(n_chunks, nch);
     part_base[row] = base;
     if (base < max_chunks) ticket[base] = 0;
@@ -360,91 +373,119 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
     const int32_t cap = (int32_t)min(capacity, (uint64_t)0x7fffffff);
     if (wave < n_piece_waves) {
         const uint32_t total = min(*n_chunks, max_chunks);
-        for (uint32_t pc = wave; pc < total; pc += n_piece_waves) {
-            const uint2 rc = desc[pc];
-            const int re = min(rowptr[rc.x + 1], cap);
-            const int rs = min(rowptr[rc.x], re);
-            const int c0 = rs + (int)rc.y * SPMM_CHUNK;
-            const int n = max(0, min(re - c0, SPMM_CHUNK));
-            int32_t src = 0;
-            float a = 0.f;
-            if (lane < n) {
-                const int32_t c = colidx[c0 + lane];
-                a = val[c0 + lane];
-                src = row_index ? row_index[c] : c;
-            }
-            float acc[CH][VEC];
-#pragma unroll
-            for (int m = 0; m < CH; ++m)
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[m][i] = 0.f;
-            spmm_wave_entries<VEC, CH, U>(acc, src, a, n, X, ldx, d, lane, [](int) { return true; });
-            float *o = part + (int64_t)pc * d;
-#pragma unroll
-            for (int m = 0; m < CH; ++m) {
-                const int col = (m * 64 + lane) * VEC;
-                if (col < d) vstore_device<VEC>(o + col, acc[m]);
-            }
-            // pieces of this row that exist (the list may have been cut short at max_chunks)
-            const uint32_t first = pc - rc.y;
-            const uint32_t nch = min((uint32_t)((re - rs + SPMM_CHUNK - 1) / SPMM_CHUNK), total - first);
-            // the partial row went out with device-scope stores: once they have completed it is visible
-            // to every wavefront of the device, and only then is the ticket drawn
+        constexpr int PSTRIDE = CH * VEC * 64;
+        // The partial row of a piece goes out with device-scope stores; once they have completed it is
+        // visible to every wavefront of the device, and only then may the ticket be drawn.  Neither wait
+        // is taken on the spot: the stores of piece k are waited for, and its ticket drawn, after piece
+        // k+1 has been summed, and the number drawn is looked at after piece k+2 (the gathers of the
+        // pieces in between hide both latencies).  `owed`: stored, ticket not drawn; `drawn`: ticket
+        // requested, number not looked at yet.
+        uint32_t owed_first = 0, owed_nch = 0, owed_row = 0;
+        uint32_t drawn_first = 0, drawn_nch = 0, drawn_row = 0, drawn_t = 0;
+        bool owed = false, drawn = false;
+        auto draw_ticket = [&]() {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            uint32_t t = 0;
-            if (lane == 0) t = atomicAdd(&ticket[first], 1u);
-            t = (uint32_t)__builtin_amdgcn_readfirstlane((int)t);
-            if (t + 1 != nch) continue;
+            drawn_t = 0;
+            if (lane == 0) drawn_t = atomicAdd(&ticket[owed_first], 1u);
+            drawn_first = owed_first; drawn_nch = owed_nch; drawn_row = owed_row;
+            drawn = true; owed = false;
+        };
+        auto finish_row = [&]() {
+            drawn = false;
+            const uint32_t t = (uint32_t)__builtin_amdgcn_readfirstlane((int)drawn_t);
+            if (t + 1 != drawn_nch) return;
             // last ticket: all partial rows of the row are complete; they are read with device-scope loads
+            float sum[CH][VEC];
 #pragma unroll
             for (int m = 0; m < CH; ++m)
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[m][i] = 0.f;
-            const float *pr = part + (int64_t)first * d;
+                for (int i = 0; i < VEC; ++i) sum[m][i] = 0.f;
+            const float *pr = part + (int64_t)drawn_first * PSTRIDE + lane;
             uint32_t c = 0;
-            for (; c + 4 <= nch; c += 4) {
-                float v[4][CH][VEC];
+            for (; c + U <= drawn_nch; c += U) {
+                float v[U][CH][VEC];
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int m = 0; m < CH; ++m) {
                         const int col = (m * 64 + lane) * VEC;
-                        if (col < d) vload_device<VEC>(v[u][m], pr + (int64_t)(c + u) * d + col);
+                        if (col < d) vload_device<VEC>(v[u][m], pr + (int64_t)(c + u) * PSTRIDE + m * VEC * 64);
                     }
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int m = 0; m < CH; ++m) {
                         const int col = (m * 64 + lane) * VEC;
                         if (col < d) {
 #pragma unroll
-                            for (int i = 0; i < VEC; ++i) acc[m][i] += v[u][m][i];
+                            for (int i = 0; i < VEC; ++i) sum[m][i] += v[u][m][i];
                         }
                     }
             }
-            for (; c < nch; ++c) {
+            for (; c < drawn_nch; ++c) {
 #pragma unroll
                 for (int m = 0; m < CH; ++m) {
                     const int col = (m * 64 + lane) * VEC;
                     if (col < d) {
                         float v[VEC];
-                        vload_device<VEC>(v, pr + (int64_t)c * d + col);
+                        vload_device<VEC>(v, pr + (int64_t)c * PSTRIDE + m * VEC * 64);
 #pragma unroll
-                        for (int i = 0; i < VEC; ++i) acc[m][i] += v[i];
+                        for (int i = 0; i < VEC; ++i) sum[m][i] += v[i];
                     }
                 }
             }
-            float *orow = out + (int64_t)rc.x * ldo;
+            float *orow = out + (int64_t)drawn_row * ldo;
 #pragma unroll
             for (int m = 0; m < CH; ++m) {
                 const int col = (m * 64 + lane) * VEC;
                 if (col < d) {
-                    spmm_epilogue<VEC>(acc[m], ep, (int64_t)rc.x, col);
-                    vstore<VEC>(orow + col, acc[m]);
+                    spmm_epilogue<VEC>(sum[m], ep, (int64_t)drawn_row, col);
+                    vstore<VEC>(orow + col, sum[m]);
                 }
             }
-            if (lane == 0) ticket[first] = 0;
+            if (lane == 0) ticket[drawn_first] = 0;
+        };
+        for (uint32_t pc = wave; pc < total; pc += n_piece_waves) {
+            const uint2 rc = desc[pc];
+            const int re = min(rowptr[rc.x + 1], cap);
+            const int rs = min(rowptr[rc.x], re);
+            const int plen = (int)spmm_piece_len(re - rs);
+            const int c0 = rs + (int)rc.y * plen;
+            const int c1 = min(re, c0 + plen);
+            float acc[CH][VEC];
+#pragma unroll
+            for (int m = 0; m < CH; ++m)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[m][i] = 0.f;
+            for (int cb = c0; cb < c1; cb += SPMM_CHUNK) {      // 64 entries at a time
+                const int n = min(c1 - cb, SPMM_CHUNK);
+                int32_t src = 0;
+                float a = 0.f;
+                if (lane < n) {
+                    const int32_t c = colidx[cb + lane];
+                    a = val[cb + lane];
+                    src = row_index ? row_index[c] : c;
+                }
+                spmm_wave_entries<VEC, CH, U>(acc, src, a, n, X, ldx, d, lane, [](int) { return true; });
+            }
+            if (drawn) finish_row();
+            if (owed) draw_ticket();
+            // a partial row holds the words of the wavefront's registers in register order: word (m, i)
+            // of lane l at (m * VEC + i) * 64 + l
+            float *o = part + (int64_t)pc * PSTRIDE + lane;
+#pragma unroll
+            for (int m = 0; m < CH; ++m) {
+                const int col = (m * 64 + lane) * VEC;
+                if (col < d) vstore_device<VEC>(o + m * VEC * 64, acc[m]);
+            }
+            // pieces of this row that exist (the list may have been cut short at max_chunks)
+            owed_first = pc - rc.y;
+            owed_nch = min((uint32_t)((re - rs + plen - 1) / plen), total - owed_first);
+            owed_row = rc.x;
+            owed = true;
         }
+        if (drawn) finish_row();
+        if (owed) { draw_ticket(); finish_row(); }
         return;
     }
     spmm_wave_rows<VEC, CH>(rows, rowptr, colidx, val, cap, X, ldx, row_index, d, wave - n_piece_waves,
@@ -486,11 +527,14 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, con
             if (rc) return rc;
         }
         pv = plan_view(plan, A->rows, max_chunks);
-        part = ws->get<float>((size_t)max_chunks * d);
+        part = ws->get<float>((size_t)max_chunks * (CH * VEC * 64));
         if (!ws->ok)
             return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_spmm: scratch too small (%zu bytes needed): call sgnn_ctx_reserve",
                              ws->off);
-        n_piece_waves = cdiv(std::min<unsigned>(max_chunks, SPMM_PIECE_WAVES), SPMM_NT / 64) * (SPMM_NT / 64);
+        // wavefronts that take pieces: 2048, more for matrices with many entries (about 32 pieces of 64 entries
+        // each if every entry sat in a long row); those that find no piece leave at once
+        const uint64_t want = std::min<uint64_t>(std::max<uint64_t>(A->capacity / 2048, SPMM_PIECE_WAVES), 65536);
+        n_piece_waves = cdiv(std::min<uint64_t>(max_chunks, want), SPMM_NT / 64) * (SPMM_NT / 64);
     }
     SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH>), dim3(n_piece_waves / (SPMM_NT / 64) + cdiv(A->rows, rows_per_block)),
                 dim3(SPMM_NT), 0, st, A->rows, A->rowptr, A->colidx, A->val, A->capacity, X, ldx, row_index, d,
@@ -524,7 +568,7 @@ size_t sgnn_spmm_ws_bytes(uint64_t max_entries, uint32_t B, uint32_t d_max)
 {
     // a plan built on the fly plus the partial rows, for the smallest long-row threshold
     const size_t max_chunks = (size_t)(max_entries / SPMM_SHORT + max_entries / SPMM_CHUNK + 2);
-    return max_chunks * ((size_t)d_max * sizeof(float) + 12) + (size_t)B * 4 + 5 * 256;
+    return max_chunks * (((size_t)d_max + 255) * sizeof(float) + 12) + (size_t)B * 4 + 5 * 256;
 }
 
 extern "C" uint64_t sgnn_csr_plan_bytes(uint32_t rows, uint64_t capacity)

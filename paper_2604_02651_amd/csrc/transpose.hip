@@ -10,10 +10,11 @@
 //   4. order    every row of the transpose is put in ascending column order by ranking: an entry goes
 //               to the position equal to the number of smaller keys in its row.  Keys are unique
 //               (a CSR row holds a column once), so the result is the same whatever step 3 did.
-// Ranking costs O(n^2) comparisons for a row of n entries; rows of a mini-batch are short and the
-// few long ones are spread over a whole workgroup each.
+// Ranking by comparison costs n^2 for a row of n entries, which is what the short rows of a
+// mini-batch get; the hub columns of a power-law graph are ranked through a bitmap instead.
 #include <algorithm>
 
+#include "block_prims.h"
 #include "common.h"
 
 namespace {
@@ -58,27 +59,115 @@ __global__ __launch_bounds__(256) void transpose_scatter_kernel(const int32_t *_
     }
 }
 
-// Rows of the transpose with up to `short_len` entries: a wavefront per row.  Longer rows: a workgroup per
-// row in a second launch of the same kernel (whole = 1).
-__global__ __launch_bounds__(256) void transpose_order_kernel(const uint32_t *__restrict__ rowptr_T, uint32_t cols,
+// Ordering pass: a workgroup takes 256 rows of the transpose.
+//   up to 16 entries      the row's own thread ranks them (n^2 comparisons, n tiny)
+//   up to 512 entries     the wavefront takes such rows of its 64 one after the other, a lane per entry
+//   longer (hub columns)  the workgroup takes them one after the other and ranks through a bitmap over
+//                         the source rows: the keys of a window of ORDER_WINDOW source rows set their bits,
+//                         a prefix sum over the popcounts of the bitmap words gives every key its rank
+//                         (entries in earlier windows + bits below it): O(n + rows / 32) work per row
+constexpr uint32_t ORDER_TINY = 16, ORDER_WAVE = 512;
+constexpr uint32_t ORDER_WINDOW = 131072;                 // source rows per bitmap window: 16 KB of bits
+
+__global__ __launch_bounds__(256) void transpose_order_kernel(const uint32_t *__restrict__ rowptr_T, uint32_t cols, uint32_t rows,
                                                               const int32_t *__restrict__ tmp_row,
-                                                              const float *__restrict__ tmp_val, uint32_t short_len,
-                                                              int whole, int32_t *__restrict__ colidx_T,
+                                                              const float *__restrict__ tmp_val, int32_t *__restrict__ colidx_T,
                                                               float *__restrict__ val_T)
 {
-    const uint32_t nthr = whole ? 256u : 64u;
-    const uint32_t t = whole ? threadIdx.x : (threadIdx.x & 63);
-    const uint32_t unit = whole ? blockIdx.x : blockIdx.x * 4 + (threadIdx.x >> 6);
-    const uint32_t nunits = whole ? gridDim.x : gridDim.x * 4;
-    for (uint32_t j = unit; j < cols; j += nunits) {
-        const uint32_t s = rowptr_T[j], n = rowptr_T[j + 1] - s;
-        if (whole ? n <= short_len : n > short_len) continue;
-        for (uint32_t k = t; k < n; k += nthr) {
-            const int32_t key = tmp_row[s + k];
+    __shared__ uint32_t bits[ORDER_WINDOW / 32];
+    __shared__ uint32_t pre[ORDER_WINDOW / 32];
+    __shared__ __attribute__((aligned(16))) int32_t wkeys[256 / 64][ORDER_WAVE];     // keys of the row a wavefront is ranking
+    __shared__ uint32_t red[256 / 64 + 1];
+    __shared__ uint32_t hub[256];
+    __shared__ uint32_t n_hub;
+    // rows are dealt out to the workgroups in turn: the hub columns of a power-law graph have neighbouring
+    // numbers and would otherwise all land in one workgroup
+    const uint32_t j = threadIdx.x * gridDim.x + blockIdx.x;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    uint32_t s = 0, n = 0;
+    if (j < cols) { s = rowptr_T[j]; n = rowptr_T[j + 1] - s; }
+    if (threadIdx.x == 0) n_hub = 0;
+    __syncthreads();
+    if (n <= ORDER_TINY) {
+        // all keys of the row in registers (the loads go out together), ranked by comparison
+        int32_t key[ORDER_TINY];
+        float vv[ORDER_TINY];
+#pragma unroll
+        for (uint32_t k = 0; k < ORDER_TINY; ++k) {
+            key[k] = 0x7fffffff; vv[k] = 0.f;
+            if (k < n) { key[k] = tmp_row[s + k]; vv[k] = tmp_val[s + k]; }
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < ORDER_TINY; ++k) {
+            if (k < n) {
+                uint32_t rank = 0;
+#pragma unroll
+                for (uint32_t q = 0; q < ORDER_TINY; ++q) rank += key[q] < key[k] ? 1u : 0u;    // unused slots hold the largest int
+                colidx_T[s + rank] = key[k];
+                val_T[s + rank] = vv[k];
+            }
+        }
+    } else if (n > ORDER_WAVE) hub[atomicAdd(&n_hub, 1u)] = threadIdx.x;     // any order: every hub row is done in full
+    uint64_t mid = __ballot(n > ORDER_TINY && n <= ORDER_WAVE);
+    while (mid) {
+        const int src = __builtin_amdgcn_readfirstlane(__builtin_ctzll(mid));
+        mid &= mid - 1;
+        const uint32_t ss = (uint32_t)__builtin_amdgcn_readlane((int)s, src), nn = (uint32_t)__builtin_amdgcn_readlane((int)n, src);
+        // the keys of the row go to the wavefront's LDS slot, padded to a multiple of four with the largest int
+        const uint32_t n4 = (nn + 3) & ~3u;
+        for (uint32_t k = lane; k < n4; k += 64) wkeys[wv][k] = k < nn ? tmp_row[ss + k] : 0x7fffffff;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (uint32_t k = lane; k < nn; k += 64) {
+            const int32_t key = wkeys[wv][k];
             uint32_t rank = 0;
-            for (uint32_t q = 0; q < n; ++q) rank += tmp_row[s + q] < key ? 1u : 0u;
-            colidx_T[s + rank] = key;
-            val_T[s + rank] = tmp_val[s + k];
+            for (uint32_t q = 0; q < n4; q += 4) {
+                const int4 kk = *reinterpret_cast<const int4 *>(&wkeys[wv][q]);
+                rank += (kk.x < key ? 1u : 0u) + (kk.y < key ? 1u : 0u) + (kk.z < key ? 1u : 0u) + (kk.w < key ? 1u : 0u);
+            }
+            colidx_T[ss + rank] = key;
+            val_T[ss + rank] = tmp_val[ss + k];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    __syncthreads();
+    const uint32_t nh = n_hub;
+    for (uint32_t h = 0; h < nh; ++h) {
+        const uint32_t jj = hub[h] * gridDim.x + blockIdx.x;
+        const uint32_t ss = rowptr_T[jj], nn = rowptr_T[jj + 1] - ss;
+        uint32_t before = 0;                                  // entries of the row in earlier windows
+        for (uint32_t w0 = 0; w0 < rows; w0 += ORDER_WINDOW) {
+            const uint32_t wn = min(ORDER_WINDOW, rows - w0), words = (wn + 31) / 32;
+            for (uint32_t i = threadIdx.x; i < words; i += 256) bits[i] = 0;
+            __syncthreads();
+            for (uint32_t k = threadIdx.x; k < nn; k += 256) {
+                const uint32_t key = (uint32_t)tmp_row[ss + k] - w0;
+                if (key < wn) atomicOr(&bits[key >> 5], 1u << (key & 31));
+            }
+            __syncthreads();
+            // exclusive prefix of the popcounts: thread t owns the words [t * per, (t + 1) * per)
+            const uint32_t per = (words + 255) / 256;
+            const uint32_t i0 = min(threadIdx.x * per, words), i1 = min(i0 + per, words);
+            uint32_t mine = 0;
+            for (uint32_t i = i0; i < i1; ++i) mine += __popc(bits[i]);
+            uint32_t total;
+            uint32_t ex = block_excl_scan<uint32_t, 256>(mine, &total, red);
+            for (uint32_t i = i0; i < i1; ++i) { pre[i] = ex; ex += __popc(bits[i]); }
+            __syncthreads();
+            for (uint32_t k = threadIdx.x; k < nn; k += 256) {
+                const int32_t key32 = tmp_row[ss + k];
+                const uint32_t key = (uint32_t)key32 - w0;
+                if (key < wn) {
+                    const uint32_t rank = before + pre[key >> 5] + __popc(bits[key >> 5] & ((1u << (key & 31)) - 1u));
+                    colidx_T[ss + rank] = key32;
+                    val_T[ss + rank] = tmp_val[ss + k];
+                }
+            }
+            before += total;
+            __syncthreads();
         }
     }
 }
@@ -118,12 +207,8 @@ int sgnn_launch_csr_transpose(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_csr *out, w
     const unsigned rowgrid = (unsigned)std::max<uint32_t>(1, std::min<uint32_t>(cdiv(rows, 4), 8192));
     SGNN_LAUNCH(ctx, st, "transpose_scatter_kernel", SGNN_TAG, transpose_scatter_kernel, dim3(rowgrid), dim3(256), 0, st, A->rowptr,
                 rows, A->colidx, A->val, A->capacity, cols, rowptr_T, cursor, tmp_row, tmp_val);
-    const uint32_t short_len = 256;
-    const unsigned colgrid = (unsigned)std::max<uint32_t>(1, std::min<uint32_t>(cdiv(cols, 4), 8192));
-    SGNN_LAUNCH(ctx, st, "transpose_order_kernel", SGNN_TAG, transpose_order_kernel, dim3(colgrid), dim3(256), 0, st, rowptr_T, cols,
-                tmp_row, tmp_val, short_len, 0, out->colidx, out->val);
-    SGNN_LAUNCH(ctx, st, "transpose_order_kernel", SGNN_TAG, transpose_order_kernel, dim3(std::min<uint32_t>(cols, 4096)), dim3(256),
-                0, st, rowptr_T, cols, tmp_row, tmp_val, short_len, 1, out->colidx, out->val);
+    SGNN_LAUNCH(ctx, st, "transpose_order_kernel", SGNN_TAG, transpose_order_kernel, dim3(cdiv(cols, 256)), dim3(256), 0, st, rowptr_T,
+                cols, rows, tmp_row, tmp_val, out->colidx, out->val);
     SGNN_LAUNCH(ctx, st, "transpose_finish_kernel", SGNN_TAG, transpose_finish_kernel, dim3(1), dim3(1), 0, st, rowptr_T, cols,
                 out->nnz_dev);
     return SGNN_OK;

@@ -99,6 +99,29 @@ def test_spmm_rows_of_every_length_class(d):
     assert torch.equal(out, out3)
 
 
+@pytest.mark.parametrize("d", [47, 256])
+def test_spmm_hub_rows_get_longer_pieces(d):
+    # rows beyond 256 pieces of 64 entries are cut into longer pieces: one row right at the limit, one
+    # just beyond it, one far beyond it
+    rng = np.random.default_rng(13)
+    rows, cols = 40, 70000
+    lens = rng.integers(0, 4, rows)
+    lens[[3, 10, 11, 39]] = [50000, 16385, 16384, 33000]
+    lists = [np.sort(rng.choice(cols, n, replace=False)).astype(np.int32) for n in lens]
+    rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    ci = np.concatenate(lists); v = rng.standard_normal(len(ci)).astype(np.float32)
+    ctx().reserve(cols, len(ci), rows, d, len(ci))
+    A = sg.Csr.from_arrays(rows, cols, rp, ci, v, DEV, with_plan=True)
+    sg.sgnn_csr_plan(ctx(), A)
+    X = _rand((cols, d), 3)
+    out = torch.full((rows, d), 7.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_spmm(ctx(), A, dev(X), out)
+    assert rel_err(out.cpu().numpy(), oracle.spmm(rp, ci, v, X.astype(np.float64))) < TOL_F32
+    out2 = torch.zeros_like(out)
+    sg.sgnn_spmm(ctx(), A, dev(X), out2)
+    assert torch.equal(out, out2)
+
+
 @pytest.mark.parametrize("d", [32, 256])
 def test_spmm_many_long_rows_repeated(d):
     # thousands of pieces of long rows in flight on all compute dies, their partial rows handed from

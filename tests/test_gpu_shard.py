@@ -106,3 +106,30 @@ def test_transpose_of_a_shard_and_of_a_directed_matrix(tiny_graph):
     assert np.array_equal(MT.val.cpu().numpy()[:len(cT)], vT)
     assert torch.equal(MT.colidx, MT2.colidx) and torch.equal(MT.val, MT2.val)
     ctx().status()
+
+
+def test_transpose_rows_of_every_length_class():
+    """Columns with a handful of entries (ranked by one thread), with a few hundred (by a wavefront) and
+    hub columns ranked through the bitmap over the source rows, here wider than one bitmap window."""
+    rng = np.random.default_rng(21)
+    rows, cols = 150000, 1500
+    per_row = rng.integers(0, 3, rows)
+    r_idx = np.repeat(np.arange(rows), per_row)
+    c_idx = rng.integers(20, cols, len(r_idx))
+    extra = []
+    for col, n in ((3, 17), (4, 300), (5, 512), (6, 513), (7, 6000), (8, 40000), (300, 2500)):
+        extra.append((np.sort(rng.choice(rows, n, replace=False)), np.full(n, col)))
+    r_idx = np.concatenate([r_idx] + [e[0] for e in extra]); c_idx = np.concatenate([c_idx] + [e[1] for e in extra])
+    key = np.unique(r_idx.astype(np.int64) * cols + c_idx)          # a row holds a column once, in ascending order
+    r_idx, c_idx = (key // cols).astype(np.int64), (key % cols).astype(np.int32)
+    rp = np.zeros(rows + 1, np.int32); np.add.at(rp, r_idx + 1, 1); rp = np.cumsum(rp).astype(np.int32)
+    v = rng.standard_normal(len(c_idx)).astype(np.float32)
+    ctx().reserve(rows, len(c_idx), max(rows, cols), 8, len(c_idx))
+    M = sg.Csr.from_arrays(rows, cols, rp, c_idx, v, DEV)
+    MT = sg.Csr(cols, rows, len(c_idx), DEV)
+    sg.sgnn_csr_transpose(ctx(), M, MT)
+    rT, cT, vT = oracle.csr_transpose(rows, cols, rp, c_idx, v)
+    assert np.array_equal(MT.rowptr.cpu().numpy(), rT)
+    assert np.array_equal(MT.colidx.cpu().numpy()[:len(cT)], cT)
+    assert np.array_equal(MT.val.cpu().numpy()[:len(cT)], vT)
+    ctx().status()
