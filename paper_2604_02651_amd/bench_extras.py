@@ -5,6 +5,9 @@
       the fused layer tail (RMSNorm + ReLU + dropout + residual, Eqs. 7-10) forward and backward
   python -m paper_2604_02651_amd.bench_extras --what eval  [--config large]
       the full-graph evaluation forward: normalised adjacency of all N vertices (Eq. 3), every layer
+  python -m paper_2604_02651_amd.bench_extras --what stages [--config large]
+      mini-batch construction stage by stage: sampler (Gkeys/s against the integer ALU), induced CSR
+      extraction and the feature slice (GB/s of compulsory traffic against HBM)
   python -m paper_2604_02651_amd.bench_extras --what shard [--config medium] [--grid 2]
       one GPU's share of the distributed extraction (Algorithm 2): the shard of the mini-batch matrix
       for one row range and one column range of a grid x grid partition, and its transpose
@@ -139,6 +142,60 @@ def bench_eval(cfg, args):
             "kernels": ks}
 
 
+def bench_stages(cfg, args):
+    import torch
+    import paper_2604_02651_amd as sg
+    import synth_inputs as si
+    dev = "cuda:0"
+    g = si.config_graph(cfg, device=dev)
+    E = int(g.colidx.numel())
+    X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=dev)
+    labels = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=dev)
+    ctx = sg.Context(0)
+    exp = cfg.B + (E - cfg.N) * (cfg.B / cfg.N) * ((cfg.B - 1) / max(cfg.N - 1, 1))
+    cap = int(min(E, 2 * exp + 16 * cfg.B + 65536))
+    ctx.reserve(cfg.N, E, cfg.B, cfg.d_in, cap)
+    W = (cfg.N + 63) // 64
+    S = torch.empty(cfg.B, dtype=torch.int32, device=dev)
+    bm = torch.empty(W, dtype=torch.int64, device=dev)
+    rk = torch.empty(W, dtype=torch.int32, device=dev)
+    A = sg.Csr(cfg.B, cfg.B, cap, dev)
+    X_S = torch.empty((cfg.B, cfg.d_in), dtype=torch.float32, device=dev)
+    y_S = torch.empty(cfg.B, dtype=torch.int32, device=dev)
+    reps = 8
+    steps = iter(range(10 ** 6))
+    rec_s = _timed(ctx, lambda: sg.sgnn_sample_uniform(ctx, cfg.N, cfg.B, cfg.sampler_seed, next(steps), S, bm, rk), reps)
+    sg.sgnn_sample_uniform(ctx, cfg.N, cfg.B, cfg.sampler_seed, 0, S, bm, rk)
+    nnz = sg.sgnn_induced_csr(ctx, cfg.N, g.rowptr, g.colidx, None, S, cfg.B, bm, rk, A, want_nnz=True)
+    Sl = S.long()
+    sumdeg = int((g.rowptr[Sl + 1] - g.rowptr[Sl]).sum().item())
+    rec_i = _timed(ctx, lambda: sg.sgnn_induced_csr(ctx, cfg.N, g.rowptr, g.colidx, None, S, cfg.B, bm, rk, A), reps)
+    rec_g = _timed(ctx, lambda: sg.sgnn_gather_rows(ctx, X, S, cfg.B, X_S, labels, y_S), reps)
+    us = lambda recs, pred=lambda n: True: 1e3 * sum(ms for n, _, _, ms in recs if pred(n)) / reps
+    t_s, t_g = us(rec_s), us(rec_g)
+    t_i = us(rec_i, lambda n: n.startswith("induced"))       # without the SpMM plan of the new matrix
+    t_plan = us(rec_i, lambda n: n.startswith("spmm_plan"))
+    # sampler: three passes over N/2 Philox blocks of about 100 integer lane-operations each
+    lane_ops = 3.0 * (cfg.N / 2.0) * 100.0
+    alu_peak = 256 * 4 * 16 * 2.4e9                            # lanes x clock: one 32-bit integer operation per lane and cycle
+    ext_bytes = 4.0 * sumdeg + 16.0 * cfg.B + 8.0 * nnz + 4.0 * (cfg.B + 1)
+    sl_bytes = 2.0 * cfg.B * cfg.d_in * 4 + 8.0 * cfg.B
+    ctx.status()
+    return {"metric": "mini-batch construction (sample + induced CSR + slice)", "unit": "us", "value": t_s + t_i + t_plan + t_g,
+            "higher_is_better": False, "dtype": "integer keys and indices, f32 values", "data": "synthetic",
+            "config": {"workload": "%s: R-MAT N=%d, E=%d stored entries, |S|=%d, d_in=%d" % (cfg.name, cfg.N, E, cfg.B, cfg.d_in),
+                       "sum_deg_S": sumdeg, "induced_entries": nnz},
+            "sampler": {"us": t_s, "Gkeys_per_s": cfg.N / (t_s * 1e-6) / 1e9, "bound": "alu",
+                        "achieved": lane_ops / (t_s * 1e-6) / 1e12, "peak": alu_peak / 1e12, "unit": "T lane-ops/s",
+                        "frac": lane_ops / (t_s * 1e-6) / alu_peak},
+            "induced_csr": {"us": t_i, "plan_us": t_plan, "bound": "hbm", "algorithmic_bytes": ext_bytes,
+                            "achieved": ext_bytes / (t_i * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": ext_bytes / (t_i * 1e-6) / 1e9 / PEAK_HBM_GBS},
+            "slice": {"us": t_g, "bound": "hbm", "algorithmic_bytes": sl_bytes, "achieved": sl_bytes / (t_g * 1e-6) / 1e9,
+                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": sl_bytes / (t_g * 1e-6) / 1e9 / PEAK_HBM_GBS},
+            "kernels": {"sampler": _kernels(rec_s, reps), "induced": _kernels(rec_i, reps), "slice": _kernels(rec_g, reps)}}
+
+
 def bench_shard(cfg, args):
     import torch
     import paper_2604_02651_amd as sg
@@ -182,8 +239,8 @@ def bench_shard(cfg, args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--what", required=True, choices=["tail", "eval", "shard"])
-    ap.add_argument("--config", default=None, help="tiny | medium | large | dense (default: medium; eval: large)")
+    ap.add_argument("--what", required=True, choices=["tail", "eval", "shard", "stages"])
+    ap.add_argument("--config", default=None, help="tiny | medium | large | dense | xlarge (default: medium; eval and stages: large)")
     ap.add_argument("--grid", type=int, default=2, help="shard: the matrix is cut into grid x grid shards")
     args = ap.parse_args()
     import torch
@@ -191,8 +248,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench_extras: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    cfg = si.CONFIGS[args.config or ("large" if args.what == "eval" else "medium")]
-    out = {"tail": bench_tail, "eval": bench_eval, "shard": bench_shard}[args.what](cfg, args)
+    cfg = si.CONFIGS[args.config or ("large" if args.what in ("eval", "stages") else "medium")]
+    out = {"tail": bench_tail, "eval": bench_eval, "shard": bench_shard, "stages": bench_stages}[args.what](cfg, args)
     print(json.dumps(out))
 
 

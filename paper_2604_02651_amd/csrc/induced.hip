@@ -12,8 +12,8 @@
 //   1. induced_deg_kernel      row length of every sampled row and per-workgroup sums
 //   2. induced_offsets_kernel  flat offsets P[B+1] (exclusive prefix of the row lengths)
 //   3. induced_count_kernel    survivors per tile (wave ballots / popcounts)
-//   4. induced_group_kernel    only beyond 2048 tiles: survivors per group of 2048 tiles
-//   5. induced_fill_kernel     ordered compaction inside the tile; writes colidx, val, rowptr
+//   4. prefix sum              survivors in earlier tiles, for every tile
+//   5. induced_fill_kernel     survivors only (keep words of pass 3): ordered compaction, colidx, val, rowptr
 //   6. induced_renorm_kernel   only for norm_mode 1: weights from the degrees of the induced graph
 // A tile stages the starts of the rows it touches in LDS, so finding the row of an edge is a
 // binary search in LDS, and the whole tile needs one barrier for its ordered compaction.
@@ -26,8 +26,9 @@ namespace {
 
 constexpr int IND_NT = 256;
 constexpr int IND_ITEMS = 8;
-constexpr int IND_TILE = IND_NT * IND_ITEMS;      // 2048 flat edges per workgroup
-constexpr int IND_GROUP = 2048;                   // tiles per group of the two-level tile offsets
+constexpr int IND_TILE = IND_NT * IND_ITEMS;      // 2048 flat edges per workgroup (4096 and 8192 with 512 threads measured slower)
+constexpr int IND_WORDS = IND_ITEMS * (IND_NT / 64);   // 64-bit keep words of a tile: one per slab and wavefront
+constexpr int IND_ROWS = 512;                     // rows a tile's LDS table holds (more only when rows average under 4 edges): 6 KB, so LDS does not limit occupancy
 constexpr unsigned IND_MAX_GRID = 8192;
 constexpr int DEG_TILE = 2048;                    // sampled rows per workgroup in the offset kernels
 
@@ -37,7 +38,7 @@ struct shard_range { int64_t r0, r1, c0, c1; };
 template <class RP>
 __global__ __launch_bounds__(256) void induced_deg_kernel(const RP *__restrict__ rowptr, const int32_t *__restrict__ S,
                                                           uint32_t B, shard_range rg, uint32_t *__restrict__ deg,
-                                                          uint64_t *__restrict__ wg_sum)
+                                                          int64_t *__restrict__ rowstart, uint64_t *__restrict__ wg_sum)
 {
     __shared__ uint64_t lds[256 / 64];
     uint64_t s = 0;
@@ -47,8 +48,10 @@ __global__ __launch_bounds__(256) void induced_deg_kernel(const RP *__restrict__
         if (i < B) {
             const int64_t v = S[i];
             // a sampled row outside the shard's row range contributes no edge: it comes out as an empty row
-            const uint32_t dgr = (v >= rg.r0 && v < rg.r1) ? (uint32_t)(rowptr[v + 1] - rowptr[v]) : 0u;
+            const int64_t rs = (int64_t)rowptr[v];
+            const uint32_t dgr = (v >= rg.r0 && v < rg.r1) ? (uint32_t)((int64_t)rowptr[v + 1] - rs) : 0u;
             deg[i] = dgr;
+            rowstart[i] = rs;      // kept for the tile kernels: no second gather through S
             s += dgr;
         }
     }
@@ -56,9 +59,12 @@ __global__ __launch_bounds__(256) void induced_deg_kernel(const RP *__restrict__
     if (threadIdx.x == 0) wg_sum[blockIdx.x] = t;
 }
 
+// Also tells every tile of IND_TILE flat edges which row its first edge belongs to: the row that covers the
+// flat offset c * IND_TILE writes its number to tile_row[c] (a hub row covers many tile starts, most rows
+// none), so that the tile kernels need no search for their first row.
 __global__ __launch_bounds__(256) void induced_offsets_kernel(const uint32_t *__restrict__ deg, uint32_t B,
                                                               const uint64_t *__restrict__ wg_sum,
-                                                              uint64_t *__restrict__ P)
+                                                              uint64_t *__restrict__ P, uint32_t *__restrict__ tile_row)
 {
     __shared__ uint64_t lds[256 / 64 + 1];
     uint64_t part = 0;
@@ -77,7 +83,10 @@ __global__ __launch_bounds__(256) void induced_offsets_kernel(const uint32_t *__
     uint64_t ex = block_excl_scan<uint64_t, 256>(s, &total, lds) + base;
 #pragma unroll
     for (int k = 0; k < DEG_TILE / 256; ++k) {
-        if (i0 + k < B) P[i0 + k] = ex;
+        if (i0 + k < B) {
+            P[i0 + k] = ex;
+            for (uint64_t c = (ex + IND_TILE - 1) / IND_TILE; c * IND_TILE < ex + d[k]; ++c) tile_row[c] = i0 + k;
+        }
         ex += d[k];
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) P[B] = base + total;
@@ -96,31 +105,34 @@ __device__ __forceinline__ uint32_t find_row(const uint64_t *__restrict__ P, uin
 // Per-tile row table in LDS.  Rows r_lo .. r_lo+nr-1 intersect the tile [f0, f1).
 //   relP[k]  = P[r_lo+k] - f0, clamped to -1 when the row starts before the tile
 //   ebase[k] = rowptr[S[r]] - P[r]: the position in colidx of flat edge f of that row is ebase + f
-// staged == false (more rows than the table holds: only possible when the input has rows without
-// any entry) falls back to searching P in global memory.
+// staged == false (more rows than the table holds: rows averaging under four edges, or the run of empty
+// rows behind the last tile of a shard) falls back to searching P in global memory.
 struct tile_table {
-    int32_t relP[IND_TILE];
-    int64_t ebase[IND_TILE];
-    uint32_t r_lo, nr;
+    int32_t relP[IND_ROWS + 1];
+    int64_t ebase[IND_ROWS + 1];
 };
 
-template <class RP>
-__device__ __forceinline__ bool stage_tile(tile_table &tt, const RP *__restrict__ rowptr, const int32_t *__restrict__ S,
-                                           uint32_t B, const uint64_t *__restrict__ P, uint64_t f0, uint64_t f1)
+// Rows r_lo .. r_lo + nr - 1 of a tile: from the row of its first edge to the row of the first edge of the next
+// tile (which holds the tile's last edge, or starts right behind it and is then never found by the search);
+// the last tile takes every row up to the last one.
+__device__ __forceinline__ void tile_rows(const uint32_t *__restrict__ tile_row, uint64_t c, uint64_t n_tiles, uint32_t B,
+                                          uint32_t &r_lo, uint32_t &nr)
 {
-    if (threadIdx.x == 0) {
-        tt.r_lo = find_row(P, 0, B - 1, f0);
-        tt.nr = find_row(P, tt.r_lo, B - 1, f1 - 1) - tt.r_lo + 1;
-    }
-    __syncthreads();
-    const uint32_t r_lo = tt.r_lo, nr = tt.nr;
-    const bool staged = nr <= (uint32_t)IND_TILE;
+    r_lo = c ? tile_row[c] : 0;        // the first tile also takes the empty rows in front of the first edge
+    const uint32_t r_hi = c + 1 < n_tiles ? tile_row[c + 1] : B - 1;
+    nr = r_hi - r_lo + 1;
+}
+
+__device__ __forceinline__ bool stage_tile(tile_table &tt, const int64_t *__restrict__ rowstart,
+                                           const uint64_t *__restrict__ P, uint64_t f0, uint32_t r_lo, uint32_t nr)
+{
+    const bool staged = nr <= (uint32_t)IND_ROWS + 1;
     if (staged) {
         for (uint32_t k = threadIdx.x; k < nr; k += IND_NT) {
             const uint64_t p = P[r_lo + k];
-            const int64_t v = S[r_lo + k];
-            tt.relP[k] = p < f0 ? -1 : (int32_t)(p - f0);
-            tt.ebase[k] = (int64_t)rowptr[v] - (int64_t)p;
+            const int64_t rel = (int64_t)p - (int64_t)f0;      // signed on purpose: the row may start in front of the tile
+            tt.relP[k] = rel < 0 ? -1 : (rel > IND_TILE ? IND_TILE : (int32_t)rel);
+            tt.ebase[k] = rowstart[r_lo + k] - (int64_t)p;
         }
     }
     __syncthreads();
@@ -138,197 +150,210 @@ __device__ __forceinline__ uint32_t find_row_lds(const tile_table &tt, uint32_t 
     return lo;
 }
 
-template <class RP>
-__global__ __launch_bounds__(IND_NT) void induced_count_kernel(const RP *__restrict__ rowptr,
-                                                               const int32_t *__restrict__ colidx,
-                                                               const int32_t *__restrict__ S, uint32_t B,
+// The same search for the IND_ITEMS edges of a thread at once, in lock step with a fixed number of rounds,
+// so that the LDS reads of the slabs are in flight together (x[k] < 0: no edge, the result is unused).
+__device__ __forceinline__ void find_rows_lds(const tile_table &tt, uint32_t nr, const int32_t (&x)[IND_ITEMS],
+                                              uint32_t (&rk)[IND_ITEMS])
+{
+#pragma unroll
+    for (int k = 0; k < IND_ITEMS; ++k) rk[k] = 0;
+    for (uint32_t step = 1u << (31 - __clz((int)nr)); step; step >>= 1) {
+#pragma unroll
+        for (int k = 0; k < IND_ITEMS; ++k) {
+            const uint32_t t = rk[k] + step;
+            if (t < nr && tt.relP[t] <= x[k]) rk[k] = t;
+        }
+    }
+}
+
+__global__ __launch_bounds__(IND_NT) void induced_count_kernel(const int64_t *__restrict__ rowstart,
+                                                               const int32_t *__restrict__ colidx, uint32_t B,
                                                                const uint64_t *__restrict__ bitmap, shard_range rg,
                                                                const uint64_t *__restrict__ P,
+                                                               const uint32_t *__restrict__ tile_row,
                                                                uint32_t *__restrict__ tile_total,
+                                                               uint64_t *__restrict__ keepbits,
                                                                uint64_t *__restrict__ n_tiles_out)
 {
     __shared__ tile_table tt;
     __shared__ uint32_t lds[IND_NT / 64];
+    const unsigned lane = lane_id(), wave = threadIdx.x >> 6;
     const uint64_t F = P[B];
     const uint64_t n_tiles = (F + IND_TILE - 1) / IND_TILE;
     if (blockIdx.x == 0 && threadIdx.x == 0) *n_tiles_out = n_tiles;
     for (uint64_t c = blockIdx.x; c < n_tiles; c += gridDim.x) {
         const uint64_t f0 = c * IND_TILE, f1 = min(F, f0 + IND_TILE);
-        const bool staged = stage_tile(tt, rowptr, S, B, P, f0, f1);
-        const uint32_t nr = tt.nr, r_lo = tt.r_lo;
-        int32_t u[IND_ITEMS];
+        uint32_t r_lo, nr;
+        tile_rows(tile_row, c, n_tiles, B, r_lo, nr);
+        const bool staged = stage_tile(tt, rowstart, P, f0, r_lo, nr);
+        int32_t x[IND_ITEMS], u[IND_ITEMS];
+        uint32_t rk[IND_ITEMS];
 #pragma unroll
         for (int k = 0; k < IND_ITEMS; ++k) {
             const uint64_t f = f0 + (uint64_t)k * IND_NT + threadIdx.x;
+            x[k] = f < f1 ? (int32_t)(f - f0) : -1;
+        }
+        if (staged) find_rows_lds(tt, nr, x, rk);
+#pragma unroll
+        for (int k = 0; k < IND_ITEMS; ++k) {
             u[k] = -1;
-            if (f < f1) {
+            if (x[k] >= 0) {
+                const uint64_t f = f0 + (uint64_t)x[k];
                 int64_t e;
-                if (staged) e = tt.ebase[find_row_lds(tt, nr, (int32_t)(f - f0))] + (int64_t)f;
+                if (staged) e = tt.ebase[rk[k]] + (int64_t)f;
                 else {
                     const uint32_t r = find_row(P, r_lo, r_lo + nr - 1, f);
-                    e = (int64_t)rowptr[S[r]] + (int64_t)(f - P[r]);
+                    e = rowstart[r] + (int64_t)(f - P[r]);
                 }
                 u[k] = colidx[e];
                 if (u[k] < rg.c0 || u[k] >= rg.c1) u[k] = -1;   // a column outside the shard
             }
         }
+        uint64_t word[IND_ITEMS];
+#pragma unroll
+        for (int k = 0; k < IND_ITEMS; ++k) word[k] = u[k] >= 0 ? bitmap[(uint32_t)u[k] >> 6] : 0ull;
+        // one keep word per slab and wavefront, kept for the fill pass; the count is their popcount
         uint32_t cnt = 0;
 #pragma unroll
-        for (int k = 0; k < IND_ITEMS; ++k)
-            if (u[k] >= 0) cnt += (uint32_t)((bitmap[(uint32_t)u[k] >> 6] >> (u[k] & 63)) & 1ull);
+        for (int k = 0; k < IND_ITEMS; ++k) {
+            const uint64_t bal = __ballot(u[k] >= 0 && ((word[k] >> (u[k] & 63)) & 1ull));
+            if (lane == 0) {
+                keepbits[c * IND_WORDS + k * (IND_NT / 64) + wave] = bal;
+                cnt += (uint32_t)__popcll(bal);
+            }
+        }
         const uint32_t t = block_sum<uint32_t, IND_NT>(cnt, lds);   // ends with a barrier: tt may be reused
         if (threadIdx.x == 0) tile_total[c] = t;
     }
 }
 
-// survivors per group of IND_GROUP consecutive tiles
-__global__ __launch_bounds__(256) void induced_group_kernel(const uint32_t *__restrict__ tile_total,
-                                                            const uint64_t *__restrict__ n_tiles_p,
-                                                            uint32_t *__restrict__ group_total)
-{
-    __shared__ uint32_t lds[256 / 64];
-    const uint64_t n_tiles = *n_tiles_p;
-    const uint64_t c0 = (uint64_t)blockIdx.x * IND_GROUP;
-    uint32_t s = 0;
-    for (uint64_t c = c0 + threadIdx.x; c < min(n_tiles, c0 + IND_GROUP); c += 256) s += tile_total[c];
-    const uint32_t t = block_sum<uint32_t, 256>(s, lds);
-    if (threadIdx.x == 0) group_total[blockIdx.x] = t;
-}
-
-// survivors in tiles [0, c): whole groups from group_total, the rest from tile_total
-__device__ __forceinline__ uint32_t survivors_before(const uint32_t *__restrict__ tile_total,
-                                                     const uint32_t *__restrict__ group_total, uint64_t c, uint32_t *lds)
-{
-    const uint64_t gq = group_total ? c / IND_GROUP : 0;
-    uint32_t s = 0;
-    for (uint64_t i = threadIdx.x; i < gq; i += IND_NT) s += group_total[i];
-    for (uint64_t i = gq * IND_GROUP + threadIdx.x; i < c; i += IND_NT) s += tile_total[i];
-    return block_sum<uint32_t, IND_NT>(s, lds);
-}
-
+// Fill pass.  The keep words of the count pass say which edges survive, so only survivors are looked at again:
+// position = survivors in earlier tiles + survivors before the edge in the tile (prefix over the popcounts of
+// the tile's keep words).  Row offsets come from the row side: every row that starts inside the tile gets the
+// position of the first survivor at or behind its start, which also covers rows without any stored entry.
 template <class RP>
 __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
     const RP *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *__restrict__ gval,
-    const int32_t *__restrict__ S, uint32_t B, const uint64_t *__restrict__ bitmap, const uint32_t *__restrict__ rank,
-    shard_range rg, const uint64_t *__restrict__ P, const uint32_t *__restrict__ tile_total, const uint32_t *__restrict__ group_total,
-    const uint64_t *__restrict__ n_tiles_p, double p, int write_val, int32_t *__restrict__ rowptr_S,
-    int32_t *__restrict__ colidx_S, float *__restrict__ val_S, uint64_t capacity, uint32_t *__restrict__ nnz_dev,
-    uint32_t *__restrict__ status, int empty_rows_here)
+    const int32_t *__restrict__ S, const int64_t *__restrict__ rowstart, const uint32_t *__restrict__ deg, uint32_t B,
+    const uint64_t *__restrict__ bitmap, const uint32_t *__restrict__ rank, const uint64_t *__restrict__ P,
+    const uint32_t *__restrict__ tile_row, const uint32_t *__restrict__ tile_off_all, const uint64_t *__restrict__ n_tiles_p, const uint64_t *__restrict__ keepbits, float inv_p, int write_val,
+    int32_t *__restrict__ rowptr_S, int32_t *__restrict__ colidx_S, float *__restrict__ val_S, uint64_t capacity,
+    uint32_t *__restrict__ nnz_dev, uint32_t *__restrict__ status)
 {
-    // empty_rows_here: rows without any stored entry get their offset from the thread that holds the first
-    // entry of the next row, one after the other (fine for the odd isolated vertex); 0: a kernel of its own
-    // does it afterwards (a shard leaves every sampled row outside its row range empty)
     __shared__ tile_table tt;
-    __shared__ uint32_t lds[IND_NT / 64];
-    __shared__ uint32_t wcnt[IND_ITEMS][IND_NT / 64];
+    __shared__ uint64_t balw[IND_WORDS];
+    __shared__ uint32_t pre[IND_WORDS + 1];
     const uint64_t F = P[B];
     const uint64_t n_tiles = *n_tiles_p;
     const unsigned lane = lane_id(), wave = threadIdx.x >> 6;
     if (blockIdx.x == 0) {
-        const uint32_t total = survivors_before(tile_total, group_total, n_tiles, lds);
+        const uint32_t total = tile_off_all[n_tiles];
         if (threadIdx.x == 0) {
             if (total > 0x7fffffffu) atomicOr(status, SGNN_ST_NNZ_OVERFLOW);
             rowptr_S[B] = (int32_t)total;
-            // rows at the end that have no stored entry at all
-            if (empty_rows_here)
-                for (int64_t r = (int64_t)B - 1; r >= 0 && P[r] == F; --r) rowptr_S[r] = (int32_t)total;
             if (nnz_dev) *nnz_dev = total;
         }
+        if (n_tiles == 0)       // not a single edge: every row is empty
+            for (uint32_t r = threadIdx.x; r < B; r += IND_NT) rowptr_S[r] = 0;
     }
     for (uint64_t c = blockIdx.x; c < n_tiles; c += gridDim.x) {
         const uint64_t f0 = c * IND_TILE, f1 = min(F, f0 + IND_TILE);
-        const uint32_t tile_off = survivors_before(tile_total, group_total, c, lds);
-        const bool staged = stage_tile(tt, rowptr, S, B, P, f0, f1);
-        const uint32_t nr = tt.nr, r_lo = tt.r_lo;
+        const uint32_t tile_len = (uint32_t)(f1 - f0);
+        const bool last = c + 1 == n_tiles;
+        const uint32_t tile_off = tile_off_all[c];     // survivors in earlier tiles (exclusive prefix of the tile counts)
+        uint32_t r_lo, nr;
+        tile_rows(tile_row, c, n_tiles, B, r_lo, nr);
+        if (wave == 0) {
+            uint64_t w = 0;
+            if (lane < IND_WORDS) { w = keepbits[c * IND_WORDS + lane]; balw[lane] = w; }
+            const uint32_t pc = (uint32_t)__popcll(w);
+            const uint32_t inc = wave_incl_scan(pc);
+            if (lane < IND_WORDS) pre[lane] = inc - pc;
+            if (lane == IND_WORDS - 1) pre[IND_WORDS] = inc;
+        }
+        const bool staged = stage_tile(tt, rowstart, P, f0, r_lo, nr);     // ends with a barrier
 
-        int32_t u[IND_ITEMS];
-        uint32_t rk[IND_ITEMS];      // row of the edge, relative to r_lo
-        int64_t eidx[IND_ITEMS];
-        bool first[IND_ITEMS];       // the edge is the first stored entry of its row
+        // row offsets.  A row that starts right at the end of the tile is empty if it is not the row the next
+        // tile begins with (that tile writes that one); behind the last tile every such row is empty.
+        for (uint32_t k = threadIdx.x; k < nr; k += IND_NT) {
+            int64_t x;
+            if (staged) x = tt.relP[k];
+            else {
+                const int64_t rel = (int64_t)P[r_lo + k] - (int64_t)f0;
+                x = rel < 0 ? -1 : (rel > IND_TILE ? IND_TILE : rel);
+            }
+            if (x < 0) continue;
+            if (x < (int64_t)tile_len) {
+                const uint32_t wd = ((uint32_t)x / IND_NT) * (IND_NT / 64) + (((uint32_t)x % IND_NT) >> 6);
+                rowptr_S[r_lo + k] = (int32_t)(tile_off + pre[wd] + (uint32_t)__popcll(balw[wd] & ((1ull << (x & 63)) - 1ull)));
+            } else if (x == (int64_t)tile_len && (last || k + 1 < nr)) rowptr_S[r_lo + k] = (int32_t)(tile_off + pre[IND_WORDS]);
+        }
+
+        // survivors
+        int32_t x[IND_ITEMS], u[IND_ITEMS];
+        uint32_t rk[IND_ITEMS];
 #pragma unroll
         for (int k = 0; k < IND_ITEMS; ++k) {
-            const uint64_t f = f0 + (uint64_t)k * IND_NT + threadIdx.x;
-            u[k] = -1; rk[k] = 0; eidx[k] = 0; first[k] = false;
-            if (f < f1) {
-                if (staged) {
-                    const int32_t x = (int32_t)(f - f0);
-                    rk[k] = find_row_lds(tt, nr, x);
-                    eidx[k] = tt.ebase[rk[k]] + (int64_t)f;
-                    first[k] = tt.relP[rk[k]] == x;
-                } else {
+            const bool mine = (balw[k * (IND_NT / 64) + wave] >> lane) & 1ull;
+            x[k] = mine ? (int32_t)(k * IND_NT + threadIdx.x) : -1;
+        }
+        if (staged) find_rows_lds(tt, nr, x, rk);
+        int64_t eidx[IND_ITEMS];
+#pragma unroll
+        for (int k = 0; k < IND_ITEMS; ++k) {
+            u[k] = -1; eidx[k] = 0;
+            if (x[k] >= 0) {
+                const uint64_t f = f0 + (uint64_t)x[k];
+                if (staged) eidx[k] = tt.ebase[rk[k]] + (int64_t)f;
+                else {
                     const uint32_t r = find_row(P, r_lo, r_lo + nr - 1, f);
                     rk[k] = r - r_lo;
-                    eidx[k] = (int64_t)rowptr[S[r]] + (int64_t)(f - P[r]);
-                    first[k] = P[r] == f;
+                    eidx[k] = rowstart[r] + (int64_t)(f - P[r]);
                 }
                 u[k] = colidx[eidx[k]];
             }
         }
-        uint64_t word[IND_ITEMS], bal[IND_ITEMS];
-#pragma unroll
-        for (int k = 0; k < IND_ITEMS; ++k) word[k] = u[k] >= 0 ? bitmap[(uint32_t)u[k] >> 6] : 0ull;
+        uint64_t word[IND_ITEMS];
+        uint32_t rnk[IND_ITEMS];
+        int64_t du[IND_ITEMS];
 #pragma unroll
         for (int k = 0; k < IND_ITEMS; ++k) {
-            const bool keep = u[k] >= 0 && u[k] >= rg.c0 && u[k] < rg.c1 && ((word[k] >> (u[k] & 63)) & 1ull);
-            bal[k] = __ballot(keep);
-            if (lane == 0) wcnt[k][wave] = __popcll(bal[k]);
+            word[k] = 0; rnk[k] = 0; du[k] = 1;
+            if (u[k] >= 0) {
+                word[k] = bitmap[(uint32_t)u[k] >> 6];
+                rnk[k] = rank[(uint32_t)u[k] >> 6];
+                if (write_val && !gval) du[k] = (int64_t)rowptr[(int64_t)u[k] + 1] - (int64_t)rowptr[u[k]];
+            }
         }
-        __syncthreads();
-        uint32_t base = tile_off;
         const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
         for (int k = 0; k < IND_ITEMS; ++k) {
-            uint32_t before = 0, slab = 0;
-#pragma unroll
-            for (int w = 0; w < IND_NT / 64; ++w) {
-                const uint32_t cw = wcnt[k][w];
-                if (w < (int)wave) before += cw;
-                slab += cw;
-            }
-            const uint32_t pos = base + before + __popcll(bal[k] & below);   // survivors ahead of this edge
-            base += slab;
             if (u[k] < 0) continue;
-            const uint32_t r = r_lo + rk[k];
-            if (first[k]) {
-                // everything before the first entry of row r belongs to earlier rows
-                rowptr_S[r] = (int32_t)pos;
-                if (empty_rows_here) {
-                    const uint64_t Pr = P[r];
-                    for (int64_t q = (int64_t)r - 1; q >= 0 && P[q] == Pr; --q) rowptr_S[q] = (int32_t)pos;
+            const uint32_t wd = k * (IND_NT / 64) + wave;
+            const uint32_t pos = tile_off + pre[wd] + (uint32_t)__popcll(balw[wd] & below);
+            if (pos >= capacity) continue;
+            colidx_S[pos] = (int32_t)(rnk[k] + (uint32_t)__popcll(word[k] & ((1ull << (u[k] & 63)) - 1ull)));
+            if (write_val) {
+                const uint32_t r = r_lo + rk[k];
+                const int64_t v = S[r];
+                float a;
+                if (gval) a = gval[eidx[k]];
+                else {
+                    // 1 / sqrt(deg(v) deg(u)) in single precision: product, reciprocal square root, one Newton step.
+                    // Against the double-precision formula rounded once: a few 1e-7 relative (two roundings of
+                    // 2^-24 here, one for 1/p, the Newton step leaves under one more), inside the 1e-6 the weights are held to.
+                    // A row that holds an edge lies inside the row range: deg is its full length.
+                    const float xx = (float)deg[r] * (float)du[k];
+                    float y = __frsqrt_rn(xx);
+                    const float err = fmaf(-xx * y, y, 1.0f);
+                    a = fmaf(0.5f * y, err, y);
                 }
-            }
-            if (((bal[k] >> lane) & 1ull) && pos < capacity) {
-                colidx_S[pos] = (int32_t)(rank[(uint32_t)u[k] >> 6] + __popcll(word[k] & ((1ull << (u[k] & 63)) - 1ull)));
-                if (write_val) {
-                    const int64_t v = S[r];
-                    double a;
-                    if (gval) a = (double)gval[eidx[k]];
-                    else {
-                        const double dv = (double)(rowptr[v + 1] - rowptr[v]);
-                        const double du = (double)(rowptr[(int64_t)u[k] + 1] - rowptr[u[k]]);
-                        a = 1.0 / sqrt(dv * du);
-                    }
-                    if ((int64_t)u[k] != v) a /= p;
-                    val_S[pos] = (float)a;
-                }
+                if ((int64_t)u[k] != v) a *= inv_p;
+                val_S[pos] = a;
             }
         }
-        __syncthreads();   // wcnt and the row table are reused by the next tile
+        __syncthreads();   // the keep words and the row table are reused by the next tile
     }
-}
-
-// Offsets of the rows without any stored entry, one thread per row: such a row starts where the next
-// row that has stored entries starts (found by binary search in the flat offsets), or at the end.
-__global__ __launch_bounds__(256) void induced_empty_rows_kernel(const uint64_t *__restrict__ P, uint32_t B,
-                                                                 int32_t *rowptr_S)
-{
-    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= B) return;
-    const uint64_t Pi = P[i];
-    if (P[i + 1] != Pi) return;
-    // the last row whose flat offset is still Pi is the one that holds the entries (none does when Pi is the
-    // end of the flat range); its offset was written by the fill kernel and no thread of this kernel touches it
-    rowptr_S[i] = Pi == P[B] ? rowptr_S[B] : rowptr_S[find_row(P, i, B - 1, Pi)];
 }
 
 // norm_mode 1: a_ij = 1/sqrt(c_i c_j) with c = entry counts of the induced rows, off-diagonal / p.
@@ -358,39 +383,36 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
     const RP *rowptr = static_cast<const RP *>(g->rowptr);
     ws_alloc ws(ctx);
     const uint64_t max_tiles = g->E / IND_TILE + 2;
-    const unsigned n_groups = cdiv(max_tiles, IND_GROUP);
     const unsigned n_deg_wg = cdiv(B, DEG_TILE);
     uint32_t *deg = ws.get<uint32_t>(B);
+    int64_t *rowstart = ws.get<int64_t>(B);
     uint64_t *deg_sum = ws.get<uint64_t>(n_deg_wg);
     uint64_t *P = ws.get<uint64_t>((size_t)B + 1);
     uint32_t *tile_total = ws.get<uint32_t>(max_tiles);
-    uint32_t *group_total = ws.get<uint32_t>(n_groups);
+    uint32_t *tile_row = ws.get<uint32_t>(max_tiles + 1);
+    uint64_t *keepbits = ws.get<uint64_t>(max_tiles * IND_WORDS);
+    uint32_t *tile_off = ws.get<uint32_t>(max_tiles + 1);
+    uint32_t *scan_tmp = ws.get<uint32_t>(sgnn_scan_tmp_elems(max_tiles));
     uint64_t *n_tiles = ws.get<uint64_t>(1);
     if (!ws.ok)
         return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_induced_csr: scratch too small (%zu bytes needed): call sgnn_ctx_reserve",
                          ws.off);
 
     SGNN_LAUNCH(ctx, st, "induced_deg_kernel", SGNN_TAG, induced_deg_kernel<RP>, dim3(n_deg_wg), dim3(256), 0, st, rowptr, S, B,
-                rg, deg, deg_sum);
+                rg, deg, rowstart, deg_sum);
     SGNN_LAUNCH(ctx, st, "induced_offsets_kernel", SGNN_TAG, induced_offsets_kernel, dim3(n_deg_wg), dim3(256), 0, st, deg, B,
-                deg_sum, P);
+                deg_sum, P, tile_row);
     const unsigned grid = (unsigned)std::min<uint64_t>(max_tiles, IND_MAX_GRID);
-    SGNN_LAUNCH(ctx, st, "induced_count_kernel", SGNN_TAG, induced_count_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr,
-                g->colidx, S, B, bitmap, rg, P, tile_total, n_tiles);
-    const bool grouped = max_tiles > IND_GROUP;
-    if (grouped)
-        SGNN_LAUNCH(ctx, st, "induced_group_kernel", SGNN_TAG, induced_group_kernel, dim3(n_groups), dim3(256), 0, st,
-                    tile_total, n_tiles, group_total);
+    SGNN_LAUNCH(ctx, st, "induced_count_kernel", SGNN_TAG, induced_count_kernel, dim3(grid), dim3(IND_NT), 0, st, rowstart,
+                g->colidx, B, bitmap, rg, P, tile_row, tile_total, keepbits, n_tiles);
+    int rc = sgnn_scan_u32_devn(ctx, tile_total, tile_off, n_tiles, max_tiles, scan_tmp, st);
+    if (rc) return rc;
     double p = 1.0;
     if (rescale && B > 1) p = ((double)B - 1.0) / ((double)g->N - 1.0);
-    const bool whole_rows = rg.r0 <= 0 && rg.r1 >= (int64_t)g->N;
     SGNN_LAUNCH(ctx, st, "induced_fill_kernel", SGNN_TAG, induced_fill_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr,
-                g->colidx, norm_mode == 0 ? g->val : nullptr, S, B, bitmap, rank, rg, P, tile_total,
-                grouped ? group_total : nullptr, n_tiles, p, norm_mode == 0 ? 1 : 0, out->rowptr, out->colidx, out->val,
-                out->capacity, out->nnz_dev, ctx->status, whole_rows ? 1 : 0);
-    if (!whole_rows)
-        SGNN_LAUNCH(ctx, st, "induced_empty_rows_kernel", SGNN_TAG, induced_empty_rows_kernel, dim3(cdiv(B, 256)), dim3(256), 0,
-                    st, P, B, out->rowptr);
+                g->colidx, norm_mode == 0 ? g->val : nullptr, S, rowstart, deg, B, bitmap, rank, P, tile_row, tile_off,
+                n_tiles, keepbits, (float)(1.0 / p), norm_mode == 0 ? 1 : 0, out->rowptr, out->colidx, out->val,
+                out->capacity, out->nnz_dev, ctx->status);
     if (norm_mode == 1)
         SGNN_LAUNCH(ctx, st, "induced_renorm_kernel", SGNN_TAG, induced_renorm_kernel, dim3(cdiv((uint64_t)B * 64, 256)),
                     dim3(256), 0, st, out->rowptr, out->colidx, out->val, B, out->capacity, p);
@@ -431,8 +453,8 @@ __global__ __launch_bounds__(256) void graph_normalize_kernel(uint64_t N, const 
 size_t sgnn_induced_ws_bytes(uint64_t E, uint32_t B)
 {
     const uint64_t max_tiles = E / IND_TILE + 2;
-    return (size_t)B * 4 + ((size_t)B + 1) * 8 + (size_t)cdiv(B, DEG_TILE) * 8 + max_tiles * 4 +
-           (size_t)cdiv(max_tiles, IND_GROUP) * 4 + 8 + 8 * 256;
+    return (size_t)B * 12 + ((size_t)B + 1) * 8 + (size_t)cdiv(B, DEG_TILE) * 8 + max_tiles * 4 + (max_tiles + 1) * 4 +
+           max_tiles * IND_WORDS * 8 + (max_tiles + 1) * 4 + sgnn_scan_tmp_elems(max_tiles) * 4 + 8 + 12 * 256;
 }
 
 int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B, const uint64_t *bitmap,

@@ -21,6 +21,7 @@
 
 #include <algorithm>
 
+#include "block_prims.h"
 #include "common.h"
 
 namespace {
@@ -86,6 +87,7 @@ __host__ __device__ inline int64_t spmm_piece_len(int64_t len)
     return c;
 }
 constexpr unsigned SPMM_PIECE_WAVES = 2048;
+constexpr int SPMM_PLAN_NT = 1024;  // rows per workgroup of the plan kernel
 
 // Plan of a matrix (device memory): header, first chunk number per row, chunk descriptors.
 struct spmm_plan_view {
@@ -140,27 +142,35 @@ inline spmm_plan_view plan_view(void *plan, uint32_t rows, uint32_t max_chunks)
 
 __global__ void spmm_plan_clear_kernel(uint32_t *n_chunks) { *n_chunks = 0; }
 
-// One thread per row: a long row reserves its chunk numbers with one atomic add, records the
-// first of them in part_base[row] and writes one (row, chunk) descriptor per chunk.  The chunk
+// One thread per row: the long rows of a wavefront reserve their chunk numbers with one atomic add,
+// each records its first one in part_base[row] and writes one (row, chunk) descriptor per chunk.  The chunk
 // numbering depends on timing; the values computed from it do not.
-__global__ __launch_bounds__(256) void spmm_plan_kernel(uint32_t rows, const int32_t *__restrict__ rowptr, uint64_t capacity,
+__global__ __launch_bounds__(SPMM_PLAN_NT) void spmm_plan_kernel(uint32_t rows, const int32_t *__restrict__ rowptr, uint64_t capacity,
                                                         uint32_t *__restrict__ n_chunks,
                                                         uint32_t max_chunks, uint32_t *__restrict__ part_base,
                                                         uint2 *__restrict__ desc, uint32_t *__restrict__ ticket)
 {
-    const uint32_t row = blockIdx.x * 256 + threadIdx.x;
+    __shared__ uint32_t scan_lds[SPMM_PLAN_NT / 64 + 1];
+    __shared__ uint32_t wg_base;
+    const uint32_t row = blockIdx.x * SPMM_PLAN_NT + threadIdx.x;
     const uint64_t entries = min((uint64_t)rowptr[rows], capacity);
     const int long_len = spmm_long_len(rows, entries);
     if (row == 0) {
         n_chunks[1] = (uint32_t)long_len;
         n_chunks[2] = (uint32_t)spmm_rows_per_wave(rows, entries);
     }
-    if (row >= rows) return;
-    const int64_t len = min((int64_t)rowptr[row + 1], (int64_t)capacity) - min((int64_t)rowptr[row], (int64_t)capacity);
-    if (len <= long_len) return;
+    int64_t len = 0;
+    if (row < rows) len = min((int64_t)rowptr[row + 1], (int64_t)capacity) - min((int64_t)rowptr[row], (int64_t)capacity);
     const int64_t plen = spmm_piece_len(len);
-    const uint32_t nch = (uint32_t)((len + plen - 1) / plen);
-    const uint32_t base = atomicAdd(n_chunks, nch);
+    const uint32_t nch = len > long_len ? (uint32_t)((len + plen - 1) / plen) : 0u;
+    // one atomic per workgroup of 1024 rows (atomics on one address cost about 10 ns each, whoever issues
+    // them): the long rows of the workgroup take consecutive piece numbers
+    uint32_t wg_total;
+    const uint32_t excl = block_excl_scan<uint32_t, SPMM_PLAN_NT>(nch, &wg_total, scan_lds);
+    if (threadIdx.x == 0) wg_base = wg_total ? atomicAdd(n_chunks, wg_total) : 0u;
+    __syncthreads();
+    if (nch == 0) return;
+    const uint32_t base = wg_base + excl;
     part_base[row] = base;
     if (base < max_chunks) ticket[base] = 0;
     for (uint32_t c = 0; c < nch && base + c < max_chunks; ++c) desc[base + c] = make_uint2(row, c);
@@ -497,7 +507,7 @@ int build_plan(sgnn_ctx *ctx, const sgnn_csr *A, void *plan, hipStream_t st)
     const uint32_t max_chunks = spmm_max_chunks(A->rows, A->capacity);
     const spmm_plan_view pv = plan_view(plan, A->rows, max_chunks);
     SGNN_LAUNCH(ctx, st, "spmm_plan_clear_kernel", SGNN_TAG, spmm_plan_clear_kernel, dim3(1), dim3(1), 0, st, pv.n_chunks);
-    SGNN_LAUNCH(ctx, st, "spmm_plan_kernel", SGNN_TAG, spmm_plan_kernel, dim3(cdiv(A->rows, 256)), dim3(256), 0, st, A->rows,
+    SGNN_LAUNCH(ctx, st, "spmm_plan_kernel", SGNN_TAG, spmm_plan_kernel, dim3(cdiv(A->rows, SPMM_PLAN_NT)), dim3(SPMM_PLAN_NT), 0, st, A->rows,
                 A->rowptr, A->capacity, pv.n_chunks, max_chunks, pv.part_base, pv.desc, pv.ticket);
     return SGNN_OK;
 }
