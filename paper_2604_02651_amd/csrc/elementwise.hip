@@ -138,7 +138,8 @@ __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, 
     const uint32_t gq = threadIdx.x >> lpr_log2, g = threadIdx.x & (lpr - 1);
     float loss = 0.f;
     const float invB = 1.f / (float)B;
-    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {       // unrolled: the loads of the four passes go out together
         const uint32_t row = (blockIdx.x * 4 + q) * rows_per_pass + gq;
         const bool live = row < B;
         const float *o = O + (int64_t)(live ? row : 0) * ldo;
