@@ -79,10 +79,11 @@ def main():
     dev = "cuda:0"
     cfg = si.CONFIGS[args.config]
     g = si.config_graph(cfg, device=dev)
-    X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=dev)
+    model = args.workload == "model"
+    X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=dev,
+                           dtype=torch.bfloat16 if cfg.bf16_features and not model else torch.float32)
     labels = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=dev)
     weights = si.layer_weights(cfg, device=dev)
-    model = args.workload == "model"
     if model:
         d_h = cfg.hidden
         n_layers = max(cfg.layers - 1, 1)
@@ -228,7 +229,7 @@ def main():
     if not args.no_cpu_baseline and not model:
         import oracle
         rp, ci = g.rowptr.cpu().numpy(), g.colidx.cpu().numpy()
-        Xh, lh = X.cpu().numpy(), labels.cpu().numpy()
+        Xh, lh = X.float().cpu().numpy(), labels.cpu().numpy()
         wnp = [(W.double().cpu().numpy(), b.double().cpu().numpy()) for W, b in weights]
         nsteps = args.cpu_steps or {"tiny": 50, "medium": 8}.get(cfg.name, 1)
         oracle.gcn_step(cfg.N, rp, ci, Xh, lh, wnp, min(cfg.B, 1024), cfg.sampler_seed, 0, bf16=cfg.bf16_mfma)  # warm-up

@@ -190,7 +190,8 @@ int sgnn_csr_transpose(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_csr *out, sgnn_str
  */
 typedef struct {
     void *ptr;
-    int dtype; /* SGNN_F32 (SGNN_BF16 storage is not implemented) */
+    int dtype; /* SGNN_F32; SGNN_BF16 (bfloat16 storage, ld in elements) only where a call says so: the input
+                * operand of a sparse product, i.e. X of sgnn_spmm and H of an aggregate-first sgnn_gcn_fwd */
     int64_t rows, cols, ld;
     const int32_t *row_index;
 } sgnn_mat;

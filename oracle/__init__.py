@@ -354,9 +354,16 @@ def gcn_step(N, rowptr, colidx, X, labels, weights, B, seed, step, bf16=False, n
     return out
 
 
-def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie_band=0.0):
+def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie_band=0.0, dO=None):
     """The layer part of a step on an already extracted mini-batch: L layers forward, mean
-    cross-entropy, L layers backward (see gcn_step for relu_ties / tie_band)."""
+    cross-entropy, L layers backward (see gcn_step for relu_ties / tie_band).
+
+    dO, when given, replaces the oracle's own loss gradient as the start of the backward pass (the
+    forward values and the returned loss and "dO" stay the oracle's).  With rounded operands the
+    logits of the two sides agree to a relative 2^-8 or so; where they are large (the 1/p rescale
+    makes them so) that is an absolute difference a softmax turns into a different gradient row,
+    so a test checks the loss gradient against softmax_xent of the logits it was computed from and
+    hands it in here to compare the backward pass on the same start."""
     B = len(rpS) - 1
     H = np.ascontiguousarray(X_S, np.float64)
     yS = np.ascontiguousarray(y_S, np.int32)
@@ -373,6 +380,9 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
             mask = np.where(band, np.asarray(relu_ties[l], bool), mask)
         Ts.append(T); Hs.append(Y); masks.append(mask); bands.append(band)
     loss, dY = softmax_xent(Hs[-1], yS)
+    dO_own = dY
+    if dO is not None:
+        dY = np.ascontiguousarray(dO, np.float64)
     dWs, dbs, dHs = [None] * L, [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
         W, b = weights[l]
@@ -381,5 +391,5 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
         dH, dW, db = gcn_bwd(rpT, ciT, vT, Ts[l], W, Ymask, dY, relu=relu, bf16=bf16, need_dH=(l > 0))
         dWs[l], dbs[l], dHs[l] = dW, db, dH
         dY = dH
-    return dict(rowptr=rpS, colidx=ciS, val=vS, X_S=H, y_S=yS, T=Ts, H=Hs, loss=loss, dW=dWs, db=dbs, dH=dHs,
+    return dict(rowptr=rpS, colidx=ciS, val=vS, X_S=H, y_S=yS, T=Ts, H=Hs, loss=loss, dO=dO_own, dW=dWs, db=dbs, dH=dHs,
                 relu_band=bands, relu_mask=masks)

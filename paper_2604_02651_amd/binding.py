@@ -21,6 +21,7 @@ SGNN_XFORM_FIRST = 4
 SGNN_DY_MASKED = 8
 SGNN_FUSE_TAIL = 16
 SGNN_F32 = 0
+SGNN_BF16 = 1
 
 _ERR_NAMES = {-1: "SGNN_ERR_INVALID_ARG", -2: "SGNN_ERR_CAPACITY", -3: "SGNN_ERR_UNSUPPORTED", -4: "SGNN_ERR_HIP",
               -5: "SGNN_ERR_INTERNAL"}
@@ -128,14 +129,16 @@ def _ptr(t: Optional[torch.Tensor], dtype=None, name="tensor"):
     return C.c_void_p(t.data_ptr())
 
 
-def _mat(t: torch.Tensor, row_index: Optional[torch.Tensor] = None, name="matrix") -> _Mat:
+def _mat(t: torch.Tensor, row_index: Optional[torch.Tensor] = None, name="matrix", allow_bf16: bool = False) -> _Mat:
+    """allow_bf16: the matrix may be stored as bfloat16 (the input operand of a sparse product)."""
     if t.dim() != 2:
         raise TypeError("%s must be 2-D" % name)
-    p = _ptr(t, torch.float32, name)
+    bf16 = allow_bf16 and t.dtype == torch.bfloat16
+    p = _ptr(t, torch.bfloat16 if bf16 else torch.float32, name)
     ri = _ptr(row_index, torch.int32, name + ".row_index")
     rows = row_index.numel() if row_index is not None else t.shape[0]
     ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
-    return _Mat(p, SGNN_F32, rows, t.shape[1], ld, ri)
+    return _Mat(p, SGNN_BF16 if bf16 else SGNN_F32, rows, t.shape[1], ld, ri)
 
 
 class Context:
@@ -325,7 +328,7 @@ def sgnn_gather_rows(ctx: Context, X: Optional[torch.Tensor], S: torch.Tensor, B
 def sgnn_gcn_fwd(ctx: Context, A: Csr, H: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], flags: int,
                  Y: torch.Tensor, T: Optional[torch.Tensor], row_index: Optional[torch.Tensor] = None, stream=None):
     a = A.struct()
-    h, w, y = _mat(H, row_index, "H"), _mat(W, None, "W"), _mat(Y, None, "Y")
+    h, w, y = _mat(H, row_index, "H", allow_bf16=True), _mat(W, None, "W"), _mat(Y, None, "Y")
     t = _mat(T, None, "T") if T is not None else None
     ctx.check(lib().sgnn_gcn_fwd(ctx._h, C.byref(a), C.byref(h), C.byref(w), _ptr(bias, torch.float32, "bias"), flags,
                                  C.byref(y), C.byref(t) if t is not None else None, _stream(stream)))
@@ -405,7 +408,7 @@ def sgnn_spmm(ctx: Context, A: Csr, X: torch.Tensor, out: torch.Tensor, row_inde
               stream=None, add: Optional[torch.Tensor] = None):
     """out = A X (+ add)."""
     a = A.struct()
-    x, o = _mat(X, row_index, "X"), _mat(out, None, "out")
+    x, o = _mat(X, row_index, "X", allow_bf16=True), _mat(out, None, "out")
     ad = _mat(add, None, "add") if add is not None else None
     ctx.check(lib().sgnn_spmm(ctx._h, C.byref(a), C.byref(x), C.byref(ad) if ad is not None else None, C.byref(o),
                               _stream(stream)))

@@ -65,6 +65,8 @@ int bind_device(sgnn_ctx *ctx)
 }
 
 bool mat_ok(const sgnn_mat *m) { return m && m->ptr && m->dtype == SGNN_F32 && m->rows >= 0 && m->cols >= 0 && m->ld >= m->cols; }
+// the operand of a sparse product may also be stored as bfloat16
+bool mat_ok_in(const sgnn_mat *m) { return m && m->ptr && (m->dtype == SGNN_F32 || m->dtype == SGNN_BF16) && m->rows >= 0 && m->cols >= 0 && m->ld >= m->cols; }
 
 bool csr_ok(const sgnn_csr *c) { return c && c->rowptr && (c->capacity == 0 || (c->colidx && c->val)); }
 
@@ -313,14 +315,14 @@ int sgnn_gather_rows(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, cons
 int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_mat *add, sgnn_mat *out, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
-    if (!csr_ok(A) || !mat_ok(X) || !mat_ok(out)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: bad argument");
+    if (!csr_ok(A) || !mat_ok_in(X) || !mat_ok(out)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: bad argument");
     if (out->rows != A->rows || out->cols != X->cols || (!X->row_index && X->rows != A->cols) ||
         (add && (!mat_ok(add) || add->row_index || add->rows != out->rows || add->cols != out->cols)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: shape mismatch");
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_spmm(ctx, A, static_cast<const float *>(X->ptr), X->ld, X->row_index, X->cols,
+    return sgnn_launch_spmm(ctx, A, X->ptr, X->dtype == SGNN_BF16, X->ld, X->row_index, X->cols,
                             static_cast<float *>(out->ptr), out->ld, nullptr, 0, nullptr, 0,
                             add ? static_cast<const float *>(add->ptr) : nullptr, add ? add->ld : 0, &ws,
                             static_cast<hipStream_t>(stream));
@@ -347,8 +349,11 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     const bool xform_first = (flags & SGNN_XFORM_FIRST) != 0;
-    if (!csr_ok(A) || !mat_ok(H) || !mat_ok(W) || !mat_ok(Y) || (!xform_first && !mat_ok(T)))
+    if (!csr_ok(A) || !mat_ok_in(H) || !mat_ok(W) || !mat_ok(Y) || (!xform_first && !mat_ok(T)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_fwd: bad argument");
+    if (xform_first && H->dtype != SGNN_F32)
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gcn_fwd: a transform-first layer reads its input in the dense product, "
+                                                    "which takes fp32 storage only");
     const int64_t Bn = A->rows, d_in = W->rows, d_out = W->cols;
     if (H->cols != d_in || Y->rows != Bn || Y->cols != d_out || (!H->row_index && H->rows != A->cols) ||
         (H->row_index && H->rows != A->cols) || W->row_index || Y->row_index ||
@@ -361,7 +366,7 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
     const int gflags = flags & (SGNN_RELU | SGNN_BF16_MFMA);
     if (!xform_first) {
         // Eqs. 5-6 in the paper's order: aggregate, then transform with bias and activation fused
-        rc = sgnn_launch_spmm(ctx, A, static_cast<const float *>(H->ptr), H->ld, H->row_index, d_in,
+        rc = sgnn_launch_spmm(ctx, A, H->ptr, H->dtype == SGNN_BF16, H->ld, H->row_index, d_in,
                               static_cast<float *>(T->ptr), T->ld, nullptr, 0, nullptr, 0, nullptr, 0, &ws, st);
         if (rc) return rc;
         return sgnn_launch_gemm(ctx, 0, 0, Bn, d_out, d_in, static_cast<const float *>(T->ptr), T->ld, nullptr,
@@ -376,7 +381,7 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
     rc = sgnn_launch_gemm(ctx, 0, 0, A->cols, d_out, d_in, static_cast<const float *>(H->ptr), H->ld, H->row_index,
                           static_cast<const float *>(W->ptr), W->ld, nullptr, flags & SGNN_BF16_MFMA, P, ldp, nullptr, 0, nullptr, &ws, st);
     if (rc) return rc;
-    return sgnn_launch_spmm(ctx, A, P, ldp, nullptr, d_out, static_cast<float *>(Y->ptr), Y->ld, bias,
+    return sgnn_launch_spmm(ctx, A, P, 0, ldp, nullptr, d_out, static_cast<float *>(Y->ptr), Y->ld, bias,
                             (flags & SGNN_RELU) ? 1 : 0, nullptr, 0, nullptr, 0, &ws, st);
 }
 
@@ -441,7 +446,7 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
             rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, nullptr, static_cast<const float *>(W->ptr), W->ld,
                                   nullptr, mfma, dT, ld_in, nullptr, 0, nullptr, &ws, st);
             if (rc) return rc;
-            rc = sgnn_launch_spmm(ctx, A_T, dT, ld_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, hmask, ldhm, nullptr, 0, &ws,
+            rc = sgnn_launch_spmm(ctx, A_T, dT, 0, ld_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, hmask, ldhm, nullptr, 0, &ws,
                                   st);
             if (rc) return rc;
         }
@@ -450,7 +455,7 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     // transform-first layer: dP = A^T dZ (width d_out), dW = H^T dP, dH = dP W^T; T is the layer input H
     float *dP = ws.get<float>((size_t)Bn * ld_out);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
-    rc = sgnn_launch_spmm(ctx, A_T, dZ, lddz, nullptr, d_out, dP, ld_out, nullptr, 0, nullptr, 0, nullptr, 0, &ws, st);
+    rc = sgnn_launch_spmm(ctx, A_T, dZ, 0, lddz, nullptr, d_out, dP, ld_out, nullptr, 0, nullptr, 0, nullptr, 0, &ws, st);
     if (rc) return rc;
     if (dW) {
         rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, T->row_index, dP, ld_out,

@@ -103,7 +103,7 @@ int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, ui
                         int64_t R1, int64_t C0, int64_t C1, sgnn_csr *out, hipStream_t st);
 int sgnn_launch_csr_transpose(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_csr *out, ws_alloc *ws, hipStream_t st);
 size_t sgnn_transpose_ws_bytes(uint64_t max_entries, uint32_t B);
-int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index,
+int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const void *X, int x_bf16, int64_t ldx, const int32_t *row_index,
                      int64_t d, float *out, int64_t ldo, const float *bias, int relu, const float *mask, int64_t ldm,
                      const float *add, int64_t ldadd, ws_alloc *ws, hipStream_t st);
 int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st);   // fills A->plan when it is attached

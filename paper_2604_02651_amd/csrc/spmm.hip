@@ -44,6 +44,26 @@ template <int VEC> __device__ __forceinline__ void vload(float (&dst)[VEC], cons
     }
 }
 
+// A feature row stored as bfloat16 (16-bit patterns: the upper half of an fp32): widened while it is read.
+struct bf16_bits { uint16_t v; };
+
+template <int VEC> __device__ __forceinline__ void vload(float (&dst)[VEC], const bf16_bits *p)
+{
+    if constexpr (VEC == 1) dst[0] = __builtin_bit_cast(float, (uint32_t)p->v << 16);
+    else if constexpr (VEC == 2) {
+        const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
+        dst[0] = __builtin_bit_cast(float, w << 16);
+        dst[1] = __builtin_bit_cast(float, w & 0xffff0000u);
+    } else {
+        static_assert(VEC == 4, "vector width");
+        const uint2 w = *reinterpret_cast<const uint2 *>(p);
+        dst[0] = __builtin_bit_cast(float, w.x << 16);
+        dst[1] = __builtin_bit_cast(float, w.x & 0xffff0000u);
+        dst[2] = __builtin_bit_cast(float, w.y << 16);
+        dst[3] = __builtin_bit_cast(float, w.y & 0xffff0000u);
+    }
+}
+
 template <int VEC> __device__ __forceinline__ void vstore(float *p, const float (&src)[VEC])
 {
     if constexpr (VEC == 1) *p = src[0];
@@ -215,10 +235,10 @@ __device__ __forceinline__ void spmm_epilogue(float (&v)[VEC], const spmm_epi &e
 // flight at a time whatever the lengths of the rows, the 64 lanes covering the columns.  Every
 // value that steers the walk (row number, row bounds, entry number) is the same in all lanes.
 // A row longer than long_len is left out: its chunks and the fix-up write it.
-template <int VEC, int CH>
+template <int VEC, int CH, typename XT>
 __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const int32_t *__restrict__ rowptr,
                                                const int32_t *__restrict__ colidx, const float *__restrict__ val,
-                                               uint64_t capacity, const float *__restrict__ X, int64_t ldx,
+                                               uint64_t capacity, const XT *__restrict__ X, int64_t ldx,
                                                const int32_t *__restrict__ row_index, int d, uint32_t wave, int rows_per_wave,
                                                int long_len, float *__restrict__ out, int64_t ldo,
                                                const spmm_epi &ep)
@@ -286,7 +306,7 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const int32_t *__r
 #pragma unroll
             for (int t = 0; t < U; ++t) {
                 const int jj = __builtin_amdgcn_readfirstlane(min(j0 + t, n - 1));
-                const float *x = X + (int64_t)__builtin_amdgcn_readlane(src, jj) * ldx;
+                const XT *x = X + (int64_t)__builtin_amdgcn_readlane(src, jj) * ldx;
                 av[t] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), jj));
 #pragma unroll
                 for (int m = 0; m < CH; ++m) {
@@ -320,8 +340,8 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const int32_t *__r
 // acc += sum over the n <= 64 entries starting at e, which lane l < n holds as (src, a): U feature
 // rows in flight at a time, handed out by lane index.  keep(j) tells whether entry j still counts
 // and may move the caller's row state; it is called in entry order.
-template <int VEC, int CH, int U, typename Keep>
-__device__ __forceinline__ void spmm_wave_entries(float (&acc)[CH][VEC], int32_t src, float a, int n, const float *__restrict__ X,
+template <int VEC, int CH, int U, typename XT, typename Keep>
+__device__ __forceinline__ void spmm_wave_entries(float (&acc)[CH][VEC], int32_t src, float a, int n, const XT *__restrict__ X,
                                                   int64_t ldx, int d, int lane, Keep keep)
 {
     bool go = true;
@@ -330,7 +350,7 @@ __device__ __forceinline__ void spmm_wave_entries(float (&acc)[CH][VEC], int32_t
 #pragma unroll
         for (int t = 0; t < U; ++t) {
             const int jj = __builtin_amdgcn_readfirstlane(min(j0 + t, n - 1));
-            const float *x = X + (int64_t)__builtin_amdgcn_readlane(src, jj) * ldx;
+            const XT *x = X + (int64_t)__builtin_amdgcn_readlane(src, jj) * ldx;
             av[t] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), jj));
 #pragma unroll
             for (int m = 0; m < CH; ++m) {
@@ -366,11 +386,11 @@ template <int VEC, int CH> struct spmm_unroll { static constexpr int U = CH * VE
 // draws a ticket of the row, and the holder of the last ticket reads all partial rows back with
 // device-scope loads and adds them up in piece order - the same sum whoever does it.  That wavefront also puts the ticket counter
 // back to zero for the next product with this plan.
-template <int VEC, int CH>
+template <int VEC, int CH, typename XT>
 __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const int32_t *__restrict__ rowptr,
                                                             const int32_t *__restrict__ colidx,
                                                             const float *__restrict__ val, uint64_t capacity,
-                                                            const float *__restrict__ X, int64_t ldx,
+                                                            const XT *__restrict__ X, int64_t ldx,
                                                             const int32_t *__restrict__ row_index, int d,
                                                             unsigned n_piece_waves, const uint32_t *__restrict__ n_chunks,
                                                             uint32_t max_chunks, const uint2 *__restrict__ desc,
@@ -476,7 +496,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
                     a = val[cb + lane];
                     src = row_index ? row_index[c] : c;
                 }
-                spmm_wave_entries<VEC, CH, U>(acc, src, a, n, X, ldx, d, lane, [](int) { return true; });
+                spmm_wave_entries<VEC, CH, U, XT>(acc, src, a, n, X, ldx, d, lane, [](int) { return true; });
             }
             if (drawn) finish_row();
             if (owed) draw_ticket();
@@ -498,7 +518,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
         if (owed) { draw_ticket(); finish_row(); }
         return;
     }
-    spmm_wave_rows<VEC, CH>(rows, rowptr, colidx, val, cap, X, ldx, row_index, d, wave - n_piece_waves,
+    spmm_wave_rows<VEC, CH, XT>(rows, rowptr, colidx, val, cap, X, ldx, row_index, d, wave - n_piece_waves,
                             n_chunks ? (int)n_chunks[2] : rows_per_wave, n_chunks ? (int)n_chunks[1] : 0x7fffffff, out, ldo, ep);
 }
 
@@ -512,14 +532,14 @@ int build_plan(sgnn_ctx *ctx, const sgnn_csr *A, void *plan, hipStream_t st)
     return SGNN_OK;
 }
 
-template <int VEC, int CH>
-int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int d, float *out,
+template <int VEC, int CH, typename XT>
+int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const XT *X, int64_t ldx, const int32_t *row_index, int d, float *out,
               int64_t ldo, const spmm_epi &ep, ws_alloc *ws, hipStream_t st)
 {
     const int rows_per_wave = spmm_rows_per_wave(A->rows, A->capacity);   // lower bound of the plan's figure
     const unsigned rows_per_block = (unsigned)(SPMM_NT / 64) * (unsigned)rows_per_wave;
     char tag[56];
-    snprintf(tag, sizeof(tag), "%ux%u d=%d <%d,%d>", A->rows, A->cols, d, VEC, CH);
+    snprintf(tag, sizeof(tag), "%ux%u d=%d <%d,%d>%s", A->rows, A->cols, d, VEC, CH, sizeof(XT) == 2 ? " bf16 in" : "");
     const bool may_have_long = A->capacity > (uint64_t)SPMM_SHORT;
     spmm_plan_view pv = {nullptr, nullptr, nullptr, nullptr};
     float *part = nullptr;
@@ -546,27 +566,27 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, con
         const uint64_t want = std::min<uint64_t>(std::max<uint64_t>(A->capacity / 2048, SPMM_PIECE_WAVES), 65536);
         n_piece_waves = cdiv(std::min<uint64_t>(max_chunks, want), SPMM_NT / 64) * (SPMM_NT / 64);
     }
-    SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH>), dim3(n_piece_waves / (SPMM_NT / 64) + cdiv(A->rows, rows_per_block)),
+    SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH, XT>), dim3(n_piece_waves / (SPMM_NT / 64) + cdiv(A->rows, rows_per_block)),
                 dim3(SPMM_NT), 0, st, A->rows, A->rowptr, A->colidx, A->val, A->capacity, X, ldx, row_index, d,
                 n_piece_waves, pv.n_chunks, max_chunks, pv.desc, pv.ticket, part, out, ldo, ep, rows_per_wave);
     return SGNN_OK;
 }
 
-template <int VEC>
-int launch_v(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int d, float *out,
+template <int VEC, typename XT>
+int launch_v(sgnn_ctx *ctx, const sgnn_csr *A, const XT *X, int64_t ldx, const int32_t *row_index, int d, float *out,
              int64_t ldo, const spmm_epi &ep, ws_alloc *ws, hipStream_t st)
 {
     const int per = (d + VEC - 1) / VEC;   // lanes needed for one pass over the row
     const int ch = (per + 63) / 64;
     switch (ch) {
-    case 1: return launch_vc<VEC, 1>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
-    case 2: return launch_vc<VEC, 2>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
-    case 3: return launch_vc<VEC, 3>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
-    case 4: return launch_vc<VEC, 4>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
-    case 5: return launch_vc<VEC, 5>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
-    case 6: return launch_vc<VEC, 6>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
-    case 7: return launch_vc<VEC, 7>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
-    case 8: return launch_vc<VEC, 8>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 1: return launch_vc<VEC, 1, XT>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 2: return launch_vc<VEC, 2, XT>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 3: return launch_vc<VEC, 3, XT>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 4: return launch_vc<VEC, 4, XT>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 5: return launch_vc<VEC, 5, XT>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 6: return launch_vc<VEC, 6, XT>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 7: return launch_vc<VEC, 7, XT>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
+    case 8: return launch_vc<VEC, 8, XT>(ctx, A, X, ldx, row_index, d, out, ldo, ep, ws, st);
     default: break;
     }
     return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_spmm: feature width %d is beyond %d columns", d, 64 * 8 * VEC);
@@ -592,23 +612,30 @@ int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st)
     return build_plan(ctx, A, A->plan, st);
 }
 
-int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const float *X, int64_t ldx, const int32_t *row_index, int64_t d,
+template <typename XT>
+static int launch_x(sgnn_ctx *ctx, const sgnn_csr *A, const XT *X, int64_t ldx, const int32_t *row_index, int64_t d, float *out,
+                    int64_t ldo, const spmm_epi &ep, ws_alloc *ws, hipStream_t st)
+{
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(ep.mask) |
+                           reinterpret_cast<uintptr_t>(ep.add);
+    // the narrowest vector with which one wavefront still covers the row
+    const int64_t lds_ = ldx | ldo | (ep.mask ? ep.ldm : 0) | (ep.add ? ep.ldadd : 0);
+    const bool ok4 = d % 4 == 0 && lds_ % 4 == 0 && (bits & 15) == 0;
+    const bool ok2 = d % 2 == 0 && lds_ % 2 == 0 && (bits & 7) == 0;
+    if (d <= 64) return launch_v<1, XT>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
+    if (d <= 128 && ok2) return launch_v<2, XT>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
+    if (ok4) return launch_v<4, XT>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
+    if (ok2) return launch_v<2, XT>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
+    return launch_v<1, XT>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
+}
+
+// X: cols x d, fp32 or (x_bf16) bfloat16 bit patterns, leading dimension ldx in elements
+int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const void *X, int x_bf16, int64_t ldx, const int32_t *row_index, int64_t d,
                      float *out, int64_t ldo, const float *bias, int relu, const float *mask, int64_t ldm, const float *add,
                      int64_t ldadd, ws_alloc *ws, hipStream_t st)
 {
     const spmm_epi ep = {bias, relu, mask, ldm, add, ldadd};
     if (A->rows == 0 || d == 0) return SGNN_OK;
-    const uintptr_t bits = reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(mask) |
-                           reinterpret_cast<uintptr_t>(add);
-    // the narrowest vector with which one wavefront still covers the row
-    const int64_t lds_ = ldx | ldo | (mask ? ldm : 0) | (add ? ldadd : 0);
-    const bool ok4 = d % 4 == 0 && lds_ % 4 == 0 && (bits & 15) == 0;
-    const bool ok2 = d % 2 == 0 && lds_ % 2 == 0 && (bits & 7) == 0;
-    if (d <= 64) return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
-    if (d <= 128 && ok2) return launch_v<2>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
-    if (ok4)
-        return launch_v<4>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
-    if (ok2)
-        return launch_v<2>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
-    return launch_v<1>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
+    if (x_bf16) return launch_x(ctx, A, static_cast<const bf16_bits *>(X), ldx, row_index, d, out, ldo, ep, ws, st);
+    return launch_x(ctx, A, static_cast<const float *>(X), ldx, row_index, d, out, ldo, ep, ws, st);
 }

@@ -44,6 +44,9 @@ class GcnStep:
         # a layer that narrows (d_out < d_in) is evaluated transform-first: its sparse products run at
         # width d_out, and its backward pass needs the layer input instead of the aggregate
         self.xform_first = [auto_order and dims[l + 1] < dims[l] for l in range(self.L)]
+        if X.dtype == torch.bfloat16 and (not fuse_slice or self.xform_first[0]):
+            raise ValueError("bfloat16 features are read by the first layer's sparse product only: they need fuse_slice "
+                             "and a first layer that aggregates first")
         self.fuse_relu_bwd = fuse_relu_bwd
         self.side_dw = side_dw      # run() / graphs: weight-gradient GEMMs on the second stream
         def mat(d):   # B x d with rows starting 16-byte aligned (leading dimension a multiple of 4)

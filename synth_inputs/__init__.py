@@ -298,6 +298,7 @@ class Config:
     classes: int
     B: int
     bf16_mfma: bool = False
+    bf16_features: bool = False      # the input features are stored as bfloat16
     steps: int = 1
     graph_seed: int = 1234
     feature_seed: int = 1
@@ -315,7 +316,7 @@ CONFIGS = {
     "medium": Config("medium", 262144, 2097152, 128, 256, 3, 32, 32768, steps=16),
     "large": Config("large", 2449029, 61859140, 100, 256, 3, 47, 262144, bf16_mfma=True),
     "dense": Config("dense", 232965, 57307946, 602, 256, 2, 41, 65536),
-    "xlarge": Config("xlarge", 111059956, 1615685872, 128, 256, 3, 172, 1048576, bf16_mfma=True),
+    "xlarge": Config("xlarge", 111059956, 1615685872, 128, 256, 3, 172, 1048576, bf16_mfma=True, bf16_features=True),
 }
 
 

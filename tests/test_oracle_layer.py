@@ -254,3 +254,28 @@ def test_relu_tie_band_only_acts_inside_the_band():
     assert diff.sum() == 1 and diff[k]
     assert np.array_equal(out["loss"], base["loss"]) and all(np.array_equal(a, b) for a, b in zip(out["H"], base["H"]))
     assert not np.array_equal(out["dW"][0], base["dW"][0])
+
+
+def test_backward_from_a_given_loss_gradient():
+    # layers_step(dO=...) starts the backward pass from the gradient handed in and leaves everything of the
+    # forward pass alone: its own gradient gives the same result bit for bit, twice the gradient twice the
+    # weight gradients (the backward pass is linear in it), and "dO" / loss stay the oracle's own.
+    rng = np.random.default_rng(1)
+    Bn = 10
+    dense = (rng.random((Bn, Bn)) < 0.4) * rng.random((Bn, Bn)) + np.eye(Bn)
+    rp = [0]; ci = []; v = []
+    for i in range(Bn):
+        nz = np.nonzero(dense[i])[0]
+        ci += list(nz); v += list(dense[i, nz].astype(np.float32)); rp.append(len(ci))
+    rp, ci, v = np.array(rp, np.int32), np.array(ci, np.int32), np.array(v, np.float32)
+    X = rng.standard_normal((Bn, 4)); y = rng.integers(0, 3, Bn).astype(np.int32)
+    Ws = [(rng.standard_normal((4, 5)), rng.standard_normal(5) * 0.1), (rng.standard_normal((5, 3)), np.zeros(3))]
+    base = oracle.layers_step(rp, ci, v, X, y, Ws)
+    loss, dO = oracle.softmax_xent(base["H"][-1], y)
+    assert np.array_equal(base["dO"], dO) and base["loss"] == loss
+    same = oracle.layers_step(rp, ci, v, X, y, Ws, dO=dO)
+    twice = oracle.layers_step(rp, ci, v, X, y, Ws, dO=2.0 * dO)
+    for l in range(2):
+        assert np.array_equal(same["dW"][l], base["dW"][l]) and np.array_equal(same["db"][l], base["db"][l])
+        assert np.allclose(twice["dW"][l], 2.0 * base["dW"][l], rtol=1e-13, atol=0)
+    assert twice["loss"] == base["loss"] and np.array_equal(twice["dO"], dO)
