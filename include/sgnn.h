@@ -138,6 +138,9 @@ typedef struct {
     uint64_t capacity;
     uint32_t *nnz_dev;
     void *plan;
+    int rowptr_is_i64; /* 0: rowptr is int32 (every matrix the library writes); 1: rowptr points at int64
+                        * offsets - a full graph with 2^31 entries or more as the matrix of a sparse product
+                        * (sgnn_spmm, sgnn_gcn_fwd, sgnn_csr_plan); other calls refuse such a matrix */
 } sgnn_csr;
 
 uint64_t sgnn_csr_plan_bytes(uint32_t rows, uint64_t capacity);
@@ -246,9 +249,12 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
  * The full graph as a sparse matrix for the full-graph evaluation forward (the paper's evaluation
  * rounds run the model on all N vertices): int32 row offsets and the weights of Eq. 3,
  * a_vu = 1 / sqrt(deg(v) deg(u)) (g->val verbatim when given), no 1/p rescale.
- *   rowptr32  out device int32[N + 1];  val out device fp32[E]
+ *   rowptr32  out device int32[N + 1], or NULL: the offsets are not copied and the caller uses the
+ *             graph's own (sgnn_csr.rowptr_is_i64 = g->rowptr_is_i64) - the only way with 2^31 - 1 or more
+ *             stored entries, where a non-NULL rowptr32 is SGNN_ERR_UNSUPPORTED
+ *   val       out device fp32[E]
  * Together with g->colidx they form an sgnn_csr {rows = cols = N, capacity = E} for sgnn_gcn_fwd /
- * sgnn_spmm.  Graphs with 2^31 - 1 or more stored entries are SGNN_ERR_UNSUPPORTED (32-bit offsets).
+ * sgnn_spmm.
  */
 int sgnn_graph_normalized_csr(sgnn_ctx *ctx, const sgnn_graph *g, int32_t *rowptr32, float *val,
                               sgnn_stream stream);

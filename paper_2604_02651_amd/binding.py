@@ -40,7 +40,8 @@ class _Graph(C.Structure):
 
 class _Csr(C.Structure):
     _fields_ = [("rows", C.c_uint32), ("cols", C.c_uint32), ("rowptr", C.c_void_p), ("colidx", C.c_void_p),
-                ("val", C.c_void_p), ("capacity", C.c_uint64), ("nnz_dev", C.c_void_p), ("plan", C.c_void_p)]
+                ("val", C.c_void_p), ("capacity", C.c_uint64), ("nnz_dev", C.c_void_p), ("plan", C.c_void_p),
+                ("rowptr_is_i64", C.c_int)]
 
 
 class _Mat(C.Structure):
@@ -214,12 +215,13 @@ class Csr:
         return c
 
     def struct(self) -> _Csr:
-        return _Csr(self.rows, self.cols, _ptr(self.rowptr, torch.int32), _ptr(self.colidx, torch.int32),
+        i64 = self.rowptr.dtype == torch.int64         # a full graph with 2^31 entries or more (sparse products only)
+        return _Csr(self.rows, self.cols, _ptr(self.rowptr, torch.int64 if i64 else torch.int32), _ptr(self.colidx, torch.int32),
                     _ptr(self.val, torch.float32), self.capacity, _ptr(self.nnz_dev, torch.int32),
-                    _ptr(self.plan, torch.int64) if self.plan is not None else None)
+                    _ptr(self.plan, torch.int64) if self.plan is not None else None, int(i64))
 
     def nnz(self) -> int:
-        return int(self.nnz_dev.item())
+        return int(self.nnz_dev.item()) if self.nnz_dev is not None else int(self.rowptr[-1].item())
 
 
 # ------------------------------------------------------------------------------------------------
@@ -271,13 +273,14 @@ def sgnn_graph_normalized_csr(ctx: Context, N: int, rowptr: torch.Tensor, colidx
     out = Csr.__new__(Csr)
     out.rows, out.cols, out.capacity = N, N, E
     dev = colidx.device
-    out.rowptr = torch.empty(N + 1, dtype=torch.int32, device=dev)
+    big = E >= 2 ** 31 - 1
+    out.rowptr = rowptr if big else torch.empty(N + 1, dtype=torch.int32, device=dev)     # the graph's own int64 offsets when 32 bits do not do
     out.colidx = colidx
     out.val = torch.empty(max(E, 1), dtype=torch.float32, device=dev)
-    out.nnz_dev = torch.full((1,), E, dtype=torch.int32, device=dev)
+    out.nnz_dev = None if big else torch.full((1,), E, dtype=torch.int32, device=dev)
     out.plan = None
-    ctx.check(lib().sgnn_graph_normalized_csr(ctx._h, C.byref(g), _ptr(out.rowptr, torch.int32), _ptr(out.val, torch.float32),
-                                              _stream(stream)))
+    ctx.check(lib().sgnn_graph_normalized_csr(ctx._h, C.byref(g), None if big else _ptr(out.rowptr, torch.int32),
+                                              _ptr(out.val, torch.float32), _stream(stream)))
     if with_plan:
         nbytes = int(lib().sgnn_csr_plan_bytes(N, E))
         out.plan = torch.zeros((nbytes + 7) // 8, dtype=torch.int64, device=dev)

@@ -68,7 +68,7 @@ bool mat_ok(const sgnn_mat *m) { return m && m->ptr && m->dtype == SGNN_F32 && m
 // the operand of a sparse product may also be stored as bfloat16
 bool mat_ok_in(const sgnn_mat *m) { return m && m->ptr && (m->dtype == SGNN_F32 || m->dtype == SGNN_BF16) && m->rows >= 0 && m->cols >= 0 && m->ld >= m->cols; }
 
-bool csr_ok(const sgnn_csr *c) { return c && c->rowptr && (c->capacity == 0 || (c->colidx && c->val)); }
+bool csr_ok(const sgnn_csr *c) { return c && c->rowptr && (c->capacity == 0 || (c->colidx && c->val)) && (c->rowptr_is_i64 == 0 || c->rowptr_is_i64 == 1); }
 
 } // namespace
 
@@ -234,6 +234,7 @@ static int induced_impl(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, ui
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint32_t *nnz_dev = out->nnz_dev;
+    if (out->rowptr_is_i64) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_induced_csr: a mini-batch matrix has int32 row offsets");
     sgnn_csr o = *out;
     o.rows = o.cols = B;
     if (nnz_host && !nnz_dev) o.nnz_dev = ctx->status + 2;
@@ -279,6 +280,8 @@ int sgnn_csr_transpose(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_csr *out, sgnn_str
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     if (!csr_ok(A) || !out || !out->rowptr || (out->capacity > 0 && (!out->colidx || !out->val)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_csr_transpose: bad argument");
+    if (A->rowptr_is_i64 || out->rowptr_is_i64)
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_csr_transpose: int32 row offsets only");
     if (out->rows != A->cols || out->cols != A->rows || out->capacity < A->capacity)
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_csr_transpose: out must be cols x rows with at least A's capacity");
     int rc = bind_device(ctx);
@@ -577,11 +580,15 @@ int sgnn_adam_step(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v, 
 int sgnn_graph_normalized_csr(sgnn_ctx *ctx, const sgnn_graph *g, int32_t *rowptr32, float *val, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
-    if (!g || !g->rowptr || !g->colidx || !rowptr32 || !val)
+    if (!g || !g->rowptr || !g->colidx || !val)
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_graph_normalized_csr: bad argument");
-    if (g->E >= 0x7fffffffull || g->N >= 0x7fffffffull)
-        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_graph_normalized_csr: %llu entries do not fit 32-bit row offsets",
+    if (g->N >= 0x7fffffffull) return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_graph_normalized_csr: N must be below 2^31");
+    if (rowptr32 && g->E >= 0x7fffffffull)
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_graph_normalized_csr: %llu entries do not fit 32-bit row offsets: pass "
+                                                    "rowptr32 = NULL and use the graph's own int64 offsets in the sgnn_csr",
                          (unsigned long long)g->E);
+    if (!g->rowptr_is_i64 && g->E >= 0x7fffffffull)
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_graph_normalized_csr: E >= 2^31 needs an int64 rowptr");
     int rc = bind_device(ctx);
     if (rc) return rc;
     return sgnn_launch_graph_normalize(ctx, g, rowptr32, val, static_cast<hipStream_t>(stream));

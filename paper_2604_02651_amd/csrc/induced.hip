@@ -432,7 +432,7 @@ __global__ __launch_bounds__(256) void graph_normalize_kernel(uint64_t N, const 
     const uint64_t wave = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6), nwaves = (uint64_t)gridDim.x * 4;
     for (uint64_t v = wave; v < N; v += nwaves) {
         const int64_t rs = (int64_t)rowptr[v], re = (int64_t)rowptr[v + 1];
-        if (lane == 0) {
+        if (lane == 0 && rowptr32) {
             rowptr32[v] = (int32_t)rs;
             if (v + 1 == N) rowptr32[N] = (int32_t)re;
         }

@@ -92,6 +92,19 @@ template <int VEC> __device__ __forceinline__ void vload_device(float (&dst)[VEC
     for (int i = 0; i < VEC; ++i) dst[i] = __hip_atomic_load(p + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Row offsets are int32 (mini-batch matrices) or int64 (a full graph with 2^31 entries or more).
+__device__ __forceinline__ int64_t rp_load(const void *__restrict__ rowptr, int rp64, uint64_t i)
+{
+    return rp64 ? static_cast<const int64_t *>(rowptr)[i] : (int64_t) static_cast<const int32_t *>(rowptr)[i];
+}
+
+__device__ __forceinline__ int64_t readlane64(int64_t v, int lane)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), lane);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 constexpr int SPMM_NT = 256;       // threads of a workgroup
 constexpr int SPMM_SHORT = 32;     // smallest length from which a row counts as long
 constexpr int SPMM_CHUNK = 64;     // entries per piece of a long row: what one wavefront fetches at once
@@ -117,13 +130,16 @@ struct spmm_plan_view {
     uint32_t *ticket;       // [max_chunks], used at the first chunk number of a long row; zero between products
 };
 
-// Rows longer than this count as long: four times the mean row length of the matrix.  Evaluated
-// on the device from the true entry count when the plan is built (header word 1 of the plan).
+// Rows longer than this count as long: four times the mean row length of the matrix, and at least
+// 1/65536 of its entries (a full graph with 10^9 entries has long rows in the hundreds that one
+// wavefront walks without holding anything up; what must be cut are its hubs).  Evaluated on the
+// device from the true entry count when the plan is built (header word 1 of the plan).
 __host__ __device__ inline int spmm_long_len(uint32_t rows, uint64_t entries)
 {
     const uint64_t mean = rows ? entries / rows : 0;
     uint64_t t = 4 * mean;
     if (t < SPMM_SHORT) t = SPMM_SHORT;
+    if (t < (entries >> 16)) t = entries >> 16;      // never more than 65536 long rows, however large the matrix
     if (t > (1u << 20)) t = 1u << 20;
     return (int)t;
 }
@@ -146,7 +162,8 @@ inline uint32_t spmm_max_chunks(uint32_t rows, uint64_t capacity)
     // of them, each with at most one partly filled chunk, plus the full chunks
     (void)rows;
     const uint64_t n = capacity / SPMM_SHORT + capacity / SPMM_CHUNK + 2;
-    return (uint32_t)std::min<uint64_t>(n, 0x7fffffffu);
+    // and no more than 65536 long rows (spmm_long_len) of at most SPMM_MAX_PIECES pieces each
+    return (uint32_t)std::min<uint64_t>(n, (uint64_t)65536 * SPMM_MAX_PIECES + 2);
 }
 
 inline spmm_plan_view plan_view(void *plan, uint32_t rows, uint32_t max_chunks)
@@ -165,7 +182,7 @@ __global__ void spmm_plan_clear_kernel(uint32_t *n_chunks) { *n_chunks = 0; }
 // One thread per row: the long rows of a wavefront reserve their chunk numbers with one atomic add,
 // each records its first one in part_base[row] and writes one (row, chunk) descriptor per chunk.  The chunk
 // numbering depends on timing; the values computed from it do not.
-__global__ __launch_bounds__(SPMM_PLAN_NT) void spmm_plan_kernel(uint32_t rows, const int32_t *__restrict__ rowptr, uint64_t capacity,
+__global__ __launch_bounds__(SPMM_PLAN_NT) void spmm_plan_kernel(uint32_t rows, const void *__restrict__ rowptr, int rp64, uint64_t capacity,
                                                         uint32_t *__restrict__ n_chunks,
                                                         uint32_t max_chunks, uint32_t *__restrict__ part_base,
                                                         uint2 *__restrict__ desc, uint32_t *__restrict__ ticket)
@@ -173,14 +190,14 @@ __global__ __launch_bounds__(SPMM_PLAN_NT) void spmm_plan_kernel(uint32_t rows, 
     __shared__ uint32_t scan_lds[SPMM_PLAN_NT / 64 + 1];
     __shared__ uint32_t wg_base;
     const uint32_t row = blockIdx.x * SPMM_PLAN_NT + threadIdx.x;
-    const uint64_t entries = min((uint64_t)rowptr[rows], capacity);
+    const uint64_t entries = min((uint64_t)rp_load(rowptr, rp64, rows), capacity);
     const int long_len = spmm_long_len(rows, entries);
     if (row == 0) {
         n_chunks[1] = (uint32_t)long_len;
         n_chunks[2] = (uint32_t)spmm_rows_per_wave(rows, entries);
     }
     int64_t len = 0;
-    if (row < rows) len = min((int64_t)rowptr[row + 1], (int64_t)capacity) - min((int64_t)rowptr[row], (int64_t)capacity);
+    if (row < rows) len = min(rp_load(rowptr, rp64, (uint64_t)row + 1), (int64_t)capacity) - min(rp_load(rowptr, rp64, row), (int64_t)capacity);
     const int64_t plen = spmm_piece_len(len);
     const uint32_t nch = len > long_len ? (uint32_t)((len + plen - 1) / plen) : 0u;
     // one atomic per workgroup of 1024 rows (atomics on one address cost about 10 ns each, whoever issues
@@ -236,20 +253,26 @@ __device__ __forceinline__ void spmm_epilogue(float (&v)[VEC], const spmm_epi &e
 // value that steers the walk (row number, row bounds, entry number) is the same in all lanes.
 // A row longer than long_len is left out: its chunks and the fix-up write it.
 template <int VEC, int CH, typename XT>
-__device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const int32_t *__restrict__ rowptr,
+__device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const void *__restrict__ rowptr, int rp64,
                                                const int32_t *__restrict__ colidx, const float *__restrict__ val,
                                                uint64_t capacity, const XT *__restrict__ X, int64_t ldx,
-                                               const int32_t *__restrict__ row_index, int d, uint32_t wave, int rows_per_wave,
+                                               const int32_t *__restrict__ row_index, int d, uint64_t wave, int rows_per_wave,
                                                int long_len, float *__restrict__ out, int64_t ldo,
                                                const spmm_epi &ep)
 {
     constexpr int U = CH * VEC <= 4 ? 8 : (CH * VEC <= 8 ? 4 : 2);
     const int lane = threadIdx.x & 63;
-    const uint64_t r0 = (uint64_t)wave * (uint64_t)rows_per_wave;
+    const uint64_t r0 = wave * (uint64_t)rows_per_wave;
     if (r0 >= rows) return;
     const int nr = (int)min((uint64_t)rows_per_wave, rows - r0);
-    const int32_t cap = (int32_t)min(capacity, (uint64_t)0x7fffffff);
-    const int32_t rp = lane <= nr ? min(rowptr[r0 + lane], cap) : 0;   // lane k: start of row r0 + k
+    // lane k: start of row r0 + k, as an offset from the start of the block's first row (a block of
+    // rows holds far fewer than 2^31 entries, so everything behind this line is 32-bit)
+    int64_t rpl = 0;
+    if (lane <= nr) rpl = min(rp_load(rowptr, rp64, r0 + lane), (int64_t)min(capacity, (uint64_t)0x7fffffffffffffffull));
+    const int64_t block_base = readlane64(rpl, 0);
+    const int32_t rp = lane <= nr ? (int32_t)(rpl - block_base) : 0;
+    colidx += block_base;
+    val += block_base;
     const int e_end = __builtin_amdgcn_readlane(rp, nr);
     int e = __builtin_amdgcn_readlane(rp, 0);
     int row = 0, row_end = __builtin_amdgcn_readlane(rp, 1);
@@ -387,7 +410,7 @@ template <int VEC, int CH> struct spmm_unroll { static constexpr int U = CH * VE
 // device-scope loads and adds them up in piece order - the same sum whoever does it.  That wavefront also puts the ticket counter
 // back to zero for the next product with this plan.
 template <int VEC, int CH, typename XT>
-__global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const int32_t *__restrict__ rowptr,
+__global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const void *__restrict__ rowptr, int rp64,
                                                             const int32_t *__restrict__ colidx,
                                                             const float *__restrict__ val, uint64_t capacity,
                                                             const XT *__restrict__ X, int64_t ldx,
@@ -400,7 +423,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
     constexpr int U = spmm_unroll<VEC, CH>::U;
     const int lane = threadIdx.x & 63;
     const uint32_t wave = blockIdx.x * (uint32_t)(SPMM_NT / 64) + (threadIdx.x >> 6);
-    const int32_t cap = (int32_t)min(capacity, (uint64_t)0x7fffffff);
+    const int64_t cap = (int64_t)min(capacity, (uint64_t)0x7fffffffffffffffull);
     if (wave < n_piece_waves) {
         const uint32_t total = min(*n_chunks, max_chunks);
         constexpr int PSTRIDE = CH * VEC * 64;
@@ -477,18 +500,18 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
         };
         for (uint32_t pc = wave; pc < total; pc += n_piece_waves) {
             const uint2 rc = desc[pc];
-            const int re = min(rowptr[rc.x + 1], cap);
-            const int rs = min(rowptr[rc.x], re);
-            const int plen = (int)spmm_piece_len(re - rs);
-            const int c0 = rs + (int)rc.y * plen;
-            const int c1 = min(re, c0 + plen);
+            const int64_t re = min(rp_load(rowptr, rp64, (uint64_t)rc.x + 1), cap);
+            const int64_t rs = min(rp_load(rowptr, rp64, rc.x), re);
+            const int64_t plen = spmm_piece_len(re - rs);
+            const int64_t c0 = rs + (int64_t)rc.y * plen;
+            const int64_t c1 = min(re, c0 + plen);
             float acc[CH][VEC];
 #pragma unroll
             for (int m = 0; m < CH; ++m)
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[m][i] = 0.f;
-            for (int cb = c0; cb < c1; cb += SPMM_CHUNK) {      // 64 entries at a time
-                const int n = min(c1 - cb, SPMM_CHUNK);
+            for (int64_t cb = c0; cb < c1; cb += SPMM_CHUNK) {      // 64 entries at a time
+                const int n = (int)min(c1 - cb, (int64_t)SPMM_CHUNK);
                 int32_t src = 0;
                 float a = 0.f;
                 if (lane < n) {
@@ -518,8 +541,13 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
         if (owed) { draw_ticket(); finish_row(); }
         return;
     }
-    spmm_wave_rows<VEC, CH, XT>(rows, rowptr, colidx, val, cap, X, ldx, row_index, d, wave - n_piece_waves,
-                            n_chunks ? (int)n_chunks[2] : rows_per_wave, n_chunks ? (int)n_chunks[1] : 0x7fffffff, out, ldo, ep);
+    // blocks of rows, grid-stride: the grid is capped (a launch holds fewer than 2^32 threads), a full graph
+    // of 10^8 rows has more blocks than that
+    const int rpw = n_chunks ? (int)n_chunks[2] : rows_per_wave;
+    const int long_len = n_chunks ? (int)n_chunks[1] : 0x7fffffff;
+    const uint64_t n_row_waves = (uint64_t)gridDim.x * (SPMM_NT / 64) - n_piece_waves;
+    for (uint64_t w = wave - n_piece_waves; w * (uint64_t)rpw < rows; w += n_row_waves)
+        spmm_wave_rows<VEC, CH, XT>(rows, rowptr, rp64, colidx, val, capacity, X, ldx, row_index, d, w, rpw, long_len, out, ldo, ep);
 }
 
 int build_plan(sgnn_ctx *ctx, const sgnn_csr *A, void *plan, hipStream_t st)
@@ -528,7 +556,7 @@ int build_plan(sgnn_ctx *ctx, const sgnn_csr *A, void *plan, hipStream_t st)
     const spmm_plan_view pv = plan_view(plan, A->rows, max_chunks);
     SGNN_LAUNCH(ctx, st, "spmm_plan_clear_kernel", SGNN_TAG, spmm_plan_clear_kernel, dim3(1), dim3(1), 0, st, pv.n_chunks);
     SGNN_LAUNCH(ctx, st, "spmm_plan_kernel", SGNN_TAG, spmm_plan_kernel, dim3(cdiv(A->rows, SPMM_PLAN_NT)), dim3(SPMM_PLAN_NT), 0, st, A->rows,
-                A->rowptr, A->capacity, pv.n_chunks, max_chunks, pv.part_base, pv.desc, pv.ticket);
+                A->rowptr, A->rowptr_is_i64, A->capacity, pv.n_chunks, max_chunks, pv.part_base, pv.desc, pv.ticket);
     return SGNN_OK;
 }
 
@@ -566,8 +594,9 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const XT *X, int64_t ldx, const 
         const uint64_t want = std::min<uint64_t>(std::max<uint64_t>(A->capacity / 2048, SPMM_PIECE_WAVES), 65536);
         n_piece_waves = cdiv(std::min<uint64_t>(max_chunks, want), SPMM_NT / 64) * (SPMM_NT / 64);
     }
-    SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH, XT>), dim3(n_piece_waves / (SPMM_NT / 64) + cdiv(A->rows, rows_per_block)),
-                dim3(SPMM_NT), 0, st, A->rows, A->rowptr, A->colidx, A->val, A->capacity, X, ldx, row_index, d,
+    const unsigned row_blocks = std::min<unsigned>(cdiv(A->rows, rows_per_block), 1u << 22);     // the kernel strides over the rest
+    SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH, XT>), dim3(n_piece_waves / (SPMM_NT / 64) + row_blocks),
+                dim3(SPMM_NT), 0, st, A->rows, A->rowptr, A->rowptr_is_i64, A->colidx, A->val, A->capacity, X, ldx, row_index, d,
                 n_piece_waves, pv.n_chunks, max_chunks, pv.desc, pv.ticket, part, out, ldo, ep, rows_per_wave);
     return SGNN_OK;
 }
@@ -597,7 +626,7 @@ int launch_v(sgnn_ctx *ctx, const sgnn_csr *A, const XT *X, int64_t ldx, const i
 size_t sgnn_spmm_ws_bytes(uint64_t max_entries, uint32_t B, uint32_t d_max)
 {
     // a plan built on the fly plus the partial rows, for the smallest long-row threshold
-    const size_t max_chunks = (size_t)(max_entries / SPMM_SHORT + max_entries / SPMM_CHUNK + 2);
+    const size_t max_chunks = spmm_max_chunks(B, max_entries);
     return max_chunks * (((size_t)d_max + 255) * sizeof(float) + 12) + (size_t)B * 4 + 5 * 256;
 }
 

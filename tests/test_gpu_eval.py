@@ -42,3 +42,38 @@ def test_full_graph_matrix_and_forward(i64):
         H = Y
     c.status()
     c.close()
+
+
+@pytest.mark.parametrize("d", [32, 128, 256])
+def test_sparse_product_with_int64_row_offsets(d):
+    """A matrix whose row offsets are int64 (how a full graph with 2^31 entries or more is handed in): the same
+    result, bit for bit, as with int32 offsets, with and without a plan; long rows included."""
+    rng = np.random.default_rng(5)
+    rows, cols = 500, 6000
+    lens = rng.integers(0, 6, rows)
+    lens[[3, 77, 400]] = [3000, 700, 65]
+    lists = [np.sort(rng.choice(cols, n, replace=False)).astype(np.int32) for n in lens]
+    rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    ci = np.concatenate(lists); v = rng.standard_normal(len(ci)).astype(np.float32)
+    c = sg.Context(0)
+    c.reserve(cols, len(ci), rows, d, len(ci))
+    X = torch.tensor(rng.standard_normal((cols, d)).astype(np.float32), device=DEV)
+    A32 = sg.Csr.from_arrays(rows, cols, rp, ci, v, DEV, with_plan=True)
+    sg.sgnn_csr_plan(c, A32)
+    ref = torch.zeros((rows, d), dtype=torch.float32, device=DEV)
+    sg.sgnn_spmm(c, A32, X, ref)
+    assert rel_err(ref.cpu().numpy(), oracle.spmm(rp, ci, v, X.cpu().numpy().astype(np.float64))) < TOL_F32
+    for with_plan in (False, True):
+        A64 = sg.Csr.from_arrays(rows, cols, rp, ci, v, DEV, with_plan=with_plan)
+        A64.rowptr = A64.rowptr.to(torch.int64)
+        if with_plan:
+            sg.sgnn_csr_plan(c, A64)
+        out = torch.full((rows, d), 3.0, dtype=torch.float32, device=DEV)
+        sg.sgnn_spmm(c, A64, X, out)
+        assert torch.equal(out, ref)
+    # calls that write or reorder a matrix keep int32 offsets
+    AT = sg.Csr(cols, rows, len(ci), DEV)
+    with pytest.raises(sg.SgnnError):
+        sg.sgnn_csr_transpose(c, A64, AT)
+    c.status()
+    c.close()

@@ -565,6 +565,35 @@ def test_whole_step_xlarge_bf16():
         assert rel_err(st.db[l].cpu().numpy(), ref["db"][l]) < TOL_BF16, ("db", l)
     assert abs(st.loss.item() - ref["loss"]) < TOL_BF16 * abs(ref["loss"])
 
+    # The full graph as the matrix of a sparse product (evaluation forward): 3.3 G entries, int64 row offsets,
+    # bfloat16 features.  The oracle computes sampled output rows one by one: random ones and the longest.
+    del st, ref
+    torch.cuda.empty_cache()
+    E = int(gd.colidx.numel())
+    c = sg.Context(0)
+    c.reserve(cfg.N, E, cfg.N, cfg.d_in, E)
+    A = sg.sgnn_graph_normalized_csr(c, cfg.N, gd.rowptr, gd.colidx)
+    assert A.rowptr.dtype == torch.int64 and A.rowptr.data_ptr() == gd.rowptr.data_ptr()
+    T = torch.empty((cfg.N, cfg.d_in), dtype=torch.float32, device=DEV)
+    sg.sgnn_spmm(c, A, Xd, T)
+    c.status()
+    deg = gd.rowptr[1:] - gd.rowptr[:-1]
+    rows = torch.cat([torch.randint(0, cfg.N, (48,), device=DEV, generator=torch.Generator(device=DEV).manual_seed(3)),
+                      torch.topk(deg, 4).indices, torch.tensor([0, cfg.N - 1], device=DEV)])
+    lists = [gd.colidx[int(gd.rowptr[v]):int(gd.rowptr[v + 1])].long() for v in rows.tolist()]
+    cols_all, inv = torch.unique(torch.cat(lists), return_inverse=True)
+    dv = deg[rows].double().cpu().numpy(); du_all = deg[cols_all].double().cpu().numpy()
+    lens = np.array([len(x) for x in lists]); rp_s = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    ci_s = inv.cpu().numpy().astype(np.int32)
+    v_s = (1.0 / np.sqrt(np.repeat(dv, lens) * du_all[ci_s])).astype(np.float32)      # Eq. 3, rounded once like the library's
+    X_s = Xd[cols_all].float().cpu().numpy().astype(np.float64)
+    want = oracle.spmm(rp_s, ci_s, v_s, X_s)
+    got = T[rows].cpu().numpy()
+    assert lens.max() > 100000                          # a hub row: cut into pieces, finished by the last of them
+    for i in range(len(lens)):
+        assert rel_err(got[i], want[i]) < TOL_F32, (int(rows[i]), int(lens[i]))
+    c.close()
+
 
 def test_overlapped_pipeline_matches_single_stream():
     """Building the next mini-batch on a second stream while the current one trains gives bit-identical
