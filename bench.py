@@ -161,6 +161,10 @@ def main():
         gq["ms"] += ms
         if name == "gemm_kernel":
             gq["flops"] += gemm_flops(tag) * calls
+        elif name == "gemm_skinny_bf16_kernel":
+            # tall operand streamed once, small operand resident: bound by reading A and writing C
+            m_, n_, k_ = (float(x) for x in tag.split()[2].split("x"))
+            gq["bytes"] += calls * 4.0 * (m_ * k_ + m_ * n_ + k_ * n_)
         elif name == "spmm_main_kernel":
             d = int(tag.split("d=")[1].split()[0])
             # compulsory traffic: CSR once, every input row once, the output once
@@ -171,8 +175,8 @@ def main():
     sparse_ms, sparse_bytes = sum(v["ms"] for v in sp), sum(v["bytes"] for v in sp)
     if args.breakdown:
         for name, tag, calls, ms in recs:
-            if name.startswith("spmm"):
-                print("  %-24s %-28s calls %3d  avg us %8.2f" % (name, tag, calls, 1e3 * ms / calls), file=sys.stderr)
+            if name.startswith("spmm") or name.startswith("gemm"):
+                print("  %-24s %-40s calls %3d  avg us %8.2f" % (name, tag, calls, 1e3 * ms / calls), file=sys.stderr)
         for k, v in sorted(groups.items(), key=lambda kv: -kv[1]["ms"]):
             print("%-44s calls/step %5.1f  us/step %9.2f  avg us %8.2f" %
                   (k, v["calls"] / nprof, 1e3 * v["ms"] / nprof, 1e3 * v["ms"] / v["calls"]), file=sys.stderr)

@@ -44,6 +44,7 @@ struct gemm_args {
     int relu;
     const float *mask; int64_t ldm;   // optional: C is zeroed where this M x N matrix is not positive
     int alignedA, alignedB;   // 16-byte aligned base and leading dimension a multiple of 4
+    int vecC;                 // C (and the mask, the bias) can be written / read 16 bytes at a time: aligned, N and the leading dimensions multiples of 4
     int64_t k_per_split;      // reduction range of one blockIdx.z (a multiple of BK); K when unsplit
     float *partial;           // split-K: [splits][M][N] partial products, else NULL
     uint32_t mtiles, ntiles, splits;   // the tile grid, walked by tile_of_block()
@@ -468,6 +469,130 @@ __device__ __forceinline__ void mma_slice_bf16(f32x16 (&acc)[WM / 32][WN / 32], 
     }
 }
 
+// Result tile of a wavefront (TM x TN blocks of 32 x 32, MFMA accumulator layout: lane (li, kh) holds
+// column li of rows 8 (r / 4) + 4 kh + r % 4, r = 0..15) to memory with bias / ReLU / mask.
+//   columns interleaved (B given [reduction][columns]): a lane owns TN adjacent columns: one vector store each;
+//   columns in blocks of 32 (B reduction-contiguous): a band of 32 rows goes through the wavefront's LDS slot
+//     (32 x (32 TN + 4) floats) and leaves as rows of 16 bytes per lane, the mask read the same way.
+// Without a.vecC (odd sizes, unaligned C): one element at a time.
+template <int TM, int TN, bool A_RC, bool B_RC>
+__device__ __forceinline__ void store_tile(const gemm_args &a, const f32x16 (&acc)[TM][TN], float *__restrict__ Cout, int64_t ldc,
+                                           int64_t row0, int64_t col0, int li, int kh, float *stage)
+{
+    const bool plain = a.partial != nullptr;     // partial products of a split reduction: no epilogue
+    if (!a.vecC) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t col = col0 + (B_RC ? 32 * j + li : TN * li + j);
+                if (col >= a.N) continue;
+                const float bj = (!plain && a.bias) ? a.bias[col] : 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int rho = 8 * (r / 4) + 4 * kh + (r % 4);
+                    const int64_t row = row0 + (A_RC ? 32 * i + rho : TM * rho + i);
+                    if (row < a.M) {
+                        float z = acc[i][j][r] + bj;
+                        if (!plain && a.relu) z = fmaxf(z, 0.f);
+                        if (!plain && a.mask && !(a.mask[row * a.ldm + col] > 0.f)) z = 0.f;
+                        Cout[row * ldc + col] = z;
+                    }
+                }
+            }
+        return;
+    }
+    if constexpr (!B_RC) {
+        // the lane's TN columns are adjacent
+        const int64_t col = col0 + TN * li;
+        if (col >= a.N) return;          // N is a multiple of 4 and TN divides 4: the group is wholly inside or outside
+        float bj[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bj[j] = (!plain && a.bias) ? a.bias[col + j] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            typename fvec<TN>::type m[16];
+            if (!plain && a.mask) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int rho = 8 * (r / 4) + 4 * kh + (r % 4);
+                    const int64_t row = row0 + (A_RC ? 32 * i + rho : TM * rho + i);
+                    if (row < a.M) m[r] = *reinterpret_cast<const typename fvec<TN>::type *>(a.mask + row * a.ldm + col);
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rho = 8 * (r / 4) + 4 * kh + (r % 4);
+                const int64_t row = row0 + (A_RC ? 32 * i + rho : TM * rho + i);
+                if (row >= a.M) continue;
+                typename fvec<TN>::type z;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    float t = acc[i][j][r] + bj[j];
+                    if (!plain && a.relu) t = fmaxf(t, 0.f);
+                    if (!plain && a.mask) {
+                        float mv;
+                        if constexpr (TN == 1) mv = m[r]; else mv = m[r][j];
+                        if (!(mv > 0.f)) t = 0.f;
+                    }
+                    if constexpr (TN == 1) z = t; else z[j] = t;
+                }
+                *reinterpret_cast<typename fvec<TN>::type *>(Cout + row * ldc + col) = z;
+            }
+        }
+    } else {
+        constexpr int LDW = 32 * TN + 4;          // floats per staged row: 16-byte aligned rows, banks shifted row to row
+        const int lane = li + 32 * kh;
+        float bj[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = col0 + 32 * j + li;
+            bj[j] = (!plain && a.bias && col < a.N) ? a.bias[col] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            static_assert(A_RC, "a reduction-contiguous B comes with a reduction-contiguous A");
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int rho = 8 * (r / 4) + 4 * kh + (r % 4);
+                    float t = acc[i][j][r] + bj[j];
+                    if (!plain && a.relu) t = fmaxf(t, 0.f);
+                    stage[rho * LDW + 32 * j + li] = t;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            constexpr int C4 = 8 * TN;            // groups of 4 columns per row
+            constexpr int PASSES = 32 * C4 / 64;
+            f32x4 z[PASSES], m[PASSES];
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                const int idx = p * 64 + lane, rr = idx / C4, c4 = idx % C4;
+                const int64_t row = row0 + 32 * i + rr, col = col0 + 4 * c4;
+                z[p] = *reinterpret_cast<const f32x4 *>(stage + rr * LDW + 4 * c4);
+                if (!plain && a.mask && row < a.M && col < a.N) m[p] = *reinterpret_cast<const f32x4 *>(a.mask + row * a.ldm + col);
+            }
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                const int idx = p * 64 + lane, rr = idx / C4, c4 = idx % C4;
+                const int64_t row = row0 + 32 * i + rr, col = col0 + 4 * c4;
+                if (row >= a.M || col >= a.N) continue;
+                if (!plain && a.mask) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (!(m[p][e] > 0.f)) z[p][e] = 0.f;
+                }
+                *reinterpret_cast<f32x4 *>(Cout + row * ldc + col) = z[p];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    }
+}
+
 // Pipeline: slice s+2 is fetched from memory into registers while slice s is multiplied from LDS
 // buffer s & 1; the registers are stored to the other buffer after the multiply, so there is one
 // barrier per slice.
@@ -565,25 +690,10 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
 
     float *Cout = a.partial ? a.partial + (int64_t)tb_.bz * a.M * a.N : a.C;
     const int64_t ldc = a.partial ? a.N : a.ldc;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int64_t col = n0 + wn0 + (B_RC ? 32 * j + li : TN * li + j);
-            if (col >= a.N) continue;
-            const float bj = (!a.partial && a.bias) ? a.bias[col] : 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rho = 8 * (r / 4) + 4 * kh + (r % 4);
-                const int64_t row = m0 + wm0 + (A_RC ? 32 * i + rho : TM * rho + i);
-                if (row < a.M) {
-                    float z = acc[i][j][r] + bj;
-                    if (!a.partial && a.relu) z = fmaxf(z, 0.f);
-                    if (!a.partial && a.mask && !(a.mask[row * a.ldm + col] > 0.f)) z = 0.f;
-                    Cout[row * ldc + col] = z;
-                }
-            }
-        }
+    // staging area of the epilogue (a slot per wavefront; only the block-column layout needs it)
+    __shared__ __attribute__((aligned(16))) float epi_stage[B_RC ? 4 * 32 * (32 * TN + 4) : 4];
+    float *epi_lds = epi_stage + (B_RC ? (threadIdx.x >> 6) * 32 * (32 * TN + 4) : 0);
+    store_tile<TM, TN, A_RC, B_RC>(a, acc, Cout, ldc, m0 + wm0, n0 + wn0, li, kh, epi_lds);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -749,25 +859,12 @@ __global__ __launch_bounds__(64 * DIRECT_WAVES) void gemm_direct_kernel(gemm_arg
 
     float *Cout = a.partial ? a.partial + (int64_t)tb_.bz * a.M * a.N : a.C;
     const int64_t ldc = a.partial ? a.N : a.ldc;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int64_t col = n0 + wn0 + (B_RC ? 32 * j + li : TN * li + j);
-            if (col >= a.N) continue;
-            const float bj = (!a.partial && a.bias) ? a.bias[col] : 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rho = 8 * (r / 4) + 4 * kh + (r % 4);
-                const int64_t row = m0 + wm0 + (A_RC ? 32 * i + rho : TM * rho + i);
-                if (row < a.M) {
-                    float z = acc[i][j][r] + bj;
-                    if (!a.partial && a.relu) z = fmaxf(z, 0.f);
-                    if (!a.partial && a.mask && !(a.mask[row * a.ldm + col] > 0.f)) z = 0.f;
-                    Cout[row * ldc + col] = z;
-                }
-            }
-        }
+    float *stage = nullptr;
+    if constexpr (B_RC) {
+        __syncthreads();      // every wavefront is through its last slice: the stages are free
+        stage = direct_smem + (threadIdx.x >> 6) * 32 * (32 * TN + 4);
+    }
+    store_tile<TM, TN, A_RC, B_RC>(a, acc, Cout, ldc, m0 + wm0, n0 + wn0, li, kh, stage);
 }
 
 int launch_direct(sgnn_ctx *ctx, int ta, int tb, gemm_args a, int splits, hipStream_t st)
@@ -1247,6 +1344,9 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     a.relu = (flags & SGNN_RELU) ? 1 : 0;
     a.alignedA = ((reinterpret_cast<uintptr_t>(A) & 15) == 0 && lda % 4 == 0) ? 1 : 0;
     a.alignedB = ((reinterpret_cast<uintptr_t>(B) & 15) == 0 && ldb % 4 == 0) ? 1 : 0;
+    a.vecC = ((reinterpret_cast<uintptr_t>(C) & 15) == 0 && ldc % 4 == 0 && N % 4 == 0 &&
+              (!mask || ((reinterpret_cast<uintptr_t>(mask) & 15) == 0 && ldm % 4 == 0)) &&
+              (!bias || (reinterpret_cast<uintptr_t>(bias) & 15) == 0)) ? 1 : 0;
     a.k_per_split = K;
     a.partial = nullptr;
     const int bf16 = (flags & SGNN_BF16_MFMA) ? 1 : 0;
@@ -1261,7 +1361,7 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     // twice as fine, and the partial products it writes cost more than the kernel gains.
     const int64_t a_contig = ta ? M : K, b_contig = tb ? K : N;
     const bool direct = !bf16 && !ta && a.alignedA && a.alignedB && a_contig % 4 == 0 && b_contig % 4 == 0 &&
-                        a_contig >= 4 && b_contig >= 4 && K % 32 == 0 && K >= 32 && N > 64 && M > 128;
+                        a_contig >= 4 && b_contig >= 4 && K % 32 == 0 && K >= 128 && N > 64 && M > 128;
 
     // tile shape by the width of C
     const int bn = N > 64 ? 128 : (N > 32 ? 64 : 32);
