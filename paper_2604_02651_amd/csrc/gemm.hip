@@ -1365,7 +1365,9 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
 
     // tile shape by the width of C
     const int bn = N > 64 ? 128 : (N > 32 ? 64 : 32);
-    const int bm = direct ? DIRECT_BM : (bn == 32 ? 256 : 128);
+    // narrow results: 256-row tiles, or 128-row ones when those would leave compute units without a tile
+    const bool narrow128 = bn == 32 && K < 4096 && cdiv(M, 256) < 256;
+    const int bm = direct ? DIRECT_BM : (bn == 32 ? (narrow128 ? 128 : 256) : 128);
     int splits = 1;
     const int64_t tiles = (int64_t)cdiv(M, bm) * cdiv(N, bn);
     if (tiles < 256 && K >= 4096 && !bias && !(flags & SGNN_RELU) && !mask) {
@@ -1401,6 +1403,7 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     if (direct) rc = launch_direct(ctx, ta, tb, a, splits, st);
     else if (bn == 128) rc = launch_cfg<128, 128, 64, 64>(ctx, ta, tb, bf16, a, splits, st);
     else if (bn == 64) rc = launch_cfg<128, 64, 64, 32>(ctx, ta, tb, bf16, a, splits, st);
+    else if (narrow128) rc = launch_cfg<128, 32, 32, 32>(ctx, ta, tb, bf16, a, splits, st);
     else rc = launch_cfg<256, 32, 64, 32>(ctx, ta, tb, bf16, a, splits, st);
     if (rc) return rc;
     if (splits > 1) {
