@@ -41,9 +41,9 @@ def parse_args():
     ap.add_argument("--no-fuse-slice", action="store_true")
     ap.add_argument("--no-fuse-relu-bwd", action="store_true",
                     help="separate ReLU-backward pass instead of masking inside the product that writes the input gradient")
-    ap.add_argument("--no-side-dw", action="store_true",
-                    help="keep the weight-gradient GEMMs on the main stream (default: on the second stream, concurrent "
-                         "with the rest of the backward pass)")
+    ap.add_argument("--side-dw", action="store_true",
+                    help="weight-gradient GEMMs on the second stream, concurrent with the rest of the backward pass "
+                         "(default: on the main stream - measured 1.3 % faster since the GEMM epilogues were vectorised)")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     ap.add_argument("--no-overlap", action="store_true",
                     help="everything on one stream (default: the next mini-batch is sampled on a second stream while this one trains)")
@@ -97,7 +97,7 @@ def main():
     else:
         st = sg.GcnStep(cfg.N, g.rowptr, g.colidx, X, labels, weights, cfg.B, cfg.sampler_seed, bf16=cfg.bf16_mfma,
                         fuse_slice=not args.no_fuse_slice, device=dev, fuse_relu_bwd=not args.no_fuse_relu_bwd,
-                        side_dw=not args.no_side_dw)
+                        side_dw=args.side_dw)
     period = max(cfg.steps, 1)   # the configuration's mini-batches: consecutive sampler counters
 
     use_graph = not args.no_graph and not args.no_overlap and period % 2 == 0
@@ -216,7 +216,7 @@ def main():
                                                      ("complete model %d-[%d x %d]-%d with dropout 0.1 and Adam"
                                                       % (cfg.d_in, cfg.hidden, max(cfg.layers - 1, 1), cfg.classes)) if model
                                                      else "GCN " + "-".join(map(str, cfg.dims)), period, period - 1),
-                   "fuse_slice": not args.no_fuse_slice, "fuse_relu_bwd": not args.no_fuse_relu_bwd, "side_stream_dw": not args.no_side_dw and not args.no_overlap,
+                   "fuse_slice": not args.no_fuse_slice, "fuse_relu_bwd": not args.no_fuse_relu_bwd, "side_stream_dw": args.side_dw and not args.no_overlap,
                    "overlap_sampling": not args.no_overlap, "hip_graph": use_graph,
                    "single_stream_steps_per_s": single_stream_steps_per_s, "avg_induced_entries": nnz_avg,
                    "kernel_time_us_per_step": 1e3 * total_ms / nprof},

@@ -20,7 +20,7 @@ class GcnStep:
     def __init__(self, N: int, rowptr: torch.Tensor, colidx: torch.Tensor, X: torch.Tensor, labels: torch.Tensor,
                  weights: List[Tuple[torch.Tensor, torch.Tensor]], B: int, seed: int = 0, bf16: bool = False,
                  fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None,
-                 auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = True):
+                 auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = False):
         self.N, self.B, self.seed = N, B, seed
         self.rowptr, self.colidx, self.X, self.labels = rowptr, colidx, X, labels
         self.weights = weights

@@ -604,7 +604,7 @@ def test_overlapped_pipeline_matches_single_stream():
     ld = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=DEV)
     weights = [(W.to(DEV), b.to(DEV)) for W, b in si.layer_weights(cfg)]
     a = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, weights, cfg.B, cfg.sampler_seed, device=DEV)
-    b = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, weights, cfg.B, cfg.sampler_seed, device=DEV)
+    b = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, weights, cfg.B, cfg.sampler_seed, device=DEV, side_dw=True)
     for last in (0, 1, 4, 5):
         steps = list(range(last + 1))
         b.run(steps)
@@ -616,17 +616,19 @@ def test_overlapped_pipeline_matches_single_stream():
             assert torch.equal(a.dW[l], b.dW[l]) and torch.equal(a.db[l], b.db[l]) and torch.equal(a.H[l], b.H[l])
     b.ctx.status(); b.side_ctx.status()
     # the same pipeline replayed from HIP graphs, several rounds, checked after every replay count
-    c = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, weights, cfg.B, cfg.sampler_seed, device=DEV)
-    for spg, counts in ((2, (2, 4, 6, 10)), (0, (4, 8, 12))):      # two steps a graph; the whole cycle in one graph
-        c.build_graphs(range(4), steps_per_graph=spg)
-        for n in counts:
-            c.run_graphs(n)
-            a.step((n - 1) % 4)
-            torch.cuda.synchronize()
-            assert torch.equal(a.S, c.S) and torch.equal(a.A.rowptr, c.A.rowptr) and torch.equal(a.loss, c.loss)
-            for l in range(cfg.layers):
-                assert torch.equal(a.dW[l], c.dW[l]) and torch.equal(a.db[l], c.db[l]) and torch.equal(a.H[l], c.H[l])
-    c.ctx.status(); c.side_ctx.status()
+    c = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, weights, cfg.B, cfg.sampler_seed, device=DEV, side_dw=True)
+    e = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, weights, cfg.B, cfg.sampler_seed, device=DEV)     # weight gradients on the main stream
+    for g in (c, e):
+        for spg, counts in ((2, (2, 4, 6, 10)), (0, (4, 8, 12))):      # two steps a graph; the whole cycle in one graph
+            g.build_graphs(range(4), steps_per_graph=spg)
+            for n in counts:
+                g.run_graphs(n)
+                a.step((n - 1) % 4)
+                torch.cuda.synchronize()
+                assert torch.equal(a.S, g.S) and torch.equal(a.A.rowptr, g.A.rowptr) and torch.equal(a.loss, g.loss)
+                for l in range(cfg.layers):
+                    assert torch.equal(a.dW[l], g.dW[l]) and torch.equal(a.db[l], g.db[l]) and torch.equal(a.H[l], g.H[l])
+        g.ctx.status(); g.side_ctx.status()
 
 
 @pytest.mark.parametrize("rows,cols", [(1000, 256), (77, 47), (4100, 32), (5, 1)])
