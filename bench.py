@@ -93,14 +93,13 @@ def main():
                   "W_out": si.glorot_uniform(d_h, cfg.classes, 130, device=dev).contiguous()}
         st = sg.ScaleGnnModel(cfg.N, g.rowptr, g.colidx, X, labels, params, cfg.B, sampler_seed=cfg.sampler_seed, drop_q=0.1,
                               drop_seed=1, bf16=cfg.bf16_mfma, optimizer="adam", lr=1e-3, device=dev)
-        args.no_overlap = True      # the model runs on one stream
     else:
         st = sg.GcnStep(cfg.N, g.rowptr, g.colidx, X, labels, weights, cfg.B, cfg.sampler_seed, bf16=cfg.bf16_mfma,
                         fuse_slice=not args.no_fuse_slice, device=dev, fuse_relu_bwd=not args.no_fuse_relu_bwd,
                         side_dw=args.side_dw)
     period = max(cfg.steps, 1)   # the configuration's mini-batches: consecutive sampler counters
 
-    use_graph = not args.no_graph and not args.no_overlap and period % 2 == 0
+    use_graph = not args.no_graph and not args.no_overlap and period % 2 == 0 and not model    # the model is launched eagerly
     if use_graph:
         whole = args.steps % period == 0 and args.warmup % period == 0
         st.build_graphs(range(period), steps_per_graph=0 if whole else 2)
@@ -112,7 +111,7 @@ def main():
         if args.no_overlap:
             for i in range(n):
                 st.step(i % period)
-        elif use_graph:
+        elif use_graph and not model:
             st.run_graphs(n)
         else:
             st.run([i % period for i in range(n)])

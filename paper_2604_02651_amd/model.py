@@ -22,8 +22,8 @@ class ScaleGnnModel:
                  params: Dict, B: int, sampler_seed: int = 0, drop_q: float = 0.0, drop_seed: int = 1, eps: float = 1e-6,
                  bf16: bool = False, optimizer: Optional[str] = "adam", lr: float = 1e-2, weight_decay: float = 0.0,
                  capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None):
-        """params = {"W_in": d_in x d_h, "layers": [(W_l d_h x d_h, gamma_l d_h), ...], "W_out": d_h x c}: contiguous
-        float32 device tensors, updated in place by step()."""
+        """params = {"W_in": d_in x d_h, "layers": [(W_l d_h x d_h, gamma_l d_h), ...], "W_out": d_h x c}: float32
+        device tensors with the initial values; the live parameters are self.p (same structure), updated by step()."""
         self.N, self.B = N, B
         self.rowptr, self.colidx, self.X, self.labels = rowptr, colidx, X, labels
         self.p = params
@@ -42,17 +42,15 @@ class ScaleGnnModel:
             p = (B - 1) / max(N - 1, 1)
             capacity = int(min(E, 2 * (E * p * p + B) + 16 * B + 65536))
         self.ctx.reserve(N, E, B, max(d_in, d_h, c), capacity)
-        W = (N + 63) // 64
         f32 = dict(dtype=torch.float32, device=dev)
-        self.S = torch.empty(B, dtype=torch.int32, device=dev)
-        self.bitmap = torch.empty(W, dtype=torch.int64, device=dev)
-        self.rank = torch.empty(W, dtype=torch.int32, device=dev)
-        self.A = sg.Csr(B, B, capacity, dev)
-        self.y_S = torch.empty(B, dtype=torch.int32, device=dev)
+        self.dev, self.capacity = dev, capacity
+        self._E = E
 
         def mat(d):   # B x d with rows starting 16-byte aligned
             return torch.empty((B, (d + 3) // 4 * 4), **f32)[:, :d]
-        self.X_S = mat(d_in)
+        self._mat = mat
+        self.batches = [self._new_batch()]
+        self._use(self.batches[0])
         self.Xh = [mat(d_h) for _ in range(self.L + 1)]
         self.T = [mat(d_h) for _ in range(self.L)]
         self.Z = [mat(d_h) for _ in range(self.L)]
@@ -61,23 +59,59 @@ class ScaleGnnModel:
         self.dX = [mat(d_h), mat(d_h)]
         self.dZ, self.dT = mat(d_h), mat(d_h)
         self.loss = torch.zeros(1, **f32)
-        self.g = {"W_in": torch.empty_like(params["W_in"]), "W_out": torch.empty_like(params["W_out"]),
-                  "layers": [(torch.empty_like(Wl), torch.empty_like(gl)) for Wl, gl in params["layers"]]}
-        self._pairs: List[Tuple[torch.Tensor, torch.Tensor]] = [(params["W_in"], self.g["W_in"]), (params["W_out"], self.g["W_out"])]
-        for (Wl, gl), (dWl, dgl) in zip(params["layers"], self.g["layers"]):
-            self._pairs += [(Wl, dWl), (gl, dgl)]
+        # Parameters, gradients and optimizer moments each live in ONE flat buffer (every tensor starting at a
+        # multiple of 64 floats), so that the update is a single kernel launch; self.p / self.g are views.
+        tensors = [("W_in", params["W_in"]), ("W_out", params["W_out"])]
+        for l, (Wl, gl) in enumerate(params["layers"]):
+            tensors += [(("layers", l, 0), Wl), (("layers", l, 1), gl)]
+        offs, total = [], 0
+        for _, t in tensors:
+            offs.append(total)
+            total += (t.numel() + 63) // 64 * 64
+        self.flat_p = torch.zeros(total, **f32)
+        self.flat_g = torch.zeros(total, **f32)
+        views_p, views_g = [], []
+        for (key, t), o in zip(tensors, offs):
+            vp = self.flat_p[o:o + t.numel()].view(t.shape)
+            vp.copy_(t)
+            views_p.append(vp)
+            views_g.append(self.flat_g[o:o + t.numel()].view(t.shape))
+        self.p = {"W_in": views_p[0], "W_out": views_p[1],
+                  "layers": [(views_p[2 + 2 * l], views_p[3 + 2 * l]) for l in range(self.L)]}
+        self.g = {"W_in": views_g[0], "W_out": views_g[1],
+                  "layers": [(views_g[2 + 2 * l], views_g[3 + 2 * l]) for l in range(self.L)]}
         if optimizer == "adam":
-            self.m = [torch.zeros_like(w) for w, _ in self._pairs]
-            self.v = [torch.zeros_like(w) for w, _ in self._pairs]
+            self.m = torch.zeros(total, **f32)
+            self.v = torch.zeros(total, **f32)
         elif optimizer not in (None, "sgd"):
             raise ValueError("optimizer must be 'adam', 'sgd' or None")
 
+    def _new_batch(self):
+        """Device buffers of one mini-batch: sample, bitmap, rank prefix, induced CSR, sliced features and labels."""
+        W = (self.N + 63) // 64
+        b = type("Batch", (), {})()
+        b.S = torch.empty(self.B, dtype=torch.int32, device=self.dev)
+        b.bitmap = torch.empty(W, dtype=torch.int64, device=self.dev)
+        b.rank = torch.empty(W, dtype=torch.int32, device=self.dev)
+        b.A = sg.Csr(self.B, self.B, self.capacity, self.dev)
+        b.y_S = torch.empty(self.B, dtype=torch.int32, device=self.dev)
+        b.X_S = self._mat(self.d_in)
+        b.ready, b.free = torch.cuda.Event(), torch.cuda.Event()
+        return b
+
+    def _use(self, b):
+        self.S, self.bitmap, self.rank, self.A, self.y_S, self.X_S = b.S, b.bitmap, b.rank, b.A, b.y_S, b.X_S
+
     # Algorithm 1, lines 1-4
-    def minibatch(self, t: int):
-        c = self.ctx
-        sg.sgnn_sample_uniform(c, self.N, self.B, self.sampler_seed, t, self.S, self.bitmap, self.rank)
-        sg.sgnn_induced_csr(c, self.N, self.rowptr, self.colidx, None, self.S, self.B, self.bitmap, self.rank, self.A)
-        sg.sgnn_gather_rows(c, self.X, self.S, self.B, self.X_S, self.labels, self.y_S)
+    def minibatch(self, t: int, batch=None, ctx=None, stream=None):
+        if batch is None:
+            batch = self.batches[0]
+            self._use(batch)
+        b = batch
+        c = ctx if ctx is not None else self.ctx
+        sg.sgnn_sample_uniform(c, self.N, self.B, self.sampler_seed, t, b.S, b.bitmap, b.rank, stream=stream)
+        sg.sgnn_induced_csr(c, self.N, self.rowptr, self.colidx, None, b.S, self.B, b.bitmap, b.rank, b.A, stream=stream)
+        sg.sgnn_gather_rows(c, self.X, b.S, self.B, b.X_S, self.labels, b.y_S, stream=stream)
 
     # line 5 (Sec. III-B)
     def forward(self, t: int):
@@ -112,15 +146,49 @@ class ScaleGnnModel:
         if self.optimizer is None:
             return
         self.t_opt += 1
-        for i, (w, g) in enumerate(self._pairs):
-            if self.optimizer == "sgd":
-                sg.sgnn_sgd_step(self.ctx, w, g, self.lr, self.weight_decay)
-            else:
-                sg.sgnn_adam_step(self.ctx, w, g, self.m[i], self.v[i], self.lr, self.t_opt)
+        if self.optimizer == "sgd":
+            sg.sgnn_sgd_step(self.ctx, self.flat_p, self.flat_g, self.lr, self.weight_decay)
+        else:
+            sg.sgnn_adam_step(self.ctx, self.flat_p, self.flat_g, self.m, self.v, self.lr, self.t_opt)
 
     def step(self, t: int):
         """One training step with sampler / dropout counter t; the loss stays on the device in self.loss."""
+        self._use(self.batches[0])
         self.minibatch(t)
         self.forward(t)
         self.backward(t)
         self.update()
+
+    def run(self, steps):
+        """The same steps with the mini-batch of step i+1 built on a second stream (default priority, a context
+        of its own) while step i trains (Sec. V-A of the paper): two sets of mini-batch buffers, ordered by a
+        ready and a free event per set.  Same results as step() one after the other, bit for bit."""
+        steps = list(steps)
+        if not steps:
+            return
+        if not hasattr(self, "side_stream"):
+            self.side_stream = torch.cuda.Stream(device=self.dev)
+            self.side_ctx = sg.Context(self.dev.index or 0)
+            self.side_ctx.reserve(self.N, self._E, self.B, max(self.d_in, self.d_h, self.c), self.capacity)
+            self.batches.append(self._new_batch())
+        main, side = torch.cuda.current_stream(), self.side_stream
+        start = torch.cuda.Event()
+        start.record(main)
+        side.wait_event(start)          # whatever used the buffers before has finished
+        self.minibatch(steps[0], self.batches[0], self.side_ctx, side)
+        self.batches[0].ready.record(side)
+        for i, t in enumerate(steps):
+            b = self.batches[i % 2]
+            if i + 1 < len(steps):
+                nb = self.batches[(i + 1) % 2]
+                if i >= 1:
+                    side.wait_event(nb.free)    # the training of step i-1 has let go of that set
+                self.minibatch(steps[i + 1], nb, self.side_ctx, side)
+                nb.ready.record(side)
+            main.wait_event(b.ready)
+            self._use(b)
+            self.forward(t)
+            self.backward(t)
+            self.update()
+            b.free.record(main)
+        main.wait_stream(side)

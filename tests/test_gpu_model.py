@@ -135,6 +135,25 @@ def test_sgd_training_follows_the_oracle_for_a_few_steps():
     assert rel_err(mdl.p["layers"][0][0].cpu().numpy(), pn["layers"][0][0]) < 1e-4
 
 
+def test_overlapped_training_matches_step_by_step():
+    # the mini-batch of step t+1 built on a second stream while step t trains: the same parameters, bit for bit,
+    # after more steps than there are buffer sets, twice in a row
+    cfg, gd, Xd, ld, params = _model_inputs(seed=3)
+    kw = dict(sampler_seed=5, drop_q=0.1, drop_seed=3, optimizer="adam", lr=1e-3, device=DEV)
+    a = sg.ScaleGnnModel(cfg.N, gd.rowptr, gd.colidx, Xd, ld, _to_dev(params), cfg.B, **kw)
+    b = sg.ScaleGnnModel(cfg.N, gd.rowptr, gd.colidx, Xd, ld, _to_dev(params), cfg.B, **kw)
+    for first, n in ((0, 5), (5, 4)):
+        for t in range(first, first + n):
+            a.step(t)
+        b.run(range(first, first + n))
+        torch.cuda.synchronize()
+        assert torch.equal(a.loss, b.loss)
+        assert torch.equal(a.p["W_in"], b.p["W_in"]) and torch.equal(a.p["W_out"], b.p["W_out"])
+        for (Wa, ga), (Wb, gb) in zip(a.p["layers"], b.p["layers"]):
+            assert torch.equal(Wa, Wb) and torch.equal(ga, gb)
+    a.ctx.status(); b.ctx.status(); b.side_ctx.status()
+
+
 def test_training_reduces_the_loss():
     # a few hundred Adam steps on a synthetic task (labels = arg max of fixed random projections of the features)
     cfg, gd, Xd, ld, params = _model_inputs(seed=2)
