@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--side-dw", action="store_true",
                     help="weight-gradient GEMMs on the second stream, concurrent with the rest of the backward pass "
                          "(default: on the main stream - measured 1.3 % faster since the GEMM epilogues were vectorised)")
+    ap.add_argument("--fork", default="mid", choices=["mid", "start"],
+                    help="where a captured step forks the next mini-batch's construction: after its first layer, "
+                         "rejoining before its last backward call (mid), or around the whole step (start)")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     ap.add_argument("--no-overlap", action="store_true",
                     help="everything on one stream (default: the next mini-batch is sampled on a second stream while this one trains)")
@@ -102,7 +105,7 @@ def main():
     use_graph = not args.no_graph and not args.no_overlap and period % 2 == 0 and not model    # the model is launched eagerly
     if use_graph:
         whole = args.steps % period == 0 and args.warmup % period == 0
-        st.build_graphs(range(period), steps_per_graph=0 if whole else 2)
+        st.build_graphs(range(period), steps_per_graph=0 if whole else 2, fork=args.fork)
         if not whole and (args.steps % 2 or args.warmup % 2):
             print("bench.py: with HIP graphs --steps and --warmup must be even", file=sys.stderr)
             sys.exit(2)

@@ -619,8 +619,9 @@ def test_overlapped_pipeline_matches_single_stream():
     c = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, weights, cfg.B, cfg.sampler_seed, device=DEV, side_dw=True)
     e = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, weights, cfg.B, cfg.sampler_seed, device=DEV)     # weight gradients on the main stream
     for g in (c, e):
-        for spg, counts in ((2, (2, 4, 6, 10)), (0, (4, 8, 12))):      # two steps a graph; the whole cycle in one graph
-            g.build_graphs(range(4), steps_per_graph=spg)
+        # two steps a graph; the whole cycle in one graph; the side branch forked mid-step or at the step's start
+        for spg, fork, counts in ((2, "mid", (2, 4, 6, 10)), (0, "mid", (4, 8, 12)), (0, "start", (4, 8))):
+            g.build_graphs(range(4), steps_per_graph=spg, fork=fork)
             for n in counts:
                 g.run_graphs(n)
                 a.step((n - 1) % 4)
