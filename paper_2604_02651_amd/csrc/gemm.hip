@@ -1239,6 +1239,186 @@ int launch_skinny(sgnn_ctx *ctx, const gemm_args &a, int tb, hipStream_t st)
     return launch_skinny_t<false>(ctx, a, tb, none, st);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Thin products of the classifier layer (one dimension of 32 or less), fp32.  At these shapes the tile
+// kernels are bound by the latency of their few staging rounds, not by arithmetic or bandwidth: here
+// every operand goes from global memory straight into the register layout of v_mfma_f32_32x32x2_f32
+// (lane (li, kh) supplies element (li, kh) of a 32 x 2 operand), with all loads of a wavefront in
+// flight at once and several wavefronts per SIMD.
+//
+// gemm_thin_tn_kernel: C = A^T B, A given K x M, B given K x N with N <= 32, K long (the weight
+// gradient of a narrow layer, Eq. 24).  A workgroup takes 128 columns of A^T B's rows (blockIdx.y)
+// and one reduction range (blockIdx.x), split evenly over its eight wavefronts.  Per pair of
+// reduction steps a lane loads 16 bytes of A (its four columns 4 li .. 4 li + 3 of row k + kh: one
+// value for each of the four 32 x 32 tiles, whose row i is thus column 4 i + j of A) and one value of
+// B.  The eight partial results are added in LDS in a fixed order and written as one split-K partial
+// product (the caller sums those with splitk_reduce_kernel); the column sums of B go the same way.
+// ---------------------------------------------------------------------------------------------
+constexpr int THIN_WAVES = 8, THIN_PAIRS = 16;   // wavefronts per workgroup; pairs of reduction steps per pass
+template <bool GATHER>
+__global__ __launch_bounds__(64 * THIN_WAVES) void gemm_thin_tn_kernel(gemm_args a)
+{
+    __shared__ __attribute__((aligned(16))) float red[4][128 * 32];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, li = lane & 31, kh = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.y * 128;
+    const int64_t kbeg = (int64_t)blockIdx.x * a.k_per_split;
+    const int64_t kend = min(a.K, kbeg + a.k_per_split);
+    const int64_t kw = a.k_per_split / THIN_WAVES;          // a multiple of 2
+    const int64_t k0 = kbeg + wave * kw, k1 = min(kend, k0 + kw);
+    const int64_t mcol = m0 + 4 * li;
+    const bool mok = mcol < a.M, nok = li < a.N;
+    f32x16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    float cs = 0.f;
+    for (int64_t k = k0; k < k1; k += 2 * THIN_PAIRS) {
+        // every load is issued unconditionally at a clamped (valid) address and zeroed afterwards where it is
+        // out of range (a load under a branch would be waited for before the next one is issued), and all of
+        // a pass are requested before its first multiply (the scheduling barrier keeps them there)
+        f32x4 av[THIN_PAIRS];
+        float bv[THIN_PAIRS];
+        int64_t ar[THIN_PAIRS];
+#pragma unroll
+        for (int s = 0; s < THIN_PAIRS; ++s) {
+            const int64_t kc = min(k + 2 * s + kh, k1 - 1);
+            ar[s] = GATHER ? (int64_t)a.a_row_index[kc] : kc;
+        }
+#pragma unroll
+        for (int s = 0; s < THIN_PAIRS; ++s) {
+            av[s] = *reinterpret_cast<const f32x4 *>(a.A + ar[s] * a.lda + (mok ? mcol : 0));
+            bv[s] = a.B[min(k + 2 * s + kh, k1 - 1) * a.ldb + (nok ? li : 0)];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < THIN_PAIRS; ++s) {
+            const bool ok = k + 2 * s + kh < k1;
+            const float y = (ok && nok) ? bv[s] : 0.f;
+            cs += y;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float x = (ok && mok) ? av[s][j] : 0.f;
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[j], 0, 0, 0);
+            }
+        }
+    }
+    // acc[j][r] is the element (row 4 rho + j of the 128, column li); tree sum over the wavefronts in LDS:
+    // (w, w + 4) -> w, then (w, w + 2) -> w, then (0, 1) -> 0, each a fixed order of additions
+#pragma unroll
+    for (int half = THIN_WAVES / 2; half >= 1; half >>= 1) {
+        if (wave >= half && wave < 2 * half) {
+            float *dst = red[wave - half];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dst[(4 * (8 * (r / 4) + 4 * kh + (r % 4)) + j) * 32 + li] = acc[j][r];
+        }
+        __syncthreads();
+        if (wave < half) {
+            const float *src = red[wave];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[j][r] += src[(4 * (8 * (r / 4) + 4 * kh + (r % 4)) + j) * 32 + li];
+        }
+        __syncthreads();
+    }
+    cs += __shfl_xor(cs, 32);
+    if (a.colsum && blockIdx.y == 0) {
+        float *cs_red = red[0];       // free again: the tree sum ended with a barrier
+        if (kh == 0) cs_red[wave * 32 + li] = cs;
+        __syncthreads();
+        if (wave == 0 && kh == 0 && nok) {
+            float t = 0.f;
+#pragma unroll
+            for (int w = 0; w < THIN_WAVES; ++w) t += cs_red[w * 32 + li];
+            a.colsum[(int64_t)blockIdx.x * a.N + li] = t;
+        }
+    }
+    if (wave == 0 && nok) {
+        float *out = a.partial + (int64_t)blockIdx.x * a.M * a.N;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = m0 + 4 * (8 * (r / 4) + 4 * kh + (r % 4)) + j;
+                if (row < a.M) out[row * a.N + li] = acc[j][r];
+            }
+    }
+}
+
+// gemm_smallk_nt_kernel: C = epilogue(A B^T), A given M x K, B given N x K, K <= 64 a multiple of 4
+// (the gradient with respect to the input of a narrow layer, Eq. 22).  A wavefront computes 32 rows
+// by 64 columns; the four wavefronts of a workgroup share the rows.  The reduction index is dealt to
+// the two halves of the wavefront in two contiguous runs (lanes kh = 0 take k < 4 Q, the others the
+// rest: any pairing of reduction steps gives the same sum up to rounding order), so that a lane reads
+// its operand rows 16 bytes at a time with no element unused.  Q = 16-byte chunks per lane and row.
+template <int Q>
+__global__ __launch_bounds__(256) void gemm_smallk_nt_kernel(gemm_args a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, li = lane & 31, kh = lane >> 5;
+    const int64_t r0 = (int64_t)blockIdx.x * 32;
+    const int64_t n0 = (int64_t)blockIdx.y * 256 + 64 * wave;
+    if (n0 >= a.N) return;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    // every load is issued unconditionally at a clamped (valid) address and zeroed afterwards where it is out of
+    // range: a load under a branch would be waited for before the next one is issued
+    f32x4 av[Q], bv[2][Q];
+    const int64_t arow = min(r0 + li, a.M - 1);
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int64_t k = 4 * (Q * kh + q);
+        const bool kok = k < a.K;
+        const int64_t kc = kok ? k : 0;
+        const f32x4 x = *reinterpret_cast<const f32x4 *>(a.A + arow * a.lda + kc);
+        av[q] = kok ? x : zero4;           // rows beyond M compute values that are never stored
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int64_t n = min(n0 + 32 * t + li, a.N - 1);
+            const f32x4 y = *reinterpret_cast<const f32x4 *>(a.B + n * a.ldb + kc);
+            bv[t][q] = kok ? y : zero4;    // as are columns beyond N
+        }
+    }
+    // the mask values of the lane's results, requested before the multiplies
+    float mk[2][16];
+    if (a.mask) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = min(r0 + 8 * (r / 4) + 4 * kh + (r % 4), a.M - 1), col = min(n0 + 32 * t + li, a.N - 1);
+                mk[t][r] = a.mask[row * a.ldm + col];
+            }
+    }
+    f32x16 acc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][e], bv[t][q][e], acc[t], 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int64_t col = n0 + 32 * t + li;
+        if (col >= a.N) continue;
+        const float bj = a.bias ? a.bias[col] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = r0 + 8 * (r / 4) + 4 * kh + (r % 4);
+            if (row >= a.M) continue;
+            float z = acc[t][r] + bj;
+            if (a.relu) z = fmaxf(z, 0.f);
+            if (a.mask && !(mk[t][r] > 0.f)) z = 0.f;
+            a.C[row * a.ldc + col] = z;
+        }
+    }
+}
+
 // Sum of the split-K partial products in a fixed order (bit-reproducible).
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t MN,
                                                             int64_t N, float *__restrict__ C, int64_t ldc,
@@ -1355,6 +1535,45 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     // tall A times a small B on the bf16 path: stream A once with B resident in LDS
     if (bf16 && !ta && K >= 1 && K <= 256 && N >= 1 && N <= 256 && M >= 4096 && a.alignedA)
         return launch_skinny(ctx, a, tb, st);
+
+    // classifier-width products, fp32: straight from global memory into the MFMA operand layout
+    if (!bf16 && !ta && tb && !a_row_index && K >= 4 && K <= 64 && K % 4 == 0 && a.alignedA && a.alignedB && M >= 1 && N >= 1 &&
+        M <= (int64_t)0x7fffffff * 32 && N <= (int64_t)65535 * 256) {
+        if (b_colsum) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: column sums of B go with A^T B only");
+        char tag[56];
+        snprintf(tag, sizeof(tag), "NT smallk %lldx%lldx%lld f32", (long long)M, (long long)N, (long long)K);
+        dim3 grid((unsigned)cdiv(M, 32), (unsigned)cdiv(N, 256)), block(256);
+        const int q = (int)cdiv(K, 8);
+        if (q <= 1)      { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, gemm_smallk_nt_kernel<1>, grid, block, 0, st, a); }
+        else if (q <= 2) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, gemm_smallk_nt_kernel<2>, grid, block, 0, st, a); }
+        else if (q <= 4) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, gemm_smallk_nt_kernel<4>, grid, block, 0, st, a); }
+        else             { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, gemm_smallk_nt_kernel<8>, grid, block, 0, st, a); }
+        return SGNN_OK;
+    }
+    if (!bf16 && ta && !tb && N >= 1 && N <= 32 && K >= 4096 && M >= 4 && M % 4 == 0 && a.alignedA && !bias && !(flags & SGNN_RELU) &&
+        !mask && M <= (int64_t)65535 * 128) {
+        // reduction ranges of 16 steps per wavefront and pass, at most 256 of them
+        int64_t splits = cdiv(K, (int64_t)2 * THIN_PAIRS * THIN_WAVES);
+        if (splits > 256) splits = 256;
+        const int64_t unit = 2 * THIN_WAVES;
+        const int64_t kps = cdiv(cdiv(K, splits), unit) * unit;
+        splits = cdiv(K, kps);
+        a.k_per_split = kps;
+        a.splits = (uint32_t)splits;
+        a.partial = ws->get<float>((size_t)splits * M * N);
+        float *cs_part = b_colsum ? ws->get<float>((size_t)splits * N) : nullptr;
+        if (!ws->ok)
+            return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gemm: scratch too small for the split reduction: call sgnn_ctx_reserve");
+        a.colsum = cs_part;
+        char tag[56];
+        snprintf(tag, sizeof(tag), "TN thin %lldx%lldx%lld f32", (long long)M, (long long)N, (long long)K);
+        const dim3 grid((unsigned)splits, (unsigned)cdiv(M, 128)), block(64 * THIN_WAVES);
+        if (a_row_index) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, gemm_thin_tn_kernel<true>, grid, block, 0, st, a); }
+        else             { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, gemm_thin_tn_kernel<false>, grid, block, 0, st, a); }
+        SGNN_LAUNCH(ctx, st, "splitk_reduce_kernel", SGNN_TAG, splitk_reduce_kernel, dim3(cdiv(M * N + (cs_part ? N : 0), 256)),
+                    dim3(256), 0, st, a.partial, (int)splits, M * N, N, C, ldc, cs_part, b_colsum);
+        return SGNN_OK;
+    }
 
     // wide fp32 results with whole chunks and whole slices: the direct-to-LDS kernel, 256 x 128 tiles.  Not for
     // the long reductions onto a small result (T^T dZ): with two 256 x 128 tiles the split would have to be

@@ -284,6 +284,42 @@ def test_gemm_weight_gradient_with_column_sums(M, N, K, bf16):
         sg.sgnn_gemm(ctx(), False, False, dev(At.T.copy()), dev(Bm), None, flags, C2, b_colsum=cs2)
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 32, 32768), (100, 7, 4129), (132, 32, 5000), (260, 20, 70001), (4, 1, 4096),
+                                   (128, 32, 9000)])
+def test_gemm_fp32_narrow_weight_gradient(M, N, K):
+    # A^T B with a result of classifier width (at most 32 columns) and a long reduction: operands go from memory
+    # straight into the matrix-core layout; ragged in every dimension, with and without the column sums of B
+    ctx().reserve(1, 1, 70001, 272)
+    At = _rand((K, M + 4), 41)[:, :M]; Bm = _rand((K, N + 1), 42)[:, :N]
+    C = torch.full((M, N), 3.0, dtype=torch.float32, device=DEV); cs = torch.full((N,), 9.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), True, False, dev(_rand((K, M + 4), 41))[:, :M], dev(_rand((K, N + 1), 42))[:, :N], None, 0, C, b_colsum=cs)
+    ref = oracle.gemm(At.T.copy(), Bm.copy())
+    assert rel_err(C.cpu().numpy(), ref) < TOL_F32
+    # a sum of thousands of signed terms cancels: the error is measured against the sum of their magnitudes
+    B64 = Bm.astype(np.float64)
+    assert np.abs(cs.cpu().numpy() - B64.sum(axis=0)).max() < TOL_F32 * np.abs(B64).sum(axis=0).max()
+    C2 = torch.zeros_like(C)
+    sg.sgnn_gemm(ctx(), True, False, dev(_rand((K, M + 4), 41))[:, :M], dev(_rand((K, N + 1), 42))[:, :N], None, 0, C2)
+    assert torch.equal(C, C2)
+
+
+@pytest.mark.parametrize("M,N,K", [(32768, 256, 32), (1000, 70, 4), (77, 300, 64), (5000, 33, 20), (31, 256, 8), (4100, 520, 48)])
+def test_gemm_fp32_short_reduction(M, N, K):
+    # A B^T with a reduction of classifier length (at most 64): every epilogue, ragged rows and columns
+    A = _rand((M, K), 43); Bt = _rand((N, K), 44); bias = _rand(N, 45)
+    mask = np.maximum(_rand((M, N), 46), 0.0)
+    C = torch.full((M, N + 4), 7.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), False, True, dev(A), dev(Bt), None, 0, C[:, :N])
+    prod = oracle.gemm(A, Bt.T.copy())
+    assert rel_err(C[:, :N].cpu().numpy(), prod) < TOL_F32
+    assert torch.all(C[:, N:] == 7.0)
+    sg.sgnn_gemm(ctx(), False, True, dev(A), dev(Bt), dev(bias), sg.SGNN_RELU, C[:, :N])
+    assert rel_err(C[:, :N].cpu().numpy(), np.maximum(prod + bias, 0)) < TOL_F32
+    sg.sgnn_gemm(ctx(), False, True, dev(A), dev(Bt), None, 0, C[:, :N], mask=dev(mask))
+    assert rel_err(C[:, :N].cpu().numpy(), np.where(mask > 0, prod, 0.0)) < TOL_F32
+    assert torch.all(C[:, :N][dev(mask) <= 0] == 0)
+
+
 def test_gemm_fp32_weight_gradient_shape():
     # dW = T^T dZ of the headline workload: 256 x 256 result, reduction over 32768 rows, split and summed in a fixed order
     K, M, N = 32768, 256, 256
@@ -486,6 +522,17 @@ def test_whole_step_with_a_narrowing_first_layer():
         _run_config("tiny_narrow", [1], False)
     finally:
         del si.CONFIGS["tiny_narrow"]
+
+
+def test_whole_step_with_narrow_layers_and_a_long_batch():
+    # two narrowing layers (32 -> 16 -> 8) over 6000 sampled vertices: both weight gradients are long reductions onto
+    # results of at most 16 columns, the first one reading the feature rows through row_index = S
+    si.CONFIGS["narrow_long"] = si.Config("narrow_long", 16384, 131072, 32, 16, 2, 8, 6000)
+    try:
+        _run_config("narrow_long", [0], True)
+        _run_config("narrow_long", [1], False)
+    finally:
+        del si.CONFIGS["narrow_long"]
 
 
 def test_whole_step_tiny_bf16():
