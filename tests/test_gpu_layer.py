@@ -285,21 +285,23 @@ def test_gemm_weight_gradient_with_column_sums(M, N, K, bf16):
 
 
 @pytest.mark.parametrize("M,N,K", [(256, 32, 32768), (100, 7, 4129), (132, 32, 5000), (260, 20, 70001), (4, 1, 4096),
-                                   (128, 32, 9000)])
+                                   (128, 32, 9000), (256, 64, 8192), (132, 100, 5001), (512, 256, 4096), (260, 34, 4500),
+                                   (128, 256, 32768)])
 def test_gemm_fp32_narrow_weight_gradient(M, N, K):
-    # A^T B with a result of classifier width (at most 32 columns) and a long reduction: operands go from memory
+    # A^T B with a small result (a few tiles of 128 x 32 or 128 x 64) and a long reduction: operands go from memory
     # straight into the matrix-core layout; ragged in every dimension, with and without the column sums of B
     ctx().reserve(1, 1, 70001, 272)
-    At = _rand((K, M + 4), 41)[:, :M]; Bm = _rand((K, N + 1), 42)[:, :N]
+    pad = 1 if N <= 32 else 4          # wider results need 16-byte aligned rows of B, narrow ones take any
+    At = _rand((K, M + 4), 41)[:, :M]; Bm = _rand((K, N + pad), 42)[:, :N]
     C = torch.full((M, N), 3.0, dtype=torch.float32, device=DEV); cs = torch.full((N,), 9.0, dtype=torch.float32, device=DEV)
-    sg.sgnn_gemm(ctx(), True, False, dev(_rand((K, M + 4), 41))[:, :M], dev(_rand((K, N + 1), 42))[:, :N], None, 0, C, b_colsum=cs)
+    sg.sgnn_gemm(ctx(), True, False, dev(_rand((K, M + 4), 41))[:, :M], dev(_rand((K, N + pad), 42))[:, :N], None, 0, C, b_colsum=cs)
     ref = oracle.gemm(At.T.copy(), Bm.copy())
     assert rel_err(C.cpu().numpy(), ref) < TOL_F32
     # a sum of thousands of signed terms cancels: the error is measured against the sum of their magnitudes
     B64 = Bm.astype(np.float64)
     assert np.abs(cs.cpu().numpy() - B64.sum(axis=0)).max() < TOL_F32 * np.abs(B64).sum(axis=0).max()
     C2 = torch.zeros_like(C)
-    sg.sgnn_gemm(ctx(), True, False, dev(_rand((K, M + 4), 41))[:, :M], dev(_rand((K, N + 1), 42))[:, :N], None, 0, C2)
+    sg.sgnn_gemm(ctx(), True, False, dev(_rand((K, M + 4), 41))[:, :M], dev(_rand((K, N + pad), 42))[:, :N], None, 0, C2)
     assert torch.equal(C, C2)
 
 
