@@ -106,7 +106,7 @@ __device__ __forceinline__ int64_t readlane64(int64_t v, int lane)
 }
 
 constexpr int SPMM_NT = 256;       // threads of a workgroup
-constexpr int SPMM_SHORT = 32;     // smallest length from which a row counts as long
+constexpr int SPMM_SHORT = 8;      // smallest length from which a row counts as long
 constexpr int SPMM_CHUNK = 64;     // entries per piece of a long row: what one wavefront fetches at once
 constexpr int SPMM_MAX_PIECES = 256;   // pieces per row: longer rows get longer pieces
 
@@ -158,10 +158,11 @@ __host__ __device__ inline int spmm_rows_per_wave(uint32_t rows, uint64_t entrie
 
 inline uint32_t spmm_max_chunks(uint32_t rows, uint64_t capacity)
 {
-    // a long row has more than SPMM_SHORT entries whatever the mean is: at most capacity / SPMM_SHORT
-    // of them, each with at most one partly filled chunk, plus the full chunks
-    (void)rows;
-    const uint64_t n = capacity / SPMM_SHORT + capacity / SPMM_CHUNK + 2;
+    // a long row has more than SPMM_SHORT entries whatever the mean is, and more than four times the
+    // mean (rounded down, so at least twice the exact mean once there is an entry per row): at most
+    // capacity / SPMM_SHORT of them and at most half the rows, each with at most one partly filled
+    // chunk, plus the full chunks
+    const uint64_t n = std::min<uint64_t>(capacity / SPMM_SHORT, (uint64_t)rows / 2 + 1) + capacity / SPMM_CHUNK + 2;
     // and no more than 65536 long rows (spmm_long_len) of at most SPMM_MAX_PIECES pieces each
     return (uint32_t)std::min<uint64_t>(n, (uint64_t)65536 * SPMM_MAX_PIECES + 2);
 }
@@ -400,7 +401,7 @@ __device__ __forceinline__ void spmm_wave_entries(float (&acc)[CH][VEC], int32_t
     }
 }
 
-template <int VEC, int CH> struct spmm_unroll { static constexpr int U = CH * VEC <= 4 ? 8 : (CH * VEC <= 8 ? 4 : 2); };
+template <int VEC, int CH> struct spmm_unroll { static constexpr int U = CH * VEC <= 1 ? 16 : (CH * VEC <= 4 ? 8 : (CH * VEC <= 8 ? 4 : 2)); };
 
 // Wavefronts [0, n_piece_waves) take pieces of long rows (grid-stride over the pieces the plan
 // lists) and write one partial row per piece; the others take blocks of rows_per_wave rows.
@@ -520,6 +521,19 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
                     src = row_index ? row_index[c] : c;
                 }
                 spmm_wave_entries<VEC, CH, U, XT>(acc, src, a, n, X, ldx, d, lane, [](int) { return true; });
+            }
+            if (re - rs <= plen) {
+                // the row's only piece: it is the row, written as the row-block wavefronts write theirs
+                float *orow = out + (int64_t)rc.x * ldo;
+#pragma unroll
+                for (int m = 0; m < CH; ++m) {
+                    const int col = (m * 64 + lane) * VEC;
+                    if (col < d) {
+                        spmm_epilogue<VEC>(acc[m], ep, (int64_t)rc.x, col);
+                        vstore<VEC>(orow + col, acc[m]);
+                    }
+                }
+                continue;
             }
             if (drawn) finish_row();
             if (owed) draw_ticket();
