@@ -309,9 +309,11 @@ int sgnn_tail_bwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *inv_rms, const 
 /*
  * Mean softmax cross-entropy over B rows of C logits (Sec. III-B, single-label loss) and its
  * gradient dO = (softmax(O) - onehot(label)) / B.  loss_dev: device float[1] or NULL.
+ * dO_colsum: device float[C] or NULL (needs dO): the column sums of dO, i.e. the bias gradient of a
+ * last layer without activation (Sec. III-C), from the same pass and in a fixed summation order.
  */
 int sgnn_softmax_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B,
-                      uint32_t C, float *loss_dev, float *dO, int64_t lddo, sgnn_stream stream);
+                      uint32_t C, float *loss_dev, float *dO, int64_t lddo, float *dO_colsum, sgnn_stream stream);
 
 /*
  * Mean binary cross-entropy on logits over the B x C entries, the paper's loss for multi-label tasks

@@ -400,11 +400,14 @@ def sgnn_tail_bwd(ctx: Context, Z: torch.Tensor, inv_rms: torch.Tensor, gamma: O
 
 
 def sgnn_softmax_xent(ctx: Context, O: torch.Tensor, labels: torch.Tensor, loss: Optional[torch.Tensor],
-                      dO: Optional[torch.Tensor], stream=None):
+                      dO: Optional[torch.Tensor], stream=None, dO_colsum: Optional[torch.Tensor] = None):
+    """dO_colsum: optional float[C], receives the column sums of dO (the bias gradient of a last layer without activation)."""
+    if dO_colsum is not None and dO_colsum.numel() != O.shape[1]:
+        raise ValueError("dO_colsum must have one element per class")
     ctx.check(lib().sgnn_softmax_xent(ctx._h, _ptr(O, torch.float32, "O"), O.stride(0), _ptr(labels, torch.int32, "labels"),
                                       O.shape[0], O.shape[1], _ptr(loss, torch.float32, "loss"),
                                       _ptr(dO, torch.float32, "dO"), dO.stride(0) if dO is not None else 0,
-                                      _stream(stream)))
+                                      _ptr(dO_colsum, torch.float32, "dO_colsum"), _stream(stream)))
 
 
 def sgnn_spmm(ctx: Context, A: Csr, X: torch.Tensor, out: torch.Tensor, row_index: Optional[torch.Tensor] = None,

@@ -606,15 +606,15 @@ int sgnn_copy_f32(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, sgnn_s
 }
 
 int sgnn_softmax_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C,
-                      float *loss_dev, float *dO, int64_t lddo, sgnn_stream stream)
+                      float *loss_dev, float *dO, int64_t lddo, float *dO_colsum, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
-    if (!O || !labels || B == 0 || C == 0 || ldo < C || (dO && lddo < C))
+    if (!O || !labels || B == 0 || C == 0 || ldo < C || (dO && lddo < C) || (dO_colsum && !dO))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_softmax_xent: bad argument");
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_xent(ctx, O, ldo, labels, B, C, loss_dev, dO, lddo, &ws, static_cast<hipStream_t>(stream));
+    return sgnn_launch_xent(ctx, O, ldo, labels, B, C, loss_dev, dO, lddo, dO_colsum, &ws, static_cast<hipStream_t>(stream));
 }
 
 } // extern "C"

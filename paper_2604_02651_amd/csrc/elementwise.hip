@@ -125,14 +125,20 @@ __global__ __launch_bounds__(1024) void colsum_final_kernel(const float *__restr
 }
 
 // A group of lpr lanes (a power of two >= C, at most 64) owns a row and keeps it in registers
-// (NX values a lane: C <= 64 * NX); a workgroup covers 4 * 256 / lpr rows and writes one partial loss.
+// (NX values a lane: C <= 64 * NX); a workgroup covers 4 * 256 / lpr rows and writes one partial loss
+// and, if asked, its column sums of dO (the bias gradient of a last layer without activation):
+// cs_partial[workgroup][C], summed over its rows in a fixed order.
 template <int NX>
 __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, int64_t ldo,
                                                    const int32_t *__restrict__ labels, uint32_t B, uint32_t C,
                                                    int lpr_log2, float *__restrict__ dO, int64_t lddo,
-                                                   float *__restrict__ partial)
+                                                   float *__restrict__ partial, float *__restrict__ cs_partial)
 {
     __shared__ float lds[4];
+    __shared__ float cs_lds[4][64 * NX];
+    float csum[NX];
+#pragma unroll
+    for (int t = 0; t < NX; ++t) csum[t] = 0.f;
     const int lpr = 1 << lpr_log2;
     const uint32_t rows_per_pass = 256u >> lpr_log2;
     const uint32_t gq = threadIdx.x >> lpr_log2, g = threadIdx.x & (lpr - 1);
@@ -170,25 +176,65 @@ __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, 
 #pragma unroll
                 for (int t = 0; t < NX; ++t) {
                     const uint32_t j = g + t * lpr;
-                    if (j < C) dO[(int64_t)row * lddo + j] = (x[t] * inv_sum - ((int32_t)j == y ? 1.f : 0.f)) * invB;
+                    if (j < C) {
+                        const float dv = (x[t] * inv_sum - ((int32_t)j == y ? 1.f : 0.f)) * invB;
+                        dO[(int64_t)row * lddo + j] = dv;
+                        csum[t] += dv;
+                    }
                 }
             }
         }
     }
     loss = wave_sum(loss);
     if (lane_id() == 0) lds[threadIdx.x >> 6] = loss;
+    if (cs_partial) {
+        // lanes of a wavefront with the same position in their group hold the same columns
+#pragma unroll
+        for (int t = 0; t < NX; ++t) {
+            for (int sft = lpr; sft < 64; sft <<= 1) csum[t] += __shfl_xor(csum[t], sft, 64);
+            if ((int)lane_id() < lpr) cs_lds[threadIdx.x >> 6][t * lpr + g] = csum[t];
+        }
+    }
     __syncthreads();
     if (threadIdx.x == 0) partial[blockIdx.x] = (lds[0] + lds[1]) + (lds[2] + lds[3]);
+    if (cs_partial) {
+        for (int i = threadIdx.x; i < NX * lpr; i += 256) {
+            const uint32_t j = (uint32_t)i;           // slot t * lpr + g holds column g + t * lpr
+            if (j < C) cs_partial[(int64_t)blockIdx.x * C + j] = (cs_lds[0][i] + cs_lds[1][i]) + (cs_lds[2][i] + cs_lds[3][i]);
+        }
+    }
 }
 
+// Workgroup 0: the mean loss from the partial losses.  Workgroups 1 ..: 64 columns each of the column sums of
+// dO, from the partial sums of the loss kernel's workgroups, added as colsum_final_kernel adds its partial sums.
 __global__ __launch_bounds__(1024) void xent_final_kernel(const float *__restrict__ partial, int n, float invB,
-                                                          float *__restrict__ loss)
+                                                          float *__restrict__ loss, const float *__restrict__ cs_partial,
+                                                          int cols, float *__restrict__ colsum)
 {
-    __shared__ float lds[1024 / 64];
+    __shared__ float lds[1024];
+    if (blockIdx.x == 0) {
+        if (!loss) return;
+        float s = 0.f;
+        for (int i = threadIdx.x; i < n; i += 1024) s += partial[i];
+        s = block_sum<float, 1024>(s, lds);
+        if (threadIdx.x == 0) *loss = s * invB;
+        return;
+    }
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int col = (blockIdx.x - 1) * 64 + tx;
     float s = 0.f;
-    for (int i = threadIdx.x; i < n; i += 1024) s += partial[i];
-    s = block_sum<float, 1024>(s, lds);
-    if (threadIdx.x == 0) *loss = s * invB;
+    if (col < cols) {
+#pragma unroll 8
+        for (int w = ty; w < n; w += 16) s += cs_partial[(int64_t)w * cols + col];
+    }
+    lds[threadIdx.x] = s;
+    __syncthreads();
+    if (ty == 0 && col < cols) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += lds[w * 64 + tx];
+        colsum[col] = t;
+    }
 }
 
 // plain copy, 16 bytes a lane: the reference point for bandwidth counters
@@ -299,25 +345,27 @@ int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const 
 }
 
 int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C, float *loss,
-                     float *dO, int64_t lddo, ws_alloc *ws, hipStream_t st)
+                     float *dO, int64_t lddo, float *dO_colsum, ws_alloc *ws, hipStream_t st)
 {
     int lpr_log2 = 0;
     while ((1u << lpr_log2) < C && lpr_log2 < 6) ++lpr_log2;
     const unsigned rows_per_wg = 4u * (256u >> lpr_log2);
     const unsigned nwg = cdiv(B, rows_per_wg);
     float *partial = ws->get<float>(nwg);
+    float *cs_partial = dO_colsum ? ws->get<float>((size_t)nwg * C) : nullptr;
     if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_softmax_xent: scratch too small: call sgnn_ctx_reserve");
     const unsigned nx = (C + (1u << lpr_log2) - 1) >> lpr_log2;
     if (nx <= 1)
-        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<1>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial);
+        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<1>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial, cs_partial);
     else if (nx <= 4)
-        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<4>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial);
+        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<4>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial, cs_partial);
     else if (nx <= 16)
-        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<16>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial);
+        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<16>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial, cs_partial);
     else
         return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_softmax_xent: more than 1024 classes are not supported");
-    if (loss) {
-        SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, 1.f / (float)B, loss);
+    if (loss || dO_colsum) {
+        SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1 + (dO_colsum ? cdiv(C, 64) : 0)), dim3(1024), 0, st,
+                    partial, (int)nwg, 1.f / (float)B, loss, cs_partial, (int)C, dO_colsum);
     }
     return SGNN_OK;
 }
@@ -348,6 +396,7 @@ int sgnn_launch_bce(sgnn_ctx *ctx, const float *O, int64_t ldo, const float *Y, 
     const float inv = (float)(1.0 / ((double)B * (double)C));
     SGNN_LAUNCH(ctx, st, "bce_kernel", SGNN_TAG, bce_kernel, dim3(nwg), dim3(256), 0, st, O, ldo, Y, ldy, B, C, inv, dO, lddo, partial);
     if (loss)
-        SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, inv, loss);
+        SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, inv, loss,
+                    (const float *)nullptr, 0, (float *)nullptr);
     return SGNN_OK;
 }

@@ -102,7 +102,8 @@ class GcnStep:
                 after_first()
 
     def loss_and_grad(self):
-        sg.sgnn_softmax_xent(self.ctx, self.H[-1], self.y_S, self.loss, self.dO)
+        # the last layer has no activation: its bias gradient is the column sum of dO, taken in the same pass
+        sg.sgnn_softmax_xent(self.ctx, self.H[-1], self.y_S, self.loss, self.dO, dO_colsum=self.db[-1])
 
     def backward(self, side=None, before_last=None):
         """side = (stream, context): the weight gradients dW = T^T dZ of the layers whose dZ is the incoming
@@ -124,6 +125,8 @@ class GcnStep:
                 else:
                     saved = self.H[l - 1]
             dW, db = self.dW[l], self.db[l]
+            if l == self.L - 1:
+                db = None                            # came with the loss gradient
             if l == 0 and before_last is not None:
                 before_last()
             if side is not None and not self.xform_first[l] and (masked or not relu):

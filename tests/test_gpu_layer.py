@@ -451,6 +451,30 @@ def test_softmax_xent_and_gather():
     assert torch.equal(lo, lo2)
 
 
+@pytest.mark.parametrize("B,C", [(1000, 47), (32768, 32), (77, 3), (5000, 172), (4099, 64), (300, 700)])
+def test_softmax_xent_with_column_sums(B, C):
+    # the column sums of dO (bias gradient of a last layer without activation) from the same pass: every class-count
+    # bracket of the kernel (lanes per row, values per lane), ragged row counts, and the plain call unchanged by it
+    O = _rand((B, C + 1), 6)[:, :C] * 3; y = np.random.default_rng(7).integers(0, C, B).astype(np.int32)
+    ctx().reserve(B, 1, B, max(C, 8))
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV); dO = torch.zeros((B, C), dtype=torch.float32, device=DEV)
+    cs = torch.full((C,), 9.0, dtype=torch.float32, device=DEV)
+    Od = dev(_rand((B, C + 1), 6) * 3)[:, :C]
+    sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss, dO, dO_colsum=cs)
+    l_ref, dO_ref = oracle.softmax_xent(O.copy(), y)
+    assert abs(loss.item() - l_ref) < TOL_F32 * abs(l_ref) and rel_err(dO.cpu().numpy(), dO_ref) < TOL_F32
+    # a column of dO sums values of both signs: the error is measured against the sum of their magnitudes
+    assert np.abs(cs.cpu().numpy() - dO_ref.sum(axis=0)).max() < TOL_F32 * np.abs(dO_ref).sum(axis=0).max()
+    loss2 = torch.zeros_like(loss); dO2 = torch.zeros_like(dO); cs2 = torch.zeros_like(cs)
+    sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss2, dO2, dO_colsum=cs2)
+    assert torch.equal(cs, cs2) and torch.equal(loss, loss2)
+    dO3 = torch.zeros_like(dO)
+    sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss2, dO3)
+    assert torch.equal(dO, dO3) and torch.equal(loss, loss2)
+    with pytest.raises(sg.SgnnError):
+        sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss2, None, dO_colsum=cs2)
+
+
 def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_bwd=True):
     cfg = si.CONFIGS[name]
     bf16 = cfg.bf16_mfma if bf16 is None else bf16
