@@ -1246,49 +1246,46 @@ int launch_skinny(sgnn_ctx *ctx, const gemm_args &a, int tb, hipStream_t st)
 // (lane (li, kh) supplies element (li, kh) of a 32 x 2 operand), with all loads of a wavefront in
 // flight at once and several wavefronts per SIMD.
 //
-// gemm_thin_tn_kernel: C = A^T B, A given K x M, B given K x N, K long and the result small (the
-// weight gradients, Eq. 24).  A workgroup takes a 128 x 32 NT tile of the result and one reduction
-// range, split evenly over its eight wavefronts (two per SIMD: one multiplies while the other's loads
-// are in flight).  Per pair of reduction steps a lane loads 16 bytes of A (its four columns
-// 4 li .. 4 li + 3 of row k + kh: one value for each of four 32-row tiles, whose row i is thus
-// column 4 i + j of A) and NT values of B (columns NT li + t).  The eight partial results are added
-// in LDS in a fixed order and written as one split-K partial product (the caller sums those with
-// splitk_reduce_kernel); the column sums of B go the same way.  NT = 1 takes any N <= 32 and any
-// leading dimension of B; NT = 2 needs even N and 8-byte aligned rows of B.
+// gemm_thin_tn_kernel: C = A^T B, A given K x M, B given K x N with N <= 32, K long (the weight
+// gradient of the classifier layer, Eq. 24).  A workgroup takes 128 rows of the result and one
+// reduction range, split evenly over its eight wavefronts (two per SIMD: one multiplies while the
+// other's loads are in flight).  Per pair of reduction steps a lane loads 16 bytes of A (its four
+// columns 4 li .. 4 li + 3 of row k + kh: one value for each of four 32-row tiles, whose row i is
+// thus column 4 i + j of A) and one value of B.  The eight partial results are added in LDS in a
+// fixed order and written as one split-K partial product (the caller sums those with
+// splitk_reduce_kernel); the column sums of B go the same way.
 // ---------------------------------------------------------------------------------------------
-constexpr int THIN_WAVES = 8;   // wavefronts per workgroup
-template <bool GATHER, int NT, int PAIRS>    // PAIRS: pairs of reduction steps per pass
+constexpr int THIN_WAVES = 8;    // wavefronts per workgroup
+constexpr int THIN_PAIRS = 16;   // pairs of reduction steps per pass
+template <bool GATHER>
 __global__ __launch_bounds__(64 * THIN_WAVES) void gemm_thin_tn_kernel(gemm_args a)
 {
-    constexpr int SLOTS = NT == 1 ? 4 : 2;                 // 64 KB of LDS either way
-    __shared__ __attribute__((aligned(16))) float red[SLOTS][128 * 32 * NT];
+    constexpr int PAIRS = THIN_PAIRS;
+    __shared__ __attribute__((aligned(16))) float red[4][128 * 32];
     const gemm_tile tb_ = tile_of_block(a);
     if (!tb_.valid) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, li = lane & 31, kh = lane >> 5;
-    const int64_t m0 = (int64_t)tb_.bx * 128, n0 = (int64_t)tb_.by * (32 * NT);
+    const int64_t m0 = (int64_t)tb_.bx * 128;
     const int64_t kbeg = (int64_t)tb_.bz * a.k_per_split;
     const int64_t kend = min(a.K, kbeg + a.k_per_split);
     const int64_t kw = a.k_per_split / THIN_WAVES;          // a multiple of 2
     const int64_t k0 = kbeg + wave * kw, k1 = min(kend, k0 + kw);
-    const int64_t mcol = m0 + 4 * li, ncol = n0 + NT * li;
-    const bool mok = mcol < a.M, nok = ncol < a.N;          // N is even when NT = 2: both columns or neither
-    typedef typename fvec<NT>::type bvec;
-    f32x16 acc[4][NT];
+    const int64_t mcol = m0 + 4 * li;
+    const bool mok = mcol < a.M, nok = li < a.N;
+    f32x16 acc[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[j][t][r] = 0.f;
-    float cs[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) cs[t] = 0.f;
-    // Every load is issued unconditionally at a clamped (valid) address and zeroed afterwards where it is out
-    // of range (a load under a branch would be waited for before the next one is issued), and all loads of a
-    // pass are requested before its first multiply (the scheduling barrier keeps them there).  A second
-    // register set that prefetches the next pass measured slower: the other wavefront of the SIMD already
-    // multiplies while this one waits.
-    auto issue = [&](f32x4 (&av)[PAIRS], bvec (&bv)[PAIRS], int64_t k) {
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    float cs = 0.f;
+    for (int64_t k = k0; k < k1; k += 2 * PAIRS) {
+        // Every load is issued unconditionally at a clamped (valid) address and zeroed afterwards where it is
+        // out of range (a load under a branch would be waited for before the next one is issued), and all
+        // loads of a pass are requested before its first multiply (the scheduling barrier keeps them there).
+        // A second register set that prefetches the next pass measured slower: the other wavefront of the
+        // SIMD already multiplies while this one waits.
+        f32x4 av[PAIRS];
+        float bv[PAIRS];
         int64_t ar[PAIRS];
 #pragma unroll
         for (int s = 0; s < PAIRS; ++s) {
@@ -1298,88 +1295,52 @@ __global__ __launch_bounds__(64 * THIN_WAVES) void gemm_thin_tn_kernel(gemm_args
 #pragma unroll
         for (int s = 0; s < PAIRS; ++s) {
             av[s] = *reinterpret_cast<const f32x4 *>(a.A + ar[s] * a.lda + (mok ? mcol : 0));
-            bv[s] = *reinterpret_cast<const bvec *>(a.B + min(k + 2 * s + kh, k1 - 1) * a.ldb + (nok ? ncol : 0));
+            bv[s] = a.B[min(k + 2 * s + kh, k1 - 1) * a.ldb + (nok ? li : 0)];
         }
-    };
-    auto mult = [&](const f32x4 (&av)[PAIRS], const bvec (&bv)[PAIRS], int64_t k) {
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < PAIRS; ++s) {
             const bool ok = k + 2 * s + kh < k1;
-            float y[NT];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                float b;
-                if constexpr (NT == 1) b = bv[s]; else b = bv[s][t];
-                y[t] = (ok && nok) ? b : 0.f;
-                cs[t] += y[t];
-            }
+            const float y = (ok && nok) ? bv[s] : 0.f;
+            cs += y;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float x = (ok && mok) ? av[s][j] : 0.f;
-#pragma unroll
-                for (int t = 0; t < NT; ++t) acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y[t], acc[j][t], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[j], 0, 0, 0);
             }
         }
-    };
-    for (int64_t k = k0; k < k1; k += 2 * PAIRS) {
-        f32x4 av[PAIRS];
-        bvec bv[PAIRS];
-        issue(av, bv, k);
-        __builtin_amdgcn_sched_barrier(0);
-        mult(av, bv, k);
     }
-    // acc[j][t][r] is the element (row 4 rho + j of the 128, column NT li + t of the 32 NT); sum over the
-    // wavefronts in LDS: (w, w + 4) -> w, then (w, w + 2) -> w, then (0, 1) -> 0, each a fixed order of
-    // additions, SLOTS senders at a time
-    auto put = [&](float *dst) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                bvec v;
-#pragma unroll
-                for (int t = 0; t < NT; ++t) { if constexpr (NT == 1) v = acc[j][t][r]; else v[t] = acc[j][t][r]; }
-                *reinterpret_cast<bvec *>(dst + ((4 * (8 * (r / 4) + 4 * kh + (r % 4)) + j) * 32 + li) * NT) = v;
-            }
-    };
-    auto add = [&](const float *src) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const bvec v = *reinterpret_cast<const bvec *>(src + ((4 * (8 * (r / 4) + 4 * kh + (r % 4)) + j) * 32 + li) * NT);
-#pragma unroll
-                for (int t = 0; t < NT; ++t) { if constexpr (NT == 1) acc[j][t][r] += v; else acc[j][t][r] += v[t]; }
-            }
-    };
+    // acc[j][r] is the element (row 4 rho + j of the 128, column li); tree sum over the wavefronts in LDS:
+    // (w, w + 4) -> w, then (w, w + 2) -> w, then (0, 1) -> 0, each a fixed order of additions
 #pragma unroll
     for (int half = THIN_WAVES / 2; half >= 1; half >>= 1) {
-        // receivers 0 .. half-1, senders half .. 2 half - 1, SLOTS pairs per round
-        for (int base = 0; base < half; base += SLOTS) {
-            const int w = wave - half - base;               // sender's slot
-            if (wave >= half && w >= 0 && w < SLOTS && wave < 2 * half) put(red[w]);
-            __syncthreads();
-            const int rcv = wave - base;
-            if (wave < half && rcv >= 0 && rcv < SLOTS) add(red[rcv]);
-            __syncthreads();
-        }
-    }
+        if (wave >= half && wave < 2 * half) {
+            float *dst = red[wave - half];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) cs[t] += __shfl_xor(cs[t], 32);
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dst[(4 * (8 * (r / 4) + 4 * kh + (r % 4)) + j) * 32 + li] = acc[j][r];
+        }
+        __syncthreads();
+        if (wave < half) {
+            const float *src = red[wave];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[j][r] += src[(4 * (8 * (r / 4) + 4 * kh + (r % 4)) + j) * 32 + li];
+        }
+        __syncthreads();
+    }
+    cs += __shfl_xor(cs, 32);
     if (a.colsum && tb_.bx == 0) {
         float *cs_red = red[0];       // free again: the tree sum ended with a barrier
-        if (kh == 0)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) cs_red[(wave * 32 + li) * NT + t] = cs[t];
+        if (kh == 0) cs_red[wave * 32 + li] = cs;
         __syncthreads();
         if (wave == 0 && kh == 0 && nok) {
+            float t = 0.f;
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                float sum = 0.f;
-#pragma unroll
-                for (int w = 0; w < THIN_WAVES; ++w) sum += cs_red[(w * 32 + li) * NT + t];
-                a.colsum[(int64_t)tb_.bz * a.N + ncol + t] = sum;
-            }
+            for (int w = 0; w < THIN_WAVES; ++w) t += cs_red[w * 32 + li];
+            a.colsum[(int64_t)tb_.bz * a.N + li] = t;
         }
     }
     if (wave == 0 && nok) {
@@ -1389,11 +1350,7 @@ __global__ __launch_bounds__(64 * THIN_WAVES) void gemm_thin_tn_kernel(gemm_args
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t row = m0 + 4 * (8 * (r / 4) + 4 * kh + (r % 4)) + j;
-                if (row >= a.M) continue;
-                bvec v;
-#pragma unroll
-                for (int t = 0; t < NT; ++t) { if constexpr (NT == 1) v = acc[j][t][r]; else v[t] = acc[j][t][r]; }
-                *reinterpret_cast<bvec *>(out + row * a.N + ncol) = v;
+                if (row < a.M) out[row * a.N + li] = acc[j][r];
             }
     }
 }
@@ -1601,11 +1558,11 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
         return SGNN_OK;
     }
     // long reductions onto a result of classifier width (that layer's weight gradient): 128 x 32 tiles, as many
-    // reduction ranges as give every compute unit a workgroup.  (The same kernel with 128 x 64 tiles, NT = 2, runs
-    // the wide weight gradients as fast as the LDS-tiled kernel below, no faster: both wait for operands.)
+    // reduction ranges as give every compute unit a workgroup.  (A variant with 128 x 64 tiles ran the wide weight
+    // gradients as fast as the LDS-tiled kernel below, no faster: both wait for operands.)
     if (!bf16 && ta && !tb && N >= 1 && N <= 32 && cdiv(M, 128) <= 64 && K >= 4096 && M >= 4 && M % 4 == 0 && a.alignedA && !bias &&
         !(flags & SGNN_RELU) && !mask) {
-        constexpr int PAIRS = 16;
+        constexpr int PAIRS = THIN_PAIRS;
         a.mtiles = cdiv(M, 128); a.ntiles = 1;
         const int64_t tiles = a.mtiles;
         int64_t splits = std::max<int64_t>(1, 256 / tiles);
@@ -1625,8 +1582,8 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
         // at most 64 tiles and K >= 4096: always several reduction ranges, which tile_of_block() keeps together
         // on an XCD (all tiles of a range read the same rows of B)
         const dim3 grid((unsigned)(cdiv(splits, 8) * 8 * tiles)), block(64 * THIN_WAVES);
-        if (a_row_index) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_thin_tn_kernel<true, 1, PAIRS>), grid, block, 0, st, a); }
-        else             { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_thin_tn_kernel<false, 1, PAIRS>), grid, block, 0, st, a); }
+        if (a_row_index) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, gemm_thin_tn_kernel<true>, grid, block, 0, st, a); }
+        else             { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, gemm_thin_tn_kernel<false>, grid, block, 0, st, a); }
         SGNN_LAUNCH(ctx, st, "splitk_reduce_kernel", SGNN_TAG, splitk_reduce_kernel, dim3(cdiv(M * N + (cs_part ? N : 0), 256)),
                     dim3(256), 0, st, a.partial, (int)splits, M * N, N, C, ldc, cs_part, b_colsum);
         return SGNN_OK;
