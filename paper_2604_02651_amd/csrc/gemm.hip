@@ -1357,21 +1357,25 @@ __global__ __launch_bounds__(64 * THIN_WAVES) void gemm_thin_tn_kernel(gemm_args
 
 // gemm_smallk_nt_kernel: C = epilogue(A B^T), A given M x K, B given N x K, K <= 64 a multiple of 4
 // (the gradient with respect to the input of a narrow layer, Eq. 22).  A wavefront computes 32 rows
-// by 64 columns; the four wavefronts of a workgroup share the rows.  The reduction index is dealt to
-// the two halves of the wavefront in two contiguous runs (lanes kh = 0 take k < 4 Q, the others the
-// rest: any pairing of reduction steps gives the same sum up to rounding order), so that a lane reads
-// its operand rows 16 bytes at a time with no element unused.  Q = 16-byte chunks per lane and row.
+// by 32 columns (eight wavefronts per SIMD in flight: with 32 x 64 the registers allowed three, and the
+// last of 1 1/3 rounds of wavefronts ran on a nearly empty chip); the four wavefronts of a workgroup
+// share the rows.  The reduction index is dealt to the two halves of the wavefront in two contiguous
+// runs (lanes kh = 0 take k < 4 Q, the others the rest: any pairing of reduction steps gives the same
+// sum up to rounding order), so that a lane reads its operand rows 16 bytes at a time with no element
+// unused.  Q = 16-byte chunks per lane and row.
+constexpr int SMALLK_TW = 1;    // 32-column tiles per wavefront
 template <int Q>
 __global__ __launch_bounds__(256) void gemm_smallk_nt_kernel(gemm_args a)
 {
+    constexpr int TW = SMALLK_TW;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, li = lane & 31, kh = lane >> 5;
     const int64_t r0 = (int64_t)blockIdx.x * 32;
-    const int64_t n0 = (int64_t)blockIdx.y * 256 + 64 * wave;
+    const int64_t n0 = (int64_t)blockIdx.y * (128 * TW) + 32 * TW * wave;
     if (n0 >= a.N) return;
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     // every load is issued unconditionally at a clamped (valid) address and zeroed afterwards where it is out of
     // range: a load under a branch would be waited for before the next one is issued
-    f32x4 av[Q], bv[2][Q];
+    f32x4 av[Q], bv[TW][Q];
     const int64_t arow = min(r0 + li, a.M - 1);
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
@@ -1381,26 +1385,26 @@ __global__ __launch_bounds__(256) void gemm_smallk_nt_kernel(gemm_args a)
         const f32x4 x = *reinterpret_cast<const f32x4 *>(a.A + arow * a.lda + kc);
         av[q] = kok ? x : zero4;           // rows beyond M compute values that are never stored
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < TW; ++t) {
             const int64_t n = min(n0 + 32 * t + li, a.N - 1);
             const f32x4 y = *reinterpret_cast<const f32x4 *>(a.B + n * a.ldb + kc);
             bv[t][q] = kok ? y : zero4;    // as are columns beyond N
         }
     }
     // the mask values of the lane's results, requested before the multiplies
-    float mk[2][16];
+    float mk[TW][16];
     if (a.mask) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < TW; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t row = min(r0 + 8 * (r / 4) + 4 * kh + (r % 4), a.M - 1), col = min(n0 + 32 * t + li, a.N - 1);
                 mk[t][r] = a.mask[row * a.ldm + col];
             }
     }
-    f32x16 acc[2];
+    f32x16 acc[TW];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < TW; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 #pragma unroll
@@ -1408,9 +1412,9 @@ __global__ __launch_bounds__(256) void gemm_smallk_nt_kernel(gemm_args a)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][e], bv[t][q][e], acc[t], 0, 0, 0);
+            for (int t = 0; t < TW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][e], bv[t][q][e], acc[t], 0, 0, 0);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < TW; ++t) {
         const int64_t col = n0 + 32 * t + li;
         if (col >= a.N) continue;
         const float bj = a.bias ? a.bias[col] : 0.f;
@@ -1545,11 +1549,11 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
 
     // classifier-width products, fp32: straight from global memory into the MFMA operand layout
     if (!bf16 && !ta && tb && !a_row_index && K >= 4 && K <= 64 && K % 4 == 0 && a.alignedA && a.alignedB && M >= 1 && N >= 1 &&
-        M <= (int64_t)0x7fffffff * 32 && N <= (int64_t)65535 * 256) {
+        M <= (int64_t)0x7fffffff * 32 && N <= (int64_t)65535 * 128) {
         if (b_colsum) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: column sums of B go with A^T B only");
         char tag[56];
         snprintf(tag, sizeof(tag), "NT smallk %lldx%lldx%lld f32", (long long)M, (long long)N, (long long)K);
-        dim3 grid((unsigned)cdiv(M, 32), (unsigned)cdiv(N, 256)), block(256);
+        dim3 grid((unsigned)cdiv(M, 32), (unsigned)cdiv(N, 128 * SMALLK_TW)), block(256);
         const int q = (int)cdiv(K, 8);
         if (q <= 1)      { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, gemm_smallk_nt_kernel<1>, grid, block, 0, st, a); }
         else if (q <= 2) { SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, gemm_smallk_nt_kernel<2>, grid, block, 0, st, a); }
