@@ -8,6 +8,9 @@
   python -m paper_2604_02651_amd.bench_extras --what stages [--config large]
       mini-batch construction stage by stage: sampler (Gkeys/s against the integer ALU), induced CSR
       extraction and the feature slice (GB/s of compulsory traffic against HBM)
+  python -m paper_2604_02651_amd.bench_extras --what gemm  [--config medium] [--only TN]
+      the dense products of one training step at the configuration's shapes (transform, input
+      gradient, weight gradient of every layer: Eqs. 6, 22, 24), each alone, against the MFMA peak
   python -m paper_2604_02651_amd.bench_extras --what shard [--config medium] [--grid 2]
       one GPU's share of the distributed extraction (Algorithm 2): the shard of the mini-batch matrix
       for one row range and one column range of a grid x grid partition, and its transpose
@@ -212,6 +215,53 @@ def bench_stages(cfg, args):
             "kernels": {"sampler": _kernels(rec_s, reps), "induced": _kernels(rec_i, reps), "slice": _kernels(rec_g, reps)}}
 
 
+def bench_gemm(cfg, args):
+    """Every dense product of a step of the aggregate-first / transform-first layer stack, alone."""
+    import torch
+    import paper_2604_02651_amd as sg
+    dev = "cuda:0"
+    Bn, dims = cfg.B, cfg.dims
+    ctx = sg.Context(0)
+    ctx.reserve(1, 1, Bn, max(dims))
+    flags = sg.SGNN_BF16_MFMA if cfg.bf16_mfma else 0
+    peak = 2500.0 if cfg.bf16_mfma else 157.3
+    gen = torch.Generator(device=dev).manual_seed(1)
+    shapes = []          # (name, trans_a, trans_b, M, N, K, masked)
+    for l in range(cfg.layers):
+        di, do = dims[l], dims[l + 1]
+        shapes.append(("NN layer %d transform" % l, False, False, Bn, do, di, False))
+        if l > 0:
+            shapes.append(("NT layer %d input gradient" % l, False, True, Bn, di, do, do < di))
+        shapes.append(("TN layer %d weight gradient" % l, True, False, di, do, Bn, False))
+    if args.only:
+        shapes = [sh for sh in shapes if sh[0].startswith(args.only)]
+    out, reps = [], 20
+    for name, ta, tb, M, N, K, masked in shapes:
+        A = torch.randn((K, M) if ta else (M, K), device=dev, generator=gen)
+        Bm = torch.randn((N, K) if tb else (K, N), device=dev, generator=gen)
+        Cm = torch.empty((M, N), device=dev)
+        mask = torch.randn((M, N), device=dev, generator=gen) if masked else None
+        recs = _timed(ctx, lambda: sg.sgnn_gemm(ctx, ta, tb, A, Bm, None, flags, Cm, mask=mask), reps)
+        us = sum(ms for _, _, _, ms in recs) * 1e3 / reps
+        main_us = sum(ms for n, _, _, ms in recs if n == "gemm_kernel") * 1e3 / reps
+        fl = 2.0 * M * N * K
+        byt = 4.0 * (M * K + K * N + M * N * (2 if masked else 1))
+        out.append({"product": name, "M": M, "N": N, "K": K, "us": us, "gemm_kernel_us": main_us,
+                    "TFLOP/s": fl / (us * 1e-6) / 1e12, "frac_of_mfma_peak": fl / (us * 1e-6) / 1e12 / peak,
+                    "compulsory_GB/s": byt / (us * 1e-6) / 1e9, "kernels": _kernels(recs, reps)})
+        del A, Bm, Cm, mask
+    ctx.status()
+    tot_fl = sum(2.0 * o["M"] * o["N"] * o["K"] for o in out)
+    tot_us = sum(o["us"] for o in out)
+    return {"metric": "dense products of one training step, each alone (event-timed, launch floor of about 6 us each included)",
+            "unit": "TFLOP/s", "value": tot_fl / (tot_us * 1e-6) / 1e12, "us_per_step": tot_us,
+            "dtype": "bf16" if cfg.bf16_mfma else "f32", "data": "synthetic",
+            "config": {"workload": "%s: |S| = %d, widths %s" % (cfg.name, Bn, "-".join(str(d) for d in dims))},
+            "roofline": {"bound": "mfma", "achieved": tot_fl / (tot_us * 1e-6) / 1e12, "peak": peak, "unit": "TFLOP/s",
+                         "frac": tot_fl / (tot_us * 1e-6) / 1e12 / peak, "traffic": None},
+            "products": out}
+
+
 def bench_shard(cfg, args):
     import torch
     import paper_2604_02651_amd as sg
@@ -255,9 +305,10 @@ def bench_shard(cfg, args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--what", required=True, choices=["tail", "eval", "shard", "stages"])
+    ap.add_argument("--what", required=True, choices=["tail", "eval", "shard", "stages", "gemm"])
     ap.add_argument("--config", default=None, help="tiny | medium | large | dense | xlarge (default: medium; eval and stages: large)")
     ap.add_argument("--grid", type=int, default=2, help="shard: the matrix is cut into grid x grid shards")
+    ap.add_argument("--only", default="", help="gemm: only the products whose name starts with this (NN, NT, TN)")
     args = ap.parse_args()
     import torch
     import synth_inputs as si
@@ -265,7 +316,7 @@ def main():
         print("bench_extras: no GPU visible", file=sys.stderr)
         sys.exit(1)
     cfg = si.CONFIGS[args.config or ("large" if args.what in ("eval", "stages") else "medium")]
-    out = {"tail": bench_tail, "eval": bench_eval, "shard": bench_shard, "stages": bench_stages}[args.what](cfg, args)
+    out = {"tail": bench_tail, "eval": bench_eval, "shard": bench_shard, "stages": bench_stages, "gemm": bench_gemm}[args.what](cfg, args)
     print(json.dumps(out))
 
 

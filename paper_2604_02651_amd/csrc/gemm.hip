@@ -699,7 +699,8 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
 // ---------------------------------------------------------------------------------------------
 // fp32 path with direct global -> LDS loads (global_load_lds_dwordx4: lane l's 16 bytes land at
 // a wave-uniform LDS base + 16 l, no register staging).  256 x 128 tile, eight wavefronts with
-// 64 x 64 sub-tiles (two per SIMD), slices of 32 along the reduction in a ring of three LDS
+// 64 x 64 sub-tiles (two per SIMD) - or, for the split reductions of the weight gradients, a
+// 128 x 128 tile, eight wavefronts with 64 x 32 sub-tiles - slices of 32 along the reduction in a ring of three LDS
 // stages: slice s + 2 is in flight while slice s is multiplied, one barrier per slice placed in the
 // middle of the slice's multiplies, waits on the loads stated explicitly (vmcnt).  Needs whole 16-byte chunks (as the fast path) and a
 // reduction range that is a multiple of 32.
@@ -714,21 +715,20 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
 #define SGNN_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define SGNN_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
 constexpr int DIRECT_BM = 256, DIRECT_BN = 128, DIRECT_BK = 32, DIRECT_STAGES = 3, DIRECT_WAVES = 8;
-constexpr int DIRECT_STAGE_FLOATS = (DIRECT_BM + DIRECT_BN) * DIRECT_BK;
-constexpr size_t DIRECT_LDS_BYTES = (size_t)DIRECT_STAGES * DIRECT_STAGE_FLOATS * sizeof(float);
 
 // s_waitcnt vmcnt(n) only (expcnt and lgkmcnt left at their maxima), gfx9 encoding
 #define SGNN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
 
-// Issues the loads of one operand slice: R rows, wave-loads dealt round-robin to the 8 wavefronts.
-template <int R, bool RC>
+// Issues the loads of one operand slice: R rows, wave-loads dealt round-robin to the WAVES wavefronts.
+template <int R, bool RC, int WAVES>
 __device__ __forceinline__ void direct_issue(float *lds, const float *__restrict__ G, int64_t ld, int64_t row0, int64_t rows_total,
                                              int64_t k0, const int32_t *__restrict__ ridx, int lane, int wave)
 {
-    constexpr int LOADS = R * DIRECT_BK / 4 / 64 / DIRECT_WAVES;   // wave-loads per wavefront
+    constexpr int LOADS = R * DIRECT_BK / 4 / 64 / WAVES;   // wave-loads per wavefront
+    static_assert(LOADS * 64 * WAVES * 4 == R * DIRECT_BK, "the wavefronts share the slice evenly");
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
-        const int q = wave + DIRECT_WAVES * j;   // wave-load number: LDS floats [256 q, 256 q + 256)
+        const int q = wave + WAVES * j;   // wave-load number: LDS floats [256 q, 256 q + 256)
         const float *g;
         if (RC) {
             const int r = 8 * q + (lane >> 3), pos = lane & 7;
@@ -770,18 +770,21 @@ __device__ __forceinline__ void direct_frag(float (&v)[T][4], const float *L, in
     }
 }
 
-template <bool TA, bool TB, bool GATHER>
-__global__ __launch_bounds__(64 * DIRECT_WAVES) void gemm_direct_kernel(gemm_args a)
+template <int BM, int WAVES, int TN, bool TA, bool TB, bool GATHER>
+__global__ __launch_bounds__(64 * WAVES) void gemm_direct_kernel(gemm_args a)
 {
-    constexpr int BM = DIRECT_BM, BN = DIRECT_BN, BK = DIRECT_BK, TM = 2, TN = 2;
+    constexpr int BN = DIRECT_BN, BK = DIRECT_BK, TM = 2;
+    constexpr int WAVES_N = BN / (32 * TN);
+    static_assert(BM * BN == WAVES * 64 * 32 * TN, "a 64 x 32 TN sub-tile per wavefront");
+    constexpr int STAGE_FLOATS = (BM + BN) * BK;
     constexpr bool A_RC = !TA, B_RC = TB;
-    constexpr int LOADS = (BM + BN) * BK / 4 / 64 / DIRECT_WAVES;   // loads per thread and slice
+    constexpr int LOADS = (BM + BN) * BK / 4 / 64 / WAVES;   // loads per thread and slice
     extern __shared__ __attribute__((aligned(16))) float direct_smem[];
     const gemm_tile tb_ = tile_of_block(a);
     if (!tb_.valid) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 31, kh = lane >> 5;
-    const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+    const int wm0 = (wave / WAVES_N) * 64, wn0 = (wave % WAVES_N) * (32 * TN);
     const int64_t m0 = (int64_t)tb_.bx * BM, n0 = (int64_t)tb_.by * BN;
     const int64_t kbeg = (int64_t)tb_.bz * a.k_per_split;
     const int64_t kend = min(a.K, kbeg + a.k_per_split);
@@ -798,10 +801,10 @@ __global__ __launch_bounds__(64 * DIRECT_WAVES) void gemm_direct_kernel(gemm_arg
     // a slice number past the end loads the last slice again, into a stage nobody reads any more:
     // the loop body then has no branch, and every wait in it counts a fixed number of operations
     auto issue = [&](int s) {
-        float *st = direct_smem + (s % DIRECT_STAGES) * DIRECT_STAGE_FLOATS;
+        float *st = direct_smem + (s % DIRECT_STAGES) * STAGE_FLOATS;
         const int64_t k0 = kbeg + (int64_t)min(s, nslices - 1) * BK;
-        direct_issue<BM, A_RC>(st, a.A, a.lda, m0, a.M, k0, GATHER ? a.a_row_index : nullptr, lane, wave);
-        direct_issue<BN, B_RC>(st + BM * BK, a.B, a.ldb, n0, a.N, k0, nullptr, lane, wave);
+        direct_issue<BM, A_RC, WAVES>(st, a.A, a.lda, m0, a.M, k0, GATHER ? a.a_row_index : nullptr, lane, wave);
+        direct_issue<BN, B_RC, WAVES>(st + BM * BK, a.B, a.ldb, n0, a.N, k0, nullptr, lane, wave);
     };
     // Schedule of a slice (four quads of four reduction steps each, operand values double buffered in
     // registers):   read q1 | multiply q0 | read q2 | multiply q1 | wait + barrier + issue slice it+2 |
@@ -811,7 +814,7 @@ __global__ __launch_bounds__(64 * DIRECT_WAVES) void gemm_direct_kernel(gemm_arg
     // no wavefront ever waits on memory or LDS latency with an empty MFMA queue behind it.
     float av[2][TM][4], bv[2][TN][4];
     auto frags = [&](int buf, int slice, int q) {
-        const float *LA = direct_smem + (slice % DIRECT_STAGES) * DIRECT_STAGE_FLOATS, *LB = LA + BM * BK;
+        const float *LA = direct_smem + (slice % DIRECT_STAGES) * STAGE_FLOATS, *LB = LA + BM * BK;
         direct_frag<BM, A_RC, TM>(av[buf], LA, wm0, 16 * (q / 2), q & 1, li, kh);
         direct_frag<BN, B_RC, TN>(bv[buf], LB, wn0, 16 * (q / 2), q & 1, li, kh);
     };
@@ -833,8 +836,21 @@ __global__ __launch_bounds__(64 * DIRECT_WAVES) void gemm_direct_kernel(gemm_arg
         asm volatile("" ::: "memory");
         frags(0, 0, 0);
     }
+    // column sums of B (the bias gradient next to dW = T^T dZ), by the first row block of tiles only: B of a
+    // slice lies in LDS as [32 reduction steps][128 columns]; a thread adds up its column over every
+    // (threads / 128)-th reduction step while the slice is current
+    constexpr int CS_PARTS = WAVES * 64 / BN;
+    const bool do_cs = TA && !TB && a.colsum && tb_.bx == 0;
+    float cs = 0.f;
     for (int it = 0; it < nslices; ++it) {
         frags(1, it, 1);
+        if constexpr (TA && !TB) {
+            if (do_cs) {
+                const float *LB = direct_smem + (it % DIRECT_STAGES) * STAGE_FLOATS + BM * BK;
+#pragma unroll
+                for (int k = 0; k < BK / CS_PARTS; ++k) cs += LB[(k * CS_PARTS + threadIdx.x / BN) * BN + threadIdx.x % BN];
+            }
+        }
         __builtin_amdgcn_sched_barrier(0);
         multiply(0);
         __builtin_amdgcn_sched_barrier(0);
@@ -857,6 +873,20 @@ __global__ __launch_bounds__(64 * DIRECT_WAVES) void gemm_direct_kernel(gemm_arg
         __builtin_amdgcn_sched_barrier(0);
     }
 
+    if constexpr (TA && !TB) {
+        if (do_cs) {
+            __syncthreads();      // every wavefront is through its last slice: the stages are free
+            direct_smem[threadIdx.x] = cs;
+            __syncthreads();
+            const int64_t col = n0 + threadIdx.x;
+            if (threadIdx.x < BN && col < a.N) {
+                float t = 0.f;
+#pragma unroll
+                for (int p = 0; p < CS_PARTS; ++p) t += direct_smem[p * BN + threadIdx.x];
+                a.colsum[(a.partial ? (int64_t)tb_.bz * a.N : 0) + col] = t;
+            }
+        }
+    }
     float *Cout = a.partial ? a.partial + (int64_t)tb_.bz * a.M * a.N : a.C;
     const int64_t ldc = a.partial ? a.N : a.ldc;
     float *stage = nullptr;
@@ -867,9 +897,10 @@ __global__ __launch_bounds__(64 * DIRECT_WAVES) void gemm_direct_kernel(gemm_arg
     store_tile<TM, TN, A_RC, B_RC>(a, acc, Cout, ldc, m0 + wm0, n0 + wn0, li, kh, stage);
 }
 
-int launch_direct(sgnn_ctx *ctx, int ta, int tb, gemm_args a, int splits, hipStream_t st)
+int launch_direct(sgnn_ctx *ctx, int ta, int tb, gemm_args a, int splits, bool bm128, hipStream_t st)
 {
-    a.mtiles = (uint32_t)cdiv(a.M, DIRECT_BM);
+    const int bm = bm128 ? 128 : DIRECT_BM, waves = DIRECT_WAVES;
+    a.mtiles = (uint32_t)cdiv(a.M, bm);
     a.ntiles = (uint32_t)cdiv(a.N, DIRECT_BN);
     a.splits = (uint32_t)splits;
     const uint64_t members = splits > 1 ? (uint64_t)a.mtiles * a.ntiles : a.ntiles;
@@ -877,27 +908,31 @@ int launch_direct(sgnn_ctx *ctx, int ta, int tb, gemm_args a, int splits, hipStr
     const uint64_t nblocks = cdiv(groups, 8) * 8 * members;
     if (nblocks > 0x7fffffffull) return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gemm: more than 2^31 tiles");
     char tag[56];
-    snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld f32", ta ? 'T' : 'N', tb ? 'T' : 'N', DIRECT_BM, DIRECT_BN, (long long)a.M,
+    snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld f32", ta ? 'T' : 'N', tb ? 'T' : 'N', bm, DIRECT_BN, (long long)a.M,
              (long long)a.N, (long long)a.K);
-    dim3 grid((unsigned)nblocks), block(64 * DIRECT_WAVES);
+    dim3 grid((unsigned)nblocks), block(64 * waves);
+    const size_t lds_bytes = (size_t)DIRECT_STAGES * (bm + DIRECT_BN) * DIRECT_BK * sizeof(float);
     const bool gather = a.a_row_index != nullptr;
-#define SGNN_DIRECT_CASE(TA_, TB_, G_)                                                                                  \
-    if (ta == TA_ && tb == TB_ && gather == G_) {                                                                       \
+#define SGNN_DIRECT_CASE_BM(BM_, W_, TN_, TA_, TB_, G_)                                                                 \
+    if (bm == BM_ && ta == TA_ && tb == TB_ && gather == G_) {                                                          \
         static bool attr_set = false;                                                                                   \
         if (!attr_set) {                                                                                                \
-            SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_direct_kernel<TA_, TB_, G_>),        \
+            SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_direct_kernel<BM_, W_, TN_, TA_, TB_, G_>), \
                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));                 \
             attr_set = true;                                                                                            \
         }                                                                                                               \
-        SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_direct_kernel<TA_, TB_, G_>), grid, block, DIRECT_LDS_BYTES, st, a); \
+        SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_direct_kernel<BM_, W_, TN_, TA_, TB_, G_>), grid, block, lds_bytes, st, a); \
         return SGNN_OK;                                                                                                 \
     }
+#define SGNN_DIRECT_CASE(TA_, TB_, G_) SGNN_DIRECT_CASE_BM(DIRECT_BM, DIRECT_WAVES, 2, TA_, TB_, G_)
+    SGNN_DIRECT_CASE_BM(128, 8, 1, true, false, false)
     SGNN_DIRECT_CASE(false, false, false)
     SGNN_DIRECT_CASE(false, true, false)
     SGNN_DIRECT_CASE(true, false, false)
     SGNN_DIRECT_CASE(false, false, true)
     SGNN_DIRECT_CASE(false, true, true)
     SGNN_DIRECT_CASE(true, false, true)
+#undef SGNN_DIRECT_CASE_BM
 #undef SGNN_DIRECT_CASE
     return SGNN_OK;
 }
@@ -1595,10 +1630,20 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
 
     // wide fp32 results with whole chunks and whole slices: the direct-to-LDS kernel, 256 x 128 tiles.  Not for
     // the long reductions onto a small result (T^T dZ): with two 256 x 128 tiles the split would have to be
-    // twice as fine, and the partial products it writes cost more than the kernel gains.
+    // twice as fine, and the partial products it writes cost more than the kernel gains (those take the
+    // kernel's 128 x 128 form, direct128 below).
     const int64_t a_contig = ta ? M : K, b_contig = tb ? K : N;
     const bool direct = !bf16 && !ta && a.alignedA && a.alignedB && a_contig % 4 == 0 && b_contig % 4 == 0 &&
                         a_contig >= 4 && b_contig >= 4 && K % 32 == 0 && K >= 128 && N > 64 && M > 128;
+
+    // the weight gradients of the wide layers (A^T B, long reduction onto a result of a few 128 x 128 tiles): the same
+    // kernel with 128-row tiles, one workgroup per reduction range and tile, two slices in flight behind the one
+    // being multiplied (the register-staged tile kernel has one, and its wavefronts wait for it half of the time) and
+    // eight wavefronts, two per SIMD (with four, one per SIMD, it was no faster than the tile kernel: nothing
+    // multiplies while the only wavefront of a SIMD issues loads, reads LDS or stands at the barrier)
+    const bool direct128 = !bf16 && ta && !tb && !a_row_index && a.alignedA && a.alignedB && M % 4 == 0 && N % 4 == 0 &&
+                           M > 64 && N > 64 && K % 32 == 0 && K >= 4096 && !bias && !(flags & SGNN_RELU) && !mask &&
+                           (int64_t)cdiv(M, 128) * cdiv(N, 128) <= 64;
 
     // tile shape by the width of C
     const int bn = N > 64 ? 128 : (N > 32 ? 64 : 32);
@@ -1626,7 +1671,7 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
     bool cs_fused = false;
     if (b_colsum) {
         if (!ta || tb) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: column sums of B go with A^T B only");
-        cs_fused = !direct && a.alignedA && a.alignedB && M % 4 == 0 && N % 4 == 0 && M >= 4 && N >= 4 && K >= 1;
+        cs_fused = !direct && a.alignedA && a.alignedB && M % 4 == 0 && N % 4 == 0 && M >= 4 && N >= 4 && K >= 1;   // direct128 included
         if (cs_fused) {
             if (splits > 1) {
                 cs_partial = ws->get<float>((size_t)splits * N);
@@ -1637,7 +1682,8 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
         }
     }
     int rc;
-    if (direct) rc = launch_direct(ctx, ta, tb, a, splits, st);
+    if (direct) rc = launch_direct(ctx, ta, tb, a, splits, false, st);
+    else if (direct128 && splits > 1) rc = launch_direct(ctx, ta, tb, a, splits, true, st);
     else if (bn == 128) rc = launch_cfg<128, 128, 64, 64>(ctx, ta, tb, bf16, a, splits, st);
     else if (bn == 64) rc = launch_cfg<128, 64, 64, 32>(ctx, ta, tb, bf16, a, splits, st);
     else if (narrow128) rc = launch_cfg<128, 32, 32, 32>(ctx, ta, tb, bf16, a, splits, st);
