@@ -3,16 +3,21 @@
 
 One "step" is one pass of the whole path over one mini-batch: uniform vertex sample -> induced
 normalised CSR -> slice -> L GCN layers forward -> cross-entropy -> L layers backward, every
-stage in libsgnn's HIP kernels, inputs resident in HBM before the clock starts.
+stage in libsgnn's HIP kernels, inputs resident in HBM before the clock starts.  Consecutive
+steps use consecutive sampler counters (t = 0, 1, 2, ...): no two timed steps of a run share a
+mini-batch unless the run is longer than the cycle of captured steps.
 
-Prints ONE JSON line: throughput in steps/s, the roofline figure of the kernel that takes the
-most time (measured with HIP events recorded on the launch stream, in a second pass over the
-same steps so that event overhead does not touch the throughput figure), and the CPU oracle
-timed on the host cores on a bounded sample of the same workload.
+Prints ONE JSON line: throughput in steps/s of the headline workload (the largest configuration
+that fits one GPU), the roofline figure of the kernel that takes the most time (measured with HIP
+events recorded on the launch stream, in a second pass over the same steps so that event overhead
+does not touch the throughput figure), the CPU oracle timed on the host cores on a bounded sample
+of the same workload, and - as sub-objects under "other_workloads" - the same measurement on
+further configurations (fp32 end to end; fp32-stored features).
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -25,14 +30,25 @@ if ROOT not in sys.path:
 METRIC = "sampled GCN mini-batch steps/sec (fwd+bwd)"
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
+T_START = time.perf_counter()
+
+
+def log(msg):
+    print("[bench %6.1f s] %s" % (time.perf_counter() - T_START, msg), file=sys.stderr, flush=True)
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=160)
-    ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--config", default="medium", help="tiny | medium | large | dense | xlarge (medium is the headline workload)")
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--config", default="xlarge",
+                    help="tiny | medium | large | dense | xlarge (xlarge, the largest configuration that fits one GPU, "
+                         "is the headline workload)")
+    ap.add_argument("--extras", default="auto",
+                    help="comma-separated further workloads reported as sub-objects: dense, large, medium, tiny, "
+                         "xlarge_f32_features; 'auto' = dense,xlarge_f32_features with the xlarge headline, none otherwise; "
+                         "'none' = no sub-objects")
     ap.add_argument("--workload", default="gcn", choices=["gcn", "model"],
                     help="gcn: the plain GCN stack of the configuration (the headline); model: the paper's complete model "
                          "(input projection, residual layers with RMSNorm / ReLU / dropout, output head, Adam) at the "
@@ -42,18 +58,24 @@ def parse_args():
     ap.add_argument("--no-fuse-relu-bwd", action="store_true",
                     help="separate ReLU-backward pass instead of masking inside the product that writes the input gradient")
     ap.add_argument("--side-dw", action="store_true",
-                    help="weight-gradient GEMMs on the second stream, concurrent with the rest of the backward pass "
-                         "(default: on the main stream - measured 1.3 % faster since the GEMM epilogues were vectorised)")
+                    help="weight-gradient GEMMs on the second stream, concurrent with the rest of the backward pass")
     ap.add_argument("--fork", default="mid", choices=["mid", "start"],
                     help="where a captured step forks the next mini-batch's construction: after its first layer, "
                          "rejoining before its last backward call (mid), or around the whole step (start)")
-    ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
+    ap.add_argument("--graph", default="auto", choices=["auto", "on", "off"],
+                    help="replay HIP graphs of the overlapped pipeline (auto: where a step is short enough to be launch bound)")
+    ap.add_argument("--no-graph", action="store_true", help="same as --graph off")
     ap.add_argument("--no-overlap", action="store_true",
                     help="everything on one stream (default: the next mini-batch is sampled on a second stream while this one trains)")
-    ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = pick by config)")
+    ap.add_argument("--fp32-activations", action="store_true",
+                    help="with bf16 GEMM operands, keep the forward activations in fp32 storage (default: bf16 storage)")
+    ap.add_argument("--cpu-seconds", type=float, default=25.0, help="target amount of oracle work to time")
     ap.add_argument("--breakdown", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB copy kernel five times (reference point for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--profile-steps-only", type=int, default=0,
+                    help="run only this many single-stream steps after the warm-up and print no oracle leg "
+                         "(the form the rocprofv3 summaries under profiles/ are made with)")
     return ap.parse_args()
 
 
@@ -63,30 +85,30 @@ def gemm_flops(tag: str) -> float:
     return 2.0 * float(dims[0]) * float(dims[1]) * float(dims[2])
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build is the single-GPU hot path; --gpus N with N > 1 is not supported "
-              "(no collectives are part of it)", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
-    import torch
-
-    import paper_2604_02651_amd as sg
-    import synth_inputs as si
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    dev = "cuda:0"
-    cfg = si.CONFIGS[args.config]
-    g = si.config_graph(cfg, device=dev)
-    model = args.workload == "model"
-    X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=dev,
-                           dtype=torch.bfloat16 if cfg.bf16_features and not model else torch.float32)
+def make_inputs(si, torch, cfg, dev, feature_dtype, graph=None):
+    g = graph if graph is not None else si.config_graph(cfg, device=dev)
+    log("%s: graph ready (N=%d, E=%d)" % (cfg.name, cfg.N, g.E))
+    X = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=dev, dtype=feature_dtype)
     labels = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=dev)
     weights = si.layer_weights(cfg, device=dev)
+    log("%s: features (%s) / labels / weights ready" % (cfg.name, str(feature_dtype).replace("torch.", "")))
+    return g, X, labels, weights
+
+
+def cycle_length(steps: int) -> int:
+    """Number of distinct consecutive mini-batches captured in one HIP graph (even)."""
+    if steps % 16 == 0:
+        return 16
+    if steps <= 64:
+        return max(steps - steps % 2, 2)
+    return 16
+
+
+def measure(args, sg, si, torch, cfg, g, X, labels, weights, use_graph_req: str, label: str):
+    """Throughput of `args.steps` steps after `args.warmup`, and the per-kernel pass.  Returns
+    (fields of the JSON line, the step object)."""
+    dev = "cuda:0"
+    model = args.workload == "model"
     if model:
         d_h = cfg.hidden
         n_layers = max(cfg.layers - 1, 1)
@@ -97,57 +119,76 @@ def main():
         st = sg.ScaleGnnModel(cfg.N, g.rowptr, g.colidx, X, labels, params, cfg.B, sampler_seed=cfg.sampler_seed, drop_q=0.1,
                               drop_seed=1, bf16=cfg.bf16_mfma, optimizer="adam", lr=1e-3, device=dev)
     else:
+        kw = {}
+        if "bf16_activations" in sg.GcnStep.__init__.__code__.co_varnames:
+            kw["bf16_activations"] = cfg.bf16_mfma and not args.fp32_activations
         st = sg.GcnStep(cfg.N, g.rowptr, g.colidx, X, labels, weights, cfg.B, cfg.sampler_seed, bf16=cfg.bf16_mfma,
                         fuse_slice=not args.no_fuse_slice, device=dev, fuse_relu_bwd=not args.no_fuse_relu_bwd,
-                        side_dw=args.side_dw)
-    period = max(cfg.steps, 1)   # the configuration's mini-batches: consecutive sampler counters
+                        side_dw=args.side_dw, **kw)
+    K, W = args.steps, args.warmup
 
-    use_graph = not args.no_graph and not args.no_overlap and period % 2 == 0 and not model    # the model is launched eagerly
+    if args.profile_steps_only:
+        for t in range(W):
+            st.step(t)
+        torch.cuda.synchronize()
+        for t in range(args.profile_steps_only):
+            st.step(W + t)
+        torch.cuda.synchronize()
+        st.ctx.status()
+        return None, st
+
+    # launch-bound steps (a few hundred microseconds) gain from graph replay; long steps do not
+    launch_bound = cfg.B <= 65536 and cfg.name != "dense"
+    use_graph = (not model and not args.no_overlap and K >= 2 and
+                 (use_graph_req == "on" or (use_graph_req == "auto" and launch_bound)))
+    cyc = cycle_length(K) if use_graph else 0
     if use_graph:
-        whole = args.steps % period == 0 and args.warmup % period == 0
-        st.build_graphs(range(period), steps_per_graph=0 if whole else 2, fork=args.fork)
-        if not whole and (args.steps % 2 or args.warmup % 2):
-            print("bench.py: with HIP graphs --steps and --warmup must be even", file=sys.stderr)
-            sys.exit(2)
+        st.build_graphs(range(cyc), steps_per_graph=0, fork=args.fork)     # counters 0 .. cyc-1 in one graph
+    n_graph = (K // cyc) * cyc if use_graph else 0
 
-    def run(n):
+    def eager(ts):
         if args.no_overlap:
-            for i in range(n):
-                st.step(i % period)
-        elif use_graph and not model:
-            st.run_graphs(n)
+            for t in ts:
+                st.step(t)
         else:
-            st.run([i % period for i in range(n)])
+            st.run(list(ts))
 
-    run(args.warmup)
+    # warm-up: W eager steps (they also build the second stream's buffers), plus one untimed replay of the graph
+    eager(range(W))
+    if use_graph:
+        st.run_graphs(cyc)
     torch.cuda.synchronize()
     st.ctx.status()
     t0 = time.perf_counter()
-    run(args.steps)
+    if use_graph:
+        st.run_graphs(n_graph)                       # counters 0 .. cyc-1, round and round
+    if n_graph < K:
+        eager(range(n_graph, K))                     # the remainder, launched from the host
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     st.ctx.status()
-    steps_per_s = args.steps / elapsed
+    steps_per_s = K / elapsed
     # the same K steps on a single stream, for reference
     t1 = time.perf_counter()
-    for i in range(args.steps):
-        st.step(i % period)
+    for t in range(K):
+        st.step(t)
     torch.cuda.synchronize()
-    single_stream_steps_per_s = args.steps / (time.perf_counter() - t1)
+    single_stream_steps_per_s = K / (time.perf_counter() - t1)
+    log("%s: %.1f steps/s (single stream %.1f)" % (label, steps_per_s, single_stream_steps_per_s))
 
     # ---- per-kernel pass: the same steps with every launch bracketed by events on its stream ----
-    nprof = min(args.steps, period)
+    nprof = min(K, 16)
     st.ctx.profile(True)
-    nnz_total = 0
-    for i in range(nprof):
-        st.step(i % period)
+    for t in range(nprof):
+        st.step(t)
     recs = st.ctx.profile_read()
     st.ctx.profile(False)
-    for i in range(nprof):     # entry counts of those steps, for the byte figures of the sparse kernels
+    nnz_total = 0
+    for t in range(nprof):     # entry counts of those steps, for the byte figures of the sparse kernels
         if model:
-            st.minibatch(i % period)
+            st.minibatch(t)
         else:
-            st.sample(i % period); st.induce()
+            st.sample(t); st.induce()
         nnz_total += st.A.nnz()
     nnz_avg = nnz_total / nprof
     groups = {}
@@ -161,31 +202,38 @@ def main():
         gq = groups.setdefault(key, {"calls": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
         gq["calls"] += calls
         gq["ms"] += ms
-        if name == "gemm_kernel":
+        if name in ("gemm_kernel", "gemm_direct_kernel"):
             gq["flops"] += gemm_flops(tag) * calls
         elif name == "gemm_skinny_bf16_kernel":
-            # tall operand streamed once, small operand resident: bound by reading A and writing C
-            m_, n_, k_ = (float(x) for x in tag.split()[2].split("x"))
-            gq["bytes"] += calls * 4.0 * (m_ * k_ + m_ * n_ + k_ * n_)
+            # tall operand streamed once, small operand resident: bound by reading A and writing C.
+            # tag: "NN|NT skinny MxNxK bf16 [a=<bytes>] [c=<bytes>]" (element sizes of the tall operand and of the
+            # result as stored; 4 where not stated)
+            p = tag.split()
+            m_, n_, k_ = (float(x) for x in p[2].split("x"))
+            ea = next((float(w[2:]) for w in p if w.startswith("a=")), 4.0)
+            ec = next((float(w[2:]) for w in p if w.startswith("c=")), 4.0)
+            gq["bytes"] += calls * (ea * m_ * k_ + ec * m_ * n_ + 4.0 * k_ * n_)
         elif name == "spmm_main_kernel":
             d = int(tag.split("d=")[1].split()[0])
+            w = tag.split()
+            ein = next((float(x[3:]) for x in w if x.startswith("in=")), 2.0 if "bf16 in" in tag else 4.0)
+            eout = next((float(x[4:]) for x in w if x.startswith("out=")), 4.0)
             # compulsory traffic: CSR once, every input row once, the output once
-            gq["bytes"] += calls * (8.0 * nnz_avg + 4.0 * (cfg.B + 1) + 2.0 * cfg.B * d * 4)
+            gq["bytes"] += calls * (8.0 * nnz_avg + 4.0 * (cfg.B + 1) + cfg.B * d * (ein + eout))
     total_ms = sum(v["ms"] for v in groups.values())
     dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
     sp = [v for k, v in groups.items() if k.startswith("spmm_main_kernel")]
     sparse_ms, sparse_bytes = sum(v["ms"] for v in sp), sum(v["bytes"] for v in sp)
     if args.breakdown:
         for name, tag, calls, ms in recs:
-            if name.startswith("spmm") or name.startswith("gemm"):
-                print("  %-24s %-40s calls %3d  avg us %8.2f" % (name, tag, calls, 1e3 * ms / calls), file=sys.stderr)
+            print("  %-28s %-44s calls %3d  avg us %9.2f" % (name, tag, calls, 1e3 * ms / calls), file=sys.stderr)
         for k, v in sorted(groups.items(), key=lambda kv: -kv[1]["ms"]):
             print("%-44s calls/step %5.1f  us/step %9.2f  avg us %8.2f" %
                   (k, v["calls"] / nprof, 1e3 * v["ms"] / nprof, 1e3 * v["ms"] / v["calls"]), file=sys.stderr)
         print("sum of kernel time per step: %.1f us; wall per step: %.1f us" % (1e3 * total_ms / nprof, 1e6 / steps_per_s),
               file=sys.stderr)
     if dom["flops"] > 0:
-        dt = "bf16" if dom_name.endswith("bf16>") else "f32"
+        dt = "bf16" if "bf16" in dom_name else "f32"
         achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
                     "frac": achieved / PEAK_TFLOPS[dt], "traffic": None}
@@ -204,26 +252,133 @@ def main():
     roofline["kernel"] = dom_name
     roofline["avg_launch_us"] = 1e3 * dom["ms"] / dom["calls"]
     roofline["launches_per_step"] = dom["calls"] / nprof
+    roofline["algorithmic_per_launch"] = (dom["flops"] or dom["bytes"]) / dom["calls"]
     roofline["share_of_kernel_time"] = dom["ms"] / total_ms if total_ms > 0 else None
     # the sparse products as a whole (all widths), the other large group
     roofline["spmm_all_widths"] = {"bound": "hbm", "achieved": sparse_bytes / (sparse_ms * 1e-3) / 1e9 if sparse_ms > 0 else 0.0,
                                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "us_per_step": 1e3 * sparse_ms / nprof}
+    top = sorted(groups.items(), key=lambda kv: -kv[1]["ms"])[:6]
+    roofline["top_kernels_us_per_step"] = {k: round(1e3 * v["ms"] / nprof, 1) for k, v in top}
 
+    feat = "bf16" if X.dtype == torch.bfloat16 else "f32"
+    act = "bf16" if getattr(st, "bf16_activations", False) else "f32"
     out = {
-        "metric": METRIC, "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.bf16_mfma else "f32", "data": "synthetic",
-        "config": {"workload": "%s: R-MAT N=%d, E=%d stored entries, |S|=%d, %s, %d mini-batches (sampler "
-                               "counters 0..%d)" % (cfg.name, cfg.N, g.E, cfg.B,
-                                                     ("complete model %d-[%d x %d]-%d with dropout 0.1 and Adam"
-                                                      % (cfg.d_in, cfg.hidden, max(cfg.layers - 1, 1), cfg.classes)) if model
-                                                     else "GCN " + "-".join(map(str, cfg.dims)), period, period - 1),
-                   "fuse_slice": not args.no_fuse_slice, "fuse_relu_bwd": not args.no_fuse_relu_bwd, "side_stream_dw": args.side_dw and not args.no_overlap,
+        "value": steps_per_s, "unit": "steps/s", "steps": K, "warmup": W, "ms_per_step": 1e3 * elapsed / K,
+        "dtype": "bf16" if cfg.bf16_mfma else "f32",
+        "config": {"workload": "%s: R-MAT N=%d, E=%d stored entries, |S|=%d, %s, features stored %s, activations stored %s, "
+                               "%d timed mini-batches with sampler counters %s"
+                               % (label, cfg.N, g.E, cfg.B,
+                                  ("complete model %d-[%d x %d]-%d with dropout 0.1 and Adam"
+                                   % (cfg.d_in, cfg.hidden, max(cfg.layers - 1, 1), cfg.classes)) if model
+                                  else "GCN " + "-".join(map(str, cfg.dims)), feat, act, K,
+                                  ("0..%d" % (K - 1)) if not use_graph or cyc >= K else
+                                  ("0..%d repeated (cycle of %d captured steps)" % (cyc - 1, cyc))),
+                   "fuse_slice": not args.no_fuse_slice, "fuse_relu_bwd": not args.no_fuse_relu_bwd,
+                   "side_stream_dw": args.side_dw and not args.no_overlap,
                    "overlap_sampling": not args.no_overlap, "hip_graph": use_graph,
+                   "graph_steps": n_graph, "eager_steps": K - n_graph,
+                   "warmup_extra_graph_replays": 1 if use_graph else 0,
                    "single_stream_steps_per_s": single_stream_steps_per_s, "avg_induced_entries": nnz_avg,
                    "kernel_time_us_per_step": 1e3 * total_ms / nprof},
         "roofline": roofline,
     }
+    return out, st
+
+
+def cpu_baseline(args, si, torch, cfg, g, X, weights):
+    """The oracle on the host cores on a bounded sample of the workload, in steps/s.
+
+    One step is timed stage by stage.  The sampler (a sort of all N keys) and the extraction (a scan of
+    the sampled rows) are timed whole.  The layers (forward, loss, backward) are timed whole when a flop
+    estimate puts them under ten seconds; otherwise on the mini-batch induced by every r-th vertex of the
+    same sample, their time multiplied by r (the dense products, which dominate, are linear in the number
+    of rows).  Where a whole step is short, several whole steps with consecutive counters are timed."""
+    import numpy as np
+    import oracle
+    wnp = [(W.double().cpu().numpy(), b.double().cpu().numpy()) for W, b in weights]
+    rp, ci = g.rowptr.cpu().numpy(), g.colidx.cpu().numpy()
+    log("%s: graph copied to the host for the oracle" % cfg.name)
+
+    def rows_for(S):       # the slice: rows handed over as data, not timed as oracle work
+        St = torch.as_tensor(S.astype(np.int64))
+        Xs = X[St.to(X.device)].float().cpu().numpy().astype(np.float64)
+        ys = si.labels_for(St, cfg.classes, cfg.label_seed).numpy()
+        return Xs, ys
+
+    def layers(S):
+        rpS, ciS, vS = oracle.induced_csr(cfg.N, rp, ci, S)
+        Xs, ys = rows_for(S)
+        c0 = time.perf_counter()
+        oracle.layers_step(rpS, ciS, vS, Xs, ys, wnp, bf16=cfg.bf16_mfma)
+        return time.perf_counter() - c0
+
+    def stages(t):
+        c0 = time.perf_counter()
+        S = oracle.sample_uniform(cfg.N, cfg.B, cfg.sampler_seed, t)
+        c1 = time.perf_counter()
+        oracle.induced_csr(cfg.N, rp, ci, S)
+        c2 = time.perf_counter()
+        return S, c1 - c0, c2 - c1
+
+    dims = cfg.dims
+    flops = 6.0 * cfg.B * sum(dims[l] * dims[l + 1] for l in range(cfg.layers))
+    r = 1
+    while flops / r > 10.0 * 15e9 and r < 1024:      # plain C loops on all cores: about 15 GFLOP/s
+        r *= 2
+    layers(np.arange(min(cfg.B, 1024), dtype=np.int32))       # warm-up: library load, thread pool
+    S, a, b = stages(0)
+    lay = layers(S[::r].copy())
+    step_s = a + b + lay * r
+    log("%s: oracle sampler %.2f s, extraction %.2f s, layers %.2f s at |S|/%d" % (cfg.name, a, b, lay, r))
+    cores = oracle.num_threads()
+    if r == 1:
+        n = int(max(0, min(49, (args.cpu_seconds - step_s) // max(step_s, 1e-3))))
+        total = step_s
+        for t in range(1, n + 1):
+            S, a, b = stages(t)
+            total += a + b + layers(S)
+        return {"value": (n + 1) / total, "unit": "steps/s", "cores": cores, "kind": "oracle",
+                "sample": "%d whole steps (sampler counters 0..%d) of the same workload: sampler, extraction and "
+                          "layers (forward, loss, backward), %.1f s of oracle time" % (n + 1, n, total)}
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle",
+            "sample": "one step (sampler counter 0), stage by stage: sampler over all N = %d keys (%.1f s) and extraction "
+                      "of the whole |S| = %d mini-batch (%.1f s) timed whole; forward + loss + backward of the layers "
+                      "timed on the mini-batch induced by every %d-th sampled vertex (%d rows, %.1f s) and multiplied "
+                      "by %d" % (cfg.N, a, cfg.B, b, r, len(S[::r]), lay, r)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is the single-GPU hot path; --gpus N with N > 1 is not supported "
+              "(no collectives are part of it)", file=sys.stderr)
+        sys.exit(2)
+    if args.steps < 1 or args.warmup < 0:
+        print("bench.py: --steps must be at least 1 and --warmup at least 0", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2604_02651_amd as sg
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    log("torch and libsgnn loaded")
+    dev = "cuda:0"
+    graph_req = "off" if args.no_graph else args.graph
+    cfg = si.CONFIGS[args.config]
+    model = args.workload == "model"
+    fdt = torch.bfloat16 if cfg.bf16_features and not model else torch.float32
+    g, X, labels, weights = make_inputs(si, torch, cfg, dev, fdt)
+    res, st = measure(args, sg, si, torch, cfg, g, X, labels, weights, graph_req, cfg.name)
+    if args.profile_steps_only:
+        return
+    out = {"metric": METRIC, "value": res["value"], "unit": res["unit"], "n_gpus": 1, "steps": res["steps"],
+           "warmup": res["warmup"], "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": res["dtype"], "data": "synthetic", "config": res["config"],
+           "roofline": res["roofline"]}
 
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
@@ -231,22 +386,44 @@ def main():
         for _ in range(5):
             sg.sgnn_copy_f32(st.ctx, src, dst)
         torch.cuda.synchronize()
+        del src, dst
 
+    del st
+    gc.collect()
+    torch.cuda.empty_cache()
     if not args.no_cpu_baseline and not model:
-        import oracle
-        rp, ci = g.rowptr.cpu().numpy(), g.colidx.cpu().numpy()
-        Xh, lh = X.float().cpu().numpy(), labels.cpu().numpy()
-        wnp = [(W.double().cpu().numpy(), b.double().cpu().numpy()) for W, b in weights]
-        nsteps = args.cpu_steps or {"tiny": 50, "medium": 8}.get(cfg.name, 1)
-        oracle.gcn_step(cfg.N, rp, ci, Xh, lh, wnp, min(cfg.B, 1024), cfg.sampler_seed, 0, bf16=cfg.bf16_mfma)  # warm-up
-        c0 = time.perf_counter()
-        for t in range(nsteps):
-            oracle.gcn_step(cfg.N, rp, ci, Xh, lh, wnp, cfg.B, cfg.sampler_seed, t % period, bf16=cfg.bf16_mfma)
-        cpu_s = time.perf_counter() - c0
-        out["cpu_baseline"] = {"value": nsteps / cpu_s, "unit": "steps/s", "cores": oracle.num_threads(), "kind": "oracle",
-                               "sample": "%d whole steps (sampler counters 0..%d) of the same workload, %.1f s"
-                                         % (nsteps, nsteps - 1, cpu_s)}
-    print(json.dumps(out))
+        out["cpu_baseline"] = cpu_baseline(args, si, torch, cfg, g, X, weights)
+        log("oracle leg done: %.4f steps/s" % out["cpu_baseline"]["value"])
+
+    extras = args.extras
+    if extras == "auto":
+        extras = "dense,xlarge_f32_features" if (cfg.name == "xlarge" and not model) else "none"
+    others = {}
+    for name in [e for e in extras.split(",") if e and e != "none"]:
+        try:
+            if name == "xlarge_f32_features":
+                c2 = si.CONFIGS["xlarge"]
+                g2 = g if cfg.name == "xlarge" else None
+                del X
+                X = None
+                gc.collect(); torch.cuda.empty_cache()
+                g2, X2, l2, w2 = make_inputs(si, torch, c2, dev, torch.float32, graph=g2)
+            else:
+                c2 = si.CONFIGS[name]
+                g2, X2, l2, w2 = make_inputs(si, torch, c2, dev, torch.float32)
+            r2, st2 = measure(args, sg, si, torch, c2, g2, X2, l2, w2, graph_req, name)
+            others[name] = {"value": r2["value"], "unit": "steps/s", "ms_per_step": r2["ms_per_step"], "dtype": r2["dtype"],
+                            "workload": r2["config"]["workload"], "hip_graph": r2["config"]["hip_graph"],
+                            "single_stream_steps_per_s": r2["config"]["single_stream_steps_per_s"],
+                            "roofline": r2["roofline"]}
+            del st2, X2, l2, w2, g2
+            gc.collect(); torch.cuda.empty_cache()
+        except Exception as e:       # a sub-object must never cost the headline line
+            others[name] = {"error": "%s: %s" % (type(e).__name__, e)}
+            log("extra workload %s failed: %s" % (name, e))
+    if others:
+        out["other_workloads"] = others
+    print(json.dumps(out), flush=True)
 
 
 if __name__ == "__main__":

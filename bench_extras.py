@@ -1,17 +1,17 @@
 #!/usr/bin/env python3
 """Measurements of the parts of the method around the headline step, one JSON line each:
 
-  python -m paper_2604_02651_amd.bench_extras --what tail  [--config medium]
+  python bench_extras.py --what tail  [--config medium]
       the fused layer tail (RMSNorm + ReLU + dropout + residual, Eqs. 7-10) forward and backward
-  python -m paper_2604_02651_amd.bench_extras --what eval  [--config large]
+  python bench_extras.py --what eval  [--config large]
       the full-graph evaluation forward: normalised adjacency of all N vertices (Eq. 3), every layer
-  python -m paper_2604_02651_amd.bench_extras --what stages [--config large]
+  python bench_extras.py --what stages [--config large]
       mini-batch construction stage by stage: sampler (Gkeys/s against the integer ALU), induced CSR
       extraction and the feature slice (GB/s of compulsory traffic against HBM)
-  python -m paper_2604_02651_amd.bench_extras --what gemm  [--config medium] [--only TN]
+  python bench_extras.py --what gemm  [--config medium] [--only TN]
       the dense products of one training step at the configuration's shapes (transform, input
       gradient, weight gradient of every layer: Eqs. 6, 22, 24), each alone, against the MFMA peak
-  python -m paper_2604_02651_amd.bench_extras --what shard [--config medium] [--grid 2]
+  python bench_extras.py --what shard [--config medium] [--grid 2]
       one GPU's share of the distributed extraction (Algorithm 2): the shard of the mini-batch matrix
       for one row range and one column range of a grid x grid partition, and its transpose
 
@@ -25,7 +25,7 @@ import json
 import os
 import sys
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
