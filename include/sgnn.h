@@ -107,6 +107,28 @@ int sgnn_sample_uniform(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, ui
                         int32_t *S, uint64_t *bitmap, uint32_t *rank, sgnn_stream stream);
 
 /*
+ * The same sample for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  It takes no context (creating one allocates) and runs on
+ * the CURRENT device; the kernels are those of sgnn_sample_uniform, and so are S, bitmap and rank, bit for bit.
+ * The sampler's scratch (histogram, selection state, candidate list, workgroup counts: 1.7 MB) is a
+ * file-scope device array inside the library, of which every GPU the library runs on holds one copy until
+ * the process ends; its address is looked up once per device (by sgnn_ctx_create on that device, else by the
+ * first call here) and the call itself makes no hipMalloc / hipFree and no allocating library call.
+ *   N           at most SGNN_STATIC_SAMPLER_MAX_N (what the array is sized for); beyond it SGNN_ERR_CAPACITY
+ *   status_dev  device uint32[1] or NULL: sticky error bits OR-ed in by the kernels (bit 0: the selection was
+ *               inconsistent - candidate list overflow, probability below 1e-15 for Philox keys); with NULL the
+ *               bits go to a word inside the array that nothing reads
+ * All calls on one GPU share that GPU's array, whichever stream they use: two calls that overlap in time on
+ * one GPU race.  What has to start at zero is cleared by a kernel at the start of every call (no memset node,
+ * so the call can be captured into a HIP graph).
+ * Errors as sgnn_sample_uniform; the message of a failure is returned by sgnn_last_error(NULL) on the
+ * calling thread.
+ */
+#define SGNN_STATIC_SAMPLER_MAX_N (1ull << 27)
+int sgnn_sample_uniform_static(uint64_t N, uint32_t B, uint64_t seed, uint64_t step, int32_t *S, uint64_t *bitmap,
+                               uint32_t *rank, uint32_t *status_dev, sgnn_stream stream);
+
+/*
  * The full graph: canonical CSR of A + I (Eq. 3) - ascending unique columns in every row and
  * exactly one self-loop per row.  rowptr has N+1 entries of int32 or int64.
  * val == NULL: a_vu = 1/sqrt(deg(v) deg(u)), deg = row length (self-loop included);

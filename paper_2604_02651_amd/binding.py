@@ -74,6 +74,7 @@ def lib():
         L.sgnn_ctx_profile.argtypes = [vp, ci]
         L.sgnn_ctx_profile_read.argtypes = [vp, C.c_char_p, u64]
         L.sgnn_sample_uniform.argtypes = [vp, u64, u32, u64, u64, vp, vp, vp, vp]
+        L.sgnn_sample_uniform_static.argtypes = [u64, u32, u64, u64, vp, vp, vp, vp, vp]
         L.sgnn_induced_csr.argtypes = [vp, C.POINTER(_Graph), vp, u32, vp, vp, ci, ci, C.POINTER(_Csr),
                                        C.POINTER(u64), vp]
         L.sgnn_csr_plan_bytes.argtypes = [u32, u64]
@@ -237,6 +238,20 @@ def sgnn_sample_uniform(ctx: Context, N: int, B: int, seed: int, step: int, S: t
     ctx.check(lib().sgnn_sample_uniform(ctx._h, N, B, seed & (2**64 - 1), step & (2**64 - 1), _ptr(S, torch.int32, "S"),
                                         _ptr(bitmap, torch.int64, "bitmap"), _ptr(rank, torch.int32, "rank"),
                                         _stream(stream)))
+
+
+def sgnn_sample_uniform_static(N: int, B: int, seed: int, step: int, S: torch.Tensor, bitmap: torch.Tensor,
+                               rank: torch.Tensor, status: Optional[torch.Tensor] = None, stream=None):
+    """sgnn_sample_uniform without a context and without any allocation, on the current device of S."""
+    W = (N + 63) // 64
+    if S.numel() < B or bitmap.numel() < W or rank.numel() < W:
+        raise ValueError("output tensor too small")
+    with torch.cuda.device(S.device):
+        rc = lib().sgnn_sample_uniform_static(N, B, seed & (2**64 - 1), step & (2**64 - 1), _ptr(S, torch.int32, "S"),
+                                              _ptr(bitmap, torch.int64, "bitmap"), _ptr(rank, torch.int32, "rank"),
+                                              _ptr(status, torch.int32, "status"), _stream(stream))
+    if rc < 0:
+        raise SgnnError(rc, lib().sgnn_last_error(None).decode())
 
 
 def sgnn_induced_csr(ctx: Context, N: int, rowptr: torch.Tensor, colidx: torch.Tensor, val: Optional[torch.Tensor],

@@ -10,19 +10,22 @@
 #include "common.h"
 
 size_t sgnn_sampler_persist_bytes();
+int sgnn_static_scratch_init(int device);
 size_t sgnn_sampler_ws_bytes(uint64_t N);
 size_t sgnn_induced_ws_bytes(uint64_t E, uint32_t B);
 size_t sgnn_gemm_ws_bytes(uint32_t d_max);
 size_t sgnn_spmm_ws_bytes(uint64_t max_entries, uint32_t B, uint32_t d_max);
 
+// message of the last failing call that had no context (the allocation-free entry point), per thread
+static thread_local char g_err_no_ctx[512] = "";
+
 int sgnn_fail(sgnn_ctx *ctx, int code, const char *fmt, ...)
 {
-    if (ctx) {
-        va_list ap;
-        va_start(ap, fmt);
-        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
-        va_end(ap);
-    }
+    va_list ap;
+    va_start(ap, fmt);
+    if (ctx) vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    else vsnprintf(g_err_no_ctx, sizeof(g_err_no_ctx), fmt, ap);
+    va_end(ap);
     return code;
 }
 
@@ -96,6 +99,8 @@ int sgnn_ctx_create(sgnn_ctx **out, int device)
         return SGNN_ERR_HIP;
     }
     ctx->status = reinterpret_cast<uint32_t *>(ctx->persist + PERSIST_BYTES - 256);
+    sgnn_static_scratch_init(device);     // address of the allocation-free sampler's scratch on this device (failure is
+                                          // reported by that entry point itself)
     *out = ctx;
     return SGNN_OK;
 }
@@ -116,7 +121,7 @@ int sgnn_ctx_destroy(sgnn_ctx *ctx)
     return SGNN_OK;
 }
 
-const char *sgnn_last_error(const sgnn_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+const char *sgnn_last_error(const sgnn_ctx *ctx) { return ctx ? ctx->err : g_err_no_ctx; }
 
 int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t d_max, uint64_t max_entries)
 {

@@ -13,6 +13,7 @@
 //   6. sampler_rank_kernel     rank prefix per bitmap word and the ascending list S
 #include "block_prims.h"
 #include <algorithm>
+#include <mutex>
 
 #include "common.h"
 #include "philox.h"
@@ -281,6 +282,39 @@ size_t sgnn_sampler_ws_bytes(uint64_t N)
     return cap * 12 + EMIT_MAX_WG * 4 + 4 * 256;
 }
 
+// The six launches.  ctx may be NULL (no profiling, errors through sgnn_fail(NULL, ...)); every buffer
+// comes from the caller of this function: hist (HIST_BINS words, zero on entry, left zero), state,
+// the candidate list of `cap` entries, EMIT_MAX_WG workgroup counts and the sticky status word.
+#define SAMP_LAUNCH(name, kernel, grid, block, ...)                                                        \
+    do {                                                                                                  \
+        if (ctx && ctx->prof_on) sgnn_prof_begin(ctx, st, name, "");                                       \
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                                       \
+        if (ctx && ctx->prof_on) sgnn_prof_end(ctx, st);                                                   \
+        SGNN_LAUNCH_CHECK(ctx, name);                                                                     \
+    } while (0)
+
+static int sampler_launches(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, uint64_t step, int32_t *S,
+                            uint64_t *bitmap, uint32_t *rank, uint32_t *hist, sampler_state *state, uint64_t *cand_key,
+                            uint32_t *cand_v, uint32_t cap, uint32_t *wg_count, uint32_t *status, hipStream_t st)
+{
+    const uint64_t J = (N + 1) >> 1;
+    const unsigned grid = (unsigned)std::min<uint64_t>(cdiv(J, SAMP_NT), 2048);
+    SAMP_LAUNCH("sampler_hist_kernel", sampler_hist_kernel, dim3(grid), dim3(SAMP_NT), N, seed, step, hist);
+    SAMP_LAUNCH("sampler_pick_bin_kernel", sampler_pick_bin_kernel, dim3(1), dim3(1024), B, hist, state);
+    SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel, dim3(grid), dim3(SAMP_NT), N, seed, step, state, cand_key,
+                cand_v, cap, status);
+    SAMP_LAUNCH("sampler_threshold_kernel", sampler_threshold_kernel, dim3(1), dim3(1024), state, cand_key, cand_v, cap);
+
+    const uint64_t W = (N + 63) / 64;
+    const unsigned egrid = (unsigned)std::min<uint64_t>(cdiv(W, 8), EMIT_MAX_WG);
+    const uint64_t wpw = (uint64_t)cdiv(cdiv(W, egrid), 8) * 8;
+    SAMP_LAUNCH("sampler_emit_kernel", sampler_emit_kernel, dim3(egrid), dim3(SAMP_NT), N, seed, step, state, bitmap, W, wpw,
+                wg_count);
+    SAMP_LAUNCH("sampler_rank_kernel", sampler_rank_kernel, dim3(egrid), dim3(SAMP_NT), bitmap, W, wpw, wg_count, B, rank, S,
+                status);
+    return SGNN_OK;
+}
+
 int sgnn_launch_sampler(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, uint64_t step, int32_t *S,
                         uint64_t *bitmap, uint32_t *rank, hipStream_t st)
 {
@@ -294,21 +328,91 @@ int sgnn_launch_sampler(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, ui
     if (!ws.ok)
         return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_sample_uniform: scratch too small (%zu bytes needed): call sgnn_ctx_reserve",
                          ws.off);
+    return sampler_launches(ctx, N, B, seed, step, S, bitmap, rank, hist, state, cand_key, cand_v, cap, wg_count, ctx->status, st);
+}
 
-    const uint64_t J = (N + 1) >> 1;
-    const unsigned grid = (unsigned)std::min<uint64_t>(cdiv(J, SAMP_NT), 2048);
-    SGNN_LAUNCH(ctx, st, "sampler_hist_kernel", SGNN_TAG, sampler_hist_kernel, dim3(grid), dim3(SAMP_NT), 0, st, N, seed, step, hist);
-    SGNN_LAUNCH(ctx, st, "sampler_pick_bin_kernel", SGNN_TAG, sampler_pick_bin_kernel, dim3(1), dim3(1024), 0, st, B, hist, state);
-    SGNN_LAUNCH(ctx, st, "sampler_collect_kernel", SGNN_TAG, sampler_collect_kernel, dim3(grid), dim3(SAMP_NT), 0, st, N, seed, step, state, cand_key, cand_v,
-                       cap, ctx->status);
-    SGNN_LAUNCH(ctx, st, "sampler_threshold_kernel", SGNN_TAG, sampler_threshold_kernel, dim3(1), dim3(1024), 0, st, state, cand_key, cand_v, cap);
+// ---- the same sampler without any allocation: scratch in a file-scope device array ---------------------
 
-    const uint64_t W = (N + 63) / 64;
-    const unsigned egrid = (unsigned)std::min<uint64_t>(cdiv(W, 8), EMIT_MAX_WG);
-    const uint64_t wpw = (uint64_t)cdiv(cdiv(W, egrid), 8) * 8;
-    SGNN_LAUNCH(ctx, st, "sampler_emit_kernel", SGNN_TAG, sampler_emit_kernel, dim3(egrid), dim3(SAMP_NT), 0, st, N, seed, step, state, bitmap, W, wpw,
-                       wg_count);
-    SGNN_LAUNCH(ctx, st, "sampler_rank_kernel", SGNN_TAG, sampler_rank_kernel, dim3(egrid), dim3(SAMP_NT), 0, st, bitmap, W, wpw, wg_count, B, rank, S,
-                       ctx->status);
+namespace {
+
+constexpr uint64_t STATIC_MAX_N = SGNN_STATIC_SAMPLER_MAX_N;
+constexpr uint32_t STATIC_CAP = (uint32_t)(2 * (STATIC_MAX_N >> HIST_BITS) + 8192);     // cand_capacity(STATIC_MAX_N)
+constexpr size_t ST_HIST = 0;                                        // uint32[HIST_BINS]
+constexpr size_t ST_STATE = ST_HIST + HIST_BINS * sizeof(uint32_t);  // sampler_state
+constexpr size_t ST_STATUS = ST_STATE + 256;                         // uint32 sticky status (when the caller passes none)
+constexpr size_t ST_WG = ST_STATUS + 256;                            // uint32[EMIT_MAX_WG]
+constexpr size_t ST_CKEY = ST_WG + EMIT_MAX_WG * sizeof(uint32_t);   // uint64[STATIC_CAP]
+constexpr size_t ST_CV = ST_CKEY + (size_t)STATIC_CAP * sizeof(uint64_t);   // uint32[STATIC_CAP]
+constexpr size_t ST_BYTES = (ST_CV + (size_t)STATIC_CAP * sizeof(uint32_t) + 255) & ~size_t(255);
+constexpr int MAX_DEVICES = 64;
+
+// zeroes the histogram and the selection state: the array keeps the last call's contents, and a call that
+// was abandoned half way (a failed launch) may have left counts behind
+__global__ __launch_bounds__(SAMP_NT) void sampler_static_clear_kernel(uint32_t *__restrict__ words, uint32_t n)
+{
+    for (uint32_t i = blockIdx.x * SAMP_NT + threadIdx.x; i < n; i += gridDim.x * SAMP_NT) words[i] = 0;
+}
+
+} // namespace
+
+// Every GPU the library runs on holds its own copy of this array, at its own address, until the process ends.
+static __device__ __align__(256) uint8_t scratch[ST_BYTES];
+
+// device address of `scratch` on each GPU, resolved once per device with that device current
+static uint8_t *g_scratch_ptr[MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(int device, uint8_t **out)
+{
+    if (device < 0 || device >= MAX_DEVICES)
+        return sgnn_fail(nullptr, SGNN_ERR_UNSUPPORTED, "sgnn_sample_uniform_static: device %d outside the supported 0..%d", device,
+                         MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        uint8_t *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return sgnn_fail(nullptr, SGNN_ERR_HIP, "sgnn_sample_uniform_static: hipGetSymbolAddress failed on device %d: %s", device,
+                             hipGetErrorString(e));
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
     return SGNN_OK;
+}
+
+// Called by sgnn_ctx_create (the library's set-up call) with the context's device current, so that a later
+// sgnn_sample_uniform_static on that device finds the address resolved.
+int sgnn_static_scratch_init(int device)
+{
+    uint8_t *p = nullptr;
+    return static_scratch(device, &p);
+}
+
+extern "C" int sgnn_sample_uniform_static(uint64_t N, uint32_t B, uint64_t seed, uint64_t step, int32_t *S, uint64_t *bitmap,
+                                          uint32_t *rank, uint32_t *status_dev, sgnn_stream stream)
+{
+    if (!S || !bitmap || !rank) return sgnn_fail(nullptr, SGNN_ERR_INVALID_ARG, "sgnn_sample_uniform_static: null output pointer");
+    if (B == 0 || B > N)
+        return sgnn_fail(nullptr, SGNN_ERR_INVALID_ARG, "sgnn_sample_uniform_static: need 1 <= B <= N (B=%u, N=%llu)", B,
+                         (unsigned long long)N);
+    if (N > STATIC_MAX_N)
+        return sgnn_fail(nullptr, SGNN_ERR_CAPACITY, "sgnn_sample_uniform_static: N = %llu exceeds the %llu vertices the static "
+                         "scratch is sized for; use sgnn_sample_uniform with a context", (unsigned long long)N,
+                         (unsigned long long)STATIC_MAX_N);
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return sgnn_fail(nullptr, SGNN_ERR_HIP, "sgnn_sample_uniform_static: hipGetDevice failed");
+    uint8_t *ptr = nullptr;
+    int rc = static_scratch(device, &ptr);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(ptr + ST_HIST);
+    sampler_state *state = reinterpret_cast<sampler_state *>(ptr + ST_STATE);
+    uint32_t *status = status_dev ? status_dev : reinterpret_cast<uint32_t *>(ptr + ST_STATUS);
+    sgnn_ctx *ctx = nullptr;
+    // histogram and state are contiguous: one small fill kernel (no memset node: the call may be captured)
+    SAMP_LAUNCH("sampler_static_clear_kernel", sampler_static_clear_kernel, dim3(2), dim3(SAMP_NT), hist,
+                (uint32_t)((ST_STATUS - ST_HIST) / sizeof(uint32_t)));
+    return sampler_launches(nullptr, N, B, seed, step, S, bitmap, rank, hist, state, reinterpret_cast<uint64_t *>(ptr + ST_CKEY),
+                            reinterpret_cast<uint32_t *>(ptr + ST_CV), cand_capacity(N), reinterpret_cast<uint32_t *>(ptr + ST_WG),
+                            status, st);
 }
