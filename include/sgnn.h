@@ -75,8 +75,11 @@ const char *sgnn_last_error(const sgnn_ctx *ctx);
 
 /*
  * Synchronises `stream` and reads the device-side status word that kernels set when a
- * consistency check fails (sampler candidate buffer overflow).  Returns SGNN_OK or
- * SGNN_ERR_INTERNAL, and clears the word.
+ * check on the device fails, and clears the word.  Returns SGNN_OK; SGNN_ERR_CAPACITY if the
+ * only finding is that an asynchronous sgnn_induced_csr (nnz_host == NULL) produced more entries
+ * than out->capacity (the surplus was dropped, so whatever was computed from that matrix is
+ * invalid); SGNN_ERR_INTERNAL for a failed consistency check (sampler candidate buffer overflow,
+ * an entry count of 2^31 or more).
  */
 int sgnn_ctx_status(sgnn_ctx *ctx, sgnn_stream stream);
 
@@ -178,7 +181,9 @@ int sgnn_csr_plan(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_stream stream);
  *   rescale   1       divide off-diagonal entries by p;  0: leave them
  *   out               rows/cols are set to B; rowptr[B+1] always complete; colidx/val are written
  *                     up to out->capacity entries
- *   nnz_host          NULL: fully asynchronous.  Otherwise the stream is synchronised, the entry
+ *   nnz_host          NULL: fully asynchronous; an entry count above out->capacity then sets a sticky
+ *                     bit in the device status word, which the next sgnn_ctx_status reports as
+ *                     SGNN_ERR_CAPACITY.  Otherwise the stream is synchronised, the entry
  *                     count is stored there, and SGNN_ERR_CAPACITY is returned if it exceeds
  *                     out->capacity (the required count is still reported).
  * The entry count must stay below 2^31 (checked on the device, reported by sgnn_ctx_status).

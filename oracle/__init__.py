@@ -336,7 +336,7 @@ def num_threads() -> int:
 
 
 def gcn_step(N, rowptr, colidx, X, labels, weights, B, seed, step, bf16=False, norm_mode=0, rescale=1,
-             relu_ties=None, tie_band=0.0):
+             relu_ties=None, tie_band=0.0, store_bf16=False, dO_ties=None, logit_band=0.0):
     """One whole mini-batch step (Algorithm 1 without the parameter update): sample, induce,
     slice, L layers forward (ReLU on all but the last), mean cross-entropy, L layers backward.
     `weights` is a list of (W, b).  Returns a dict of every intermediate, float64.
@@ -344,26 +344,62 @@ def gcn_step(N, rowptr, colidx, X, labels, weights, B, seed, step, bf16=False, n
     ReLU ties: a pre-activation within tie_band * max|Z| of zero has no decidable sign at the
     working precision, and either mask value is a correct result there.  relu_ties[l], when
     given, is a boolean B x d_out array; inside that band (and only there) the backward mask of
-    layer l takes its value instead of the oracle's own Z > 0.  The forward values never change."""
+    layer l takes its value instead of the oracle's own Z > 0.  The forward values never change.
+    store_bf16, dO_ties, logit_band: see layers_step."""
     S = sample_uniform(N, B, seed, step)
     rpS, ciS, vS = induced_csr(N, rowptr, colidx, S, None, norm_mode, rescale)
     H = gather_rows(X, S)
     yS = gather_labels(labels, S)
-    out = layers_step(rpS, ciS, vS, H, yS, weights, bf16=bf16, relu_ties=relu_ties, tie_band=tie_band)
+    out = layers_step(rpS, ciS, vS, H, yS, weights, bf16=bf16, relu_ties=relu_ties, tie_band=tie_band,
+                      store_bf16=store_bf16, dO_ties=dO_ties, logit_band=logit_band)
     out["S"] = S
     return out
 
 
-def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie_band=0.0, dO=None):
+def undecidable_loss_rows(O, labels, logit_band):
+    """Rows of the logits O whose cross-entropy gradient row is not decidable at a relative logit
+    accuracy of logit_band.
+
+    With every logit of row i known to within eps_i = logit_band * max_j |O_ij|, a probability
+    p_j = softmax(O_i)_j lies between p_j e^(-2 eps_i) and p_j e^(2 eps_i), and so does 1 - p_j with
+    respect to itself; entry j of the gradient row (softmax(O_i) - onehot(y_i)) / B can therefore move
+    by at most min(p_j, 1 - p_j) (e^(2 eps_i) - 1) / B.  The row is undecidable when that bound, taken
+    over its entries, exceeds logit_band times the largest gradient entry of the whole batch (the
+    scale the weight gradients are measured on): large logits whose leading probabilities are not
+    saturated.  Rows with small logits, and rows with one dominant class, are decidable."""
+    O = np.asarray(O, np.float64)
+    if logit_band <= 0.0:
+        return np.zeros(O.shape[0], bool)
+    m = O.max(axis=1, keepdims=True)
+    e = np.exp(O - m)
+    p = e / e.sum(axis=1, keepdims=True)
+    eps = logit_band * np.abs(O).max(axis=1)
+    onehot = np.zeros_like(p)
+    onehot[np.arange(O.shape[0]), np.asarray(labels, np.int64)] = 1.0
+    g = np.abs(p - onehot).max()
+    q = np.minimum(p, 1.0 - p).max(axis=1)
+    with np.errstate(over="ignore"):
+        grow = np.expm1(2.0 * eps)
+    bound = np.where(q > 0.0, q * np.where(np.isfinite(grow), grow, np.finfo(np.float64).max / 2), 0.0)
+    return bound > logit_band * g
+
+
+def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie_band=0.0, store_bf16=False,
+                dO_ties=None, logit_band=0.0):
     """The layer part of a step on an already extracted mini-batch: L layers forward, mean
     cross-entropy, L layers backward (see gcn_step for relu_ties / tie_band).
 
-    dO, when given, replaces the oracle's own loss gradient as the start of the backward pass (the
-    forward values and the returned loss and "dO" stay the oracle's).  With rounded operands the
-    logits of the two sides agree to a relative 2^-8 or so; where they are large (the 1/p rescale
-    makes them so) that is an absolute difference a softmax turns into a different gradient row,
-    so a test checks the loss gradient against softmax_xent of the logits it was computed from and
-    hands it in here to compare the backward pass on the same start."""
+    store_bf16: the activations H_l (l < L) are stored as bfloat16 between the layers (the reading
+    taken for the configuration whose features and activations are bfloat16): they are rounded to
+    nearest even once, after the activation, and everything downstream - the next aggregation, the
+    ReLU mask - sees the stored value.  The aggregates T_l are GEMM operands and are rounded by
+    bf16=True already; the logits H_L and all gradients stay unrounded.
+
+    dO_ties, logit_band: the loss gradient has the same kind of undecidable set as the ReLU mask.
+    Rows of the logits for which undecidable_loss_rows(H_L, y, logit_band) holds form the returned
+    "dO_band"; inside it (and only there) the backward pass starts from the rows of dO_ties when
+    given; every other row starts from the oracle's own gradient.  The forward values, the loss and
+    the returned "dO" are always the oracle's own."""
     B = len(rpS) - 1
     H = np.ascontiguousarray(X_S, np.float64)
     yS = np.ascontiguousarray(y_S, np.int32)
@@ -378,11 +414,15 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
         band = np.abs(Z) <= tie_band * np.abs(Z).max() if relu else np.zeros_like(mask)
         if relu and relu_ties is not None and relu_ties[l] is not None:
             mask = np.where(band, np.asarray(relu_ties[l], bool), mask)
+        if relu and store_bf16:
+            Y = round_bf16(Y)
         Ts.append(T); Hs.append(Y); masks.append(mask); bands.append(band)
     loss, dY = softmax_xent(Hs[-1], yS)
     dO_own = dY
-    if dO is not None:
-        dY = np.ascontiguousarray(dO, np.float64)
+    dO_band = undecidable_loss_rows(Hs[-1], yS, logit_band)
+    if dO_ties is not None and dO_band.any():
+        dY = dY.copy()
+        dY[dO_band] = np.asarray(dO_ties, np.float64)[dO_band]
     dWs, dbs, dHs = [None] * L, [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
         W, b = weights[l]
@@ -391,5 +431,5 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
         dH, dW, db = gcn_bwd(rpT, ciT, vT, Ts[l], W, Ymask, dY, relu=relu, bf16=bf16, need_dH=(l > 0))
         dWs[l], dbs[l], dHs[l] = dW, db, dH
         dY = dH
-    return dict(rowptr=rpS, colidx=ciS, val=vS, X_S=H, y_S=yS, T=Ts, H=Hs, loss=loss, dO=dO_own, dW=dWs, db=dbs, dH=dHs,
-                relu_band=bands, relu_mask=masks)
+    return dict(rowptr=rpS, colidx=ciS, val=vS, X_S=H, y_S=yS, T=Ts, H=Hs, loss=loss, dO=dO_own, dO_band=dO_band, dW=dWs,
+                db=dbs, dH=dHs, relu_band=bands, relu_mask=masks)

@@ -161,9 +161,12 @@ int sgnn_ctx_status(sgnn_ctx *ctx, sgnn_stream stream)
     if (word) {
         SGNN_HIP(ctx, hipMemsetAsync(ctx->status, 0, sizeof(word), st));
         SGNN_HIP(ctx, hipStreamSynchronize(st));
-        return sgnn_fail(ctx, SGNN_ERR_INTERNAL, "device status 0x%x:%s%s", word,
+        return sgnn_fail(ctx, (word & ~SGNN_ST_CAPACITY_OVERFLOW) ? SGNN_ERR_INTERNAL : SGNN_ERR_CAPACITY,
+                         "device status 0x%x:%s%s%s", word,
                          (word & SGNN_ST_CAND_OVERFLOW) ? " sampler selection inconsistent" : "",
-                         (word & SGNN_ST_NNZ_OVERFLOW) ? " induced entry count exceeds int32" : "");
+                         (word & SGNN_ST_NNZ_OVERFLOW) ? " induced entry count exceeds int32" : "",
+                         (word & SGNN_ST_CAPACITY_OVERFLOW) ? " a mini-batch matrix had more entries than its capacity "
+                                                              "(entries were dropped: the results of that step are invalid)" : "");
     }
     return SGNN_OK;
 }
@@ -243,7 +246,8 @@ static int induced_impl(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, ui
     sgnn_csr o = *out;
     o.rows = o.cols = B;
     if (nnz_host && !nnz_dev) o.nnz_dev = ctx->status + 2;
-    rc = sgnn_launch_induced(ctx, g, S, B, bitmap, rank, norm_mode, rescale, R0, R1, C0, C1, &o, st);
+    // with a host read-back the overflow is reported right here; without one through the sticky status word
+    rc = sgnn_launch_induced(ctx, g, S, B, bitmap, rank, norm_mode, rescale, R0, R1, C0, C1, &o, nnz_host ? 0 : 1, st);
     if (rc) return rc;
     rc = sgnn_launch_spmm_plan(ctx, &o, st);
     if (rc) return rc;

@@ -38,6 +38,7 @@ struct sgnn_ctx {
 // status bits
 #define SGNN_ST_CAND_OVERFLOW 1u
 #define SGNN_ST_NNZ_OVERFLOW 2u
+#define SGNN_ST_CAPACITY_OVERFLOW 4u
 
 int sgnn_fail(sgnn_ctx *ctx, int code, const char *fmt, ...);
 
@@ -100,7 +101,7 @@ int sgnn_launch_sampler(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, ui
                         uint64_t *bitmap, uint32_t *rank, hipStream_t st);
 int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B,
                         const uint64_t *bitmap, const uint32_t *rank, int norm_mode, int rescale, int64_t R0,
-                        int64_t R1, int64_t C0, int64_t C1, sgnn_csr *out, hipStream_t st);
+                        int64_t R1, int64_t C0, int64_t C1, sgnn_csr *out, int sticky_capacity, hipStream_t st);
 int sgnn_launch_csr_transpose(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_csr *out, ws_alloc *ws, hipStream_t st);
 size_t sgnn_transpose_ws_bytes(uint64_t max_entries, uint32_t B);
 int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const void *X, int x_bf16, int64_t ldx, const int32_t *row_index,

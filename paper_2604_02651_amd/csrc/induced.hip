@@ -38,9 +38,11 @@ struct shard_range { int64_t r0, r1, c0, c1; };
 template <class RP>
 __global__ __launch_bounds__(256) void induced_deg_kernel(const RP *__restrict__ rowptr, const int32_t *__restrict__ S,
                                                           uint32_t B, shard_range rg, uint32_t *__restrict__ deg,
-                                                          int64_t *__restrict__ rowstart, uint64_t *__restrict__ wg_sum)
+                                                          int64_t *__restrict__ rowstart, uint64_t *__restrict__ wg_sum,
+                                                          unsigned long long *__restrict__ total64)
 {
     __shared__ uint64_t lds[256 / 64];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *total64 = 0ull;     // survivors of the whole mini-batch, summed by the count pass
     uint64_t s = 0;
 #pragma unroll
     for (int k = 0; k < DEG_TILE / 256; ++k) {
@@ -173,7 +175,8 @@ __global__ __launch_bounds__(IND_NT) void induced_count_kernel(const int64_t *__
                                                                const uint32_t *__restrict__ tile_row,
                                                                uint32_t *__restrict__ tile_total,
                                                                uint64_t *__restrict__ keepbits,
-                                                               uint64_t *__restrict__ n_tiles_out)
+                                                               uint64_t *__restrict__ n_tiles_out,
+                                                               unsigned long long *__restrict__ total64)
 {
     __shared__ tile_table tt;
     __shared__ uint32_t lds[IND_NT / 64];
@@ -181,6 +184,7 @@ __global__ __launch_bounds__(IND_NT) void induced_count_kernel(const int64_t *__
     const uint64_t F = P[B];
     const uint64_t n_tiles = (F + IND_TILE - 1) / IND_TILE;
     if (blockIdx.x == 0 && threadIdx.x == 0) *n_tiles_out = n_tiles;
+    unsigned long long wg_total = 0;      // 64 bits: the 32-bit prefix over the tile counts wraps beyond 2^32 survivors
     for (uint64_t c = blockIdx.x; c < n_tiles; c += gridDim.x) {
         const uint64_t f0 = c * IND_TILE, f1 = min(F, f0 + IND_TILE);
         uint32_t r_lo, nr;
@@ -223,8 +227,9 @@ __global__ __launch_bounds__(IND_NT) void induced_count_kernel(const int64_t *__
             }
         }
         const uint32_t t = block_sum<uint32_t, IND_NT>(cnt, lds);   // ends with a barrier: tt may be reused
-        if (threadIdx.x == 0) tile_total[c] = t;
+        if (threadIdx.x == 0) { tile_total[c] = t; wg_total += t; }
     }
+    if (threadIdx.x == 0 && wg_total) atomicAdd(total64, wg_total);     // integer: the sum does not depend on the order
 }
 
 // Fill pass.  The keep words of the count pass say which edges survive, so only survivors are looked at again:
@@ -238,7 +243,8 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
     const uint64_t *__restrict__ bitmap, const uint32_t *__restrict__ rank, const uint64_t *__restrict__ P,
     const uint32_t *__restrict__ tile_row, const uint32_t *__restrict__ tile_off_all, const uint64_t *__restrict__ n_tiles_p, const uint64_t *__restrict__ keepbits, float inv_p, int write_val,
     int32_t *__restrict__ rowptr_S, int32_t *__restrict__ colidx_S, float *__restrict__ val_S, uint64_t capacity,
-    uint32_t *__restrict__ nnz_dev, uint32_t *__restrict__ status)
+    uint32_t *__restrict__ nnz_dev, uint32_t *__restrict__ status, const unsigned long long *__restrict__ total64,
+    int sticky_capacity)
 {
     __shared__ tile_table tt;
     __shared__ uint64_t balw[IND_WORDS];
@@ -249,7 +255,11 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
     if (blockIdx.x == 0) {
         const uint32_t total = tile_off_all[n_tiles];
         if (threadIdx.x == 0) {
-            if (total > 0x7fffffffu) atomicOr(status, SGNN_ST_NNZ_OVERFLOW);
+            const unsigned long long t64 = *total64;
+            if (t64 > 0x7fffffffull) atomicOr(status, SGNN_ST_NNZ_OVERFLOW);
+            // entries beyond the capacity are dropped below: without a host read-back of the count the caller learns
+            // of it through the sticky status word (sgnn_ctx_status)
+            if (sticky_capacity && t64 > capacity) atomicOr(status, SGNN_ST_CAPACITY_OVERFLOW);
             rowptr_S[B] = (int32_t)total;
             if (nnz_dev) *nnz_dev = total;
         }
@@ -378,7 +388,8 @@ __global__ __launch_bounds__(256) void induced_renorm_kernel(const int32_t *__re
 
 template <class RP>
 int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B, const uint64_t *bitmap,
-                 const uint32_t *rank, int norm_mode, int rescale, shard_range rg, sgnn_csr *out, hipStream_t st)
+                 const uint32_t *rank, int norm_mode, int rescale, shard_range rg, sgnn_csr *out, int sticky_capacity,
+                 hipStream_t st)
 {
     const RP *rowptr = static_cast<const RP *>(g->rowptr);
     ws_alloc ws(ctx);
@@ -394,17 +405,18 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
     uint32_t *tile_off = ws.get<uint32_t>(max_tiles + 1);
     uint32_t *scan_tmp = ws.get<uint32_t>(sgnn_scan_tmp_elems(max_tiles));
     uint64_t *n_tiles = ws.get<uint64_t>(1);
+    unsigned long long *total64 = ws.get<unsigned long long>(1);
     if (!ws.ok)
         return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_induced_csr: scratch too small (%zu bytes needed): call sgnn_ctx_reserve",
                          ws.off);
 
     SGNN_LAUNCH(ctx, st, "induced_deg_kernel", SGNN_TAG, induced_deg_kernel<RP>, dim3(n_deg_wg), dim3(256), 0, st, rowptr, S, B,
-                rg, deg, rowstart, deg_sum);
+                rg, deg, rowstart, deg_sum, total64);
     SGNN_LAUNCH(ctx, st, "induced_offsets_kernel", SGNN_TAG, induced_offsets_kernel, dim3(n_deg_wg), dim3(256), 0, st, deg, B,
                 deg_sum, P, tile_row);
     const unsigned grid = (unsigned)std::min<uint64_t>(max_tiles, IND_MAX_GRID);
     SGNN_LAUNCH(ctx, st, "induced_count_kernel", SGNN_TAG, induced_count_kernel, dim3(grid), dim3(IND_NT), 0, st, rowstart,
-                g->colidx, B, bitmap, rg, P, tile_row, tile_total, keepbits, n_tiles);
+                g->colidx, B, bitmap, rg, P, tile_row, tile_total, keepbits, n_tiles, total64);
     int rc = sgnn_scan_u32_devn(ctx, tile_total, tile_off, n_tiles, max_tiles, scan_tmp, st);
     if (rc) return rc;
     double p = 1.0;
@@ -412,7 +424,7 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
     SGNN_LAUNCH(ctx, st, "induced_fill_kernel", SGNN_TAG, induced_fill_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr,
                 g->colidx, norm_mode == 0 ? g->val : nullptr, S, rowstart, deg, B, bitmap, rank, P, tile_row, tile_off,
                 n_tiles, keepbits, (float)(1.0 / p), norm_mode == 0 ? 1 : 0, out->rowptr, out->colidx, out->val,
-                out->capacity, out->nnz_dev, ctx->status);
+                out->capacity, out->nnz_dev, ctx->status, total64, sticky_capacity);
     if (norm_mode == 1)
         SGNN_LAUNCH(ctx, st, "induced_renorm_kernel", SGNN_TAG, induced_renorm_kernel, dim3(cdiv((uint64_t)B * 64, 256)),
                     dim3(256), 0, st, out->rowptr, out->colidx, out->val, B, out->capacity, p);
@@ -454,16 +466,16 @@ size_t sgnn_induced_ws_bytes(uint64_t E, uint32_t B)
 {
     const uint64_t max_tiles = E / IND_TILE + 2;
     return (size_t)B * 12 + ((size_t)B + 1) * 8 + (size_t)cdiv(B, DEG_TILE) * 8 + max_tiles * 4 + (max_tiles + 1) * 4 +
-           max_tiles * IND_WORDS * 8 + (max_tiles + 1) * 4 + sgnn_scan_tmp_elems(max_tiles) * 4 + 8 + 12 * 256;
+           max_tiles * IND_WORDS * 8 + (max_tiles + 1) * 4 + sgnn_scan_tmp_elems(max_tiles) * 4 + 16 + 13 * 256;
 }
 
 int sgnn_launch_induced(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t B, const uint64_t *bitmap,
                         const uint32_t *rank, int norm_mode, int rescale, int64_t R0, int64_t R1, int64_t C0, int64_t C1,
-                        sgnn_csr *out, hipStream_t st)
+                        sgnn_csr *out, int sticky_capacity, hipStream_t st)
 {
     const shard_range rg = {R0, R1, C0, C1};
-    if (g->rowptr_is_i64) return launch_typed<int64_t>(ctx, g, S, B, bitmap, rank, norm_mode, rescale, rg, out, st);
-    return launch_typed<int32_t>(ctx, g, S, B, bitmap, rank, norm_mode, rescale, rg, out, st);
+    if (g->rowptr_is_i64) return launch_typed<int64_t>(ctx, g, S, B, bitmap, rank, norm_mode, rescale, rg, out, sticky_capacity, st);
+    return launch_typed<int32_t>(ctx, g, S, B, bitmap, rank, norm_mode, rescale, rg, out, sticky_capacity, st);
 }
 
 int sgnn_launch_graph_normalize(sgnn_ctx *ctx, const sgnn_graph *g, int32_t *rowptr32, float *val, hipStream_t st)

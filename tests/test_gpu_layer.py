@@ -6,7 +6,7 @@ import torch
 import oracle
 import paper_2604_02651_amd as sg
 import synth_inputs as si
-from gpu_util import DEV, TOL_BF16, TOL_F32, ctx, dev, rel_err
+from gpu_util import DEV, TOL_BF16, TOL_F32, TOL_VAL, ctx, dev, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -502,6 +502,8 @@ def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_b
         assert np.array_equal(st.S.cpu().numpy(), ref["S"])
         assert np.array_equal(st.A.rowptr.cpu().numpy(), ref["rowptr"]) and nnz == len(ref["colidx"])
         assert np.array_equal(st.A.colidx.cpu().numpy()[:nnz], ref["colidx"])
+        got_val = st.A.val.cpu().numpy()[:nnz].astype(np.float64)
+        assert np.all(np.abs(got_val - ref["val"]) <= TOL_VAL * np.abs(ref["val"]))
         assert np.array_equal(st.y_S.cpu().numpy(), ref["y_S"])
         if not fuse_slice:
             assert np.array_equal(st.X_S.cpu().numpy().astype(np.float64), ref["X_S"])
@@ -613,29 +615,45 @@ def test_whole_step_xlarge_bf16():
     y_S = si.labels_for(St, cfg.classes, cfg.label_seed).numpy()
     assert np.array_equal(st.y_S.cpu().numpy(), y_S)
     wnp = [(W.double().numpy(), b.double().numpy()) for W, b in weights]
-    ref = oracle.layers_step(rpS, ciS, vS, X_S, y_S, wnp, bf16=True, tie_band=1e-3)
-    ties = [st.H[l].cpu().numpy() > 0 for l in range(cfg.layers)]
+    store = bool(getattr(st, "bf16_activations", False))
+    band_l = TOL_BF16        # logits are held to this bar; it also defines which loss-gradient rows are decidable
+    ref = oracle.layers_step(rpS, ciS, vS, X_S, y_S, wnp, bf16=True, tie_band=1e-3, store_bf16=store, logit_band=band_l)
+    Hg = [st.H[l].float().cpu().numpy() for l in range(cfg.layers)]
+    ties = [h > 0 for h in Hg]
     for l in range(cfg.layers - 1):
         assert np.array_equal(ties[l][~ref["relu_band"][l]], ref["relu_mask"][l][~ref["relu_band"][l]])
-    # The loss gradient against its definition on the logits it was computed from (fp32 arithmetic), then the
-    # backward pass of both sides from that same gradient: with 1/p = 106 the logits reach the hundreds, a
-    # relative 2^-8 between the two sides' logits is an absolute 1, and one hub row whose two largest logits
-    # are that close gets a different softmax row on each side - which then carries most of the difference in
-    # every weight gradient (seen with bfloat16 features: 98 % of the error of dW of the last layer sat in
-    # the two columns of those classes).
+    # The loss gradient.  With 1/p = 106 the logits of hub rows reach the hundreds, a relative 2^-8 between the two
+    # sides' logits is an absolute 1 there, and a row whose leading logits are that close gets a different softmax
+    # row on each side.  The oracle says which rows those are from ITS OWN logits (undecidable_loss_rows); the
+    # device's gradient (checked against the definition on the logits it was computed from, to fp32 accuracy)
+    # enters the oracle's backward pass inside that set only, and only after its logits have been shown to lie
+    # within the band of the oracle's there; every other row starts from the oracle's own gradient.
+    O_gpu = Hg[-1].astype(np.float64)
     dO_gpu = st.dO.cpu().numpy().astype(np.float64)
-    _, dO_def = oracle.softmax_xent(st.H[-1].cpu().numpy().astype(np.float64), y_S.astype(np.int32))
+    _, dO_def = oracle.softmax_xent(O_gpu, y_S.astype(np.int32))
     assert rel_err(dO_gpu, dO_def) < TOL_F32
-    # the two sides' own gradients: rows of probabilities that differ by more than the bf16 bar are rare
+    und = ref["dO_band"]
+    O_ref = ref["H"][-1]
+    eps = band_l * np.abs(O_ref).max(axis=1)
     row_diff = np.abs(dO_gpu - ref["dO"]).max(axis=1) * cfg.B
-    assert np.mean(row_diff > TOL_BF16) < 1e-3
-    ref = oracle.layers_step(rpS, ciS, vS, X_S, y_S, wnp, bf16=True, tie_band=1e-3, relu_ties=ties, dO=dO_gpu)
+    print("undecidable loss rows: %d of %d (%.3f %%); largest own-gradient row difference outside them %.2e, inside %.2e"
+          % (und.sum(), cfg.B, 100.0 * und.mean(), row_diff[~und].max(), row_diff[und].max() if und.any() else 0.0), flush=True)
+    assert und.mean() < 0.02
+    assert np.all(np.abs(O_gpu - O_ref)[und] <= eps[und, None])
+    assert row_diff[~und].max() <= band_l            # decidable rows: the two sides' own gradients agree to the bar
+    if any((ties[l] != ref["relu_mask"][l]).any() for l in range(cfg.layers - 1)) or und.any():
+        ref = oracle.layers_step(rpS, ciS, vS, X_S, y_S, wnp, bf16=True, tie_band=1e-3, relu_ties=ties, store_bf16=store,
+                                 logit_band=band_l, dO_ties=dO_gpu)
     for l in range(cfg.layers):
         if st.T[l] is not None:
-            assert rel_err(st.T[l].cpu().numpy(), ref["T"][l]) < TOL_BF16, ("T", l)
-        assert rel_err(st.H[l].cpu().numpy(), ref["H"][l + 1]) < TOL_BF16, ("H", l)
+            assert rel_err(st.T[l].float().cpu().numpy(), ref["T"][l]) < TOL_BF16, ("T", l)
+        assert rel_err(Hg[l], ref["H"][l + 1]) < TOL_BF16, ("H", l)
         assert rel_err(st.dW[l].cpu().numpy(), ref["dW"][l]) < TOL_BF16, ("dW", l)
         assert rel_err(st.db[l].cpu().numpy(), ref["db"][l]) < TOL_BF16, ("db", l)
+        if l > 0:
+            # the ReLU backward of layer l-1 is fused into the product that writes dH: the buffer holds dH where
+            # H_{l-1} > 0 and zero elsewhere (the mask was checked against the oracle's above)
+            assert rel_err(st.dH[l].float().cpu().numpy(), ref["dH"][l] * ties[l - 1]) < TOL_BF16, ("dH", l)
     assert abs(st.loss.item() - ref["loss"]) < TOL_BF16 * abs(ref["loss"])
 
     # The full graph as the matrix of a sparse product (evaluation forward): 3.3 G entries, int64 row offsets,

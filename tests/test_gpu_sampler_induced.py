@@ -161,3 +161,13 @@ def test_induced_capacity_overflow_is_reported(tiny_graph):
     assert np.array_equal(out.rowptr.cpu().numpy(), ref[0])
     assert out.nnz() == len(ref[1])
     assert np.array_equal(out.colidx.cpu().numpy()[:100], ref[1][:100])
+    # without a host read-back of the count the overflow is sticky in the device status word: the next status query
+    # fails with the capacity code (once), so a training loop on the asynchronous path cannot run on a cut matrix unnoticed
+    with pytest.raises(sg.SgnnError) as e:
+        ctx().status()
+    assert e.value.code == -2 and "capacity" in str(e.value)
+    ctx().status()
+    # a matrix that fits leaves the word clear
+    out = sg.Csr(B, B, len(ref[1]), DEV)
+    sg.sgnn_induced_csr(ctx(), N, g.rowptr.to(DEV), g.colidx.to(DEV), None, S, B, bitmap, rank, out)
+    ctx().status()

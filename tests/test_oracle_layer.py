@@ -256,26 +256,81 @@ def test_relu_tie_band_only_acts_inside_the_band():
     assert not np.array_equal(out["dW"][0], base["dW"][0])
 
 
-def test_backward_from_a_given_loss_gradient():
-    # layers_step(dO=...) starts the backward pass from the gradient handed in and leaves everything of the
-    # forward pass alone: its own gradient gives the same result bit for bit, twice the gradient twice the
-    # weight gradients (the backward pass is linear in it), and "dO" / loss stay the oracle's own.
-    rng = np.random.default_rng(1)
-    Bn = 10
+def _small_stack(rng, Bn=10, scale=1.0):
     dense = (rng.random((Bn, Bn)) < 0.4) * rng.random((Bn, Bn)) + np.eye(Bn)
     rp = [0]; ci = []; v = []
     for i in range(Bn):
         nz = np.nonzero(dense[i])[0]
         ci += list(nz); v += list(dense[i, nz].astype(np.float32)); rp.append(len(ci))
     rp, ci, v = np.array(rp, np.int32), np.array(ci, np.int32), np.array(v, np.float32)
-    X = rng.standard_normal((Bn, 4)); y = rng.integers(0, 3, Bn).astype(np.int32)
+    X = rng.standard_normal((Bn, 4)) * scale; y = rng.integers(0, 3, Bn).astype(np.int32)
     Ws = [(rng.standard_normal((4, 5)), rng.standard_normal(5) * 0.1), (rng.standard_normal((5, 3)), np.zeros(3))]
-    base = oracle.layers_step(rp, ci, v, X, y, Ws)
+    return rp, ci, v, X, y, Ws
+
+
+def test_undecidable_loss_rows_are_the_large_unsaturated_ones():
+    # closed cases of the criterion max_j min(p_j, 1-p_j) (e^(2 eps) - 1) > band * max_ij|p - onehot|, eps = band * max|o|:
+    # small logits are decidable whatever their gap; large logits with one dominant class are decidable;
+    # large logits with two close leaders are not.
+    O = np.array([[0.10, 0.09, -0.2],        # small: eps = 2e-3, bound 0.5 * 4e-3
+                  [400.0, 100.0, -50.0],      # saturated: 1 - p = e^-300
+                  [400.0, 399.5, -50.0],      # two leaders half a unit apart with eps = 8: undecidable
+                  [400.0, 360.0, 0.0],        # gap 40 against 2 eps = 16: 1 - p = e^-40, bound e^-24
+                  [400.0, 390.0, 0.0]])       # gap 10 < 2 eps: a permitted perturbation swaps the leaders
+    y = np.array([2, 1, 0, 0, 0], np.int32)
+    assert oracle.undecidable_loss_rows(O, y, 2e-2).tolist() == [False, False, True, False, True]
+    assert not oracle.undecidable_loss_rows(O, y, 0.0).any()
+    # the bound it is built on holds for every permitted perturbation: rows declared decidable move by less
+    # than the band, and some undecidable row moves by far more
+    rng = np.random.default_rng(3)
+    band = 2e-2
+    O = rng.standard_normal((300, 6)) * rng.choice([0.1, 1.0, 30.0, 300.0], (300, 1))
+    y = rng.integers(0, 6, 300).astype(np.int32)
+    und = oracle.undecidable_loss_rows(O, y, band)
+    assert und.any() and not und.all()
+    _, g0 = oracle.softmax_xent(O, y)
+    eps = band * np.abs(O).max(axis=1, keepdims=True)
+    worst = np.zeros(300)
+    for _ in range(30):
+        _, g1 = oracle.softmax_xent(O + eps * rng.choice([-1.0, 1.0], O.shape), y)
+        worst = np.maximum(worst, np.abs(g1 - g0).max(axis=1) / np.abs(g0).max())
+    assert worst[~und].max() <= band and worst[und].max() > 5 * band
+
+
+def test_loss_gradient_ties_enter_only_inside_the_band():
+    # like relu_ties: rows handed in replace the oracle's own loss-gradient rows inside the undecidable set and
+    # nowhere else; forward values, loss and the returned dO stay the oracle's own
+    rng = np.random.default_rng(1)
+    rp, ci, v, X, y, Ws = _small_stack(rng, scale=0.3)      # logits up to about 10: two of the ten rows fall in the band
+    base = oracle.layers_step(rp, ci, v, X, y, Ws, logit_band=2e-2)
     loss, dO = oracle.softmax_xent(base["H"][-1], y)
     assert np.array_equal(base["dO"], dO) and base["loss"] == loss
-    same = oracle.layers_step(rp, ci, v, X, y, Ws, dO=dO)
-    twice = oracle.layers_step(rp, ci, v, X, y, Ws, dO=2.0 * dO)
+    bandrows = base["dO_band"]
+    assert np.array_equal(bandrows, oracle.undecidable_loss_rows(base["H"][-1], y, 2e-2))
+    assert bandrows.any() and not bandrows.all()
+    ties = rng.standard_normal(dO.shape)           # arbitrary rows: only those inside the band may show
+    out = oracle.layers_step(rp, ci, v, X, y, Ws, logit_band=2e-2, dO_ties=ties)
+    patched = dO.copy(); patched[bandrows] = ties[bandrows]
+    # the weight gradient of the last layer is T^T dO with the patched start
+    assert np.allclose(out["dW"][1], base["T"][1].T @ patched, rtol=1e-12, atol=1e-12)
+    assert np.allclose(out["db"][1], patched.sum(axis=0), rtol=1e-12, atol=1e-15)
+    assert out["loss"] == base["loss"] and np.array_equal(out["dO"], dO)
+    assert all(np.array_equal(a, b) for a, b in zip(out["H"], base["H"]))
+    # without a band nothing handed in is used
+    same = oracle.layers_step(rp, ci, v, X, y, Ws, dO_ties=ties)
     for l in range(2):
-        assert np.array_equal(same["dW"][l], base["dW"][l]) and np.array_equal(same["db"][l], base["db"][l])
-        assert np.allclose(twice["dW"][l], 2.0 * base["dW"][l], rtol=1e-13, atol=0)
-    assert twice["loss"] == base["loss"] and np.array_equal(twice["dO"], dO)
+        assert np.array_equal(same["dW"][l], oracle.layers_step(rp, ci, v, X, y, Ws)["dW"][l])
+
+
+def test_stored_bf16_activations_round_once_after_the_activation():
+    rng = np.random.default_rng(5)
+    rp, ci, v, X, y, Ws = _small_stack(rng)
+    full = oracle.layers_step(rp, ci, v, X, y, Ws, bf16=True)
+    st = oracle.layers_step(rp, ci, v, X, y, Ws, bf16=True, store_bf16=True)
+    # the first layer sees the same input: its stored output is the rounded one, the mask is untouched
+    assert np.array_equal(st["H"][1], oracle.round_bf16(full["H"][1])) and not np.array_equal(st["H"][1], full["H"][1])
+    assert np.array_equal(st["relu_mask"][0], full["relu_mask"][0])
+    assert np.array_equal(st["H"][1], np.asarray(torch.tensor(full["H"][1]).to(torch.bfloat16).double()))
+    # the logits are computed from the stored activations and are not rounded themselves
+    T2, Z2 = oracle.gcn_fwd(rp, ci, v, st["H"][1], Ws[1][0], Ws[1][1], relu=False, bf16=True)
+    assert np.array_equal(st["H"][2], Z2) and np.array_equal(st["T"][1], T2)
