@@ -212,7 +212,8 @@ def measure(args, sg, si, torch, cfg, g, X, labels, weights, use_graph_req: str,
             m_, n_, k_ = (float(x) for x in p[2].split("x"))
             ea = next((float(w[2:]) for w in p if w.startswith("a=")), 4.0)
             ec = next((float(w[2:]) for w in p if w.startswith("c=")), 4.0)
-            gq["bytes"] += calls * (ea * m_ * k_ + ec * m_ * n_ + 4.0 * k_ * n_)
+            em = next((float(w[2:]) for w in p if w.startswith("m=")), 4.0) if "mask" in p else 0.0   # a mask read along with C
+            gq["bytes"] += calls * (ea * m_ * k_ + (ec + em) * m_ * n_ + 4.0 * k_ * n_)
         elif name == "spmm_main_kernel":
             d = int(tag.split("d=")[1].split()[0])
             w = tag.split()

@@ -220,8 +220,10 @@ int sgnn_csr_transpose(sgnn_ctx *ctx, const sgnn_csr *A, sgnn_csr *out, sgnn_str
  */
 typedef struct {
     void *ptr;
-    int dtype; /* SGNN_F32; SGNN_BF16 (bfloat16 storage, ld in elements) only where a call says so: the input
-                * operand of a sparse product, i.e. X of sgnn_spmm and H of an aggregate-first sgnn_gcn_fwd */
+    int dtype; /* SGNN_F32; SGNN_BF16 (bfloat16 storage, round to nearest even, ld in elements) only where a call
+                * says so: the operand and the result of a sparse product (X and out of sgnn_spmm) and, with
+                * SGNN_BF16_MFMA, the activations of a layer (H, T, Y of sgnn_gcn_fwd; T, Y, H_in of sgnn_gcn_bwd).
+                * Gradients, weights and the logits handed to the loss are always fp32. */
     int64_t rows, cols, ld;
     const int32_t *row_index;
 } sgnn_mat;
@@ -238,13 +240,19 @@ int sgnn_gather_rows(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, cons
 /*
  * One GCN layer forward (Eqs. 5-6, 8): T = A H, Y = act(T W + bias).
  *   A     B x B mini-batch CSR (entries beyond A->capacity are never read)
- *   H     B x d_in fp32; H->row_index is honoured (fuses the slice of Eq. 26 into layer 1: pass
- *         the full feature matrix with row_index = S)
+ *   H     B x d_in fp32 or bfloat16; H->row_index is honoured (fuses the slice of Eq. 26 into layer 1:
+ *         pass the full feature matrix with row_index = S)
  *   W     d_in x d_out fp32;  bias fp32[d_out] or NULL
  *   flags SGNN_RELU, SGNN_BF16_MFMA
- *   Y     out B x d_out fp32
- *   T     out B x d_in fp32, the aggregate, kept by the caller for the backward pass; unused (may be
- *         NULL) with SGNN_XFORM_FIRST, where the backward pass needs the layer input H instead
+ *   Y     out B x d_out fp32 or bfloat16
+ *   T     out B x d_in fp32 or bfloat16, the aggregate, kept by the caller for the backward pass; unused
+ *         (may be NULL) with SGNN_XFORM_FIRST, where the backward pass needs the layer input H instead
+ * bfloat16 storage of T, of Y, or of the input of a transform-first layer needs SGNN_BF16_MFMA (else
+ * SGNN_ERR_UNSUPPORTED): the dense product rounds its operands to bfloat16 anyway, so a bfloat16 T holds
+ * exactly what the product would have read, and only Y - rounded once, after the activation - carries a
+ * new rounding.  A transform-first layer whose input is bfloat16 keeps its intermediate product H W in
+ * bfloat16 as well.  The tall-operand kernel (B >= 4096, widths up to 256) reads and writes the 16-bit
+ * storage itself; other shapes go through fp32 copies in the context scratch.
  */
 int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn_mat *W,
                  const float *bias, int flags, sgnn_mat *Y, sgnn_mat *T, sgnn_stream stream);
@@ -253,13 +261,13 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
  * One GCN layer backward (Sec. III-C): dZ = dY where Y > 0 (all of dY without SGNN_RELU or with SGNN_DY_MASKED),
  * dbias = column sums of dZ, dW = T^T dZ, dT = dZ W^T, dH = A_T dT.
  *   A_T   the transpose of the forward matrix as CSR (the same object when it is symmetric)
- *   T, W, Y   as in the forward call;  dY  B x d_out fp32
+ *   T, W, Y   as in the forward call (T and Y in the storage they were written in);  dY  B x d_out fp32
  *             with SGNN_XFORM_FIRST (same flag as in the forward call) T is the layer INPUT H
  *             (B x d_in, row_index honoured) and the products are dP = A_T dZ, dW = H^T dP,
  *             dH = dP W^T
  *   dH    out B x d_in fp32, or NULL to skip it (first layer)
- *   H_in  optional (NULL = none; needs dH): the layer's input activations, B x d_in fp32, the output
- *         of the ReLU of the layer below.  dH is then returned already multiplied by [H_in > 0],
+ *   H_in  optional (NULL = none; needs dH): the layer's input activations, B x d_in fp32 or bfloat16, the
+ *         output of the ReLU of the layer below.  dH is then returned already multiplied by [H_in > 0],
  *         i.e. with that layer's ReLU backward fused into the product that writes dH; call that
  *         layer's backward with SGNN_DY_MASKED so that it skips its own masking pass.
  *   dW    out fp32[d_in x d_out] row-major, overwritten, or NULL to skip it (a caller that computes
@@ -373,18 +381,20 @@ int sgnn_adam_step(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v, 
 /* Plain operators, exported for tests and for callers that build their own layer. */
 
 /*
- * out = A X (+ add): A rows x cols CSR, X cols x d fp32 (X->row_index honoured), out rows x d fp32;
+ * out = A X (+ add): A rows x cols CSR, X cols x d fp32 or bfloat16 (X->row_index honoured), out rows x d fp32
+ * or bfloat16 (accumulated in fp32, rounded to nearest even when stored);
  * add: optional rows x d fp32 matrix added to the product (NULL = none; must not be `out`) - the skip path of a residual layer merged into the transposed product of Sec. III-C.
  */
 int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_mat *add, sgnn_mat *out,
               sgnn_stream stream);
 
 /*
- * C = act(op(A) op(B) + bias): fp32 row-major, M x N result, reduction length K.
+ * C = act(op(A) op(B) + bias): row-major, M x N result, reduction length K.  B and bias are fp32; A, C and the
+ * mask are fp32 (SGNN_F32) or - with SGNN_BF16_MFMA - stored as bfloat16 (SGNN_BF16, leading dimension in elements).
  *   trans_a 0: A is M x K;  1: A is K x M (used as its transpose)
  *   trans_b 0: B is K x N;  1: B is N x K (used as its transpose)
  *   flags   SGNN_RELU, SGNN_BF16_MFMA;  bias fp32[N] or NULL
- *   mask    optional M x N fp32 matrix (leading dimension ldm), read only: C is set to zero wherever
+ *   mask    optional M x N matrix (leading dimension ldm), read only: C is set to zero wherever
  *           mask <= 0 - the ReLU backward of the layer below (Sec. III-C) applied to an input
  *           gradient as it is written, with that layer's output as the mask.  NULL = none.
  *   b_colsum  optional, with trans_a = 1 and trans_b = 0 only: out fp32[N], the column sums of B over its
@@ -392,9 +402,9 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_ma
  *             the operand the product reads anyway.  NULL = not wanted.
  */
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
-              const float *A, int64_t lda, const float *B, int64_t ldb, const float *bias,
-              int flags, float *C, int64_t ldc, const float *mask, int64_t ldm, float *b_colsum,
-              sgnn_stream stream);
+              const void *A, int a_dtype, int64_t lda, const float *B, int64_t ldb, const float *bias,
+              int flags, void *C, int c_dtype, int64_t ldc, const void *mask, int mask_dtype, int64_t ldm,
+              float *b_colsum, sgnn_stream stream);
 
 /*
  * dst[0..n) = src[0..n) (fp32, 16-byte aligned, n a multiple of 4): a plain streaming copy of known

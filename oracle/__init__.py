@@ -336,7 +336,7 @@ def num_threads() -> int:
 
 
 def gcn_step(N, rowptr, colidx, X, labels, weights, B, seed, step, bf16=False, norm_mode=0, rescale=1,
-             relu_ties=None, tie_band=0.0, store_bf16=False, dO_ties=None, logit_band=0.0):
+             relu_ties=None, tie_band=0.0, store_bf16=False, dO_ties=None, logit_band=0.0, grad_band=None):
     """One whole mini-batch step (Algorithm 1 without the parameter update): sample, induce,
     slice, L layers forward (ReLU on all but the last), mean cross-entropy, L layers backward.
     `weights` is a list of (W, b).  Returns a dict of every intermediate, float64.
@@ -351,25 +351,27 @@ def gcn_step(N, rowptr, colidx, X, labels, weights, B, seed, step, bf16=False, n
     H = gather_rows(X, S)
     yS = gather_labels(labels, S)
     out = layers_step(rpS, ciS, vS, H, yS, weights, bf16=bf16, relu_ties=relu_ties, tie_band=tie_band,
-                      store_bf16=store_bf16, dO_ties=dO_ties, logit_band=logit_band)
+                      store_bf16=store_bf16, dO_ties=dO_ties, logit_band=logit_band, grad_band=grad_band)
     out["S"] = S
     return out
 
 
-def undecidable_loss_rows(O, labels, logit_band):
+def undecidable_loss_rows(O, labels, logit_band, grad_band=None):
     """Rows of the logits O whose cross-entropy gradient row is not decidable at a relative logit
-    accuracy of logit_band.
+    accuracy of logit_band, to within grad_band (default: the same figure).
 
     With every logit of row i known to within eps_i = logit_band * max_j |O_ij|, a probability
     p_j = softmax(O_i)_j lies between p_j e^(-2 eps_i) and p_j e^(2 eps_i), and so does 1 - p_j with
     respect to itself; entry j of the gradient row (softmax(O_i) - onehot(y_i)) / B can therefore move
     by at most min(p_j, 1 - p_j) (e^(2 eps_i) - 1) / B.  The row is undecidable when that bound, taken
-    over its entries, exceeds logit_band times the largest gradient entry of the whole batch (the
+    over its entries, exceeds grad_band times the largest gradient entry of the whole batch (the
     scale the weight gradients are measured on): large logits whose leading probabilities are not
     saturated.  Rows with small logits, and rows with one dominant class, are decidable."""
     O = np.asarray(O, np.float64)
     if logit_band <= 0.0:
         return np.zeros(O.shape[0], bool)
+    if grad_band is None:
+        grad_band = logit_band
     m = O.max(axis=1, keepdims=True)
     e = np.exp(O - m)
     p = e / e.sum(axis=1, keepdims=True)
@@ -381,11 +383,11 @@ def undecidable_loss_rows(O, labels, logit_band):
     with np.errstate(over="ignore"):
         grow = np.expm1(2.0 * eps)
     bound = np.where(q > 0.0, q * np.where(np.isfinite(grow), grow, np.finfo(np.float64).max / 2), 0.0)
-    return bound > logit_band * g
+    return bound > grad_band * g
 
 
 def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie_band=0.0, store_bf16=False,
-                dO_ties=None, logit_band=0.0):
+                dO_ties=None, logit_band=0.0, grad_band=None):
     """The layer part of a step on an already extracted mini-batch: L layers forward, mean
     cross-entropy, L layers backward (see gcn_step for relu_ties / tie_band).
 
@@ -419,7 +421,7 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
         Ts.append(T); Hs.append(Y); masks.append(mask); bands.append(band)
     loss, dY = softmax_xent(Hs[-1], yS)
     dO_own = dY
-    dO_band = undecidable_loss_rows(Hs[-1], yS, logit_band)
+    dO_band = undecidable_loss_rows(Hs[-1], yS, logit_band, grad_band)
     if dO_ties is not None and dO_band.any():
         dY = dY.copy()
         dY[dO_band] = np.asarray(dO_ties, np.float64)[dO_band]

@@ -102,7 +102,7 @@ def lib():
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
-        L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, i64, vp, i64, vp, vp]
+        L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, ci, i64, vp, i64, vp, ci, vp, ci, i64, vp, ci, i64, vp, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
                      "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_gemm_tail_fwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose", "sgnn_sigmoid_bce", "sgnn_colsum",
@@ -346,8 +346,8 @@ def sgnn_gather_rows(ctx: Context, X: Optional[torch.Tensor], S: torch.Tensor, B
 def sgnn_gcn_fwd(ctx: Context, A: Csr, H: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], flags: int,
                  Y: torch.Tensor, T: Optional[torch.Tensor], row_index: Optional[torch.Tensor] = None, stream=None):
     a = A.struct()
-    h, w, y = _mat(H, row_index, "H", allow_bf16=True), _mat(W, None, "W"), _mat(Y, None, "Y")
-    t = _mat(T, None, "T") if T is not None else None
+    h, w, y = _mat(H, row_index, "H", allow_bf16=True), _mat(W, None, "W"), _mat(Y, None, "Y", allow_bf16=True)
+    t = _mat(T, None, "T", allow_bf16=True) if T is not None else None
     ctx.check(lib().sgnn_gcn_fwd(ctx._h, C.byref(a), C.byref(h), C.byref(w), _ptr(bias, torch.float32, "bias"), flags,
                                  C.byref(y), C.byref(t) if t is not None else None, _stream(stream)))
 
@@ -358,10 +358,10 @@ def sgnn_gcn_bwd(ctx: Context, A_T: Csr, T: torch.Tensor, W: torch.Tensor, Y: Op
     """T is the saved aggregate, or with SGNN_XFORM_FIRST the layer input (row_index honoured).
     H_in (the layer input, output of the ReLU below): dH comes back multiplied by [H_in > 0]."""
     a = A_T.struct()
-    t, w, dy = _mat(T, row_index, "T"), _mat(W, None, "W"), _mat(dY, None, "dY")
-    y = _mat(Y, None, "Y") if Y is not None else None
+    t, w, dy = _mat(T, row_index, "T", allow_bf16=True), _mat(W, None, "W"), _mat(dY, None, "dY")
+    y = _mat(Y, None, "Y", allow_bf16=True) if Y is not None else None
     dh = _mat(dH, None, "dH") if dH is not None else None
-    hin = _mat(H_in, None, "H_in") if H_in is not None else None
+    hin = _mat(H_in, None, "H_in", allow_bf16=True) if H_in is not None else None
     if dW is not None and (dW.shape != W.shape or not dW.is_contiguous()):
         raise ValueError("dW must be contiguous with the shape of W")
     ctx.check(lib().sgnn_gcn_bwd(ctx._h, C.byref(a), C.byref(t), C.byref(w), C.byref(y) if y is not None else None,
@@ -429,7 +429,7 @@ def sgnn_spmm(ctx: Context, A: Csr, X: torch.Tensor, out: torch.Tensor, row_inde
               stream=None, add: Optional[torch.Tensor] = None):
     """out = A X (+ add)."""
     a = A.struct()
-    x, o = _mat(X, row_index, "X", allow_bf16=True), _mat(out, None, "out")
+    x, o = _mat(X, row_index, "X", allow_bf16=True), _mat(out, None, "out", allow_bf16=True)
     ad = _mat(add, None, "add") if add is not None else None
     ctx.check(lib().sgnn_spmm(ctx._h, C.byref(a), C.byref(x), C.byref(ad) if ad is not None else None, C.byref(o),
                               _stream(stream)))
@@ -460,17 +460,26 @@ def sgnn_adam_step(ctx: Context, w: torch.Tensor, g: torch.Tensor, m: torch.Tens
                                    beta2, eps, t, _stream(stream)))
 
 
+def _dt(t: Optional[torch.Tensor], name: str) -> int:
+    if t is None or t.dtype == torch.float32:
+        return SGNN_F32
+    if t.dtype == torch.bfloat16:
+        return SGNN_BF16
+    raise TypeError("%s must be float32 or bfloat16, got %s" % (name, t.dtype))
+
+
 def sgnn_gemm(ctx: Context, trans_a: bool, trans_b: bool, A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor],
               flags: int, Cm: torch.Tensor, stream=None, b_colsum: Optional[torch.Tensor] = None,
               mask: Optional[torch.Tensor] = None):
-    """C = act(op(A) op(B) + bias), zero where mask <= 0 (mask: a matrix shaped like C); b_colsum: column sums of B."""
+    """C = act(op(A) op(B) + bias), zero where mask <= 0 (mask: a matrix shaped like C); b_colsum: column sums of B.
+    A, C and the mask may be bfloat16 tensors (with SGNN_BF16_MFMA)."""
     M, N = Cm.shape
     if mask is not None and tuple(mask.shape) != (M, N):
         raise ValueError("mask must have the shape of C")
     K = A.shape[0] if trans_a else A.shape[1]
-    ctx.check(lib().sgnn_gemm(ctx._h, int(trans_a), int(trans_b), M, N, K, _ptr(A, torch.float32, "A"), A.stride(0),
+    ctx.check(lib().sgnn_gemm(ctx._h, int(trans_a), int(trans_b), M, N, K, _ptr(A, None, "A"), _dt(A, "A"), A.stride(0),
                               _ptr(B, torch.float32, "B"), B.stride(0), _ptr(bias, torch.float32, "bias"), flags,
-                              _ptr(Cm, torch.float32, "C"), Cm.stride(0), _ptr(mask, torch.float32, "mask"),
+                              _ptr(Cm, None, "C"), _dt(Cm, "C"), Cm.stride(0), _ptr(mask, None, "mask"), _dt(mask, "mask"),
                               mask.stride(0) if mask is not None else 0, _ptr(b_colsum, torch.float32, "b_colsum"),
                               _stream(stream)))
 

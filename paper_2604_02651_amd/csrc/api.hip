@@ -131,7 +131,10 @@ int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t
     size_t need = sgnn_sampler_ws_bytes(N);
     need = std::max(need, sgnn_induced_ws_bytes(E, B));
     // backward: dZ and dT (B x d_max each), split-K partials, column-sum partials
-    size_t layer = (size_t)2 * B * pad4(d_max) * 4 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 +
+    // Products whose kernel does not handle bfloat16 storage itself (fewer than 4096 rows, or wider than 256) go through
+    // widened / narrowed fp32 copies: three more B x d_max matrices for those shapes.
+    const size_t copies = (B < 4096 || d_max > 256) ? 5 : 2;
+    size_t layer = copies * B * pad4(d_max) * 4 + 5 * 256 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 +
                    sgnn_spmm_ws_bytes(max_entries, B, d_max) + 16 * 256;
     need = std::max(need, layer);
     need = std::max(need, sgnn_transpose_ws_bytes(max_entries, B));
@@ -327,33 +330,39 @@ int sgnn_gather_rows(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, cons
 int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_mat *add, sgnn_mat *out, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
-    if (!csr_ok(A) || !mat_ok_in(X) || !mat_ok(out)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: bad argument");
+    if (!csr_ok(A) || !mat_ok_in(X) || !mat_ok_in(out)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: bad argument");
     if (out->rows != A->rows || out->cols != X->cols || (!X->row_index && X->rows != A->cols) ||
         (add && (!mat_ok(add) || add->row_index || add->rows != out->rows || add->cols != out->cols)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm: shape mismatch");
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_spmm(ctx, A, X->ptr, X->dtype == SGNN_BF16, X->ld, X->row_index, X->cols,
-                            static_cast<float *>(out->ptr), out->ld, nullptr, 0, nullptr, 0,
-                            add ? static_cast<const float *>(add->ptr) : nullptr, add ? add->ld : 0, &ws,
-                            static_cast<hipStream_t>(stream));
+    return sgnn_launch_spmm_x(ctx, A, X->ptr, X->dtype == SGNN_BF16, X->ld, X->row_index, X->cols, out->ptr,
+                              out->dtype == SGNN_BF16, out->ld, nullptr, 0, nullptr, 0, 0,
+                              add ? static_cast<const float *>(add->ptr) : nullptr, add ? add->ld : 0, &ws,
+                              static_cast<hipStream_t>(stream));
 }
 
-int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
-              const float *B, int64_t ldb, const float *bias, int flags, float *C, int64_t ldc, const float *mask,
-              int64_t ldm, float *b_colsum, sgnn_stream stream)
+int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int a_dtype, int64_t lda,
+              const float *B, int64_t ldb, const float *bias, int flags, void *C, int c_dtype, int64_t ldc, const void *mask,
+              int mask_dtype, int64_t ldm, float *b_colsum, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     if (!A || !B || !C || M < 0 || N < 0 || K < 0) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: bad argument");
+    if ((a_dtype != SGNN_F32 && a_dtype != SGNN_BF16) || (c_dtype != SGNN_F32 && c_dtype != SGNN_BF16) ||
+        (mask && mask_dtype != SGNN_F32 && mask_dtype != SGNN_BF16))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: unknown storage type");
+    if ((a_dtype == SGNN_BF16 || c_dtype == SGNN_BF16) && !(flags & SGNN_BF16_MFMA))
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gemm: bfloat16 storage of A or C goes with SGNN_BF16_MFMA only");
     if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N || (mask && ldm < N))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: leading dimension too small");
     if (M == 0 || N == 0) return SGNN_OK;
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_gemm(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, nullptr, B, ldb, bias, flags, C, ldc, mask, mask ? ldm : 0, b_colsum, &ws,
-                            static_cast<hipStream_t>(stream));
+    return sgnn_launch_gemm_x(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, a_dtype == SGNN_BF16, lda, nullptr, B, ldb, bias, flags,
+                              C, c_dtype == SGNN_BF16, ldc, mask, mask && mask_dtype == SGNN_BF16, mask ? ldm : 0, b_colsum, &ws,
+                              static_cast<hipStream_t>(stream));
 }
 
 int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn_mat *W, const float *bias, int flags,
@@ -361,11 +370,12 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     const bool xform_first = (flags & SGNN_XFORM_FIRST) != 0;
-    if (!csr_ok(A) || !mat_ok_in(H) || !mat_ok(W) || !mat_ok(Y) || (!xform_first && !mat_ok(T)))
+    if (!csr_ok(A) || !mat_ok_in(H) || !mat_ok(W) || !mat_ok_in(Y) || (!xform_first && !mat_ok_in(T)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_fwd: bad argument");
-    if (xform_first && H->dtype != SGNN_F32)
-        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gcn_fwd: a transform-first layer reads its input in the dense product, "
-                                                    "which takes fp32 storage only");
+    const bool h16 = H->dtype == SGNN_BF16, y16 = Y->dtype == SGNN_BF16, t16 = !xform_first && T->dtype == SGNN_BF16;
+    if ((y16 || t16 || (xform_first && h16)) && !(flags & SGNN_BF16_MFMA))
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gcn_fwd: bfloat16 storage of T, Y or of the input of a transform-first "
+                                                    "layer goes with SGNN_BF16_MFMA only (the dense product rounds to it anyway)");
     const int64_t Bn = A->rows, d_in = W->rows, d_out = W->cols;
     if (H->cols != d_in || Y->rows != Bn || Y->cols != d_out || (!H->row_index && H->rows != A->cols) ||
         (H->row_index && H->rows != A->cols) || W->row_index || Y->row_index ||
@@ -378,23 +388,25 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
     const int gflags = flags & (SGNN_RELU | SGNN_BF16_MFMA);
     if (!xform_first) {
         // Eqs. 5-6 in the paper's order: aggregate, then transform with bias and activation fused
-        rc = sgnn_launch_spmm(ctx, A, H->ptr, H->dtype == SGNN_BF16, H->ld, H->row_index, d_in,
-                              static_cast<float *>(T->ptr), T->ld, nullptr, 0, nullptr, 0, nullptr, 0, &ws, st);
+        rc = sgnn_launch_spmm_x(ctx, A, H->ptr, h16, H->ld, H->row_index, d_in, T->ptr, t16, T->ld, nullptr, 0, nullptr, 0, 0, nullptr,
+                                0, &ws, st);
         if (rc) return rc;
-        return sgnn_launch_gemm(ctx, 0, 0, Bn, d_out, d_in, static_cast<const float *>(T->ptr), T->ld, nullptr,
-                                static_cast<const float *>(W->ptr), W->ld, bias, gflags, static_cast<float *>(Y->ptr), Y->ld,
-                                nullptr, 0, nullptr, &ws, st);
+        return sgnn_launch_gemm_x(ctx, 0, 0, Bn, d_out, d_in, T->ptr, t16, T->ld, nullptr, static_cast<const float *>(W->ptr), W->ld,
+                                  bias, gflags, Y->ptr, y16, Y->ld, nullptr, 0, 0, nullptr, &ws, st);
     }
     // A (H W): transform first (the aggregation then runs at width d_out), bias and activation
     // fused into the sparse product
-    const int64_t ldp = pad4(d_out);   // rows of the scratch matrices start 16-byte aligned
-    float *P = ws.get<float>((size_t)A->cols * ldp);
+    // The product H W lives in scratch; with the layer's input stored as bfloat16 it is stored as bfloat16 too (the
+    // activations of such a stack are 16-bit between all of its kernels).
+    const int64_t ldp = pad4(d_out);   // rows of the scratch matrices start 16-byte aligned (8-byte for 16-bit elements)
+    const bool p16 = h16;
+    float *P = ws.get<float>(p16 ? ((size_t)A->cols * ldp + 1) / 2 : (size_t)A->cols * ldp);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_fwd: scratch too small: call sgnn_ctx_reserve");
-    rc = sgnn_launch_gemm(ctx, 0, 0, A->cols, d_out, d_in, static_cast<const float *>(H->ptr), H->ld, H->row_index,
-                          static_cast<const float *>(W->ptr), W->ld, nullptr, flags & SGNN_BF16_MFMA, P, ldp, nullptr, 0, nullptr, &ws, st);
+    rc = sgnn_launch_gemm_x(ctx, 0, 0, A->cols, d_out, d_in, H->ptr, h16, H->ld, H->row_index, static_cast<const float *>(W->ptr), W->ld,
+                            nullptr, flags & SGNN_BF16_MFMA, P, p16, ldp, nullptr, 0, 0, nullptr, &ws, st);
     if (rc) return rc;
-    return sgnn_launch_spmm(ctx, A, P, 0, ldp, nullptr, d_out, static_cast<float *>(Y->ptr), Y->ld, bias,
-                            (flags & SGNN_RELU) ? 1 : 0, nullptr, 0, nullptr, 0, &ws, st);
+    return sgnn_launch_spmm_x(ctx, A, P, p16, ldp, nullptr, d_out, Y->ptr, y16, Y->ld, bias, (flags & SGNN_RELU) ? 1 : 0, nullptr, 0, 0,
+                              nullptr, 0, &ws, st);
 }
 
 int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sgnn_mat *W, const sgnn_mat *Y,
@@ -402,13 +414,16 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
                  sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
-    if (!csr_ok(A_T) || !mat_ok(T) || !mat_ok(W) || !mat_ok(dY) || (dH && !mat_ok(dH)))
+    if (!csr_ok(A_T) || !mat_ok_in(T) || !mat_ok(W) || !mat_ok(dY) || (dH && !mat_ok(dH)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: bad argument");
+    const bool t16 = T->dtype == SGNN_BF16;
+    if (t16 && !(flags & SGNN_BF16_MFMA))
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gcn_bwd: a saved matrix stored as bfloat16 goes with SGNN_BF16_MFMA only");
     const int relu = (flags & SGNN_RELU) ? 1 : 0;
     const bool xform_first = (flags & SGNN_XFORM_FIRST) != 0;
     const bool dy_masked = (flags & SGNN_DY_MASKED) != 0;   // the caller's dY already carries this layer's ReLU mask
-    if (relu && !dy_masked && !mat_ok(Y)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: SGNN_RELU needs Y");
-    if (H_in && (!dH || !mat_ok(H_in) || H_in->row_index))
+    if (relu && !dy_masked && !mat_ok_in(Y)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: SGNN_RELU needs Y");
+    if (H_in && (!dH || !mat_ok_in(H_in) || H_in->row_index))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: H_in needs dH and must be a plain matrix");
     const int64_t Bn = T->rows, d_in = W->rows, d_out = W->cols;
     if (T->cols != d_in || dY->rows != Bn || dY->cols != d_out ||
@@ -428,8 +443,9 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     const float *dZ = static_cast<const float *>(dY->ptr);
     int64_t lddz = dY->ld;
     const int mask_here = relu && !dy_masked;
-    const float *hmask = H_in ? static_cast<const float *>(H_in->ptr) : nullptr;
+    const void *hmask = H_in ? H_in->ptr : nullptr;
     const int64_t ldhm = H_in ? H_in->ld : 0;
+    const int hm16 = (H_in && H_in->dtype == SGNN_BF16) ? 1 : 0;
     // the bias gradient rides on the weight-gradient product when both read the same dZ = dY
     const bool db_in_gemm = dbias && dW && !mask_here && !xform_first;
     if (mask_here || (dbias && !db_in_gemm)) {
@@ -438,17 +454,17 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
             dZbuf = ws.get<float>((size_t)Bn * ld_out);
             if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
         }
-        rc = sgnn_launch_relu_bwd_bias(ctx, mask_here ? static_cast<const float *>(Y->ptr) : nullptr, mask_here ? Y->ld : 0,
-                                       static_cast<const float *>(dY->ptr), dY->ld, mask_here, Bn, d_out, dZbuf, ld_out,
-                                       dbias, &ws, st);
+        rc = sgnn_launch_relu_bwd_bias(ctx, mask_here ? Y->ptr : nullptr, (mask_here && Y->dtype == SGNN_BF16) ? 1 : 0,
+                                       mask_here ? Y->ld : 0, static_cast<const float *>(dY->ptr), dY->ld, mask_here, Bn, d_out, dZbuf,
+                                       ld_out, dbias, &ws, st);
         if (rc) return rc;
         if (mask_here) { dZ = dZbuf; lddz = ld_out; }
     }
     if (!xform_first) {
         // dW = T^T dZ
         if (dW) {
-            rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, nullptr, dZ, lddz,
-                                  nullptr, mfma, dW, d_out, nullptr, 0, db_in_gemm ? dbias : nullptr, &ws, st);
+            rc = sgnn_launch_gemm_x(ctx, 1, 0, d_in, d_out, Bn, T->ptr, t16, T->ld, nullptr, dZ, lddz, nullptr, mfma, dW, 0, d_out, nullptr,
+                                    0, 0, db_in_gemm ? dbias : nullptr, &ws, st);
             if (rc) return rc;
         }
         if (dH) {
@@ -458,8 +474,8 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
             rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, nullptr, static_cast<const float *>(W->ptr), W->ld,
                                   nullptr, mfma, dT, ld_in, nullptr, 0, nullptr, &ws, st);
             if (rc) return rc;
-            rc = sgnn_launch_spmm(ctx, A_T, dT, 0, ld_in, nullptr, d_in, static_cast<float *>(dH->ptr), dH->ld, nullptr, 0, hmask, ldhm, nullptr, 0, &ws,
-                                  st);
+            rc = sgnn_launch_spmm_x(ctx, A_T, dT, 0, ld_in, nullptr, d_in, dH->ptr, 0, dH->ld, nullptr, 0, hmask, hm16, ldhm, nullptr, 0,
+                                    &ws, st);
             if (rc) return rc;
         }
         return SGNN_OK;
@@ -470,13 +486,13 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     rc = sgnn_launch_spmm(ctx, A_T, dZ, 0, lddz, nullptr, d_out, dP, ld_out, nullptr, 0, nullptr, 0, nullptr, 0, &ws, st);
     if (rc) return rc;
     if (dW) {
-        rc = sgnn_launch_gemm(ctx, 1, 0, d_in, d_out, Bn, static_cast<const float *>(T->ptr), T->ld, T->row_index, dP, ld_out,
-                              nullptr, mfma, dW, d_out, nullptr, 0, nullptr, &ws, st);
+        rc = sgnn_launch_gemm_x(ctx, 1, 0, d_in, d_out, Bn, T->ptr, t16, T->ld, T->row_index, dP, ld_out, nullptr, mfma, dW, 0, d_out,
+                                nullptr, 0, 0, nullptr, &ws, st);
         if (rc) return rc;
     }
     if (dH)
-        rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dP, ld_out, nullptr, static_cast<const float *>(W->ptr), W->ld,
-                              nullptr, mfma, static_cast<float *>(dH->ptr), dH->ld, hmask, ldhm, nullptr, &ws, st);
+        rc = sgnn_launch_gemm_x(ctx, 0, 1, Bn, d_in, d_out, dP, 0, ld_out, nullptr, static_cast<const float *>(W->ptr), W->ld, nullptr,
+                                mfma, dH->ptr, 0, dH->ld, hmask, hm16, ldhm, nullptr, &ws, st);
     return rc;
 }
 
@@ -562,7 +578,7 @@ int sgnn_colsum(sgnn_ctx *ctx, const sgnn_mat *X, float *out, sgnn_stream stream
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_relu_bwd_bias(ctx, nullptr, 0, static_cast<const float *>(X->ptr), X->ld, 0, X->rows, X->cols, nullptr, 0,
+    return sgnn_launch_relu_bwd_bias(ctx, nullptr, 0, 0, static_cast<const float *>(X->ptr), X->ld, 0, X->rows, X->cols, nullptr, 0,
                                      out, &ws, static_cast<hipStream_t>(stream));
 }
 

@@ -107,6 +107,9 @@ size_t sgnn_transpose_ws_bytes(uint64_t max_entries, uint32_t B);
 int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const void *X, int x_bf16, int64_t ldx, const int32_t *row_index,
                      int64_t d, float *out, int64_t ldo, const float *bias, int relu, const float *mask, int64_t ldm,
                      const float *add, int64_t ldadd, ws_alloc *ws, hipStream_t st);
+int sgnn_launch_spmm_x(sgnn_ctx *ctx, const sgnn_csr *A, const void *X, int x_bf16, int64_t ldx, const int32_t *row_index, int64_t d,
+                       void *out, int out_bf16, int64_t ldo, const float *bias, int relu, const void *mask, int mask_bf16,
+                       int64_t ldm, const float *add, int64_t ldadd, ws_alloc *ws, hipStream_t st);
 int sgnn_launch_spmm_plan(sgnn_ctx *ctx, const sgnn_csr *A, hipStream_t st);   // fills A->plan when it is attached
 // a_row_index (may be NULL): physical row of A for every logical row (M x K operand: rows of the
 // result; K x M operand used transposed: reduction index)
@@ -114,11 +117,16 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
                      int64_t lda, const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias,
                      int flags, float *C, int64_t ldc, const float *mask, int64_t ldm, float *b_colsum, ws_alloc *ws,
                      hipStream_t st);
+// The same with A, C and the mask optionally stored as bfloat16 (a_bf16 / c_bf16 / m_bf16; leading dimensions in
+// elements; needs SGNN_BF16_MFMA): read and written as stored by the kernels that can, converted through scratch for the others.
+int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const void *A, int a_bf16, int64_t lda,
+                       const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias, int flags, void *C, int c_bf16,
+                       int64_t ldc, const void *mask, int m_bf16, int64_t ldm, float *b_colsum, ws_alloc *ws, hipStream_t st);
 int sgnn_launch_gemm_tail(sgnn_ctx *ctx, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *W,
                           int64_t ldw, const float *gamma, float eps, const float *R, int64_t ldr, float q, uint64_t seed,
                           uint32_t layer, uint64_t step, float *Z, int64_t ldz, float *Y, int64_t ldy, float *inv_rms,
                           hipStream_t st);
-int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const float *dY, int64_t lddy,
+int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const void *Y, int y_bf16, int64_t ldy, const float *dY, int64_t lddy,
                               int relu, int64_t rows, int64_t cols, float *dZ, int64_t lddz, float *dbias,
                               ws_alloc *ws, hipStream_t st);
 int sgnn_launch_gather(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, const int32_t *S, uint32_t B,

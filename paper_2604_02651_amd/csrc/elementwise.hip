@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const float *__restric
 // A thread owns VEC consecutive columns; tx < cwp walks the column chunks, ty the rows of the
 // workgroup's slab, four rows in flight.
 template <int VEC>
-__global__ __launch_bounds__(256) void relu_bwd_colsum_kernel(const float *__restrict__ Y, int64_t ldy,
+__global__ __launch_bounds__(256) void relu_bwd_colsum_kernel(const float *__restrict__ Y, int y_bf16, int64_t ldy,
                                                               const float *__restrict__ dY, int64_t lddy, int relu,
                                                               int64_t rows, int cols, int64_t rows_per_wg, int cwp_log2,
                                                               float *__restrict__ dZ, int64_t lddz,
@@ -75,7 +75,11 @@ __global__ __launch_bounds__(256) void relu_bwd_colsum_kernel(const float *__res
                 float g[VEC], y[VEC];
                 vload<VEC>(g, dY + r * lddy + col);
                 if (relu) {
-                    vload<VEC>(y, Y + r * ldy + col);
+                    if (y_bf16) {      // Y stored as bfloat16: positive iff the 16-bit pattern is a positive integer
+                        const uint16_t *y16 = reinterpret_cast<const uint16_t *>(Y) + r * ldy + col;
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) y[i] = (int16_t)y16[i] > 0 ? 1.f : 0.f;
+                    } else vload<VEC>(y, Y + r * ldy + col);
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) if (!(y[i] > 0.f)) g[i] = 0.f;
                 }
@@ -125,13 +129,15 @@ __global__ __launch_bounds__(1024) void colsum_final_kernel(const float *__restr
 }
 
 // A group of lpr lanes (a power of two >= C, at most 64) owns a row and keeps it in registers
-// (NX values a lane: C <= 64 * NX); a workgroup covers 4 * 256 / lpr rows and writes one partial loss
-// and, if asked, its column sums of dO (the bias gradient of a last layer without activation):
-// cs_partial[workgroup][C], summed over its rows in a fixed order.
+// (NX values a lane: C <= 64 * NX); a block of 4 * 256 / lpr rows is one round of a workgroup, which walks the
+// blocks grid-stride (a fixed assignment, so every sum below is taken in the same order whenever it runs) and
+// writes one partial loss and, if asked, its column sums of dO (the bias gradient of a last layer without
+// activation): cs_partial[workgroup][C].  The number of workgroups is bounded by the launcher: what the final
+// kernel has to add up does not grow with the batch.
 template <int NX>
 __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, int64_t ldo,
                                                    const int32_t *__restrict__ labels, uint32_t B, uint32_t C,
-                                                   int lpr_log2, float *__restrict__ dO, int64_t lddo,
+                                                   int lpr_log2, uint32_t n_blocks, float *__restrict__ dO, int64_t lddo,
                                                    float *__restrict__ partial, float *__restrict__ cs_partial)
 {
     __shared__ float lds[4];
@@ -144,9 +150,10 @@ __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, 
     const uint32_t gq = threadIdx.x >> lpr_log2, g = threadIdx.x & (lpr - 1);
     float loss = 0.f;
     const float invB = 1.f / (float)B;
+    for (uint32_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {       // unrolled: the loads of the four passes go out together
-        const uint32_t row = (blockIdx.x * 4 + q) * rows_per_pass + gq;
+        const uint32_t row = (blk * 4 + q) * rows_per_pass + gq;
         const bool live = row < B;
         const float *o = O + (int64_t)(live ? row : 0) * ldo;
         float x[NX];
@@ -184,6 +191,7 @@ __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, 
                 }
             }
         }
+    }
     }
     loss = wave_sum(loss);
     if (lane_id() == 0) lds[threadIdx.x >> 6] = loss;
@@ -315,10 +323,11 @@ int sgnn_launch_gather(sgnn_ctx *ctx, const float *X, int64_t d, int64_t ldx, co
     return SGNN_OK;
 }
 
-int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const float *dY, int64_t lddy, int relu,
+int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const void *Yv, int y_bf16, int64_t ldy, const float *dY, int64_t lddy, int relu,
                               int64_t rows, int64_t cols, float *dZ, int64_t lddz, float *dbias, ws_alloc *ws,
                               hipStream_t st)
 {
+    const float *Y = static_cast<const float *>(Yv);
     int64_t rows_per_wg = (rows + 1023) / 1024;
     if (rows_per_wg < 64) rows_per_wg = 64;
     const unsigned nwg = cdiv(rows, rows_per_wg);
@@ -333,10 +342,10 @@ int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const 
     int cwp_log2 = 0;
     while ((1 << cwp_log2) < cw && cwp_log2 < 8) ++cwp_log2;
     if (v4)
-        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<4>, dim3(nwg), dim3(256), 0, st, Y, ldy,
+        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<4>, dim3(nwg), dim3(256), 0, st, Y, y_bf16, ldy,
                     dY, lddy, relu, rows, (int)cols, rows_per_wg, cwp_log2, dZ, lddz, partial);
     else
-        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<1>, dim3(nwg), dim3(256), 0, st, Y, ldy,
+        SGNN_LAUNCH(ctx, st, "relu_bwd_colsum_kernel", SGNN_TAG, relu_bwd_colsum_kernel<1>, dim3(nwg), dim3(256), 0, st, Y, y_bf16, ldy,
                     dY, lddy, relu, rows, (int)cols, rows_per_wg, cwp_log2, dZ, lddz, partial);
     if (dbias)
         SGNN_LAUNCH(ctx, st, "colsum_final_kernel", SGNN_TAG, colsum_final_kernel, dim3(cdiv(cols, 64)), dim3(1024), 0, st,
@@ -347,22 +356,28 @@ int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const float *Y, int64_t ldy, const 
 int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C, float *loss,
                      float *dO, int64_t lddo, float *dO_colsum, ws_alloc *ws, hipStream_t st)
 {
-    int lpr_log2 = 0;
-    while ((1u << lpr_log2) < C && lpr_log2 < 6) ++lpr_log2;
-    const unsigned rows_per_wg = 4u * (256u >> lpr_log2);
-    const unsigned nwg = cdiv(B, rows_per_wg);
+    // lanes per row: the fewest (a power of two from 4 to 64) with which a lane holds at most eight values of a row.
+    // Fewer lanes per row mean shorter reductions and more rows in flight per wavefront (172 classes: 32 lanes x 6).
+    int lpr_log2 = 6;
+    while (lpr_log2 > 2 && C <= (4u << lpr_log2)) --lpr_log2;
+    const unsigned rows_per_block = 4u * (256u >> lpr_log2);
+    const unsigned n_blocks = cdiv(B, rows_per_block);
+    const unsigned nwg = std::min(n_blocks, 4096u);     // 16 workgroups a compute unit walk the row blocks
     float *partial = ws->get<float>(nwg);
     float *cs_partial = dO_colsum ? ws->get<float>((size_t)nwg * C) : nullptr;
     if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_softmax_xent: scratch too small: call sgnn_ctx_reserve");
     const unsigned nx = (C + (1u << lpr_log2) - 1) >> lpr_log2;
-    if (nx <= 1)
-        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<1>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial, cs_partial);
-    else if (nx <= 4)
-        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<4>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial, cs_partial);
-    else if (nx <= 16)
-        SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<16>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, dO, lddo, partial, cs_partial);
-    else
-        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_softmax_xent: more than 1024 classes are not supported");
+#define SGNN_XENT(NX_)                                                                                                       \
+    SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<NX_>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, \
+                n_blocks, dO, lddo, partial, cs_partial)
+    if (nx <= 1) SGNN_XENT(1);
+    else if (nx <= 2) SGNN_XENT(2);
+    else if (nx <= 4) SGNN_XENT(4);
+    else if (nx <= 6) SGNN_XENT(6);
+    else if (nx <= 8) SGNN_XENT(8);
+    else if (nx <= 16) SGNN_XENT(16);
+    else return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_softmax_xent: more than 1024 classes are not supported");
+#undef SGNN_XENT
     if (loss || dO_colsum) {
         SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1 + (dO_colsum ? cdiv(C, 64) : 0)), dim3(1024), 0, st,
                     partial, (int)nwg, 1.f / (float)B, loss, cs_partial, (int)C, dO_colsum);

@@ -49,6 +49,10 @@ struct gemm_args {
     float *partial;           // split-K: [splits][M][N] partial products, else NULL
     uint32_t mtiles, ntiles, splits;   // the tile grid, walked by tile_of_block()
     float *colsum;            // optional (A^T B products): column sums of B; [splits][N] partial sums when split
+    int a_bf16, c_bf16, m_bf16;   // A / C / the mask are stored as bfloat16 (16-bit patterns; leading dimensions in elements).
+                                  // Only the kernels that say so look at these; the launcher converts for the others.
+    int vecM;                     // the mask can be read in chunks of four elements (aligned, N and ldm multiples of 4)
+    int c_pair;                   // a bfloat16 C can be written two columns (4 bytes) at a time
 };
 
 // Tile of a workgroup.  The grid is one-dimensional and the hardware hands consecutive workgroup
@@ -305,7 +309,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(gemm_args a)
 // Operand staged [BK][R+4]: the T tiles of the wavefront are interleaved, tile i covers rows
 // w0 + T li + i, so one 4T-byte load gives a lane its value for all T tiles.
 // ---------------------------------------------------------------------------------------------
-template <int R, int BK, bool RC>
+// SRC16: the operand is stored as bfloat16 (G points at 16-bit patterns, ld in elements): a chunk of four is
+// 8 bytes and is widened to fp32 in registers, everything behind the fetch is unchanged.
+__device__ __forceinline__ f32x4 widen_bf16x4(uint2 w)
+{
+    return f32x4{__builtin_bit_cast(float, w.x << 16), __builtin_bit_cast(float, w.x & 0xffff0000u),
+                 __builtin_bit_cast(float, w.y << 16), __builtin_bit_cast(float, w.y & 0xffff0000u)};
+}
+
+template <int R, int BK, bool RC, bool SRC16 = false>
 __device__ __forceinline__ void fetch_fast(f32x4 *reg, const float *__restrict__ G, int64_t ld, int64_t row0,
                                            int64_t rows_total, int64_t k0, int64_t k_end, int64_t k_total,
                                            const int32_t *__restrict__ ridx = nullptr)
@@ -332,7 +344,10 @@ __device__ __forceinline__ void fetch_fast(f32x4 *reg, const float *__restrict__
         (void)valid;   // the reduction tail is zeroed by mask_fast when the slice is stored to LDS,
                        // so that nothing here waits for the load
         f32x4 x = {0.f, 0.f, 0.f, 0.f};
-        if (g::TOTAL % 256 == 0 || idx < g::TOTAL) x = *reinterpret_cast<const f32x4 *>(G + gr * ld + gc);
+        if (g::TOTAL % 256 == 0 || idx < g::TOTAL) {
+            if constexpr (SRC16) x = widen_bf16x4(*reinterpret_cast<const uint2 *>(reinterpret_cast<const u16 *>(G) + gr * ld + gc));
+            else x = *reinterpret_cast<const f32x4 *>(G + gr * ld + gc);
+        }
         reg[v] = x;
     }
 }
@@ -596,7 +611,8 @@ __device__ __forceinline__ void store_tile(const gemm_args &a, const f32x16 (&ac
 // Pipeline: slice s+2 is fetched from memory into registers while slice s is multiplied from LDS
 // buffer s & 1; the registers are stored to the other buffer after the multiply, so there is one
 // barrier per slice.
-template <int BM, int BN, int WM, int WN, bool TA, bool TB, bool BF16>
+// ABF: A is stored as bfloat16 (the saved aggregate of a layer whose activations are kept in bfloat16).
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, bool BF16, bool ABF = false>
 __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
 {
     constexpr int BK = 32;
@@ -632,7 +648,7 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
 
     f32x4 ra[gA::NV], rb[gB::NV];
     auto fetch = [&](int s) {
-        fetch_fast<BM, BK, A_RC>(ra, a.A, a.lda, m0, a.M, kbeg + (int64_t)s * BK, kend, a.K, a.a_row_index);
+        fetch_fast<BM, BK, A_RC, ABF>(ra, a.A, a.lda, m0, a.M, kbeg + (int64_t)s * BK, kend, a.K, a.a_row_index);
         fetch_fast<BN, BK, B_RC>(rb, a.B, a.ldb, n0, a.N, kbeg + (int64_t)s * BK, kend, a.K);
     };
     // column sums of B (the bias gradient next to dW = T^T dZ): every thread fetches the same four columns
@@ -982,7 +998,30 @@ struct skinny_tail {
 // NT8 = column tiles of 32 (N <= 32 NT8), S = slices of 32 along the reduction (K <= 32 S).  Both are
 // compile-time so that the order of every load and store of a row block is fixed: the waits on the
 // slices in flight then count exactly the operations issued after them.
-template <int NT8, int S, bool TAIL>
+// one element of the mask matrix (fp32 or bfloat16 storage): is it positive?
+__device__ __forceinline__ bool skinny_mask_at(const gemm_args &a, int64_t row, int64_t col)
+{
+    if (a.m_bf16) return (int16_t) reinterpret_cast<const u16 *>(a.mask)[row * a.ldm + col] > 0;
+    return a.mask[row * a.ldm + col] > 0.f;
+}
+
+// The four ballots of a 16-byte mask chunk (all lanes take part: no divergence around them), and of those the word
+// that holds the bits of this lane's column: e = li % 4.
+__device__ __forceinline__ uint64_t skinny_mask_word(const f32x4 &m, int li)
+{
+    const uint64_t b0 = __ballot(m[0] > 0.f), b1 = __ballot(m[1] > 0.f), b2 = __ballot(m[2] > 0.f), b3 = __ballot(m[3] > 0.f);
+    const uint64_t w01 = (li & 1) ? b1 : b0, w23 = (li & 1) ? b3 : b2;
+    return (li & 2) ? w23 : w01;
+}
+
+// MASK: the result is zeroed where a.mask (M x N, 16-byte chunks) is not positive.  That variant reads the mask
+// tile by tile during the epilogue and needs registers for it: it does not fetch the next row block's first
+// slices behind the current one's last multiplies but after the epilogue.
+// ABF: A is stored as bfloat16 (lda in elements, rows 8-byte aligned): a lane's chunk of four reduction values is 8 bytes
+// and goes to the LDS patch as it is.  a.c_bf16 (a run-time switch of the epilogue): C is stored as bfloat16, rounded to
+// nearest even; neighbouring lanes swap one value of every row pair so that a lane writes two adjacent columns at once.
+// a.m_bf16: the mask is stored as bfloat16.
+template <int NT8, int S, bool TAIL, bool MASK, bool ABF = false>
 __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gemm_args a, int tb, uint32_t n_rowblocks,
                                                                              skinny_tail tl)
 {
@@ -1068,36 +1107,54 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
     // loads: lane -> rows lr + 8 v (v = 0..3) of the wavefront's 32, 16-byte chunk kc of the slice
     const int lr = lane >> 3, kc = lane & 7;
     const int last_chunk = (K - 1) & ~3;
-    const float *rowp[4];
+    using ring_t = typename std::conditional<ABF, uint2, f32x4>::type;   // a lane's chunk of four reduction values
+    const float *rowp[4];        // with ABF: really 16-bit elements, addressed through elem()
     auto row_pointers = [&](uint32_t rb) {   // a row block past the end repeats the last one (loaded, never used)
         rb = min(rb, n_rowblocks - 1);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             int64_t row = min((int64_t)rb * (32 * SKINNY_WAVES) + wave * 32 + lr + 8 * v, a.M - 1);
             if (a.a_row_index) row = a.a_row_index[row];
-            rowp[v] = a.A + row * a.lda;
+            if constexpr (ABF) rowp[v] = reinterpret_cast<const float *>(reinterpret_cast<const u16 *>(a.A) + row * a.lda);
+            else rowp[v] = a.A + row * a.lda;
         }
     };
-    auto issue = [&](f32x4 (&r)[4], int slice) {
+    auto issue = [&](ring_t (&r)[4], int slice) {
         const int k = min(32 * slice + 4 * kc, last_chunk);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) r[v] = *reinterpret_cast<const f32x4 *>(rowp[v] + k);
-    };
-    auto stage = [&](f32x4 (&r)[4], int slice) {
-        const int k = 32 * slice + 4 * kc;
-        if (k + 4 > K) {     // the ragged end of the reduction
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (k + e >= K) r[v][e] = 0.f;
-        }
-#pragma unroll
         for (int v = 0; v < 4; ++v) {
-            uint2 w;
-            w.x = (uint32_t)to_bf16_bits(r[v][0]) | ((uint32_t)to_bf16_bits(r[v][1]) << 16);
-            w.y = (uint32_t)to_bf16_bits(r[v][2]) | ((uint32_t)to_bf16_bits(r[v][3]) << 16);
-            *reinterpret_cast<uint2 *>(LA + (lr + 8 * v) * 40 + 4 * kc) = w;
+            if constexpr (ABF) r[v] = *reinterpret_cast<const uint2 *>(reinterpret_cast<const u16 *>(rowp[v]) + k);
+            else r[v] = *reinterpret_cast<const f32x4 *>(rowp[v] + k);
+        }
+    };
+    auto stage = [&](ring_t (&r)[4], int slice) {
+        const int k = 32 * slice + 4 * kc;
+        if constexpr (ABF) {
+            if (k + 4 > K) {     // the ragged end of the reduction: zero the 16-bit values at or beyond K
+                const int left = K - k;      // values of the chunk that count: below 4, possibly <= 0
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    r[v].x = left <= 0 ? 0u : (left == 1 ? (r[v].x & 0xffffu) : r[v].x);
+                    r[v].y = left <= 2 ? 0u : (left == 3 ? (r[v].y & 0xffffu) : r[v].y);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) *reinterpret_cast<uint2 *>(LA + (lr + 8 * v) * 40 + 4 * kc) = r[v];
+        } else {
+            if (k + 4 > K) {     // the ragged end of the reduction
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (k + e >= K) r[v][e] = 0.f;
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                uint2 w;
+                w.x = (uint32_t)to_bf16_bits(r[v][0]) | ((uint32_t)to_bf16_bits(r[v][1]) << 16);
+                w.y = (uint32_t)to_bf16_bits(r[v][2]) | ((uint32_t)to_bf16_bits(r[v][3]) << 16);
+                *reinterpret_cast<uint2 *>(LA + (lr + 8 * v) * 40 + 4 * kc) = w;
+            }
         }
     };
     auto multiply = [&](int slice) {
@@ -1113,7 +1170,7 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
             }
     };
 
-    f32x4 ring[D][4];
+    ring_t ring[D][4];
     row_pointers(blockIdx.x);
 #pragma unroll
     for (int u = 0; u < D; ++u) issue(ring[u], u);
@@ -1121,27 +1178,88 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
 #pragma unroll
         for (int sl = 0; sl < S; ++sl) {
             stage(ring[sl % D], sl);
-            if (sl + D == S) row_pointers(rb + gridDim.x);       // the loads from here on belong to the next row block
-            issue(ring[sl % D], (sl + D) % S);
+            if (!MASK || sl + D < S) {
+                if (sl + D == S) row_pointers(rb + gridDim.x);       // the loads from here on belong to the next row block
+                issue(ring[sl % D], (sl + D) % S);
+            }
             multiply(sl);
         }
         // the row block is complete: write it
         const int64_t wrow = (int64_t)rb * (32 * SKINNY_WAVES) + wave * 32;
         const int64_t row0 = wrow + 4 * kh;   // the lane's first row
-        float *cl = a.C + row0 * a.ldc + li;
-        const float *mk = a.mask ? a.mask + row0 * a.ldm + li : nullptr;
+        float *cl = a.C + row0 * a.ldc + li;      // fp32 result; a bfloat16 result is addressed in the branches below
         if (wrow + 32 <= a.M) {
+            // The mask (zero the result where another M x N matrix is not positive: the ReLU backward of the layer
+            // below) is read the way A is: 16 bytes a lane, lane (lr, kc) takes columns 4 kc .. 4 kc + 3 of rows
+            // lr + 8 v of a 32-column tile, one tile ahead of the stores.  Four ballots per load turn a tile's mask
+            // into sixteen wave-uniform 64-bit words (bit 8 lr + kc of word (v, e) = row lr + 8 v, column 4 kc + e),
+            // from which every lane picks the bits of its own sixteen elements.  Read element by element in the
+            // accumulator layout (4 bytes a lane, a load in front of every store) the mask tripled the kernel's time.
+            constexpr bool vmask = MASK;
+            f32x4 mreg0, mreg1, mreg2, mreg3;                // with a bfloat16 mask: 8 bytes a lane, in .x and .y as bit patterns
+            uint64_t ws0 = 0, ws1 = 0, ws2 = 0, ws3 = 0;      // per v: the word (v, e = li % 4) of the current tile
+            const bool m16 = a.m_bf16 != 0, c16 = a.c_bf16 != 0;
+            const int64_t m8 = 8 * a.ldm;
+#define SKINNY_MASK_ISSUE(j_)                                                                                   \
+    {                                                                                                          \
+        const int64_t mo_ = (wrow + lr) * a.ldm + min((int64_t)(32 * (j_) + 4 * kc), (int64_t)(N - 4)); /* N is a multiple of 4 here */ \
+        if (m16) {                                                                                             \
+            const u16 *mp_ = reinterpret_cast<const u16 *>(a.mask) + mo_;                                      \
+            const uint2 q0_ = *reinterpret_cast<const uint2 *>(mp_), q1_ = *reinterpret_cast<const uint2 *>(mp_ + m8),          \
+                        q2_ = *reinterpret_cast<const uint2 *>(mp_ + 2 * m8), q3_ = *reinterpret_cast<const uint2 *>(mp_ + 3 * m8); \
+            mreg0 = widen_bf16x4(q0_); mreg1 = widen_bf16x4(q1_); mreg2 = widen_bf16x4(q2_); mreg3 = widen_bf16x4(q3_);       \
+        } else {                                                                                               \
+            const float *mp_ = a.mask + mo_;                                                                   \
+            mreg0 = *reinterpret_cast<const f32x4 *>(mp_);                                                     \
+            mreg1 = *reinterpret_cast<const f32x4 *>(mp_ + m8);                                                \
+            mreg2 = *reinterpret_cast<const f32x4 *>(mp_ + 2 * m8);                                            \
+            mreg3 = *reinterpret_cast<const f32x4 *>(mp_ + 3 * m8);                                            \
+        }                                                                                                      \
+    }
+            if constexpr (vmask) SKINNY_MASK_ISSUE(0)
 #pragma unroll
             for (int j = 0; j < NT8; ++j) {
+                if constexpr (vmask) {
+                    ws0 = skinny_mask_word(mreg0, li);
+                    ws1 = skinny_mask_word(mreg1, li);
+                    ws2 = skinny_mask_word(mreg2, li);
+                    ws3 = skinny_mask_word(mreg3, li);
+                    if (j + 1 < NT8) SKINNY_MASK_ISSUE(j + 1)
+                }
                 if (32 * j + li < N) {
                     const float bj = Lbias[32 * j + li];
+                    float zv[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int rr = 8 * (r / 4) + (r % 4);
                         float z = acc[j][r] + bj;
                         z = relu ? fmaxf(z, 0.f) : z;
-                        if (mk) z = mk[(int64_t)rr * a.ldm + 32 * j] > 0.f ? z : 0.f;
-                        cl[(int64_t)rr * a.ldc + 32 * j] = z;
+                        if constexpr (vmask) {
+                            // row 8 (r / 4) + 4 kh + r % 4 of the wavefront's 32: v = r / 4, lr = 4 kh + r % 4; column li: kc = li / 4, e = li % 4
+                            const uint64_t w = (r / 4) == 0 ? ws0 : ((r / 4) == 1 ? ws1 : ((r / 4) == 2 ? ws2 : ws3));
+                            z = ((w >> (8 * (4 * kh + (r % 4)) + (li >> 2))) & 1ull) ? z : 0.f;
+                        } else if (a.mask) z = skinny_mask_at(a, row0 + rr, 32 * j + li) ? z : 0.f;
+                        zv[r] = z;
+                    }
+                    if (!c16) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) cl[(int64_t)(8 * (r / 4) + (r % 4)) * a.ldc + 32 * j] = zv[r];
+                    } else if (a.c_pair) {
+                        // bfloat16 result, two adjacent columns a lane: of every pair of rows (r, r + 1) the even lane
+                        // takes row r and the odd lane row r + 1, each receiving its neighbour's value of that row
+                        u16 *cp = reinterpret_cast<u16 *>(a.C) + (row0 + (li & 1)) * a.ldc + 32 * j + (li & ~1);
+#pragma unroll
+                        for (int r = 0; r < 16; r += 2) {
+                            const float send = (li & 1) ? zv[r] : zv[r + 1];
+                            const float recv = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+                            const float lo = (li & 1) ? recv : zv[r], hi = (li & 1) ? zv[r + 1] : recv;
+                            *reinterpret_cast<uint32_t *>(cp + (int64_t)(8 * (r / 4) + (r % 4)) * a.ldc) =
+                                (uint32_t)to_bf16_bits(lo) | ((uint32_t)to_bf16_bits(hi) << 16);
+                        }
+                    } else {
+                        u16 *cp = reinterpret_cast<u16 *>(a.C) + row0 * a.ldc + 32 * j + li;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) cp[(int64_t)(8 * (r / 4) + (r % 4)) * a.ldc] = to_bf16_bits(zv[r]);
                     }
                 }
             }
@@ -1154,11 +1272,13 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
                     float z = acc[j][r] + Lbias[32 * j + li];
                     z = relu ? fmaxf(z, 0.f) : z;
                     if (32 * j + li < N && row0 + rr < a.M) {
-                        if (mk) z = mk[(int64_t)rr * a.ldm + 32 * j] > 0.f ? z : 0.f;
-                        cl[(int64_t)rr * a.ldc + 32 * j] = z;
+                        if (a.mask) z = skinny_mask_at(a, row0 + rr, 32 * j + li) ? z : 0.f;
+                        if (a.c_bf16) reinterpret_cast<u16 *>(a.C)[(row0 + rr) * a.ldc + 32 * j + li] = to_bf16_bits(z);
+                        else cl[(int64_t)rr * a.ldc + 32 * j] = z;
                     }
                 }
         }
+#undef SKINNY_MASK_ISSUE
         if constexpr (TAIL) {
             // 1 / rms of the lane's sixteen rows: squares summed over its columns, then over the 32 lanes that
             // share those rows (xor distances below 32 stay inside the half wavefront)
@@ -1223,6 +1343,11 @@ __global__ __launch_bounds__(64 * SKINNY_WAVES) void gemm_skinny_bf16_kernel(gem
         for (int j = 0; j < NT8; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+        if constexpr (MASK) {
+            row_pointers(rb + gridDim.x);
+#pragma unroll
+            for (int u = 0; u < D; ++u) issue(ring[u], u);
+        }
     }
 }
 
@@ -1232,16 +1357,39 @@ int launch_skinny_ns(sgnn_ctx *ctx, const gemm_args &a, int tb, const skinny_tai
     const size_t lds = skinny_lds_bytes(NT8, 32 * S + 8);
     static bool attr_set = false;
     if (!attr_set) {
-        SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny_bf16_kernel<NT8, S, TAIL>),
+        SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny_bf16_kernel<NT8, S, TAIL, false>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        if constexpr (!TAIL)
+            SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny_bf16_kernel<NT8, S, false, true>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_set = true;
     }
     const uint32_t n_rowblocks = (uint32_t)cdiv(a.M, 32 * SKINNY_WAVES);
     char tag[56];
-    snprintf(tag, sizeof(tag), "N%c skinny%s %lldx%lldx%lld bf16", tb ? 'T' : 'N', TAIL ? "+tail" : "", (long long)a.M, (long long)a.N,
-             (long long)a.K);
-    SGNN_LAUNCH(ctx, st, "gemm_skinny_bf16_kernel", tag, (gemm_skinny_bf16_kernel<NT8, S, TAIL>),
-                dim3(std::min<uint32_t>(n_rowblocks, 256)), dim3(64 * SKINNY_WAVES), lds, st, a, tb, n_rowblocks, tl);
+    const bool vmask = !TAIL && a.mask && a.vecM;      // the mask in chunks of four; else element by element
+    snprintf(tag, sizeof(tag), "N%c skinny%s %lldx%lldx%lld bf16 a=%d c=%d%s", tb ? 'T' : 'N', TAIL ? "+tail" : "", (long long)a.M,
+             (long long)a.N, (long long)a.K, a.a_bf16 ? 2 : 4, a.c_bf16 ? 2 : 4, a.mask ? (a.m_bf16 ? " mask m=2" : " mask m=4") : "");
+    const dim3 grid(std::min<uint32_t>(n_rowblocks, 256)), block(64 * SKINNY_WAVES);
+    if constexpr (!TAIL) {
+        if (a.a_bf16) {       // the launcher sends a bfloat16 A here only without a chunked mask
+            static bool attr16 = false;
+            if (!attr16) {
+                SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny_bf16_kernel<NT8, S, false, false, true>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+                attr16 = true;
+            }
+            SGNN_LAUNCH(ctx, st, "gemm_skinny_bf16_kernel", tag, (gemm_skinny_bf16_kernel<NT8, S, false, false, true>), grid, block, lds,
+                        st, a, tb, n_rowblocks, tl);
+            return SGNN_OK;
+        }
+        if (vmask) {
+            SGNN_LAUNCH(ctx, st, "gemm_skinny_bf16_kernel", tag, (gemm_skinny_bf16_kernel<NT8, S, false, true>), grid, block, lds, st, a,
+                        tb, n_rowblocks, tl);
+            return SGNN_OK;
+        }
+    }
+    SGNN_LAUNCH(ctx, st, "gemm_skinny_bf16_kernel", tag, (gemm_skinny_bf16_kernel<NT8, S, TAIL, false>), grid, block, lds, st, a, tb,
+                n_rowblocks, tl);
     return SGNN_OK;
 }
 
@@ -1521,13 +1669,17 @@ int launch_cfg(sgnn_ctx *ctx, int ta, int tb, int bf16, gemm_args a, int splits,
     const bool fast = a.alignedA && a.alignedB && a_contig % 4 == 0 && b_contig % 4 == 0 && a_contig >= 4 && b_contig >= 4 &&
                       a.K >= 1 && a.M >= 1 && a.N >= 1;
     if (fast && !(ta && tb)) {
-        snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld %s", ta ? 'T' : 'N', tb ? 'T' : 'N', BM, BN, (long long)a.M,
-                 (long long)a.N, (long long)a.K, bf16 ? "bf16" : "f32");
+        snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld %s%s", ta ? 'T' : 'N', tb ? 'T' : 'N', BM, BN, (long long)a.M,
+                 (long long)a.N, (long long)a.K, bf16 ? "bf16" : "f32", a.a_bf16 ? " a=2" : "");
 #define SGNN_GEMM_FAST(TA_, TB_, BF_)                                                                              \
     if (ta == TA_ && tb == TB_ && bf16 == BF_) {                                                                   \
         SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, TA_, TB_, BF_>), grid, block, 0, st, a); \
         return SGNN_OK;                                                                                            \
     }
+        if (a.a_bf16) {      // the launcher sends only A^T B with bf16 operands here in this storage
+            SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, true, false, true, true>), grid, block, 0, st, a);
+            return SGNN_OK;
+        }
         SGNN_GEMM_FAST(false, false, false)
         SGNN_GEMM_FAST(false, true, false)
         SGNN_GEMM_FAST(true, false, false)
@@ -1553,34 +1705,120 @@ int launch_cfg(sgnn_ctx *ctx, int ta, int tb, int bf16, gemm_args a, int splits,
     return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gemm: trans_a and trans_b together are not implemented");
 }
 
+
+// bfloat16 <-> fp32 copies of a matrix (rows x cols), for the products whose kernel does not read or write the
+// 16-bit storage itself; src rows optionally gathered through ridx.
+__global__ __launch_bounds__(256) void widen_bf16_kernel(const u16 *__restrict__ src, int64_t lds_, const int32_t *__restrict__ ridx,
+                                                         int64_t rows, int64_t cols, float *__restrict__ dst, int64_t ldd)
+{
+    const int64_t n = rows * cols;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / cols, c = i % cols;
+        const int64_t sr = ridx ? (int64_t)ridx[r] : r;
+        dst[r * ldd + c] = __builtin_bit_cast(float, (uint32_t)src[sr * lds_ + c] << 16);
+    }
+}
+
+__global__ __launch_bounds__(256) void narrow_bf16_kernel(const float *__restrict__ src, int64_t lds_, int64_t rows, int64_t cols,
+                                                          u16 *__restrict__ dst, int64_t ldd)
+{
+    const int64_t n = rows * cols;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / cols, c = i % cols;
+        dst[r * ldd + c] = to_bf16_bits(src[r * lds_ + c]);
+    }
+}
+
 } // namespace
 
 size_t sgnn_gemm_ws_bytes(uint32_t d_max) { return (size_t)256 * d_max * d_max * 4 + (size_t)256 * d_max * 4 + 512; }
+
+static inline int64_t gemm_pad4(int64_t d) { return (d + 3) & ~int64_t(3); }
 
 int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
                      const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias, int flags, float *C,
                      int64_t ldc, const float *mask, int64_t ldm, float *b_colsum, ws_alloc *ws, hipStream_t st)
 {
+    return sgnn_launch_gemm_x(ctx, ta, tb, M, N, K, A, 0, lda, a_row_index, B, ldb, bias, flags, C, 0, ldc, mask, 0, ldm, b_colsum, ws,
+                              st);
+}
+
+int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const void *Av, int a_bf16, int64_t lda,
+                       const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias, int flags, void *Cv, int c_bf16,
+                       int64_t ldc, const void *maskv, int m_bf16, int64_t ldm, float *b_colsum, ws_alloc *ws, hipStream_t st)
+{
+    const int bf16 = (flags & SGNN_BF16_MFMA) ? 1 : 0;
+    if ((a_bf16 || c_bf16) && !bf16)
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gemm: bfloat16 storage of A or C goes with SGNN_BF16_MFMA only");
+    if (!maskv) m_bf16 = 0;
+    // Which kernel reads or writes the 16-bit storage itself: the tall-operand kernel (A, C, the mask; A only without a
+    // chunked mask) and the chunked tile kernel for A^T B (A).  For everything else the operand is widened into scratch
+    // first (exact), or the result narrowed from scratch afterwards (the same rounding the kernel would apply).
+    const bool a_al16 = (reinterpret_cast<uintptr_t>(Av) & 7) == 0 && lda % 4 == 0;
+    const bool m_chunks = maskv && N % 4 == 0 && ldm % 4 == 0 && (reinterpret_cast<uintptr_t>(maskv) & (m_bf16 ? 7 : 15)) == 0;
+    const bool skinny_shape = bf16 && !ta && K >= 1 && K <= 256 && N >= 1 && N <= 256 && M >= 4096;
+    const bool tn_fast16 = bf16 && ta && !tb && a_al16 && (reinterpret_cast<uintptr_t>(B) & 15) == 0 && ldb % 4 == 0 && M % 4 == 0 &&
+                           N % 4 == 0 && M >= 4 && N >= 4 && K >= 1;
+    const bool a_native = a_bf16 && ((skinny_shape && a_al16 && !m_chunks) || tn_fast16);
+    const bool cm_native = skinny_shape && (a_bf16 ? a_native : ((reinterpret_cast<uintptr_t>(Av) & 15) == 0 && lda % 4 == 0));
+    const float *A = static_cast<const float *>(Av);
+    if (a_bf16 && !a_native) {
+        const int64_t rows = ta ? K : M, cols = ta ? M : K, ldw = gemm_pad4(cols);
+        float *Aw = ws->get<float>((size_t)rows * ldw);
+        if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gemm: scratch too small to widen a bfloat16 operand: call sgnn_ctx_reserve");
+        if (rows * cols > 0)
+            SGNN_LAUNCH(ctx, st, "widen_bf16_kernel", SGNN_TAG, widen_bf16_kernel, dim3((unsigned)std::min<int64_t>(cdiv(rows * cols, 256), 65536)),
+                        dim3(256), 0, st, static_cast<const u16 *>(Av), lda, a_row_index, rows, cols, Aw, ldw);
+        A = Aw; lda = ldw; a_row_index = nullptr; a_bf16 = 0;
+    }
+    const float *mask = static_cast<const float *>(maskv);
+    if (m_bf16 && !cm_native) {
+        const int64_t ldw = gemm_pad4(N);
+        float *Mw = ws->get<float>((size_t)M * ldw);
+        if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gemm: scratch too small to widen a bfloat16 mask: call sgnn_ctx_reserve");
+        if (M * N > 0)
+            SGNN_LAUNCH(ctx, st, "widen_bf16_kernel", SGNN_TAG, widen_bf16_kernel, dim3((unsigned)std::min<int64_t>(cdiv(M * N, 256), 65536)),
+                        dim3(256), 0, st, static_cast<const u16 *>(maskv), ldm, (const int32_t *)nullptr, M, N, Mw, ldw);
+        mask = Mw; ldm = ldw; m_bf16 = 0;
+    }
+    float *C = static_cast<float *>(Cv);
+    if (c_bf16 && !cm_native) {
+        const int64_t ldw = gemm_pad4(N);
+        float *Cw = ws->get<float>((size_t)M * ldw);
+        if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gemm: scratch too small for a bfloat16 result: call sgnn_ctx_reserve");
+        int rc = sgnn_launch_gemm_x(ctx, ta, tb, M, N, K, A, a_bf16, lda, a_row_index, B, ldb, bias, flags, Cw, 0, ldw, mask, m_bf16, ldm,
+                                    b_colsum, ws, st);
+        if (rc) return rc;
+        if (M * N > 0)
+            SGNN_LAUNCH(ctx, st, "narrow_bf16_kernel", SGNN_TAG, narrow_bf16_kernel, dim3((unsigned)std::min<int64_t>(cdiv(M * N, 256), 65536)),
+                        dim3(256), 0, st, Cw, ldw, M, N, static_cast<u16 *>(Cv), ldc);
+        return SGNN_OK;
+    }
+
     gemm_args a;
     a.mask = mask; a.ldm = ldm;
     a.colsum = nullptr;
     a.a_row_index = a_row_index;
     a.M = M; a.N = N; a.K = K;
     a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.bias = bias; a.C = C; a.ldc = ldc;
+    a.a_bf16 = a_bf16; a.c_bf16 = c_bf16; a.m_bf16 = m_bf16;
     a.relu = (flags & SGNN_RELU) ? 1 : 0;
-    a.alignedA = ((reinterpret_cast<uintptr_t>(A) & 15) == 0 && lda % 4 == 0) ? 1 : 0;
+    a.alignedA = a_bf16 ? (a_al16 ? 1 : 0) : (((reinterpret_cast<uintptr_t>(A) & 15) == 0 && lda % 4 == 0) ? 1 : 0);
     a.alignedB = ((reinterpret_cast<uintptr_t>(B) & 15) == 0 && ldb % 4 == 0) ? 1 : 0;
-    a.vecC = ((reinterpret_cast<uintptr_t>(C) & 15) == 0 && ldc % 4 == 0 && N % 4 == 0 &&
+    a.vecM = (mask && N % 4 == 0 && ldm % 4 == 0 && (reinterpret_cast<uintptr_t>(mask) & (m_bf16 ? 7 : 15)) == 0) ? 1 : 0;
+    a.c_pair = (c_bf16 && N % 2 == 0 && ldc % 2 == 0 && (reinterpret_cast<uintptr_t>(C) & 3) == 0) ? 1 : 0;
+    a.vecC = (!c_bf16 && !m_bf16 && (reinterpret_cast<uintptr_t>(C) & 15) == 0 && ldc % 4 == 0 && N % 4 == 0 &&
               (!mask || ((reinterpret_cast<uintptr_t>(mask) & 15) == 0 && ldm % 4 == 0)) &&
               (!bias || (reinterpret_cast<uintptr_t>(bias) & 15) == 0)) ? 1 : 0;
     a.k_per_split = K;
     a.partial = nullptr;
-    const int bf16 = (flags & SGNN_BF16_MFMA) ? 1 : 0;
     const int BK = bf16 ? 32 : SGNN_GEMM_BK_F32;
 
     // tall A times a small B on the bf16 path: stream A once with B resident in LDS
-    if (bf16 && !ta && K >= 1 && K <= 256 && N >= 1 && N <= 256 && M >= 4096 && a.alignedA)
+    if (skinny_shape && a.alignedA) {
+        if (b_colsum) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: column sums of B go with A^T B only");
         return launch_skinny(ctx, a, tb, st);
+    }
 
     // classifier-width products, fp32: straight from global memory into the MFMA operand layout
     if (!bf16 && !ta && tb && !a_row_index && K >= 4 && K <= 64 && K % 4 == 0 && a.alignedA && a.alignedB && M >= 1 && N >= 1 &&
@@ -1694,7 +1932,7 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
                     dim3(256), 0, st, a.partial, splits, M * N, N, C, ldc, cs_partial, b_colsum);
     }
     if (b_colsum && !cs_fused)
-        return sgnn_launch_relu_bwd_bias(ctx, nullptr, 0, B, ldb, 0, K, N, nullptr, 0, b_colsum, ws, st);
+        return sgnn_launch_relu_bwd_bias(ctx, nullptr, 0, 0, B, ldb, 0, K, N, nullptr, 0, b_colsum, ws, st);
     return SGNN_OK;
 }
 

@@ -75,6 +75,19 @@ template <int VEC> __device__ __forceinline__ void vstore(float *p, const float 
     }
 }
 
+// A finished output row segment: fp32 as it is, or rounded to bfloat16 (nearest even) and packed.
+template <int VEC> __device__ __forceinline__ void vstore_out(float *out, int64_t elem, const float (&src)[VEC], int out_bf16)
+{
+    if (!out_bf16) { vstore<VEC>(out + elem, src); return; }
+    uint16_t *p = reinterpret_cast<uint16_t *>(out) + elem;
+    uint16_t h[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) h[i] = __builtin_bit_cast(uint16_t, (__bf16)src[i]);
+    if constexpr (VEC == 1) *p = h[0];
+    else if constexpr (VEC == 2) *reinterpret_cast<uint32_t *>(p) = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+    else *reinterpret_cast<uint2 *>(p) = make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+}
+
 // Device-scope stores and loads (relaxed atomics, one word each): the store goes through to the
 // level of the memory system that all compute dies share and the load reads from there, so data
 // handed from one wavefront to another inside a kernel needs no write-back or invalidation of a
@@ -223,6 +236,8 @@ struct spmm_epi {
     int64_t ldm;
     const float *add;   // optional matrix added to the result last (the skip path of a residual layer)
     int64_t ldadd;
+    int out_bf16;       // the result is stored as bfloat16 (rounded to nearest even; `out` then points at 16-bit elements)
+    int mask_bf16;      // the mask matrix is stored as bfloat16
 };
 
 template <int VEC>
@@ -235,7 +250,8 @@ __device__ __forceinline__ void spmm_epilogue(float (&v)[VEC], const spmm_epi &e
     }
     if (ep.mask) {
         float m[VEC];
-        vload<VEC>(m, ep.mask + row * ep.ldm + col);
+        if (ep.mask_bf16) vload<VEC>(m, reinterpret_cast<const bf16_bits *>(ep.mask) + row * ep.ldm + col);
+        else vload<VEC>(m, ep.mask + row * ep.ldm + col);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) v[i] = m[i] > 0.f ? v[i] : 0.f;
     }
@@ -287,13 +303,13 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const void *__rest
     // the current row is complete: write it (unless it is a long one) and move to the next
     auto next_row = [&]() {
         if (!row_long) {
-            float *o = out + (int64_t)(r0 + row) * ldo;
+            const int64_t o = (int64_t)(r0 + row) * ldo;
 #pragma unroll
             for (int m = 0; m < CH; ++m) {
                 const int col = (m * 64 + lane) * VEC;
                 if (col < d) {
                     spmm_epilogue<VEC>(acc[m], ep, (int64_t)(r0 + row), col);
-                    vstore<VEC>(o + col, acc[m]);
+                    vstore_out<VEC>(out, o + col, acc[m], ep.out_bf16);
                 }
             }
         }
@@ -488,13 +504,13 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
                     }
                 }
             }
-            float *orow = out + (int64_t)drawn_row * ldo;
+            const int64_t orow = (int64_t)drawn_row * ldo;
 #pragma unroll
             for (int m = 0; m < CH; ++m) {
                 const int col = (m * 64 + lane) * VEC;
                 if (col < d) {
                     spmm_epilogue<VEC>(sum[m], ep, (int64_t)drawn_row, col);
-                    vstore<VEC>(orow + col, sum[m]);
+                    vstore_out<VEC>(out, orow + col, sum[m], ep.out_bf16);
                 }
             }
             if (lane == 0) ticket[drawn_first] = 0;
@@ -524,13 +540,13 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
             }
             if (re - rs <= plen) {
                 // the row's only piece: it is the row, written as the row-block wavefronts write theirs
-                float *orow = out + (int64_t)rc.x * ldo;
+                const int64_t orow = (int64_t)rc.x * ldo;
 #pragma unroll
                 for (int m = 0; m < CH; ++m) {
                     const int col = (m * 64 + lane) * VEC;
                     if (col < d) {
                         spmm_epilogue<VEC>(acc[m], ep, (int64_t)rc.x, col);
-                        vstore<VEC>(orow + col, acc[m]);
+                        vstore_out<VEC>(out, orow + col, acc[m], ep.out_bf16);
                     }
                 }
                 continue;
@@ -581,7 +597,8 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const XT *X, int64_t ldx, const 
     const int rows_per_wave = spmm_rows_per_wave(A->rows, A->capacity);   // lower bound of the plan's figure
     const unsigned rows_per_block = (unsigned)(SPMM_NT / 64) * (unsigned)rows_per_wave;
     char tag[56];
-    snprintf(tag, sizeof(tag), "%ux%u d=%d <%d,%d>%s", A->rows, A->cols, d, VEC, CH, sizeof(XT) == 2 ? " bf16 in" : "");
+    snprintf(tag, sizeof(tag), "%ux%u d=%d <%d,%d> in=%d out=%d%s", A->rows, A->cols, d, VEC, CH, (int)sizeof(XT), ep.out_bf16 ? 2 : 4,
+             ep.mask ? (ep.mask_bf16 ? " m=2" : " m=4") : "");
     const bool may_have_long = A->capacity > (uint64_t)SPMM_SHORT;
     spmm_plan_view pv = {nullptr, nullptr, nullptr, nullptr};
     float *part = nullptr;
@@ -677,8 +694,17 @@ int sgnn_launch_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const void *X, int x_bf16
                      float *out, int64_t ldo, const float *bias, int relu, const float *mask, int64_t ldm, const float *add,
                      int64_t ldadd, ws_alloc *ws, hipStream_t st)
 {
-    const spmm_epi ep = {bias, relu, mask, ldm, add, ldadd};
+    return sgnn_launch_spmm_x(ctx, A, X, x_bf16, ldx, row_index, d, out, 0, ldo, bias, relu, mask, 0, ldm, add, ldadd, ws, st);
+}
+
+// The same with the result (out_bf16) and the mask (mask_bf16) optionally stored as bfloat16; their leading
+// dimensions are in elements.
+int sgnn_launch_spmm_x(sgnn_ctx *ctx, const sgnn_csr *A, const void *X, int x_bf16, int64_t ldx, const int32_t *row_index, int64_t d,
+                       void *out, int out_bf16, int64_t ldo, const float *bias, int relu, const void *mask, int mask_bf16,
+                       int64_t ldm, const float *add, int64_t ldadd, ws_alloc *ws, hipStream_t st)
+{
+    const spmm_epi ep = {bias, relu, static_cast<const float *>(mask), ldm, add, ldadd, out_bf16 ? 1 : 0, (mask && mask_bf16) ? 1 : 0};
     if (A->rows == 0 || d == 0) return SGNN_OK;
-    if (x_bf16) return launch_x(ctx, A, static_cast<const bf16_bits *>(X), ldx, row_index, d, out, ldo, ep, ws, st);
-    return launch_x(ctx, A, static_cast<const float *>(X), ldx, row_index, d, out, ldo, ep, ws, st);
+    if (x_bf16) return launch_x(ctx, A, static_cast<const bf16_bits *>(X), ldx, row_index, d, static_cast<float *>(out), ldo, ep, ws, st);
+    return launch_x(ctx, A, static_cast<const float *>(X), ldx, row_index, d, static_cast<float *>(out), ldo, ep, ws, st);
 }

@@ -20,7 +20,9 @@ class GcnStep:
     def __init__(self, N: int, rowptr: torch.Tensor, colidx: torch.Tensor, X: torch.Tensor, labels: torch.Tensor,
                  weights: List[Tuple[torch.Tensor, torch.Tensor]], B: int, seed: int = 0, bf16: bool = False,
                  fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None,
-                 auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = False):
+                 auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = False, bf16_activations: bool = False):
+        """bf16_activations (with bf16): the aggregates T_l and the layer outputs H_l (all but the logits) are stored as
+        bfloat16; gradients stay fp32."""
         self.N, self.B, self.seed = N, B, seed
         self.rowptr, self.colidx, self.X, self.labels = rowptr, colidx, X, labels
         self.weights = weights
@@ -49,10 +51,15 @@ class GcnStep:
                              "and a first layer that aggregates first")
         self.fuse_relu_bwd = fuse_relu_bwd
         self.side_dw = side_dw      # run() / graphs: weight-gradient GEMMs on the second stream
-        def mat(d):   # B x d with rows starting 16-byte aligned (leading dimension a multiple of 4)
-            return torch.empty((B, (d + 3) // 4 * 4), dtype=torch.float32, device=dev)[:, :d]
-        self.T = [None if self.xform_first[l] else mat(dims[l]) for l in range(self.L)]
-        self.H = [mat(dims[l + 1]) for l in range(self.L)]
+        if bf16_activations and not bf16:
+            raise ValueError("bfloat16 storage of the activations goes with bfloat16 GEMM operands (bf16=True)")
+        self.bf16_activations = bf16_activations
+        act = torch.bfloat16 if bf16_activations else torch.float32
+        def mat(d, dtype=torch.float32):   # B x d with rows starting 16-byte aligned (leading dimension a multiple of 8 / 4)
+            pad = 8 if dtype == torch.bfloat16 else 4
+            return torch.empty((B, (d + pad - 1) // pad * pad), dtype=dtype, device=dev)[:, :d]
+        self.T = [None if self.xform_first[l] else mat(dims[l], act) for l in range(self.L)]
+        self.H = [mat(dims[l + 1], act if l < self.L - 1 else torch.float32) for l in range(self.L)]
         self.dH = [mat(dims[l]) if l > 0 else None for l in range(self.L)]
         self.dO = mat(dims[-1])
         self.dW = [torch.empty_like(w) for w, _ in weights]

@@ -10,6 +10,7 @@ DEV = "cuda:0"
 TOL_F32 = 1e-5     # relative error bar for fp32 features and gradients
 TOL_BF16 = 2e-2    # relative error bar with bfloat16 GEMM operands
 TOL_VAL = 1e-6     # edge weights (fp64 formula rounded once to fp32 on both sides)
+LOGIT_BAND = 2.0 ** -7   # accuracy of a logit relative to its row's largest, bfloat16 operands and storage (checked where it is used)
 
 _ctx = None
 

@@ -1,12 +1,13 @@
 """GPU parity: SpMM, MFMA GEMM, layer forward / backward and the whole step against the CPU oracle."""
 import numpy as np
 import pytest
+import scipy.sparse as sp
 import torch
 
 import oracle
 import paper_2604_02651_amd as sg
 import synth_inputs as si
-from gpu_util import DEV, TOL_BF16, TOL_F32, TOL_VAL, ctx, dev, rel_err
+from gpu_util import DEV, LOGIT_BAND, TOL_BF16, TOL_F32, TOL_VAL, ctx, dev, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -229,6 +230,93 @@ def test_gemm_masked_result(M, N, K, bf16):
     ref = np.where(mask[:, :N] > 0, rd(A) @ rd(Bt).T, 0.0)
     assert rel_err(C.cpu().numpy(), ref) < (1e-4 if bf16 else TOL_F32)
     assert torch.all(C[dev(mask)[:, :N] <= 0] == 0)
+
+
+@pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("M,N,K", [(5000, 256, 172), (4096, 256, 256), (9001, 172, 256), (4100, 100, 47), (6000, 36, 128),
+                                   (4500, 64, 200)])
+def test_gemm_tall_bf16_masked_in_chunks(M, N, K, tb):
+    # the tall-operand bf16 kernel with a mask it can read 16 bytes at a time (aligned, leading dimension a multiple of
+    # four): every column-tile and slice count of the kernel, a ragged last row block, a mask wider than the result
+    A = _rand((M, K), 21); Bm = _rand((N, K) if tb else (K, N), 22)
+    mask = np.maximum(_rand((M, N + 4), 23), 0.0)
+    md = dev(mask)[:, :N]
+    assert md.stride(0) % 4 == 0 and md.data_ptr() % 16 == 0
+    C = torch.full((M, N), 5.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), False, tb, dev(A), dev(Bm), None, sg.SGNN_BF16_MFMA, C, mask=md)
+    prod = oracle.round_bf16(A) @ (oracle.round_bf16(Bm).T if tb else oracle.round_bf16(Bm))
+    ref = np.where(mask[:, :N] > 0, prod, 0.0)
+    assert rel_err(C.cpu().numpy(), ref) < 1e-4
+    assert torch.all(C[md <= 0] == 0)
+
+
+def _bf(x):
+    return torch.as_tensor(np.ascontiguousarray(x)).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("M,N,K", [(5000, 256, 172), (4096, 256, 256), (9001, 172, 256), (4100, 100, 48), (6000, 36, 128),
+                                   (4500, 64, 200), (1000, 256, 128), (300, 47, 100)])
+def test_gemm_bf16_stored_operand_and_result(M, N, K, tb):
+    # A and C stored as bfloat16 (tall shapes: the kernel reads and writes them; short ones: fp32 copies in scratch):
+    # the product of the stored values, rounded once to bfloat16 when written
+    A = oracle.round_bf16(_rand((M, K), 31)); Bm = _rand((N, K) if tb else (K, N), 32); bias = _rand((N,), 33)
+    Ad = _bf(np.pad(A, ((0, 0), (0, (-K) % 8)))).to(DEV)[:, :K]
+    C = torch.full((M, (N + 7) // 8 * 8), 5.0, dtype=torch.bfloat16, device=DEV)[:, :N]
+    ctx().reserve(1, 1, M, 256)
+    sg.sgnn_gemm(ctx(), False, tb, Ad, dev(Bm), dev(bias), sg.SGNN_BF16_MFMA | sg.SGNN_RELU, C)
+    Br = oracle.round_bf16(Bm)
+    ref = np.maximum(A @ (Br.T if tb else Br) + bias, 0.0)
+    got = C.float().cpu().numpy().astype(np.float64)
+    # the kernel accumulates in fp32 and rounds once: within one bfloat16 unit of the rounded exact result
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4 * np.abs(ref).max())
+    assert rel_err(got, oracle.round_bf16(ref)) < 2.0 ** -8
+    # fp32 result from the same stored operand: to fp32 accuracy
+    C32 = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), False, tb, Ad, dev(Bm), dev(bias), sg.SGNN_BF16_MFMA | sg.SGNN_RELU, C32)
+    assert rel_err(C32.cpu().numpy(), ref) < 1e-4
+
+
+@pytest.mark.parametrize("M,N,K", [(5000, 256, 172), (4100, 100, 48), (700, 64, 40)])
+def test_gemm_bf16_stored_mask_and_weight_gradient(M, N, K):
+    # the mask stored as bfloat16 (chunked and element-wise paths), and A^T B with a bfloat16-stored A
+    A = _rand((M, K), 41); Bt = _rand((N, K), 42)
+    mask = oracle.round_bf16(np.maximum(_rand((M, N), 43), 0.0))
+    md = _bf(np.pad(mask, ((0, 0), (0, (-N) % 8)))).to(DEV)[:, :N]
+    C = torch.full((M, N), 5.0, dtype=torch.float32, device=DEV)
+    ctx().reserve(1, 1, M, 256)
+    sg.sgnn_gemm(ctx(), False, True, dev(A), dev(Bt), None, sg.SGNN_BF16_MFMA, C, mask=md)
+    ref = np.where(mask > 0, oracle.round_bf16(A) @ oracle.round_bf16(Bt).T, 0.0)
+    assert rel_err(C.cpu().numpy(), ref) < 1e-4 and torch.all(C[md <= 0] == 0)
+    # dW = T^T dZ with T stored as bfloat16 (M rows reduced), with the column sums of dZ
+    T = oracle.round_bf16(_rand((M, K), 44)); dZ = _rand((M, N), 45)
+    Td = _bf(np.pad(T, ((0, 0), (0, (-K) % 8)))).to(DEV)[:, :K]
+    dW = torch.zeros((K, N), dtype=torch.float32, device=DEV); cs = torch.zeros(N, dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), True, False, Td, dev(dZ), None, sg.SGNN_BF16_MFMA, dW, b_colsum=cs)
+    assert rel_err(dW.cpu().numpy(), T.T @ oracle.round_bf16(dZ)) < 1e-4
+    assert rel_err(cs.cpu().numpy(), dZ.astype(np.float64).sum(axis=0)) < 1e-4
+    dW32 = torch.zeros_like(dW)
+    sg.sgnn_gemm(ctx(), True, False, dev(T, torch.float32), dev(dZ), None, sg.SGNN_BF16_MFMA, dW32)
+    assert torch.equal(dW, dW32)          # the stored values are what the fp32-stored operand rounds to: same product
+
+
+@pytest.mark.parametrize("d", [256, 172, 128, 100, 47, 33])
+def test_spmm_bf16_stored_result(d):
+    # out stored as bfloat16: the fp32 sum rounded once; with a bfloat16 input as well
+    rng = np.random.default_rng(d)
+    rows = 3000
+    dense = (rng.random((rows, rows)) < 0.002) * rng.random((rows, rows))
+    dense[5, :] = rng.random(rows) * (rng.random(rows) < 0.5)           # a long row: pieces and the last-ticket sum
+    A = sp.csr_matrix(dense.astype(np.float32))
+    X = oracle.round_bf16(_rand((rows, d), 51))
+    Ad = sg.Csr.from_arrays(rows, rows, A.indptr.astype(np.int32), A.indices.astype(np.int32), A.data.astype(np.float32), DEV)
+    ctx().reserve(rows, A.nnz, rows, max(d, 8), A.nnz)
+    want = oracle.spmm(A.indptr.astype(np.int32), A.indices.astype(np.int32), A.data.astype(np.float32), X)
+    for xin in (dev(X, torch.float32), _bf(np.pad(X, ((0, 0), (0, (-d) % 8)))).to(DEV)[:, :d]):
+        out = torch.full((rows, (d + 7) // 8 * 8), 3.0, dtype=torch.bfloat16, device=DEV)[:, :d]
+        sg.sgnn_spmm(ctx(), Ad, xin, out)
+        got = out.float().cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-5 * np.abs(want).max())
 
 
 @pytest.mark.parametrize("bf16", [False, True])
@@ -475,7 +563,7 @@ def test_softmax_xent_with_column_sums(B, C):
         sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss2, None, dO_colsum=cs2)
 
 
-def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_bwd=True):
+def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_bwd=True, bf16_act=False):
     cfg = si.CONFIGS[name]
     bf16 = cfg.bf16_mfma if bf16 is None else bf16
     # inputs are generated with torch on the GPU (integer parts are device independent) and copied
@@ -486,7 +574,8 @@ def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_b
     weights = si.layer_weights(cfg)
     st = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld,
                     [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B, cfg.sampler_seed, bf16=bf16,
-                    fuse_slice=fuse_slice, device=DEV, auto_order=auto_order, fuse_relu_bwd=fuse_relu_bwd)
+                    fuse_slice=fuse_slice, device=DEV, auto_order=auto_order, fuse_relu_bwd=fuse_relu_bwd,
+                    bf16_activations=bf16_act)
     g = si.Graph(cfg.N, gd.rowptr.cpu(), gd.colidx.cpu())
     X, labels = Xd.cpu(), ld.cpu()
     wnp = [(W.double().numpy(), b.double().numpy()) for W, b in weights]
@@ -497,7 +586,7 @@ def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_b
         torch.cuda.synchronize()
         st.ctx.status()
         args = (cfg.N, g.rowptr.numpy(), g.colidx.numpy(), X.numpy(), labels.numpy(), wnp, cfg.B, cfg.sampler_seed, t)
-        ref = oracle.gcn_step(*args, bf16=bf16, tie_band=band)
+        ref = oracle.gcn_step(*args, bf16=bf16, tie_band=band, store_bf16=bf16_act)
         nnz = st.A.nnz()
         assert np.array_equal(st.S.cpu().numpy(), ref["S"])
         assert np.array_equal(st.A.rowptr.cpu().numpy(), ref["rowptr"]) and nnz == len(ref["colidx"])
@@ -510,18 +599,33 @@ def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_b
         ties = []
         for l in range(cfg.layers):
             if st.T[l] is not None:      # transform-first layers never form the aggregate
-                assert rel_err(st.T[l].cpu().numpy(), ref["T"][l]) < tol, ("T", l)
-            assert rel_err(st.H[l].cpu().numpy(), ref["H"][l + 1]) < tol, ("H", l)
+                assert rel_err(st.T[l].float().cpu().numpy(), ref["T"][l]) < tol, ("T", l)
+            assert rel_err(st.H[l].float().cpu().numpy(), ref["H"][l + 1]) < tol, ("H", l)
             # the ReLU decision must agree wherever the pre-activation is decidably non-zero
-            got_mask = st.H[l].cpu().numpy() > 0
+            got_mask = st.H[l].float().cpu().numpy() > 0
             if l < cfg.layers - 1:
                 assert np.array_equal(got_mask[~ref["relu_band"][l]], ref["relu_mask"][l][~ref["relu_band"][l]])
             ties.append(got_mask)
         assert abs(st.loss.item() - ref["loss"]) < tol * abs(ref["loss"])
         # inside the undecidable band either mask is correct: the gradients are checked against the
         # oracle evaluated with the decisions the kernels took there
-        if any((ties[l] != ref["relu_mask"][l]).any() for l in range(cfg.layers - 1)):
-            ref = oracle.gcn_step(*args, bf16=bf16, tie_band=band, relu_ties=ties)
+        kw = {}
+        if bf16:
+            # the loss gradient has an undecidable set as well (rows with large, unsaturated logits, defined by the
+            # oracle from its own logits): the device's rows enter there, after being checked against the definition
+            # and after the device's logits have been shown to lie within the band of the oracle's
+            und = oracle.undecidable_loss_rows(ref["H"][-1], ref["y_S"], LOGIT_BAND, tol)
+            O_gpu = st.H[-1].cpu().numpy().astype(np.float64)
+            dO_gpu = st.dO.cpu().numpy().astype(np.float64)
+            _, dO_def = oracle.softmax_xent(O_gpu, ref["y_S"])
+            assert rel_err(dO_gpu, dO_def) < TOL_F32
+            eps = LOGIT_BAND * np.abs(ref["H"][-1]).max(axis=1)
+            assert np.all(np.abs(O_gpu - ref["H"][-1])[und] <= eps[und, None])
+            assert und.mean() < 0.1
+            if und.any():
+                kw = dict(logit_band=LOGIT_BAND, grad_band=tol, dO_ties=dO_gpu)
+        if any((ties[l] != ref["relu_mask"][l]).any() for l in range(cfg.layers - 1)) or kw:
+            ref = oracle.gcn_step(*args, bf16=bf16, tie_band=band, relu_ties=ties, store_bf16=bf16_act, **kw)
         for l in range(cfg.layers):
             assert rel_err(st.dW[l].cpu().numpy(), ref["dW"][l]) < tol, ("dW", l)
             assert rel_err(st.db[l].cpu().numpy(), ref["db"][l]) < tol, ("db", l)
@@ -571,6 +675,21 @@ def test_whole_step_medium():
     _run_config("medium", [0, 15], True)
 
 
+@pytest.mark.parametrize("auto_order", [False, True])
+@pytest.mark.parametrize("fuse_relu_bwd", [False, True])
+def test_whole_step_bf16_activations_medium(auto_order, fuse_relu_bwd):
+    # |S| = 32768: the tall-operand kernel reads and writes the 16-bit activations itself (aggregate-first and
+    # transform-first layers, fused and separate ReLU backward)
+    _run_config("medium", [3], True, bf16=True, auto_order=auto_order, fuse_relu_bwd=fuse_relu_bwd, bf16_act=True)
+
+
+@pytest.mark.parametrize("fuse_slice", [False, True])
+def test_whole_step_bf16_activations_tiny(fuse_slice):
+    # |S| = 1024: every product goes through the fp32 copies in scratch
+    _run_config("tiny", [0, 1], fuse_slice, bf16=True, bf16_act=True)
+    _run_config("tiny", [2], fuse_slice, bf16=True, bf16_act=True, auto_order=False, fuse_relu_bwd=False)
+
+
 def test_whole_step_large_bf16():
     # co-purchase-shaped graph at full size: 2.4 M vertices, 124 M stored entries, |S| = 262144
     _run_config("large", [0], True)
@@ -595,7 +714,7 @@ def test_whole_step_xlarge_bf16():
     ld = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=DEV)
     weights = si.layer_weights(cfg)
     st = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B,
-                    cfg.sampler_seed, bf16=True, fuse_slice=True, device=DEV)
+                    cfg.sampler_seed, bf16=True, fuse_slice=True, device=DEV, bf16_activations=True)   # as the benchmark runs it
     st.step(0)
     torch.cuda.synchronize()
     st.ctx.status()
@@ -616,8 +735,9 @@ def test_whole_step_xlarge_bf16():
     assert np.array_equal(st.y_S.cpu().numpy(), y_S)
     wnp = [(W.double().numpy(), b.double().numpy()) for W, b in weights]
     store = bool(getattr(st, "bf16_activations", False))
-    band_l = TOL_BF16        # logits are held to this bar; it also defines which loss-gradient rows are decidable
-    ref = oracle.layers_step(rpS, ciS, vS, X_S, y_S, wnp, bf16=True, tie_band=1e-3, store_bf16=store, logit_band=band_l)
+    band_l = LOGIT_BAND      # accuracy of a logit relative to its row's largest (checked below on the rows it matters for)
+    ref = oracle.layers_step(rpS, ciS, vS, X_S, y_S, wnp, bf16=True, tie_band=1e-3, store_bf16=store, logit_band=band_l,
+                             grad_band=TOL_BF16)
     Hg = [st.H[l].float().cpu().numpy() for l in range(cfg.layers)]
     ties = [h > 0 for h in Hg]
     for l in range(cfg.layers - 1):
@@ -640,10 +760,10 @@ def test_whole_step_xlarge_bf16():
           % (und.sum(), cfg.B, 100.0 * und.mean(), row_diff[~und].max(), row_diff[und].max() if und.any() else 0.0), flush=True)
     assert und.mean() < 0.02
     assert np.all(np.abs(O_gpu - O_ref)[und] <= eps[und, None])
-    assert row_diff[~und].max() <= band_l            # decidable rows: the two sides' own gradients agree to the bar
+    assert row_diff[~und].max() <= TOL_BF16          # decidable rows: the two sides' own gradients agree to the bar
     if any((ties[l] != ref["relu_mask"][l]).any() for l in range(cfg.layers - 1)) or und.any():
         ref = oracle.layers_step(rpS, ciS, vS, X_S, y_S, wnp, bf16=True, tie_band=1e-3, relu_ties=ties, store_bf16=store,
-                                 logit_band=band_l, dO_ties=dO_gpu)
+                                 logit_band=band_l, grad_band=TOL_BF16, dO_ties=dO_gpu)
     for l in range(cfg.layers):
         if st.T[l] is not None:
             assert rel_err(st.T[l].float().cpu().numpy(), ref["T"][l]) < TOL_BF16, ("T", l)

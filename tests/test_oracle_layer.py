@@ -295,6 +295,14 @@ def test_undecidable_loss_rows_are_the_large_unsaturated_ones():
         _, g1 = oracle.softmax_xent(O + eps * rng.choice([-1.0, 1.0], O.shape), y)
         worst = np.maximum(worst, np.abs(g1 - g0).max(axis=1) / np.abs(g0).max())
     assert worst[~und].max() <= band and worst[und].max() > 5 * band
+    # a separate bar for the gradient: logits known four times better than the bar they are measured against
+    und4 = oracle.undecidable_loss_rows(O, y, band / 4, band)
+    assert und4.sum() < und.sum() and not (und4 & ~und).any()
+    worst4 = np.zeros(300)
+    for _ in range(30):
+        _, g1 = oracle.softmax_xent(O + 0.25 * eps * rng.choice([-1.0, 1.0], O.shape), y)
+        worst4 = np.maximum(worst4, np.abs(g1 - g0).max(axis=1) / np.abs(g0).max())
+    assert worst4[~und4].max() <= band
 
 
 def test_loss_gradient_ties_enter_only_inside_the_band():
