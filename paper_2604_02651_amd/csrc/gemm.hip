@@ -19,6 +19,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 #include "philox.h"
@@ -318,7 +319,7 @@ __device__ __forceinline__ f32x4 widen_bf16x4(uint2 w)
 }
 
 template <int R, int BK, bool RC, bool SRC16 = false>
-__device__ __forceinline__ void fetch_fast(f32x4 *reg, const float *__restrict__ G, int64_t ld, int64_t row0,
+__device__ __forceinline__ void fetch_fast(typename std::conditional<SRC16, uint2, f32x4>::type *reg, const float *__restrict__ G, int64_t ld, int64_t row0,
                                            int64_t rows_total, int64_t k0, int64_t k_end, int64_t k_total,
                                            const int32_t *__restrict__ ridx = nullptr)
 {
@@ -343,13 +344,27 @@ __device__ __forceinline__ void fetch_fast(f32x4 *reg, const float *__restrict__
         if (ridx) gr = ridx[gr];
         (void)valid;   // the reduction tail is zeroed by mask_fast when the slice is stored to LDS,
                        // so that nothing here waits for the load
-        f32x4 x = {0.f, 0.f, 0.f, 0.f};
-        if (g::TOTAL % 256 == 0 || idx < g::TOTAL) {
-            if constexpr (SRC16) x = widen_bf16x4(*reinterpret_cast<const uint2 *>(reinterpret_cast<const u16 *>(G) + gr * ld + gc));
-            else x = *reinterpret_cast<const f32x4 *>(G + gr * ld + gc);
+        if constexpr (SRC16) {
+            // kept as loaded (8 bytes of bit patterns): widened by widen_fast() when the slice is staged, so that
+            // nothing but the staging waits for a load of the slice
+            uint2 w = make_uint2(0u, 0u);
+            if (g::TOTAL % 256 == 0 || idx < g::TOTAL) w = *reinterpret_cast<const uint2 *>(reinterpret_cast<const u16 *>(G) + gr * ld + gc);
+            reg[v] = w;
+        } else {
+            f32x4 x = {0.f, 0.f, 0.f, 0.f};
+            if (g::TOTAL % 256 == 0 || idx < g::TOTAL) x = *reinterpret_cast<const f32x4 *>(G + gr * ld + gc);
+            reg[v] = x;
         }
-        reg[v] = x;
     }
+}
+
+// chunks fetched from a bfloat16 operand (8 bytes of bit patterns) to four fp32 values
+template <int R, int BK, bool RC>
+__device__ __forceinline__ void widen_fast(f32x4 *reg, const uint2 *raw)
+{
+    using g = fetch_geom<R, BK, RC>;
+#pragma unroll
+    for (int v = 0; v < g::NV; ++v) reg[v] = widen_bf16x4(raw[v]);
 }
 
 // zero the chunks of a fetched slice that lie at or beyond the end of the reduction range
@@ -647,8 +662,11 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     f32x4 ra[gA::NV], rb[gB::NV];
+    typename std::conditional<ABF, uint2, f32x4>::type *ra_fetch;      // where the fetch puts A: ra itself, or the raw 16-bit chunks
+    uint2 ra16[ABF ? gA::NV : 1];
+    if constexpr (ABF) ra_fetch = ra16; else ra_fetch = ra;
     auto fetch = [&](int s) {
-        fetch_fast<BM, BK, A_RC, ABF>(ra, a.A, a.lda, m0, a.M, kbeg + (int64_t)s * BK, kend, a.K, a.a_row_index);
+        fetch_fast<BM, BK, A_RC, ABF>(ra_fetch, a.A, a.lda, m0, a.M, kbeg + (int64_t)s * BK, kend, a.K, a.a_row_index);
         fetch_fast<BN, BK, B_RC>(rb, a.B, a.ldb, n0, a.N, kbeg + (int64_t)s * BK, kend, a.K);
     };
     // column sums of B (the bias gradient next to dW = T^T dZ): every thread fetches the same four columns
@@ -656,6 +674,7 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
     f32x4 cs = {0.f, 0.f, 0.f, 0.f};
     const bool do_cs = TA && !TB && a.colsum && tb_.bx == 0;
     auto stage = [&](int s) {
+        if constexpr (ABF) widen_fast<BM, BK, A_RC>(ra, ra16);
         mask_fast<BM, BK, A_RC>(ra, kbeg + (int64_t)s * BK, kend);
         mask_fast<BN, BK, B_RC>(rb, kbeg + (int64_t)s * BK, kend);
         if constexpr (TA && !TB) {

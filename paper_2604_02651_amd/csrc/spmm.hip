@@ -64,6 +64,29 @@ template <int VEC> __device__ __forceinline__ void vload(float (&dst)[VEC], cons
     }
 }
 
+// A gathered chunk as the load instruction returns it (fp32 values, or packed bfloat16 pairs), and its i-th value.
+// Widening a bfloat16 chunk right behind its load would make every gather wait for the one before it; kept raw, all
+// gathers of a round are in flight together and the widening happens where the value is multiplied.
+template <int VEC, typename XT> struct raw_chunk { float v[VEC]; };
+template <int VEC> struct raw_chunk<VEC, bf16_bits> { uint32_t w[(VEC + 1) / 2]; };
+
+template <int VEC> __device__ __forceinline__ void raw_load(raw_chunk<VEC, float> &r, const float *p) { vload<VEC>(r.v, p); }
+template <int VEC> __device__ __forceinline__ void raw_load(raw_chunk<VEC, bf16_bits> &r, const bf16_bits *p)
+{
+    if constexpr (VEC == 1) r.w[0] = p->v;
+    else if constexpr (VEC == 2) r.w[0] = *reinterpret_cast<const uint32_t *>(p);
+    else {
+        const uint2 q = *reinterpret_cast<const uint2 *>(p);
+        r.w[0] = q.x; r.w[1] = q.y;
+    }
+}
+template <int VEC> __device__ __forceinline__ float raw_get(const raw_chunk<VEC, float> &r, int i) { return r.v[i]; }
+template <int VEC> __device__ __forceinline__ float raw_get(const raw_chunk<VEC, bf16_bits> &r, int i)
+{
+    const uint32_t w = r.w[i >> 1];
+    return __builtin_bit_cast(float, (i & 1) ? (w & 0xffff0000u) : (w << 16));
+}
+
 template <int VEC> __device__ __forceinline__ void vstore(float *p, const float (&src)[VEC])
 {
     if constexpr (VEC == 1) *p = src[0];
@@ -342,7 +365,8 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const void *__rest
         }
         int used = n;
         for (int j0 = 0; j0 < n && used == n; j0 += U) {
-            float v[U][CH][VEC], av[U];
+            raw_chunk<VEC, XT> v[U][CH];
+            float av[U];
 #pragma unroll
             for (int t = 0; t < U; ++t) {
                 const int jj = __builtin_amdgcn_readfirstlane(min(j0 + t, n - 1));
@@ -351,7 +375,7 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const void *__rest
 #pragma unroll
                 for (int m = 0; m < CH; ++m) {
                     const int col = (m * 64 + lane) * VEC;
-                    if (col < d) vload<VEC>(v[t][m], x + col);
+                    if (col < d) raw_load<VEC>(v[t][m], x + col);
                 }
             }
 #pragma unroll
@@ -366,7 +390,7 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const void *__rest
                             const int col = (m * 64 + lane) * VEC;
                             if (col < d) {
 #pragma unroll
-                                for (int i = 0; i < VEC; ++i) acc[m][i] = fmaf(av[t], v[t][m][i], acc[m][i]);
+                                for (int i = 0; i < VEC; ++i) acc[m][i] = fmaf(av[t], raw_get<VEC>(v[t][m], i), acc[m][i]);
                             }
                         }
                     }
@@ -386,7 +410,8 @@ __device__ __forceinline__ void spmm_wave_entries(float (&acc)[CH][VEC], int32_t
 {
     bool go = true;
     for (int j0 = 0; j0 < n && go; j0 += U) {
-        float v[U][CH][VEC], av[U];
+        raw_chunk<VEC, XT> v[U][CH];
+        float av[U];
 #pragma unroll
         for (int t = 0; t < U; ++t) {
             const int jj = __builtin_amdgcn_readfirstlane(min(j0 + t, n - 1));
@@ -395,7 +420,7 @@ __device__ __forceinline__ void spmm_wave_entries(float (&acc)[CH][VEC], int32_t
 #pragma unroll
             for (int m = 0; m < CH; ++m) {
                 const int col = (m * 64 + lane) * VEC;
-                if (col < d) vload<VEC>(v[t][m], x + col);
+                if (col < d) raw_load<VEC>(v[t][m], x + col);
             }
         }
 #pragma unroll
@@ -408,7 +433,7 @@ __device__ __forceinline__ void spmm_wave_entries(float (&acc)[CH][VEC], int32_t
                         const int col = (m * 64 + lane) * VEC;
                         if (col < d) {
 #pragma unroll
-                            for (int i = 0; i < VEC; ++i) acc[m][i] = fmaf(av[t], v[t][m][i], acc[m][i]);
+                            for (int i = 0; i < VEC; ++i) acc[m][i] = fmaf(av[t], raw_get<VEC>(v[t][m], i), acc[m][i]);
                         }
                     }
                 }
