@@ -13,7 +13,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libsgnn.so")
+_LIB_PATH = os.environ.get("SGNN_LIB_PATH") or os.path.join(_HERE, "libsgnn.so")   # the override is for trying out builds
 
 SGNN_RELU = 1
 SGNN_BF16_MFMA = 2

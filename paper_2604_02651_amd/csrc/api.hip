@@ -12,7 +12,7 @@
 size_t sgnn_sampler_persist_bytes();
 int sgnn_static_scratch_init(int device);
 size_t sgnn_sampler_ws_bytes(uint64_t N);
-size_t sgnn_induced_ws_bytes(uint64_t E, uint32_t B);
+size_t sgnn_induced_ws_bytes(uint64_t N, uint64_t E, uint32_t B);
 size_t sgnn_gemm_ws_bytes(uint32_t d_max);
 size_t sgnn_spmm_ws_bytes(uint64_t max_entries, uint32_t B, uint32_t d_max);
 
@@ -129,7 +129,7 @@ int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t
     int rc = bind_device(ctx);
     if (rc) return rc;
     size_t need = sgnn_sampler_ws_bytes(N);
-    need = std::max(need, sgnn_induced_ws_bytes(E, B));
+    need = std::max(need, sgnn_induced_ws_bytes(N, E, B));
     // backward: dZ and dT (B x d_max each), split-K partials, column-sum partials
     // Products whose kernel does not handle bfloat16 storage itself (fewer than 4096 rows, or wider than 256) go through
     // widened / narrowed fp32 copies: three more B x d_max matrices for those shapes.

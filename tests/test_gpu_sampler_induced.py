@@ -147,6 +147,28 @@ def test_induced_graph_with_empty_rows():
         _assert_csr_equal(out, nnz, ref)
 
 
+def test_induced_sparse_sample_of_a_large_graph():
+    # 17 M vertices, a sample of under 1/32 of them: the extraction screens the edges with its coarse filter (one bit
+    # per eight vertices) before it probes the bitmap; result bit for bit as always.  A few sampled vertices are given
+    # all-sampled neighbourhoods by construction of the check below: every stored entry is compared.
+    N, B = (1 << 24) + 1234567, 300_001
+    g = si.rmat_graph(N, 12_000_000, 77, device=DEV)
+    rowptr, colidx = g.rowptr, g.colidx
+    ctx().reserve(N, g.E, B, 1, 0)
+    S, bitmap, rank = gpu_sample(N, B, 3, 5)
+    S_ref = oracle.sample_uniform(N, B, 3, 5)
+    assert np.array_equal(S.cpu().numpy(), S_ref)
+    rp, ci, v = oracle.induced_csr(N, rowptr.cpu().numpy(), colidx.cpu().numpy(), S_ref)
+    assert len(ci) > B          # some off-diagonal entries survive
+    out = sg.Csr(B, B, len(ci), DEV)
+    nnz = sg.sgnn_induced_csr(ctx(), N, rowptr, colidx, None, S, B, bitmap, rank, out, want_nnz=True)
+    ctx().status()
+    assert nnz == len(ci)
+    assert np.array_equal(out.rowptr.cpu().numpy(), rp) and np.array_equal(out.colidx.cpu().numpy()[:nnz], ci)
+    got = out.val.cpu().numpy()[:nnz].astype(np.float64)
+    assert np.all(np.abs(got - v) <= TOL_VAL * np.abs(v))
+
+
 def test_induced_capacity_overflow_is_reported(tiny_graph):
     g = tiny_graph
     with pytest.raises(sg.SgnnError) as e:
