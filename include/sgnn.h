@@ -222,8 +222,9 @@ typedef struct {
     void *ptr;
     int dtype; /* SGNN_F32; SGNN_BF16 (bfloat16 storage, round to nearest even, ld in elements) only where a call
                 * says so: the operand and the result of a sparse product (X and out of sgnn_spmm) and, with
-                * SGNN_BF16_MFMA, the activations of a layer (H, T, Y of sgnn_gcn_fwd; T, Y, H_in of sgnn_gcn_bwd).
-                * Gradients, weights and the logits handed to the loss are always fp32. */
+                * SGNN_BF16_MFMA, the activations of a layer (H, T, Y of sgnn_gcn_fwd; T, Y, H_in of sgnn_gcn_bwd) and the
+                * gradient handed from one layer to the one below (dH, dY of sgnn_gcn_bwd).  Weights, their gradients,
+                * the logits handed to the loss and the loss gradient are always fp32. */
     int64_t rows, cols, ld;
     const int32_t *row_index;
 } sgnn_mat;
@@ -261,11 +262,15 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
  * One GCN layer backward (Sec. III-C): dZ = dY where Y > 0 (all of dY without SGNN_RELU or with SGNN_DY_MASKED),
  * dbias = column sums of dZ, dW = T^T dZ, dT = dZ W^T, dH = A_T dT.
  *   A_T   the transpose of the forward matrix as CSR (the same object when it is symmetric)
- *   T, W, Y   as in the forward call (T and Y in the storage they were written in);  dY  B x d_out fp32
+ *   T, W, Y   as in the forward call (T and Y in the storage they were written in);  dY  B x d_out fp32, or
+ *             bfloat16 where only the dense products read it: an aggregate-first layer whose mask dY already
+ *             carries (SGNN_DY_MASKED, or no SGNN_RELU), with dW wherever dbias is asked for (the bias gradient
+ *             is then the sum of the stored, rounded values); anything else with a bfloat16 dY is SGNN_ERR_UNSUPPORTED
  *             with SGNN_XFORM_FIRST (same flag as in the forward call) T is the layer INPUT H
  *             (B x d_in, row_index honoured) and the products are dP = A_T dZ, dW = H^T dP,
  *             dH = dP W^T
- *   dH    out B x d_in fp32, or NULL to skip it (first layer)
+ *   dH    out B x d_in fp32 or bfloat16 (rounded to nearest even when stored: what the dense products of the
+ *         layer below would round it to anyway), or NULL to skip it (first layer)
  *   H_in  optional (NULL = none; needs dH): the layer's input activations, B x d_in fp32 or bfloat16, the
  *         output of the ReLU of the layer below.  dH is then returned already multiplied by [H_in > 0],
  *         i.e. with that layer's ReLU backward fused into the product that writes dH; call that
@@ -389,7 +394,7 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_ma
               sgnn_stream stream);
 
 /*
- * C = act(op(A) op(B) + bias): row-major, M x N result, reduction length K.  B and bias are fp32; A, C and the
+ * C = act(op(A) op(B) + bias): row-major, M x N result, reduction length K.  bias is fp32; A, B, C and the
  * mask are fp32 (SGNN_F32) or - with SGNN_BF16_MFMA - stored as bfloat16 (SGNN_BF16, leading dimension in elements).
  *   trans_a 0: A is M x K;  1: A is K x M (used as its transpose)
  *   trans_b 0: B is K x N;  1: B is N x K (used as its transpose)
@@ -402,9 +407,9 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_ma
  *             the operand the product reads anyway.  NULL = not wanted.
  */
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
-              const void *A, int a_dtype, int64_t lda, const float *B, int64_t ldb, const float *bias,
-              int flags, void *C, int c_dtype, int64_t ldc, const void *mask, int mask_dtype, int64_t ldm,
-              float *b_colsum, sgnn_stream stream);
+              const void *A, int a_dtype, int64_t lda, const void *B, int b_dtype, int64_t ldb,
+              const float *bias, int flags, void *C, int c_dtype, int64_t ldc, const void *mask, int mask_dtype,
+              int64_t ldm, float *b_colsum, sgnn_stream stream);
 
 /*
  * dst[0..n) = src[0..n) (fp32, 16-byte aligned, n a multiple of 4): a plain streaming copy of known

@@ -395,7 +395,10 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
     taken for the configuration whose features and activations are bfloat16): they are rounded to
     nearest even once, after the activation, and everything downstream - the next aggregation, the
     ReLU mask - sees the stored value.  The aggregates T_l are GEMM operands and are rounded by
-    bf16=True already; the logits H_L and all gradients stay unrounded.
+    bf16=True already; the logits H_L stay unrounded.  The gradient dH_l handed from layer l to layer
+    l-1 is stored as bfloat16 too: the dense products of layer l-1 round it anyway, so the one thing
+    that changes is that layer's bias gradient, which becomes the column sum of the rounded values.
+    The loss gradient and the gradients inside a layer stay unrounded.
 
     dO_ties, logit_band: the loss gradient has the same kind of undecidable set as the ReLU mask.
     Rows of the logits for which undecidable_loss_rows(H_L, y, logit_band) holds form the returned
@@ -429,6 +432,8 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
     for l in range(L - 1, -1, -1):
         W, b = weights[l]
         relu = l < L - 1
+        if store_bf16 and l < L - 1:
+            dY = round_bf16(dY)            # dH_{l+1} as stored (the ReLU mask is 0 / 1: rounding before or after it is the same)
         Ymask = masks[l].astype(np.float64) if relu else Hs[l + 1]     # gcn_bwd only tests Y > 0
         dH, dW, db = gcn_bwd(rpT, ciT, vT, Ts[l], W, Ymask, dY, relu=relu, bf16=bf16, need_dH=(l > 0))
         dWs[l], dbs[l], dHs[l] = dW, db, dH

@@ -102,7 +102,7 @@ def lib():
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
-        L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, ci, i64, vp, i64, vp, ci, vp, ci, i64, vp, ci, i64, vp, vp]
+        L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, ci, i64, vp, ci, i64, vp, ci, vp, ci, i64, vp, ci, i64, vp, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
                      "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_gemm_tail_fwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose", "sgnn_sigmoid_bce", "sgnn_colsum",
@@ -358,9 +358,9 @@ def sgnn_gcn_bwd(ctx: Context, A_T: Csr, T: torch.Tensor, W: torch.Tensor, Y: Op
     """T is the saved aggregate, or with SGNN_XFORM_FIRST the layer input (row_index honoured).
     H_in (the layer input, output of the ReLU below): dH comes back multiplied by [H_in > 0]."""
     a = A_T.struct()
-    t, w, dy = _mat(T, row_index, "T", allow_bf16=True), _mat(W, None, "W"), _mat(dY, None, "dY")
+    t, w, dy = _mat(T, row_index, "T", allow_bf16=True), _mat(W, None, "W"), _mat(dY, None, "dY", allow_bf16=True)
     y = _mat(Y, None, "Y", allow_bf16=True) if Y is not None else None
-    dh = _mat(dH, None, "dH") if dH is not None else None
+    dh = _mat(dH, None, "dH", allow_bf16=True) if dH is not None else None
     hin = _mat(H_in, None, "H_in", allow_bf16=True) if H_in is not None else None
     if dW is not None and (dW.shape != W.shape or not dW.is_contiguous()):
         raise ValueError("dW must be contiguous with the shape of W")
@@ -472,13 +472,13 @@ def sgnn_gemm(ctx: Context, trans_a: bool, trans_b: bool, A: torch.Tensor, B: to
               flags: int, Cm: torch.Tensor, stream=None, b_colsum: Optional[torch.Tensor] = None,
               mask: Optional[torch.Tensor] = None):
     """C = act(op(A) op(B) + bias), zero where mask <= 0 (mask: a matrix shaped like C); b_colsum: column sums of B.
-    A, C and the mask may be bfloat16 tensors (with SGNN_BF16_MFMA)."""
+    A, B, C and the mask may be bfloat16 tensors (with SGNN_BF16_MFMA)."""
     M, N = Cm.shape
     if mask is not None and tuple(mask.shape) != (M, N):
         raise ValueError("mask must have the shape of C")
     K = A.shape[0] if trans_a else A.shape[1]
     ctx.check(lib().sgnn_gemm(ctx._h, int(trans_a), int(trans_b), M, N, K, _ptr(A, None, "A"), _dt(A, "A"), A.stride(0),
-                              _ptr(B, torch.float32, "B"), B.stride(0), _ptr(bias, torch.float32, "bias"), flags,
+                              _ptr(B, None, "B"), _dt(B, "B"), B.stride(0), _ptr(bias, torch.float32, "bias"), flags,
                               _ptr(Cm, None, "C"), _dt(Cm, "C"), Cm.stride(0), _ptr(mask, None, "mask"), _dt(mask, "mask"),
                               mask.stride(0) if mask is not None else 0, _ptr(b_colsum, torch.float32, "b_colsum"),
                               _stream(stream)))

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsgnn.so")
-SOURCES = ["api.hip", "scan.hip", "sampler.hip", "induced.hip", "spmm.hip", "gemm.hip", "elementwise.hip", "tail.hip", "transpose.hip"]
+SOURCES = ["api.hip", "scan.hip", "sampler.hip", "induced.hip", "spmm.hip", "gemm.hip", "gemm_tn.hip", "elementwise.hip", "tail.hip", "transpose.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I" + CSRC, "-I" + INCLUDE]
 

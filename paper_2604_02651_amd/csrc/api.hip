@@ -134,7 +134,7 @@ int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t
     // Products whose kernel does not handle bfloat16 storage itself (fewer than 4096 rows, or wider than 256) go through
     // widened / narrowed fp32 copies: three more B x d_max matrices for those shapes.
     const size_t copies = (B < 4096 || d_max > 256) ? 5 : 2;
-    size_t layer = copies * B * pad4(d_max) * 4 + 5 * 256 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 +
+    size_t layer = copies * B * (((size_t)d_max + 7) & ~size_t(7)) * 4 + 5 * 256 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 +
                    sgnn_spmm_ws_bytes(max_entries, B, d_max) + 16 * 256;
     need = std::max(need, layer);
     need = std::max(need, sgnn_transpose_ws_bytes(max_entries, B));
@@ -344,24 +344,25 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_ma
 }
 
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int a_dtype, int64_t lda,
-              const float *B, int64_t ldb, const float *bias, int flags, void *C, int c_dtype, int64_t ldc, const void *mask,
-              int mask_dtype, int64_t ldm, float *b_colsum, sgnn_stream stream)
+              const void *B, int b_dtype, int64_t ldb, const float *bias, int flags, void *C, int c_dtype, int64_t ldc,
+              const void *mask, int mask_dtype, int64_t ldm, float *b_colsum, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
     if (!A || !B || !C || M < 0 || N < 0 || K < 0) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: bad argument");
-    if ((a_dtype != SGNN_F32 && a_dtype != SGNN_BF16) || (c_dtype != SGNN_F32 && c_dtype != SGNN_BF16) ||
+    if ((a_dtype != SGNN_F32 && a_dtype != SGNN_BF16) || (b_dtype != SGNN_F32 && b_dtype != SGNN_BF16) ||
+        (c_dtype != SGNN_F32 && c_dtype != SGNN_BF16) ||
         (mask && mask_dtype != SGNN_F32 && mask_dtype != SGNN_BF16))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: unknown storage type");
-    if ((a_dtype == SGNN_BF16 || c_dtype == SGNN_BF16) && !(flags & SGNN_BF16_MFMA))
-        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gemm: bfloat16 storage of A or C goes with SGNN_BF16_MFMA only");
+    if ((a_dtype == SGNN_BF16 || b_dtype == SGNN_BF16 || c_dtype == SGNN_BF16) && !(flags & SGNN_BF16_MFMA))
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gemm: bfloat16 storage of A, B or C goes with SGNN_BF16_MFMA only");
     if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N || (mask && ldm < N))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: leading dimension too small");
     if (M == 0 || N == 0) return SGNN_OK;
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_gemm_x(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, a_dtype == SGNN_BF16, lda, nullptr, B, ldb, bias, flags,
-                              C, c_dtype == SGNN_BF16, ldc, mask, mask && mask_dtype == SGNN_BF16, mask ? ldm : 0, b_colsum, &ws,
+    return sgnn_launch_gemm_x(ctx, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, a_dtype == SGNN_BF16, lda, nullptr, B,
+                              b_dtype == SGNN_BF16, ldb, bias, flags, C, c_dtype == SGNN_BF16, ldc, mask, mask && mask_dtype == SGNN_BF16, mask ? ldm : 0, b_colsum, &ws,
                               static_cast<hipStream_t>(stream));
 }
 
@@ -391,19 +392,19 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
         rc = sgnn_launch_spmm_x(ctx, A, H->ptr, h16, H->ld, H->row_index, d_in, T->ptr, t16, T->ld, nullptr, 0, nullptr, 0, 0, nullptr,
                                 0, &ws, st);
         if (rc) return rc;
-        return sgnn_launch_gemm_x(ctx, 0, 0, Bn, d_out, d_in, T->ptr, t16, T->ld, nullptr, static_cast<const float *>(W->ptr), W->ld,
-                                  bias, gflags, Y->ptr, y16, Y->ld, nullptr, 0, 0, nullptr, &ws, st);
+        return sgnn_launch_gemm_x(ctx, 0, 0, Bn, d_out, d_in, T->ptr, t16, T->ld, nullptr, W->ptr, 0, W->ld, bias, gflags, Y->ptr, y16,
+                                  Y->ld, nullptr, 0, 0, nullptr, &ws, st);
     }
     // A (H W): transform first (the aggregation then runs at width d_out), bias and activation
     // fused into the sparse product
     // The product H W lives in scratch; with the layer's input stored as bfloat16 it is stored as bfloat16 too (the
     // activations of such a stack are 16-bit between all of its kernels).
-    const int64_t ldp = pad4(d_out);   // rows of the scratch matrices start 16-byte aligned (8-byte for 16-bit elements)
+    const int64_t ldp = (d_out + 7) & ~int64_t(7);   // rows of the scratch matrix start 16-byte aligned, in fp32 and in 16-bit elements
     const bool p16 = h16;
     float *P = ws.get<float>(p16 ? ((size_t)A->cols * ldp + 1) / 2 : (size_t)A->cols * ldp);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_fwd: scratch too small: call sgnn_ctx_reserve");
-    rc = sgnn_launch_gemm_x(ctx, 0, 0, A->cols, d_out, d_in, H->ptr, h16, H->ld, H->row_index, static_cast<const float *>(W->ptr), W->ld,
-                            nullptr, flags & SGNN_BF16_MFMA, P, p16, ldp, nullptr, 0, 0, nullptr, &ws, st);
+    rc = sgnn_launch_gemm_x(ctx, 0, 0, A->cols, d_out, d_in, H->ptr, h16, H->ld, H->row_index, W->ptr, 0, W->ld, nullptr,
+                            flags & SGNN_BF16_MFMA, P, p16, ldp, nullptr, 0, 0, nullptr, &ws, st);
     if (rc) return rc;
     return sgnn_launch_spmm_x(ctx, A, P, p16, ldp, nullptr, d_out, Y->ptr, y16, Y->ld, bias, (flags & SGNN_RELU) ? 1 : 0, nullptr, 0, 0,
                               nullptr, 0, &ws, st);
@@ -414,11 +415,11 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
                  sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
-    if (!csr_ok(A_T) || !mat_ok_in(T) || !mat_ok(W) || !mat_ok(dY) || (dH && !mat_ok(dH)))
+    if (!csr_ok(A_T) || !mat_ok_in(T) || !mat_ok(W) || !mat_ok_in(dY) || (dH && !mat_ok_in(dH)))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gcn_bwd: bad argument");
-    const bool t16 = T->dtype == SGNN_BF16;
-    if (t16 && !(flags & SGNN_BF16_MFMA))
-        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gcn_bwd: a saved matrix stored as bfloat16 goes with SGNN_BF16_MFMA only");
+    const bool t16 = T->dtype == SGNN_BF16, dy16 = dY->dtype == SGNN_BF16, dh16 = dH && dH->dtype == SGNN_BF16;
+    if ((t16 || dy16 || dh16) && !(flags & SGNN_BF16_MFMA))
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gcn_bwd: bfloat16 storage of T, dY or dH goes with SGNN_BF16_MFMA only");
     const int relu = (flags & SGNN_RELU) ? 1 : 0;
     const bool xform_first = (flags & SGNN_XFORM_FIRST) != 0;
     const bool dy_masked = (flags & SGNN_DY_MASKED) != 0;   // the caller's dY already carries this layer's ReLU mask
@@ -437,12 +438,18 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     hipStream_t st = static_cast<hipStream_t>(stream);
     ws_alloc ws(ctx);
     const int mfma = flags & SGNN_BF16_MFMA;
-    const int64_t ld_out = pad4(d_out), ld_in = pad4(d_in);   // rows of the scratch matrices start 16-byte aligned
+    // rows of the scratch matrices start 16-byte aligned (a multiple of 8 elements also serves the 16-bit ones)
+    const int64_t ld_out = (d_out + 7) & ~int64_t(7), ld_in = (d_in + 7) & ~int64_t(7);
 
     // element-wise backward: ReLU mask and bias gradient
-    const float *dZ = static_cast<const float *>(dY->ptr);
+    const void *dZ = dY->ptr;
+    int dz16 = dy16 ? 1 : 0;
     int64_t lddz = dY->ld;
     const int mask_here = relu && !dy_masked;
+    if (dy16 && (mask_here || xform_first || (dbias && !dW)))
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gcn_bwd: a bfloat16 dY is read by the dense products only: it needs an "
+                                                    "aggregate-first layer whose ReLU mask it already carries (SGNN_DY_MASKED, or no "
+                                                    "SGNN_RELU), and dW wherever dbias is asked for");
     const void *hmask = H_in ? H_in->ptr : nullptr;
     const int64_t ldhm = H_in ? H_in->ld : 0;
     const int hm16 = (H_in && H_in->dtype == SGNN_BF16) ? 1 : 0;
@@ -458,41 +465,44 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
                                        mask_here ? Y->ld : 0, static_cast<const float *>(dY->ptr), dY->ld, mask_here, Bn, d_out, dZbuf,
                                        ld_out, dbias, &ws, st);
         if (rc) return rc;
-        if (mask_here) { dZ = dZbuf; lddz = ld_out; }
+        if (mask_here) { dZ = dZbuf; lddz = ld_out; dz16 = 0; }
     }
     if (!xform_first) {
         // dW = T^T dZ
         if (dW) {
-            rc = sgnn_launch_gemm_x(ctx, 1, 0, d_in, d_out, Bn, T->ptr, t16, T->ld, nullptr, dZ, lddz, nullptr, mfma, dW, 0, d_out, nullptr,
-                                    0, 0, db_in_gemm ? dbias : nullptr, &ws, st);
+            rc = sgnn_launch_gemm_x(ctx, 1, 0, d_in, d_out, Bn, T->ptr, t16, T->ld, nullptr, dZ, dz16, lddz, nullptr, mfma, dW, 0, d_out,
+                                    nullptr, 0, 0, db_in_gemm ? dbias : nullptr, &ws, st);
             if (rc) return rc;
         }
         if (dH) {
             // dT = dZ W^T, dH = A^T dT
             float *dT = ws.get<float>((size_t)Bn * ld_in);
             if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
-            rc = sgnn_launch_gemm(ctx, 0, 1, Bn, d_in, d_out, dZ, lddz, nullptr, static_cast<const float *>(W->ptr), W->ld,
-                                  nullptr, mfma, dT, ld_in, nullptr, 0, nullptr, &ws, st);
+            rc = sgnn_launch_gemm_x(ctx, 0, 1, Bn, d_in, d_out, dZ, dz16, lddz, nullptr, W->ptr, 0, W->ld, nullptr, mfma, dT, 0, ld_in,
+                                    nullptr, 0, 0, nullptr, &ws, st);
             if (rc) return rc;
-            rc = sgnn_launch_spmm_x(ctx, A_T, dT, 0, ld_in, nullptr, d_in, dH->ptr, 0, dH->ld, nullptr, 0, hmask, hm16, ldhm, nullptr, 0,
-                                    &ws, st);
+            rc = sgnn_launch_spmm_x(ctx, A_T, dT, 0, ld_in, nullptr, d_in, dH->ptr, dh16, dH->ld, nullptr, 0, hmask, hm16, ldhm, nullptr,
+                                    0, &ws, st);
             if (rc) return rc;
         }
         return SGNN_OK;
     }
-    // transform-first layer: dP = A^T dZ (width d_out), dW = H^T dP, dH = dP W^T; T is the layer input H
-    float *dP = ws.get<float>((size_t)Bn * ld_out);
+    // transform-first layer: dP = A^T dZ (width d_out), dW = H^T dP, dH = dP W^T; T is the layer input H.
+    // dP is read by those two dense products only: with the layer's input stored as bfloat16 it is stored as bfloat16 as
+    // well (the value the products would round it to), which halves its traffic and lets dW take the streaming kernel.
+    const bool p16 = t16;
+    float *dP = ws.get<float>(p16 ? ((size_t)Bn * ld_out + 1) / 2 : (size_t)Bn * ld_out);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
-    rc = sgnn_launch_spmm(ctx, A_T, dZ, 0, lddz, nullptr, d_out, dP, ld_out, nullptr, 0, nullptr, 0, nullptr, 0, &ws, st);
+    rc = sgnn_launch_spmm_x(ctx, A_T, dZ, 0, lddz, nullptr, d_out, dP, p16, ld_out, nullptr, 0, nullptr, 0, 0, nullptr, 0, &ws, st);   // dZ is fp32 here
     if (rc) return rc;
     if (dW) {
-        rc = sgnn_launch_gemm_x(ctx, 1, 0, d_in, d_out, Bn, T->ptr, t16, T->ld, T->row_index, dP, ld_out, nullptr, mfma, dW, 0, d_out,
+        rc = sgnn_launch_gemm_x(ctx, 1, 0, d_in, d_out, Bn, T->ptr, t16, T->ld, T->row_index, dP, p16, ld_out, nullptr, mfma, dW, 0, d_out,
                                 nullptr, 0, 0, nullptr, &ws, st);
         if (rc) return rc;
     }
     if (dH)
-        rc = sgnn_launch_gemm_x(ctx, 0, 1, Bn, d_in, d_out, dP, 0, ld_out, nullptr, static_cast<const float *>(W->ptr), W->ld, nullptr,
-                                mfma, dH->ptr, 0, dH->ld, hmask, hm16, ldhm, nullptr, &ws, st);
+        rc = sgnn_launch_gemm_x(ctx, 0, 1, Bn, d_in, d_out, dP, p16, ld_out, nullptr, W->ptr, 0, W->ld, nullptr, mfma, dH->ptr, dh16, dH->ld,
+                                hmask, hm16, ldhm, nullptr, &ws, st);
     return rc;
 }
 

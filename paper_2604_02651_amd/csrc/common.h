@@ -117,11 +117,17 @@ int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_
                      int64_t lda, const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias,
                      int flags, float *C, int64_t ldc, const float *mask, int64_t ldm, float *b_colsum, ws_alloc *ws,
                      hipStream_t st);
-// The same with A, C and the mask optionally stored as bfloat16 (a_bf16 / c_bf16 / m_bf16; leading dimensions in
+// The same with A, B, C and the mask optionally stored as bfloat16 (a_bf16 / b_bf16 / c_bf16 / m_bf16; leading dimensions in
 // elements; needs SGNN_BF16_MFMA): read and written as stored by the kernels that can, converted through scratch for the others.
 int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const void *A, int a_bf16, int64_t lda,
-                       const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias, int flags, void *C, int c_bf16,
-                       int64_t ldc, const void *mask, int m_bf16, int64_t ldm, float *b_colsum, ws_alloc *ws, hipStream_t st);
+                       const int32_t *a_row_index, const void *B, int b_bf16, int64_t ldb, const float *bias, int flags, void *C,
+                       int c_bf16, int64_t ldc, const void *mask, int m_bf16, int64_t ldm, float *b_colsum, ws_alloc *ws,
+                       hipStream_t st);
+int sgnn_launch_splitk_reduce(sgnn_ctx *ctx, const float *partial, int splits, int64_t M, int64_t N, float *C, int64_t ldc,
+                              const float *cs_partial, float *cs_out, hipStream_t st);
+// A^T B, both operands bfloat16, result up to 256 x 256, long reduction: SGNN_ERR_UNSUPPORTED (nothing launched) outside its range
+int sgnn_launch_gemm_tn_stream(sgnn_ctx *ctx, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                               float *C, int64_t ldc, float *b_colsum, ws_alloc *ws, hipStream_t st);
 int sgnn_launch_gemm_tail(sgnn_ctx *ctx, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *W,
                           int64_t ldw, const float *gamma, float eps, const float *R, int64_t ldr, float q, uint64_t seed,
                           uint32_t layer, uint64_t step, float *Z, int64_t ldz, float *Y, int64_t ldy, float *inv_rms,

@@ -50,6 +50,7 @@ struct gemm_args {
     float *partial;           // split-K: [splits][M][N] partial products, else NULL
     uint32_t mtiles, ntiles, splits;   // the tile grid, walked by tile_of_block()
     float *colsum;            // optional (A^T B products): column sums of B; [splits][N] partial sums when split
+    int b_bf16;                   // B is stored as bfloat16 (A^T B on the chunked tile kernel only)
     int a_bf16, c_bf16, m_bf16;   // A / C / the mask are stored as bfloat16 (16-bit patterns; leading dimensions in elements).
                                   // Only the kernels that say so look at these; the launcher converts for the others.
     int vecM;                     // the mask can be read in chunks of four elements (aligned, N and ldm multiples of 4)
@@ -627,7 +628,7 @@ __device__ __forceinline__ void store_tile(const gemm_args &a, const f32x16 (&ac
 // buffer s & 1; the registers are stored to the other buffer after the multiply, so there is one
 // barrier per slice.
 // ABF: A is stored as bfloat16 (the saved aggregate of a layer whose activations are kept in bfloat16).
-template <int BM, int BN, int WM, int WN, bool TA, bool TB, bool BF16, bool ABF = false>
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, bool BF16, bool ABF = false, bool BBF = false>
 __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
 {
     constexpr int BK = 32;
@@ -665,9 +666,12 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
     typename std::conditional<ABF, uint2, f32x4>::type *ra_fetch;      // where the fetch puts A: ra itself, or the raw 16-bit chunks
     uint2 ra16[ABF ? gA::NV : 1];
     if constexpr (ABF) ra_fetch = ra16; else ra_fetch = ra;
+    typename std::conditional<BBF, uint2, f32x4>::type *rb_fetch;
+    uint2 rb16[BBF ? gB::NV : 1];
+    if constexpr (BBF) rb_fetch = rb16; else rb_fetch = rb;
     auto fetch = [&](int s) {
         fetch_fast<BM, BK, A_RC, ABF>(ra_fetch, a.A, a.lda, m0, a.M, kbeg + (int64_t)s * BK, kend, a.K, a.a_row_index);
-        fetch_fast<BN, BK, B_RC>(rb, a.B, a.ldb, n0, a.N, kbeg + (int64_t)s * BK, kend, a.K);
+        fetch_fast<BN, BK, B_RC, BBF>(rb_fetch, a.B, a.ldb, n0, a.N, kbeg + (int64_t)s * BK, kend, a.K);
     };
     // column sums of B (the bias gradient next to dW = T^T dZ): every thread fetches the same four columns
     // of B in every slice, so it adds its chunks up as they pass; only the first row block of tiles does it
@@ -675,6 +679,7 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(gemm_args a)
     const bool do_cs = TA && !TB && a.colsum && tb_.bx == 0;
     auto stage = [&](int s) {
         if constexpr (ABF) widen_fast<BM, BK, A_RC>(ra, ra16);
+        if constexpr (BBF) widen_fast<BN, BK, B_RC>(rb, rb16);
         mask_fast<BM, BK, A_RC>(ra, kbeg + (int64_t)s * BK, kend);
         mask_fast<BN, BK, B_RC>(rb, kbeg + (int64_t)s * BK, kend);
         if constexpr (TA && !TB) {
@@ -1390,7 +1395,18 @@ int launch_skinny_ns(sgnn_ctx *ctx, const gemm_args &a, int tb, const skinny_tai
              (long long)a.N, (long long)a.K, a.a_bf16 ? 2 : 4, a.c_bf16 ? 2 : 4, a.mask ? (a.m_bf16 ? " mask m=2" : " mask m=4") : "");
     const dim3 grid(std::min<uint32_t>(n_rowblocks, 256)), block(64 * SKINNY_WAVES);
     if constexpr (!TAIL) {
-        if (a.a_bf16) {       // the launcher sends a bfloat16 A here only without a chunked mask
+        if (a.a_bf16 && vmask) {
+            static bool attr16m = false;
+            if (!attr16m) {
+                SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny_bf16_kernel<NT8, S, false, true, true>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+                attr16m = true;
+            }
+            SGNN_LAUNCH(ctx, st, "gemm_skinny_bf16_kernel", tag, (gemm_skinny_bf16_kernel<NT8, S, false, true, true>), grid, block, lds,
+                        st, a, tb, n_rowblocks, tl);
+            return SGNN_OK;
+        }
+        if (a.a_bf16) {
             static bool attr16 = false;
             if (!attr16) {
                 SGNN_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny_bf16_kernel<NT8, S, false, false, true>),
@@ -1689,14 +1705,19 @@ int launch_cfg(sgnn_ctx *ctx, int ta, int tb, int bf16, gemm_args a, int splits,
                       a.K >= 1 && a.M >= 1 && a.N >= 1;
     if (fast && !(ta && tb)) {
         snprintf(tag, sizeof(tag), "%c%c %dx%d %lldx%lldx%lld %s%s", ta ? 'T' : 'N', tb ? 'T' : 'N', BM, BN, (long long)a.M,
-                 (long long)a.N, (long long)a.K, bf16 ? "bf16" : "f32", a.a_bf16 ? " a=2" : "");
+                 (long long)a.N, (long long)a.K, bf16 ? "bf16" : "f32", a.a_bf16 ? (a.b_bf16 ? " a=2 b=2" : " a=2") : (a.b_bf16 ? " b=2" : ""));
 #define SGNN_GEMM_FAST(TA_, TB_, BF_)                                                                              \
     if (ta == TA_ && tb == TB_ && bf16 == BF_) {                                                                   \
         SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, TA_, TB_, BF_>), grid, block, 0, st, a); \
         return SGNN_OK;                                                                                            \
     }
-        if (a.a_bf16) {      // the launcher sends only A^T B with bf16 operands here in this storage
-            SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, true, false, true, true>), grid, block, 0, st, a);
+        if (a.a_bf16 || a.b_bf16) {      // the launcher sends only A^T B with bf16 operands here in this storage
+            if (a.a_bf16 && a.b_bf16)
+                SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, true, false, true, true, true>), grid, block, 0, st, a);
+            else if (a.a_bf16)
+                SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, true, false, true, true, false>), grid, block, 0, st, a);
+            else
+                SGNN_LAUNCH(ctx, st, "gemm_kernel", tag, (gemm_fast_kernel<BM, BN, WM, WN, true, false, true, false, true>), grid, block, 0, st, a);
             return SGNN_OK;
         }
         SGNN_GEMM_FAST(false, false, false)
@@ -1754,31 +1775,51 @@ size_t sgnn_gemm_ws_bytes(uint32_t d_max) { return (size_t)256 * d_max * d_max *
 
 static inline int64_t gemm_pad4(int64_t d) { return (d + 3) & ~int64_t(3); }
 
+// C = sum of `splits` partial products [splits][M][N] in a fixed order; cs_out = the same for [splits][N] column sums.
+int sgnn_launch_splitk_reduce(sgnn_ctx *ctx, const float *partial, int splits, int64_t M, int64_t N, float *C, int64_t ldc,
+                              const float *cs_partial, float *cs_out, hipStream_t st)
+{
+    SGNN_LAUNCH(ctx, st, "splitk_reduce_kernel", SGNN_TAG, splitk_reduce_kernel, dim3(cdiv(M * N + (cs_partial ? N : 0), 256)), dim3(256),
+                0, st, partial, splits, M * N, N, C, ldc, cs_partial, cs_out);
+    return SGNN_OK;
+}
+
 int sgnn_launch_gemm(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
                      const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias, int flags, float *C,
                      int64_t ldc, const float *mask, int64_t ldm, float *b_colsum, ws_alloc *ws, hipStream_t st)
 {
-    return sgnn_launch_gemm_x(ctx, ta, tb, M, N, K, A, 0, lda, a_row_index, B, ldb, bias, flags, C, 0, ldc, mask, 0, ldm, b_colsum, ws,
+    return sgnn_launch_gemm_x(ctx, ta, tb, M, N, K, A, 0, lda, a_row_index, B, 0, ldb, bias, flags, C, 0, ldc, mask, 0, ldm, b_colsum, ws,
                               st);
 }
 
 int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int64_t K, const void *Av, int a_bf16, int64_t lda,
-                       const int32_t *a_row_index, const float *B, int64_t ldb, const float *bias, int flags, void *Cv, int c_bf16,
-                       int64_t ldc, const void *maskv, int m_bf16, int64_t ldm, float *b_colsum, ws_alloc *ws, hipStream_t st)
+                       const int32_t *a_row_index, const void *Bv, int b_bf16, int64_t ldb, const float *bias, int flags, void *Cv,
+                       int c_bf16, int64_t ldc, const void *maskv, int m_bf16, int64_t ldm, float *b_colsum, ws_alloc *ws,
+                       hipStream_t st)
 {
     const int bf16 = (flags & SGNN_BF16_MFMA) ? 1 : 0;
-    if ((a_bf16 || c_bf16) && !bf16)
+    if ((a_bf16 || b_bf16 || c_bf16) && !bf16)
         return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gemm: bfloat16 storage of A or C goes with SGNN_BF16_MFMA only");
     if (!maskv) m_bf16 = 0;
-    // Which kernel reads or writes the 16-bit storage itself: the tall-operand kernel (A, C, the mask; A only without a
-    // chunked mask) and the chunked tile kernel for A^T B (A).  For everything else the operand is widened into scratch
+    // Which kernel reads or writes the 16-bit storage itself: the tall-operand kernel (A, C, the mask) and the chunked
+    // tile kernel for A^T B (A and B).  For everything else the operand is widened into scratch
     // first (exact), or the result narrowed from scratch afterwards (the same rounding the kernel would apply).
     const bool a_al16 = (reinterpret_cast<uintptr_t>(Av) & 7) == 0 && lda % 4 == 0;
-    const bool m_chunks = maskv && N % 4 == 0 && ldm % 4 == 0 && (reinterpret_cast<uintptr_t>(maskv) & (m_bf16 ? 7 : 15)) == 0;
     const bool skinny_shape = bf16 && !ta && K >= 1 && K <= 256 && N >= 1 && N <= 256 && M >= 4096;
-    const bool tn_fast16 = bf16 && ta && !tb && a_al16 && (reinterpret_cast<uintptr_t>(B) & 15) == 0 && ldb % 4 == 0 && M % 4 == 0 &&
-                           N % 4 == 0 && M >= 4 && N >= 4 && K >= 1;
-    const bool a_native = a_bf16 && ((skinny_shape && a_al16 && !m_chunks) || tn_fast16);
+    const bool a_al = a_bf16 ? a_al16 : ((reinterpret_cast<uintptr_t>(Av) & 15) == 0 && lda % 4 == 0);
+    const bool b_al = (reinterpret_cast<uintptr_t>(Bv) & (b_bf16 ? 7 : 15)) == 0 && ldb % 4 == 0;
+    const bool tn_fast16 = bf16 && ta && !tb && a_al && b_al && M % 4 == 0 && N % 4 == 0 && M >= 4 && N >= 4 && K >= 1;
+    const bool a_native = a_bf16 && ((skinny_shape && a_al16) || tn_fast16);
+    const float *B = static_cast<const float *>(Bv);
+    if (b_bf16 && !tn_fast16) {
+        const int64_t rows = tb ? N : K, cols = tb ? K : N, ldw = gemm_pad4(cols);
+        float *Bw = ws->get<float>((size_t)rows * ldw);
+        if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gemm: scratch too small to widen a bfloat16 operand: call sgnn_ctx_reserve");
+        if (rows * cols > 0)
+            SGNN_LAUNCH(ctx, st, "widen_bf16_kernel", SGNN_TAG, widen_bf16_kernel, dim3((unsigned)std::min<int64_t>(cdiv(rows * cols, 256), 65536)),
+                        dim3(256), 0, st, static_cast<const u16 *>(Bv), ldb, (const int32_t *)nullptr, rows, cols, Bw, ldw);
+        B = Bw; ldb = ldw; b_bf16 = 0;
+    }
     const bool cm_native = skinny_shape && (a_bf16 ? a_native : ((reinterpret_cast<uintptr_t>(Av) & 15) == 0 && lda % 4 == 0));
     const float *A = static_cast<const float *>(Av);
     if (a_bf16 && !a_native) {
@@ -1805,8 +1846,8 @@ int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int6
         const int64_t ldw = gemm_pad4(N);
         float *Cw = ws->get<float>((size_t)M * ldw);
         if (!ws->ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gemm: scratch too small for a bfloat16 result: call sgnn_ctx_reserve");
-        int rc = sgnn_launch_gemm_x(ctx, ta, tb, M, N, K, A, a_bf16, lda, a_row_index, B, ldb, bias, flags, Cw, 0, ldw, mask, m_bf16, ldm,
-                                    b_colsum, ws, st);
+        int rc = sgnn_launch_gemm_x(ctx, ta, tb, M, N, K, A, a_bf16, lda, a_row_index, B, b_bf16, ldb, bias, flags, Cw, 0, ldw, mask, m_bf16,
+                                    ldm, b_colsum, ws, st);
         if (rc) return rc;
         if (M * N > 0)
             SGNN_LAUNCH(ctx, st, "narrow_bf16_kernel", SGNN_TAG, narrow_bf16_kernel, dim3((unsigned)std::min<int64_t>(cdiv(M * N, 256), 65536)),
@@ -1820,10 +1861,10 @@ int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int6
     a.a_row_index = a_row_index;
     a.M = M; a.N = N; a.K = K;
     a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.bias = bias; a.C = C; a.ldc = ldc;
-    a.a_bf16 = a_bf16; a.c_bf16 = c_bf16; a.m_bf16 = m_bf16;
+    a.a_bf16 = a_bf16; a.b_bf16 = b_bf16; a.c_bf16 = c_bf16; a.m_bf16 = m_bf16;
     a.relu = (flags & SGNN_RELU) ? 1 : 0;
     a.alignedA = a_bf16 ? (a_al16 ? 1 : 0) : (((reinterpret_cast<uintptr_t>(A) & 15) == 0 && lda % 4 == 0) ? 1 : 0);
-    a.alignedB = ((reinterpret_cast<uintptr_t>(B) & 15) == 0 && ldb % 4 == 0) ? 1 : 0;
+    a.alignedB = b_bf16 ? 1 : (((reinterpret_cast<uintptr_t>(B) & 15) == 0 && ldb % 4 == 0) ? 1 : 0);     // a bfloat16 B got here through tn_fast16 only
     a.vecM = (mask && N % 4 == 0 && ldm % 4 == 0 && (reinterpret_cast<uintptr_t>(mask) & (m_bf16 ? 7 : 15)) == 0) ? 1 : 0;
     a.c_pair = (c_bf16 && N % 2 == 0 && ldc % 2 == 0 && (reinterpret_cast<uintptr_t>(C) & 3) == 0) ? 1 : 0;
     a.vecC = (!c_bf16 && !m_bf16 && (reinterpret_cast<uintptr_t>(C) & 15) == 0 && ldc % 4 == 0 && N % 4 == 0 &&
@@ -1837,6 +1878,13 @@ int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int6
     if (skinny_shape && a.alignedA) {
         if (b_colsum) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm: column sums of B go with A^T B only");
         return launch_skinny(ctx, a, tb, st);
+    }
+
+    // A^T B with both operands stored as bfloat16 and a result of up to 256 x 256 (the weight gradients of a stack whose
+    // activations and hand-down gradients are 16-bit): the streaming kernel, when it takes the shape
+    if (bf16 && ta && !tb && a_bf16 && b_bf16 && !a_row_index && !bias && !(flags & SGNN_RELU) && !mask) {
+        const int rc = sgnn_launch_gemm_tn_stream(ctx, M, N, K, A, lda, B, ldb, C, ldc, b_colsum, ws, st);
+        if (rc != SGNN_ERR_UNSUPPORTED) return rc;
     }
 
     // classifier-width products, fp32: straight from global memory into the MFMA operand layout

@@ -22,7 +22,8 @@ class GcnStep:
                  fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None,
                  auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = False, bf16_activations: bool = False):
         """bf16_activations (with bf16): the aggregates T_l and the layer outputs H_l (all but the logits) are stored as
-        bfloat16; gradients stay fp32."""
+        bfloat16, and so is the gradient dH_l handed to an aggregate-first layer below whose ReLU backward is fused
+        upstream (only dense products, which round it to bfloat16 anyway, read it); every other gradient stays fp32."""
         self.N, self.B, self.seed = N, B, seed
         self.rowptr, self.colidx, self.X, self.labels = rowptr, colidx, X, labels
         self.weights = weights
@@ -60,7 +61,11 @@ class GcnStep:
             return torch.empty((B, (d + pad - 1) // pad * pad), dtype=dtype, device=dev)[:, :d]
         self.T = [None if self.xform_first[l] else mat(dims[l], act) for l in range(self.L)]
         self.H = [mat(dims[l + 1], act if l < self.L - 1 else torch.float32) for l in range(self.L)]
-        self.dH = [mat(dims[l]) if l > 0 else None for l in range(self.L)]
+        # dH[l] is the dY of layer l-1: bfloat16 when that layer reads it in its dense products only
+        def dh_type(l):
+            below_ok = not self.xform_first[l - 1] and fuse_relu_bwd
+            return act if (bf16_activations and below_ok) else torch.float32
+        self.dH = [mat(dims[l], dh_type(l)) if l > 0 else None for l in range(self.L)]
         self.dO = mat(dims[-1])
         self.dW = [torch.empty_like(w) for w, _ in weights]
         self.db = [torch.empty_like(b) for _, b in weights]

@@ -298,6 +298,47 @@ def test_gemm_bf16_stored_mask_and_weight_gradient(M, N, K):
     dW32 = torch.zeros_like(dW)
     sg.sgnn_gemm(ctx(), True, False, dev(T, torch.float32), dev(dZ), None, sg.SGNN_BF16_MFMA, dW32)
     assert torch.equal(dW, dW32)          # the stored values are what the fp32-stored operand rounds to: same product
+    # B stored as bfloat16 as well (the gradient handed down by the layer above); its column sums are those of the stored values
+    dZr = oracle.round_bf16(dZ)
+    dZd = _bf(np.pad(dZr, ((0, 0), (0, (-N) % 8)))).to(DEV)[:, :N]
+    for Aop in (Td, dev(T, torch.float32)):
+        dWb = torch.zeros_like(dW); csb = torch.zeros_like(cs)
+        sg.sgnn_gemm(ctx(), True, False, Aop, dZd, None, sg.SGNN_BF16_MFMA, dWb, b_colsum=csb)
+        assert torch.equal(dWb, dW)
+        assert rel_err(csb.cpu().numpy(), dZr.sum(axis=0)) < 1e-5
+    # the masked input gradient written as bfloat16 from a bfloat16-stored operand
+    Ab = oracle.round_bf16(A)
+    Abd = _bf(np.pad(Ab, ((0, 0), (0, (-K) % 8)))).to(DEV)[:, :K]
+    C16 = torch.full((M, (N + 7) // 8 * 8), 5.0, dtype=torch.bfloat16, device=DEV)[:, :N]
+    sg.sgnn_gemm(ctx(), False, True, Abd, dev(Bt), None, sg.SGNN_BF16_MFMA, C16, mask=md)
+    got = C16.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4 * np.abs(ref).max()) and torch.all(C16[md <= 0] == 0)
+
+
+@pytest.mark.parametrize("K,M,N", [(16384, 256, 256), (40000 // 32 * 32, 128, 256), (8192, 256, 172), (12000 // 32 * 32, 100, 48),
+                                   (65536, 4, 2), (9984, 130, 66), (8192, 256, 8), (32768, 36, 250)])
+def test_weight_gradient_of_bf16_stored_operands_streams(K, M, N):
+    # A^T B with both operands stored as bfloat16 and a long reduction: the streaming kernel (every frame size up to
+    # 256 x 256, leading dimensions with and without padding, wavefronts with nothing to do), with the column sums of B;
+    # fixed split and summation order: bit-reproducible
+    A = oracle.round_bf16(_rand((K, M), 61)); Bm = oracle.round_bf16(_rand((K, N), 62))
+    Ad = _bf(np.pad(A, ((0, 0), (0, (-M) % 8)))).to(DEV)[:, :M]
+    Bd = _bf(np.pad(Bm, ((0, 0), (0, (-N) % 8)))).to(DEV)[:, :N]
+    ctx().reserve(1, 1, K, 256)
+    C = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV); cs = torch.full((N,), 7.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_gemm(ctx(), True, False, Ad, Bd, None, sg.SGNN_BF16_MFMA, C, b_colsum=cs)
+    assert rel_err(C.cpu().numpy(), A.T @ Bm) < 1e-5
+    assert np.abs(cs.cpu().numpy() - Bm.sum(axis=0)).max() < 1e-5 * np.abs(Bm).sum(axis=0).max()
+    C2 = torch.zeros_like(C); cs2 = torch.zeros_like(cs)
+    sg.sgnn_gemm(ctx(), True, False, Ad, Bd, None, sg.SGNN_BF16_MFMA, C2, b_colsum=cs2)
+    assert torch.equal(C, C2) and torch.equal(cs, cs2)
+    C3 = torch.zeros_like(C)
+    sg.sgnn_gemm(ctx(), True, False, Ad, Bd, None, sg.SGNN_BF16_MFMA, C3)          # without the column sums
+    assert torch.equal(C, C3)
+    # the same product from fp32-stored copies of the same values (the tile kernel): equal up to summation order
+    C4 = torch.zeros_like(C)
+    sg.sgnn_gemm(ctx(), True, False, dev(A, torch.float32), dev(Bm, torch.float32), None, sg.SGNN_BF16_MFMA, C4)
+    assert rel_err(C4.cpu().numpy(), C.cpu().numpy().astype(np.float64)) < 1e-5
 
 
 @pytest.mark.parametrize("d", [256, 172, 128, 100, 47, 33])
@@ -633,7 +674,7 @@ def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_b
                 # with the ReLU backward of layer l-1 fused into the product that writes dH, the buffer holds
                 # dH where H_{l-1} > 0 and zero elsewhere (the mask was checked against the oracle's above)
                 want = ref["dH"][l] * ties[l - 1] if fuse_relu_bwd else ref["dH"][l]
-                assert rel_err(st.dH[l].cpu().numpy(), want) < tol, ("dH", l)
+                assert rel_err(st.dH[l].float().cpu().numpy(), want) < tol, ("dH", l)
 
 
 @pytest.mark.parametrize("fuse_relu_bwd", [False, True])

@@ -342,3 +342,9 @@ def test_stored_bf16_activations_round_once_after_the_activation():
     # the logits are computed from the stored activations and are not rounded themselves
     T2, Z2 = oracle.gcn_fwd(rp, ci, v, st["H"][1], Ws[1][0], Ws[1][1], relu=False, bf16=True)
     assert np.array_equal(st["H"][2], Z2) and np.array_equal(st["T"][1], T2)
+    # the gradient handed down to the first layer is stored rounded: its bias gradient is the column sum of the rounded,
+    # masked values, and its weight gradient (whose product rounds that operand anyway) is what it would be without storage
+    dZ0 = oracle.round_bf16(st["dH"][1]) * st["relu_mask"][0]
+    assert np.allclose(st["db"][0], dZ0.sum(axis=0), rtol=1e-13, atol=1e-15)
+    assert not np.allclose(st["db"][0], (st["dH"][1] * st["relu_mask"][0]).sum(axis=0), rtol=1e-9, atol=0)
+    assert np.allclose(st["dW"][0], oracle.round_bf16(st["T"][0]).T @ dZ0, rtol=1e-12, atol=1e-15)
