@@ -76,6 +76,8 @@ bool csr_ok(const sgnn_csr *c) { return c && c->rowptr && (c->capacity == 0 || (
 } // namespace
 
 static inline int64_t pad4(int64_t d) { return (d + 3) & ~int64_t(3); }
+// leading dimension of a scratch matrix: rows start on 64-byte boundaries (16 fp32 or 32 bfloat16 elements)
+static inline int64_t pad_ld(int64_t d, bool is16) { return is16 ? ((d + 31) & ~int64_t(31)) : ((d + 15) & ~int64_t(15)); }
 
 extern "C" {
 
@@ -134,7 +136,7 @@ int sgnn_ctx_reserve(sgnn_ctx *ctx, uint64_t N, uint64_t E, uint32_t B, uint32_t
     // Products whose kernel does not handle bfloat16 storage itself (fewer than 4096 rows, or wider than 256) go through
     // widened / narrowed fp32 copies: three more B x d_max matrices for those shapes.
     const size_t copies = (B < 4096 || d_max > 256) ? 5 : 2;
-    size_t layer = copies * B * (((size_t)d_max + 7) & ~size_t(7)) * 4 + 5 * 256 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 +
+    size_t layer = copies * B * (((size_t)d_max + 15) & ~size_t(15)) * 4 + 5 * 256 + sgnn_gemm_ws_bytes(d_max) + (size_t)1100 * d_max * 4 +
                    sgnn_spmm_ws_bytes(max_entries, B, d_max) + 16 * 256;
     need = std::max(need, layer);
     need = std::max(need, sgnn_transpose_ws_bytes(max_entries, B));
@@ -399,8 +401,8 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
     // fused into the sparse product
     // The product H W lives in scratch; with the layer's input stored as bfloat16 it is stored as bfloat16 too (the
     // activations of such a stack are 16-bit between all of its kernels).
-    const int64_t ldp = (d_out + 7) & ~int64_t(7);   // rows of the scratch matrix start 16-byte aligned, in fp32 and in 16-bit elements
     const bool p16 = h16;
+    const int64_t ldp = pad_ld(d_out, p16);
     float *P = ws.get<float>(p16 ? ((size_t)A->cols * ldp + 1) / 2 : (size_t)A->cols * ldp);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_fwd: scratch too small: call sgnn_ctx_reserve");
     rc = sgnn_launch_gemm_x(ctx, 0, 0, A->cols, d_out, d_in, H->ptr, h16, H->ld, H->row_index, W->ptr, 0, W->ld, nullptr,
@@ -438,8 +440,8 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     hipStream_t st = static_cast<hipStream_t>(stream);
     ws_alloc ws(ctx);
     const int mfma = flags & SGNN_BF16_MFMA;
-    // rows of the scratch matrices start 16-byte aligned (a multiple of 8 elements also serves the 16-bit ones)
-    const int64_t ld_out = (d_out + 7) & ~int64_t(7), ld_in = (d_in + 7) & ~int64_t(7);
+    const int64_t ld_in = pad_ld(d_in, false);        // dT (fp32)
+    const int64_t ld_out = pad_ld(d_out, t16 && xform_first);     // dZ (fp32), or dP of a transform-first layer (16-bit with a 16-bit input)
 
     // element-wise backward: ReLU mask and bias gradient
     const void *dZ = dY->ptr;

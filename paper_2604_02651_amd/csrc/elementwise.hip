@@ -129,11 +129,14 @@ __global__ __launch_bounds__(1024) void colsum_final_kernel(const float *__restr
 }
 
 // A group of lpr lanes (a power of two >= C, at most 64) owns a row and keeps it in registers
-// (NX values a lane: C <= 64 * NX); a block of 4 * 256 / lpr rows is one round of a workgroup, which walks the
+// (NX values a lane: C <= 64 * NX); a block of XENT_PASSES * 256 / lpr rows is one round of a workgroup, which walks the
 // blocks grid-stride (a fixed assignment, so every sum below is taken in the same order whenever it runs) and
 // writes one partial loss and, if asked, its column sums of dO (the bias gradient of a last layer without
 // activation): cs_partial[workgroup][C].  The number of workgroups is bounded by the launcher: what the final
 // kernel has to add up does not grow with the batch.
+#ifndef XENT_PASSES
+#define XENT_PASSES 4
+#endif
 template <int NX>
 __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, int64_t ldo,
                                                    const int32_t *__restrict__ labels, uint32_t B, uint32_t C,
@@ -152,10 +155,11 @@ __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, 
     const float invB = 1.f / (float)B;
     for (uint32_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {       // unrolled: the loads of the four passes go out together
-        const uint32_t row = (blk * 4 + q) * rows_per_pass + gq;
+    for (int q = 0; q < XENT_PASSES; ++q) {       // unrolled: the loads of all passes go out together
+        const uint32_t row = (blk * XENT_PASSES + q) * rows_per_pass + gq;
         const bool live = row < B;
         const float *o = O + (int64_t)(live ? row : 0) * ldo;
+        const int32_t y = labels[live ? row : 0];      // requested along with the row: nothing below waits for a second round trip
         float x[NX];
         float m = -INFINITY;
 #pragma unroll
@@ -167,17 +171,20 @@ __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, 
         for (int s = lpr >> 1; s > 0; s >>= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
         // e = exp(x - max), kept: the probabilities are e / sum (one exponential per entry, and no rounding of
         // the log-sum-exp in between: with logits in the hundreds that rounding alone is 1e-4 of a probability)
-        float sum = 0.f;
+        float sum = 0.f, oy = 0.f;      // oy: (logit of the label) - max, in the lane that holds that column
+        bool mine = false;
 #pragma unroll
         for (int t = 0; t < NX; ++t) {
+            if ((int32_t)(g + t * lpr) == y && x[t] != -INFINITY) { oy = x[t] - m; mine = true; }
             x[t] = (x[t] == -INFINITY) ? 0.f : expf(x[t] - m);
             sum += x[t];
         }
         for (int s = lpr >> 1; s > 0; s >>= 1) sum += __shfl_xor(sum, s, 64);
         if (live) {
-            const float lse = m + logf(sum);
-            const int32_t y = labels[row];
-            if (g == 0) loss += lse - ((uint32_t)y < C ? o[y] : 0.f);
+            // - log p_y = log(sum) - (o_y - max): added by the lane that holds column y (a label outside [0, C) adds the
+            // log-sum-exp alone, through lane 0 of the row)
+            if (mine) loss += logf(sum) - oy;
+            else if (g == 0 && (uint32_t)y >= C) loss += m + logf(sum);
             if (dO) {
                 const float inv_sum = 1.f / sum;
 #pragma unroll
@@ -360,7 +367,7 @@ int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *
     // Fewer lanes per row mean shorter reductions and more rows in flight per wavefront (172 classes: 32 lanes x 6).
     int lpr_log2 = 6;
     while (lpr_log2 > 2 && C <= (4u << lpr_log2)) --lpr_log2;
-    const unsigned rows_per_block = 4u * (256u >> lpr_log2);
+    const unsigned rows_per_block = XENT_PASSES * (256u >> lpr_log2);
     const unsigned n_blocks = cdiv(B, rows_per_block);
     const unsigned nwg = std::min(n_blocks, 4096u);     // 16 workgroups a compute unit walk the row blocks
     float *partial = ws->get<float>(nwg);

@@ -276,12 +276,14 @@ struct spmm_epi {
     int mask_bf16;      // the mask matrix is stored as bfloat16
 };
 
+// bias: the lane's VEC bias values (zeros without a bias), loaded once per wavefront: a lane's columns never change,
+// and a load of them in front of every row's store cost a third of the kernel on a 2^20-row matrix
 template <int VEC>
-__device__ __forceinline__ void spmm_epilogue(float (&v)[VEC], const spmm_epi &ep, int64_t row, int col)
+__device__ __forceinline__ void spmm_epilogue(float (&v)[VEC], const spmm_epi &ep, int64_t row, int col, const float (&bias)[VEC])
 {
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
-        if (ep.bias) v[i] += ep.bias[col + i];
+        v[i] += bias[i];
         if (ep.relu) v[i] = fmaxf(v[i], 0.f);
     }
     if (ep.mask) {
@@ -311,7 +313,7 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const void *__rest
                                                uint64_t capacity, const XT *__restrict__ X, int64_t ldx,
                                                const int32_t *__restrict__ row_index, int d, uint64_t wave, int rows_per_wave,
                                                int long_len, float *__restrict__ out, int64_t ldo,
-                                               const spmm_epi &ep)
+                                               const spmm_epi &ep, const float (&bias)[CH][VEC])
 {
     constexpr int U = CH * VEC <= 4 ? SPMM_U4 : (CH * VEC <= 8 ? 4 : 2);
     const int lane = threadIdx.x & 63;
@@ -344,7 +346,7 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const void *__rest
             for (int m = 0; m < CH; ++m) {
                 const int col = (m * 64 + lane) * VEC;
                 if (col < d) {
-                    spmm_epilogue<VEC>(acc[m], ep, (int64_t)(r0 + row), col);
+                    spmm_epilogue<VEC>(acc[m], ep, (int64_t)(r0 + row), col, bias[m]);
                     vstore_out<VEC>(out, o + col, acc[m], ep.out_bf16);
                 }
             }
@@ -478,6 +480,14 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
     constexpr int U = spmm_unroll<VEC, CH>::U;
     const int lane = threadIdx.x & 63;
     const uint32_t wave = blockIdx.x * (uint32_t)(SPMM_NT / 64) + (threadIdx.x >> 6);
+    float bias[CH][VEC];
+#pragma unroll
+    for (int m = 0; m < CH; ++m)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            const int col = (m * 64 + lane) * VEC + i;
+            bias[m][i] = (ep.bias && col < d) ? ep.bias[col] : 0.f;
+        }
     const int64_t cap = (int64_t)min(capacity, (uint64_t)0x7fffffffffffffffull);
     if (wave < n_piece_waves) {
         const uint32_t total = min(*n_chunks, max_chunks);
@@ -547,7 +557,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
             for (int m = 0; m < CH; ++m) {
                 const int col = (m * 64 + lane) * VEC;
                 if (col < d) {
-                    spmm_epilogue<VEC>(sum[m], ep, (int64_t)drawn_row, col);
+                    spmm_epilogue<VEC>(sum[m], ep, (int64_t)drawn_row, col, bias[m]);
                     vstore_out<VEC>(out, orow + col, sum[m], ep.out_bf16);
                 }
             }
@@ -583,7 +593,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
                 for (int m = 0; m < CH; ++m) {
                     const int col = (m * 64 + lane) * VEC;
                     if (col < d) {
-                        spmm_epilogue<VEC>(acc[m], ep, (int64_t)rc.x, col);
+                        spmm_epilogue<VEC>(acc[m], ep, (int64_t)rc.x, col, bias[m]);
                         vstore_out<VEC>(out, orow + col, acc[m], ep.out_bf16);
                     }
                 }
@@ -615,7 +625,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
     const int long_len = n_chunks ? (int)n_chunks[1] : 0x7fffffff;
     const uint64_t n_row_waves = (uint64_t)gridDim.x * (SPMM_NT / 64) - n_piece_waves;
     for (uint64_t w = wave - n_piece_waves; w * (uint64_t)rpw < rows; w += n_row_waves)
-        spmm_wave_rows<VEC, CH, XT>(rows, rowptr, rp64, colidx, val, capacity, X, ldx, row_index, d, w, rpw, long_len, out, ldo, ep);
+        spmm_wave_rows<VEC, CH, XT>(rows, rowptr, rp64, colidx, val, capacity, X, ldx, row_index, d, w, rpw, long_len, out, ldo, ep, bias);
 }
 
 int build_plan(sgnn_ctx *ctx, const sgnn_csr *A, void *plan, hipStream_t st)

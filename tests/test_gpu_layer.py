@@ -604,6 +604,28 @@ def test_softmax_xent_with_column_sums(B, C):
         sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss2, None, dO_colsum=cs2)
 
 
+@pytest.mark.parametrize("B,C", [(5000, 172), (4099, 64), (300, 700), (32768, 32), (1000, 1024), (77, 16), (1, 48)])
+def test_softmax_xent_aligned_rows_and_large_logits(B, C):
+    # class counts and leading dimensions that are multiples of four (rows 16-byte aligned), every lanes-per-row bracket,
+    # ragged row counts, logits in the hundreds (the label's logit comes from the lane that holds its column)
+    O = _rand((B, C + 4), 8)[:, :C] * 5; y = np.random.default_rng(9).integers(0, C, B).astype(np.int32)
+    O[::7] *= 40.0                                   # rows with logits in the hundreds
+    ctx().reserve(B, 1, B, max(C, 8))
+    Od = dev(np.pad(O, ((0, 0), (0, 4))))[:, :C]
+    assert Od.stride(0) % 4 == 0
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV); dO = torch.zeros((B, C + 4), dtype=torch.float32, device=DEV)[:, :C]
+    cs = torch.full((C,), 9.0, dtype=torch.float32, device=DEV)
+    sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss, dO, dO_colsum=cs)
+    l_ref, dO_ref = oracle.softmax_xent(O.copy(), y)
+    assert abs(loss.item() - l_ref) < TOL_F32 * abs(l_ref) and rel_err(dO.cpu().numpy(), dO_ref) < TOL_F32
+    assert np.abs(cs.cpu().numpy() - dO_ref.sum(axis=0)).max() < TOL_F32 * np.abs(dO_ref).sum(axis=0).max()
+    loss2 = torch.zeros_like(loss); dO2 = torch.zeros_like(dO); cs2 = torch.zeros_like(cs)
+    sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss2, dO2, dO_colsum=cs2)
+    assert torch.equal(cs, cs2) and torch.equal(loss, loss2) and torch.equal(dO, dO2)
+    sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss2, None)       # the loss alone
+    assert torch.equal(loss, loss2)
+
+
 def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_bwd=True, bf16_act=False):
     cfg = si.CONFIGS[name]
     bf16 = cfg.bf16_mfma if bf16 is None else bf16
