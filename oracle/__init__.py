@@ -161,8 +161,14 @@ def gather_labels(Y, S) -> np.ndarray:
 
 
 def round_bf16(x):
-    f = lib().oracle_round_bf16
-    return np.vectorize(lambda t: f(float(t)), otypes=[np.float64])(np.asarray(x, np.float64))
+    """Every element rounded to bfloat16 (nearest, ties to even), returned as float64."""
+    a = np.ascontiguousarray(x, np.float64)
+    out = np.empty_like(a)
+    L = lib()
+    L.oracle_round_bf16_array.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+    L.oracle_round_bf16_array.restype = None
+    L.oracle_round_bf16_array(a.ctypes.data, out.ctypes.data, a.size)
+    return out
 
 
 def spmm(rowptr, colidx, val, H) -> np.ndarray:

@@ -287,6 +287,12 @@ double oracle_round_bf16(double x)
     return (double)f;
 }
 
+/* the same rounding, element by element, over an array (dst may be src) */
+void oracle_round_bf16_array(const double *src, double *dst, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) dst[i] = oracle_round_bf16(src[i]);
+}
+
 /* out[i,:] = sum_e val[e] * H[col[e],:]  (Eq. 5) */
 void oracle_spmm(int64_t rows, const int32_t *rowptr, const int32_t *colidx, const float *val,
                  const double *H, int64_t d, double *out)
