@@ -1855,7 +1855,7 @@ int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int6
         return SGNN_OK;
     }
 
-    gemm_args a;
+    gemm_args a = {};      // every field the call does not set is zero (fp32 storage, no mask, no row gather)
     a.mask = mask; a.ldm = ldm;
     a.colsum = nullptr;
     a.a_row_index = a_row_index;
@@ -2014,7 +2014,7 @@ int sgnn_launch_gemm_tail(sgnn_ctx *ctx, int64_t M, int64_t N, int64_t K, const 
     if (!(q >= 0.f) || !(q < 1.f)) return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_gemm_tail_fwd: need 0 <= drop_q < 1");
     const bool alignedA = (reinterpret_cast<uintptr_t>(A) & 15) == 0 && lda % 4 == 0;
     if (!(K >= 1 && K <= 256 && N >= 1 && N <= 256 && N % 4 == 0 && M >= 4096 && alignedA)) return SGNN_ERR_UNSUPPORTED;
-    gemm_args a;
+    gemm_args a = {};      // every field the call does not set is zero (fp32 storage, no mask, no row gather)
     a.a_row_index = nullptr;
     a.M = M; a.N = N; a.K = K;
     a.A = A; a.lda = lda; a.B = W; a.ldb = ldw; a.bias = nullptr; a.C = Z; a.ldc = ldz;
