@@ -214,6 +214,14 @@ def measure(args, sg, si, torch, cfg, g, X, labels, weights, use_graph_req: str,
             ec = next((float(w[2:]) for w in p if w.startswith("c=")), 4.0)
             em = next((float(w[2:]) for w in p if w.startswith("m=")), 4.0) if "mask" in p else 0.0   # a mask read along with C
             gq["bytes"] += calls * (ea * m_ * k_ + (ec + em) * m_ * n_ + 4.0 * k_ * n_)
+        elif name == "gemm_tn_stream_kernel":
+            # both tall operands streamed once (tag: "TN stream MxNxK bf16 a=<bytes> b=<bytes>"); the result is small
+            p = tag.split()
+            m_, n_, k_ = (float(x) for x in p[2].split("x"))
+            ea = next((float(w[2:]) for w in p if w.startswith("a=")), 2.0)
+            eb = next((float(w[2:]) for w in p if w.startswith("b=")), 2.0)
+            gq["bytes"] += calls * k_ * (ea * m_ + eb * n_)
+            gq["flops"] += calls * 2.0 * m_ * n_ * k_
         elif name == "spmm_main_kernel":
             d = int(tag.split("d=")[1].split()[0])
             w = tag.split()

@@ -23,6 +23,7 @@ namespace {
 constexpr int HIST_BITS = 11;
 constexpr int HIST_BINS = 1 << HIST_BITS;
 constexpr int SAMP_NT = 256;
+constexpr int SCAN_NT = 1024;            // key passes: few large workgroups, so that few of them meet on one address
 constexpr unsigned EMIT_MAX_WG = 1024;
 
 struct sampler_state {
@@ -42,21 +43,24 @@ __device__ __forceinline__ void vertex_pair_keys(uint64_t j, uint64_t seed, uint
     ko = ((uint64_t)o.w3 << 32) | o.w2;
 }
 
-__global__ __launch_bounds__(SAMP_NT) void sampler_hist_kernel(uint64_t N, uint64_t seed, uint64_t step,
+// The merge of the workgroups' histograms costs one device-wide atomic per bin and workgroup, and atomics on one
+// address are taken one after the other (about 50 ns each, measured): with 2048 workgroups the merge took four
+// times as long as the keys.  Hence at most a few hundred workgroups of 1024 threads.
+__global__ __launch_bounds__(SCAN_NT) void sampler_hist_kernel(uint64_t N, uint64_t seed, uint64_t step,
                                                                uint32_t *__restrict__ hist)
 {
     __shared__ uint32_t lh[HIST_BINS];
-    for (int i = threadIdx.x; i < HIST_BINS; i += SAMP_NT) lh[i] = 0;
+    for (int i = threadIdx.x; i < HIST_BINS; i += SCAN_NT) lh[i] = 0;
     __syncthreads();
     const uint64_t J = (N + 1) >> 1;
-    for (uint64_t j = (uint64_t)blockIdx.x * SAMP_NT + threadIdx.x; j < J; j += (uint64_t)gridDim.x * SAMP_NT) {
+    for (uint64_t j = (uint64_t)blockIdx.x * SCAN_NT + threadIdx.x; j < J; j += (uint64_t)gridDim.x * SCAN_NT) {
         uint64_t ke, ko;
         vertex_pair_keys(j, seed, step, ke, ko);
         atomicAdd(&lh[ke >> (64 - HIST_BITS)], 1u);
         if (2 * j + 1 < N) atomicAdd(&lh[ko >> (64 - HIST_BITS)], 1u);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < HIST_BINS; i += SAMP_NT) {
+    for (int i = threadIdx.x; i < HIST_BINS; i += SCAN_NT) {
         uint32_t c = lh[i];
         if (c) atomicAdd(&hist[i], c);
     }
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(1024) void sampler_pick_bin_kernel(uint32_t B, uint
     if (threadIdx.x == 0) state->ncand = 0;
 }
 
-__global__ __launch_bounds__(SAMP_NT) void sampler_collect_kernel(uint64_t N, uint64_t seed, uint64_t step,
+__global__ __launch_bounds__(SCAN_NT) void sampler_collect_kernel(uint64_t N, uint64_t seed, uint64_t step,
                                                                   sampler_state *__restrict__ state,
                                                                   uint64_t *__restrict__ cand_key,
                                                                   uint32_t *__restrict__ cand_v, uint32_t cap,
@@ -98,7 +102,7 @@ __global__ __launch_bounds__(SAMP_NT) void sampler_collect_kernel(uint64_t N, ui
     const uint64_t J = (N + 1) >> 1;
     if (threadIdx.x == 0) { l_n = 0; l_fail = 0xffffffffu; }
     __syncthreads();
-    for (uint64_t j = (uint64_t)blockIdx.x * SAMP_NT + threadIdx.x; j < J; j += (uint64_t)gridDim.x * SAMP_NT) {
+    for (uint64_t j = (uint64_t)blockIdx.x * SCAN_NT + threadIdx.x; j < J; j += (uint64_t)gridDim.x * SCAN_NT) {
         uint64_t ke, ko;
         vertex_pair_keys(j, seed, step, ke, ko);
         const bool me = (uint32_t)(ke >> (64 - HIST_BITS)) == bin;
@@ -125,43 +129,62 @@ __global__ __launch_bounds__(SAMP_NT) void sampler_collect_kernel(uint64_t N, ui
     if (threadIdx.x == 0) l_base = n_local ? atomicAdd(&state->ncand, n_local) : 0u;
     __syncthreads();
     const uint32_t base = l_base;
-    for (uint32_t i = threadIdx.x; i < n_local; i += SAMP_NT) {
+    for (uint32_t i = threadIdx.x; i < n_local; i += SCAN_NT) {
         if (base + i < cap) { cand_key[base + i] = l_key[i]; cand_v[base + i] = l_v[i]; }
         else atomicOr(status, SGNN_ST_CAND_OVERFLOW);
     }
 }
 
 // Exact r-th smallest (key, v) among the candidates: most-significant-digit radix select over the
-// 96-bit composite, 8 bits a pass.  One workgroup.
+// 96-bit composite, 8 bits a pass, starting below the 11 bits that all candidates share.  One
+// workgroup; a thread keeps its first THR_R candidates in registers, so that a pass costs no memory
+// traffic, and the passes stop as soon as the chosen digit holds a single candidate (after three or
+// four of them for keys that differ, instead of eleven).
+constexpr int THR_R = 12;
+
 __global__ __launch_bounds__(1024) void sampler_threshold_kernel(sampler_state *__restrict__ state,
                                                                  const uint64_t *__restrict__ cand_key,
                                                                  const uint32_t *__restrict__ cand_v, uint32_t cap)
 {
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t sel_digit, sel_r;
+    __shared__ uint32_t sel_digit, sel_r, sel_cnt;
+    __shared__ uint64_t found_key;
+    __shared__ uint32_t found_v;
     const uint32_t n = min(state->ncand, cap);
     uint32_t r = state->r;
-    uint64_t pk = 0;   // decided high bits of the key
-    uint32_t pv = 0;   // decided high bits of the vertex
-    for (int pass = 0; pass < 12; ++pass) {
+    uint64_t rk[THR_R];
+    uint32_t rv[THR_R];
+#pragma unroll
+    for (int q = 0; q < THR_R; ++q) {
+        const uint32_t i = q * 1024 + threadIdx.x;
+        rk[q] = i < n ? cand_key[i] : 0ull;
+        rv[q] = i < n ? cand_v[i] : 0u;
+    }
+    uint64_t pk = (uint64_t)state->bin << (64 - HIST_BITS);   // decided high bits of the key
+    uint32_t pv = 0;                                          // decided high bits of the vertex
+    int kd = HIST_BITS, vd = 0;                               // how many of each are decided
+    if (threadIdx.x == 0) sel_cnt = 0;
+
+    // does (k, v) agree with every decided bit?
+    auto agrees = [&](uint64_t k, uint32_t v) {
+        if ((k >> (64 - kd)) != (pk >> (64 - kd))) return false;
+        return vd == 0 || (v >> (32 - vd)) == (pv >> (32 - vd));
+    };
+    bool single = false;
+    while (kd < 64 || vd < 32) {
+        const bool in_key = kd < 64;
+        const int width = in_key ? min(8, 64 - kd) : 8;
+        const int lo = in_key ? 64 - kd - width : 32 - vd - 8;
+        const uint32_t dmask = (1u << width) - 1u;
         if (threadIdx.x < 256) hist[threadIdx.x] = 0;
         __syncthreads();
-        for (uint32_t i = threadIdx.x; i < n; i += 1024) {
-            const uint64_t k = cand_key[i];
-            const uint32_t v = cand_v[i];
-            bool match;
-            uint32_t digit;
-            if (pass < 8) {
-                const int decided = 8 * pass;
-                match = decided == 0 || (k >> (64 - decided)) == (pk >> (64 - decided));
-                digit = (uint32_t)(k >> (56 - decided)) & 255u;
-            } else {
-                const int decided = 8 * (pass - 8);
-                match = k == pk && (decided == 0 || (v >> (32 - decided)) == (pv >> (32 - decided)));
-                digit = (v >> (24 - decided)) & 255u;
-            }
-            if (match) atomicAdd(&hist[digit], 1u);
-        }
+        auto count = [&](uint64_t k, uint32_t v) {
+            if (agrees(k, v)) atomicAdd(&hist[(in_key ? (uint32_t)(k >> lo) : (v >> lo)) & dmask], 1u);
+        };
+#pragma unroll
+        for (int q = 0; q < THR_R; ++q)
+            if (q * 1024 + threadIdx.x < n) count(rk[q], rv[q]);
+        for (uint32_t i = THR_R * 1024 + threadIdx.x; i < n; i += 1024) count(cand_key[i], cand_v[i]);
         __syncthreads();
         if (threadIdx.x < 64) {
             // lane l owns digits 4l .. 4l+3
@@ -170,18 +193,34 @@ __global__ __launch_bounds__(1024) void sampler_threshold_kernel(sampler_state *
             const uint32_t s = a0 + a1 + a2 + a3;
             const uint32_t ex = wave_incl_scan(s) - s;
             if (ex < r && r <= ex + s) {
-                uint32_t d = 4 * threadIdx.x, e = ex;
-                if (r > e + a0) { e += a0; ++d; if (r > e + a1) { e += a1; ++d; if (r > e + a2) { e += a2; ++d; } } }
+                uint32_t d = 4 * threadIdx.x, e = ex, c = a0;
+                if (r > e + a0) { e += a0; ++d; c = a1; if (r > e + a1) { e += a1; ++d; c = a2; if (r > e + a2) { e += a2; ++d; c = a3; } } }
                 sel_digit = d;
                 sel_r = r - e;
+                sel_cnt = c;
             }
         }
         __syncthreads();
         const uint32_t d = sel_digit;
         r = sel_r;
-        if (pass < 8) pk |= (uint64_t)d << (56 - 8 * pass);
-        else pv |= d << (24 - 8 * (pass - 8));
+        single = sel_cnt == 1;
+        if (in_key) { pk |= (uint64_t)d << lo; kd += width; }
+        else { pv |= d << lo; vd += 8; }
         __syncthreads();
+        if (single) break;
+    }
+    if (single) {
+        // exactly one candidate agrees with the decided bits: it is the threshold
+        auto take = [&](uint64_t k, uint32_t v) {
+            if (agrees(k, v)) { found_key = k; found_v = v; }
+        };
+#pragma unroll
+        for (int q = 0; q < THR_R; ++q)
+            if (q * 1024 + threadIdx.x < n) take(rk[q], rv[q]);
+        for (uint32_t i = THR_R * 1024 + threadIdx.x; i < n; i += 1024) take(cand_key[i], cand_v[i]);
+        __syncthreads();
+        pk = found_key;
+        pv = found_v;
     }
     if (threadIdx.x == 0) {
         state->thr_key = pk;
@@ -200,8 +239,11 @@ __device__ __forceinline__ uint64_t spread_even(uint32_t x32)
     return x;
 }
 
-// Workgroup g owns bitmap words [g*wpw, (g+1)*wpw), wpw a multiple of 8.  A wavefront builds two
-// words per iteration: lane l evaluates vertices 2j and 2j+1 of Philox block j = 32*w0 + l.
+// Workgroup g owns bitmap words [g*wpw, (g+1)*wpw), wpw a multiple of 8.  A wavefront takes 64 words
+// at a time and builds two of them per iteration: lane l evaluates vertices 2j and 2j+1 of Philox block
+// j = 32*w0 + l.  Lane l keeps word l of the 64, so that the wave writes them with one 512-byte store:
+// an 8-byte store by a single lane per word reached memory as a partial write of its own, a quarter of a
+// million of them at a rate of about one per nanosecond.
 __global__ __launch_bounds__(SAMP_NT) void sampler_emit_kernel(uint64_t N, uint64_t seed, uint64_t step,
                                                                const sampler_state *__restrict__ state,
                                                                uint64_t *__restrict__ bitmap, uint64_t W, uint64_t wpw,
@@ -214,22 +256,28 @@ __global__ __launch_bounds__(SAMP_NT) void sampler_emit_kernel(uint64_t N, uint6
     const uint64_t wend = min(W, wbeg + wpw);
     const unsigned wave = threadIdx.x >> 6, lane = lane_id();
     uint32_t cnt = 0;
-    for (uint64_t w0 = wbeg + 2 * wave; w0 < wend; w0 += 2 * (SAMP_NT / 64)) {
-        const uint64_t j = w0 * 32 + lane;
-        const uint64_t ve = 2 * j, vo = 2 * j + 1;
-        bool ie = false, io = false;
-        if (ve < N) {
-            uint64_t ke, ko;
-            vertex_pair_keys(j, seed, step, ke, ko);
-            ie = ke < tk || (ke == tk && (uint32_t)ve <= tv);
-            io = vo < N && (ko < tk || (ko == tk && (uint32_t)vo <= tv));
+    for (uint64_t chunk = wbeg + 64 * wave; chunk < wend; chunk += 64 * (SAMP_NT / 64)) {
+        uint64_t mine = 0;
+        for (unsigned it = 0; it < 32; ++it) {
+            const uint64_t w0 = chunk + 2 * it;
+            if (w0 >= wend) break;
+            const uint64_t j = w0 * 32 + lane;
+            const uint64_t ve = 2 * j, vo = 2 * j + 1;
+            bool ie = false, io = false;
+            if (ve < N) {
+                uint64_t ke, ko;
+                vertex_pair_keys(j, seed, step, ke, ko);
+                ie = ke < tk || (ke == tk && (uint32_t)ve <= tv);
+                io = vo < N && (ko < tk || (ko == tk && (uint32_t)vo <= tv));
+            }
+            const uint64_t be = __ballot(ie), bo = __ballot(io);
+            const uint64_t word0 = spread_even((uint32_t)be) | (spread_even((uint32_t)bo) << 1);
+            const uint64_t word1 = spread_even((uint32_t)(be >> 32)) | (spread_even((uint32_t)(bo >> 32)) << 1);
+            if (lane == 2 * it) mine = word0;
+            if (lane == 2 * it + 1) mine = word1;
+            cnt += __popcll(word0) + __popcll(word1);
         }
-        const uint64_t be = __ballot(ie), bo = __ballot(io);
-        const uint64_t word0 = spread_even((uint32_t)be) | (spread_even((uint32_t)bo) << 1);
-        const uint64_t word1 = spread_even((uint32_t)(be >> 32)) | (spread_even((uint32_t)(bo >> 32)) << 1);
-        if (lane == 0) bitmap[w0] = word0;
-        if (lane == 1 && w0 + 1 < wend) bitmap[w0 + 1] = word1;
-        cnt += __popcll(word0) + __popcll(word1);
+        if (chunk + lane < wend) bitmap[chunk + lane] = mine;
     }
     if (lane == 0) lds[wave] = cnt;
     __syncthreads();
@@ -298,10 +346,11 @@ static int sampler_launches(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed
                             uint32_t *cand_v, uint32_t cap, uint32_t *wg_count, uint32_t *status, hipStream_t st)
 {
     const uint64_t J = (N + 1) >> 1;
-    const unsigned grid = (unsigned)std::min<uint64_t>(cdiv(J, SAMP_NT), 2048);
-    SAMP_LAUNCH("sampler_hist_kernel", sampler_hist_kernel, dim3(grid), dim3(SAMP_NT), N, seed, step, hist);
+    const unsigned grid =
+        (unsigned)std::min<uint64_t>(cdiv(J, SCAN_NT), std::min<uint64_t>(std::max<uint64_t>(256, N >> 19), 2048));
+    SAMP_LAUNCH("sampler_hist_kernel", sampler_hist_kernel, dim3(grid), dim3(SCAN_NT), N, seed, step, hist);
     SAMP_LAUNCH("sampler_pick_bin_kernel", sampler_pick_bin_kernel, dim3(1), dim3(1024), B, hist, state);
-    SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel, dim3(grid), dim3(SAMP_NT), N, seed, step, state, cand_key,
+    SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel, dim3(grid), dim3(SCAN_NT), N, seed, step, state, cand_key,
                 cand_v, cap, status);
     SAMP_LAUNCH("sampler_threshold_kernel", sampler_threshold_kernel, dim3(1), dim3(1024), state, cand_key, cand_v, cap);
 
