@@ -784,6 +784,30 @@ __device__ __forceinline__ void direct_issue(float *lds, const float *__restrict
     }
 }
 
+// The same for a transposed operand whose reduction rows are gathered (row k of the operand is row ridx[k] of G).
+// The indices of a slice are fetched one slice ahead, before the loads of the current slice are issued: by the time
+// they are used, only loads issued after them are outstanding, so the wait the compiler places before their use
+// does not drain the slice in flight.  Whatever order the loads end up in, the wait before the barrier
+// (at most as many operations outstanding as one slice has loads) still covers every older slice.
+template <int R, int WAVES>
+__device__ __forceinline__ void direct_issue_gathered_t(float *lds, const float *__restrict__ G, int64_t ld, int64_t row0,
+                                                        int64_t rows_total, int64_t k0_next, const int32_t *__restrict__ ridx,
+                                                        int lane, int wave, int32_t (&rows)[R * DIRECT_BK / 4 / 64 / WAVES])
+{
+    constexpr int LOADS = R * DIRECT_BK / 4 / 64 / WAVES;
+    int32_t cur[LOADS];
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) cur[j] = rows[j];
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) rows[j] = ridx[k0_next + (64 * (wave + WAVES * j) + lane) / (R / 4)];
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+        const int q = wave + WAVES * j, ch = (64 * q + lane) % (R / 4);
+        const float *g = G + (int64_t)cur[j] * ld + min(row0 + 4 * ch, rows_total - 4);
+        __builtin_amdgcn_global_load_lds(SGNN_GPTR(g), SGNN_LPTR(lds + 256 * q), 16, 0, 0);
+    }
+}
+
 // Operand values of one quad of a slice: reduction steps kk + 8 kh + 4 half + {0..3} for the T tiles of the wavefront.
 template <int R, bool RC, int T>
 __device__ __forceinline__ void direct_frag(float (&v)[T][4], const float *L, int w0, int kk, int half, int li, int kh)
@@ -840,9 +864,21 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_direct_kernel(gemm_args a)
 
     // a slice number past the end loads the last slice again, into a stage nobody reads any more:
     // the loop body then has no branch, and every wait in it counts a fixed number of operations
+    constexpr int LOADS_A = BM * BK / 4 / 64 / WAVES;
+    [[maybe_unused]] int32_t a_rows[LOADS_A];   // gathered A^T: the rows of the slice issued next
+    if constexpr (GATHER && TA) {
+        if (nslices > 0) {
+#pragma unroll
+            for (int j = 0; j < LOADS_A; ++j) a_rows[j] = a.a_row_index[kbeg + (64 * (wave + WAVES * j) + lane) / (BM / 4)];
+        }
+    }
     auto issue = [&](int s) {
         float *st = direct_smem + (s % DIRECT_STAGES) * STAGE_FLOATS;
         const int64_t k0 = kbeg + (int64_t)min(s, nslices - 1) * BK;
+        if constexpr (GATHER && TA) {
+            const int64_t k0_next = kbeg + (int64_t)min(s + 1, nslices - 1) * BK;
+            direct_issue_gathered_t<BM, WAVES>(st, a.A, a.lda, m0, a.M, k0_next, a.a_row_index, lane, wave, a_rows);
+        } else
         direct_issue<BM, A_RC, WAVES>(st, a.A, a.lda, m0, a.M, k0, GATHER ? a.a_row_index : nullptr, lane, wave);
         direct_issue<BN, B_RC, WAVES>(st + BM * BK, a.B, a.ldb, n0, a.N, k0, nullptr, lane, wave);
     };
@@ -966,6 +1002,7 @@ int launch_direct(sgnn_ctx *ctx, int ta, int tb, gemm_args a, int splits, bool b
     }
 #define SGNN_DIRECT_CASE(TA_, TB_, G_) SGNN_DIRECT_CASE_BM(DIRECT_BM, DIRECT_WAVES, 2, TA_, TB_, G_)
     SGNN_DIRECT_CASE_BM(128, 8, 1, true, false, false)
+    SGNN_DIRECT_CASE_BM(128, 8, 1, true, false, true)
     SGNN_DIRECT_CASE(false, false, false)
     SGNN_DIRECT_CASE(false, true, false)
     SGNN_DIRECT_CASE(true, false, false)
@@ -1810,6 +1847,13 @@ int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int6
     const bool b_al = (reinterpret_cast<uintptr_t>(Bv) & (b_bf16 ? 7 : 15)) == 0 && ldb % 4 == 0;
     const bool tn_fast16 = bf16 && ta && !tb && a_al && b_al && M % 4 == 0 && N % 4 == 0 && M >= 4 && N >= 4 && K >= 1;
     const bool a_native = a_bf16 && ((skinny_shape && a_al16) || tn_fast16);
+    // A^T B with both operands stored as bfloat16 and a result of up to 256 x 256 (the weight gradients of a stack whose
+    // activations and hand-down gradients are 16-bit): the streaming kernel, when it takes the shape (any M and N,
+    // odd ones included, which the chunked tile kernel would only take after widening both operands)
+    if (bf16 && ta && !tb && a_bf16 && b_bf16 && !c_bf16 && !a_row_index && !bias && !(flags & SGNN_RELU) && !maskv) {
+        const int rc = sgnn_launch_gemm_tn_stream(ctx, M, N, K, Av, lda, Bv, ldb, static_cast<float *>(Cv), ldc, b_colsum, ws, st);
+        if (rc != SGNN_ERR_UNSUPPORTED) return rc;
+    }
     const float *B = static_cast<const float *>(Bv);
     if (b_bf16 && !tn_fast16) {
         const int64_t rows = tb ? N : K, cols = tb ? K : N, ldw = gemm_pad4(cols);
@@ -1880,13 +1924,6 @@ int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int6
         return launch_skinny(ctx, a, tb, st);
     }
 
-    // A^T B with both operands stored as bfloat16 and a result of up to 256 x 256 (the weight gradients of a stack whose
-    // activations and hand-down gradients are 16-bit): the streaming kernel, when it takes the shape
-    if (bf16 && ta && !tb && a_bf16 && b_bf16 && !a_row_index && !bias && !(flags & SGNN_RELU) && !mask) {
-        const int rc = sgnn_launch_gemm_tn_stream(ctx, M, N, K, A, lda, B, ldb, C, ldc, b_colsum, ws, st);
-        if (rc != SGNN_ERR_UNSUPPORTED) return rc;
-    }
-
     // classifier-width products, fp32: straight from global memory into the MFMA operand layout
     if (!bf16 && !ta && tb && !a_row_index && K >= 4 && K <= 64 && K % 4 == 0 && a.alignedA && a.alignedB && M >= 1 && N >= 1 &&
         M <= (int64_t)0x7fffffff * 32 && N <= (int64_t)65535 * 128) {
@@ -1946,7 +1983,7 @@ int sgnn_launch_gemm_x(sgnn_ctx *ctx, int ta, int tb, int64_t M, int64_t N, int6
     // being multiplied (the register-staged tile kernel has one, and its wavefronts wait for it half of the time) and
     // eight wavefronts, two per SIMD (with four, one per SIMD, it was no faster than the tile kernel: nothing
     // multiplies while the only wavefront of a SIMD issues loads, reads LDS or stands at the barrier)
-    const bool direct128 = !bf16 && ta && !tb && !a_row_index && a.alignedA && a.alignedB && M % 4 == 0 && N % 4 == 0 &&
+    const bool direct128 = !bf16 && ta && !tb && a.alignedA && a.alignedB && M % 4 == 0 && N % 4 == 0 &&
                            M > 64 && N > 64 && K % 32 == 0 && K >= 4096 && !bias && !(flags & SGNN_RELU) && !mask &&
                            (int64_t)cdiv(M, 128) * cdiv(N, 128) <= 64;
 

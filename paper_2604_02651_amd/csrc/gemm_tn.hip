@@ -161,19 +161,25 @@ __global__ __launch_bounds__(64 * TNS_WAVES) void gemm_tn_stream_kernel(tns_args
     if (wave_live) {
         float *P = a.partial + (int64_t)blockIdx.x * a.M * a.N;
         const int n = wn0 + 2 * li;
+        const bool n_even = (a.N & 1) == 0;   // odd N: rows of the partial result start on odd words, one store per value
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int m = wm0 + 4 * (8 * (r / 4) + 4 * kh + (r % 4)) + i;
-                if (m < a.M && n < a.N) {            // N is even: the pair is wholly inside or outside
-                    float2 v = make_float2(acc[i][0][r], acc[i][1][r]);
-                    *reinterpret_cast<float2 *>(P + (int64_t)m * a.N + n) = v;
+                if (m < a.M && n < a.N) {
+                    float *p = P + (int64_t)m * a.N + n;
+                    if (n_even) *reinterpret_cast<float2 *>(p) = make_float2(acc[i][0][r], acc[i][1][r]);   // wholly inside
+                    else {
+                        p[0] = acc[i][0][r];
+                        if (n + 1 < a.N) p[1] = acc[i][1][r];
+                    }
                 }
             }
         if (do_cs && kh == 0 && n < a.N) {           // result row 0: register 0 of the lanes with kh == 0
-            float2 v = make_float2(cs[0][0], cs[1][0]);
-            *reinterpret_cast<float2 *>(a.cs_partial + (int64_t)blockIdx.x * a.N + n) = v;
+            float *p = a.cs_partial + (int64_t)blockIdx.x * a.N + n;
+            p[0] = cs[0][0];
+            if (n + 1 < a.N) p[1] = cs[1][0];
         }
     }
 }
@@ -185,7 +191,7 @@ __global__ __launch_bounds__(64 * TNS_WAVES) void gemm_tn_stream_kernel(tns_args
 int sgnn_launch_gemm_tn_stream(sgnn_ctx *ctx, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
                                float *C, int64_t ldc, float *b_colsum, ws_alloc *ws, hipStream_t st)
 {
-    if (M < 1 || N < 2 || M > 256 || N > 256 || N % 2 || K < 8192 || K % TNS_BK || lda % 8 || ldb % 8 || lda > 256 || ldb > 256 ||
+    if (M < 1 || N < 2 || M > 256 || N > 256 || K < 8192 || K % TNS_BK || lda % 8 || ldb % 8 || lda > 256 || ldb > 256 ||
         lda < M || ldb < N || (reinterpret_cast<uintptr_t>(A) & 15) || (reinterpret_cast<uintptr_t>(B) & 15))
         return SGNN_ERR_UNSUPPORTED;
     // one workgroup a compute unit; every workgroup at least 16 slices

@@ -20,7 +20,8 @@ class GcnStep:
     def __init__(self, N: int, rowptr: torch.Tensor, colidx: torch.Tensor, X: torch.Tensor, labels: torch.Tensor,
                  weights: List[Tuple[torch.Tensor, torch.Tensor]], B: int, seed: int = 0, bf16: bool = False,
                  fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None,
-                 auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = False, bf16_activations: bool = False):
+                 auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = False, bf16_activations: bool = False,
+                 pad_features: bool = True):
         """bf16_activations (with bf16): the aggregates T_l and the layer outputs H_l (all but the logits) are stored as
         bfloat16, and so is the gradient dH_l handed to an aggregate-first layer below whose ReLU backward is fused
         upstream (only dense products, which round it to bfloat16 anyway, read it); every other gradient stays fp32."""
@@ -40,7 +41,7 @@ class GcnStep:
             exp = B + (E - N) * (B / N) * ((B - 1) / max(N - 1, 1))
             capacity = int(min(E, 2 * exp + 16 * B + 65536))
         self.capacity = capacity
-        self.ctx.reserve(N, E, B, max(dims), capacity)
+        self.ctx.reserve(N, E, B, max(max(dims), (dims[0] + 31) // 32 * 32), capacity)   # a padded first layer included
         self.dev = dev
         self.batches = [self._new_batch()]
         self._use(self.batches[0])
@@ -50,6 +51,20 @@ class GcnStep:
         if X.dtype == torch.bfloat16 and (not fuse_slice or self.xform_first[0]):
             raise ValueError("bfloat16 features are read by the first layer's sparse product only: they need fuse_slice "
                              "and a first layer that aggregates first")
+        # A transform-first first layer multiplies X[S] by W_1 and X[S]^T by dP: with fp32 operands both go through
+        # the direct-to-LDS kernels, which copy whole 32-column slices of 16-byte aligned rows.  A feature width that is
+        # not a multiple of 32 (602) is therefore padded with zero columns, in a copy of X made once here, and W_1 / dW_1
+        # live in buffers with as many zero rows; weights[0][0] and dW[0] are views of their first d_in rows.
+        self.d_in_padded = dims[0]
+        if pad_features and self.xform_first[0] and fuse_slice and not bf16 and X.dtype == torch.float32 and dims[0] % 32:
+            dp = (dims[0] + 31) // 32 * 32
+            Xp = torch.zeros((N, dp), dtype=torch.float32, device=dev)
+            Xp[:, :dims[0]] = X
+            Wp = torch.zeros((dp, dims[1]), dtype=torch.float32, device=dev)
+            Wp[:dims[0]] = weights[0][0]
+            self.X, self.d_in_padded = Xp, dp
+            self._W0 = Wp
+            self.weights = [(Wp[:dims[0]], weights[0][1])] + list(weights[1:])
         self.fuse_relu_bwd = fuse_relu_bwd
         self.side_dw = side_dw      # run() / graphs: weight-gradient GEMMs on the second stream
         if bf16_activations and not bf16:
@@ -68,6 +83,10 @@ class GcnStep:
         self.dH = [mat(dims[l], dh_type(l)) if l > 0 else None for l in range(self.L)]
         self.dO = mat(dims[-1])
         self.dW = [torch.empty_like(w) for w, _ in weights]
+        self._dW0 = None
+        if self.d_in_padded != dims[0]:
+            self._dW0 = torch.zeros_like(self._W0)
+            self.dW[0] = self._dW0[:dims[0]]
         self.db = [torch.empty_like(b) for _, b in weights]
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
 
@@ -106,6 +125,8 @@ class GcnStep:
         for l, (W, b) in enumerate(self.weights):
             flags = self.flags | (sg.SGNN_RELU if l < self.L - 1 else 0) | (sg.SGNN_XFORM_FIRST if self.xform_first[l] else 0)
             if l == 0 and self.fuse_slice:
+                if self._dW0 is not None:
+                    W = self._W0
                 sg.sgnn_gcn_fwd(self.ctx, self.A, self.X, W, b, flags, self.H[0], self.T[0], row_index=self.S)
             else:
                 Hin = self.X_S if l == 0 else self.H[l - 1]
@@ -137,6 +158,8 @@ class GcnStep:
                 else:
                     saved = self.H[l - 1]
             dW, db = self.dW[l], self.db[l]
+            if l == 0 and self._dW0 is not None:
+                W, dW = self._W0, self._dW0
             if l == self.L - 1:
                 db = None                            # came with the loss gradient
             if l == 0 and before_last is not None:

@@ -316,7 +316,8 @@ def test_gemm_bf16_stored_mask_and_weight_gradient(M, N, K):
 
 
 @pytest.mark.parametrize("K,M,N", [(16384, 256, 256), (40000 // 32 * 32, 128, 256), (8192, 256, 172), (12000 // 32 * 32, 100, 48),
-                                   (65536, 4, 2), (9984, 130, 66), (8192, 256, 8), (32768, 36, 250)])
+                                   (65536, 4, 2), (9984, 130, 66), (8192, 256, 8), (32768, 36, 250),
+                                   (16384, 256, 47), (8192, 255, 3), (8192, 64, 255)])   # odd widths: one store per value
 def test_weight_gradient_of_bf16_stored_operands_streams(K, M, N):
     # A^T B with both operands stored as bfloat16 and a long reduction: the streaming kernel (every frame size up to
     # 256 x 256, leading dimensions with and without padding, wavefronts with nothing to do), with the column sums of B;
@@ -728,6 +729,18 @@ def test_whole_step_with_narrow_layers_and_a_long_batch():
         _run_config("narrow_long", [1], False)
     finally:
         del si.CONFIGS["narrow_long"]
+
+
+def test_whole_step_with_a_ragged_feature_width():
+    # 100 features into 96 hidden units, transform-first, 4128 sampled vertices: the step pads the features to 128
+    # columns, and both products of the first layer gather their rows of X inside the direct-to-LDS kernels
+    # (X[S] W_1 by tile row, X[S]^T dP by reduction row, a long reduction split into ranges)
+    si.CONFIGS["ragged_wide"] = si.Config("ragged_wide", 16384, 131072, 100, 96, 2, 8, 4128)
+    try:
+        _run_config("ragged_wide", [0, 1], True)
+        _run_config("ragged_wide", [2], False)
+    finally:
+        del si.CONFIGS["ragged_wide"]
 
 
 def test_whole_step_tiny_bf16():
