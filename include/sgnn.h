@@ -262,7 +262,9 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
  * One GCN layer backward (Sec. III-C): dZ = dY where Y > 0 (all of dY without SGNN_RELU or with SGNN_DY_MASKED),
  * dbias = column sums of dZ, dW = T^T dZ, dT = dZ W^T, dH = A_T dT.
  *   A_T   the transpose of the forward matrix as CSR (the same object when it is symmetric)
- *   T, W, Y   as in the forward call (T and Y in the storage they were written in);  dY  B x d_out fp32, or
+ *   T, W, Y   as in the forward call (T and Y in the storage they were written in; with T stored as bfloat16
+ *             the internal dT - and dP below - is stored as bfloat16 too, rounded to nearest even once);
+ *             dY  B x d_out fp32, or
  *             bfloat16 where only the dense products read it: an aggregate-first layer whose mask dY already
  *             carries (SGNN_DY_MASKED, or no SGNN_RELU), with dW wherever dbias is asked for (the bias gradient
  *             is then the sum of the stored, rounded values); anything else with a bfloat16 dY is SGNN_ERR_UNSUPPORTED

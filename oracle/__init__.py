@@ -209,15 +209,17 @@ def gcn_fwd(rowptr, colidx, val, H, W, bias=None, relu: bool = True, bf16: bool 
     return T, Y
 
 
-def gcn_bwd(rowptr_T, colidx_T, val_T, T, W, Y, dY, relu: bool = True, bf16: bool = False, need_dH: bool = True):
-    """Returns (dH or None, dW, db), float64."""
+def gcn_bwd(rowptr_T, colidx_T, val_T, T, W, Y, dY, relu: bool = True, bf16: bool = False, need_dH: bool = True,
+            store_dT_bf16: bool = False):
+    """Returns (dH or None, dW, db), float64.  store_dT_bf16: dT = dZ W^T is rounded to bfloat16 (as
+    stored) before dH = A^T dT."""
     rp = _arr(rowptr_T, np.int32); ci = _arr(colidx_T, np.int32); v = _arr(val_T, np.float32)
     T = _arr(T, np.float64); W = _arr(W, np.float64); Y = _arr(Y, np.float64); dY = _arr(dY, np.float64)
     B = rp.shape[0] - 1
     dH = np.zeros((B, W.shape[0]), np.float64) if need_dH else None
     dW = np.zeros_like(W); db = np.zeros(W.shape[1], np.float64)
     lib().oracle_gcn_bwd(B, _p(rp, C.c_int32), _p(ci, C.c_int32), _p(v, C.c_float), _p(T, C.c_double), W.shape[0],
-                         _p(W, C.c_double), W.shape[1], _p(Y, C.c_double), _p(dY, C.c_double), int(relu), int(bf16),
+                         _p(W, C.c_double), W.shape[1], _p(Y, C.c_double), _p(dY, C.c_double), int(relu), int(bool(bf16)) | (2 if store_dT_bf16 else 0),
                          _p(dH, C.c_double), _p(dW, C.c_double), _p(db, C.c_double))
     return dH, dW, db
 
@@ -404,7 +406,9 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
     bf16=True already; the logits H_L stay unrounded.  The gradient dH_l handed from layer l to layer
     l-1 is stored as bfloat16 too: the dense products of layer l-1 round it anyway, so the one thing
     that changes is that layer's bias gradient, which becomes the column sum of the rounded values.
-    The loss gradient and the gradients inside a layer stay unrounded.
+    Inside a layer the gradient of the aggregate, dT_l = dZ_l W_l^T, is stored as bfloat16 as well (the
+    mirror image of the forward pass, whose sparse product reads bfloat16 activations): it is rounded once
+    before dH_l = A^T dT_l.  The loss gradient and dZ stay unrounded.
 
     dO_ties, logit_band: the loss gradient has the same kind of undecidable set as the ReLU mask.
     Rows of the logits for which undecidable_loss_rows(H_L, y, logit_band) holds form the returned
@@ -441,7 +445,8 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
         if store_bf16 and l < L - 1:
             dY = round_bf16(dY)            # dH_{l+1} as stored (the ReLU mask is 0 / 1: rounding before or after it is the same)
         Ymask = masks[l].astype(np.float64) if relu else Hs[l + 1]     # gcn_bwd only tests Y > 0
-        dH, dW, db = gcn_bwd(rpT, ciT, vT, Ts[l], W, Ymask, dY, relu=relu, bf16=bf16, need_dH=(l > 0))
+        dH, dW, db = gcn_bwd(rpT, ciT, vT, Ts[l], W, Ymask, dY, relu=relu, bf16=bf16, need_dH=(l > 0),
+                             store_dT_bf16=store_bf16)
         dWs[l], dbs[l], dHs[l] = dW, db, dH
         dY = dH
     return dict(rowptr=rpS, colidx=ciS, val=vS, X_S=H, y_S=yS, T=Ts, H=Hs, loss=loss, dO=dO_own, dO_band=dO_band, dW=dWs,

@@ -379,7 +379,9 @@ void oracle_gcn_fwd(int64_t B, const int32_t *rowptr, const int32_t *colidx, con
  * Layer backward (Sec. III-C).  dZ = dY where Y > 0 (all of dY when relu == 0); db = column sums of
  * dZ; dW = T^T dZ; dT = dZ W^T; dH = A_S^T dT, computed with the explicitly transposed CSR
  * (rowptr_T, colidx_T, val_T).  dH may be NULL (first layer: features are not trained).  With
- * bf16 != 0 the operands of both GEMMs (T, dZ, W) are rounded to bfloat16 first.
+ * bit 0 of bf16 set the operands of both GEMMs (T, dZ, W) are rounded to bfloat16 first; with bit 1
+ * set the gradient of the aggregate, dT = dZ W^T, is stored as bfloat16 (rounded once) before the
+ * transposed sparse product reads it.
  */
 void oracle_gcn_bwd(int64_t B, const int32_t *rowptr_T, const int32_t *colidx_T, const float *val_T,
                     const double *T, int64_t d_in, const double *W, int64_t d_out, const double *Y,
@@ -395,9 +397,10 @@ void oracle_gcn_bwd(int64_t B, const int32_t *rowptr_T, const int32_t *colidx_T,
     }
     double *Tr = (double *)malloc(sizeof(double) * (size_t)(B * d_in));
     double *Wr = (double *)malloc(sizeof(double) * (size_t)(d_in * d_out));
-    round_copy(T, Tr, B * d_in, bf16);
-    round_copy(W, Wr, d_in * d_out, bf16);
-    if (bf16) round_copy(dZ, dZ, B * d_out, 1);
+    const int round_operands = bf16 & 1, store_dT_bf16 = bf16 & 2;
+    round_copy(T, Tr, B * d_in, round_operands);
+    round_copy(W, Wr, d_in * d_out, round_operands);
+    if (round_operands) round_copy(dZ, dZ, B * d_out, 1);
     /* dW[k, j] = sum_i T[i, k] dZ[i, j] */
     for (int64_t k = 0; k < d_in * d_out; ++k) dW[k] = 0.0;
 #pragma omp parallel for schedule(static)
@@ -416,6 +419,7 @@ void oracle_gcn_bwd(int64_t B, const int32_t *rowptr_T, const int32_t *colidx_T,
                 for (int64_t j = 0; j < d_out; ++j) s += dZ[i * d_out + j] * Wr[k * d_out + j];
                 dT[i * d_in + k] = s;
             }
+        if (store_dT_bf16) round_copy(dT, dT, B * d_in, 1);
         oracle_spmm(B, rowptr_T, colidx_T, val_T, dT, d_in, dH);
         free(dT);
     }

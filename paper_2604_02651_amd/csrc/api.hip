@@ -440,7 +440,11 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     hipStream_t st = static_cast<hipStream_t>(stream);
     ws_alloc ws(ctx);
     const int mfma = flags & SGNN_BF16_MFMA;
-    const int64_t ld_in = pad_ld(d_in, false);        // dT (fp32)
+    // dT = dZ W^T of an aggregate-first layer is written by a dense product and read by the transposed sparse product
+    // only: with the layer's aggregate stored as bfloat16 it is stored as bfloat16 as well (the mirror image of the
+    // forward pass, whose sparse product reads 16-bit activations), which halves the bytes of both kernels
+    const bool dt16 = t16 && !xform_first;
+    const int64_t ld_in = pad_ld(d_in, dt16);         // dT
     const int64_t ld_out = pad_ld(d_out, t16 && xform_first);     // dZ (fp32), or dP of a transform-first layer (16-bit with a 16-bit input)
 
     // element-wise backward: ReLU mask and bias gradient
@@ -478,13 +482,13 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
         }
         if (dH) {
             // dT = dZ W^T, dH = A^T dT
-            float *dT = ws.get<float>((size_t)Bn * ld_in);
+            float *dT = ws.get<float>(dt16 ? ((size_t)Bn * ld_in + 1) / 2 : (size_t)Bn * ld_in);
             if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
-            rc = sgnn_launch_gemm_x(ctx, 0, 1, Bn, d_in, d_out, dZ, dz16, lddz, nullptr, W->ptr, 0, W->ld, nullptr, mfma, dT, 0, ld_in,
+            rc = sgnn_launch_gemm_x(ctx, 0, 1, Bn, d_in, d_out, dZ, dz16, lddz, nullptr, W->ptr, 0, W->ld, nullptr, mfma, dT, dt16, ld_in,
                                     nullptr, 0, 0, nullptr, &ws, st);
             if (rc) return rc;
-            rc = sgnn_launch_spmm_x(ctx, A_T, dT, 0, ld_in, nullptr, d_in, dH->ptr, dh16, dH->ld, nullptr, 0, hmask, hm16, ldhm, nullptr,
-                                    0, &ws, st);
+            rc = sgnn_launch_spmm_x(ctx, A_T, dT, dt16, ld_in, nullptr, d_in, dH->ptr, dh16, dH->ld, nullptr, 0, hmask, hm16, ldhm,
+                                    nullptr, 0, &ws, st);
             if (rc) return rc;
         }
         return SGNN_OK;

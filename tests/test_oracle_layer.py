@@ -348,3 +348,26 @@ def test_stored_bf16_activations_round_once_after_the_activation():
     assert np.allclose(st["db"][0], dZ0.sum(axis=0), rtol=1e-13, atol=1e-15)
     assert not np.allclose(st["db"][0], (st["dH"][1] * st["relu_mask"][0]).sum(axis=0), rtol=1e-9, atol=0)
     assert np.allclose(st["dW"][0], oracle.round_bf16(st["T"][0]).T @ dZ0, rtol=1e-12, atol=1e-15)
+
+
+def test_stored_bf16_gradient_of_the_aggregate_rounds_once_before_the_sparse_product():
+    # with stored bfloat16 activations the gradient of the aggregate, dT = dZ W^T, is stored as bfloat16 too: the
+    # transposed sparse product reads the rounded values, and nothing else in the layer changes
+    import scipy.sparse as sp
+    rng = np.random.default_rng(6)
+    rp, ci, v, X, y, Ws = _small_stack(rng)
+    Bn = len(rp) - 1
+    A = sp.csr_matrix((np.asarray(v, np.float64), ci, rp), shape=(Bn, Bn))
+    st = oracle.layers_step(rp, ci, v, X, y, Ws, bf16=True, store_bf16=True)
+    dZ1 = oracle.round_bf16(st["dO"])                       # operand of the dense product (no ReLU on the last layer)
+    dT1_exact = dZ1 @ oracle.round_bf16(Ws[1][0]).T
+    dT1 = oracle.round_bf16(dT1_exact)
+    assert np.allclose(st["dH"][1], A.T @ dT1, rtol=1e-12, atol=1e-15)
+    assert not np.allclose(st["dH"][1], A.T @ dT1_exact, rtol=1e-9, atol=0)
+    # the layer function alone: the flag changes dH only, and without it dT stays unrounded
+    Ymask = np.ones_like(st["dO"])
+    rpT, ciT, vT = oracle.csr_transpose(Bn, Bn, rp, ci, v)
+    dH_r, dW_r, db_r = oracle.gcn_bwd(rpT, ciT, vT, st["T"][1], Ws[1][0], Ymask, st["dO"], relu=False, bf16=True, store_dT_bf16=True)
+    dH_u, dW_u, db_u = oracle.gcn_bwd(rpT, ciT, vT, st["T"][1], Ws[1][0], Ymask, st["dO"], relu=False, bf16=True)
+    assert np.array_equal(dW_r, dW_u) and np.array_equal(db_r, db_u)
+    assert np.allclose(dH_u, A.T @ dT1_exact, rtol=1e-12, atol=1e-15) and np.allclose(dH_r, A.T @ dT1, rtol=1e-12, atol=1e-15)
