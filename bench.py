@@ -67,6 +67,7 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="same as --graph off")
     ap.add_argument("--no-overlap", action="store_true",
                     help="everything on one stream (default: the next mini-batch is sampled on a second stream while this one trains)")
+    ap.add_argument("--fp32-loss-grad", action="store_true", help="keep the loss gradient dO in fp32 (default: bfloat16 with the activations)")
     ap.add_argument("--fp32-activations", action="store_true",
                     help="with bf16 GEMM operands, keep the forward activations in fp32 storage (default: bf16 storage)")
     ap.add_argument("--cpu-seconds", type=float, default=25.0, help="target amount of oracle work to time")
@@ -122,6 +123,8 @@ def measure(args, sg, si, torch, cfg, g, X, labels, weights, use_graph_req: str,
         kw = {}
         if "bf16_activations" in sg.GcnStep.__init__.__code__.co_varnames:
             kw["bf16_activations"] = cfg.bf16_mfma and not args.fp32_activations
+        if args.fp32_loss_grad:
+            kw["bf16_loss_grad"] = False
         st = sg.GcnStep(cfg.N, g.rowptr, g.colidx, X, labels, weights, cfg.B, cfg.sampler_seed, bf16=cfg.bf16_mfma,
                         fuse_slice=not args.no_fuse_slice, device=dev, fuse_relu_bwd=not args.no_fuse_relu_bwd,
                         side_dw=args.side_dw, **kw)

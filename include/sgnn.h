@@ -265,9 +265,9 @@ int sgnn_gcn_fwd(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *H, const sgnn
  *   T, W, Y   as in the forward call (T and Y in the storage they were written in; with T stored as bfloat16
  *             the internal dT - and dP below - is stored as bfloat16 too, rounded to nearest even once);
  *             dY  B x d_out fp32, or
- *             bfloat16 where only the dense products read it: an aggregate-first layer whose mask dY already
- *             carries (SGNN_DY_MASKED, or no SGNN_RELU), with dW wherever dbias is asked for (the bias gradient
- *             is then the sum of the stored, rounded values); anything else with a bfloat16 dY is SGNN_ERR_UNSUPPORTED
+ *             bfloat16 when it already carries the layer's mask (SGNN_DY_MASKED, or no SGNN_RELU); dbias is then
+ *             available along with the dW of an aggregate-first layer only (the sum of the stored, rounded
+ *             values); anything else with a bfloat16 dY is SGNN_ERR_UNSUPPORTED
  *             with SGNN_XFORM_FIRST (same flag as in the forward call) T is the layer INPUT H
  *             (B x d_in, row_index honoured) and the products are dP = A_T dZ, dW = H^T dP,
  *             dH = dP W^T
@@ -351,11 +351,14 @@ int sgnn_tail_bwd(sgnn_ctx *ctx, const sgnn_mat *Z, const float *inv_rms, const 
 /*
  * Mean softmax cross-entropy over B rows of C logits (Sec. III-B, single-label loss) and its
  * gradient dO = (softmax(O) - onehot(label)) / B.  loss_dev: device float[1] or NULL.
+ * dO: device B x C with leading dimension lddo (elements), fp32 (dO_dtype = SGNN_F32) or bfloat16 (SGNN_BF16:
+ * every entry rounded to nearest even as it is stored, and dO_colsum adds the stored values), or NULL.
  * dO_colsum: device float[C] or NULL (needs dO): the column sums of dO, i.e. the bias gradient of a
  * last layer without activation (Sec. III-C), from the same pass and in a fixed summation order.
  */
 int sgnn_softmax_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B,
-                      uint32_t C, float *loss_dev, float *dO, int64_t lddo, float *dO_colsum, sgnn_stream stream);
+                      uint32_t C, float *loss_dev, void *dO, int dO_dtype, int64_t lddo, float *dO_colsum,
+                      sgnn_stream stream);
 
 /*
  * Mean binary cross-entropy on logits over the B x C entries, the paper's loss for multi-label tasks

@@ -408,7 +408,9 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
     that changes is that layer's bias gradient, which becomes the column sum of the rounded values.
     Inside a layer the gradient of the aggregate, dT_l = dZ_l W_l^T, is stored as bfloat16 as well (the
     mirror image of the forward pass, whose sparse product reads bfloat16 activations): it is rounded once
-    before dH_l = A^T dT_l.  The loss gradient and dZ stay unrounded.
+    before dH_l = A^T dT_l.  The loss gradient dO is stored as bfloat16 too: the last layer's bias gradient is
+    the column sum of the rounded values, and its other products start from them (the returned "dO" is the
+    unrounded one).  dZ stays unrounded.
 
     dO_ties, logit_band: the loss gradient has the same kind of undecidable set as the ReLU mask.
     Rows of the logits for which undecidable_loss_rows(H_L, y, logit_band) holds form the returned
@@ -442,8 +444,9 @@ def layers_step(rpS, ciS, vS, X_S, y_S, weights, bf16=False, relu_ties=None, tie
     for l in range(L - 1, -1, -1):
         W, b = weights[l]
         relu = l < L - 1
-        if store_bf16 and l < L - 1:
-            dY = round_bf16(dY)            # dH_{l+1} as stored (the ReLU mask is 0 / 1: rounding before or after it is the same)
+        if store_bf16:
+            # dO (l = L-1) and dH_{l+1} as stored (the ReLU mask is 0 / 1: rounding before or after it is the same)
+            dY = round_bf16(dY)
         Ymask = masks[l].astype(np.float64) if relu else Hs[l + 1]     # gcn_bwd only tests Y > 0
         dH, dW, db = gcn_bwd(rpT, ciT, vT, Ts[l], W, Ymask, dY, relu=relu, bf16=bf16, need_dH=(l > 0),
                              store_dT_bf16=store_bf16)

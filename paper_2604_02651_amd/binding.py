@@ -99,7 +99,7 @@ def lib():
         L.sgnn_csr_transpose.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Csr), vp]
         L.sgnn_sigmoid_bce.argtypes = [vp, vp, i64, vp, i64, u32, u32, vp, vp, i64, vp]
         L.sgnn_colsum.argtypes = [vp, C.POINTER(_Mat), vp, vp]
-        L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, i64, vp]
+        L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, C.c_int, i64, vp, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, ci, i64, vp, ci, i64, vp, ci, vp, ci, i64, vp, ci, i64, vp, vp]
@@ -419,9 +419,12 @@ def sgnn_softmax_xent(ctx: Context, O: torch.Tensor, labels: torch.Tensor, loss:
     """dO_colsum: optional float[C], receives the column sums of dO (the bias gradient of a last layer without activation)."""
     if dO_colsum is not None and dO_colsum.numel() != O.shape[1]:
         raise ValueError("dO_colsum must have one element per class")
+    if dO is not None and (dO.shape != O.shape or dO.stride(1) != 1):
+        raise ValueError("dO must have the shape of O and unit column stride")
     ctx.check(lib().sgnn_softmax_xent(ctx._h, _ptr(O, torch.float32, "O"), O.stride(0), _ptr(labels, torch.int32, "labels"),
                                       O.shape[0], O.shape[1], _ptr(loss, torch.float32, "loss"),
-                                      _ptr(dO, torch.float32, "dO"), dO.stride(0) if dO is not None else 0,
+                                      _ptr(dO, dO.dtype if dO is not None and dO.dtype == torch.bfloat16 else torch.float32, "dO"),
+                                      _dt(dO, "dO"), dO.stride(0) if dO is not None else 0,
                                       _ptr(dO_colsum, torch.float32, "dO_colsum"), _stream(stream)))
 
 

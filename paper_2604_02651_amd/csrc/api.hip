@@ -452,10 +452,10 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     int dz16 = dy16 ? 1 : 0;
     int64_t lddz = dY->ld;
     const int mask_here = relu && !dy_masked;
-    if (dy16 && (mask_here || xform_first || (dbias && !dW)))
-        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gcn_bwd: a bfloat16 dY is read by the dense products only: it needs an "
-                                                    "aggregate-first layer whose ReLU mask it already carries (SGNN_DY_MASKED, or no "
-                                                    "SGNN_RELU), and dW wherever dbias is asked for");
+    if (dy16 && (mask_here || (dbias && (!dW || xform_first))))
+        return sgnn_fail(ctx, SGNN_ERR_UNSUPPORTED, "sgnn_gcn_bwd: a bfloat16 dY must carry the layer's ReLU mask already "
+                                                    "(SGNN_DY_MASKED, or no SGNN_RELU), and dbias then comes with the dW of an "
+                                                    "aggregate-first layer only");
     const void *hmask = H_in ? H_in->ptr : nullptr;
     const int64_t ldhm = H_in ? H_in->ld : 0;
     const int hm16 = (H_in && H_in->dtype == SGNN_BF16) ? 1 : 0;
@@ -499,7 +499,7 @@ int sgnn_gcn_bwd(sgnn_ctx *ctx, const sgnn_csr *A_T, const sgnn_mat *T, const sg
     const bool p16 = t16;
     float *dP = ws.get<float>(p16 ? ((size_t)Bn * ld_out + 1) / 2 : (size_t)Bn * ld_out);
     if (!ws.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_gcn_bwd: scratch too small: call sgnn_ctx_reserve");
-    rc = sgnn_launch_spmm_x(ctx, A_T, dZ, 0, lddz, nullptr, d_out, dP, p16, ld_out, nullptr, 0, nullptr, 0, 0, nullptr, 0, &ws, st);   // dZ is fp32 here
+    rc = sgnn_launch_spmm_x(ctx, A_T, dZ, dz16, lddz, nullptr, d_out, dP, p16, ld_out, nullptr, 0, nullptr, 0, 0, nullptr, 0, &ws, st);
     if (rc) return rc;
     if (dW) {
         rc = sgnn_launch_gemm_x(ctx, 1, 0, d_in, d_out, Bn, T->ptr, t16, T->ld, T->row_index, dP, p16, ld_out, nullptr, mfma, dW, 0, d_out,
@@ -647,15 +647,17 @@ int sgnn_copy_f32(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, sgnn_s
 }
 
 int sgnn_softmax_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C,
-                      float *loss_dev, float *dO, int64_t lddo, float *dO_colsum, sgnn_stream stream)
+                      float *loss_dev, void *dO, int dO_dtype, int64_t lddo, float *dO_colsum, sgnn_stream stream)
 {
     if (!ctx) return SGNN_ERR_INVALID_ARG;
-    if (!O || !labels || B == 0 || C == 0 || ldo < C || (dO && lddo < C) || (dO_colsum && !dO))
+    if (!O || !labels || B == 0 || C == 0 || ldo < C || (dO && lddo < C) || (dO_colsum && !dO) ||
+        (dO && dO_dtype != SGNN_F32 && dO_dtype != SGNN_BF16))
         return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_softmax_xent: bad argument");
     int rc = bind_device(ctx);
     if (rc) return rc;
     ws_alloc ws(ctx);
-    return sgnn_launch_xent(ctx, O, ldo, labels, B, C, loss_dev, dO, lddo, dO_colsum, &ws, static_cast<hipStream_t>(stream));
+    return sgnn_launch_xent(ctx, O, ldo, labels, B, C, loss_dev, dO, dO_dtype == SGNN_BF16 ? 1 : 0, lddo, dO_colsum, &ws,
+                            static_cast<hipStream_t>(stream));
 }
 
 } // extern "C"

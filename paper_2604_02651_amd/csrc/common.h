@@ -151,4 +151,4 @@ int sgnn_launch_adam(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v
 int sgnn_launch_graph_normalize(sgnn_ctx *ctx, const sgnn_graph *g, int32_t *rowptr32, float *val, hipStream_t st);
 int sgnn_launch_copy(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, hipStream_t st);
 int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C,
-                     float *loss, float *dO, int64_t lddo, float *dO_colsum, ws_alloc *ws, hipStream_t st);
+                     float *loss, void *dO, int do_bf16, int64_t lddo, float *dO_colsum, ws_alloc *ws, hipStream_t st);

@@ -140,9 +140,11 @@ __global__ __launch_bounds__(1024) void colsum_final_kernel(const float *__restr
 template <int NX>
 __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, int64_t ldo,
                                                    const int32_t *__restrict__ labels, uint32_t B, uint32_t C,
-                                                   int lpr_log2, uint32_t n_blocks, float *__restrict__ dO, int64_t lddo,
-                                                   float *__restrict__ partial, float *__restrict__ cs_partial)
+                                                   int lpr_log2, uint32_t n_blocks, void *__restrict__ dOv, int do_bf16,
+                                                   int64_t lddo, float *__restrict__ partial, float *__restrict__ cs_partial)
 {
+    float *dO = static_cast<float *>(dOv);
+    unsigned short *dO16 = static_cast<unsigned short *>(dOv);
     __shared__ float lds[4];
     __shared__ float cs_lds[4][64 * NX];
     float csum[NX];
@@ -191,8 +193,13 @@ __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, 
                 for (int t = 0; t < NX; ++t) {
                     const uint32_t j = g + t * lpr;
                     if (j < C) {
-                        const float dv = (x[t] * inv_sum - ((int32_t)j == y ? 1.f : 0.f)) * invB;
-                        dO[(int64_t)row * lddo + j] = dv;
+                        float dv = (x[t] * inv_sum - ((int32_t)j == y ? 1.f : 0.f)) * invB;
+                        if (do_bf16) {
+                            // stored rounded to nearest even; the column sums add what is stored
+                            const __bf16 h = (__bf16)dv;
+                            dO16[(int64_t)row * lddo + j] = __builtin_bit_cast(unsigned short, h);
+                            dv = (float)h;
+                        } else dO[(int64_t)row * lddo + j] = dv;
                         csum[t] += dv;
                     }
                 }
@@ -361,7 +368,7 @@ int sgnn_launch_relu_bwd_bias(sgnn_ctx *ctx, const void *Yv, int y_bf16, int64_t
 }
 
 int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C, float *loss,
-                     float *dO, int64_t lddo, float *dO_colsum, ws_alloc *ws, hipStream_t st)
+                     void *dO, int do_bf16, int64_t lddo, float *dO_colsum, ws_alloc *ws, hipStream_t st)
 {
     // lanes per row: the fewest (a power of two from 4 to 64) with which a lane holds at most eight values of a row.
     // Fewer lanes per row mean shorter reductions and more rows in flight per wavefront (172 classes: 32 lanes x 6).
@@ -376,7 +383,7 @@ int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *
     const unsigned nx = (C + (1u << lpr_log2) - 1) >> lpr_log2;
 #define SGNN_XENT(NX_)                                                                                                       \
     SGNN_LAUNCH(ctx, st, "xent_kernel", SGNN_TAG, xent_kernel<NX_>, dim3(nwg), dim3(256), 0, st, O, ldo, labels, B, C, lpr_log2, \
-                n_blocks, dO, lddo, partial, cs_partial)
+                n_blocks, dO, do_bf16, lddo, partial, cs_partial)
     if (nx <= 1) SGNN_XENT(1);
     else if (nx <= 2) SGNN_XENT(2);
     else if (nx <= 4) SGNN_XENT(4);

@@ -21,10 +21,11 @@ class GcnStep:
                  weights: List[Tuple[torch.Tensor, torch.Tensor]], B: int, seed: int = 0, bf16: bool = False,
                  fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None,
                  auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = False, bf16_activations: bool = False,
-                 pad_features: bool = True):
+                 pad_features: bool = True, bf16_loss_grad: bool = True):
         """bf16_activations (with bf16): the aggregates T_l and the layer outputs H_l (all but the logits) are stored as
         bfloat16, and so is the gradient dH_l handed to an aggregate-first layer below whose ReLU backward is fused
-        upstream (only dense products, which round it to bfloat16 anyway, read it); every other gradient stays fp32."""
+        upstream (only dense products, which round it to bfloat16 anyway, read it); the loss gradient dO is stored as
+        bfloat16 as well; every other gradient handed between calls stays fp32."""
         self.N, self.B, self.seed = N, B, seed
         self.rowptr, self.colidx, self.X, self.labels = rowptr, colidx, X, labels
         self.weights = weights
@@ -81,7 +82,9 @@ class GcnStep:
             below_ok = not self.xform_first[l - 1] and fuse_relu_bwd
             return act if (bf16_activations and below_ok) else torch.float32
         self.dH = [mat(dims[l], dh_type(l)) if l > 0 else None for l in range(self.L)]
-        self.dO = mat(dims[-1])
+        # the loss gradient: bfloat16 along with the activations (the last layer has no ReLU, so whichever product reads
+        # it - dense or sparse - takes the stored values as they are; its bias gradient comes with the loss kernel)
+        self.dO = mat(dims[-1], act if bf16_loss_grad else torch.float32)
         self.dW = [torch.empty_like(w) for w, _ in weights]
         self._dW0 = None
         if self.d_in_padded != dims[0]:

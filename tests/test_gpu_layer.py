@@ -624,6 +624,12 @@ def test_softmax_xent_aligned_rows_and_large_logits(B, C):
     sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss2, dO2, dO_colsum=cs2)
     assert torch.equal(cs, cs2) and torch.equal(loss, loss2) and torch.equal(dO, dO2)
     sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss2, None)       # the loss alone
+    # dO stored as bfloat16: the same values rounded to nearest even once, and the column sums of what is stored
+    dO16 = torch.zeros((B, (C + 31) // 32 * 32), dtype=torch.bfloat16, device=DEV)[:, :C]; cs16 = torch.zeros_like(cs)
+    sg.sgnn_softmax_xent(ctx(), Od, dev(y), loss2, dO16, dO_colsum=cs16)
+    assert torch.equal(dO16, dO.to(torch.bfloat16)) and torch.equal(loss, loss2)
+    stored = dO16.float().cpu().numpy().astype(np.float64)
+    assert np.abs(cs16.cpu().numpy() - stored.sum(axis=0)).max() < TOL_F32 * np.abs(stored).sum(axis=0).max()
     assert torch.equal(loss, loss2)
 
 
@@ -680,9 +686,9 @@ def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_b
             # and after the device's logits have been shown to lie within the band of the oracle's
             und = oracle.undecidable_loss_rows(ref["H"][-1], ref["y_S"], LOGIT_BAND, tol)
             O_gpu = st.H[-1].cpu().numpy().astype(np.float64)
-            dO_gpu = st.dO.cpu().numpy().astype(np.float64)
+            dO_gpu = st.dO.float().cpu().numpy().astype(np.float64)
             _, dO_def = oracle.softmax_xent(O_gpu, ref["y_S"])
-            assert rel_err(dO_gpu, dO_def) < TOL_F32
+            assert rel_err(dO_gpu, dO_def) < (2.0 ** -8 if st.dO.dtype == torch.bfloat16 else TOL_F32)   # as stored
             eps = LOGIT_BAND * np.abs(ref["H"][-1]).max(axis=1)
             assert np.all(np.abs(O_gpu - ref["H"][-1])[und] <= eps[und, None])
             assert und.mean() < 0.1
@@ -825,9 +831,9 @@ def test_whole_step_xlarge_bf16():
     # enters the oracle's backward pass inside that set only, and only after its logits have been shown to lie
     # within the band of the oracle's there; every other row starts from the oracle's own gradient.
     O_gpu = Hg[-1].astype(np.float64)
-    dO_gpu = st.dO.cpu().numpy().astype(np.float64)
+    dO_gpu = st.dO.float().cpu().numpy().astype(np.float64)
     _, dO_def = oracle.softmax_xent(O_gpu, y_S.astype(np.int32))
-    assert rel_err(dO_gpu, dO_def) < TOL_F32
+    assert rel_err(dO_gpu, dO_def) < (2.0 ** -8 if st.dO.dtype == torch.bfloat16 else TOL_F32)       # as stored
     und = ref["dO_band"]
     O_ref = ref["H"][-1]
     eps = band_l * np.abs(O_ref).max(axis=1)

@@ -371,3 +371,21 @@ def test_stored_bf16_gradient_of_the_aggregate_rounds_once_before_the_sparse_pro
     dH_u, dW_u, db_u = oracle.gcn_bwd(rpT, ciT, vT, st["T"][1], Ws[1][0], Ymask, st["dO"], relu=False, bf16=True)
     assert np.array_equal(dW_r, dW_u) and np.array_equal(db_r, db_u)
     assert np.allclose(dH_u, A.T @ dT1_exact, rtol=1e-12, atol=1e-15) and np.allclose(dH_r, A.T @ dT1, rtol=1e-12, atol=1e-15)
+
+
+def test_stored_bf16_loss_gradient_changes_the_last_bias_gradient_only():
+    # dO stored as bfloat16: the last layer's bias gradient is the column sum of the rounded values; its weight
+    # gradient, whose product rounds dO anyway, is what it was; the returned dO is the unrounded one
+    rng = np.random.default_rng(7)
+    rp, ci, v, X, y, Ws = _small_stack(rng)
+    plain = oracle.layers_step(rp, ci, v, X, y, Ws, bf16=True)
+    st = oracle.layers_step(rp, ci, v, X, y, Ws, bf16=True, store_bf16=True)
+    _, dO = oracle.softmax_xent(st["H"][-1], y)
+    assert np.array_equal(st["dO"], dO)
+    r = oracle.round_bf16(dO)
+    assert np.allclose(st["db"][1], r.sum(axis=0), rtol=1e-13, atol=1e-16)
+    assert not np.allclose(st["db"][1], dO.sum(axis=0), rtol=1e-9, atol=0) or np.array_equal(r, dO)
+    assert np.allclose(st["dW"][1], oracle.round_bf16(st["T"][1]).T @ r, rtol=1e-12, atol=1e-16)
+    # without stored activations the bias gradient sums the unrounded values
+    _, dO_p = oracle.softmax_xent(plain["H"][-1], y)
+    assert np.allclose(plain["db"][1], dO_p.sum(axis=0), rtol=1e-13, atol=1e-16)
