@@ -1,9 +1,12 @@
 // Uniform vertex sampling without replacement (Sec. III-D "Vertex Sampling", Eq. 20).
 //
 // The sample is the B vertices with the smallest (key(v), v), key(v) being 64 bits of
-// Philox4x32-10 (Salmon et al., SC'11) counted by (v/2, step) and keyed by the seed.  Keys are
-// never stored: every pass recomputes them (about 100 integer ALU operations per two vertices),
-// which is cheaper on this machine than writing and re-reading 8 bytes per vertex.
+// Philox4x32-10 (Salmon et al., SC'11) counted by (v/2, step) and keyed by the seed.  Whole keys are
+// never stored.  A pass that recomputes them is bound by the 20 quarter-rate 32 x 32 -> 64 multiplies
+// of a Philox call (about 19 us per 2^23 calls, measured), three passes cost three times that; with
+// scratch for two bytes per vertex the first pass also stores the top 16 bits of every key, and the
+// later passes read those instead: they decide all but 2^-11 (candidates) and 2^-16 (ties with the
+// threshold's prefix) of the vertices, and only for these is the key computed again.
 //
 //   1. sampler_hist_kernel     histogram of the top 11 key bits (LDS histograms, one merge)
 //   2. sampler_pick_bin_kernel the bin b* that holds the B-th smallest key and the rank r inside
@@ -46,8 +49,9 @@ __device__ __forceinline__ void vertex_pair_keys(uint64_t j, uint64_t seed, uint
 // The merge of the workgroups' histograms costs one device-wide atomic per bin and workgroup, and atomics on one
 // address are taken one after the other (about 50 ns each, measured): with 2048 workgroups the merge took four
 // times as long as the keys.  Hence at most a few hundred workgroups of 1024 threads.
+// prefix (may be NULL): word j receives the top 16 bits of the keys of vertices 2j (low half) and 2j+1.
 __global__ __launch_bounds__(SCAN_NT) void sampler_hist_kernel(uint64_t N, uint64_t seed, uint64_t step,
-                                                               uint32_t *__restrict__ hist)
+                                                               uint32_t *__restrict__ hist, uint32_t *__restrict__ prefix)
 {
     __shared__ uint32_t lh[HIST_BINS];
     for (int i = threadIdx.x; i < HIST_BINS; i += SCAN_NT) lh[i] = 0;
@@ -58,6 +62,7 @@ __global__ __launch_bounds__(SCAN_NT) void sampler_hist_kernel(uint64_t N, uint6
         vertex_pair_keys(j, seed, step, ke, ko);
         atomicAdd(&lh[ke >> (64 - HIST_BITS)], 1u);
         if (2 * j + 1 < N) atomicAdd(&lh[ko >> (64 - HIST_BITS)], 1u);
+        if (prefix) prefix[j] = (uint32_t)(ke >> 48) | ((uint32_t)(ko >> 48) << 16);
     }
     __syncthreads();
     for (int i = threadIdx.x; i < HIST_BINS; i += SCAN_NT) {
@@ -86,11 +91,13 @@ __global__ __launch_bounds__(1024) void sampler_pick_bin_kernel(uint32_t B, uint
     if (threadIdx.x == 0) state->ncand = 0;
 }
 
+template <bool PREFIX>
 __global__ __launch_bounds__(SCAN_NT) void sampler_collect_kernel(uint64_t N, uint64_t seed, uint64_t step,
                                                                   sampler_state *__restrict__ state,
                                                                   uint64_t *__restrict__ cand_key,
                                                                   uint32_t *__restrict__ cand_v, uint32_t cap,
-                                                                  uint32_t *__restrict__ status)
+                                                                  uint32_t *__restrict__ status,
+                                                                  const uint32_t *__restrict__ prefix)
 {
     // Matches are rare (one vertex in 2048): a workgroup gathers its own in LDS and reserves room in
     // the global list with ONE atomic add, instead of one add per match on a single hot address.
@@ -102,26 +109,45 @@ __global__ __launch_bounds__(SCAN_NT) void sampler_collect_kernel(uint64_t N, ui
     const uint64_t J = (N + 1) >> 1;
     if (threadIdx.x == 0) { l_n = 0; l_fail = 0xffffffffu; }
     __syncthreads();
-    for (uint64_t j = (uint64_t)blockIdx.x * SCAN_NT + threadIdx.x; j < J; j += (uint64_t)gridDim.x * SCAN_NT) {
-        uint64_t ke, ko;
-        vertex_pair_keys(j, seed, step, ke, ko);
-        const bool me = (uint32_t)(ke >> (64 - HIST_BITS)) == bin;
-        const bool mo = (2 * j + 1 < N) && (uint32_t)(ko >> (64 - HIST_BITS)) == bin;
-        if (me || mo) {
-            const uint32_t cnt = (me ? 1u : 0u) + (mo ? 1u : 0u);
-            uint32_t p = atomicAdd(&l_n, cnt);
-            if (p + cnt <= LCAP) {
-                if (me) { l_key[p] = ke; l_v[p] = (uint32_t)(2 * j); ++p; }
-                if (mo) { l_key[p] = ko; l_v[p] = (uint32_t)(2 * j + 1); }
-            } else {
-                // the local list is full (far beyond the expected load): straight to the global list.
-                // Reservations only grow, so every one before the first that failed fitted, and they
-                // fill [0, first failing offset) without holes.
-                atomicMin(&l_fail, p);
-                uint32_t q = atomicAdd(&state->ncand, cnt);
-                if (me) { if (q < cap) { cand_key[q] = ke; cand_v[q] = (uint32_t)(2 * j); } else atomicOr(status, SGNN_ST_CAND_OVERFLOW); ++q; }
-                if (mo) { if (q < cap) { cand_key[q] = ko; cand_v[q] = (uint32_t)(2 * j + 1); } else atomicOr(status, SGNN_ST_CAND_OVERFLOW); }
+    auto append = [&](bool me, bool mo, uint64_t ke, uint64_t ko, uint64_t j) {
+        if (!(me || mo)) return;
+        const uint32_t cnt = (me ? 1u : 0u) + (mo ? 1u : 0u);
+        uint32_t p = atomicAdd(&l_n, cnt);
+        if (p + cnt <= LCAP) {
+            if (me) { l_key[p] = ke; l_v[p] = (uint32_t)(2 * j); ++p; }
+            if (mo) { l_key[p] = ko; l_v[p] = (uint32_t)(2 * j + 1); }
+        } else {
+            // the local list is full (far beyond the expected load): straight to the global list.
+            // Reservations only grow, so every one before the first that failed fitted, and they
+            // fill [0, first failing offset) without holes.
+            atomicMin(&l_fail, p);
+            uint32_t q = atomicAdd(&state->ncand, cnt);
+            if (me) { if (q < cap) { cand_key[q] = ke; cand_v[q] = (uint32_t)(2 * j); } else atomicOr(status, SGNN_ST_CAND_OVERFLOW); ++q; }
+            if (mo) { if (q < cap) { cand_key[q] = ko; cand_v[q] = (uint32_t)(2 * j + 1); } else atomicOr(status, SGNN_ST_CAND_OVERFLOW); }
+        }
+    };
+    const uint64_t J_rounds = PREFIX ? (J + 3) / 4 : J;      // loop items: quads of prefix words, or Philox blocks
+    for (uint64_t j = (uint64_t)blockIdx.x * SCAN_NT + threadIdx.x; j < J_rounds; j += (uint64_t)gridDim.x * SCAN_NT) {
+        if constexpr (PREFIX) {
+            // a thread takes four prefix words (eight vertices) per round; the stored prefixes hold the bin, and the
+            // keys themselves are computed for the matches only
+            const uint4 pp4 = *reinterpret_cast<const uint4 *>(prefix + 4 * j);      // the array is padded to whole quads
+            const uint32_t pw[4] = {pp4.x, pp4.y, pp4.z, pp4.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint64_t jj = 4 * j + q;
+                const bool he = 2 * jj < N && ((pw[q] & 0xffffu) >> (16 - HIST_BITS)) == bin;
+                const bool ho = 2 * jj + 1 < N && (pw[q] >> (32 - HIST_BITS)) == bin;
+                if (he || ho) {
+                    uint64_t k0, k1;
+                    vertex_pair_keys(jj, seed, step, k0, k1);
+                    append(he, ho, k0, k1, jj);
+                }
             }
+        } else {
+            uint64_t ke, ko;
+            vertex_pair_keys(j, seed, step, ke, ko);
+            append((uint32_t)(ke >> (64 - HIST_BITS)) == bin, (2 * j + 1 < N) && (uint32_t)(ko >> (64 - HIST_BITS)) == bin, ke, ko, j);
         }
     }
     __syncthreads();
@@ -288,6 +314,75 @@ __global__ __launch_bounds__(SAMP_NT) void sampler_emit_kernel(uint64_t N, uint6
     }
 }
 
+// The same from the stored key prefixes.  A wavefront takes eight bitmap words (512 vertices) per round: lane l
+// loads the prefixes of vertices 8l .. 8l+7 of the span with one 16-byte load and reduces them to one byte of the
+// bitmap (a prefix below the threshold's is in, one above is out, an equal one - 2^-16 of the vertices - has its key
+// computed again); the 64 bytes pass through a wavefront-private strip of LDS, from which lanes 0 .. 7 read and
+// write their eight words with one 64-byte store.  No scalar bit interleaving, no key arithmetic.
+__global__ __launch_bounds__(SAMP_NT) void sampler_emit_prefix_kernel(uint64_t N, uint64_t seed, uint64_t step,
+                                                                      const sampler_state *__restrict__ state,
+                                                                      uint64_t *__restrict__ bitmap, uint64_t W, uint64_t wpw,
+                                                                      uint32_t *__restrict__ wg_count,
+                                                                      const uint32_t *__restrict__ prefix)
+{
+    __shared__ uint32_t lds[SAMP_NT / 64];
+    __shared__ __attribute__((aligned(8))) uint8_t strip[SAMP_NT / 64][64];
+    const uint64_t tk = state->thr_key;
+    const uint32_t tv = state->thr_v;
+    const uint32_t tp = (uint32_t)(tk >> 48);
+    const uint64_t wbeg = (uint64_t)blockIdx.x * wpw;
+    const uint64_t wend = min(W, wbeg + wpw);
+    const unsigned wave = threadIdx.x >> 6, lane = lane_id();
+    volatile uint8_t *my_bytes = strip[wave];
+    volatile uint64_t *my_words = reinterpret_cast<volatile uint64_t *>(strip[wave]);
+    uint32_t cnt = 0;
+    // wbeg and wpw are multiples of 8: a round's eight words lie inside [wbeg, wend) or behind W (vertices >= N: empty)
+    for (uint64_t wb = wbeg + 8 * wave; wb < wend; wb += 8 * (SAMP_NT / 64)) {
+        const uint64_t v0 = wb * 64 + 8 * lane;                  // first of the lane's eight vertices
+        uint32_t byte = 0;
+        if (v0 < N) {
+            const uint4 pp4 = *reinterpret_cast<const uint4 *>(prefix + (v0 >> 1));      // the array is padded to whole quads
+            const uint32_t pw[4] = {pp4.x, pp4.y, pp4.z, pp4.w};
+            bool tie = false;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t pe = pw[q] & 0xffffu, po = pw[q] >> 16;
+                byte |= (pe < tp ? 1u : 0u) << (2 * q) | (po < tp ? 1u : 0u) << (2 * q + 1);
+                tie = tie || pe == tp || po == tp;
+            }
+            if (tie) {
+#pragma unroll 1
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t pe = pw[q] & 0xffffu, po = pw[q] >> 16;
+                    if (pe != tp && po != tp) continue;
+                    const uint64_t ve = v0 + 2 * q, vo = ve + 1;
+                    uint64_t ke, ko;
+                    vertex_pair_keys(ve >> 1, seed, step, ke, ko);
+                    const uint32_t ie = (ke < tk || (ke == tk && (uint32_t)ve <= tv)) ? 1u : 0u;
+                    const uint32_t io = (ko < tk || (ko == tk && (uint32_t)vo <= tv)) ? 1u : 0u;
+                    byte = (byte & ~(3u << (2 * q))) | ie << (2 * q) | io << (2 * q + 1);
+                }
+            }
+            // vertices at and behind N (the odd partner of the last vertex, the padding of the last quad) are out
+            if (v0 + 8 > N) byte &= (1u << (N - v0)) - 1u;
+        }
+        my_bytes[lane] = (uint8_t)byte;          // volatile: written and read in program order; LDS serves a wavefront in order
+        if (lane < 8) {
+            const uint64_t word = my_words[lane];
+            if (wb + lane < wend) bitmap[wb + lane] = word;
+            cnt += (uint32_t)__popcll(word);
+        }
+    }
+    cnt = wave_sum(cnt);
+    if (lane == 0) lds[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int i = 0; i < SAMP_NT / 64; ++i) t += lds[i];
+        wg_count[blockIdx.x] = t;
+    }
+}
+
 __global__ __launch_bounds__(SAMP_NT) void sampler_rank_kernel(const uint64_t *__restrict__ bitmap, uint64_t W,
                                                                uint64_t wpw, const uint32_t *__restrict__ wg_count,
                                                                uint32_t B, uint32_t *__restrict__ rank,
@@ -324,10 +419,13 @@ size_t sgnn_sampler_persist_bytes() { return HIST_BINS * sizeof(uint32_t) + 256;
 
 static uint32_t cand_capacity(uint64_t N) { return (uint32_t)(2 * (N >> HIST_BITS) + 8192); }
 
+// the key prefixes pay once a pass over the keys costs more than their traffic; below that the keys are recomputed
+static size_t prefix_bytes(uint64_t N) { return N >= (1ull << 20) ? (size_t)(((N + 1) >> 1) + 4) * sizeof(uint32_t) : 0; }   // padded to whole quads
+
 size_t sgnn_sampler_ws_bytes(uint64_t N)
 {
     const size_t cap = cand_capacity(N);
-    return cap * 12 + EMIT_MAX_WG * 4 + 4 * 256;
+    return cap * 12 + EMIT_MAX_WG * 4 + 4 * 256 + prefix_bytes(N) + 256;
 }
 
 // The six launches.  ctx may be NULL (no profiling, errors through sgnn_fail(NULL, ...)); every buffer
@@ -343,22 +441,30 @@ size_t sgnn_sampler_ws_bytes(uint64_t N)
 
 static int sampler_launches(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, uint64_t step, int32_t *S,
                             uint64_t *bitmap, uint32_t *rank, uint32_t *hist, sampler_state *state, uint64_t *cand_key,
-                            uint32_t *cand_v, uint32_t cap, uint32_t *wg_count, uint32_t *status, hipStream_t st)
+                            uint32_t *cand_v, uint32_t cap, uint32_t *wg_count, uint32_t *status, uint32_t *prefix, hipStream_t st)
 {
     const uint64_t J = (N + 1) >> 1;
     const unsigned grid =
         (unsigned)std::min<uint64_t>(cdiv(J, SCAN_NT), std::min<uint64_t>(std::max<uint64_t>(256, N >> 19), 2048));
-    SAMP_LAUNCH("sampler_hist_kernel", sampler_hist_kernel, dim3(grid), dim3(SCAN_NT), N, seed, step, hist);
+    SAMP_LAUNCH("sampler_hist_kernel", sampler_hist_kernel, dim3(grid), dim3(SCAN_NT), N, seed, step, hist, prefix);
     SAMP_LAUNCH("sampler_pick_bin_kernel", sampler_pick_bin_kernel, dim3(1), dim3(1024), B, hist, state);
-    SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel, dim3(grid), dim3(SCAN_NT), N, seed, step, state, cand_key,
-                cand_v, cap, status);
+    if (prefix)
+        SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel<true>, dim3(grid), dim3(SCAN_NT), N, seed, step, state, cand_key,
+                    cand_v, cap, status, (const uint32_t *)prefix);
+    else
+        SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel<false>, dim3(grid), dim3(SCAN_NT), N, seed, step, state, cand_key,
+                    cand_v, cap, status, (const uint32_t *)nullptr);
     SAMP_LAUNCH("sampler_threshold_kernel", sampler_threshold_kernel, dim3(1), dim3(1024), state, cand_key, cand_v, cap);
 
     const uint64_t W = (N + 63) / 64;
     const unsigned egrid = (unsigned)std::min<uint64_t>(cdiv(W, 8), EMIT_MAX_WG);
     const uint64_t wpw = (uint64_t)cdiv(cdiv(W, egrid), 8) * 8;
-    SAMP_LAUNCH("sampler_emit_kernel", sampler_emit_kernel, dim3(egrid), dim3(SAMP_NT), N, seed, step, state, bitmap, W, wpw,
-                wg_count);
+    if (prefix)
+        SAMP_LAUNCH("sampler_emit_kernel", sampler_emit_prefix_kernel, dim3(egrid), dim3(SAMP_NT), N, seed, step, state, bitmap, W,
+                    wpw, wg_count, (const uint32_t *)prefix);
+    else
+        SAMP_LAUNCH("sampler_emit_kernel", sampler_emit_kernel, dim3(egrid), dim3(SAMP_NT), N, seed, step, state, bitmap, W, wpw,
+                    wg_count);
     SAMP_LAUNCH("sampler_rank_kernel", sampler_rank_kernel, dim3(egrid), dim3(SAMP_NT), bitmap, W, wpw, wg_count, B, rank, S,
                 status);
     return SGNN_OK;
@@ -374,10 +480,11 @@ int sgnn_launch_sampler(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, ui
     uint64_t *cand_key = ws.get<uint64_t>(cap);
     uint32_t *cand_v = ws.get<uint32_t>(cap);
     uint32_t *wg_count = ws.get<uint32_t>(EMIT_MAX_WG);
+    uint32_t *prefix = prefix_bytes(N) ? ws.get<uint32_t>(prefix_bytes(N) / sizeof(uint32_t)) : nullptr;
     if (!ws.ok)
         return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_sample_uniform: scratch too small (%zu bytes needed): call sgnn_ctx_reserve",
                          ws.off);
-    return sampler_launches(ctx, N, B, seed, step, S, bitmap, rank, hist, state, cand_key, cand_v, cap, wg_count, ctx->status, st);
+    return sampler_launches(ctx, N, B, seed, step, S, bitmap, rank, hist, state, cand_key, cand_v, cap, wg_count, ctx->status, prefix, st);
 }
 
 // ---- the same sampler without any allocation: scratch in a file-scope device array ---------------------
@@ -463,5 +570,5 @@ extern "C" int sgnn_sample_uniform_static(uint64_t N, uint32_t B, uint64_t seed,
                 (uint32_t)((ST_STATUS - ST_HIST) / sizeof(uint32_t)));
     return sampler_launches(nullptr, N, B, seed, step, S, bitmap, rank, hist, state, reinterpret_cast<uint64_t *>(ptr + ST_CKEY),
                             reinterpret_cast<uint32_t *>(ptr + ST_CV), cand_capacity(N), reinterpret_cast<uint32_t *>(ptr + ST_WG),
-                            status, st);
+                            status, nullptr, st);      // no room for key prefixes in the static array: every pass recomputes the keys
 }

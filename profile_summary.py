@@ -4,7 +4,7 @@
     python3 profile_summary.py stats    <dir>/<name>_kernel_stats.csv        OUT.txt --cmd "<command that made it>"
     python3 profile_summary.py traffic  <fetch>_counter_collection.csv <write>_counter_collection.csv OUT.txt \
                                         --workload xlarge --cmd "<the two commands>"
-    python3 profile_summary.py counters <pmc>_counter_collection.csv OUT.txt --cmd "<command>"
+    python3 profile_summary.py counters <pmc>_counter_collection.csv OUT.txt --cmd "<command>" [--durations STATS.txt]
 
 stats:    per-kernel calls / total / average / share from `rocprofv3 --kernel-trace --stats` (libsgnn's kernels only).
 traffic:  HBM bytes per launch from two `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each
@@ -111,14 +111,25 @@ def cmd_counters(args):
     lines = ["# rocprofv3 --pmc counters per kernel launch (averages over the dispatches of a kernel)", "# command: " + args.cmd]
     if args.note:
         lines.append("# " + args.note)
-    lines.append("%-40s %6s " % ("kernel", "disp") + " ".join("%24s" % n[-24:] for n in names) + "   mfma_busy  wait_share")
+    dur = {}
+    if args.durations:       # a "stats" summary of the same workload: average duration per kernel
+        for ln in open(args.durations):
+            f = ln.split()
+            if len(f) >= 7 and f[-5].replace(".", "").isdigit() and not ln.startswith("#"):
+                dur[" ".join(f[:-6])] = float(f[-4])
+    lines.append("# mfma_busy = SQ_VALU_MFMA_BUSY_CYCLES / SQ_BUSY_CU_CYCLES as collected (the first is summed over the four SIMDs of a")
+    lines.append("# compute unit: divide by 4 for a per-SIMD share); mfma_share = SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x average")
+    lines.append("# duration x 2.4 GHz), the share of the launch during which a SIMD's matrix pipe was busy at the nominal clock")
+    lines.append("%-40s %6s " % ("kernel", "disp") + " ".join("%24s" % n[-24:] for n in names) + "   mfma_busy  wait_share  mfma_share")
     for k, v in sorted(acc.items(), key=lambda kv: -sum(x[1] for x in kv[1].values())):
         n = max(x[0] for x in v.values())
         avg = {c: v[c][1] / v[c][0] for c in v}
         busy = avg["SQ_VALU_MFMA_BUSY_CYCLES"] / avg["SQ_BUSY_CU_CYCLES"] if "SQ_VALU_MFMA_BUSY_CYCLES" in avg and avg.get("SQ_BUSY_CU_CYCLES") else None
         wait = avg["SQ_WAIT_INST_ANY"] / avg["SQ_WAVE_CYCLES"] if "SQ_WAIT_INST_ANY" in avg and avg.get("SQ_WAVE_CYCLES") else None
         lines.append("%-40s %6d " % (k[:40], n) + " ".join("%24.1f" % avg.get(c, float("nan")) for c in names) +
-                     "   %9s  %10s" % ("%.3f" % busy if busy is not None else "-", "%.3f" % wait if wait is not None else "-"))
+                     "   %9s  %10s" % ("%.3f" % busy if busy is not None else "-", "%.3f" % wait if wait is not None else "-") +
+                     ("  %10.3f" % (avg["SQ_VALU_MFMA_BUSY_CYCLES"] / (1024.0 * dur[k] * 2400.0))
+                      if k in dur and "SQ_VALU_MFMA_BUSY_CYCLES" in avg else "  %10s" % "-"))
     open(args.out, "w").write("\n".join(lines) + "\n")
     print("\n".join(lines[:14]))
 
@@ -130,6 +141,7 @@ def main():
     ap.add_argument("--cmd", default="")
     ap.add_argument("--note", default="")
     ap.add_argument("--workload", default="")
+    ap.add_argument("--durations", default="", help="counters: a stats summary of the same workload (adds mfma_share)")
     args = ap.parse_args()
     args.out = args.inputs.pop()
     {"stats": cmd_stats, "traffic": cmd_traffic, "counters": cmd_counters}[args.what](args)

@@ -15,6 +15,10 @@ pytestmark = pytest.mark.gpu
     (1, 1, 0, 0), (2, 1, 0, 0), (63, 17, 1, 2), (64, 64, 0, 0), (65, 64, 3, 1), (129, 1, 0, 5),
     (4096, 1024, 0, 0), (4096, 1024, 0, 1), (5000, 4999, 9, 9), (100003, 777, 2**40 + 3, 2**35 + 1),
     (262144, 32768, 0, 0), (262144, 32768, 0, 15), (1000003, 1000003, 4, 4), (1000003, 250000, 5, 6),
+    # from 2^20 vertices on the later passes read stored key prefixes: even and odd N, ragged last quad and last word,
+    # B = N, nearly all, a handful
+    (1048576, 1000, 1, 1), (1048577, 1048577, 2, 3), (1048583, 5, 3, 0), (2097213, 1048576, 8, 8), (1048583, 1048576, 0, 2),
+    (3000001, 300000, 11, 2**33),
 ])
 def test_sampler_matches_oracle(N, B, seed, step):
     S, bitmap, rank = gpu_sample(N, B, seed, step)
