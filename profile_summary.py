@@ -33,8 +33,9 @@ def short(n: str) -> str:
                                                  "T" if m.group(5) == "true" else "N", "bf16" if m.group(6) == "true" else "f32")
     m = re.match(r"gemm_direct_kernel<(\d+), \d+, \d+, (\w+), (\w+), (\w+)>", n)
     if m:
-        return "gemm_direct_kernel<%sx128,%s%s,f32>" % (m.group(1), "T" if m.group(2) == "true" else "N",
-                                                        "T" if m.group(3) == "true" else "N")
+        # bench.py files the direct-to-LDS kernel under gemm_kernel with its tile shape
+        return "gemm_kernel<%sx128,%s%s,f32>" % (m.group(1), "T" if m.group(2) == "true" else "N",
+                                                 "T" if m.group(3) == "true" else "N")
     if n.startswith("gemm_thin_tn_kernel"):
         return "gemm_kernel<thin32,TN,f32>"
     if n.startswith("gemm_smallk_nt_kernel"):

@@ -777,6 +777,12 @@ def test_whole_step_large_bf16():
     _run_config("large", [0], True)
 
 
+def test_whole_step_large_bf16_storage():
+    # the same graph in the configuration bench.py times: activations, hand-down gradients and the loss gradient
+    # stored as bfloat16 (another sampler counter than the fp32-storage test above)
+    _run_config("large", [1], True, bf16_act=True)
+
+
 def test_whole_step_dense():
     # social-shaped graph at full size: mean degree about 490, |S| = 65536, 602 input features
     _run_config("dense", [0], True)
