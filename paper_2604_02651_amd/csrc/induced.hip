@@ -141,16 +141,36 @@ __device__ __forceinline__ void tile_rows(const uint32_t *__restrict__ tile_row,
     nr = r_hi - r_lo + 1;
 }
 
-__device__ __forceinline__ bool stage_tile(tile_table &tt, const int64_t *__restrict__ rowstart,
-                                           const uint64_t *__restrict__ P, uint64_t f0, uint32_t r_lo, uint32_t nr)
+// Staging of a tile's row table.  The first IND_NT rows arrive in registers: (p, rs) of row r_lo + threadIdx.x, requested
+// while the tile before this one was being worked on (tile_prefetch), so that the two round trips that fetch a
+// tile's rows - tile_row, then P / row starts - are off its critical path.
+struct tile_pref {
+    uint64_t p;
+    int64_t rs;
+};
+
+__device__ __forceinline__ tile_pref tile_prefetch(const int64_t *__restrict__ rowstart, const uint64_t *__restrict__ P,
+                                                   bool valid, uint32_t r_lo, uint32_t nr)
+{
+    tile_pref t = {0, 0};
+    if (valid && threadIdx.x < nr && nr <= (uint32_t)IND_ROWS + 1) {
+        t.p = P[r_lo + threadIdx.x];
+        t.rs = rowstart[r_lo + threadIdx.x];
+    }
+    return t;
+}
+
+__device__ __forceinline__ bool stage_tile_prefetched(tile_table &tt, const tile_pref &pf, const int64_t *__restrict__ rowstart,
+                                                      const uint64_t *__restrict__ P, uint64_t f0, uint32_t r_lo, uint32_t nr)
 {
     const bool staged = nr <= (uint32_t)IND_ROWS + 1;
     if (staged) {
         for (uint32_t k = threadIdx.x; k < nr; k += IND_NT) {
-            const uint64_t p = P[r_lo + k];
+            const uint64_t p = k < IND_NT ? pf.p : P[r_lo + k];
+            const int64_t rs = k < IND_NT ? pf.rs : rowstart[r_lo + k];
             const int64_t rel = (int64_t)p - (int64_t)f0;      // signed on purpose: the row may start in front of the tile
             tt.relP[k] = rel < 0 ? -1 : (rel > IND_TILE ? IND_TILE : (int32_t)rel);
-            tt.ebase[k] = rowstart[r_lo + k] - (int64_t)p;
+            tt.ebase[k] = rs - (int64_t)p;
         }
     }
     __syncthreads();
@@ -202,11 +222,19 @@ __global__ __launch_bounds__(IND_NT) void induced_count_kernel(const int64_t *__
     const uint64_t n_tiles = (F + IND_TILE - 1) / IND_TILE;
     if (blockIdx.x == 0 && threadIdx.x == 0) *n_tiles_out = n_tiles;
     unsigned long long wg_total = 0;      // 64 bits: the 32-bit prefix over the tile counts wraps beyond 2^32 survivors
-    for (uint64_t c = blockIdx.x; c < n_tiles; c += gridDim.x) {
+    // software pipeline over the workgroup's tiles: the rows of the tile after next and the table of the next tile are
+    // requested before the current tile's edges are
+    const uint64_t g = gridDim.x;
+    uint32_t r_lo = 0, nr = 0, r_lo1 = 0, nr1 = 0;
+    if (blockIdx.x < n_tiles) tile_rows(tile_row, blockIdx.x, n_tiles, B, r_lo, nr);
+    if (blockIdx.x + g < n_tiles) tile_rows(tile_row, blockIdx.x + g, n_tiles, B, r_lo1, nr1);
+    tile_pref pf = tile_prefetch(rowstart, P, blockIdx.x < n_tiles, r_lo, nr);
+    for (uint64_t c = blockIdx.x; c < n_tiles; c += g) {
         const uint64_t f0 = c * IND_TILE, f1 = min(F, f0 + IND_TILE);
-        uint32_t r_lo, nr;
-        tile_rows(tile_row, c, n_tiles, B, r_lo, nr);
-        const bool staged = stage_tile(tt, rowstart, P, f0, r_lo, nr);
+        const bool staged = stage_tile_prefetched(tt, pf, rowstart, P, f0, r_lo, nr);
+        uint32_t r_lo2 = 0, nr2 = 0;
+        if (c + 2 * g < n_tiles) tile_rows(tile_row, c + 2 * g, n_tiles, B, r_lo2, nr2);
+        pf = tile_prefetch(rowstart, P, c + g < n_tiles, r_lo1, nr1);
         int32_t x[IND_ITEMS], u[IND_ITEMS];
         uint32_t rk[IND_ITEMS];
 #pragma unroll
@@ -255,6 +283,7 @@ __global__ __launch_bounds__(IND_NT) void induced_count_kernel(const int64_t *__
         }
         const uint32_t t = block_sum<uint32_t, IND_NT>(cnt, lds);   // ends with a barrier: tt may be reused
         if (threadIdx.x == 0) { tile_total[c] = t; wg_total += t; }
+        r_lo = r_lo1; nr = nr1; r_lo1 = r_lo2; nr1 = nr2;
     }
     if (threadIdx.x == 0 && wg_total) atomicAdd(total64, wg_total);     // integer: the sum does not depend on the order
 }
@@ -293,22 +322,40 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
         if (n_tiles == 0)       // not a single edge: every row is empty
             for (uint32_t r = threadIdx.x; r < B; r += IND_NT) rowptr_S[r] = 0;
     }
-    for (uint64_t c = blockIdx.x; c < n_tiles; c += gridDim.x) {
+    // software pipeline over the workgroup's tiles, as in the count pass: the next tile's keep words, offset and row
+    // table are requested while the current tile's survivors are gathered
+    const uint64_t g = gridDim.x;
+    uint32_t r_lo = 0, nr = 0, r_lo1 = 0, nr1 = 0;
+    if (blockIdx.x < n_tiles) tile_rows(tile_row, blockIdx.x, n_tiles, B, r_lo, nr);
+    if (blockIdx.x + g < n_tiles) tile_rows(tile_row, blockIdx.x + g, n_tiles, B, r_lo1, nr1);
+    tile_pref pf = tile_prefetch(rowstart, P, blockIdx.x < n_tiles, r_lo, nr);
+    uint64_t kw = 0;               // wavefront 0: keep word `lane` of the tile
+    uint32_t tile_off = 0;         // survivors in earlier tiles (exclusive prefix of the tile counts)
+    if (blockIdx.x < n_tiles) {
+        if (wave == 0 && lane < IND_WORDS) kw = keepbits[(uint64_t)blockIdx.x * IND_WORDS + lane];
+        tile_off = tile_off_all[blockIdx.x];
+    }
+    for (uint64_t c = blockIdx.x; c < n_tiles; c += g) {
         const uint64_t f0 = c * IND_TILE, f1 = min(F, f0 + IND_TILE);
         const uint32_t tile_len = (uint32_t)(f1 - f0);
         const bool last = c + 1 == n_tiles;
-        const uint32_t tile_off = tile_off_all[c];     // survivors in earlier tiles (exclusive prefix of the tile counts)
-        uint32_t r_lo, nr;
-        tile_rows(tile_row, c, n_tiles, B, r_lo, nr);
         if (wave == 0) {
-            uint64_t w = 0;
-            if (lane < IND_WORDS) { w = keepbits[c * IND_WORDS + lane]; balw[lane] = w; }
+            const uint64_t w = lane < IND_WORDS ? kw : 0ull;
+            if (lane < IND_WORDS) balw[lane] = w;
             const uint32_t pc = (uint32_t)__popcll(w);
             const uint32_t inc = wave_incl_scan(pc);
             if (lane < IND_WORDS) pre[lane] = inc - pc;
             if (lane == IND_WORDS - 1) pre[IND_WORDS] = inc;
         }
-        const bool staged = stage_tile(tt, rowstart, P, f0, r_lo, nr);     // ends with a barrier
+        const bool staged = stage_tile_prefetched(tt, pf, rowstart, P, f0, r_lo, nr);     // ends with a barrier
+        const uint32_t tile_off_cur = tile_off;
+        uint32_t r_lo2 = 0, nr2 = 0;
+        if (c + 2 * g < n_tiles) tile_rows(tile_row, c + 2 * g, n_tiles, B, r_lo2, nr2);
+        pf = tile_prefetch(rowstart, P, c + g < n_tiles, r_lo1, nr1);
+        if (c + g < n_tiles) {
+            if (wave == 0 && lane < IND_WORDS) kw = keepbits[(c + g) * IND_WORDS + lane];
+            tile_off = tile_off_all[c + g];
+        }
 
         // row offsets.  A row that starts right at the end of the tile is empty if it is not the row the next
         // tile begins with (that tile writes that one); behind the last tile every such row is empty.
@@ -322,8 +369,8 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
             if (x < 0) continue;
             if (x < (int64_t)tile_len) {
                 const uint32_t wd = ((uint32_t)x / IND_NT) * (IND_NT / 64) + (((uint32_t)x % IND_NT) >> 6);
-                rowptr_S[r_lo + k] = (int32_t)(tile_off + pre[wd] + (uint32_t)__popcll(balw[wd] & ((1ull << (x & 63)) - 1ull)));
-            } else if (x == (int64_t)tile_len && (last || k + 1 < nr)) rowptr_S[r_lo + k] = (int32_t)(tile_off + pre[IND_WORDS]);
+                rowptr_S[r_lo + k] = (int32_t)(tile_off_cur + pre[wd] + (uint32_t)__popcll(balw[wd] & ((1ull << (x & 63)) - 1ull)));
+            } else if (x == (int64_t)tile_len && (last || k + 1 < nr)) rowptr_S[r_lo + k] = (int32_t)(tile_off_cur + pre[IND_WORDS]);
         }
 
         // survivors
@@ -367,7 +414,7 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
         for (int k = 0; k < IND_ITEMS; ++k) {
             if (u[k] < 0) continue;
             const uint32_t wd = k * (IND_NT / 64) + wave;
-            const uint32_t pos = tile_off + pre[wd] + (uint32_t)__popcll(balw[wd] & below);
+            const uint32_t pos = tile_off_cur + pre[wd] + (uint32_t)__popcll(balw[wd] & below);
             if (pos >= capacity) continue;
             colidx_S[pos] = (int32_t)(rnk[k] + (uint32_t)__popcll(word[k] & ((1ull << (u[k] & 63)) - 1ull)));
             if (write_val) {
@@ -390,6 +437,7 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
             }
         }
         __syncthreads();   // the keep words and the row table are reused by the next tile
+        r_lo = r_lo1; nr = nr1; r_lo1 = r_lo2; nr1 = nr2;
     }
 }
 
@@ -445,7 +493,13 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
                 rg, deg, rowstart, deg_sum, total64);
     SGNN_LAUNCH(ctx, st, "induced_offsets_kernel", SGNN_TAG, induced_offsets_kernel, dim3(n_deg_wg), dim3(256), 0, st, deg, B,
                 deg_sum, P, tile_row);
-    const unsigned grid = (unsigned)std::min<uint64_t>(max_tiles, IND_MAX_GRID);
+    // Workgroups walk their tiles in a software pipeline (the next tile's row table is requested while the current
+    // tile's edges are gathered).  Where the expected number of tiles, E B / N / 2048, is a few times the 2048
+    // workgroups of the count pass that are resident at once, exactly those are launched (large graph: 94 -> 78 us);
+    // with more tiles the larger grid measured better (the chip is then full anyway), as it does for the fill pass.
+    const uint64_t expected_tiles = (uint64_t)((double)g->E * (double)B / (double)std::max<uint64_t>(g->N, 1) / IND_TILE);
+    const unsigned grid_fill = (unsigned)std::min<uint64_t>(max_tiles, IND_MAX_GRID);
+    const unsigned grid = (expected_tiles >= 2048 && expected_tiles < IND_MAX_GRID) ? 2048u : grid_fill;
     if (use_coarse)
         SGNN_LAUNCH(ctx, st, "induced_coarse_kernel", SGNN_TAG, induced_coarse_kernel, dim3((unsigned)std::min<uint64_t>(cdiv(W, 256), 4096)),
                     dim3(256), 0, st, bitmap, W, coarse);
@@ -455,7 +509,7 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
     if (rc) return rc;
     double p = 1.0;
     if (rescale && B > 1) p = ((double)B - 1.0) / ((double)g->N - 1.0);
-    SGNN_LAUNCH(ctx, st, "induced_fill_kernel", SGNN_TAG, induced_fill_kernel<RP>, dim3(grid), dim3(IND_NT), 0, st, rowptr,
+    SGNN_LAUNCH(ctx, st, "induced_fill_kernel", SGNN_TAG, induced_fill_kernel<RP>, dim3(grid_fill), dim3(IND_NT), 0, st, rowptr,
                 g->colidx, norm_mode == 0 ? g->val : nullptr, S, rowstart, deg, B, bitmap, rank, P, tile_row, tile_off,
                 n_tiles, keepbits, (float)(1.0 / p), norm_mode == 0 ? 1 : 0, out->rowptr, out->colidx, out->val,
                 out->capacity, out->nnz_dev, ctx->status, total64, sticky_capacity);
