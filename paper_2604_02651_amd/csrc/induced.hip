@@ -300,7 +300,7 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
     const uint32_t *__restrict__ tile_row, const uint32_t *__restrict__ tile_off_all, const uint64_t *__restrict__ n_tiles_p, const uint64_t *__restrict__ keepbits, float inv_p, int write_val,
     int32_t *__restrict__ rowptr_S, int32_t *__restrict__ colidx_S, float *__restrict__ val_S, uint64_t capacity,
     uint32_t *__restrict__ nnz_dev, uint32_t *__restrict__ status, const unsigned long long *__restrict__ total64,
-    int sticky_capacity)
+    int sticky_capacity, int deg_by_rank)
 {
     __shared__ tile_table tt;
     __shared__ uint64_t balw[IND_WORDS];
@@ -406,8 +406,16 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
             if (u[k] >= 0) {
                 word[k] = bitmap[(uint32_t)u[k] >> 6];
                 rnk[k] = rank[(uint32_t)u[k] >> 6];
-                if (write_val && !gval) du[k] = (int64_t)rowptr[(int64_t)u[k] + 1] - (int64_t)rowptr[u[k]];
+                if (write_val && !gval && !deg_by_rank) du[k] = (int64_t)rowptr[(int64_t)u[k] + 1] - (int64_t)rowptr[u[k]];
             }
+        }
+        // compact column ids; a surviving column is itself a sampled vertex, so with every sampled row inside the row
+        // range its degree is already in deg[] (B entries, cache resident) and need not be gathered from rowptr
+        uint32_t cid[IND_ITEMS];
+#pragma unroll
+        for (int k = 0; k < IND_ITEMS; ++k) {
+            cid[k] = rnk[k] + (uint32_t)__popcll(word[k] & ((1ull << (u[k] & 63)) - 1ull));
+            if (u[k] >= 0 && write_val && !gval && deg_by_rank) du[k] = (int64_t)deg[min(cid[k], B - 1)];
         }
         const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
@@ -416,7 +424,7 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
             const uint32_t wd = k * (IND_NT / 64) + wave;
             const uint32_t pos = tile_off_cur + pre[wd] + (uint32_t)__popcll(balw[wd] & below);
             if (pos >= capacity) continue;
-            colidx_S[pos] = (int32_t)(rnk[k] + (uint32_t)__popcll(word[k] & ((1ull << (u[k] & 63)) - 1ull)));
+            colidx_S[pos] = (int32_t)cid[k];
             if (write_val) {
                 const uint32_t r = r_lo + rk[k];
                 const int64_t v = S[r];
@@ -512,7 +520,8 @@ int launch_typed(sgnn_ctx *ctx, const sgnn_graph *g, const int32_t *S, uint32_t 
     SGNN_LAUNCH(ctx, st, "induced_fill_kernel", SGNN_TAG, induced_fill_kernel<RP>, dim3(grid_fill), dim3(IND_NT), 0, st, rowptr,
                 g->colidx, norm_mode == 0 ? g->val : nullptr, S, rowstart, deg, B, bitmap, rank, P, tile_row, tile_off,
                 n_tiles, keepbits, (float)(1.0 / p), norm_mode == 0 ? 1 : 0, out->rowptr, out->colidx, out->val,
-                out->capacity, out->nnz_dev, ctx->status, total64, sticky_capacity);
+                out->capacity, out->nnz_dev, ctx->status, total64, sticky_capacity,
+                (rg.r0 <= 0 && rg.r1 >= (int64_t)g->N) ? 1 : 0);
     if (norm_mode == 1)
         SGNN_LAUNCH(ctx, st, "induced_renorm_kernel", SGNN_TAG, induced_renorm_kernel, dim3(cdiv((uint64_t)B * 64, 256)),
                     dim3(256), 0, st, out->rowptr, out->colidx, out->val, B, out->capacity, p);
