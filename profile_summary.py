@@ -27,7 +27,7 @@ SKIP = ("at::", "rocprim", "Cijk", "__amd_rocclr", "vectorized", "elementwise_ke
 def short(n: str) -> str:
     n = n.replace("(anonymous namespace)::", "").replace("void ", "")
     n = re.sub(r"\((?:[^()]|\([^()]*\))*\)$", "", n).strip()
-    m = re.match(r"gemm_(fast_)?kernel<(\d+), (\d+), \d+, \d+, (\w+), (\w+), (\w+)(, \w+)?>", n)
+    m = re.match(r"gemm_(fast_)?kernel<(\d+), (\d+), \d+, \d+, (\w+), (\w+), (\w+)(, \w+)*>", n)
     if m:
         return "gemm_kernel<%sx%s,%s%s,%s>" % (m.group(2), m.group(3), "T" if m.group(4) == "true" else "N",
                                                  "T" if m.group(5) == "true" else "N", "bf16" if m.group(6) == "true" else "f32")
