@@ -67,6 +67,9 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="same as --graph off")
     ap.add_argument("--no-overlap", action="store_true",
                     help="everything on one stream (default: the next mini-batch is sampled on a second stream while this one trains)")
+    ap.add_argument("--fuse-loss", choices=["auto", "off", "keep-logits", "drop-logits"], default="auto",
+                    help="last layer: the loss in the epilogue of the sparse product (auto: the step's own choice, from 2^19 "
+                         "sampled vertices on, logits still written); drop-logits does not write the logits at all")
     ap.add_argument("--fp32-loss-grad", action="store_true", help="keep the loss gradient dO in fp32 (default: bfloat16 with the activations)")
     ap.add_argument("--fp32-activations", action="store_true",
                     help="with bf16 GEMM operands, keep the forward activations in fp32 storage (default: bf16 storage)")
@@ -125,6 +128,9 @@ def measure(args, sg, si, torch, cfg, g, X, labels, weights, use_graph_req: str,
             kw["bf16_activations"] = cfg.bf16_mfma and not args.fp32_activations
         if args.fp32_loss_grad:
             kw["bf16_loss_grad"] = False
+        if args.fuse_loss != "auto":
+            kw["fuse_loss"] = args.fuse_loss != "off"
+            kw["keep_logits"] = args.fuse_loss != "drop-logits"
         st = sg.GcnStep(cfg.N, g.rowptr, g.colidx, X, labels, weights, cfg.B, cfg.sampler_seed, bf16=cfg.bf16_mfma,
                         fuse_slice=not args.no_fuse_slice, device=dev, fuse_relu_bwd=not args.no_fuse_relu_bwd,
                         side_dw=args.side_dw, **kw)
@@ -285,7 +291,7 @@ def measure(args, sg, si, torch, cfg, g, X, labels, weights, use_graph_req: str,
                                   else "GCN " + "-".join(map(str, cfg.dims)), feat, act, K,
                                   ("0..%d" % (K - 1)) if not use_graph or cyc >= K else
                                   ("0..%d repeated (cycle of %d captured steps)" % (cyc - 1, cyc))),
-                   "fuse_slice": not args.no_fuse_slice, "fuse_relu_bwd": not args.no_fuse_relu_bwd,
+                   "fuse_slice": not args.no_fuse_slice, "fuse_relu_bwd": not args.no_fuse_relu_bwd, "fuse_loss": ("keep-logits" if st.keep_logits else "drop-logits") if getattr(st, "fuse_loss", False) else "off",
                    "side_stream_dw": args.side_dw and not args.no_overlap,
                    "overlap_sampling": not args.no_overlap, "hip_graph": use_graph,
                    "graph_steps": n_graph, "eager_steps": K - n_graph,

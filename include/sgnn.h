@@ -361,6 +361,22 @@ int sgnn_softmax_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t 
                       sgnn_stream stream);
 
 /*
+ * The last layer of a transform-first stack and its loss in one pass (Sec. V "Kernel Fusion": the logits are
+ * not read back from memory): O = A X + bias (Eq. 5 with the layer's H W as X, Sec. III-B), the mean softmax
+ * cross-entropy of O's rows against `labels` and its gradient dO = (softmax(O) - onehot(label)) / A.rows, as
+ * sgnn_spmm followed by sgnn_softmax_xent would give them (same arithmetic per row; the sums over the rows are
+ * taken in another, equally fixed order: bit-reproducible from run to run).
+ *   X       A.cols x C, fp32 or bfloat16, no row_index;  bias  device fp32[C] or NULL;  labels  device int32[A.rows]
+ *   O       out A.rows x C fp32, or NULL when the caller does not keep the logits
+ *   loss_dev, dO, dO_dtype, lddo, dO_colsum   as in sgnn_softmax_xent (dO may be NULL)
+ * Up to 512 classes run in one kernel; wider or oddly aligned operands take the two kernels one after the other
+ * (with the logits in the context scratch when O is NULL).
+ */
+int sgnn_spmm_xent(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const float *bias, const int32_t *labels,
+                   sgnn_mat *O, float *loss_dev, void *dO, int dO_dtype, int64_t lddo, float *dO_colsum,
+                   sgnn_stream stream);
+
+/*
  * Mean binary cross-entropy on logits over the B x C entries, the paper's loss for multi-label tasks
  * (Sec. III-B), and its gradient dO = (logistic(O) - Y) / (B C).  Y: fp32 targets in [0, 1], B x C.
  * loss_dev: device float[1] or NULL; dO may be NULL.  Fixed summation order.

@@ -100,13 +100,14 @@ def lib():
         L.sgnn_sigmoid_bce.argtypes = [vp, vp, i64, vp, i64, u32, u32, vp, vp, i64, vp]
         L.sgnn_colsum.argtypes = [vp, C.POINTER(_Mat), vp, vp]
         L.sgnn_softmax_xent.argtypes = [vp, vp, i64, vp, u32, u32, vp, vp, C.c_int, i64, vp, vp]
+        L.sgnn_spmm_xent.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), vp, vp, C.POINTER(_Mat), vp, vp, C.c_int, i64, vp, vp]
         L.sgnn_spmm.argtypes = [vp, C.POINTER(_Csr), C.POINTER(_Mat), C.POINTER(_Mat), C.POINTER(_Mat), vp]
         L.sgnn_copy_f32.argtypes = [vp, vp, vp, i64, vp]
         L.sgnn_gemm.argtypes = [vp, ci, ci, i64, i64, i64, vp, ci, i64, vp, ci, i64, vp, ci, vp, ci, i64, vp, ci, i64, vp, vp]
         for name in ("sgnn_ctx_create", "sgnn_ctx_destroy", "sgnn_ctx_reserve", "sgnn_ctx_status",
                      "sgnn_ctx_profile", "sgnn_ctx_profile_read",
                      "sgnn_sample_uniform", "sgnn_induced_csr", "sgnn_csr_plan", "sgnn_gather_rows", "sgnn_gcn_fwd", "sgnn_gcn_bwd", "sgnn_tail_fwd", "sgnn_tail_bwd", "sgnn_gemm_tail_fwd", "sgnn_sgd_step", "sgnn_adam_step", "sgnn_graph_normalized_csr", "sgnn_induced_csr_range", "sgnn_csr_transpose", "sgnn_sigmoid_bce", "sgnn_colsum",
-                     "sgnn_softmax_xent", "sgnn_spmm", "sgnn_gemm", "sgnn_copy_f32"):
+                     "sgnn_softmax_xent", "sgnn_spmm_xent", "sgnn_spmm", "sgnn_gemm", "sgnn_copy_f32"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -426,6 +427,29 @@ def sgnn_softmax_xent(ctx: Context, O: torch.Tensor, labels: torch.Tensor, loss:
                                       _ptr(dO, dO.dtype if dO is not None and dO.dtype == torch.bfloat16 else torch.float32, "dO"),
                                       _dt(dO, "dO"), dO.stride(0) if dO is not None else 0,
                                       _ptr(dO_colsum, torch.float32, "dO_colsum"), _stream(stream)))
+
+
+def sgnn_spmm_xent(ctx: Context, A: Csr, X: torch.Tensor, bias: Optional[torch.Tensor], labels: torch.Tensor,
+                   loss: Optional[torch.Tensor], dO: Optional[torch.Tensor], O: Optional[torch.Tensor] = None,
+                   dO_colsum: Optional[torch.Tensor] = None, stream=None):
+    """O = A X + bias, its mean softmax cross-entropy against labels and the gradient dO, in one pass.  O None: the
+    logits are not kept."""
+    a = A.struct()
+    x = _mat(X, None, "X", allow_bf16=True)
+    o = _mat(O, None, "O") if O is not None else None
+    if bias is not None and bias.numel() != X.shape[1]:
+        raise ValueError("bias must have one element per class")
+    if dO is not None and (tuple(dO.shape) != (A.rows, X.shape[1]) or dO.stride(1) != 1):
+        raise ValueError("dO must be rows x classes with unit column stride")
+    if dO_colsum is not None and dO_colsum.numel() != X.shape[1]:
+        raise ValueError("dO_colsum must have one element per class")
+    if labels.numel() != A.rows:
+        raise ValueError("one label per row")
+    ctx.check(lib().sgnn_spmm_xent(ctx._h, C.byref(a), C.byref(x), _ptr(bias, torch.float32, "bias"), _ptr(labels, torch.int32, "labels"),
+                                   C.byref(o) if o is not None else None, _ptr(loss, torch.float32, "loss"),
+                                   _ptr(dO, dO.dtype if dO is not None and dO.dtype == torch.bfloat16 else torch.float32, "dO"),
+                                   _dt(dO, "dO"), dO.stride(0) if dO is not None else 0, _ptr(dO_colsum, torch.float32, "dO_colsum"),
+                                   _stream(stream)))
 
 
 def sgnn_spmm(ctx: Context, A: Csr, X: torch.Tensor, out: torch.Tensor, row_index: Optional[torch.Tensor] = None,

@@ -345,6 +345,38 @@ int sgnn_spmm(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const sgnn_ma
                               static_cast<hipStream_t>(stream));
 }
 
+int sgnn_spmm_xent(sgnn_ctx *ctx, const sgnn_csr *A, const sgnn_mat *X, const float *bias, const int32_t *labels, sgnn_mat *O,
+                   float *loss_dev, void *dO, int dO_dtype, int64_t lddo, float *dO_colsum, sgnn_stream stream)
+{
+    if (!ctx) return SGNN_ERR_INVALID_ARG;
+    if (!csr_ok(A) || !mat_ok_in(X) || X->row_index || !labels || (O && (!mat_ok(O) || O->row_index)) ||
+        (dO && dO_dtype != SGNN_F32 && dO_dtype != SGNN_BF16) || (dO_colsum && !dO))
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm_xent: bad argument");
+    const int64_t d = X->cols;
+    if (X->rows != A->cols || (O && (O->rows != A->rows || O->cols != d)) || (dO && lddo < d) || A->rows == 0 || d == 0)
+        return sgnn_fail(ctx, SGNN_ERR_INVALID_ARG, "sgnn_spmm_xent: shape mismatch");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ws_alloc ws(ctx);
+    rc = sgnn_launch_spmm_xent(ctx, A, X->ptr, X->dtype == SGNN_BF16, X->ld, d, bias, labels, O ? static_cast<float *>(O->ptr) : nullptr,
+                               O ? O->ld : 0, loss_dev, dO, dO_dtype == SGNN_BF16, lddo, dO_colsum, &ws, st);
+    if (rc != SGNN_ERR_UNSUPPORTED) return rc;
+    // a shape the fused kernels do not take: the product, then the loss kernel (logits in scratch if the caller keeps none)
+    ws_alloc ws2(ctx);
+    float *logits = O ? static_cast<float *>(O->ptr) : nullptr;
+    int64_t ldl = O ? O->ld : pad_ld(d, false);
+    if (!logits) {
+        logits = ws2.get<float>((size_t)A->rows * ldl);
+        if (!ws2.ok) return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_spmm_xent: scratch too small: call sgnn_ctx_reserve");
+    }
+    rc = sgnn_launch_spmm_x(ctx, A, X->ptr, X->dtype == SGNN_BF16, X->ld, nullptr, d, logits, 0, ldl, bias, 0, nullptr, 0, 0, nullptr, 0,
+                            &ws2, st);
+    if (rc) return rc;
+    return sgnn_launch_xent(ctx, logits, ldl, labels, A->rows, (uint32_t)d, loss_dev, dO, dO_dtype == SGNN_BF16 ? 1 : 0, lddo, dO_colsum,
+                            &ws2, st);
+}
+
 int sgnn_gemm(sgnn_ctx *ctx, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int a_dtype, int64_t lda,
               const void *B, int b_dtype, int64_t ldb, const float *bias, int flags, void *C, int c_dtype, int64_t ldc,
               const void *mask, int mask_dtype, int64_t ldm, float *b_colsum, sgnn_stream stream)

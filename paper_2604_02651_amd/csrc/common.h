@@ -150,5 +150,15 @@ int sgnn_launch_adam(sgnn_ctx *ctx, float *w, const float *g, float *m, float *v
                      double eps, int64_t t, hipStream_t st);
 int sgnn_launch_graph_normalize(sgnn_ctx *ctx, const sgnn_graph *g, int32_t *rowptr32, float *val, hipStream_t st);
 int sgnn_launch_copy(sgnn_ctx *ctx, const float *src, float *dst, int64_t n, hipStream_t st);
+// mean loss and column sums from the per-workgroup partial sums of a loss kernel (n rows of partial sums)
+// fix (may be null): fix_slots rows of cols + 1 fixed-point sums (64-bit integers; column `cols` holds loss terms) that are
+// added in as well, scaled by cs_unit / loss_unit
+int sgnn_launch_xent_final(sgnn_ctx *ctx, const float *partial, int n, float inv_rows, float *loss, const float *cs_partial, int cols,
+                           float *colsum, const unsigned long long *fix, int fix_slots, double cs_unit, double loss_unit, hipStream_t st);
+// O = A X + bias, mean softmax cross-entropy of O against labels and its gradient, in one kernel (SGNN_ERR_UNSUPPORTED,
+// nothing launched, for shapes the fused kernels do not take); out may be null (logits not kept)
+int sgnn_launch_spmm_xent(sgnn_ctx *ctx, const sgnn_csr *A, const void *X, int x_bf16, int64_t ldx, int64_t d, const float *bias,
+                          const int32_t *labels, float *out, int64_t ldo, float *loss, void *dO, int dO_bf16, int64_t lddo,
+                          float *dO_colsum, ws_alloc *ws, hipStream_t st);
 int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *labels, uint32_t B, uint32_t C,
                      float *loss, void *dO, int do_bf16, int64_t lddo, float *dO_colsum, ws_alloc *ws, hipStream_t st);

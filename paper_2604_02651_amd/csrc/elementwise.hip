@@ -229,17 +229,31 @@ __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, 
 
 // Workgroup 0: the mean loss from the partial losses.  Workgroups 1 ..: 16 columns each of the column sums of
 // dO, from the partial sums of the loss kernel's workgroups, added as colsum_final_kernel adds its partial sums.
+// fix: optional fixed-point sums (64-bit integers, fix_slots rows of cols + 1, column `cols` = loss terms) added in
+// exactly: integer addition, one conversion at the end.
 __global__ __launch_bounds__(1024) void xent_final_kernel(const float *__restrict__ partial, int n, float invB,
                                                           float *__restrict__ loss, const float *__restrict__ cs_partial,
-                                                          int cols, float *__restrict__ colsum)
+                                                          int cols, float *__restrict__ colsum,
+                                                          const unsigned long long *__restrict__ fix, int fix_slots, double cs_unit,
+                                                          double loss_unit)
 {
     __shared__ float lds[1024];
+    __shared__ long long lfix[1024];
     if (blockIdx.x == 0) {
         if (!loss) return;
         float s = 0.f;
         for (int i = threadIdx.x; i < n; i += 1024) s += partial[i];
         s = block_sum<float, 1024>(s, lds);
-        if (threadIdx.x == 0) *loss = s * invB;
+        long long f = 0;
+        if (fix)
+            for (int k = threadIdx.x; k < fix_slots; k += 1024) f += (long long)fix[(int64_t)k * (cols + 1) + cols];
+        lfix[threadIdx.x] = f;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            long long ft = 0;
+            for (int k = 0; k < 1024; ++k) ft += lfix[k];          // integers: the order does not matter
+            *loss = (s + (float)((double)ft * loss_unit)) * invB;
+        }
         return;
     }
     // 16 columns x 64 groups of partial rows per workgroup: with 64 columns and 16 groups the three or four workgroups
@@ -252,11 +266,17 @@ __global__ __launch_bounds__(1024) void xent_final_kernel(const float *__restric
         for (int w = ty; w < n; w += 64) s += cs_partial[(int64_t)w * cols + col];
     }
     lds[threadIdx.x] = s;
+    long long f = 0;
+    if (fix && col < cols)
+        for (int k = ty; k < fix_slots; k += 64) f += (long long)fix[(int64_t)k * (cols + 1) + col];
+    lfix[threadIdx.x] = f;
     __syncthreads();
     if (ty == 0 && col < cols) {
         float t = 0.f;
+        long long ft = 0;
 #pragma unroll
-        for (int w = 0; w < 64; ++w) t += lds[w * 16 + tx];
+        for (int w = 0; w < 64; ++w) { t += lds[w * 16 + tx]; ft += lfix[w * 16 + tx]; }
+        if (fix) t += (float)((double)ft * cs_unit);
         colsum[col] = t;
     }
 }
@@ -396,8 +416,16 @@ int sgnn_launch_xent(sgnn_ctx *ctx, const float *O, int64_t ldo, const int32_t *
 #undef SGNN_XENT
     if (loss || dO_colsum) {
         SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1 + (dO_colsum ? cdiv(C, 16) : 0)), dim3(1024), 0, st,
-                    partial, (int)nwg, 1.f / (float)B, loss, cs_partial, (int)C, dO_colsum);
+                    partial, (int)nwg, 1.f / (float)B, loss, cs_partial, (int)C, dO_colsum, (const unsigned long long *)nullptr, 0, 0.0, 0.0);
     }
+    return SGNN_OK;
+}
+
+int sgnn_launch_xent_final(sgnn_ctx *ctx, const float *partial, int n, float inv_rows, float *loss, const float *cs_partial, int cols,
+                           float *colsum, const unsigned long long *fix, int fix_slots, double cs_unit, double loss_unit, hipStream_t st)
+{
+    SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1 + ((colsum && cs_partial) ? cdiv(cols, 16) : 0)), dim3(1024),
+                0, st, partial, n, inv_rows, loss, cs_partial, cols, colsum, fix, fix_slots, cs_unit, loss_unit);
     return SGNN_OK;
 }
 
@@ -428,6 +456,6 @@ int sgnn_launch_bce(sgnn_ctx *ctx, const float *O, int64_t ldo, const float *Y, 
     SGNN_LAUNCH(ctx, st, "bce_kernel", SGNN_TAG, bce_kernel, dim3(nwg), dim3(256), 0, st, O, ldo, Y, ldy, B, C, inv, dO, lddo, partial);
     if (loss)
         SGNN_LAUNCH(ctx, st, "xent_final_kernel", SGNN_TAG, xent_final_kernel, dim3(1), dim3(1024), 0, st, partial, (int)nwg, inv, loss,
-                    (const float *)nullptr, 0, (float *)nullptr);
+                    (const float *)nullptr, 0, (float *)nullptr, (const unsigned long long *)nullptr, 0, 0.0, 0.0);
     return SGNN_OK;
 }

@@ -22,6 +22,8 @@
 #include <algorithm>
 
 #include "block_prims.h"
+#include <type_traits>
+
 #include "common.h"
 
 namespace {
@@ -274,7 +276,117 @@ struct spmm_epi {
     int64_t ldadd;
     int out_bf16;       // the result is stored as bfloat16 (rounded to nearest even; `out` then points at 16-bit elements)
     int mask_bf16;      // the mask matrix is stored as bfloat16
+    // softmax cross-entropy of the finished rows (kernels instantiated with XENT; bias is the only other epilogue then)
+    const int32_t *labels;      // class of every output row
+    void *dO;                   // gradient rows (softmax - onehot) * inv_rows, or null
+    int dO_bf16;
+    int64_t lddo;
+    float inv_rows;
+    float *loss_partial;        // one partial sum of -log p_label per workgroup
+    float *cs_partial;          // [workgroups][d] column sums of the stored gradient, or null
+    int write_out;              // the logits are written to `out` as well
+    // A long row is finished by whichever of its piece wavefronts comes last, so its share of the sums cannot go into
+    // that wavefront's running sums (the result would depend on the race).  It is added, as 64-bit fixed-point
+    // integers, to one of XENT_SLOTS rows of d + 1 counters chosen by the row number: integer addition is exact in
+    // any order, and the final kernel adds the slots up.  [slot][d + 1], column d holds the loss terms.
+    unsigned long long *fix;
 };
+constexpr int XENT_SLOTS = 256;
+constexpr double XENT_FIX_CS = 1152921504606846976.0;      // 2^60: a gradient entry is at most 1 in magnitude, their sum too
+constexpr double XENT_FIX_LOSS = 1073741824.0;             // 2^30: loss terms are below 2^10, at most 2^20 long rows
+
+// per-wavefront running sums of the cross-entropy epilogue
+template <int VEC, int CH> struct spmm_xent_sums {
+    float loss;
+    float cs[CH][VEC];
+};
+
+// Wavefront-wide sum / maximum for the row epilogue: four DPP steps make every lane of a 16-lane row hold the row's
+// result (quad swaps, half mirror, mirror: register-to-register, no LDS round trips as with the shuffle built-ins, of
+// which a reduction needs six in a dependent chain), four lane reads combine the rows.  The order of the additions is fixed.
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
+}
+template <bool MAX> __device__ __forceinline__ float wave_reduce_rows(float x)
+{
+    auto op = [](float a, float b) { return MAX ? fmaxf(a, b) : a + b; };
+    x = op(x, dpp_f32<0xB1>(x));      // quad_perm [1, 0, 3, 2]
+    x = op(x, dpp_f32<0x4E>(x));      // quad_perm [2, 3, 0, 1]
+    x = op(x, dpp_f32<0x141>(x));     // row_half_mirror
+    x = op(x, dpp_f32<0x140>(x));     // row_mirror
+    const int xi = __builtin_bit_cast(int, x);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 0)), r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16)),
+                r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 32)), r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 48));
+    return op(op(r0, r1), op(r2, r3));
+}
+
+// Cross-entropy of one finished row of logits v (bias already added), held by the wavefront as chunk (m, lane) =
+// columns (m * 64 + lane) * VEC ..: the row's softmax from one maximum and one sum across the wavefront, the
+// gradient row written where the logits would be read back from otherwise.  Probabilities are exp(x - max) / sum,
+// as in the stand-alone loss kernel.  A label outside [0, d) contributes the log-sum-exp alone.
+// exp(x) for x <= 0 to about 2 ulp with one hardware exponential: 2^(x log2 e), the rounding error of that product
+// (and the low part of log2 e) carried as a first-order correction.  The library expf costs some forty instructions,
+// and four of them per lane and row made the fused kernel ALU bound (the matrix has a million rows).
+__device__ __forceinline__ float exp_neg(float x)
+{
+    const float l2e_hi = 1.44269502162933349609375f, l2e_lo = 1.925963033500011e-8f;
+    const float t = x * l2e_hi;
+    float r = fmaf(x, l2e_hi, -t);
+    r = fmaf(x, l2e_lo, r);
+    const float e = __builtin_amdgcn_exp2f(t);        // 0 below 2^-126: such a probability is 0 in fp32 anyway
+    return fmaf(e, r * 0.693147182464599609375f, e);
+}
+
+// log(s) for s >= 1 with the hardware logarithm (1 ulp of log2 s)
+__device__ __forceinline__ float log_ge1(float s) { return __builtin_amdgcn_logf(s) * 0.693147182464599609375f; }
+
+template <int VEC, int CH, bool SHARED_ROW = false>
+__device__ __forceinline__ void spmm_row_xent(const float (&v)[CH][VEC], const spmm_epi &ep, int64_t row, int32_t y, int d, int lane,
+                                              spmm_xent_sums<VEC, CH> &xs)
+{
+    unsigned long long *fix = SHARED_ROW ? ep.fix + (uint64_t)(row % XENT_SLOTS) * (uint64_t)(d + 1) : nullptr;
+    auto add_loss = [&](float t) {
+        if constexpr (SHARED_ROW) atomicAdd(fix + d, (unsigned long long)(long long)llrint((double)t * XENT_FIX_LOSS));
+        else xs.loss += t;
+    };
+    float mx = -INFINITY;
+#pragma unroll
+    for (int m = 0; m < CH; ++m)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+            if ((m * 64 + lane) * VEC + i < d) mx = fmaxf(mx, v[m][i]);
+    mx = wave_reduce_rows<true>(mx);
+    float e[CH][VEC], s = 0.f;
+#pragma unroll
+    for (int m = 0; m < CH; ++m)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            e[m][i] = ((m * 64 + lane) * VEC + i < d) ? exp_neg(v[m][i] - mx) : 0.f;
+            s += e[m][i];
+        }
+    s = wave_reduce_rows<false>(s);
+    const float inv = __builtin_amdgcn_rcpf(s), lse = log_ge1(s);       // 1 ulp each
+    if ((uint32_t)y >= (uint32_t)d && lane == 0) add_loss(mx + lse);
+#pragma unroll
+    for (int m = 0; m < CH; ++m) {
+        const int col = (m * 64 + lane) * VEC;
+        if (col < d) {
+            float g[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                const bool hit = col + i == y;
+                if (hit) add_loss(lse - (v[m][i] - mx));
+                g[i] = (e[m][i] * inv - (hit ? 1.f : 0.f)) * ep.inv_rows;
+                if (ep.dO_bf16) g[i] = (float)(__bf16)g[i];       // the column sums add what is stored
+                if constexpr (SHARED_ROW) {
+                    if (ep.cs_partial) atomicAdd(fix + col + i, (unsigned long long)(long long)llrint((double)g[i] * XENT_FIX_CS));
+                } else xs.cs[m][i] += g[i];
+            }
+            if (ep.dO) vstore_out<VEC>(static_cast<float *>(ep.dO), row * ep.lddo + col, g, ep.dO_bf16);
+        }
+    }
+}
 
 // bias: the lane's VEC bias values (zeros without a bias), loaded once per wavefront: a lane's columns never change,
 // and a load of them in front of every row's store cost a third of the kernel on a 2^20-row matrix
@@ -307,13 +419,13 @@ __device__ __forceinline__ void spmm_epilogue(float (&v)[VEC], const spmm_epi &e
 // flight at a time whatever the lengths of the rows, the 64 lanes covering the columns.  Every
 // value that steers the walk (row number, row bounds, entry number) is the same in all lanes.
 // A row longer than long_len is left out: its chunks and the fix-up write it.
-template <int VEC, int CH, typename XT>
+template <int VEC, int CH, typename XT, bool XENT>
 __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const void *__restrict__ rowptr, int rp64,
                                                const int32_t *__restrict__ colidx, const float *__restrict__ val,
                                                uint64_t capacity, const XT *__restrict__ X, int64_t ldx,
                                                const int32_t *__restrict__ row_index, int d, uint64_t wave, int rows_per_wave,
                                                int long_len, float *__restrict__ out, int64_t ldo,
-                                               const spmm_epi &ep, const float (&bias)[CH][VEC])
+                                               const spmm_epi &ep, const float (&bias)[CH][VEC], spmm_xent_sums<VEC, CH> &xs)
 {
     constexpr int U = CH * VEC <= 4 ? SPMM_U4 : (CH * VEC <= 8 ? 4 : 2);
     const int lane = threadIdx.x & 63;
@@ -326,6 +438,8 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const void *__rest
     if (lane <= nr) rpl = min(rp_load(rowptr, rp64, r0 + lane), (int64_t)min(capacity, (uint64_t)0x7fffffffffffffffull));
     const int64_t block_base = readlane64(rpl, 0);
     const int32_t rp = lane <= nr ? (int32_t)(rpl - block_base) : 0;
+    int32_t ylane = 0;      // XENT: lane k holds the label of row r0 + k
+    if constexpr (XENT) ylane = lane < nr ? ep.labels[r0 + lane] : 0;
     colidx += block_base;
     val += block_base;
     const int e_end = __builtin_amdgcn_readlane(rp, nr);
@@ -342,12 +456,24 @@ __device__ __forceinline__ void spmm_wave_rows(uint32_t rows, const void *__rest
     auto next_row = [&]() {
         if (!row_long) {
             const int64_t o = (int64_t)(r0 + row) * ldo;
+            if constexpr (XENT) {
+#pragma unroll
+                for (int m = 0; m < CH; ++m)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[m][i] += bias[m][i];
+                spmm_row_xent<VEC, CH>(acc, ep, (int64_t)(r0 + row), __builtin_amdgcn_readlane(ylane, __builtin_amdgcn_readfirstlane(row)),
+                                       d, lane, xs);
+            }
 #pragma unroll
             for (int m = 0; m < CH; ++m) {
                 const int col = (m * 64 + lane) * VEC;
                 if (col < d) {
-                    spmm_epilogue<VEC>(acc[m], ep, (int64_t)(r0 + row), col, bias[m]);
-                    vstore_out<VEC>(out, o + col, acc[m], ep.out_bf16);
+                    if constexpr (XENT) {
+                        if (ep.write_out) vstore_out<VEC>(out, o + col, acc[m], 0);
+                    } else {
+                        spmm_epilogue<VEC>(acc[m], ep, (int64_t)(r0 + row), col, bias[m]);
+                        vstore_out<VEC>(out, o + col, acc[m], ep.out_bf16);
+                    }
                 }
             }
         }
@@ -466,7 +592,7 @@ template <int VEC, int CH> struct spmm_unroll { static constexpr int U = CH * VE
 // draws a ticket of the row, and the holder of the last ticket reads all partial rows back with
 // device-scope loads and adds them up in piece order - the same sum whoever does it.  That wavefront also puts the ticket counter
 // back to zero for the next product with this plan.
-template <int VEC, int CH, typename XT>
+template <int VEC, int CH, typename XT, bool XENT = false>
 __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const void *__restrict__ rowptr, int rp64,
                                                             const int32_t *__restrict__ colidx,
                                                             const float *__restrict__ val, uint64_t capacity,
@@ -489,6 +615,35 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
             bias[m][i] = (ep.bias && col < d) ? ep.bias[col] : 0.f;
         }
     const int64_t cap = (int64_t)min(capacity, (uint64_t)0x7fffffffffffffffull);
+    spmm_xent_sums<VEC, CH> xs;
+    xs.loss = 0.f;
+#pragma unroll
+    for (int m = 0; m < CH; ++m)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) xs.cs[m][i] = 0.f;
+    // a finished row held as sum (bias not yet added): written, or with XENT turned into its loss and gradient row
+    auto finish = [&](float (&sum)[CH][VEC], int64_t row, auto shared_row) {
+        const int64_t orow = row * ldo;
+        if constexpr (XENT) {
+#pragma unroll
+            for (int m = 0; m < CH; ++m)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) sum[m][i] += bias[m][i];
+            spmm_row_xent<VEC, CH, decltype(shared_row)::value>(sum, ep, row, ep.labels[row], d, lane, xs);
+        }
+#pragma unroll
+        for (int m = 0; m < CH; ++m) {
+            const int col = (m * 64 + lane) * VEC;
+            if (col < d) {
+                if constexpr (XENT) {
+                    if (ep.write_out) vstore_out<VEC>(out, orow + col, sum[m], 0);
+                } else {
+                    spmm_epilogue<VEC>(sum[m], ep, row, col, bias[m]);
+                    vstore_out<VEC>(out, orow + col, sum[m], ep.out_bf16);
+                }
+            }
+        }
+    };
     if (wave < n_piece_waves) {
         const uint32_t total = min(*n_chunks, max_chunks);
         constexpr int PSTRIDE = CH * VEC * 64;
@@ -552,15 +707,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
                     }
                 }
             }
-            const int64_t orow = (int64_t)drawn_row * ldo;
-#pragma unroll
-            for (int m = 0; m < CH; ++m) {
-                const int col = (m * 64 + lane) * VEC;
-                if (col < d) {
-                    spmm_epilogue<VEC>(sum[m], ep, (int64_t)drawn_row, col, bias[m]);
-                    vstore_out<VEC>(out, orow + col, sum[m], ep.out_bf16);
-                }
-            }
+            finish(sum, (int64_t)drawn_row, std::true_type{});      // finished by whoever came last: sums through the slots
             if (lane == 0) ticket[drawn_first] = 0;
         };
         for (uint32_t pc = wave; pc < total; pc += n_piece_waves) {
@@ -588,15 +735,7 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
             }
             if (re - rs <= plen) {
                 // the row's only piece: it is the row, written as the row-block wavefronts write theirs
-                const int64_t orow = (int64_t)rc.x * ldo;
-#pragma unroll
-                for (int m = 0; m < CH; ++m) {
-                    const int col = (m * 64 + lane) * VEC;
-                    if (col < d) {
-                        spmm_epilogue<VEC>(acc[m], ep, (int64_t)rc.x, col, bias[m]);
-                        vstore_out<VEC>(out, orow + col, acc[m], ep.out_bf16);
-                    }
-                }
+                finish(acc, (int64_t)rc.x, std::false_type{});        // pieces are dealt out in a fixed order: this wavefront's row
                 continue;
             }
             if (drawn) finish_row();
@@ -617,15 +756,52 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
         }
         if (drawn) finish_row();
         if (owed) { draw_ticket(); finish_row(); }
-        return;
+    } else {
+        // blocks of rows, grid-stride: the grid is capped (a launch holds fewer than 2^32 threads), a full graph
+        // of 10^8 rows has more blocks than that
+        const int rpw = n_chunks ? (int)n_chunks[2] : rows_per_wave;
+        const int long_len = n_chunks ? (int)n_chunks[1] : 0x7fffffff;
+        const uint64_t n_row_waves = (uint64_t)gridDim.x * (SPMM_NT / 64) - n_piece_waves;
+        for (uint64_t w = wave - n_piece_waves; w * (uint64_t)rpw < rows; w += n_row_waves)
+            spmm_wave_rows<VEC, CH, XT, XENT>(rows, rowptr, rp64, colidx, val, capacity, X, ldx, row_index, d, w, rpw, long_len, out,
+                                              ldo, ep, bias, xs);
     }
-    // blocks of rows, grid-stride: the grid is capped (a launch holds fewer than 2^32 threads), a full graph
-    // of 10^8 rows has more blocks than that
-    const int rpw = n_chunks ? (int)n_chunks[2] : rows_per_wave;
-    const int long_len = n_chunks ? (int)n_chunks[1] : 0x7fffffff;
-    const uint64_t n_row_waves = (uint64_t)gridDim.x * (SPMM_NT / 64) - n_piece_waves;
-    for (uint64_t w = wave - n_piece_waves; w * (uint64_t)rpw < rows; w += n_row_waves)
-        spmm_wave_rows<VEC, CH, XT>(rows, rowptr, rp64, colidx, val, capacity, X, ldx, row_index, d, w, rpw, long_len, out, ldo, ep, bias);
+    if constexpr (XENT) {
+        // every wavefront of the workgroup arrives here (a workgroup is all pieces or all row blocks): its sums are
+        // added in a fixed order and leave as the workgroup's partial loss and partial column sums
+        __shared__ float xl[SPMM_NT / 64];
+        __shared__ float xc[SPMM_NT / 64][CH * VEC * 64];
+        const int wv = threadIdx.x >> 6;
+        const float l = wave_sum(xs.loss);
+        if (lane == 0) xl[wv] = l;
+#pragma unroll
+        for (int m = 0; m < CH; ++m)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) xc[wv][(m * VEC + i) * 64 + lane] = xs.cs[m][i];
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+            for (int w = 0; w < SPMM_NT / 64; ++w) t += xl[w];
+            ep.loss_partial[blockIdx.x] = t;
+        }
+        if (ep.cs_partial) {
+            for (int idx = threadIdx.x; idx < CH * VEC * 64; idx += SPMM_NT) {
+                const int l2 = idx & 63, mi = idx >> 6, m = mi / VEC, i = mi % VEC;
+                const int col = (m * 64 + l2) * VEC + i;
+                if (col < d) {
+                    float t = 0.f;
+                    for (int w = 0; w < SPMM_NT / 64; ++w) t += xc[w][idx];
+                    ep.cs_partial[(int64_t)blockIdx.x * d + col] = t;
+                }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void spmm_xent_clear_kernel(unsigned long long *__restrict__ p, unsigned n)
+{
+    const unsigned i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0ull;
 }
 
 int build_plan(sgnn_ctx *ctx, const sgnn_csr *A, void *plan, hipStream_t st)
@@ -638,15 +814,21 @@ int build_plan(sgnn_ctx *ctx, const sgnn_csr *A, void *plan, hipStream_t st)
     return SGNN_OK;
 }
 
-template <int VEC, int CH, typename XT>
+// XENT: the cross-entropy epilogue; loss_out / colsum_out receive the mean loss and the column sums of the gradient
+template <int VEC, int CH, typename XT, bool XENT = false>
 int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const XT *X, int64_t ldx, const int32_t *row_index, int d, float *out,
-              int64_t ldo, const spmm_epi &ep, ws_alloc *ws, hipStream_t st)
+              int64_t ldo, const spmm_epi &ep_in, ws_alloc *ws, hipStream_t st, float *loss_out = nullptr, float *colsum_out = nullptr)
 {
+    spmm_epi ep = ep_in;
     const int rows_per_wave = spmm_rows_per_wave(A->rows, A->capacity);   // lower bound of the plan's figure
     const unsigned rows_per_block = (unsigned)(SPMM_NT / 64) * (unsigned)rows_per_wave;
     char tag[56];
-    snprintf(tag, sizeof(tag), "%ux%u d=%d <%d,%d> in=%d out=%d%s", A->rows, A->cols, d, VEC, CH, (int)sizeof(XT), ep.out_bf16 ? 2 : 4,
-             ep.mask ? (ep.mask_bf16 ? " m=2" : " m=4") : "");
+    if (XENT)
+        snprintf(tag, sizeof(tag), "%ux%u d=%d <%d,%d> in=%d out=%d xent dO=%d", A->rows, A->cols, d, VEC, CH, (int)sizeof(XT),
+                 ep.write_out ? 4 : 0, ep.dO ? (ep.dO_bf16 ? 2 : 4) : 0);
+    else
+        snprintf(tag, sizeof(tag), "%ux%u d=%d <%d,%d> in=%d out=%d%s", A->rows, A->cols, d, VEC, CH, (int)sizeof(XT), ep.out_bf16 ? 2 : 4,
+                 ep.mask ? (ep.mask_bf16 ? " m=2" : " m=4") : "");
     const bool may_have_long = A->capacity > (uint64_t)SPMM_SHORT;
     spmm_plan_view pv = {nullptr, nullptr, nullptr, nullptr};
     float *part = nullptr;
@@ -677,10 +859,24 @@ int launch_vc(sgnn_ctx *ctx, const sgnn_csr *A, const XT *X, int64_t ldx, const 
     // times the true count: most of the workgroups of such a launch would find no block of rows and leave at once, and
     // dispatching a quarter of a million of them cost a third of the kernel's time.  16384 workgroups fill the machine
     // several times over; the wavefronts stride over whatever is left.
-    const unsigned row_blocks = std::min<unsigned>(cdiv(A->rows, rows_per_block), 16384u);
-    SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH, XT>), dim3(n_piece_waves / (SPMM_NT / 64) + row_blocks),
+    // (with the cross-entropy epilogue every workgroup leaves a row of partial sums for the final kernel: a quarter of that)
+    const unsigned row_blocks = std::min<unsigned>(cdiv(A->rows, rows_per_block), XENT ? 4096u : 16384u);
+    const unsigned grid = n_piece_waves / (SPMM_NT / 64) + row_blocks;
+    if (XENT) {
+        ep.loss_partial = ws->get<float>(grid);
+        ep.cs_partial = colsum_out ? ws->get<float>((size_t)grid * d) : nullptr;
+        ep.fix = ws->get<unsigned long long>((size_t)XENT_SLOTS * (d + 1));
+        if (!ws->ok)
+            return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_spmm_xent: scratch too small (%zu bytes needed): call sgnn_ctx_reserve", ws->off);
+        const unsigned nfix = (unsigned)(XENT_SLOTS * (d + 1));
+        SGNN_LAUNCH(ctx, st, "spmm_xent_clear_kernel", SGNN_TAG, spmm_xent_clear_kernel, dim3(cdiv(nfix, 256)), dim3(256), 0, st, ep.fix, nfix);
+    }
+    SGNN_LAUNCH(ctx, st, "spmm_main_kernel", tag, (spmm_main_kernel<VEC, CH, XT, XENT>), dim3(grid),
                 dim3(SPMM_NT), 0, st, A->rows, A->rowptr, A->rowptr_is_i64, A->colidx, A->val, A->capacity, X, ldx, row_index, d,
                 n_piece_waves, pv.n_chunks, max_chunks, pv.desc, pv.ticket, part, out, ldo, ep, rows_per_wave);
+    if (XENT && (loss_out || colsum_out))
+        return sgnn_launch_xent_final(ctx, ep.loss_partial, (int)grid, ep.inv_rows, loss_out, ep.cs_partial, d, colsum_out, ep.fix, XENT_SLOTS,
+                                      1.0 / XENT_FIX_CS, 1.0 / XENT_FIX_LOSS, st);
     return SGNN_OK;
 }
 
@@ -739,6 +935,44 @@ static int launch_x(sgnn_ctx *ctx, const sgnn_csr *A, const XT *X, int64_t ldx, 
     if (ok4) return launch_v<4, XT>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
     if (ok2) return launch_v<2, XT>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
     return launch_v<1, XT>(ctx, A, X, ldx, row_index, (int)d, out, ldo, ep, ws, st);
+}
+
+// O = A X + bias with the softmax cross-entropy of O's rows in the epilogue (see spmm_row_xent).  Returns
+// SGNN_ERR_UNSUPPORTED without launching anything for widths or alignments the fused kernels are not built for
+// (more than 512 columns, rows that do not allow the vector width the column count asks for): the caller then
+// runs the product and the loss kernel one after the other.
+template <typename XT>
+static int launch_xent_x(sgnn_ctx *ctx, const sgnn_csr *A, const XT *X, int64_t ldx, int64_t d, float *out, int64_t ldo,
+                         const spmm_epi &ep, float *loss, float *colsum, ws_alloc *ws, hipStream_t st)
+{
+    // a lane moves VEC consecutive elements of X, of the logits (fp32) and of the gradient at once
+    auto fits = [](const void *ptr, int64_t ld, int elem_bytes, int vec) {
+        return !ptr || ((reinterpret_cast<uintptr_t>(ptr) % (uintptr_t)(vec * elem_bytes)) == 0 && ld % vec == 0);
+    };
+    auto ok = [&](int vec) {
+        return d % vec == 0 && fits(X, ldx, (int)sizeof(XT), vec) && fits(ep.write_out ? out : nullptr, ldo, 4, vec) &&
+               fits(ep.dO, ep.lddo, ep.dO_bf16 ? 2 : 4, vec);
+    };
+    const bool ok4 = ok(4), ok2 = ok(2);
+    if (d <= 64) return launch_vc<1, 1, XT, true>(ctx, A, X, ldx, nullptr, (int)d, out, ldo, ep, ws, st, loss, colsum);
+    if (d <= 128 && ok2) return launch_vc<2, 1, XT, true>(ctx, A, X, ldx, nullptr, (int)d, out, ldo, ep, ws, st, loss, colsum);
+    if (d <= 256 && ok4) return launch_vc<4, 1, XT, true>(ctx, A, X, ldx, nullptr, (int)d, out, ldo, ep, ws, st, loss, colsum);
+    if (d <= 512 && ok4) return launch_vc<4, 2, XT, true>(ctx, A, X, ldx, nullptr, (int)d, out, ldo, ep, ws, st, loss, colsum);
+    return SGNN_ERR_UNSUPPORTED;
+}
+
+int sgnn_launch_spmm_xent(sgnn_ctx *ctx, const sgnn_csr *A, const void *X, int x_bf16, int64_t ldx, int64_t d, const float *bias,
+                          const int32_t *labels, float *out, int64_t ldo, float *loss, void *dO, int dO_bf16, int64_t lddo,
+                          float *dO_colsum, ws_alloc *ws, hipStream_t st)
+{
+    spmm_epi ep = {};
+    ep.bias = bias;
+    ep.labels = labels;
+    ep.dO = dO; ep.dO_bf16 = dO_bf16 ? 1 : 0; ep.lddo = lddo;
+    ep.inv_rows = 1.f / (float)A->rows;
+    ep.write_out = out ? 1 : 0;
+    if (x_bf16) return launch_xent_x(ctx, A, static_cast<const bf16_bits *>(X), ldx, d, out, ldo, ep, loss, dO_colsum, ws, st);
+    return launch_xent_x(ctx, A, static_cast<const float *>(X), ldx, d, out, ldo, ep, loss, dO_colsum, ws, st);
 }
 
 // X: cols x d, fp32 or (x_bf16) bfloat16 bit patterns, leading dimension ldx in elements

@@ -21,7 +21,7 @@ class GcnStep:
                  weights: List[Tuple[torch.Tensor, torch.Tensor]], B: int, seed: int = 0, bf16: bool = False,
                  fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None,
                  auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = False, bf16_activations: bool = False,
-                 pad_features: bool = True, bf16_loss_grad: bool = True):
+                 pad_features: bool = True, bf16_loss_grad: bool = True, fuse_loss: Optional[bool] = None, keep_logits: bool = True):
         """bf16_activations (with bf16): the aggregates T_l and the layer outputs H_l (all but the logits) are stored as
         bfloat16, and so is the gradient dH_l handed to an aggregate-first layer below whose ReLU backward is fused
         upstream (only dense products, which round it to bfloat16 anyway, read it); the loss gradient dO is stored as
@@ -85,6 +85,17 @@ class GcnStep:
         # the loss gradient: bfloat16 along with the activations (the last layer has no ReLU, so whichever product reads
         # it - dense or sparse - takes the stored values as they are; its bias gradient comes with the loss kernel)
         self.dO = mat(dims[-1], act if bf16_loss_grad else torch.float32)
+        # A transform-first last layer ends in the sparse product O = A (H W) + b, whose wavefronts hold whole rows of
+        # logits: with fuse_loss the loss and its gradient are formed right there (sgnn_spmm_xent) instead of reading O
+        # back in a kernel of its own; keep_logits = False does not even write O (H[-1] then keeps stale values).
+        # The row epilogue costs the sparse kernel most of what the separate loss kernel costs (a row occupies 43 of
+        # a wavefront's 64 lanes for 172 classes): +2 % at 2^20 rows, nothing at 2^18, a loss on dense mini-batches whose
+        # long rows add their share through atomics.  fuse_loss = None picks it from 2^19 sampled vertices on.
+        if fuse_loss is None:
+            fuse_loss = B >= (1 << 19) and self.capacity <= 32 * B
+        self.fuse_loss = bool(fuse_loss) and self.L >= 2 and self.xform_first[-1]
+        self.keep_logits = keep_logits
+        self.P_last = mat(dims[-1], act) if self.fuse_loss else None
         self.dW = [torch.empty_like(w) for w, _ in weights]
         self._dW0 = None
         if self.d_in_padded != dims[0]:
@@ -127,6 +138,9 @@ class GcnStep:
         """after_first: called once the first layer has been issued (the captured pipeline forks there)."""
         for l, (W, b) in enumerate(self.weights):
             flags = self.flags | (sg.SGNN_RELU if l < self.L - 1 else 0) | (sg.SGNN_XFORM_FIRST if self.xform_first[l] else 0)
+            if l == self.L - 1 and self.fuse_loss:
+                sg.sgnn_gemm(self.ctx, False, False, self.H[l - 1], W, None, self.flags, self.P_last)   # the rest with the loss
+                continue
             if l == 0 and self.fuse_slice:
                 if self._dW0 is not None:
                     W = self._W0
@@ -139,6 +153,10 @@ class GcnStep:
 
     def loss_and_grad(self):
         # the last layer has no activation: its bias gradient is the column sum of dO, taken in the same pass
+        if self.fuse_loss:
+            sg.sgnn_spmm_xent(self.ctx, self.A, self.P_last, self.weights[-1][1], self.y_S, self.loss, self.dO,
+                              O=self.H[-1] if self.keep_logits else None, dO_colsum=self.db[-1])
+            return
         sg.sgnn_softmax_xent(self.ctx, self.H[-1], self.y_S, self.loss, self.dO, dO_colsum=self.db[-1])
 
     def backward(self, side=None, before_last=None):

@@ -361,6 +361,59 @@ def test_spmm_bf16_stored_result(d):
         assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-5 * np.abs(want).max())
 
 
+@pytest.mark.parametrize("d", [8, 41, 47, 64, 100, 172, 256, 300, 512, 173, 600])
+def test_spmm_with_the_loss_in_its_epilogue(d):
+    # O = A X + b, the mean cross-entropy of O and its gradient in one call: against the oracle, and against the
+    # product followed by the loss kernel (per row the same arithmetic: logits and gradient rows bit for bit; the sums
+    # over the rows are taken in another order).  One vector width and chunk count per column count; 173 and 600 are
+    # shapes the fused kernels do not take (two kernels behind the same call); a long row goes through the pieces
+    rng = np.random.default_rng(d)
+    rows = 3000
+    dense = (rng.random((rows, rows)) < 0.002) * rng.random((rows, rows))
+    dense[5, :] = rng.random(rows) * (rng.random(rows) < 0.5)
+    dense[77, :] = 0.0                                               # an empty row: logits = bias
+    A = sp.csr_matrix(dense.astype(np.float32))
+    rp, ci, va = A.indptr.astype(np.int32), A.indices.astype(np.int32), A.data.astype(np.float32)
+    X = oracle.round_bf16(_rand((rows, d), 52)) * 4.0
+    bias = _rand((d,), 53)
+    y = rng.integers(0, d, rows).astype(np.int32)
+    Ad = sg.Csr.from_arrays(rows, rows, rp, ci, va, DEV)
+    ctx().reserve(rows, A.nnz, rows, max(d, 8), A.nnz)
+    O_ref = oracle.spmm(rp, ci, va, X) + bias[None, :]
+    l_ref, dO_ref = oracle.softmax_xent(O_ref, y)
+    pad = (-d) % 8
+    bd, yd = dev(bias, torch.float32), dev(y)
+    for xin in (dev(np.pad(X, ((0, 0), (0, pad))), torch.float32)[:, :d], _bf(np.pad(X, ((0, 0), (0, pad)))).to(DEV)[:, :d]):
+        # the two kernels one after the other
+        O2 = torch.zeros((rows, d + pad), dtype=torch.float32, device=DEV)[:, :d]
+        sg.sgnn_spmm(ctx(), Ad, xin, O2)
+        O2 += bd
+        loss2 = torch.zeros(1, dtype=torch.float32, device=DEV); dO2 = torch.zeros_like(O2); cs2 = torch.zeros(d, dtype=torch.float32, device=DEV)
+        sg.sgnn_softmax_xent(ctx(), O2, yd, loss2, dO2, dO_colsum=cs2)
+        # one call
+        O = torch.full((rows, d + pad), 7.0, dtype=torch.float32, device=DEV)[:, :d]
+        dO = torch.full((rows, d + pad), 7.0, dtype=torch.float32, device=DEV)[:, :d]
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV); cs = torch.zeros(d, dtype=torch.float32, device=DEV)
+        sg.sgnn_spmm_xent(ctx(), Ad, xin, bd, yd, loss, dO, O=O, dO_colsum=cs)
+        assert rel_err(O.cpu().numpy(), O_ref) < TOL_F32 and rel_err(dO.cpu().numpy(), dO_ref) < TOL_F32
+        assert abs(loss.item() - l_ref) < TOL_F32 * abs(l_ref)
+        assert np.abs(cs.cpu().numpy() - dO_ref.sum(axis=0)).max() < TOL_F32 * np.abs(dO_ref).sum(axis=0).max()
+        assert rel_err(O.cpu().numpy(), O2.cpu().numpy().astype(np.float64)) < 1e-6
+        assert rel_err(dO.cpu().numpy(), dO2.cpu().numpy().astype(np.float64)) < 1e-6
+        # again: bit-reproducible; without the logits; gradient stored as bfloat16 (column sums of what is stored)
+        dO3 = torch.zeros_like(dO); loss3 = torch.zeros_like(loss); cs3 = torch.zeros_like(cs)
+        sg.sgnn_spmm_xent(ctx(), Ad, xin, bd, yd, loss3, dO3, O=None, dO_colsum=cs3)
+        assert torch.equal(dO, dO3) and torch.equal(loss, loss3) and torch.equal(cs, cs3)
+        dO16 = torch.zeros((rows, (d + 31) // 32 * 32), dtype=torch.bfloat16, device=DEV)[:, :d]; cs16 = torch.zeros_like(cs)
+        sg.sgnn_spmm_xent(ctx(), Ad, xin, bd, yd, loss3, dO16, O=None, dO_colsum=cs16)
+        assert torch.equal(dO16, dO.to(torch.bfloat16)) and torch.equal(loss, loss3)
+        stored = dO16.float().cpu().numpy().astype(np.float64)
+        assert np.abs(cs16.cpu().numpy() - stored.sum(axis=0)).max() < TOL_F32 * np.abs(stored).sum(axis=0).max()
+        sg.sgnn_spmm_xent(ctx(), Ad, xin, None, yd, loss3, None)                       # the loss alone, no bias
+        l_nb, _ = oracle.softmax_xent(O_ref - bias[None, :], y)
+        assert abs(loss3.item() - l_nb) < TOL_F32 * abs(l_nb)
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_gemm_long_reduction_is_split_and_reproducible(bf16):
     # the weight-gradient shape: short result, reduction over tens of thousands of rows
@@ -633,7 +686,7 @@ def test_softmax_xent_aligned_rows_and_large_logits(B, C):
     assert torch.equal(loss, loss2)
 
 
-def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_bwd=True, bf16_act=False):
+def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_bwd=True, bf16_act=False, fuse_loss=None):
     cfg = si.CONFIGS[name]
     bf16 = cfg.bf16_mfma if bf16 is None else bf16
     # inputs are generated with torch on the GPU (integer parts are device independent) and copied
@@ -645,7 +698,8 @@ def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_b
     st = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld,
                     [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B, cfg.sampler_seed, bf16=bf16,
                     fuse_slice=fuse_slice, device=DEV, auto_order=auto_order, fuse_relu_bwd=fuse_relu_bwd,
-                    bf16_activations=bf16_act)
+                    bf16_activations=bf16_act, fuse_loss=fuse_loss)
+    assert st.fuse_loss == (fuse_loss or (cfg.B >= (1 << 19) and cfg.layers >= 2))
     g = si.Graph(cfg.N, gd.rowptr.cpu(), gd.colidx.cpu())
     X, labels = Xd.cpu(), ld.cpu()
     wnp = [(W.double().numpy(), b.double().numpy()) for W, b in weights]
@@ -747,6 +801,13 @@ def test_whole_step_with_a_ragged_feature_width():
         _run_config("ragged_wide", [2], False)
     finally:
         del si.CONFIGS["ragged_wide"]
+
+
+def test_whole_step_with_the_loss_in_the_last_sparse_product():
+    # transform-first last layers: O = A (H W) + b, the loss and its gradient from one kernel (sgnn_spmm_xent)
+    _run_config("tiny", [0, 3], True, fuse_loss=True)
+    _run_config("medium", [1], True, fuse_loss=True)
+    _run_config("medium", [2], True, bf16=True, bf16_act=True, fuse_loss=True)
 
 
 def test_whole_step_tiny_bf16():
