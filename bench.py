@@ -236,8 +236,9 @@ def measure(args, sg, si, torch, cfg, g, X, labels, weights, use_graph_req: str,
             w = tag.split()
             ein = next((float(x[3:]) for x in w if x.startswith("in=")), 2.0 if "bf16 in" in tag else 4.0)
             eout = next((float(x[4:]) for x in w if x.startswith("out=")), 4.0)
+            edo = next((float(x[3:]) for x in w if x.startswith("dO=")), 0.0)      # the loss epilogue also writes the gradient rows
             # compulsory traffic: CSR once, every input row once, the output once
-            gq["bytes"] += calls * (8.0 * nnz_avg + 4.0 * (cfg.B + 1) + cfg.B * d * (ein + eout))
+            gq["bytes"] += calls * (8.0 * nnz_avg + 4.0 * (cfg.B + 1) + cfg.B * d * (ein + eout + edo))
     total_ms = sum(v["ms"] for v in groups.values())
     dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
     sp = [v for k, v in groups.items() if k.startswith("spmm_main_kernel")]

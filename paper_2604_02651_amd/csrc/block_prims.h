@@ -61,3 +61,20 @@ template <class T, int NT> __device__ __forceinline__ T block_sum(T x, T *lds)
     __syncthreads();
     return t;
 }
+
+// exp(x) for x <= 0 to about 2 ulp with one hardware exponential: 2^(x log2 e), the rounding error of that product
+// (and the low part of log2 e) carried as a first-order correction.  The library expf costs some forty instructions:
+// a softmax over 172 classes of a million rows is then bound by them, not by memory.
+__device__ __forceinline__ float exp_neg(float x)
+{
+    const float l2e_hi = 1.44269502162933349609375f, l2e_lo = 1.925963033500011e-8f;
+    const float t = x * l2e_hi;
+    float r = fmaf(x, l2e_hi, -t);
+    r = fmaf(x, l2e_lo, r);
+    const float e = __builtin_amdgcn_exp2f(t);        // 0 below 2^-126: such a probability is 0 in fp32 anyway
+    return fmaf(e, r * 0.693147182464599609375f, e);
+}
+
+// log(s) for s >= 1 with the hardware logarithm (1 ulp of log2 s)
+__device__ __forceinline__ float log_ge1(float s) { return __builtin_amdgcn_logf(s) * 0.693147182464599609375f; }
+

@@ -178,17 +178,17 @@ __global__ __launch_bounds__(256) void xent_kernel(const float *__restrict__ O, 
 #pragma unroll
         for (int t = 0; t < NX; ++t) {
             if ((int32_t)(g + t * lpr) == y && x[t] != -INFINITY) { oy = x[t] - m; mine = true; }
-            x[t] = (x[t] == -INFINITY) ? 0.f : expf(x[t] - m);
+            x[t] = (x[t] == -INFINITY) ? 0.f : exp_neg(x[t] - m);
             sum += x[t];
         }
         for (int s = lpr >> 1; s > 0; s >>= 1) sum += __shfl_xor(sum, s, 64);
         if (live) {
             // - log p_y = log(sum) - (o_y - max): added by the lane that holds column y (a label outside [0, C) adds the
             // log-sum-exp alone, through lane 0 of the row)
-            if (mine) loss += logf(sum) - oy;
-            else if (g == 0 && (uint32_t)y >= C) loss += m + logf(sum);
+            if (mine) loss += log_ge1(sum) - oy;
+            else if (g == 0 && (uint32_t)y >= C) loss += m + log_ge1(sum);
             if (dO) {
-                const float inv_sum = 1.f / sum;
+                const float inv_sum = __builtin_amdgcn_rcpf(sum);      // 1 ulp
 #pragma unroll
                 for (int t = 0; t < NX; ++t) {
                     const uint32_t j = g + t * lpr;

@@ -325,22 +325,6 @@ template <bool MAX> __device__ __forceinline__ float wave_reduce_rows(float x)
 // columns (m * 64 + lane) * VEC ..: the row's softmax from one maximum and one sum across the wavefront, the
 // gradient row written where the logits would be read back from otherwise.  Probabilities are exp(x - max) / sum,
 // as in the stand-alone loss kernel.  A label outside [0, d) contributes the log-sum-exp alone.
-// exp(x) for x <= 0 to about 2 ulp with one hardware exponential: 2^(x log2 e), the rounding error of that product
-// (and the low part of log2 e) carried as a first-order correction.  The library expf costs some forty instructions,
-// and four of them per lane and row made the fused kernel ALU bound (the matrix has a million rows).
-__device__ __forceinline__ float exp_neg(float x)
-{
-    const float l2e_hi = 1.44269502162933349609375f, l2e_lo = 1.925963033500011e-8f;
-    const float t = x * l2e_hi;
-    float r = fmaf(x, l2e_hi, -t);
-    r = fmaf(x, l2e_lo, r);
-    const float e = __builtin_amdgcn_exp2f(t);        // 0 below 2^-126: such a probability is 0 in fp32 anyway
-    return fmaf(e, r * 0.693147182464599609375f, e);
-}
-
-// log(s) for s >= 1 with the hardware logarithm (1 ulp of log2 s)
-__device__ __forceinline__ float log_ge1(float s) { return __builtin_amdgcn_logf(s) * 0.693147182464599609375f; }
-
 template <int VEC, int CH, bool SHARED_ROW = false>
 __device__ __forceinline__ void spmm_row_xent(const float (&v)[CH][VEC], const spmm_epi &ep, int64_t row, int32_t y, int d, int lane,
                                               spmm_xent_sums<VEC, CH> &xs)
