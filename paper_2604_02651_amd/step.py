@@ -21,7 +21,7 @@ class GcnStep:
                  weights: List[Tuple[torch.Tensor, torch.Tensor]], B: int, seed: int = 0, bf16: bool = False,
                  fuse_slice: bool = True, capacity: Optional[int] = None, device="cuda:0", ctx: Optional[sg.Context] = None,
                  auto_order: bool = True, fuse_relu_bwd: bool = True, side_dw: bool = False, bf16_activations: bool = False,
-                 pad_features: bool = True, bf16_loss_grad: bool = True, fuse_loss: Optional[bool] = None, keep_logits: bool = True):
+                 pad_features: bool = True, bf16_loss_grad: bool = True, fuse_loss: bool = False, keep_logits: bool = True):
         """bf16_activations (with bf16): the aggregates T_l and the layer outputs H_l (all but the logits) are stored as
         bfloat16, and so is the gradient dH_l handed to an aggregate-first layer below whose ReLU backward is fused
         upstream (only dense products, which round it to bfloat16 anyway, read it); the loss gradient dO is stored as
@@ -90,9 +90,7 @@ class GcnStep:
         # back in a kernel of its own; keep_logits = False does not even write O (H[-1] then keeps stale values).
         # The row epilogue costs the sparse kernel most of what the separate loss kernel costs (a row occupies 43 of
         # a wavefront's 64 lanes for 172 classes): +2 % at 2^20 rows, nothing at 2^18, a loss on dense mini-batches whose
-        # long rows add their share through atomics.  fuse_loss = None picks it from 2^19 sampled vertices on.
-        if fuse_loss is None:
-            fuse_loss = B >= (1 << 19) and self.capacity <= 32 * B
+        # long rows add their share through atomics.  Off unless asked for.
         self.fuse_loss = bool(fuse_loss) and self.L >= 2 and self.xform_first[-1]
         self.keep_logits = keep_logits
         self.P_last = mat(dims[-1], act) if self.fuse_loss else None

@@ -686,7 +686,7 @@ def test_softmax_xent_aligned_rows_and_large_logits(B, C):
     assert torch.equal(loss, loss2)
 
 
-def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_bwd=True, bf16_act=False, fuse_loss=None):
+def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_bwd=True, bf16_act=False, fuse_loss=False):
     cfg = si.CONFIGS[name]
     bf16 = cfg.bf16_mfma if bf16 is None else bf16
     # inputs are generated with torch on the GPU (integer parts are device independent) and copied
@@ -699,7 +699,7 @@ def _run_config(name, steps, fuse_slice, bf16=None, auto_order=True, fuse_relu_b
                     [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B, cfg.sampler_seed, bf16=bf16,
                     fuse_slice=fuse_slice, device=DEV, auto_order=auto_order, fuse_relu_bwd=fuse_relu_bwd,
                     bf16_activations=bf16_act, fuse_loss=fuse_loss)
-    assert st.fuse_loss == (fuse_loss or (cfg.B >= (1 << 19) and cfg.layers >= 2))
+    assert st.fuse_loss == fuse_loss
     g = si.Graph(cfg.N, gd.rowptr.cpu(), gd.colidx.cpu())
     X, labels = Xd.cpu(), ld.cpu()
     wnp = [(W.double().numpy(), b.double().numpy()) for W, b in weights]
