@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Turns rocprofv3 CSV output into the short text summaries kept under profiles/.
 
-    python3 profile_summary.py stats    <dir>/<name>_kernel_stats.csv        OUT.txt --cmd "<command that made it>"
+    python3 profile_summary.py stats    <dir>/<name>_kernel_stats.csv        OUT.txt --cmd "<command that made it>" [--trace <name>_kernel_trace.csv]
     python3 profile_summary.py traffic  <fetch>_counter_collection.csv <write>_counter_collection.csv OUT.txt \
                                         --workload xlarge --cmd "<the two commands>"
     python3 profile_summary.py counters <pmc>_counter_collection.csv OUT.txt --cmd "<command>" [--durations STATS.txt]
@@ -65,6 +65,32 @@ def cmd_stats(args):
     for k, a in sorted(agg.items(), key=lambda kv: -kv[1][1]):
         lines.append("%-44s %7d %12.1f %12.2f %6.2f%% %10.2f %10.2f" % (k[:44], a[0], a[1] / 1e3, a[1] / a[0] / 1e3,
                                                                          100.0 * a[1] / tot, a[2] / 1e3, a[3] / 1e3))
+    if args.trace:
+        # dispatches that overlapped no other dispatch in time: what HIP events around a kernel on an otherwise idle chip see
+        ev = []
+        for r in csv.DictReader(open(args.trace)):
+            ev.append((int(r["Start_Timestamp"]), int(r["End_Timestamp"]), r["Kernel_Name"]))
+        ev.sort()
+        alone = collections.OrderedDict()
+        max_end_before = 0
+        for i, (b, e, name) in enumerate(ev):
+            overl = b < max_end_before or (i + 1 < len(ev) and ev[i + 1][0] < e)
+            max_end_before = max(max_end_before, e)
+            if not ours(name):
+                continue
+            a = alone.setdefault(short(name), [0, 0, 0, 0])
+            a[2] += 1; a[3] += e - b
+            if not overl:
+                a[0] += 1; a[1] += e - b
+        lines.append("")
+        lines.append("# dispatches that overlapped no other dispatch in time (from the kernel trace of the same run): the figure that")
+        lines.append("# bench.py's event-bracketed single-stream pass measures")
+        lines.append("%-44s %7s %12s %14s %14s" % ("kernel", "alone", "avg_us", "overlapped", "avg_us"))
+        for k, a in sorted(alone.items(), key=lambda kv: -kv[1][3]):
+            no, to = a[0], a[1]
+            ov, tov = a[2] - a[0], a[3] - a[1]
+            lines.append("%-44s %7d %12s %14d %14s" % (k[:44], no, "%.2f" % (to / no / 1e3) if no else "-", ov,
+                                                        "%.2f" % (tov / ov / 1e3) if ov else "-"))
     open(args.out, "w").write("\n".join(lines) + "\n")
     print("\n".join(lines[:16]))
 
@@ -142,6 +168,7 @@ def main():
     ap.add_argument("--cmd", default="")
     ap.add_argument("--note", default="")
     ap.add_argument("--workload", default="")
+    ap.add_argument("--trace", default="", help="stats: the kernel trace CSV of the same run (adds the table of dispatches that ran alone)")
     ap.add_argument("--durations", default="", help="counters: a stats summary of the same workload (adds mfma_share)")
     args = ap.parse_args()
     args.out = args.inputs.pop()
