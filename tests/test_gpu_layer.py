@@ -414,6 +414,26 @@ def test_spmm_with_the_loss_in_its_epilogue(d):
         assert abs(loss3.item() - l_nb) < TOL_F32 * abs(l_nb)
 
 
+def test_spmm_with_the_loss_rejects_what_it_cannot_take():
+    rows, d = 64, 8
+    A = sp.identity(rows, dtype=np.float32, format="csr")
+    Ad = sg.Csr.from_arrays(rows, rows, A.indptr.astype(np.int32), A.indices.astype(np.int32), A.data.astype(np.float32), DEV)
+    ctx().reserve(rows, rows, rows, 8, rows)
+    X = dev(_rand((rows, d), 1), torch.float32); y = dev(np.zeros(rows, np.int32))
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV); dO = torch.zeros((rows, d), dtype=torch.float32, device=DEV)
+    with pytest.raises(ValueError):
+        sg.sgnn_spmm_xent(ctx(), Ad, X, None, y[:10], loss, dO)                       # a label per row
+    with pytest.raises(ValueError):
+        sg.sgnn_spmm_xent(ctx(), Ad, X, None, y, loss, dO[:, :4])                     # gradient of another shape
+    with pytest.raises(sg.SgnnError):
+        sg.sgnn_spmm_xent(ctx(), Ad, X[:32], None, y, loss, None)                     # X must have a row per column of A
+    with pytest.raises(sg.SgnnError):
+        sg.sgnn_spmm_xent(ctx(), Ad, X, None, y, loss, None, dO_colsum=torch.zeros(d, device=DEV))   # column sums of no gradient
+    sg.sgnn_spmm_xent(ctx(), Ad, X, None, y, loss, dO)                                # and the plain call still works
+    l_ref, dO_ref = oracle.softmax_xent(X.cpu().numpy().astype(np.float64), np.zeros(rows, np.int32))
+    assert abs(loss.item() - l_ref) < TOL_F32 * abs(l_ref) and rel_err(dO.cpu().numpy(), dO_ref) < TOL_F32
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_gemm_long_reduction_is_split_and_reproducible(bf16):
     # the weight-gradient shape: short result, reduction over tens of thousands of rows
