@@ -185,15 +185,17 @@ __host__ __device__ inline int spmm_long_len(uint32_t rows, uint64_t entries)
     return (int)t;
 }
 
-// Rows that one wavefront walks as a block: about 32 entries, at most 16 rows (measured on a 2^20-row matrix with 1.3
-// entries a row: 7 % faster than 16 entries / 8 rows; more gathers in flight per wavefront, 16 instead of 8, were slower),
-// and no fewer than 4096 wavefronts while the rows last.  The plan holds the figure for the true entry count (header
+// Rows that one wavefront walks as a block: about 128 entries, at most 32 rows, and no fewer than 4096 wavefronts while
+// the rows last.  Measured: 16 entries / 8 rows -> 32 / 16: 7 % faster on a 2^20-row matrix with 1.3 entries a row;
+// 32 / 16 -> 128 / 32: the five products of a 2^18-row step with 6.3 entries a row 6-9 % faster each (steps/s + 3.4 %),
+// those of the 2^20-row step 1-4 %, dense-degree and small mini-batches unchanged; more gathers in flight per
+// wavefront, 16 instead of 8, were slower at every size.  The plan holds the figure for the true entry count (header
 // word 2); the host sizes the grid with the capacity in its place, which can only give fewer rows.
 #ifndef SPMM_BLOCK_ENTRIES
-#define SPMM_BLOCK_ENTRIES 32
+#define SPMM_BLOCK_ENTRIES 128
 #endif
 #ifndef SPMM_BLOCK_ROWS
-#define SPMM_BLOCK_ROWS 16
+#define SPMM_BLOCK_ROWS 32
 #endif
 #ifndef SPMM_U4
 #define SPMM_U4 8
