@@ -29,6 +29,9 @@ constexpr int IND_ITEMS = 8;
 constexpr int IND_TILE = IND_NT * IND_ITEMS;      // 2048 flat edges per workgroup (4096 and 8192 with 512 threads measured slower)
 constexpr int IND_WORDS = IND_ITEMS * (IND_NT / 64);   // 64-bit keep words of a tile: one per slab and wavefront
 constexpr int IND_ROWS = 512;                     // rows a tile's LDS table holds (more only when rows average under 4 edges): 6 KB, so LDS does not limit occupancy
+#ifndef IND_FILL_SLOTS
+#define IND_FILL_SLOTS 2                          // survivors a thread of the fill pass works on at a time
+#endif
 constexpr unsigned IND_MAX_GRID = 8192;
 constexpr int DEG_TILE = 2048;                    // sampled rows per workgroup in the offset kernels
 
@@ -188,16 +191,16 @@ __device__ __forceinline__ uint32_t find_row_lds(const tile_table &tt, uint32_t 
     return lo;
 }
 
-// The same search for the IND_ITEMS edges of a thread at once, in lock step with a fixed number of rounds,
+// The same search for the edges of a thread at once, in lock step with a fixed number of rounds,
 // so that the LDS reads of the slabs are in flight together (x[k] < 0: no edge, the result is unused).
-__device__ __forceinline__ void find_rows_lds(const tile_table &tt, uint32_t nr, const int32_t (&x)[IND_ITEMS],
-                                              uint32_t (&rk)[IND_ITEMS])
+template <int ITEMS>
+__device__ __forceinline__ void find_rows_lds(const tile_table &tt, uint32_t nr, const int32_t (&x)[ITEMS], uint32_t (&rk)[ITEMS])
 {
 #pragma unroll
-    for (int k = 0; k < IND_ITEMS; ++k) rk[k] = 0;
+    for (int k = 0; k < ITEMS; ++k) rk[k] = 0;
     for (uint32_t step = 1u << (31 - __clz((int)nr)); step; step >>= 1) {
 #pragma unroll
-        for (int k = 0; k < IND_ITEMS; ++k) {
+        for (int k = 0; k < ITEMS; ++k) {
             const uint32_t t = rk[k] + step;
             if (t < nr && tt.relP[t] <= x[k]) rk[k] = t;
         }
@@ -305,6 +308,7 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
     __shared__ tile_table tt;
     __shared__ uint64_t balw[IND_WORDS];
     __shared__ uint32_t pre[IND_WORDS + 1];
+    __shared__ uint16_t xs[IND_TILE];
     const uint64_t F = P[B];
     const uint64_t n_tiles = *n_tiles_p;
     const unsigned lane = lane_id(), wave = threadIdx.x >> 6;
@@ -373,75 +377,87 @@ __global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
             } else if (x == (int64_t)tile_len && (last || k + 1 < nr)) rowptr_S[r_lo + k] = (int32_t)(tile_off_cur + pre[IND_WORDS]);
         }
 
-        // survivors
-        int32_t x[IND_ITEMS], u[IND_ITEMS];
-        uint32_t rk[IND_ITEMS];
-#pragma unroll
-        for (int k = 0; k < IND_ITEMS; ++k) {
-            const bool mine = (balw[k * (IND_NT / 64) + wave] >> lane) & 1ull;
-            x[k] = mine ? (int32_t)(k * IND_NT + threadIdx.x) : -1;
-        }
-        if (staged) find_rows_lds(tt, nr, x, rk);
-        int64_t eidx[IND_ITEMS];
-#pragma unroll
-        for (int k = 0; k < IND_ITEMS; ++k) {
-            u[k] = -1; eidx[k] = 0;
-            if (x[k] >= 0) {
-                const uint64_t f = f0 + (uint64_t)x[k];
-                if (staged) eidx[k] = tt.ebase[rk[k]] + (int64_t)f;
-                else {
-                    const uint32_t r = find_row(P, r_lo, r_lo + nr - 1, f);
-                    rk[k] = r - r_lo;
-                    eidx[k] = rowstart[r] + (int64_t)(f - P[r]);
-                }
-                u[k] = colidx[eidx[k]];
-            }
-        }
-        uint64_t word[IND_ITEMS];
-        uint32_t rnk[IND_ITEMS];
-        int64_t du[IND_ITEMS];
-#pragma unroll
-        for (int k = 0; k < IND_ITEMS; ++k) {
-            word[k] = 0; rnk[k] = 0; du[k] = 1;
-            if (u[k] >= 0) {
-                word[k] = bitmap[(uint32_t)u[k] >> 6];
-                rnk[k] = rank[(uint32_t)u[k] >> 6];
-                if (write_val && !gval && !deg_by_rank) du[k] = (int64_t)rowptr[(int64_t)u[k] + 1] - (int64_t)rowptr[u[k]];
-            }
-        }
-        // compact column ids; a surviving column is itself a sampled vertex, so with every sampled row inside the row
-        // range its degree is already in deg[] (B entries, cache resident) and need not be gathered from rowptr
-        uint32_t cid[IND_ITEMS];
-#pragma unroll
-        for (int k = 0; k < IND_ITEMS; ++k) {
-            cid[k] = rnk[k] + (uint32_t)__popcll(word[k] & ((1ull << (u[k] & 63)) - 1ull));
-            if (u[k] >= 0 && write_val && !gval && deg_by_rank) du[k] = (int64_t)deg[min(cid[k], B - 1)];
-        }
+        // Survivors, in their order: the flat offsets of the set bits of the keep words are written to a list in LDS, and
+        // thread i takes survivor i, i + 256, ... (IND_FILL_SLOTS of them at a time).  A thread then holds the state of a few
+        // survivors instead of one slot for each of its eight edges, of which one in eight survives on a typical
+        // mini-batch: half the registers, twice the tiles in flight on a compute unit.
         const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
         for (int k = 0; k < IND_ITEMS; ++k) {
-            if (u[k] < 0) continue;
             const uint32_t wd = k * (IND_NT / 64) + wave;
-            const uint32_t pos = tile_off_cur + pre[wd] + (uint32_t)__popcll(balw[wd] & below);
-            if (pos >= capacity) continue;
-            colidx_S[pos] = (int32_t)cid[k];
-            if (write_val) {
-                const uint32_t r = r_lo + rk[k];
-                const int64_t v = S[r];
-                float a;
-                if (gval) a = gval[eidx[k]];
-                else {
-                    // 1 / sqrt(deg(v) deg(u)) in single precision: product, reciprocal square root, one Newton step.
-                    // Against the double-precision formula rounded once: a few 1e-7 relative (two roundings of
-                    // 2^-24 here, one for 1/p, the Newton step leaves under one more), inside the 1e-6 the weights are held to.
-                    // A row that holds an edge lies inside the row range: deg is its full length.
-                    const float xx = (float)deg[r] * (float)du[k];
-                    float y = __frsqrt_rn(xx);
-                    const float err = fmaf(-xx * y, y, 1.0f);
-                    a = fmaf(0.5f * y, err, y);
+            const uint64_t w = balw[wd];
+            if ((w >> lane) & 1ull) xs[pre[wd] + (uint32_t)__popcll(w & below)] = (uint16_t)(k * IND_NT + threadIdx.x);
+        }
+        __syncthreads();
+        const uint32_t n_surv = pre[IND_WORDS];
+        for (uint32_t i0 = 0; i0 < n_surv; i0 += IND_FILL_SLOTS * IND_NT) {
+            int32_t x[IND_FILL_SLOTS], u[IND_FILL_SLOTS];
+            uint32_t rk[IND_FILL_SLOTS];
+#pragma unroll
+            for (int k = 0; k < IND_FILL_SLOTS; ++k) {
+                const uint32_t i = i0 + k * IND_NT + threadIdx.x;
+                x[k] = i < n_surv ? (int32_t)xs[i] : -1;
+            }
+            if (staged) find_rows_lds(tt, nr, x, rk);
+            int64_t eidx[IND_FILL_SLOTS];
+#pragma unroll
+            for (int k = 0; k < IND_FILL_SLOTS; ++k) {
+                u[k] = -1; eidx[k] = 0;
+                if (x[k] >= 0) {
+                    const uint64_t f = f0 + (uint64_t)x[k];
+                    if (staged) eidx[k] = tt.ebase[rk[k]] + (int64_t)f;
+                    else {
+                        const uint32_t r = find_row(P, r_lo, r_lo + nr - 1, f);
+                        rk[k] = r - r_lo;
+                        eidx[k] = rowstart[r] + (int64_t)(f - P[r]);
+                    }
+                    u[k] = colidx[eidx[k]];
                 }
-                if ((int64_t)u[k] != v) a *= inv_p;
-                val_S[pos] = a;
+            }
+            uint64_t word[IND_FILL_SLOTS];
+            uint32_t rnk[IND_FILL_SLOTS];
+            int64_t du[IND_FILL_SLOTS];
+#pragma unroll
+            for (int k = 0; k < IND_FILL_SLOTS; ++k) {
+                word[k] = 0; rnk[k] = 0; du[k] = 1;
+                if (u[k] >= 0) {
+                    word[k] = bitmap[(uint32_t)u[k] >> 6];
+                    rnk[k] = rank[(uint32_t)u[k] >> 6];
+                    if (write_val && !gval && !deg_by_rank) du[k] = (int64_t)rowptr[(int64_t)u[k] + 1] - (int64_t)rowptr[u[k]];
+                }
+            }
+            // compact column ids; a surviving column is itself a sampled vertex, so with every sampled row inside the row
+            // range its degree is already in deg[] (B entries, cache resident) and need not be gathered from rowptr
+            uint32_t cid[IND_FILL_SLOTS];
+#pragma unroll
+            for (int k = 0; k < IND_FILL_SLOTS; ++k) {
+                cid[k] = rnk[k] + (uint32_t)__popcll(word[k] & ((1ull << (u[k] & 63)) - 1ull));
+                if (u[k] >= 0 && write_val && !gval && deg_by_rank) du[k] = (int64_t)deg[min(cid[k], B - 1)];
+            }
+#pragma unroll
+            for (int k = 0; k < IND_FILL_SLOTS; ++k) {
+                if (u[k] < 0) continue;
+                const uint32_t pos = tile_off_cur + i0 + k * IND_NT + threadIdx.x;
+                if (pos >= capacity) continue;
+                colidx_S[pos] = (int32_t)cid[k];
+                if (write_val) {
+                    const uint32_t r = r_lo + rk[k];
+                    const int64_t v = S[r];
+                    float a;
+                    if (gval) a = gval[eidx[k]];
+                    else {
+                        // 1 / sqrt(deg(v) deg(u)) in single precision: product, reciprocal square root, one Newton step.
+                        // Against the double-precision formula rounded once: a few 1e-7 relative (two roundings of
+                        // 2^-24 here, one for 1/p, the Newton step leaves under one more), inside the 1e-6 the weights are held to.
+                        // A row that holds an edge lies inside the row range: deg is its full length.
+                        const float xx = (float)deg[r] * (float)du[k];
+                        float y = __frsqrt_rn(xx);
+                        const float err = fmaf(-xx * y, y, 1.0f);
+                        a = fmaf(0.5f * y, err, y);
+                    }
+                    if ((int64_t)u[k] != v) a *= inv_p;
+                    val_S[pos] = a;
+                }
             }
         }
         __syncthreads();   // the keep words and the row table are reused by the next tile

@@ -173,6 +173,44 @@ def test_induced_sparse_sample_of_a_large_graph():
     assert np.all(np.abs(got - v) <= TOL_VAL * np.abs(v))
 
 
+def test_induced_capacity_of_half_the_entries(tiny_graph):
+    # Capacity for half the entries of a matrix of many tiles: the row offsets are complete, every entry below the
+    # capacity is written as usual, none beyond it, and the status word reports the overflow.
+    g = tiny_graph
+    N, B = g.N, g.N
+    ref = oracle.induced_csr(N, g.rowptr.numpy(), g.colidx.numpy(), oracle.sample_uniform(N, B, 0, 0))
+    cap = len(ref[1]) // 2
+    assert cap > 3 * 2048
+    S, bitmap, rank = gpu_sample(N, B, 0, 0)
+    out = sg.Csr(B, B, cap, DEV)
+    sg.sgnn_induced_csr(ctx(), N, g.rowptr.to(DEV), g.colidx.to(DEV), None, S, B, bitmap, rank, out)
+    with pytest.raises(sg.SgnnError) as e:
+        ctx().status()
+    assert e.value.code == -2
+    assert np.array_equal(out.rowptr.cpu().numpy(), ref[0])
+    assert np.array_equal(out.colidx.cpu().numpy()[:cap], ref[1][:cap])
+    got = out.val.cpu().numpy()[:cap].astype(np.float64)
+    assert np.all(np.abs(got - ref[2][:cap]) <= TOL_VAL * np.abs(ref[2][:cap]))
+
+
+@pytest.mark.parametrize("max_entries", [0, 1 << 20])
+def test_induced_in_a_context_of_its_own(medium_graph, max_entries):
+    # A context of its own, reserved for exactly this graph and sample (with and without room for mini-batch entries in
+    # its scratch), gives the same matrix as the shared, generously reserved one of the other tests.
+    g = medium_graph
+    cfg = si.CONFIGS["medium"]
+    N, B = g.N, cfg.B
+    c = sg.Context(0)
+    c.reserve(N, g.E, B, 1, max_entries)
+    S, bitmap, rank = gpu_sample(N, B, cfg.sampler_seed, 3)
+    ref = oracle.induced_csr(N, g.rowptr.numpy(), g.colidx.numpy(), oracle.sample_uniform(N, B, cfg.sampler_seed, 3))
+    assert len(ref[1]) <= 1 << 20
+    out = sg.Csr(B, B, len(ref[1]), DEV)
+    nnz = sg.sgnn_induced_csr(c, N, g.rowptr.to(DEV), g.colidx.to(DEV), None, S, B, bitmap, rank, out, want_nnz=True)
+    c.status()
+    _assert_csr_equal(out, nnz, ref)
+
+
 def test_induced_capacity_overflow_is_reported(tiny_graph):
     g = tiny_graph
     with pytest.raises(sg.SgnnError) as e:
