@@ -201,8 +201,11 @@ __device__ __forceinline__ void find_rows_lds(const tile_table &tt, uint32_t nr,
     for (uint32_t step = 1u << (31 - __clz((int)nr)); step; step >>= 1) {
 #pragma unroll
         for (int k = 0; k < ITEMS; ++k) {
+            // the read is unconditional (of the last row where t is beyond it), so that the compiler issues the reads
+            // of a round together instead of branching round each one and waiting for it
             const uint32_t t = rk[k] + step;
-            if (t < nr && tt.relP[t] <= x[k]) rk[k] = t;
+            const int32_t start = tt.relP[min(t, nr - 1)];
+            rk[k] = (t < nr && start <= x[k]) ? t : rk[k];
         }
     }
 }
@@ -245,20 +248,29 @@ __global__ __launch_bounds__(IND_NT) void induced_count_kernel(const int64_t *__
             const uint64_t f = f0 + (uint64_t)k * IND_NT + threadIdx.x;
             x[k] = f < f1 ? (int32_t)(f - f0) : -1;
         }
-        if (staged) find_rows_lds(tt, nr, x, rk);
+        if (staged) {
+            // Branch-free, one step for all eight edges at a time: the eight gathers of colidx are then in flight together
+            // (with a branch round each edge the compiler waits for every load before it issues the next: eight round
+            // trips per tile instead of one).  An offset behind the end of the last tile reads the tile's first edge.
+            find_rows_lds(tt, nr, x, rk);
+            int64_t e[IND_ITEMS];
 #pragma unroll
-        for (int k = 0; k < IND_ITEMS; ++k) {
-            u[k] = -1;
-            if (x[k] >= 0) {
-                const uint64_t f = f0 + (uint64_t)x[k];
-                int64_t e;
-                if (staged) e = tt.ebase[rk[k]] + (int64_t)f;
-                else {
+            for (int k = 0; k < IND_ITEMS; ++k) e[k] = tt.ebase[rk[k]] + (int64_t)(f0 + (uint64_t)max(x[k], 0));
+#pragma unroll
+            for (int k = 0; k < IND_ITEMS; ++k) u[k] = colidx[e[k]];
+#pragma unroll
+            for (int k = 0; k < IND_ITEMS; ++k)
+                if (x[k] < 0 || u[k] < rg.c0 || u[k] >= rg.c1) u[k] = -1;   // no edge, or a column outside the shard
+        } else {
+#pragma unroll
+            for (int k = 0; k < IND_ITEMS; ++k) {
+                u[k] = -1;
+                if (x[k] >= 0) {
+                    const uint64_t f = f0 + (uint64_t)x[k];
                     const uint32_t r = find_row(P, r_lo, r_lo + nr - 1, f);
-                    e = rowstart[r] + (int64_t)(f - P[r]);
+                    u[k] = colidx[rowstart[r] + (int64_t)(f - P[r])];
+                    if (u[k] < rg.c0 || u[k] >= rg.c1) u[k] = -1;   // a column outside the shard
                 }
-                u[k] = colidx[e];
-                if (u[k] < rg.c0 || u[k] >= rg.c1) u[k] = -1;   // a column outside the shard
             }
         }
         uint64_t word[IND_ITEMS];
@@ -296,7 +308,7 @@ __global__ __launch_bounds__(IND_NT) void induced_count_kernel(const int64_t *__
 // the tile's keep words).  Row offsets come from the row side: every row that starts inside the tile gets the
 // position of the first survivor at or behind its start, which also covers rows without any stored entry.
 template <class RP>
-__global__ __launch_bounds__(IND_NT) void induced_fill_kernel(
+__global__ __launch_bounds__(IND_NT) __attribute__((amdgpu_waves_per_eu(8, 8))) void induced_fill_kernel(
     const RP *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *__restrict__ gval,
     const int32_t *__restrict__ S, const int64_t *__restrict__ rowstart, const uint32_t *__restrict__ deg, uint32_t B,
     const uint64_t *__restrict__ bitmap, const uint32_t *__restrict__ rank, const uint64_t *__restrict__ P,

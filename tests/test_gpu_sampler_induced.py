@@ -173,6 +173,22 @@ def test_induced_sparse_sample_of_a_large_graph():
     assert np.all(np.abs(got - v) <= TOL_VAL * np.abs(v))
 
 
+def test_induced_dense_rows_of_a_small_graph():
+    # 20000 vertices with 1000 entries a row, half of them sampled: the bitmap is small and the tiles are many, which is
+    # where the count pass probes a copy of the bitmap in LDS; result bit for bit as always.
+    N, B = 20000, 10000
+    g = si.rmat_graph(N, 10_000_000, 5, device=DEV)
+    assert g.E * B // N // 2048 >= 4096
+    ctx().reserve(N, g.E, B, 1, 0)
+    S, bitmap, rank = gpu_sample(N, B, 1, 2)
+    S_ref = oracle.sample_uniform(N, B, 1, 2)
+    rp, ci, v = oracle.induced_csr(N, g.rowptr.cpu().numpy(), g.colidx.cpu().numpy(), S_ref)
+    out = sg.Csr(B, B, len(ci), DEV)
+    nnz = sg.sgnn_induced_csr(ctx(), N, g.rowptr, g.colidx, None, S, B, bitmap, rank, out, want_nnz=True)
+    ctx().status()
+    _assert_csr_equal(out, nnz, (rp, ci, v))
+
+
 def test_induced_capacity_of_half_the_entries(tiny_graph):
     # Capacity for half the entries of a matrix of many tiles: the row offsets are complete, every entry below the
     # capacity is written as usual, none beyond it, and the status word reports the overflow.
