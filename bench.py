@@ -67,9 +67,9 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="same as --graph off")
     ap.add_argument("--no-overlap", action="store_true",
                     help="everything on one stream (default: the next mini-batch is sampled on a second stream while this one trains)")
-    ap.add_argument("--fuse-loss", choices=["off", "keep-logits", "drop-logits"], default="off",
-                    help="last layer: the loss in the epilogue of the sparse product (default: two kernels); drop-logits does not "
-                         "write the logits at all")
+    ap.add_argument("--fuse-loss", choices=["off", "keep-logits", "drop-logits"], default="drop-logits",
+                    help="last layer: the loss and its gradient in the epilogue of the sparse product that forms the logits; "
+                         "drop-logits (default) does not write the logits at all, off forms the loss in a kernel of its own")
     ap.add_argument("--fp32-loss-grad", action="store_true", help="keep the loss gradient dO in fp32 (default: bfloat16 with the activations)")
     ap.add_argument("--fp32-activations", action="store_true",
                     help="with bf16 GEMM operands, keep the forward activations in fp32 storage (default: bf16 storage)")
@@ -207,7 +207,8 @@ def measure(args, sg, si, torch, cfg, g, X, labels, weights, use_graph_req: str,
             p = tag.split()
             key = "gemm_kernel<%s,%s,%s>" % (p[1], p[0], p[3])
         elif name == "spmm_main_kernel":
-            key = name + tag.split()[2]
+            # the instantiation with the loss in its epilogue (tag: "... dO=<bytes>") is a kernel symbol of its own
+            key = name + (tag.split()[2][:-1] + ",xent>" if " dO=" in tag else tag.split()[2])
         gq = groups.setdefault(key, {"calls": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
         gq["calls"] += calls
         gq["ms"] += ms

@@ -721,7 +721,10 @@ __global__ __launch_bounds__(SPMM_NT) void spmm_main_kernel(uint32_t rows, const
             }
             if (re - rs <= plen) {
                 // the row's only piece: it is the row, written as the row-block wavefronts write theirs
-                finish(acc, (int64_t)rc.x, std::false_type{});        // pieces are dealt out in a fixed order: this wavefront's row
+                // With the loss epilogue its sums go the way of the rows shared between wavefronts (integer adds): the
+                // numbering of the pieces depends on the timing of the plan kernel, so which wavefront gets this row does
+                // too, and a float sum per wavefront would not come out the same bits twice.
+                finish(acc, (int64_t)rc.x, std::integral_constant<bool, XENT>{});
                 continue;
             }
             if (drawn) finish_row();

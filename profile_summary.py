@@ -40,9 +40,9 @@ def short(n: str) -> str:
         return "gemm_kernel<thin32,TN,f32>"
     if n.startswith("gemm_smallk_nt_kernel"):
         return "gemm_kernel<smallk,NT,f32>"
-    m = re.match(r"(spmm_main_kernel)<(\d+), (\d+), .*>", n)
-    if m:
-        return "%s<%s,%s>" % m.groups()[:3]
+    m = re.match(r"(spmm_main_kernel)<(\d+), (\d+), .*?(true|false)>", n)
+    if m:      # the last template argument: the instantiation with the loss in its epilogue
+        return "%s<%s,%s%s>" % (m.group(1), m.group(2), m.group(3), ",xent" if m.group(4) == "true" else "")
     return re.sub(r"<.*>$", "", n)
 
 

@@ -864,6 +864,37 @@ def test_whole_step_large_bf16_storage():
     _run_config("large", [1], True, bf16_act=True)
 
 
+def test_whole_step_large_with_the_loss_in_the_last_sparse_product():
+    # as above with the loss and its gradient formed in the epilogue of the last sparse product (logits kept, so that
+    # the oracle's statement about them can be checked)
+    _run_config("large", [2], True, bf16_act=True, fuse_loss=True)
+
+
+@pytest.mark.parametrize("name,bf16", [("large", True), ("medium", False)])
+def test_step_without_logits_is_the_step_with_logits(name, bf16):
+    # The launch configuration bench.py times does not write the logits: the same kernels with the stores of O left
+    # out.  Loss, loss gradient and every weight and bias gradient must come out bit for bit as with the logits kept
+    # (checked against the oracle above).
+    cfg = si.CONFIGS[name]
+    gd = si.rmat_graph(cfg.N, cfg.undirected_edges, cfg.graph_seed, device=DEV)
+    Xd = si.normal_features(cfg.N, cfg.d_in, cfg.feature_seed, device=DEV)
+    ld = si.uniform_labels(cfg.N, cfg.classes, cfg.label_seed, device=DEV)
+    weights = si.layer_weights(cfg)
+    got = []
+    for keep in (True, False):
+        st = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B,
+                        cfg.sampler_seed, bf16=bf16, fuse_slice=True, device=DEV, bf16_activations=bf16, fuse_loss=True,
+                        keep_logits=keep)
+        assert st.fuse_loss and st.keep_logits == keep
+        st.step(5)
+        torch.cuda.synchronize()
+        st.ctx.status()
+        got.append([st.loss.clone(), st.dO.clone()] + [w.clone() for w in st.dW] + [b.clone() for b in st.db])
+        del st
+    for a, b in zip(*got):
+        assert torch.equal(a, b)
+
+
 def test_whole_step_dense():
     # social-shaped graph at full size: mean degree about 490, |S| = 65536, 602 input features
     _run_config("dense", [0], True)
@@ -944,6 +975,24 @@ def test_whole_step_xlarge_bf16():
             # H_{l-1} > 0 and zero elsewhere (the mask was checked against the oracle's above)
             assert rel_err(st.dH[l].float().cpu().numpy(), ref["dH"][l] * ties[l - 1]) < TOL_BF16, ("dH", l)
     assert abs(st.loss.item() - ref["loss"]) < TOL_BF16 * abs(ref["loss"])
+
+    # The launch configuration bench.py times: the loss and its gradient in the epilogue of the last sparse product, the
+    # logits never written.  Same sampler counter, so the same mini-batch: against the step checked above.
+    st2 = sg.GcnStep(cfg.N, gd.rowptr, gd.colidx, Xd, ld, [(W.to(DEV), b.to(DEV)) for W, b in weights], cfg.B,
+                     cfg.sampler_seed, bf16=True, fuse_slice=True, device=DEV, bf16_activations=True, fuse_loss=True,
+                     keep_logits=False)
+    assert st2.fuse_loss
+    st2.step(0)
+    torch.cuda.synchronize()
+    st2.ctx.status()
+    assert torch.equal(st2.S, st.S) and torch.equal(st2.A.colidx[:nnz], st.A.colidx[:nnz])
+    assert abs(st2.loss.item() - st.loss.item()) < TOL_F32 * abs(st.loss.item())
+    # the same fp32 logits enter both forms of the loss; the stored bfloat16 gradient may differ in its last bit
+    assert rel_err(st2.dO.float().cpu().numpy(), dO_gpu) <= 2.0 ** -7
+    for l in range(cfg.layers):
+        assert rel_err(st2.dW[l].cpu().numpy(), st.dW[l].cpu().numpy()) < 2e-3, ("dW", l)
+        assert rel_err(st2.db[l].cpu().numpy(), st.db[l].cpu().numpy()) < 2e-3, ("db", l)
+    del st2
 
     # The full graph as the matrix of a sparse product (evaluation forward): 3.3 G entries, int64 row offsets,
     # bfloat16 features.  The oracle computes sampled output rows one by one: random ones and the longest.
