@@ -67,9 +67,11 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="same as --graph off")
     ap.add_argument("--no-overlap", action="store_true",
                     help="everything on one stream (default: the next mini-batch is sampled on a second stream while this one trains)")
-    ap.add_argument("--fuse-loss", choices=["off", "keep-logits", "drop-logits"], default="drop-logits",
+    ap.add_argument("--fuse-loss", choices=["auto", "off", "keep-logits", "drop-logits"], default="auto",
                     help="last layer: the loss and its gradient in the epilogue of the sparse product that forms the logits; "
-                         "drop-logits (default) does not write the logits at all, off forms the loss in a kernel of its own")
+                         "drop-logits does not write the logits at all, off forms the loss in a kernel of its own; auto (default): "
+                         "drop-logits where a mini-batch row is expected to hold fewer than 32 entries, off for dense-degree "
+                         "mini-batches (there the product is bound by its gathers and the epilogue's arithmetic comes on top)")
     ap.add_argument("--fp32-loss-grad", action="store_true", help="keep the loss gradient dO in fp32 (default: bfloat16 with the activations)")
     ap.add_argument("--fp32-activations", action="store_true",
                     help="with bf16 GEMM operands, keep the forward activations in fp32 storage (default: bf16 storage)")
@@ -128,9 +130,12 @@ def measure(args, sg, si, torch, cfg, g, X, labels, weights, use_graph_req: str,
             kw["bf16_activations"] = cfg.bf16_mfma and not args.fp32_activations
         if args.fp32_loss_grad:
             kw["bf16_loss_grad"] = False
-        if args.fuse_loss != "off":
+        fuse_loss = args.fuse_loss
+        if fuse_loss == "auto":     # expected entries of a mini-batch row: (E / N) (B / N)
+            fuse_loss = "drop-logits" if float(g.E) * cfg.B / (float(cfg.N) * cfg.N) < 32.0 else "off"
+        if fuse_loss != "off":
             kw["fuse_loss"] = True
-            kw["keep_logits"] = args.fuse_loss != "drop-logits"
+            kw["keep_logits"] = fuse_loss != "drop-logits"
         st = sg.GcnStep(cfg.N, g.rowptr, g.colidx, X, labels, weights, cfg.B, cfg.sampler_seed, bf16=cfg.bf16_mfma,
                         fuse_slice=not args.no_fuse_slice, device=dev, fuse_relu_bwd=not args.no_fuse_relu_bwd,
                         side_dw=args.side_dw, **kw)
