@@ -105,6 +105,9 @@ int sgnn_ctx_profile_read(sgnn_ctx *ctx, char *buf /* host */, uint64_t buf_len)
  *   rank    out uint32[ceil(N/64)], rank[w] = number of sampled vertices below 64*w, so the
  *           position of a sampled v in S is rank[v/64] + popcount(bitmap[v/64] & ((1<<v%64)-1))
  * Errors: B == 0, B > N, N >= 2^31, null pointers -> SGNN_ERR_INVALID_ARG; scratch -> CAPACITY.
+ * Debugging switch: the environment variable SGNN_SAMPLER_WINDOW_SHIFT (an integer, read at every call) moves
+ * the window of histogram bins in which a sparse sample of a large graph looks for its threshold, so that the
+ * passes taken when the window misses can be tested; the result does not depend on it.
  */
 int sgnn_sample_uniform(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, uint64_t step,
                         int32_t *S, uint64_t *bitmap, uint32_t *rank, sgnn_stream stream);

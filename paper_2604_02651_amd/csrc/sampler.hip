@@ -8,6 +8,9 @@
 // later passes read those instead: they decide all but 2^-11 (candidates) and 2^-16 (ties with the
 // threshold's prefix) of the vertices, and only for these is the key computed again.
 //
+// Sparse samples of large graphs take passes 1, 2, 4 and 6 only, pass 1 in the form of sampler_hist_window_kernel
+// (which also appends the candidates and sets the bits of the vertices that are in for certain).
+//
 //   1. sampler_hist_kernel     histogram of the top 11 key bits (LDS histograms, one merge)
 //   2. sampler_pick_bin_kernel the bin b* that holds the B-th smallest key and the rank r inside
 //   3. sampler_collect_kernel  (key, v) of every vertex in bin b* -> candidate list (about N/2048)
@@ -16,6 +19,8 @@
 //   6. sampler_rank_kernel     rank prefix per bitmap word and the ascending list S
 #include "block_prims.h"
 #include <algorithm>
+#include <cmath>
+#include <cstdlib>
 #include <mutex>
 
 #include "common.h"
@@ -35,6 +40,8 @@ struct sampler_state {
     uint32_t ncand;     // candidates appended by the collect pass
     uint32_t thr_v;     // threshold vertex
     uint64_t thr_key;   // threshold key
+    uint32_t fallback;  // windowed call whose threshold bin fell outside the window: the recomputing passes run instead
+    uint32_t nmark;     // candidates the threshold pass looked at (ncand is zero again when it ends)
 };
 
 // keys of vertices 2j (even) and 2j+1 (odd)
@@ -44,6 +51,17 @@ __device__ __forceinline__ void vertex_pair_keys(uint64_t j, uint64_t seed, uint
                                  (uint32_t)seed, (uint32_t)(seed >> 32));
     ke = ((uint64_t)o.w1 << 32) | o.w0;
     ko = ((uint64_t)o.w3 << 32) | o.w2;
+}
+
+__device__ __forceinline__ uint64_t spread_even(uint32_t x32)
+{
+    uint64_t x = x32;
+    x = (x | (x << 16)) & 0x0000FFFF0000FFFFull;
+    x = (x | (x << 8)) & 0x00FF00FF00FF00FFull;
+    x = (x | (x << 4)) & 0x0F0F0F0F0F0F0F0Full;
+    x = (x | (x << 2)) & 0x3333333333333333ull;
+    x = (x | (x << 1)) & 0x5555555555555555ull;
+    return x;
 }
 
 // The merge of the workgroups' histograms costs one device-wide atomic per bin and workgroup, and atomics on one
@@ -71,9 +89,125 @@ __global__ __launch_bounds__(SCAN_NT) void sampler_hist_kernel(uint64_t N, uint6
     }
 }
 
+// Workgroup-local candidate list: matches are rare, so a workgroup gathers its own in LDS and reserves room in the
+// global list with ONE atomic add, instead of one add per match on a single hot address.
+template <uint32_t LCAP> struct cand_lds {
+    uint64_t key[LCAP];
+    uint32_t v[LCAP];
+    uint32_t n, base, fail;
+};
+
+template <uint32_t LCAP>
+__device__ __forceinline__ void cand_append(cand_lds<LCAP> &l, bool me, bool mo, uint64_t ke, uint64_t ko, uint64_t j,
+                                            sampler_state *__restrict__ state, uint64_t *__restrict__ cand_key,
+                                            uint32_t *__restrict__ cand_v, uint32_t cap, uint32_t *__restrict__ status)
+{
+    if (!(me || mo)) return;
+    const uint32_t cnt = (me ? 1u : 0u) + (mo ? 1u : 0u);
+    uint32_t p = atomicAdd(&l.n, cnt);
+    if (p + cnt <= LCAP) {
+        if (me) { l.key[p] = ke; l.v[p] = (uint32_t)(2 * j); ++p; }
+        if (mo) { l.key[p] = ko; l.v[p] = (uint32_t)(2 * j + 1); }
+    } else {
+        // the local list is full (far beyond the expected load): straight to the global list.
+        // Reservations only grow, so every one before the first that failed fitted, and they
+        // fill [0, first failing offset) without holes.
+        atomicMin(&l.fail, p);
+        uint32_t q = atomicAdd(&state->ncand, cnt);
+        if (me) { if (q < cap) { cand_key[q] = ke; cand_v[q] = (uint32_t)(2 * j); } else atomicOr(status, SGNN_ST_CAND_OVERFLOW); ++q; }
+        if (mo) { if (q < cap) { cand_key[q] = ko; cand_v[q] = (uint32_t)(2 * j + 1); } else atomicOr(status, SGNN_ST_CAND_OVERFLOW); }
+    }
+}
+
+// every thread of the workgroup; NT threads
+template <uint32_t LCAP, int NT>
+__device__ __forceinline__ void cand_flush(cand_lds<LCAP> &l, sampler_state *__restrict__ state, uint64_t *__restrict__ cand_key,
+                                           uint32_t *__restrict__ cand_v, uint32_t cap, uint32_t *__restrict__ status)
+{
+    __syncthreads();
+    const uint32_t n_local = min(l.n, l.fail);
+    if (threadIdx.x == 0) l.base = n_local ? atomicAdd(&state->ncand, n_local) : 0u;
+    __syncthreads();
+    const uint32_t base = l.base;
+    for (uint32_t i = threadIdx.x; i < n_local; i += NT) {
+        if (base + i < cap) { cand_key[base + i] = l.key[i]; cand_v[base + i] = l.v[i]; }
+        else atomicOr(status, SGNN_ST_CAND_OVERFLOW);
+    }
+}
+
+// The one pass over the keys of a windowed call.  For a sparse sample of a large graph the bin of the threshold is
+// known before any key is: the B-th smallest of N uniform keys lies at B/N of the key range, give or take
+// sqrt(B (1 - B/N)) / N of it, so the host names a window [b_lo, b_hi] of one or two histogram bins that holds it
+// (six standard deviations either side).  This pass then does three things with every key while it has it: counts
+// its bin, appends it to the candidate list if the bin is in the window, and sets the vertex's bit in the output
+// bitmap if the bin lies below the window (such a vertex is in the sample whatever the threshold turns out to be).
+// Nothing per vertex is stored for later passes - no key prefixes - and no later pass touches a key again: the
+// threshold comes from the candidates, the candidates at or below it get their bits set (sampler_mark_kernel), and
+// the bitmap is complete.  If the threshold's bin is outside the window after all
+// (sampler_pick_bin_kernel checks), the recomputing passes run instead and overwrite everything.
+constexpr uint32_t WIN_LCAP = 2048;
+__global__ __launch_bounds__(SCAN_NT) void sampler_hist_window_kernel(uint64_t N, uint64_t seed, uint64_t step,
+                                                                      uint32_t *__restrict__ hist, uint32_t b_lo, uint32_t b_hi,
+                                                                      sampler_state *__restrict__ state,
+                                                                      uint64_t *__restrict__ cand_key, uint32_t *__restrict__ cand_v,
+                                                                      uint32_t cap, uint32_t *__restrict__ status,
+                                                                      uint64_t *__restrict__ bitmap, uint64_t W)
+{
+    __shared__ uint32_t lh[HIST_BINS];
+    __shared__ cand_lds<WIN_LCAP> cl;
+    __shared__ __attribute__((aligned(8))) uint8_t strip[SCAN_NT / 64][64];
+    for (int i = threadIdx.x; i < HIST_BINS; i += SCAN_NT) lh[i] = 0;
+    if (threadIdx.x == 0) { cl.n = 0; cl.fail = 0xffffffffu; }
+    __syncthreads();
+    const unsigned wave = threadIdx.x >> 6, lane = lane_id();
+    // A wavefront takes eight bitmap words (512 vertices) per round: lane l computes the keys of vertices 8l .. 8l+7 of
+    // the span (four Philox blocks) and reduces them to one byte of the bitmap; the 64 bytes pass through a
+    // wavefront-private strip of LDS, from which lanes 0 .. 7 read and write their eight words with one 64-byte store
+    // (as the emit pass over stored prefixes does: no bit interleaving of ballots).
+    volatile uint8_t *my_bytes = strip[wave];
+    volatile uint64_t *my_words = reinterpret_cast<volatile uint64_t *>(strip[wave]);
+    const uint64_t W8 = (W + 7) & ~7ull;
+    for (uint64_t wb = ((uint64_t)blockIdx.x * (SCAN_NT / 64) + wave) * 8; wb < W8; wb += (uint64_t)gridDim.x * (SCAN_NT / 64) * 8) {
+        const uint64_t v0 = wb * 64 + 8 * lane;                  // first of the lane's eight vertices
+        uint32_t byte = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint64_t ve = v0 + 2 * q, vo = ve + 1;
+            if (ve < N) {
+                uint64_t ke, ko;
+                vertex_pair_keys(ve >> 1, seed, step, ke, ko);
+                const uint32_t be_ = (uint32_t)(ke >> (64 - HIST_BITS)), bo_ = (uint32_t)(ko >> (64 - HIST_BITS));
+                atomicAdd(&lh[be_], 1u);
+                const bool me = be_ >= b_lo && be_ <= b_hi;
+                bool mo = false;
+                byte |= (be_ < b_lo ? 1u : 0u) << (2 * q);
+                if (vo < N) {
+                    atomicAdd(&lh[bo_], 1u);
+                    mo = bo_ >= b_lo && bo_ <= b_hi;
+                    byte |= (bo_ < b_lo ? 1u : 0u) << (2 * q + 1);
+                }
+                cand_append(cl, me, mo, ke, ko, ve >> 1, state, cand_key, cand_v, cap, status);
+            }
+        }
+        my_bytes[lane] = (uint8_t)byte;          // volatile: written and read in program order; LDS serves a wavefront in order
+        if (lane < 8) {
+            const uint64_t word = my_words[lane];
+            if (wb + lane < W) bitmap[wb + lane] = word;
+        }
+    }
+    cand_flush<WIN_LCAP, SCAN_NT>(cl, state, cand_key, cand_v, cap, status);
+    for (int i = threadIdx.x; i < HIST_BINS; i += SCAN_NT) {
+        uint32_t c = lh[i];
+        if (c) atomicAdd(&hist[i], c);
+    }
+}
+
 // One workgroup of 1024 threads, two bins a thread.  Leaves the histogram zeroed for the next call.
+// windowed: the candidates of bins b_lo .. b_hi are in the list already; they stay if the threshold's bin is one of
+// those, otherwise the list is emptied and the call falls back to the recomputing passes.
 __global__ __launch_bounds__(1024) void sampler_pick_bin_kernel(uint32_t B, uint32_t *__restrict__ hist,
-                                                                sampler_state *__restrict__ state)
+                                                                sampler_state *__restrict__ state, int windowed, uint32_t b_lo,
+                                                                uint32_t b_hi)
 {
     __shared__ uint32_t lds[1024 / 64 + 1];
     const uint32_t h0 = hist[2 * threadIdx.x], h1 = hist[2 * threadIdx.x + 1];
@@ -81,14 +215,18 @@ __global__ __launch_bounds__(1024) void sampler_pick_bin_kernel(uint32_t B, uint
     hist[2 * threadIdx.x + 1] = 0;
     uint32_t total;
     const uint32_t ex = block_excl_scan<uint32_t, 1024>(h0 + h1, &total, lds);
-    if (ex < B && B <= ex + h0) {
-        state->bin = 2 * threadIdx.x;
-        state->r = B - ex;
-    } else if (ex + h0 < B && B <= ex + h0 + h1) {
-        state->bin = 2 * threadIdx.x + 1;
-        state->r = B - ex - h0;
+    // exactly one thread owns the bin of the B-th smallest key (1 <= B <= N)
+    uint32_t bin = 0xffffffffu, r = 0;
+    if (ex < B && B <= ex + h0) { bin = 2 * threadIdx.x; r = B - ex; }
+    else if (ex + h0 < B && B <= ex + h0 + h1) { bin = 2 * threadIdx.x + 1; r = B - ex - h0; }
+    if (bin != 0xffffffffu) {
+        // with a window, r counts inside the threshold's bin as always: the threshold pass looks only at the candidates of that bin
+        const bool miss = windowed && (bin < b_lo || bin > b_hi);
+        state->bin = bin;
+        state->r = r;
+        state->fallback = miss ? 1u : 0u;
+        if (!windowed || miss) state->ncand = 0;
     }
-    if (threadIdx.x == 0) state->ncand = 0;
 }
 
 template <bool PREFIX>
@@ -97,34 +235,18 @@ __global__ __launch_bounds__(SCAN_NT) void sampler_collect_kernel(uint64_t N, ui
                                                                   uint64_t *__restrict__ cand_key,
                                                                   uint32_t *__restrict__ cand_v, uint32_t cap,
                                                                   uint32_t *__restrict__ status,
-                                                                  const uint32_t *__restrict__ prefix)
+                                                                  const uint32_t *__restrict__ prefix, int only_on_fallback)
 {
-    // Matches are rare (one vertex in 2048): a workgroup gathers its own in LDS and reserves room in
-    // the global list with ONE atomic add, instead of one add per match on a single hot address.
+    // Matches are rare (one vertex in 2048): gathered per workgroup (cand_lds).
     constexpr uint32_t LCAP = 1024;
-    __shared__ uint64_t l_key[LCAP];
-    __shared__ uint32_t l_v[LCAP];
-    __shared__ uint32_t l_n, l_base, l_fail;
+    __shared__ cand_lds<LCAP> cl;
+    if (only_on_fallback && !state->fallback) return;      // a windowed call that found its threshold bin in the window
     const uint32_t bin = state->bin;
     const uint64_t J = (N + 1) >> 1;
-    if (threadIdx.x == 0) { l_n = 0; l_fail = 0xffffffffu; }
+    if (threadIdx.x == 0) { cl.n = 0; cl.fail = 0xffffffffu; }
     __syncthreads();
     auto append = [&](bool me, bool mo, uint64_t ke, uint64_t ko, uint64_t j) {
-        if (!(me || mo)) return;
-        const uint32_t cnt = (me ? 1u : 0u) + (mo ? 1u : 0u);
-        uint32_t p = atomicAdd(&l_n, cnt);
-        if (p + cnt <= LCAP) {
-            if (me) { l_key[p] = ke; l_v[p] = (uint32_t)(2 * j); ++p; }
-            if (mo) { l_key[p] = ko; l_v[p] = (uint32_t)(2 * j + 1); }
-        } else {
-            // the local list is full (far beyond the expected load): straight to the global list.
-            // Reservations only grow, so every one before the first that failed fitted, and they
-            // fill [0, first failing offset) without holes.
-            atomicMin(&l_fail, p);
-            uint32_t q = atomicAdd(&state->ncand, cnt);
-            if (me) { if (q < cap) { cand_key[q] = ke; cand_v[q] = (uint32_t)(2 * j); } else atomicOr(status, SGNN_ST_CAND_OVERFLOW); ++q; }
-            if (mo) { if (q < cap) { cand_key[q] = ko; cand_v[q] = (uint32_t)(2 * j + 1); } else atomicOr(status, SGNN_ST_CAND_OVERFLOW); }
-        }
+        cand_append(cl, me, mo, ke, ko, j, state, cand_key, cand_v, cap, status);
     };
     const uint64_t J_rounds = PREFIX ? (J + 3) / 4 : J;      // loop items: quads of prefix words, or Philox blocks
     for (uint64_t j = (uint64_t)blockIdx.x * SCAN_NT + threadIdx.x; j < J_rounds; j += (uint64_t)gridDim.x * SCAN_NT) {
@@ -150,15 +272,7 @@ __global__ __launch_bounds__(SCAN_NT) void sampler_collect_kernel(uint64_t N, ui
             append((uint32_t)(ke >> (64 - HIST_BITS)) == bin, (2 * j + 1 < N) && (uint32_t)(ko >> (64 - HIST_BITS)) == bin, ke, ko, j);
         }
     }
-    __syncthreads();
-    const uint32_t n_local = min(l_n, l_fail);
-    if (threadIdx.x == 0) l_base = n_local ? atomicAdd(&state->ncand, n_local) : 0u;
-    __syncthreads();
-    const uint32_t base = l_base;
-    for (uint32_t i = threadIdx.x; i < n_local; i += SCAN_NT) {
-        if (base + i < cap) { cand_key[base + i] = l_key[i]; cand_v[base + i] = l_v[i]; }
-        else atomicOr(status, SGNN_ST_CAND_OVERFLOW);
-    }
+    cand_flush<LCAP, SCAN_NT>(cl, state, cand_key, cand_v, cap, status);
 }
 
 // Exact r-th smallest (key, v) among the candidates: most-significant-digit radix select over the
@@ -251,19 +365,41 @@ __global__ __launch_bounds__(1024) void sampler_threshold_kernel(sampler_state *
     if (threadIdx.x == 0) {
         state->thr_key = pk;
         state->thr_v = pv;
+        state->nmark = n;
+        state->ncand = 0;      // every thread read it long ago (barriers above): the list is empty for the next call
     }
 }
 
-__device__ __forceinline__ uint64_t spread_even(uint32_t x32)
+// Windowed calls: the candidates at or below the threshold get their bits (the vertices of the bins below the window
+// have theirs from the key pass), then the workgroup counts the rank pass wants.
+__global__ __launch_bounds__(SAMP_NT) void sampler_mark_kernel(const sampler_state *__restrict__ state,
+                                                               const uint64_t *__restrict__ cand_key,
+                                                               const uint32_t *__restrict__ cand_v, uint64_t *__restrict__ bitmap)
 {
-    uint64_t x = x32;
-    x = (x | (x << 16)) & 0x0000FFFF0000FFFFull;
-    x = (x | (x << 8)) & 0x00FF00FF00FF00FFull;
-    x = (x | (x << 4)) & 0x0F0F0F0F0F0F0F0Full;
-    x = (x | (x << 2)) & 0x3333333333333333ull;
-    x = (x | (x << 1)) & 0x5555555555555555ull;
-    return x;
+    if (state->fallback) return;
+    const uint64_t tk = state->thr_key;
+    const uint32_t tv = state->thr_v, n = state->nmark;
+    for (uint32_t i = blockIdx.x * SAMP_NT + threadIdx.x; i < n; i += gridDim.x * SAMP_NT) {
+        const uint64_t k = cand_key[i];
+        const uint32_t v = cand_v[i];
+        if (k < tk || (k == tk && v <= tv)) atomicOr((unsigned long long *)&bitmap[v >> 6], 1ull << (v & 63));
+    }
 }
+
+__global__ __launch_bounds__(SAMP_NT) void sampler_count_kernel(const sampler_state *__restrict__ state,
+                                                                const uint64_t *__restrict__ bitmap, uint64_t W, uint64_t wpw,
+                                                                uint32_t *__restrict__ wg_count)
+{
+    __shared__ uint32_t lds[SAMP_NT / 64];
+    if (state->fallback) return;       // the recomputing emit pass has written bitmap and counts
+    const uint64_t wbeg = (uint64_t)blockIdx.x * wpw;
+    const uint64_t wend = min(W, wbeg + wpw);
+    uint32_t cnt = 0;
+    for (uint64_t w = wbeg + threadIdx.x; w < wend; w += SAMP_NT) cnt += (uint32_t)__popcll(bitmap[w]);
+    cnt = block_sum<uint32_t, SAMP_NT>(cnt, lds);
+    if (threadIdx.x == 0) wg_count[blockIdx.x] = cnt;
+}
+
 
 // Workgroup g owns bitmap words [g*wpw, (g+1)*wpw), wpw a multiple of 8.  A wavefront takes 64 words
 // at a time and builds two of them per iteration: lane l evaluates vertices 2j and 2j+1 of Philox block
@@ -273,9 +409,10 @@ __device__ __forceinline__ uint64_t spread_even(uint32_t x32)
 __global__ __launch_bounds__(SAMP_NT) void sampler_emit_kernel(uint64_t N, uint64_t seed, uint64_t step,
                                                                const sampler_state *__restrict__ state,
                                                                uint64_t *__restrict__ bitmap, uint64_t W, uint64_t wpw,
-                                                               uint32_t *__restrict__ wg_count)
+                                                               uint32_t *__restrict__ wg_count, int only_on_fallback)
 {
     __shared__ uint32_t lds[SAMP_NT / 64];
+    if (only_on_fallback && !state->fallback) return;
     const uint64_t tk = state->thr_key;
     const uint32_t tv = state->thr_v;
     const uint64_t wbeg = (uint64_t)blockIdx.x * wpw;
@@ -439,32 +576,70 @@ size_t sgnn_sampler_ws_bytes(uint64_t N)
         SGNN_LAUNCH_CHECK(ctx, name);                                                                     \
     } while (0)
 
+// Window of histogram bins that holds the threshold of a sparse sample of a large graph (see
+// sampler_hist_window_kernel): the B-th smallest of N uniform keys lies at x = B/N of the key range with a standard
+// deviation of sqrt(B (1 - B/N)) / N; six of them either side must span at most two bins, or there is no window.
+// shift: moves the window by whole bins (a test's way to the fallback passes; 0 in use).
+struct sampler_window { int on; uint32_t b_lo, b_hi; };
+static sampler_window sampler_window_for(uint64_t N, uint32_t B, int shift)
+{
+    sampler_window w = {0, 0, 0};
+    if (N < (1ull << 20) || (uint64_t)B * 4 > N) return w;
+    const double p = (double)B / (double)N, x = p * HIST_BINS;
+    const double h = 6.0 * HIST_BINS * std::sqrt((double)B * (1.0 - p)) / (double)N + 1e-6;
+    if (h >= 0.45) return w;
+    const long lo = std::lround(std::floor(x - h)) + shift, hi = std::lround(std::floor(x + h)) + shift;
+    w.on = 1;
+    w.b_lo = (uint32_t)std::min<long>(std::max<long>(lo, 0), HIST_BINS - 1);
+    w.b_hi = (uint32_t)std::min<long>(std::max<long>(hi, 0), HIST_BINS - 1);
+    return w;
+}
+
 static int sampler_launches(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, uint64_t step, int32_t *S,
                             uint64_t *bitmap, uint32_t *rank, uint32_t *hist, sampler_state *state, uint64_t *cand_key,
-                            uint32_t *cand_v, uint32_t cap, uint32_t *wg_count, uint32_t *status, uint32_t *prefix, hipStream_t st)
+                            uint32_t *cand_v, uint32_t cap, uint32_t *wg_count, uint32_t *status, uint32_t *prefix,
+                            sampler_window win, hipStream_t st)
 {
     const uint64_t J = (N + 1) >> 1;
     const unsigned grid =
         (unsigned)std::min<uint64_t>(cdiv(J, SCAN_NT), std::min<uint64_t>(std::max<uint64_t>(256, N >> 19), 2048));
-    SAMP_LAUNCH("sampler_hist_kernel", sampler_hist_kernel, dim3(grid), dim3(SCAN_NT), N, seed, step, hist, prefix);
-    SAMP_LAUNCH("sampler_pick_bin_kernel", sampler_pick_bin_kernel, dim3(1), dim3(1024), B, hist, state);
-    if (prefix)
-        SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel<true>, dim3(grid), dim3(SCAN_NT), N, seed, step, state, cand_key,
-                    cand_v, cap, status, (const uint32_t *)prefix);
-    else
-        SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel<false>, dim3(grid), dim3(SCAN_NT), N, seed, step, state, cand_key,
-                    cand_v, cap, status, (const uint32_t *)nullptr);
-    SAMP_LAUNCH("sampler_threshold_kernel", sampler_threshold_kernel, dim3(1), dim3(1024), state, cand_key, cand_v, cap);
-
     const uint64_t W = (N + 63) / 64;
     const unsigned egrid = (unsigned)std::min<uint64_t>(cdiv(W, 8), EMIT_MAX_WG);
     const uint64_t wpw = (uint64_t)cdiv(cdiv(W, egrid), 8) * 8;
+    if (win.on) {
+        // one pass over the keys; the passes marked "fallback" leave at once unless the threshold's bin missed the window
+        SAMP_LAUNCH("sampler_hist_kernel", sampler_hist_window_kernel, dim3(grid), dim3(SCAN_NT), N, seed, step, hist, win.b_lo, win.b_hi,
+                    state, cand_key, cand_v, cap, status, bitmap, W);
+        SAMP_LAUNCH("sampler_pick_bin_kernel", sampler_pick_bin_kernel, dim3(1), dim3(1024), B, hist, state, 1, win.b_lo, win.b_hi);
+        SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel<false>, dim3(grid), dim3(SCAN_NT), N, seed, step, state, cand_key,
+                    cand_v, cap, status, (const uint32_t *)nullptr, 1);      // fallback
+        SAMP_LAUNCH("sampler_threshold_kernel", sampler_threshold_kernel, dim3(1), dim3(1024), state, cand_key, cand_v, cap);
+        SAMP_LAUNCH("sampler_mark_kernel", sampler_mark_kernel, dim3(64), dim3(SAMP_NT), (const sampler_state *)state,
+                    (const uint64_t *)cand_key, (const uint32_t *)cand_v, bitmap);
+        SAMP_LAUNCH("sampler_emit_kernel", sampler_emit_kernel, dim3(egrid), dim3(SAMP_NT), N, seed, step, state, bitmap, W, wpw,
+                    wg_count, 1);                                            // fallback
+        SAMP_LAUNCH("sampler_count_kernel", sampler_count_kernel, dim3(egrid), dim3(SAMP_NT), (const sampler_state *)state,
+                    (const uint64_t *)bitmap, W, wpw, wg_count);
+        SAMP_LAUNCH("sampler_rank_kernel", sampler_rank_kernel, dim3(egrid), dim3(SAMP_NT), bitmap, W, wpw, wg_count, B, rank, S,
+                    status);
+        return SGNN_OK;
+    }
+    SAMP_LAUNCH("sampler_hist_kernel", sampler_hist_kernel, dim3(grid), dim3(SCAN_NT), N, seed, step, hist, prefix);
+    SAMP_LAUNCH("sampler_pick_bin_kernel", sampler_pick_bin_kernel, dim3(1), dim3(1024), B, hist, state, 0, 0u, 0u);
+    if (prefix)
+        SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel<true>, dim3(grid), dim3(SCAN_NT), N, seed, step, state, cand_key,
+                    cand_v, cap, status, (const uint32_t *)prefix, 0);
+    else
+        SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel<false>, dim3(grid), dim3(SCAN_NT), N, seed, step, state, cand_key,
+                    cand_v, cap, status, (const uint32_t *)nullptr, 0);
+    SAMP_LAUNCH("sampler_threshold_kernel", sampler_threshold_kernel, dim3(1), dim3(1024), state, cand_key, cand_v, cap);
+
     if (prefix)
         SAMP_LAUNCH("sampler_emit_kernel", sampler_emit_prefix_kernel, dim3(egrid), dim3(SAMP_NT), N, seed, step, state, bitmap, W,
                     wpw, wg_count, (const uint32_t *)prefix);
     else
         SAMP_LAUNCH("sampler_emit_kernel", sampler_emit_kernel, dim3(egrid), dim3(SAMP_NT), N, seed, step, state, bitmap, W, wpw,
-                    wg_count);
+                    wg_count, 0);
     SAMP_LAUNCH("sampler_rank_kernel", sampler_rank_kernel, dim3(egrid), dim3(SAMP_NT), bitmap, W, wpw, wg_count, B, rank, S,
                 status);
     return SGNN_OK;
@@ -480,11 +655,16 @@ int sgnn_launch_sampler(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed, ui
     uint64_t *cand_key = ws.get<uint64_t>(cap);
     uint32_t *cand_v = ws.get<uint32_t>(cap);
     uint32_t *wg_count = ws.get<uint32_t>(EMIT_MAX_WG);
-    uint32_t *prefix = prefix_bytes(N) ? ws.get<uint32_t>(prefix_bytes(N) / sizeof(uint32_t)) : nullptr;
+    // SGNN_SAMPLER_WINDOW_SHIFT: whole bins by which the window is moved off its place (tests of the fallback passes)
+    const char *shift_env = std::getenv("SGNN_SAMPLER_WINDOW_SHIFT");
+    const sampler_window win = sampler_window_for(N, B, shift_env ? std::atoi(shift_env) : 0);
+    // a windowed call stores nothing per vertex; otherwise two bytes of key prefix per vertex from 2^20 vertices on
+    uint32_t *prefix = (!win.on && prefix_bytes(N)) ? ws.get<uint32_t>(prefix_bytes(N) / sizeof(uint32_t)) : nullptr;
     if (!ws.ok)
         return sgnn_fail(ctx, SGNN_ERR_CAPACITY, "sgnn_sample_uniform: scratch too small (%zu bytes needed): call sgnn_ctx_reserve",
                          ws.off);
-    return sampler_launches(ctx, N, B, seed, step, S, bitmap, rank, hist, state, cand_key, cand_v, cap, wg_count, ctx->status, prefix, st);
+    return sampler_launches(ctx, N, B, seed, step, S, bitmap, rank, hist, state, cand_key, cand_v, cap, wg_count, ctx->status, prefix, win,
+                            st);
 }
 
 // ---- the same sampler without any allocation: scratch in a file-scope device array ---------------------
@@ -570,5 +750,5 @@ extern "C" int sgnn_sample_uniform_static(uint64_t N, uint32_t B, uint64_t seed,
                 (uint32_t)((ST_STATUS - ST_HIST) / sizeof(uint32_t)));
     return sampler_launches(nullptr, N, B, seed, step, S, bitmap, rank, hist, state, reinterpret_cast<uint64_t *>(ptr + ST_CKEY),
                             reinterpret_cast<uint32_t *>(ptr + ST_CV), cand_capacity(N), reinterpret_cast<uint32_t *>(ptr + ST_WG),
-                            status, nullptr, st);      // no room for key prefixes in the static array: every pass recomputes the keys
+                            status, nullptr, sampler_window{0, 0, 0}, st);      // no room for key prefixes in the static array: every pass recomputes the keys
 }

@@ -19,6 +19,9 @@ pytestmark = pytest.mark.gpu
     # B = N, nearly all, a handful
     (1048576, 1000, 1, 1), (1048577, 1048577, 2, 3), (1048583, 5, 3, 0), (2097213, 1048576, 8, 8), (1048583, 1048576, 0, 2),
     (3000001, 300000, 11, 2**33),
+    # sparse samples of large graphs take one pass over the keys with a window of histogram bins named in advance:
+    # thresholds in the middle of a bin, and expected right on a bin boundary (a window of two bins)
+    (4194304, 4096, 6, 1), (8388608, 65536, 7, 2), (2097152, 2000, 1, 9), (4194304, 1, 0, 3),
 ])
 def test_sampler_matches_oracle(N, B, seed, step):
     S, bitmap, rank = gpu_sample(N, B, seed, step)
@@ -27,6 +30,24 @@ def test_sampler_matches_oracle(N, B, seed, step):
     words, rk = bitmap_rank_from_sample(N, S_ref)
     assert np.array_equal(bitmap.cpu().numpy(), words)
     assert np.array_equal(rank.cpu().numpy(), rk)
+
+
+@pytest.mark.parametrize("shift", [-3, 2])
+@pytest.mark.parametrize("N,B", [(1048576, 1000), (4194304, 4096)])
+def test_sampler_window_that_misses_falls_back(N, B, shift, monkeypatch):
+    # With its window of histogram bins moved off its place (a debugging switch of the library, read at every call) the
+    # one-pass form of the sampler finds the threshold's bin outside it and the recomputing passes take over; the
+    # call after it, with the window in place again, starts from a clean state.
+    S_ref = oracle.sample_uniform(N, B, 4, 4)
+    monkeypatch.setenv("SGNN_SAMPLER_WINDOW_SHIFT", str(shift))
+    S, bitmap, rank = gpu_sample(N, B, 4, 4)
+    assert np.array_equal(S.cpu().numpy(), S_ref)
+    words, rk = bitmap_rank_from_sample(N, S_ref)
+    assert np.array_equal(bitmap.cpu().numpy(), words) and np.array_equal(rank.cpu().numpy(), rk)
+    monkeypatch.delenv("SGNN_SAMPLER_WINDOW_SHIFT")
+    S, bitmap, rank = gpu_sample(N, B, 4, 4)
+    assert np.array_equal(S.cpu().numpy(), S_ref)
+    assert np.array_equal(bitmap.cpu().numpy(), words) and np.array_equal(rank.cpu().numpy(), rk)
 
 
 def test_sampler_is_deterministic_and_stateless():
