@@ -608,7 +608,7 @@ static int sampler_launches(sgnn_ctx *ctx, uint64_t N, uint32_t B, uint64_t seed
     const uint64_t wpw = (uint64_t)cdiv(cdiv(W, egrid), 8) * 8;
     if (win.on) {
         // one pass over the keys; the passes marked "fallback" leave at once unless the threshold's bin missed the window
-        SAMP_LAUNCH("sampler_hist_kernel", sampler_hist_window_kernel, dim3(grid), dim3(SCAN_NT), N, seed, step, hist, win.b_lo, win.b_hi,
+        SAMP_LAUNCH("sampler_hist_window_kernel", sampler_hist_window_kernel, dim3(grid), dim3(SCAN_NT), N, seed, step, hist, win.b_lo, win.b_hi,
                     state, cand_key, cand_v, cap, status, bitmap, W);
         SAMP_LAUNCH("sampler_pick_bin_kernel", sampler_pick_bin_kernel, dim3(1), dim3(1024), B, hist, state, 1, win.b_lo, win.b_hi);
         SAMP_LAUNCH("sampler_collect_kernel", sampler_collect_kernel<false>, dim3(grid), dim3(SCAN_NT), N, seed, step, state, cand_key,
