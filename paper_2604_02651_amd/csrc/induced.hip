@@ -229,7 +229,7 @@ __global__ __launch_bounds__(IND_NT) void induced_count_kernel(const int64_t *__
     if (blockIdx.x == 0 && threadIdx.x == 0) *n_tiles_out = n_tiles;
     unsigned long long wg_total = 0;      // 64 bits: the 32-bit prefix over the tile counts wraps beyond 2^32 survivors
     // software pipeline over the workgroup's tiles: the rows of the tile after next and the table of the next tile are
-    // requested before the current tile's edges are
+    // requested before the current tile's edges are gathered
     const uint64_t g = gridDim.x;
     uint32_t r_lo = 0, nr = 0, r_lo1 = 0, nr1 = 0;
     if (blockIdx.x < n_tiles) tile_rows(tile_row, blockIdx.x, n_tiles, B, r_lo, nr);

@@ -336,21 +336,26 @@ __device__ __forceinline__ void spmm_row_xent(const float (&v)[CH][VEC], const s
         if constexpr (SHARED_ROW) atomicAdd(fix + d, (unsigned long long)(long long)llrint((double)t * XENT_FIX_LOSS));
         else xs.loss += t;
     };
+    // d is a multiple of VEC (the launcher's condition for this instantiation): a lane's VEC columns of a chunk are
+    // inside the row or outside it together
     float mx = -INFINITY;
 #pragma unroll
     for (int m = 0; m < CH; ++m)
+        if ((m * 64 + lane) * VEC < d) {
 #pragma unroll
-        for (int i = 0; i < VEC; ++i)
-            if ((m * 64 + lane) * VEC + i < d) mx = fmaxf(mx, v[m][i]);
+            for (int i = 0; i < VEC; ++i) mx = fmaxf(mx, v[m][i]);
+        }
     mx = wave_reduce_rows<true>(mx);
     float e[CH][VEC], s = 0.f;
 #pragma unroll
-    for (int m = 0; m < CH; ++m)
+    for (int m = 0; m < CH; ++m) {
+        const bool in = (m * 64 + lane) * VEC < d;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
-            e[m][i] = ((m * 64 + lane) * VEC + i < d) ? exp_neg(v[m][i] - mx) : 0.f;
+            e[m][i] = in ? exp_neg(v[m][i] - mx) : 0.f;
             s += e[m][i];
         }
+    }
     s = wave_reduce_rows<false>(s);
     const float inv = __builtin_amdgcn_rcpf(s), lse = log_ge1(s);       // 1 ulp each
     if ((uint32_t)y >= (uint32_t)d && lane == 0) add_loss(mx + lse);
@@ -358,11 +363,18 @@ __device__ __forceinline__ void spmm_row_xent(const float (&v)[CH][VEC], const s
     for (int m = 0; m < CH; ++m) {
         const int col = (m * 64 + lane) * VEC;
         if (col < d) {
+            // the label's column, if it is one of this lane's: one test and one loss term per chunk, not one per column
+            const uint32_t rel = (uint32_t)(y - col);
+            if (rel < (uint32_t)VEC) {
+                float vy = v[m][0];
+#pragma unroll
+                for (int i = 1; i < VEC; ++i) vy = rel == (uint32_t)i ? v[m][i] : vy;
+                add_loss(lse - (vy - mx));
+            }
             float g[VEC];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
-                const bool hit = col + i == y;
-                if (hit) add_loss(lse - (v[m][i] - mx));
+                const bool hit = rel == (uint32_t)i;
                 g[i] = (e[m][i] * inv - (hit ? 1.f : 0.f)) * ep.inv_rows;
                 if (ep.dO_bf16) g[i] = (float)(__bf16)g[i];       // the column sums add what is stored
                 if constexpr (SHARED_ROW) {
